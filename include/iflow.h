@@ -1,0 +1,124 @@
+/*
+ * iflow.h - C ABI of libiflow.so: block-quantized weights (Inferflow, arXiv 2401.08294, Section 3)
+ * and the fused dequantize-and-multiply of the decode step, for AMD MI355X (gfx950).
+ *
+ * Conventions that hold for every call
+ *   - W is a row-major [rows][cols] matrix (rows = outputs N, cols = reduction length K).  A
+ *     quantization block is `block` consecutive elements of one row ("tensor block", Section 3).
+ *   - All data pointers are DEVICE pointers owned by the caller and must be 16-byte aligned.
+ *     Only `size_t *bytes` of iflow_packed_bytes and the scalar arguments live on the host.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues kernels on that stream and returns; the library allocates nothing, keeps no
+ *     per-call state and never synchronises.
+ *   - Arguments are validated on the host before anything is launched; a call that returns an
+ *     error other than IFLOW_ERR_DEVICE has launched nothing.
+ *   - fp16 values cross the ABI as uint16_t bit patterns (IEEE binary16).
+ *   - Inputs are assumed finite with |w| <= 65504; otherwise the result is unspecified (no fault).
+ *
+ * Packed device layout, version 1 (sizes are exact: no padding anywhere)
+ *   Every block stores its codes plus two fp16 numbers (remark after Table 3):
+ *       scale  = fp16((max - min) / L)      offset = fp16(min)
+ *   with L = 255 (8-bit), 15 (4-bit), 10 (3.5-bit, Eq.3).
+ *
+ *   IFLOW_Q3H_B64 - 32 bytes per block of 64 weights.  The 64 levels q0..q63 give 32 pair codes
+ *     c[j] = q[2j]*11 + q[2j+1] (Eq.4, 0..120).  With S, O the 16-bit patterns of scale and offset
+ *     the block is eight little-endian 32-bit words
+ *       W[i] = c[4i] | c[4i+2]<<7 | ((S>>2i)&3)<<14 | c[4i+1]<<16 | c[4i+3]<<23 | ((O>>2i)&3)<<30
+ *     for i = 0..7.  A row of nbk = cols/64 blocks occupies nbk*32 consecutive bytes and rows
+ *     follow each other, so row r starts at byte r*nbk*32.  Inside a row, blocks are grouped
+ *     into strips of 64 consecutive blocks (the last strip holds the remaining n_t <= 64).  Strip
+ *     t starts at byte t*2048 of the row and is stored as two planes: words W[0..3] of each of
+ *     its n_t blocks (16 bytes per block, blocks in order), followed by words W[4..7] of each
+ *     block.  (One wavefront reads a plane of a full strip as 1 KiB of consecutive bytes.)
+ *   IFLOW_Q4_B32 / IFLOW_Q4_B64 - first all codes, row after row, cols/2 bytes per row; then
+ *     one 4-byte header {scale, offset} per block, blocks in row-major order.  The levels of
+ *     eight consecutive weights v0..v7 form one little-endian 32-bit word whose nibbles, from
+ *     the least significant, are v0 v2 v4 v6 v1 v3 v5 v7.
+ *   IFLOW_Q8_B32 / IFLOW_Q8_B64 - first all levels as bytes in natural order (cols bytes per
+ *     row); then the headers as for 4-bit.
+ */
+#ifndef IFLOW_H
+#define IFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Formats: names and block sizes from the header rows of Table 3. */
+typedef enum {
+    IFLOW_Q8_B32 = 0,   /* 8-bit levels, block 32: 9   bits/weight */
+    IFLOW_Q8_B64 = 1,   /* 8-bit levels, block 64: 8.5 bits/weight */
+    IFLOW_Q4_B32 = 2,   /* 4-bit levels, block 32: 5   bits/weight */
+    IFLOW_Q4_B64 = 3,   /* 4-bit levels, block 64: 4.5 bits/weight */
+    IFLOW_Q3H_B64 = 4   /* 3.5-bit ("Q3H"): 11 levels, two weights per 7-bit code, block 64: 4 bits/weight */
+} iflow_format_t;
+
+typedef enum {
+    IFLOW_OK = 0,
+    IFLOW_ERR_NULL = 1,     /* a required pointer is NULL */
+    IFLOW_ERR_FORMAT = 2,   /* unknown iflow_format_t */
+    IFLOW_ERR_SHAPE = 3,    /* rows, cols or batch <= 0, cols not a multiple of the block size, or a size beyond 2^31-1 rows / cols */
+    IFLOW_ERR_SIZE = 4,     /* an output buffer is smaller than required */
+    IFLOW_ERR_ALIGN = 5,    /* a device pointer is not 16-byte aligned */
+    IFLOW_ERR_DEVICE = 6    /* a HIP call failed; see iflow_last_hip_error() */
+} iflow_status_t;
+
+/* Version of the packed layout described above (1). */
+int iflow_layout_version(void);
+
+/* Static text for a status code. */
+const char *iflow_status_string(iflow_status_t status);
+
+/* hipError_t (as int) of the most recent failed HIP call made by this library on the calling thread; 0 if none. */
+int iflow_last_hip_error(void);
+
+/* Block size (32 or 64), number of levels (256, 16 or 11), or -1 for an unknown format.  Table 3 / Eq.1 / Eq.3. */
+int iflow_format_block(iflow_format_t format);
+int iflow_format_levels(iflow_format_t format);
+
+/* Bytes of the packed matrix: rows*cols/block * (code bytes per block + 4).  This is Table 3's "actual
+ * bits/weight" (9, 8.5, 5, 4.5, 4) times rows*cols/8.  `bytes` is a host pointer. */
+iflow_status_t iflow_packed_bytes(iflow_format_t format, int64_t rows, int64_t cols, size_t *bytes);
+
+/* Eq.1 (Eq.3 for Q3H) per block, then Eq.4 packing, into the device layout.
+ *   w            [rows][cols] fp32, device, read only
+ *   packed       device, at least iflow_packed_bytes() bytes, fully overwritten
+ *   packed_bytes capacity of `packed`
+ * Per block, in IEEE fp32 without contraction: mn/mx = min/max (a zero of either sign counts as +0),
+ * scale = fp16((mx - mn)/L), offset = fp16(mn), both round-to-nearest-even; with s, o the stored
+ * values widened to fp32: level = clamp(round_half_away((w - o)/s), 0, L), or 0 when s == 0. */
+iflow_status_t iflow_quantize(iflow_format_t format, const float *w, int64_t rows, int64_t cols,
+                              void *packed, size_t packed_bytes, void *stream);
+
+/* Eq.5 then Eq.2 with the stored pair: w16[r][k] = fp16(level*scale + offset), the exact value
+ * rounded once to nearest-even (fp16 subnormals kept).  w16 is [rows][cols] fp16, device. */
+iflow_status_t iflow_dequant(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                             uint16_t *w16, void *stream);
+
+/* The decode step's product at batch 1: y[n] = sum_k w'[n][k] * x[k], w' as defined by
+ * iflow_dequant, fp32 accumulation, y rounded to fp16.  The packed matrix is streamed once.
+ *   x [cols] fp16, y [rows] fp16, both device. */
+iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                           const uint16_t *x, uint16_t *y, void *stream);
+
+/* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
+ * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].
+ *   X [batch][cols] fp16, Y [batch][rows] fp16, both device.
+ * batch 1 is iflow_qgemv; small batches stream the weights once on the vector units; larger
+ * batches run on the matrix cores from dequantized fp16 tiles. */
+iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                           const uint16_t *X, int64_t batch, uint16_t *Y, void *stream);
+
+/* Test helper: the device layout read back into plain arrays, so that a check of the quantizer does
+ * not depend on the layout.  levels [rows][cols] uint8 (Eq.5 already applied for Q3H);
+ * scale16 / offset16 [rows][cols/block] fp16 bit patterns.  All device. */
+iflow_status_t iflow_unpack_logical(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                                    uint8_t *levels, uint16_t *scale16, uint16_t *offset16, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IFLOW_H */

@@ -1,0 +1,431 @@
+"""Pins of the CPU oracle against things other than itself: the paper's printed worked example,
+brute force, closed forms, exact rational arithmetic and numpy's own fp16 / fp64 routines."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def f16(bits):
+    return np.array(bits, dtype=np.uint16).view(np.float16)
+
+
+def f16_exact(bits: int) -> Fraction:
+    """Value of an fp16 bit pattern as an exact rational, from the IEEE definition."""
+    s, e, m = bits >> 15, (bits >> 10) & 31, bits & 1023
+    assert e != 31
+    v = Fraction(m, 1 << 24) if e == 0 else Fraction(1024 + m, 1024) * Fraction(2) ** (e - 15)
+    return -v if s else v
+
+
+def read_table2():
+    rows, avg = [], None
+    with open(os.path.join(GOLDEN, "table2_example.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            if parts[0] == "avg":
+                avg = [float(v) for v in parts[1:]]
+            else:
+                rows.append([float(v) for v in parts])
+    return np.array(rows), avg
+
+
+# ---------------------------------------------------------------- Table 2 (worked example)
+@pytest.mark.parametrize("L,qcol,wcol,avg_i", [(15, 1, 2, 0), (7, 3, 4, 1), (10, 5, 6, 2)])
+def test_table2_levels_and_reconstruction(orc, L, qcol, wcol, avg_i):
+    tab, avg = read_table2()
+    w = tab[:, 0].astype(np.float32)
+    q, s_bits, o_bits = orc.quantize_block(w, L)
+    assert q.tolist() == tab[:, qcol].astype(int).tolist()
+    wq = np.array([orc.dequant_value(int(v), s_bits, o_bits) for v in q], np.uint16).view(np.float16).astype(np.float64)
+    # printed to three decimals; the fp16 header moves a value by at most ~1e-3 at this magnitude
+    assert np.max(np.abs(wq - tab[:, wcol])) <= 1.6e-3
+    err = np.mean(np.abs(wq - tab[:, 0]))
+    assert abs(err - avg[avg_i]) < 1e-3
+
+
+def test_table2_35bit_is_exact(orc):
+    tab, _ = read_table2()
+    q, s_bits, o_bits = orc.quantize_block(tab[:, 0].astype(np.float32), 10)
+    assert f16([s_bits])[0] == np.float16(0.25) and f16([o_bits])[0] == np.float16(-1.0)
+    wq = f16([orc.dequant_value(int(v), s_bits, o_bits) for v in q]).astype(np.float64)
+    assert wq.tolist() == tab[:, 6].tolist()
+    # Eq.4 on the example's levels
+    codes = [orc.pair_encode(int(q[2 * i]), int(q[2 * i + 1])) for i in range(6)]
+    assert codes == [0, 24, 37, 50, 85, 109]
+
+
+def test_table2_ideal_parameters_match_three_decimals():
+    """Eq.1/Eq.2 in exact arithmetic (no fp16 header) reproduce the printed w' to the printed digits:
+    shows that reading Eq.2 as q*scale+offset with scale=(max-min)/L is the table's arithmetic."""
+    tab, avg = read_table2()
+    w = [Fraction(str(v)) for v in tab[:, 0]]
+    for L, qcol, wcol, a in [(15, 1, 2, avg[0]), (7, 3, 4, avg[1]), (10, 5, 6, avg[2])]:
+        mn, mx = min(w), max(w)
+        errs = []
+        for i, v in enumerate(w):
+            t = (v - mn) / (mx - mn) * L
+            q = int(t + Fraction(1, 2))
+            assert q == int(tab[i, qcol])
+            wp = Fraction(q, L) * (mx - mn) + mn
+            assert abs(float(wp) - tab[i, wcol]) < 5.1e-4
+            errs.append(abs(wp - v))
+        assert abs(float(sum(errs) / len(errs)) - a) < 5.1e-4
+
+
+# ---------------------------------------------------------------- Eq.1/3: brute force and bounds
+def _cases(rng):
+    for L in (1, 3, 7, 10, 15, 255):
+        for n in (1, 2, 5, 12, 32, 64):
+            for sigma in (1e-3, 0.02, 3.0):
+                yield L, (rng.standard_normal(n) * sigma).astype(np.float32)
+
+
+def test_levels_minimise_reconstruction_error_brute_force(orc):
+    rng = np.random.default_rng(7)
+    for L, w in _cases(rng):
+        q, s_bits, o_bits = orc.quantize_block(w, L)
+        s, o = f16_exact(s_bits), f16_exact(o_bits)
+        assert q.min() >= 0 and q.max() <= L
+        if s == 0:
+            assert not q.any()
+            continue
+        for wi, qi in zip(w, q):
+            wv = Fraction(float(wi))
+            errs = [abs(wv - (o + j * s)) for j in range(L + 1)]
+            # the encoder works in fp32: allow a few ulp of (w-o)/s around an exact tie
+            assert errs[int(qi)] <= min(errs) + s * Fraction(L, 1 << 21)
+
+
+def test_half_step_error_bound(orc):
+    rng = np.random.default_rng(8)
+    for L, w in _cases(rng):
+        q, s_bits, o_bits = orc.quantize_block(w, L)
+        s, o = f16_exact(s_bits), f16_exact(o_bits)
+        mn, mx = Fraction(float(w.min())), Fraction(float(w.max()))
+        # delta: how far the fp16 header moved the two ends of the level grid
+        delta = max(Fraction(0), o - mn, mx - (o + L * s))
+        for wi, qi in zip(w, q):
+            rec = o + int(qi) * s
+            assert abs(Fraction(float(wi)) - rec) <= s / 2 + delta + s * Fraction(L, 1 << 21)
+
+
+def test_end_levels_present_and_level_count(orc):
+    rng = np.random.default_rng(9)
+    for fmt, L in ((orc.Q3H_B64, 10), (orc.Q4_B64, 15), (orc.Q4_B32, 15), (orc.Q8_B64, 255), (orc.Q8_B32, 255)):
+        assert orc.levels(fmt) == L + 1
+        w = (rng.standard_normal((16, 256)) * 0.02).astype(np.float32)
+        q, s, o = orc.quantize(fmt, w)
+        Bs = orc.block_size(fmt)
+        qb = q.reshape(-1, Bs)
+        wb = w.reshape(-1, Bs)
+        assert qb.max() <= L
+        # zero-centred blocks: the minimum maps to level 0 and the maximum to level L
+        assert (qb[np.arange(len(qb)), wb.argmin(1)] == 0).all()
+        assert (qb[np.arange(len(qb)), wb.argmax(1)] == L).all()
+    # 3.5-bit: exactly 11 distinct levels occur (Eq.3), all of them on a ramp
+    ramp = np.linspace(-1, 1, 64, dtype=np.float32)
+    q, _, _ = orc.quantize_block(ramp, 10)
+    assert sorted(set(q.tolist())) == list(range(11))
+
+
+def test_round_is_half_away_from_zero(orc):
+    # scale 1, offset 0 exactly: t = w, so 0.5 -> 1, 1.5 -> 2, 2.5 -> 3 (ties-to-even would give 0, 2, 2)
+    w = np.array([0, 0.5, 1.5, 2.5, 3.49, 3.51, 10], np.float32)
+    q, s_bits, o_bits = orc.quantize_block(w, 10)
+    assert f16([s_bits])[0] == 1 and f16([o_bits])[0] == 0
+    assert q.tolist() == [0, 1, 2, 3, 3, 4, 10]
+
+
+def test_constant_block_and_signed_zero(orc):
+    q, s_bits, o_bits = orc.quantize_block(np.full(64, 0.37, np.float32), 10)
+    assert not q.any() and s_bits == 0
+    assert f16([o_bits])[0] == np.float16(0.37)
+    assert orc.dequant_value(0, s_bits, o_bits) == o_bits            # w' = offset
+    q, s_bits, o_bits = orc.quantize_block(np.array([-0.0] * 8, np.float32), 15)
+    assert o_bits == 0 and s_bits == 0                               # -0 stored as +0
+    # range below the smallest fp16 subnormal: scale underflows to zero -> all levels 0
+    q, s_bits, _ = orc.quantize_block(np.array([1.0, 1.0 + 1.2e-7], np.float32), 10)
+    assert s_bits == 0 and not q.any()
+
+
+def test_power_of_two_rescaling_leaves_levels_unchanged(orc):
+    rng = np.random.default_rng(10)
+    w = (rng.standard_normal(64) * 0.02).astype(np.float32)
+    for L in (10, 15, 255):
+        q0, s0, o0 = orc.quantize_block(w, L)
+        for e in (-1, 2, 7):      # stays inside fp16's normal range, where scaling by 2^e is exact
+            q1, s1, o1 = orc.quantize_block(w * np.float32(2.0 ** e), L)
+            assert q1.tolist() == q0.tolist()
+            assert f16_exact(s1) == f16_exact(s0) * Fraction(2) ** e
+            assert f16_exact(o1) == f16_exact(o0) * Fraction(2) ** e
+
+
+def test_blocks_run_along_rows(orc):
+    """A block is Bs consecutive elements of a row: changing one element only changes its own block."""
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((3, 192)) * 0.02).astype(np.float32)
+    q0, s0, o0 = orc.quantize(orc.Q3H_B64, w)
+    w2 = w.copy()
+    w2[1, 70] = 5.0                     # row 1, second block of that row
+    q1, s1, o1 = orc.quantize(orc.Q3H_B64, w2)
+    changed = (q0 != q1).reshape(3, 3, 64).any(-1)
+    assert changed.tolist() == [[False] * 3, [False, True, False], [False] * 3]
+    assert (s0 != s1).tolist() == changed.tolist()
+    # per-block result equals the single-block routine
+    qb, sb, ob = orc.quantize_block(w2[1, 64:128], 10)
+    assert qb.tolist() == q1[1, 64:128].tolist() and sb == s1[1, 1] and ob == o1[1, 1]
+
+
+# ---------------------------------------------------------------- Eq.4 / Eq.5
+def test_pair_code_round_trip_all_121(orc):
+    seen = set()
+    for a in range(11):
+        for b in range(11):
+            c = orc.pair_encode(a, b)
+            assert 0 <= c <= 120 < 128           # seven bits suffice
+            assert c == a * 11 + b
+            assert orc.pair_decode(c) == (a, b)
+            seen.add(c)
+    assert seen == set(range(121))
+
+
+# ---------------------------------------------------------------- Table 3: bit budget
+def test_bits_per_weight_match_table3(orc):
+    with open(os.path.join(GOLDEN, "table3_bits_per_weight.txt")) as fh:
+        rows = [l.split() for l in fh if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for name, bs, bpw in rows:
+        fmt = orc.FORMATS[name]
+        assert orc.block_size(fmt) == int(bs)
+        for r, c in ((1, 64), (7, 4096), (4096, 11008)):
+            assert Fraction(orc.packed_bytes(fmt, r, c) * 8, r * c) == Fraction(bpw)
+    assert orc.packed_bytes(orc.Q3H_B64, 4, 100) == -1          # cols not a multiple of the block
+
+
+# ---------------------------------------------------------------- fp16 conversions vs numpy
+def test_f16_to_f32_all_patterns(orc):
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float32)
+    got = orc.f16_bits_to_f32(bits)
+    assert np.array_equal(got.view(np.uint32)[~np.isnan(ref)], ref.view(np.uint32)[~np.isnan(ref)])
+    assert np.isnan(got[np.isnan(ref)]).all()
+
+
+def test_f64_to_f16_round_to_nearest_even(orc):
+    rng = np.random.default_rng(12)
+    vals = [0.0, -0.0, 65504.0, 65519.99, 65520.0, 1e9, -1e9, 2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0000001,
+            3 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -25, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2047.5, 2048.5]
+    vals += list(rng.standard_normal(4000) * 0.02) + list(rng.standard_normal(2000) * 300)
+    vals += list(rng.standard_normal(2000) * 1e-6)
+    # exact midpoints between neighbouring fp16 values (ties)
+    b = rng.integers(0, 0x7BFF, 3000).astype(np.uint16)
+    lo = b.view(np.float16).astype(np.float64)
+    hi = (b + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    vals += list((lo + hi) / 2) + list(-(lo + hi) / 2)
+    vals = np.array(vals, np.float64)
+    with np.errstate(over="ignore"):
+        ref = vals.astype(np.float16).view(np.uint16)
+    assert np.array_equal(orc.f64_to_f16_bits(vals), ref)
+    v32 = vals.astype(np.float32)
+    with np.errstate(over="ignore"):
+        ref32 = v32.astype(np.float16).view(np.uint16)
+    assert np.array_equal(orc.f32_to_f16_bits(v32), ref32)
+
+
+# ---------------------------------------------------------------- Eq.2: exact, single rounding
+def test_dequant_value_is_exact_then_rounded_once(orc):
+    rng = np.random.default_rng(13)
+    scales = [0x0000, 0x0001, 0x0203, 0x03FF, 0x0400, 0x1C01, 0x211F, 0x2E66, 0x3C00, 0x5555, 0x7000]
+    offsets = [0x0000, 0x8001, 0x83FF, 0xA3D7, 0x23D7, 0xB001, 0x3C00, 0xBC01, 0xF000, 0x7000]
+    scales += rng.integers(0, 0x7000, 40).tolist()
+    offsets += rng.integers(0, 0x7000, 20).tolist() + (rng.integers(0, 0x7000, 20) | 0x8000).tolist()
+    for s in scales:
+        for o in offsets:
+            for q in (0, 1, 2, 5, 9, 10, 15, 128, 254, 255):
+                exact = q * f16_exact(s) + f16_exact(o)
+                as_f64 = float(exact)
+                assert Fraction(as_f64) == exact             # fits a double, so numpy rounds it once
+                with np.errstate(over="ignore"):
+                    ref = int(np.float64(as_f64).astype(np.float16).view(np.uint16))
+                got = orc.dequant_value(q, int(s), int(o))
+                if exact == 0:
+                    assert got & 0x7FFF == 0
+                else:
+                    assert got == ref, (hex(s), hex(o), q)
+
+
+def test_dequant_matrix_and_double_rounding_case(orc):
+    # a header for which fp32-then-fp16 rounding differs from rounding the exact value once
+    found = None
+    for s in range(0x1400, 0x3000, 7):
+        for o in (0x3C01, 0xBC01, 0x4401):
+            for q in (3, 5, 7, 9, 10):
+                exact = q * f16_exact(s) + f16_exact(o)
+                once = int(np.float64(float(exact)).astype(np.float16).view(np.uint16))
+                twice = int(np.float32(float(exact)).astype(np.float16).view(np.uint16))
+                if once != twice:
+                    found = (q, s, o, once)
+                    break
+    if found is not None:
+        q, s, o, once = found
+        assert orc.dequant_value(q, s, o) == once
+    rng = np.random.default_rng(14)
+    w = (rng.standard_normal((4, 128)) * 0.02).astype(np.float32)
+    for fmt in range(5):
+        q, s, o = orc.quantize(fmt, w)
+        d = orc.dequant(fmt, q, s, o)
+        Bs = orc.block_size(fmt)
+        for r in range(4):
+            for k in (0, 1, 63, 64, 127):
+                assert d[r, k] == orc.dequant_value(int(q[r, k]), int(s[r, k // Bs]), int(o[r, k // Bs]))
+        # reconstruction error of the fp16 output stays within half a step plus fp16 rounding
+        sv = s.view(np.float16).astype(np.float64).repeat(Bs, axis=1)
+        assert np.all(np.abs(d.view(np.float16).astype(np.float64) - w) <= 0.5 * sv + 2e-4)
+
+
+# ---------------------------------------------------------------- packing
+def test_canonical_record_bytes(orc):
+    rng = np.random.default_rng(15)
+    for fmt, L in ((orc.Q3H_B64, 10), (orc.Q4_B32, 15), (orc.Q4_B64, 15), (orc.Q8_B32, 255), (orc.Q8_B64, 255)):
+        Bs = orc.block_size(fmt)
+        rows, cols = 3, 2 * Bs
+        q = rng.integers(0, L + 1, (rows, cols)).astype(np.uint8)
+        s = rng.integers(0, 0x7000, (rows, 2)).astype(np.uint16)
+        o = rng.integers(0, 0x7000, (rows, 2)).astype(np.uint16)
+        rec = orc.pack_canonical(fmt, q, s, o)
+        assert rec.size == orc.packed_bytes(fmt, rows, cols)
+        per = rec.size // (rows * 2)
+        for b in range(rows * 2):
+            r, kb = divmod(b, 2)
+            blk = bytes(rec[b * per:(b + 1) * per])
+            assert int.from_bytes(blk[0:2], "little") == s[r, kb] and int.from_bytes(blk[2:4], "little") == o[r, kb]
+            qb = q[r, kb * Bs:(kb + 1) * Bs].tolist()
+            if L == 255:
+                assert list(blk[4:]) == qb
+            elif L == 15:
+                assert list(blk[4:]) == [qb[2 * j] | qb[2 * j + 1] << 4 for j in range(Bs // 2)]
+            else:
+                big = sum((qb[2 * j] * 11 + qb[2 * j + 1]) << (7 * j) for j in range(32))
+                assert blk[4:] == big.to_bytes(28, "little")
+        q2, s2, o2 = orc.unpack_canonical(fmt, rec, rows, cols)
+        assert np.array_equal(q2, q) and np.array_equal(s2, s) and np.array_equal(o2, o)
+
+
+def unpack_device_reference(fmt_name, packed, rows, cols):
+    """The device layout read back with numpy, written from the layout's specification
+    (include/iflow.h), independently of the oracle's packer."""
+    packed = np.asarray(packed, np.uint8)
+    if fmt_name == "Q3H_B64":
+        nbk = cols // 64
+        q = np.zeros((rows, cols), np.uint8)
+        s = np.zeros((rows, nbk), np.uint16)
+        o = np.zeros((rows, nbk), np.uint16)
+        words = packed.view("<u4").reshape(rows, nbk * 8)
+        for r in range(rows):
+            for kb in range(nbk):
+                t, j = divmod(kb, 64)
+                n_t = min(64, nbk - 64 * t)
+                base = t * 64 * 8
+                W = [int(words[r, base + (i // 4) * n_t * 4 + j * 4 + (i % 4)]) for i in range(8)]
+                S = O = 0
+                for i in range(8):
+                    c = [W[i] & 127, (W[i] >> 16) & 127, (W[i] >> 7) & 127, (W[i] >> 23) & 127]
+                    for m in range(4):
+                        q[r, kb * 64 + 8 * i + 2 * m] = c[m] // 11
+                        q[r, kb * 64 + 8 * i + 2 * m + 1] = c[m] % 11
+                    S |= ((W[i] >> 14) & 3) << (2 * i)
+                    O |= ((W[i] >> 30) & 3) << (2 * i)
+                s[r, kb], o[r, kb] = S, O
+        return q, s, o
+    bits, Bs = (8 if fmt_name.startswith("Q8") else 4), int(fmt_name[-2:])
+    nbk = cols // Bs
+    ncode = rows * cols * bits // 8
+    hdr = packed[ncode:].view("<u2").reshape(rows, nbk, 2)
+    if bits == 8:
+        q = packed[:ncode].reshape(rows, cols).copy()
+    else:
+        words = packed[:ncode].view("<u4").reshape(rows, cols // 8)
+        q = np.zeros((rows, cols), np.uint8)
+        for p, v in enumerate([0, 2, 4, 6, 1, 3, 5, 7]):
+            q[:, v::8] = (words >> (4 * p)) & 15
+    return q, hdr[:, :, 0].copy(), hdr[:, :, 1].copy()
+
+
+@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B32", "Q4_B64", "Q8_B32", "Q8_B64"])
+@pytest.mark.parametrize("rows,nblocks", [(1, 1), (3, 5), (2, 64), (2, 65), (2, 172)])
+def test_device_layout_round_trip(orc, name, rows, nblocks):
+    fmt = orc.FORMATS[name]
+    L = orc.levels(fmt) - 1
+    cols = nblocks * orc.block_size(fmt)
+    rng = np.random.default_rng(16 + nblocks)
+    q = rng.integers(0, L + 1, (rows, cols)).astype(np.uint8)
+    s = rng.integers(0, 0x10000, (rows, nblocks)).astype(np.uint16)
+    o = rng.integers(0, 0x10000, (rows, nblocks)).astype(np.uint16)
+    dev = orc.pack_device(fmt, q, s, o)
+    assert dev.size == orc.packed_bytes(fmt, rows, cols)
+    q2, s2, o2 = unpack_device_reference(name, dev, rows, cols)
+    assert np.array_equal(q2, q) and np.array_equal(s2, s) and np.array_equal(o2, o)
+    # same multiset of information as the canonical record: equal size, and rows stay separable for Q3H
+    assert dev.size == orc.pack_canonical(fmt, q, s, o).size
+    if name == "Q3H_B64" and rows > 1:
+        one = orc.pack_device(fmt, q[1:2], s[1:2], o[1:2])
+        assert np.array_equal(dev[one.size:2 * one.size], one)
+
+
+# ---------------------------------------------------------------- matmul: the definition
+def test_gemm_equals_numpy_fp64(orc):
+    rng = np.random.default_rng(17)
+    w16 = (rng.standard_normal((37, 192)) * 0.02).astype(np.float16)
+    x16 = rng.standard_normal((5, 192)).astype(np.float16)
+    y = orc.gemm(w16.view(np.uint16), x16.view(np.uint16))
+    ref = x16.astype(np.float64) @ w16.astype(np.float64).T          # non-square: a transposed operand fails
+    assert y.shape == (5, 37)
+    assert np.allclose(y, ref, rtol=1e-13, atol=1e-15)
+    y4 = orc.gemm(w16.view(np.uint16), x16.view(np.uint16), threads=4)
+    assert np.array_equal(y4, y)                                     # row-parallel: same per-row order
+    y32 = orc.gemm_f32(w16.view(np.uint16), x16.view(np.uint16)).view(np.float16).astype(np.float64)
+    assert np.max(np.abs(y32 - ref)) <= 2e-3 * np.sqrt(np.mean(ref ** 2))
+
+
+def test_gemm_special_vectors(orc):
+    rng = np.random.default_rng(18)
+    w = (rng.standard_normal((6, 128)) * 0.02).astype(np.float32)
+    w[2, 64:128] = 0.125                                              # a constant block
+    q, s, o = orc.quantize(orc.Q3H_B64, w)
+    d = orc.dequant(orc.Q3H_B64, q, s, o)
+    dv = d.view(np.float16).astype(np.float64)
+    e = np.zeros((1, 128), np.float16)
+    e[0, 77] = 1
+    assert np.array_equal(orc.gemm(d, e.view(np.uint16))[0], dv[:, 77])          # unit vector picks a column
+    ones = np.ones((1, 128), np.float16)
+    assert np.allclose(orc.gemm(d, ones.view(np.uint16))[0], dv.sum(1), rtol=1e-14)
+    x = rng.standard_normal((1, 128)).astype(np.float16)
+    xm = x.copy()
+    xm[0, :64] = 0
+    # constant block: its contribution is offset * sum(x)
+    assert np.isclose(orc.gemm(d, xm.view(np.uint16))[0, 2], 0.125 * xm.astype(np.float64).sum(), rtol=1e-13)
+    # linearity in x (exact for a power-of-two multiple)
+    assert np.array_equal(orc.gemm(d, (x * np.float16(4)).view(np.uint16)), 4 * orc.gemm(d, x.view(np.uint16)))
+
+
+def test_qgemm_from_canonical_record(orc):
+    rng = np.random.default_rng(19)
+    w = (rng.standard_normal((9, 256)) * 0.02).astype(np.float32)
+    x = rng.standard_normal((3, 256)).astype(np.float16)
+    for fmt in range(5):
+        q, s, o = orc.quantize(fmt, w)
+        rec = orc.pack_canonical(fmt, q, s, o)
+        y, used = orc.qgemm_canonical(fmt, rec, 9, 256, x.view(np.uint16), threads=2)
+        ref = x.astype(np.float64) @ orc.dequant(fmt, q, s, o).view(np.float16).astype(np.float64).T
+        assert used >= 1 and np.allclose(y, ref, rtol=1e-13, atol=1e-15)
+        # quantization error of the product is small against the unquantized product's spread
+        full = x.astype(np.float64) @ w.astype(np.float64).T
+        bound = {0: 0.01, 1: 0.01, 2: 0.12, 3: 0.15, 4: 0.25}[fmt]
+        assert np.sqrt(np.mean((y - full) ** 2)) <= bound * np.sqrt(np.mean(full ** 2))
