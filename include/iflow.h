@@ -60,7 +60,7 @@ typedef enum {
     IFLOW_OK = 0,
     IFLOW_ERR_NULL = 1,     /* a required pointer is NULL */
     IFLOW_ERR_FORMAT = 2,   /* unknown iflow_format_t */
-    IFLOW_ERR_SHAPE = 3,    /* rows, cols or batch <= 0, cols not a multiple of the block size, or a size beyond 2^31-1 rows / cols */
+    IFLOW_ERR_SHAPE = 3,    /* rows, cols or batch <= 0, cols not a multiple of the block size, or a size above 2^30 */
     IFLOW_ERR_SIZE = 4,     /* an output buffer is smaller than required */
     IFLOW_ERR_ALIGN = 5,    /* a device pointer is not 16-byte aligned */
     IFLOW_ERR_DEVICE = 6    /* a HIP call failed; see iflow_last_hip_error() */

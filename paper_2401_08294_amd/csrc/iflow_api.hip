@@ -1,0 +1,131 @@
+// C-ABI entry points of libiflow.so: argument validation on the host, then one launcher call.
+// Nothing here allocates, synchronises or keeps state between calls (except the thread-local
+// record of the last HIP error).
+#include "iflow_common.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+iflow_status_t device_status(hipError_t e)
+{
+    if (e == hipSuccess) return IFLOW_OK;
+    g_last_hip_error = (int)e;
+    return IFLOW_ERR_DEVICE;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape rules shared by every call: positive sizes, cols a whole number of blocks, and sizes that
+// keep every kernel index inside 32-bit block/row counters.
+iflow_status_t check_shape(iflow_format_t f, int64_t rows, int64_t cols, iflow::FormatInfo *fi)
+{
+    if (!iflow::format_info((int)f, fi)) return IFLOW_ERR_FORMAT;
+    if (rows <= 0 || cols <= 0) return IFLOW_ERR_SHAPE;
+    if (cols % fi->block != 0) return IFLOW_ERR_SHAPE;
+    if (rows > (1LL << 30) || cols > (1LL << 30)) return IFLOW_ERR_SHAPE;
+    return IFLOW_OK;
+}
+
+size_t packed_size(const iflow::FormatInfo &fi, int64_t rows, int64_t cols)
+{
+    return (size_t)rows * (size_t)(cols / fi.block) * (size_t)(fi.code_bytes + 4);
+}
+
+}  // namespace
+
+extern "C" {
+
+int iflow_layout_version(void) { return 1; }
+
+const char *iflow_status_string(iflow_status_t status)
+{
+    switch (status) {
+    case IFLOW_OK: return "ok";
+    case IFLOW_ERR_NULL: return "null pointer argument";
+    case IFLOW_ERR_FORMAT: return "unknown format";
+    case IFLOW_ERR_SHAPE: return "bad shape: sizes must be positive and cols a multiple of the block size";
+    case IFLOW_ERR_SIZE: return "output buffer too small";
+    case IFLOW_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case IFLOW_ERR_DEVICE: return "HIP call failed (see iflow_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+int iflow_last_hip_error(void) { return g_last_hip_error; }
+
+int iflow_format_block(iflow_format_t format)
+{
+    iflow::FormatInfo fi;
+    return iflow::format_info((int)format, &fi) ? fi.block : -1;
+}
+
+int iflow_format_levels(iflow_format_t format)
+{
+    iflow::FormatInfo fi;
+    return iflow::format_info((int)format, &fi) ? fi.L + 1 : -1;
+}
+
+iflow_status_t iflow_packed_bytes(iflow_format_t format, int64_t rows, int64_t cols, size_t *bytes)
+{
+    iflow::FormatInfo fi;
+    if (!bytes) return IFLOW_ERR_NULL;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    *bytes = packed_size(fi, rows, cols);
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_quantize(iflow_format_t format, const float *w, int64_t rows, int64_t cols,
+                              void *packed, size_t packed_bytes, void *stream)
+{
+    iflow::FormatInfo fi;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (!w || !packed) return IFLOW_ERR_NULL;
+    if (packed_bytes < packed_size(fi, rows, cols)) return IFLOW_ERR_SIZE;
+    if (!aligned16(w) || !aligned16(packed)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_quantize((int)format, w, rows, cols, packed, (hipStream_t)stream));
+}
+
+iflow_status_t iflow_dequant(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                             uint16_t *w16, void *stream)
+{
+    iflow::FormatInfo fi;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (!packed || !w16) return IFLOW_ERR_NULL;
+    if (!aligned16(packed) || !aligned16(w16)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_dequant((int)format, packed, rows, cols, w16, (hipStream_t)stream));
+}
+
+iflow_status_t iflow_unpack_logical(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                                    uint8_t *levels, uint16_t *scale16, uint16_t *offset16, void *stream)
+{
+    iflow::FormatInfo fi;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (!packed || !levels || !scale16 || !offset16) return IFLOW_ERR_NULL;
+    if (!aligned16(packed) || !aligned16(levels) || !aligned16(scale16) || !aligned16(offset16)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_unpack((int)format, packed, rows, cols, levels, scale16, offset16, (hipStream_t)stream));
+}
+
+iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                           const uint16_t *X, int64_t batch, uint16_t *Y, void *stream)
+{
+    iflow::FormatInfo fi;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (batch <= 0 || batch > (1LL << 30)) return IFLOW_ERR_SHAPE;
+    if (!packed || !X || !Y) return IFLOW_ERR_NULL;
+    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_qgemv((int)format, packed, rows, cols, X, batch, Y, (hipStream_t)stream));
+}
+
+iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
+                           const uint16_t *x, uint16_t *y, void *stream)
+{
+    return iflow_qgemm(format, packed, rows, cols, x, 1, y, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+// Shared declarations of libiflow's translation units: format traits, small device helpers and the
+// host-side launcher prototypes.  gfx950 (CDNA4) only: 64-wide wavefronts, DPP, packed fp16 math.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/iflow.h"
+
+namespace iflow {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// ---- formats (Table 3 of the paper: bits, block size; Eq.1 / Eq.3: number of steps L) -------------
+enum Kind { KIND_Q8 = 0, KIND_Q4 = 1, KIND_Q3H = 2 };
+
+template <int F> struct Fmt;
+template <> struct Fmt<IFLOW_Q8_B32>  { static constexpr int kind = KIND_Q8,  block = 32, L = 255, code_bytes = 32; };
+template <> struct Fmt<IFLOW_Q8_B64>  { static constexpr int kind = KIND_Q8,  block = 64, L = 255, code_bytes = 64; };
+template <> struct Fmt<IFLOW_Q4_B32>  { static constexpr int kind = KIND_Q4,  block = 32, L = 15,  code_bytes = 16; };
+template <> struct Fmt<IFLOW_Q4_B64>  { static constexpr int kind = KIND_Q4,  block = 64, L = 15,  code_bytes = 32; };
+template <> struct Fmt<IFLOW_Q3H_B64> { static constexpr int kind = KIND_Q3H, block = 64, L = 10,  code_bytes = 28; };
+
+struct FormatInfo { int kind, block, L, code_bytes; };
+inline bool format_info(int f, FormatInfo *fi)
+{
+    switch (f) {
+    case IFLOW_Q8_B32:  *fi = {KIND_Q8, 32, 255, 32}; return true;
+    case IFLOW_Q8_B64:  *fi = {KIND_Q8, 64, 255, 64}; return true;
+    case IFLOW_Q4_B32:  *fi = {KIND_Q4, 32, 15, 16};  return true;
+    case IFLOW_Q4_B64:  *fi = {KIND_Q4, 64, 15, 32};  return true;
+    case IFLOW_Q3H_B64: *fi = {KIND_Q3H, 64, 10, 28}; return true;
+    default: return false;
+    }
+}
+
+// ---- bit casts ----------------------------------------------------------------------------------
+__device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+__device__ __forceinline__ uint32_t as_u32(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
+__device__ __forceinline__ half_t as_h(uint16_t u) { return __builtin_bit_cast(half_t, u); }
+__device__ __forceinline__ uint16_t as_u16(half_t h) { return __builtin_bit_cast(uint16_t, h); }
+
+// ---- wavefront reductions over DPP (no LDS traffic) ---------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, true));
+}
+// sum within each row of 16 lanes; every lane of the row ends with the row's sum
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f32<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f32<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f32<0x141, 0xF>(v);   // row_half_mirror
+    v += dpp_f32<0x140, 0xF>(v);   // row_mirror
+    return v;
+}
+// sum over all 64 lanes; the result is valid in lane 63
+__device__ __forceinline__ float wave_sum_to_lane63(float v)
+{
+    v = row16_sum(v);
+    v += dpp_f32<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_f32<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = wave_sum_to_lane63(v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// ---- Q3H word decode ------------------------------------------------------------------------------
+// A stored 32-bit word holds four 7-bit pair codes (Eq.4) at bits 0, 7, 16 and 23 and header bits at
+// 14-15 and 30-31.  `hc` is two codes placed in the two halves of a register and OR-ed with 0x6400,
+// i.e. the fp16 pair (1024 + c_lo, 1024 + c_hi).  Eq.5 in packed fp16 / u16 arithmetic:
+//   (1024 + c) * K1 + K2 with K1 = 1489 * 2^-14 (fp16 nearest 1/11) and K2 = 931.5 lies within
+//   0.02 of 1025 + (c - 5)/11, so the fma's rounding to the unit grid of [1024, 2048) yields exactly
+//   1025 + floor(c / 11) for every c in 0..120;
+//   (0x6401 + q1) * (-11) + (0x6400 + c) mod 2^16 = 0x17F5 + (c mod 11), the fp16 number
+//   2^-20 * (2037 + q2).
+// Both results are affine in the level, which is all a dot product against x needs.
+#define IFLOW_Q3H_K1 ((half_t)0.09088134765625f)
+#define IFLOW_Q3H_K2 ((half_t)931.5f)
+#define IFLOW_Q3H_BIAS1 1025.0f
+#define IFLOW_Q3H_BIAS2 2037.0f
+#define IFLOW_Q3H_SCALE2 1048576.0f /* 2^20 */
+
+__device__ __forceinline__ half2_t q3h_high_digit(uint32_t hc)
+{
+    const half2_t k1 = {IFLOW_Q3H_K1, IFLOW_Q3H_K1}, k2 = {IFLOW_Q3H_K2, IFLOW_Q3H_K2};
+    return __builtin_elementwise_fma(as_h2(hc), k1, k2);                  // (1025 + q1) in each half
+}
+__device__ __forceinline__ half2_t q3h_low_digit(half2_t h1, uint32_t hc)
+{
+    const ushort2_t m11 = {0xFFF5, 0xFFF5};
+    ushort2_t r = __builtin_bit_cast(ushort2_t, h1) * m11 + __builtin_bit_cast(ushort2_t, hc);
+    return __builtin_bit_cast(half2_t, r);                                // 2^-20 * (2037 + q2) in each half
+}
+
+// ---- host-side launchers, one per translation unit ------------------------------------------------
+hipError_t launch_quantize(int format, const float *w, int64_t rows, int64_t cols, void *packed, hipStream_t s);
+hipError_t launch_dequant(int format, const void *packed, int64_t rows, int64_t cols, uint16_t *w16, hipStream_t s);
+hipError_t launch_unpack(int format, const void *packed, int64_t rows, int64_t cols,
+                         uint8_t *levels, uint16_t *scale16, uint16_t *offset16, hipStream_t s);
+hipError_t launch_qgemv(int format, const void *packed, int64_t rows, int64_t cols,
+                        const uint16_t *x, int64_t batch, uint16_t *y, hipStream_t s);
+
+}  // namespace iflow

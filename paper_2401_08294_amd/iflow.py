@@ -1,0 +1,119 @@
+"""Thin ctypes binding over libiflow.so, with the same names as the C ABI in include/iflow.h.
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch is used
+by callers for device memory and streams; tensors are passed as `tensor.data_ptr()` and the stream as
+`torch.cuda.current_stream().cuda_stream`.  There is no CPU fallback: if the library has not been built
+(`python -m paper_2401_08294_amd.build` or `__graft_entry__.build()`), loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libiflow.so")
+
+Q8_B32, Q8_B64, Q4_B32, Q4_B64, Q3H_B64 = range(5)
+FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B64, "Q3H_B64": Q3H_B64}
+BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 4.0}
+
+OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE = range(7)
+
+
+class IflowError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libiflow.so (once).  Raises if it is missing: the product path has no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "or `python -m paper_2401_08294_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        i64, p, sz = C.c_int64, C.c_void_p, C.c_size_t
+        L.iflow_layout_version.restype = C.c_int
+        L.iflow_status_string.restype = C.c_char_p
+        L.iflow_status_string.argtypes = [C.c_int]
+        L.iflow_last_hip_error.restype = C.c_int
+        L.iflow_format_block.argtypes = [C.c_int]
+        L.iflow_format_levels.argtypes = [C.c_int]
+        L.iflow_packed_bytes.argtypes = [C.c_int, i64, i64, C.POINTER(sz)]
+        L.iflow_quantize.argtypes = [C.c_int, p, i64, i64, p, sz, p]
+        L.iflow_dequant.argtypes = [C.c_int, p, i64, i64, p, p]
+        L.iflow_qgemv.argtypes = [C.c_int, p, i64, i64, p, p, p]
+        L.iflow_qgemm.argtypes = [C.c_int, p, i64, i64, p, i64, p, p]
+        L.iflow_unpack_logical.argtypes = [C.c_int, p, i64, i64, p, p, p, p]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    """Device address of a torch tensor, or an integer address passed through."""
+    return t if isinstance(t, int) or t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _check(status: int, what: str):
+    if status != OK:
+        raise IflowError(status, what)
+
+
+def layout_version() -> int:
+    return lib().iflow_layout_version()
+
+
+def status_string(status: int) -> str:
+    return lib().iflow_status_string(status).decode()
+
+
+def last_hip_error() -> int:
+    return lib().iflow_last_hip_error()
+
+
+def format_block(fmt: int) -> int:
+    return lib().iflow_format_block(fmt)
+
+
+def format_levels(fmt: int) -> int:
+    return lib().iflow_format_levels(fmt)
+
+
+def packed_bytes(fmt: int, rows: int, cols: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().iflow_packed_bytes(fmt, rows, cols, C.byref(out)), "iflow_packed_bytes")
+    return int(out.value)
+
+
+def quantize(fmt: int, w, rows: int, cols: int, packed, packed_capacity: int, stream=None) -> None:
+    """w: fp32 [rows][cols] device tensor; packed: uint8 device tensor of at least packed_bytes()."""
+    _check(lib().iflow_quantize(fmt, _ptr(w), rows, cols, _ptr(packed), packed_capacity, _stream(stream)), "iflow_quantize")
+
+
+def dequant(fmt: int, packed, rows: int, cols: int, w16, stream=None) -> None:
+    _check(lib().iflow_dequant(fmt, _ptr(packed), rows, cols, _ptr(w16), _stream(stream)), "iflow_dequant")
+
+
+def qgemv(fmt: int, packed, rows: int, cols: int, x, y, stream=None) -> None:
+    _check(lib().iflow_qgemv(fmt, _ptr(packed), rows, cols, _ptr(x), _ptr(y), _stream(stream)), "iflow_qgemv")
+
+
+def qgemm(fmt: int, packed, rows: int, cols: int, X, batch: int, Y, stream=None) -> None:
+    _check(lib().iflow_qgemm(fmt, _ptr(packed), rows, cols, _ptr(X), batch, _ptr(Y), _stream(stream)), "iflow_qgemm")
+
+
+def unpack_logical(fmt: int, packed, rows: int, cols: int, levels, scale16, offset16, stream=None) -> None:
+    _check(lib().iflow_unpack_logical(fmt, _ptr(packed), rows, cols, _ptr(levels), _ptr(scale16), _ptr(offset16),
+                                      _stream(stream)), "iflow_unpack_logical")

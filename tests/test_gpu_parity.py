@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: packed bytes, unpacked levels/headers and dequantized fp16 weights bit-exact; matmul outputs within
+2e-3 of the oracle's fp64 result, measured as |y - y_ref| / max(|y_ref|, rms(y_ref)) per activation row.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2401_08294_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+NAMES = ["Q3H_B64", "Q4_B64", "Q4_B32", "Q8_B64", "Q8_B32"]
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2401_08294_amd import iflow
+    assert torch.cuda.is_available(), "needs a GPU"
+    iflow.lib()
+    return torch, iflow
+
+
+def rel_err(y, yref):
+    yref = np.asarray(yref, np.float64)
+    rms = np.sqrt(np.mean(yref ** 2, axis=-1, keepdims=True))
+    den = np.maximum(np.abs(yref), np.maximum(rms, 1e-30))
+    return float(np.max(np.abs(np.asarray(y, np.float64) - yref) / den))
+
+
+def gpu_quantize(torch, iflow, fmt, w):
+    rows, cols = w.shape
+    wd = torch.from_numpy(w).cuda()
+    n = iflow.packed_bytes(fmt, rows, cols)
+    packed = torch.full((n + 64,), 0xA5, dtype=torch.uint8, device="cuda")     # canary tail
+    iflow.quantize(fmt, wd, rows, cols, packed, n)
+    torch.cuda.synchronize()
+    host = packed.cpu().numpy()
+    assert (host[n:] == 0xA5).all(), "quantizer wrote past the packed size"
+    return packed, host[:n]
+
+
+def gpu_dequant(torch, iflow, fmt, packed, rows, cols):
+    out = torch.empty((rows, cols), dtype=torch.float16, device="cuda")
+    iflow.dequant(fmt, packed, rows, cols, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().view(np.uint16)
+
+
+def gpu_unpack(torch, iflow, fmt, packed, rows, cols):
+    nbk = cols // iflow.format_block(fmt)
+    lv = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    sc = torch.empty((rows, nbk), dtype=torch.int16, device="cuda")
+    of = torch.empty((rows, nbk), dtype=torch.int16, device="cuda")
+    iflow.unpack_logical(fmt, packed, rows, cols, lv, sc, of)
+    torch.cuda.synchronize()
+    return lv.cpu().numpy(), sc.cpu().numpy().view(np.uint16), of.cpu().numpy().view(np.uint16)
+
+
+def gpu_gemm(torch, iflow, fmt, packed, rows, cols, x16):
+    batch = x16.shape[0]
+    xd = torch.from_numpy(x16.view(np.int16)).cuda()
+    y = torch.full((batch, rows), float("nan"), dtype=torch.float16, device="cuda")
+    if batch == 1:
+        iflow.qgemv(fmt, packed, rows, cols, xd, y)
+    else:
+        iflow.qgemm(fmt, packed, rows, cols, xd, batch, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy().astype(np.float64)
+
+
+def check_all(torch, iflow, orc, name, w, x16, tag):
+    """quantize -> bytes, unpack, dequant bit-exact; gemm within tolerance."""
+    fmt = iflow.FORMATS[name]
+    rows, cols = w.shape
+    say(f"[case] {tag} fmt={name} rows={rows} cols={cols} batch={x16.shape[0]}")
+    q, s, o = orc.quantize(orc.FORMATS[name], w)
+    ref_bytes = orc.pack_device(orc.FORMATS[name], q, s, o)
+    packed, got_bytes = gpu_quantize(torch, iflow, fmt, w)
+    assert got_bytes.size == ref_bytes.size
+    nbad = int(np.count_nonzero(got_bytes != ref_bytes))
+    assert nbad == 0, f"{nbad} packed bytes differ, first at {int(np.flatnonzero(got_bytes != ref_bytes)[0])}"
+    lv, sc, of = gpu_unpack(torch, iflow, fmt, packed, rows, cols)
+    assert np.array_equal(lv, q) and np.array_equal(sc, s) and np.array_equal(of, o)
+    ref_deq = orc.dequant(orc.FORMATS[name], q, s, o)
+    got_deq = gpu_dequant(torch, iflow, fmt, packed, rows, cols)
+    assert np.array_equal(got_deq, ref_deq), "dequantized fp16 weights differ"
+    yref = orc.gemm(ref_deq, x16.view(np.uint16), threads=8)
+    y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x16)
+    assert not np.isnan(y).any(), "an output was never written"
+    e = rel_err(y, yref)
+    say(f"        max rel err {e:.3e}")
+    assert e <= TOL
+    return e
+
+
+# ---- config 1: 1024 x 1024, sigma 0.02, batch 1 - every format ---------------------------------------
+@pytest.mark.parametrize("name", NAMES)
+def test_config1_all_steps(gpu, orc, name):
+    torch, iflow = gpu
+    w = synth.weights(1024, 1024, 0.02, synth.BASE_SEED + 1)
+    x = synth.activations(1, 1024, synth.BASE_SEED + 101)
+    check_all(torch, iflow, orc, name, w, x, "config1")
+
+
+# ---- ragged and tiny shapes: single block, partial strips, rows that do not fill a workgroup ------------
+@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("rows,nblocks", [(1, 1), (3, 2), (5, 65), (67, 64), (130, 172), (9, 200)])
+def test_ragged_shapes(gpu, orc, name, rows, nblocks):
+    torch, iflow = gpu
+    cols = nblocks * iflow.format_block(iflow.FORMATS[name])
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + rows * 1000 + nblocks)
+    x = synth.activations(1, cols, synth.BASE_SEED + 7)
+    check_all(torch, iflow, orc, name, w, x, "ragged")
+
+
+# ---- small batches (2, 3, 4 share a pass; 5 and 16 take several) ----------------------------------------
+@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B64", "Q8_B64"])
+@pytest.mark.parametrize("batch", [2, 3, 4, 5, 8, 16])
+def test_small_batch(gpu, orc, name, batch):
+    torch, iflow = gpu
+    rows, cols = 300, 4096 + 64 * 3
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 31, outlier_prob=0.001)
+    x = synth.activations(batch, cols, synth.BASE_SEED + 32)
+    check_all(torch, iflow, orc, name, w, x, "batch")
+
+
+# ---- degenerate values ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", NAMES)
+def test_degenerate_blocks(gpu, orc, name):
+    torch, iflow = gpu
+    rows, cols = 8, 512
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 41)
+    w[0, :] = 0.0                      # all-zero row
+    w[1, :64] = -0.0                   # negative zeros
+    w[2, :] = 0.37                     # constant blocks
+    w[3, :] = np.linspace(-1, 1, cols, dtype=np.float32)      # ramp: exact ties are likely
+    w[4, :] *= 1e-6                    # scale in fp16's subnormal range
+    w[5, :] *= 1e-9                    # range underflows fp16: scale 0
+    w[6, :128] = np.float32(1e-40)     # fp32 subnormals
+    w[7, :] = np.round(w[7, :] * 500) / 4   # many exact .5 ties after division
+    x = synth.activations(1, cols, synth.BASE_SEED + 42)
+    check_all(torch, iflow, orc, name, w, x, "degenerate")
+
+
+def test_exact_ties_round_half_away(gpu, orc):
+    """scale 1, offset 0: levels are the weights themselves, .5 cases must round away from zero."""
+    torch, iflow = gpu
+    base = np.array([0, 0.5, 1.5, 2.5, 3.49, 3.51, 4.5, 10] * 8, np.float32)
+    w = np.tile(base, (4, 1))
+    x = synth.activations(1, 64, synth.BASE_SEED + 43)
+    check_all(torch, iflow, orc, "Q3H_B64", w, x, "ties")
+    w15 = np.tile(np.array([0, 0.5, 1.5, 2.5, 7.5, 14.5, 15, 3] * 8, np.float32), (4, 1))
+    check_all(torch, iflow, orc, "Q4_B64", w15, x, "ties")
+
+
+def test_outliers_config3_shape_slice(gpu, orc):
+    """Config 3's value recipe (0.1 % of entries scaled by 10) on a slice of a 7B-shaped layer, batches 1..4."""
+    torch, iflow = gpu
+    w = synth.weights(256, 11008, 0.02, synth.BASE_SEED + 3, outlier_prob=0.001)
+    for name in ("Q3H_B64", "Q4_B64", "Q8_B64"):
+        for batch in (1, 4):
+            x = synth.activations(batch, 11008, synth.BASE_SEED + 33 + batch)
+            check_all(torch, iflow, orc, name, w, x, "config3-slice")
+
+
+# ---- full-size shapes in the benchmark's launch configuration, checked on sampled rows ------------------
+@pytest.mark.parametrize("rows,cols,sigma", [(4096, 4096, 0.02), (11008, 4096, 0.02), (4096, 11008, 0.02), (8192, 8192, 0.015)])
+def test_full_size_sampled_rows(gpu, orc, rows, cols, sigma):
+    torch, iflow = gpu
+    name, fmt = "Q3H_B64", iflow.FORMATS["Q3H_B64"]
+    say(f"[case] full-size fmt={name} rows={rows} cols={cols}")
+    w = synth.weights(rows, cols, sigma, synth.BASE_SEED + rows + cols)
+    x = synth.activations(1, cols, synth.BASE_SEED + 55)
+    packed, got_bytes = gpu_quantize(torch, iflow, fmt, w)
+    y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x)
+    deq = gpu_dequant(torch, iflow, fmt, packed, rows, cols)
+    idx = synth.sample_rows(rows, 192, synth.BASE_SEED + 56)
+    ofmt = orc.FORMATS[name]
+    q, s, o = orc.quantize(ofmt, w[idx])                       # blocks never cross rows: rows can be checked alone
+    row_bytes = orc.packed_bytes(ofmt, 1, cols)
+    ref_rows = orc.pack_device(ofmt, q, s, o).reshape(len(idx), row_bytes)
+    assert np.array_equal(got_bytes.reshape(rows, row_bytes)[idx], ref_rows)
+    ref_deq = orc.dequant(ofmt, q, s, o)
+    assert np.array_equal(deq[idx], ref_deq)
+    yref = orc.gemm(ref_deq, x.view(np.uint16), threads=8)
+    # the rms floor of the error metric comes from the sampled rows (same distribution as the rest)
+    e = rel_err(y[:, idx], yref)
+    say(f"        max rel err on {len(idx)} sampled rows {e:.3e}")
+    assert e <= TOL
+    # properties that hold at any size: every output written and finite, linear in x
+    assert np.isfinite(y).all()
+    y2 = gpu_gemm(torch, iflow, fmt, packed, rows, cols, (x * np.float16(2)).astype(np.float16))
+    assert np.array_equal(y2, 2 * y)
+
+
+# ---- unit vectors tie the product to the dequantizer; argument errors come back as codes ----------------
+def test_unit_vector_returns_column(gpu, orc):
+    torch, iflow = gpu
+    for name in NAMES:
+        fmt = iflow.FORMATS[name]
+        rows, cols = 70, 4096 + 128
+        w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 61)
+        packed, _ = gpu_quantize(torch, iflow, fmt, w)
+        deq = gpu_dequant(torch, iflow, fmt, packed, rows, cols).view(np.float16).astype(np.float64)
+        for k in (0, 1, 63, 64, 4095, 4096, cols - 1):
+            e = np.zeros((1, cols), np.float16)
+            e[0, k] = 1
+            y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, e)[0]
+            # the kernel removes a conversion bias of up to 2037 * x: exact to fp32 rounding of that magnitude
+            assert np.max(np.abs(y - deq[:, k])) <= 2e-3 * np.max(np.abs(deq[:, k])) + 1e-4, (name, k)
+
+
+def test_argument_errors(gpu):
+    torch, iflow = gpu
+    w = torch.zeros((4, 128), dtype=torch.float32, device="cuda")
+    buf = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.quantize(iflow.Q3H_B64, w, 4, 100, buf, 4096)
+    assert ei.value.status == iflow.ERR_SHAPE
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.quantize(iflow.Q3H_B64, w, 4, 128, buf, 16)
+    assert ei.value.status == iflow.ERR_SIZE
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.quantize(9, w, 4, 128, buf, 4096)
+    assert ei.value.status == iflow.ERR_FORMAT
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.quantize(iflow.Q3H_B64, w.data_ptr() + 4, 4, 128, buf, 4096)
+    assert ei.value.status == iflow.ERR_ALIGN
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.qgemm(iflow.Q3H_B64, buf, 4, 128, w, 0, buf)
+    assert ei.value.status == iflow.ERR_SHAPE

@@ -1,0 +1,123 @@
+"""CPU-only checks of the GPU library's host side: it loads, exports every symbol the header declares,
+validates arguments before touching a device, and its decode constants do what the kernels rely on."""
+import ctypes as C
+import os
+import re
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "iflow.h")
+
+
+@pytest.fixture(scope="module")
+def iflow():
+    from paper_2401_08294_amd import build, iflow as mod
+    if not os.path.exists(mod.LIB_PATH):
+        build.build_lib()
+    mod.lib()
+    return mod
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(iflow_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(iflow):
+    names = declared_symbols()
+    assert {"iflow_quantize", "iflow_dequant", "iflow_qgemv", "iflow_qgemm", "iflow_packed_bytes",
+            "iflow_unpack_logical"} <= set(names)
+    L = iflow.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in iflow.h but not exported"
+    assert iflow.layout_version() == 1
+
+
+def test_format_queries_and_bit_budget(iflow):
+    # Table 3: block sizes, levels (2^k, or 11 for Eq.3) and actual bits per weight
+    expect = {"Q8_B32": (32, 256, 9), "Q8_B64": (64, 256, 8.5), "Q4_B32": (32, 16, 5), "Q4_B64": (64, 16, 4.5),
+              "Q3H_B64": (64, 11, 4)}
+    for name, (bs, lv, bpw) in expect.items():
+        f = iflow.FORMATS[name]
+        assert iflow.format_block(f) == bs and iflow.format_levels(f) == lv
+        for r, c in ((1, 64), (4096, 4096), (4096, 11008), (28672, 8192)):
+            assert Fraction(iflow.packed_bytes(f, r, c) * 8, r * c) == Fraction(bpw)
+    assert iflow.format_block(17) == -1 and iflow.format_levels(-1) == -1
+
+
+def test_argument_validation_happens_before_any_launch(iflow):
+    L = iflow.lib()
+    sz = C.c_size_t(0)
+    assert L.iflow_packed_bytes(4, 8, 100, C.byref(sz)) == iflow.ERR_SHAPE      # cols % 64 != 0
+    assert L.iflow_packed_bytes(4, 0, 64, C.byref(sz)) == iflow.ERR_SHAPE
+    assert L.iflow_packed_bytes(4, 8, 1 << 31, C.byref(sz)) == iflow.ERR_SHAPE
+    assert L.iflow_packed_bytes(5, 8, 64, C.byref(sz)) == iflow.ERR_FORMAT
+    assert L.iflow_packed_bytes(4, 8, 64, None) == iflow.ERR_NULL
+    good = 0x10000                                                               # aligned, never dereferenced
+    assert L.iflow_quantize(4, None, 8, 64, good, 256, None) == iflow.ERR_NULL
+    assert L.iflow_quantize(4, good, 8, 64, good, 255, None) == iflow.ERR_SIZE
+    assert L.iflow_quantize(4, good + 8, 8, 64, good, 256, None) == iflow.ERR_ALIGN
+    assert L.iflow_quantize(4, good, 8, 32, good, 256, None) == iflow.ERR_SHAPE
+    assert L.iflow_dequant(4, good, 8, 64, None, None) == iflow.ERR_NULL
+    assert L.iflow_dequant(7, good, 8, 64, good, None) == iflow.ERR_FORMAT
+    assert L.iflow_qgemv(4, good, 8, 64, good, good + 2, None) == iflow.ERR_ALIGN
+    assert L.iflow_qgemm(4, good, 8, 64, good, 0, good, None) == iflow.ERR_SHAPE
+    assert L.iflow_qgemm(4, good, 8, 64, None, 3, good, None) == iflow.ERR_NULL
+    assert L.iflow_unpack_logical(4, good, 8, 64, good, good, None, None) == iflow.ERR_NULL
+    for st in range(8):
+        assert isinstance(iflow.status_string(st), str) and iflow.status_string(st)
+    with pytest.raises(iflow.IflowError):
+        iflow.packed_bytes(4, 3, 65)
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    from paper_2401_08294_amd import iflow as mod
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libiflow.so"))
+    with pytest.raises(RuntimeError):
+        mod.lib()
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2401_08294_amd")
+    bad = re.compile(r"(^\s*(from|import)\s+oracle\b)|liboracle|iflow_oracle|orc_[a-z0-9_]+\s*\(", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not bad.search(text), f"{f} reaches into the oracle"
+
+
+# ---- the fp16 / u16 identities the Q3H decode relies on, checked for every code with exact arithmetic ----
+def _fp16_round(v: Fraction) -> int:
+    f = float(v)
+    assert Fraction(f) == v
+    return int(np.float64(f).astype(np.float16).view(np.uint16))
+
+
+def test_q3h_packed_decode_identities():
+    K1 = Fraction(1489, 1 << 14)          # fp16 nearest to 1/11
+    K2 = Fraction(1863, 2)                # 931.5
+    assert _fp16_round(K1) == 0x2DD1 and _fp16_round(K2) == 0x6347
+    for c in range(121):
+        hc = 0x6400 | c                                               # fp16 1024 + c
+        h1 = _fp16_round((1024 + c) * K1 + K2)                        # one fused multiply-add
+        assert h1 == 0x6401 + c // 11                                 # fp16 1025 + floor(c/11)
+        h2 = (h1 * 0xFFF5 + hc) & 0xFFFF                              # packed u16 multiply-add by -11
+        assert h2 == 0x17F5 + c % 11
+        val = np.array([h2], np.uint16).view(np.float16)[0]
+        assert Fraction(float(val)) == Fraction(2037 + c % 11, 1 << 20)
+
+
+def test_q4_q8_magic_number_identities():
+    for v in range(16):
+        lo = np.array([0x6400 | v], np.uint16).view(np.float16)[0]
+        hi = np.array([0x5400 | (v << 4)], np.uint16).view(np.float16)[0]
+        assert float(lo) == 1024 + v and float(hi) == 64 + v
+    for v in range(256):
+        b = np.array([0x6400 | v], np.uint16).view(np.float16)[0]
+        assert float(b) == 1024 + v
