@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode step's weight stream: 3.5-bit fused dequant-GEMV on Llama-2-7B-shaped layers, batch 1.
+
+A "step" is one pass of the hot path over one decoder layer's seven linears (q, k, v, o 4096x4096; gate, up
+11008x4096; down 4096x11008): seven iflow_qgemv launches that stream 96.5 MiB of packed 3.5-bit weights once.
+Successive steps walk a ring of distinct layers (> 1 GiB of packed weights) so that no launch finds its
+weights in the 256 MB Infinity Cache or in L2: the figure is an HBM figure.  Weights are seeded synthetic
+Gaussians (sigma 0.02) quantized on the GPU by iflow_quantize before the timed region; activations are seeded
+N(0,1) fp16.  Launches are captured once into a HIP graph (one graph = one trip round the ring) and replayed;
+the timed region is bracketed by HIP events on the launch stream and by device synchronisation.
+
+Prints ONE JSON line.  `value` = algorithmic bytes per step / time per step, in GB/s (weights incl. block
+headers + activations + outputs).  `roofline` prices the GEMV kernel against 8 TB/s; `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+SIGMA = 0.02
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1600)
+    ap.add_argument("--warmup", type=int, default=160)
+    ap.add_argument("--ring", type=int, default=16, help="distinct layers in the weight ring (16 = 1.5 GiB packed)")
+    ap.add_argument("--format", default="Q3H_B64")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(rows, cols, bits_per_weight, batch=1):
+    """What the method must move once: packed weights incl. headers, activations in, outputs out."""
+    return rows * cols * bits_per_weight / 8.0 + 2.0 * batch * cols + 2.0 * batch * rows
+
+
+def cpu_baseline(fmt_name: str, reps: int = 3):
+    """The oracle, as it stands, on a bounded sample: one layer's seven linears (202 M weights), `reps` times."""
+    import numpy as np
+    from oracle import oracle
+    from paper_2401_08294_amd import synth
+    ofmt = oracle.FORMATS[fmt_name]
+    bpw = oracle.packed_bytes(ofmt, 64, 64) * 8 / 4096.0
+    threads = max(1, min(16, os.cpu_count() or 1))
+    total_bytes, total_s, used = 0.0, 0.0, 1
+    for i, (_, rows, cols) in enumerate(synth.LLAMA2_7B_LAYER):
+        w = synth.weights(rows, cols, SIGMA, synth.BASE_SEED + 900 + i)
+        x = synth.activations(1, cols, synth.BASE_SEED + 950 + i)
+        q, s, o = oracle.quantize(ofmt, w)
+        rec = oracle.pack_canonical(ofmt, q, s, o)
+        del w, q
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            _, used = oracle.qgemm_canonical(ofmt, rec, rows, cols, x.view(np.uint16), threads=threads)
+            total_s += time.perf_counter() - t0
+            total_bytes += algorithmic_bytes(rows, cols, bpw)
+    return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "sample": f"unpack + dequantize + fp64 GEMV of one layer's seven linears, {reps} passes "
+                      f"({total_bytes / 1e6:.0f} MB of packed weights in {total_s:.1f} s); the multiply is row-parallel "
+                      f"over {used} threads, unpack and dequantize are serial"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); nothing was run", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2401_08294_amd import iflow, synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    iflow.lib()
+    dev = torch.device("cuda:0")
+    fmt = iflow.FORMATS[args.format]
+    bpw = iflow.BITS_PER_WEIGHT[fmt]
+    shapes = synth.LLAMA2_7B_LAYER
+
+    # ---- build the ring of quantized layers (untimed) --------------------------------------------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED + 2)
+    ring = []
+    for layer in range(args.ring):
+        mats = []
+        for name, rows, cols in shapes:
+            w = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+            n = iflow.packed_bytes(fmt, rows, cols)
+            packed = torch.empty(n, dtype=torch.uint8, device=dev)
+            iflow.quantize(fmt, w, rows, cols, packed, n)
+            mats.append((rows, cols, packed))
+            del w
+        ring.append(mats)
+    xs = {cols: torch.randn((cols,), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+          for cols in {c for _, _, c in shapes}}
+    ys = [torch.empty((rows,), dtype=torch.float16, device=dev) for _, rows, _ in shapes]
+    torch.cuda.synchronize()
+
+    step_bytes = sum(algorithmic_bytes(r, c, bpw) for _, r, c in shapes)
+    launches_per_step = len(shapes)
+
+    stream = torch.cuda.Stream()
+    raw = stream.cuda_stream
+
+    def one_step(layer):
+        for (rows, cols, packed), y in zip(ring[layer], ys):
+            iflow.qgemv(fmt, packed, rows, cols, xs[cols], y, stream=raw)
+
+    graph = None
+    with torch.cuda.stream(stream):
+        for layer in range(min(2, args.ring)):      # load code objects before capture
+            one_step(layer)
+        stream.synchronize()
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for layer in range(args.ring):
+                    one_step(layer)
+
+        def run(nsteps, start_layer=0):
+            done, layer = 0, start_layer
+            while done < nsteps:
+                if graph is not None and layer == 0 and nsteps - done >= args.ring:
+                    graph.replay()
+                    done += args.ring
+                else:
+                    one_step(layer)
+                    done += 1
+                    layer = (layer + 1) % args.ring
+            return layer
+
+        run(args.warmup)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        run(args.steps)
+        e1.record(stream)
+        e1.synchronize()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+
+    ms_per_step = ms / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    us_per_launch = ms_per_step * 1e3 / launches_per_step
+    bytes_per_launch = step_bytes / launches_per_step
+    achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
+
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "qgemv_q3h_7b_traffic.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "achieved HBM GB/s (% of peak) of 3.5-bit fused dequant-GEMV, 7B shapes, batch 1",
+        "value": round(value, 1), "unit": "GB/s", "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 x u7-pair codes, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "llama2-7b decoder-layer linears (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
+                               f"{args.format}, batch 1, ring of {args.ring} distinct layers "
+                               f"({args.ring * step_bytes / 2**30:.2f} GiB packed), "
+                               + ("HIP-graph replay" if graph is not None else "eager launches"),
+                   "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": launches_per_step},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": "iflow::qgemv_kernel<Q3H_B64, batch 1>", "avg_launch_us": round(us_per_launch, 3),
+                     "algorithmic_bytes_per_launch": int(bytes_per_launch)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.format)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

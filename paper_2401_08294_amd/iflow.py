@@ -36,6 +36,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
                                "or `python -m paper_2401_08294_amd.build`")
+        # PyTorch ships its own HIP runtime; import it first so that the library binds to that same
+        # runtime (two runtimes in one process do not share devices, streams or memory).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         i64, p, sz = C.c_int64, C.c_void_p, C.c_size_t
         L.iflow_layout_version.restype = C.c_int
