@@ -13,6 +13,8 @@
 // (1024 + q, 64 + q), and the known bias times sum(x) is removed together with the header.
 // Row sums are reduced across the wavefront with DPP, across the wavefronts of a workgroup (one per
 // strip) through LDS.
+#include <stdlib.h>
+
 #include "iflow_common.h"
 
 namespace iflow {
@@ -35,13 +37,13 @@ template <int KIND> struct XRegs {
 __device__ __forceinline__ float dot2(half2_t a, half2_t b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
 
 template <int KIND>
-__device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restrict__ x, int k0, bool active)
+__device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restrict__ x, int k0)
 {
     constexpr int XD = Geo<KIND>::XD;
     uint32_t n[XD];
 #pragma unroll
     for (int j = 0; j < XD / 4; ++j) {
-        uint4 q = active ? reinterpret_cast<const uint4 *>(x + k0)[j] : make_uint4(0u, 0u, 0u, 0u);
+        uint4 q = reinterpret_cast<const uint4 *>(x + k0)[j];
         n[4 * j] = q.x; n[4 * j + 1] = q.y; n[4 * j + 2] = q.z; n[4 * j + 3] = q.w;
     }
     const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
@@ -88,10 +90,12 @@ __device__ __forceinline__ void lane_dot(const WRegs<KIND> &w, const XRegs<KIND>
         float a1[NB], a2[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) { a1[b] = 0.f; a2[b] = 0.f; }
+        uint32_t cmask = 0x007F007Fu, magic = 0x64006400u;
+        asm volatile("" : "+v"(cmask), "+v"(magic));                              // registers, so that (d & m) | k is one v_and_or_b32
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const uint32_t hc0 = (w.d[i] & 0x007F007Fu) | 0x64006400u;            // codes 4i, 4i+1
-            const uint32_t hc1 = ((w.d[i] >> 7) & 0x007F007Fu) | 0x64006400u;     // codes 4i+2, 4i+3
+            const uint32_t hc0 = (w.d[i] & cmask) | magic;                        // codes 4i, 4i+1
+            const uint32_t hc1 = ((w.d[i] >> 7) & cmask) | magic;                 // codes 4i+2, 4i+3
             const half2_t h1a = q3h_high_digit(hc0), h1b = q3h_high_digit(hc1);
             const half2_t h2a = q3h_low_digit(h1a, hc0), h2b = q3h_low_digit(h1b, hc1);
 #pragma unroll
@@ -144,19 +148,55 @@ __device__ __forceinline__ uint32_t q3h_header(const uint32_t (&d)[8])
 {
     uint32_t h = d[0] & 0xC000C000u;
 #pragma unroll
-    for (int i = 1; i < 8; ++i) h = (h >> 2) | (d[i] & 0xC000C000u);
+    for (int i = 1; i < 8; ++i) h = (d[i] & 0xC000C000u) | (h >> 2);
     return h;
 }
 
-template <int F, int NB, int U>
-__global__ __launch_bounds__(1024) void qgemv_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
-                                                     uint16_t *__restrict__ Y, int rows, int cols, int nbk, int rows_per_wg,
-                                                     int nstrips, int64_t header_offset)
+// ---- transpose-reduce: U per-lane partials (one per row) -> row sums ---------------------------------
+// On return, every lane with (lane & (U-1)) == u holds the sum over all 64 lanes of v[u].
+__device__ __forceinline__ float xor_lanes_16(float v) { return __shfl_xor(v, 16); }
+__device__ __forceinline__ float xor_lanes_32(float v) { return __shfl_xor(v, 32); }
+
+template <int U>
+__device__ __forceinline__ float reduce_rows(float (&v)[U], int lane)
+{
+    static_assert(U == 1 || U == 2 || U == 4, "group size");
+    float r;
+    if (U == 4) {
+        const bool b0 = lane & 1, b1 = lane & 2;
+        // keep one of each pair, hand the other to the neighbour that keeps it
+        float k0 = b0 ? v[1] : v[0], g0 = b0 ? v[0] : v[1];
+        float k1 = b0 ? v[3] : v[2], g1 = b0 ? v[2] : v[3];
+        float r0 = k0 + dpp_f32<0xB1, 0xF>(g0);          // lanes ^1
+        float r1 = k1 + dpp_f32<0xB1, 0xF>(g1);
+        float k = b1 ? r1 : r0, g = b1 ? r0 : r1;
+        r = k + dpp_f32<0x4E, 0xF>(g);                   // lanes ^2: lane & 3 == u holds the quad sum of v[u]
+    } else if (U == 2) {
+        const bool b0 = lane & 1;
+        float k = b0 ? v[1] : v[0], g = b0 ? v[0] : v[1];
+        r = k + dpp_f32<0xB1, 0xF>(g);
+        r += dpp_f32<0x4E, 0xF>(r);
+    } else {
+        r = v[0];
+        r += dpp_f32<0xB1, 0xF>(r);
+        r += dpp_f32<0x4E, 0xF>(r);
+    }
+    r += dpp_f32<0x124, 0xF>(r);                         // row_ror:4  (rotations by 4 keep lane & 3)
+    r += dpp_f32<0x128, 0xF>(r);                         // row_ror:8  -> sum over the 16-lane row
+    r += xor_lanes_16(r);
+    r += xor_lanes_32(r);
+    return r;
+}
+
+template <int F, int NB, int U, bool MULTI>
+__global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
+                                                                  uint16_t *__restrict__ Y, int rows, int cols, int nbk, int rows_per_wg,
+                                                                  int nstrips, int64_t header_offset)
 {
     typedef Fmt<F> T;
     constexpr int KIND = T::kind;
     typedef Geo<KIND> G;
-    __shared__ float part[16][NB][64];
+    __shared__ float part[MULTI ? 16 : 1][NB][64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int r0 = blockIdx.x * rows_per_wg;
@@ -164,13 +204,12 @@ __global__ __launch_bounds__(1024) void qgemv_kernel(const uint8_t *__restrict__
     float tot[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) tot[b] = 0.f;
-
     for (int t = wave; t < nstrips; t += nw) {
-        const int k0 = (t * 64 + lane) * G::WPL;              // first column of this lane
-        const bool active = k0 < cols;                        // the last strip may be ragged
-        XRegs<KIND> xr[NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) load_x<KIND>(xr[b], X + (int64_t)b * cols, k0, active);
+        // The last strip may be ragged: lanes past the end redo the strip's first lane (every load stays in
+        // bounds and unconditional, so the compiler can wait per load) and their sums are dropped.
+        const bool active = (t * 64 + lane) * G::WPL < cols;
+        const int k0 = (t * 64 + (active ? lane : 0)) * G::WPL;   // first column of this lane
+        const int lane_a = active ? lane : 0;
 
         // where this lane's codes (and, for Q4/Q8, its header) sit inside a row
         int64_t code_off, row_stride, hdr_off = 0;
@@ -178,29 +217,41 @@ __global__ __launch_bounds__(1024) void qgemv_kernel(const uint8_t *__restrict__
         if (KIND == KIND_Q3H) {
             const int n_t = min(64, nbk - t * 64);
             row_stride = (int64_t)nbk * 32;
-            code_off = (int64_t)t * 2048 + lane * 16;
+            code_off = (int64_t)t * 2048 + lane_a * 16;
             plane1 = n_t * 16;
         } else {
             row_stride = (KIND == KIND_Q4) ? cols / 2 : cols;
             code_off = (KIND == KIND_Q4) ? k0 / 2 : k0;
             hdr_off = header_offset + (int64_t)(k0 / T::block) * 4;
         }
+        const uint8_t *lane_base = packed + code_off;
 
-        for (int i = 0; i < nr; i += U) {
-            WRegs<KIND> w[U];
+        auto load_group = [&](WRegs<KIND>(&w)[U], int i) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + min(i + u, nr - 1);        // rows past the end repeat the last one and are dropped below
-                const uint8_t *p = packed + (int64_t)r * row_stride + code_off;
-                uint4 a = active ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0u, 0u, 0u, 0u);
+                const uint8_t *p = lane_base + (int64_t)r * row_stride;
+                uint4 a = *reinterpret_cast<const uint4 *>(p);
                 w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
                 if (KIND == KIND_Q3H) {
-                    uint4 c = active ? *reinterpret_cast<const uint4 *>(p + plane1) : make_uint4(0u, 0u, 0u, 0u);
+                    uint4 c = *reinterpret_cast<const uint4 *>(p + plane1);
                     w[u].d[4] = c.x; w[u].d[5] = c.y; w[u].d[6] = c.z; w[u].d[7] = c.w;
                 } else {
-                    w[u].hdr = active ? *reinterpret_cast<const uint32_t *>(packed + hdr_off + (int64_t)r * nbk * 4) : 0u;
+                    w[u].hdr = *reinterpret_cast<const uint32_t *>(packed + hdr_off + (int64_t)r * nbk * 4);
                 }
             }
+        };
+
+        // the first rows' weights are requested before anything waits on the activations
+        WRegs<KIND> wa[U], wb[U];
+        load_group(wa, 0);
+        XRegs<KIND> xr[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) load_x<KIND>(xr[b], X + (int64_t)b * cols, k0);
+        const float keep = active ? 1.0f : 0.0f;
+
+        auto compute_group = [&](const WRegs<KIND>(&w)[U], int i) {
+            float v[NB][U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float acc[NB];
@@ -210,16 +261,27 @@ __global__ __launch_bounds__(1024) void qgemv_kernel(const uint8_t *__restrict__
                 const half2_t so = as_h2(hdr);
                 const float s = (float)so.x, o = (float)so.y;
 #pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    float v = __builtin_fmaf(s, acc[b] - xr[b].bias_sum, o * xr[b].x_sum);
-                    v = wave_sum(v);
-                    if (lane == i + u) tot[b] += v;             // lanes >= nr are never written out
-                }
+                for (int b = 0; b < NB; ++b) v[b][u] = keep * __builtin_fmaf(s, acc[b] - xr[b].bias_sum, o * xr[b].x_sum);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float r = reduce_rows<U>(v[b], lane);
+                if ((lane & ~(U - 1)) == i) tot[b] += r;      // lane i+u (u = lane & (U-1)) takes row i+u; lanes >= nr are never stored
+            }
+        };
+
+        for (int i = 0; i < nr; i += 2 * U) {                 // two groups per trip: one computes while the other loads
+            const bool more = i + U < nr;
+            if (more) load_group(wb, i + U);
+            compute_group(wa, i);
+            if (more) {
+                if (i + 2 * U < nr) load_group(wa, i + 2 * U);
+                compute_group(wb, i + U);
             }
         }
     }
 
-    if (nw > 1) {                                             // one wavefront per strip: add the strips up
+    if (MULTI) {                                              // one wavefront per strip: add the strips up
 #pragma unroll
         for (int b = 0; b < NB; ++b) part[wave][b][lane] = tot[b];
         __syncthreads();
@@ -238,22 +300,216 @@ __global__ __launch_bounds__(1024) void qgemv_kernel(const uint8_t *__restrict__
     }
 }
 
+// ---- Q3H: workgroup-shared activations ----------------------------------------------------------------
+// The strip's activations are the same for every wavefront that works on it, and arranging them for the
+// decode costs about as much as one row of weights.  So a workgroup does it once: `wps` wavefronts per
+// strip permute the strip's 4096 activations into LDS in decode order (plus the two bias constants per
+// lane), and after one barrier every wavefront fetches its 32 registers with eight 16-byte LDS reads.
+// Each wavefront then handles U consecutive rows in straight-line code: all 2U weight loads are issued
+// before the staging (row base addresses are wave-uniform, so a load costs no vector arithmetic), and each
+// row is decoded as soon as its own two loads have landed.  Selects are written as multiplications by
+// 0/1 and row sums use plain DPP adds: on this part v_cndmask and ds_bpermute are several times slower
+// than an add.
+//
+// LDS layout per (strip slot, batch column): float4 xs[8][64] (register quad jj of lane l at [jj][l]), then
+// float2 sums[64] = (bias_sum, x_sum) of lane l.  After that, for the cross-strip sum, float part[S][wps*U][NB].
+template <int NB, int U>
+__global__ __launch_bounds__(1024) void q3h_gemv_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
+                                                        uint16_t *__restrict__ Y, int rows, int cols, int nbk, int nstrips,
+                                                        int S, int wps)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    constexpr int SLOT_BYTES = 8 * 64 * 16 + 64 * 8;          // xs + sums of one (strip slot, batch column)
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction: keep it scalar
+    const int slot = wave / wps, sub = wave - slot * wps;      // which strip of the pass, which row group
+    const int rows_per_wg = wps * U;
+    const int r0 = blockIdx.x * rows_per_wg + sub * U;         // first row of this wavefront
+    const int64_t row_stride = (int64_t)nbk * 32;
+    float *part = reinterpret_cast<float *>(lds + (size_t)S * NB * SLOT_BYTES);
+
+    float tot[NB][U];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int u = 0; u < U; ++u) tot[b][u] = 0.f;
+
+    for (int t0 = 0; t0 < nstrips; t0 += S) {                  // one pass unless the row is longer than S strips
+        const int t = t0 + slot;
+        const float strip_keep = t < nstrips ? 1.0f : 0.0f;    // wavefronts without a strip redo the last one, result dropped
+        const int tc = t < nstrips ? t : nstrips - 1;
+        const int n_t = min(64, nbk - tc * 64);                // blocks in this strip (ragged at the end of a row)
+        const uint32_t lane_off = (lane < n_t ? lane : 0) * 16;   // lanes past the end redo block 0: loads stay in bounds
+
+        // 1. request this thread's first chunk of activations BEFORE the weights: memory queues are served in
+        //    order, and everything else in the workgroup waits for the staged activations.
+        //    Thread c of the strip's wps*64 threads takes 16-value chunks c, c + wps*64, ...;
+        //    chunk = (batch column c/256, block blk = (c%256)/4, quarter qd = c%4) -> decode slots 4qd..4qd+3.
+        const int tid_s = sub * 64 + lane;
+        const int nchunks = 256 * NB;
+        auto chunk_src = [&](int c) {
+            const int bcol = c >> 8, cc = c & 255;
+            const int ccl = (cc >> 2) < n_t ? cc : 0;          // chunks past the end of the row read chunk 0 and are zeroed
+            return reinterpret_cast<const uint4 *>(X + (int64_t)bcol * cols + (int64_t)tc * 4096 + ccl * 16);
+        };
+        auto chunk_put = [&](int c, const uint4 q0, const uint4 q1) {
+            const int bcol = c >> 8, cc = c & 255, blk = cc >> 2, qd = cc & 3;
+            const uint32_t live = blk < n_t ? 0xFFFFFFFFu : 0u;   // columns past the end of the row count as zero
+            const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
+            const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
+            uint32_t e[4], o[4];
+            float se = 0.f, so = 0.f;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                e[m] = __builtin_amdgcn_perm(n[2 * m + 1], n[2 * m], 0x05040100u);    // (x[4m], x[4m+2])
+                o[m] = __builtin_amdgcn_perm(n[2 * m + 1], n[2 * m], 0x07060302u);    // (x[4m+1], x[4m+3])
+                se = dot2(as_h2(e[m]), ones, se);
+                so = dot2(as_h2(o[m]), ones, so);
+            }
+            uint8_t *sl = lds + (size_t)(slot * NB + bcol) * SLOT_BYTES;
+            *reinterpret_cast<uint4 *>(sl + (qd * 64 + blk) * 16) = make_uint4(e[0], e[1], e[2], e[3]);
+            *reinterpret_cast<uint4 *>(sl + ((4 + qd) * 64 + blk) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+            float bs = IFLOW_Q3H_BIAS1 * se + IFLOW_Q3H_BIAS2 * so, xs = se + so;
+            bs += dpp_f32<0xB1, 0xF>(bs); xs += dpp_f32<0xB1, 0xF>(xs);              // the four quarters of a block
+            bs += dpp_f32<0x4E, 0xF>(bs); xs += dpp_f32<0x4E, 0xF>(xs);              // sit in one quad of lanes
+            if (qd == 0) *reinterpret_cast<float2 *>(sl + 8 * 64 * 16 + blk * 8) = make_float2(bs, xs);
+        };
+        const bool has_chunk = tid_s < nchunks;                // whole wavefronts have a first chunk or not
+        const uint4 *src0 = chunk_src(has_chunk ? tid_s : 0);
+        const uint4 xq0 = src0[0], xq1 = src0[1];
+
+        // 2. request the weights of all U rows: scalar row base + per-lane offset
+        WRegs<KIND_Q3H> w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = min(r0 + u, rows - 1);               // rows past the end repeat the last one and are not stored
+            const uint8_t *p0 = packed + (int64_t)r * row_stride + (int64_t)tc * 2048;
+            const uint8_t *p1 = p0 + n_t * 16;
+            const uint4 a = *reinterpret_cast<const uint4 *>(p0 + lane_off);
+            const uint4 c = *reinterpret_cast<const uint4 *>(p1 + lane_off);
+            w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
+            w[u].d[4] = c.x; w[u].d[5] = c.y; w[u].d[6] = c.z; w[u].d[7] = c.w;
+        }
+
+        // stage: permute the activations into decode order in LDS
+        if (t0 > 0) __syncthreads();                           // the previous pass is done with LDS
+        if (has_chunk) chunk_put(tid_s, xq0, xq1);
+#pragma unroll 1
+        for (int c = tid_s + wps * 64; c < nchunks; c += wps * 64) {
+            const uint4 *src = chunk_src(c);
+            chunk_put(c, src[0], src[1]);
+        }
+        __syncthreads();
+
+        // 3. this lane's activations, in decode order
+        XRegs<KIND_Q3H> xr[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const uint8_t *sl = lds + (size_t)(slot * NB + b) * SLOT_BYTES;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
+                xr[b].v[4 * jj] = as_h2(q.x); xr[b].v[4 * jj + 1] = as_h2(q.y);
+                xr[b].v[4 * jj + 2] = as_h2(q.z); xr[b].v[4 * jj + 3] = as_h2(q.w);
+            }
+            const float2 sm = *reinterpret_cast<const float2 *>(sl + 8 * 64 * 16 + lane * 8);
+            xr[b].bias_sum = sm.x; xr[b].x_sum = sm.y;
+        }
+
+        // 4. decode and multiply, row by row as the loads land; lanes past the end see x = 0 and add nothing
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float acc[NB];
+            lane_dot<KIND_Q3H, NB>(w[u], xr, acc);
+            const half2_t so = as_h2(q3h_header(w[u].d));
+            const float s = (float)so.x, o = (float)so.y;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float v = __builtin_fmaf(s, acc[b] - xr[b].bias_sum, o * xr[b].x_sum);
+                tot[b][u] = __builtin_fmaf(strip_keep, wave_sum_to_lane63(v), tot[b][u]);   // valid in lane 63
+            }
+        }
+    }
+
+    if (S == 1) {
+        if (lane == 63) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (r0 + u < rows) Y[(int64_t)b * rows + r0 + u] = as_u16((half_t)tot[b][u]);
+        }
+    } else {                                                   // add the strips of a row up through LDS
+        if (lane == 63) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int u = 0; u < U; ++u) part[(slot * rows_per_wg + sub * U + u) * NB + b] = tot[b][u];
+        }
+        __syncthreads();
+        const int i = threadIdx.x;                             // (row in workgroup, batch column)
+        if (i < rows_per_wg * NB) {
+            const int rr = i / NB, b = i - rr * NB;
+            float sum = 0.f;
+            for (int s2 = 0; s2 < S; ++s2) sum += part[(s2 * rows_per_wg + rr) * NB + b];
+            const int r = blockIdx.x * rows_per_wg + rr;
+            if (r < rows) Y[(int64_t)b * rows + r] = as_u16((half_t)sum);
+        }
+    }
+}
+
 // ---- host side ------------------------------------------------------------------------------------
 // Launch geometry: one wavefront per strip (at most 16 per workgroup, further strips are looped), and
 // rows_per_wg chosen so that the grid has a few wavefronts per SIMD on a 256-CU part.
 static int pick_rows_per_wg(int64_t rows, int waves_per_wg)
 {
-    const int64_t target_waves = 256 * 4 * 3;
+    static const char *env = getenv("IFLOW_DEBUG_ROWS_PER_WG");
+    if (env) return atoi(env);
+    const int64_t target_waves = 256 * 4 * 2;
     int64_t r = (rows * waves_per_wg + target_waves - 1) / target_waves;
-    if (r < 2) r = 2;
+    r = (r + 3) / 4 * 4;                                      // whole groups of four rows
+    if (r < 4) r = 4;
     if (r > 64) r = 64;
     return (int)r;
+}
+
+static int env_int(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : dflt;
+}
+
+// Q3H launch geometry.  S strips of a row per workgroup (all of them when LDS allows), wps wavefronts per strip,
+// U rows per wavefront: a workgroup covers wps*U rows and has S*wps <= 16 wavefronts.
+template <int NB>
+static hipError_t q3h_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y, hipStream_t s)
+{
+    const int nbk = (int)(cols / 64);
+    const int nstrips = (nbk + 63) / 64;
+    int S = 7 / NB;                                           // LDS: 8.5 KiB per strip and batch column, kept under 64 KiB
+    if (S > nstrips) S = nstrips;
+    static const int dbg_wps = env_int("IFLOW_DEBUG_WPS", 0), dbg_u = env_int("IFLOW_DEBUG_U", 0);
+    int wps = 16 / S;
+    if (wps > 4) wps = 4;
+    int U = 4;
+    if (rows * nstrips <= 8192) U = 2;                        // small matrices: more, shorter wavefronts
+    if (dbg_wps > 0) wps = dbg_wps;
+    if (dbg_u > 0) U = dbg_u;
+    const int64_t grid = (rows + (int64_t)wps * U - 1) / ((int64_t)wps * U);
+    const size_t lds = (size_t)S * NB * (8 * 64 * 16 + 64 * 8) + (size_t)S * wps * U * NB * 4;
+    const dim3 block(64 * S * wps);
+#define IFLOW_Q3H_GO(UU) hipLaunchKernelGGL((q3h_gemv_kernel<NB, UU>), dim3((unsigned)grid), block, lds, s, \
+        static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, nstrips, S, wps)
+    if (U == 1) IFLOW_Q3H_GO(1); else if (U == 2) IFLOW_Q3H_GO(2); else IFLOW_Q3H_GO(4);
+#undef IFLOW_Q3H_GO
+    return hipGetLastError();
 }
 
 template <int F, int NB>
 static hipError_t gemv_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y, hipStream_t s)
 {
     typedef Fmt<F> T;
+    if (T::kind == KIND_Q3H) return q3h_launch<NB>(packed, rows, cols, X, Y, s);
     typedef Geo<T::kind> G;
     const int nbk = (int)(cols / T::block);
     const int nstrips = (int)((cols + 64 * G::WPL - 1) / (64 * G::WPL));
@@ -261,9 +517,13 @@ static hipError_t gemv_launch(const void *packed, int64_t rows, int64_t cols, co
     const int rpw = pick_rows_per_wg(rows, nw);
     const int64_t grid = (rows + rpw - 1) / rpw;
     const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;
-    constexpr int U = (T::kind == KIND_Q3H) ? 2 : 4;
-    hipLaunchKernelGGL((qgemv_kernel<F, NB, U>), dim3((unsigned)grid), dim3(64 * nw), 0, s,
-                       static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, rpw, nstrips, header_offset);
+    constexpr int U = 4;
+    if (nw == 1)
+        hipLaunchKernelGGL((qgemv_kernel<F, NB, U, false>), dim3((unsigned)grid), dim3(64), 0, s,
+                           static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, rpw, nstrips, header_offset);
+    else
+        hipLaunchKernelGGL((qgemv_kernel<F, NB, U, true>), dim3((unsigned)grid), dim3(64 * nw), 0, s,
+                           static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, rpw, nstrips, header_offset);
     return hipGetLastError();
 }
 
