@@ -301,59 +301,71 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
 }
 
 // ---- Q3H: workgroup-shared activations ----------------------------------------------------------------
-// The strip's activations are the same for every wavefront that works on it, and arranging them for the
-// decode costs about as much as one row of weights.  So a workgroup does it once: `wps` wavefronts per
-// strip permute the strip's 4096 activations into LDS in decode order (plus the two bias constants per
-// lane), and after one barrier every wavefront fetches its 32 registers with eight 16-byte LDS reads.
-// Each wavefront then handles U consecutive rows in straight-line code: all 2U weight loads are issued
-// before the staging (row base addresses are wave-uniform, so a load costs no vector arithmetic), and each
-// row is decoded as soon as its own two loads have landed.  Selects are written as multiplications by
-// 0/1 and row sums use plain DPP adds: on this part v_cndmask and ds_bpermute are several times slower
-// than an add.
+// The activations are the same for every wavefront, and arranging a strip of them for the decode costs
+// about as much as one row of weights.  So a workgroup does it once: its threads permute the activations
+// of up to T strips into LDS in decode order (plus the two bias constants per lane), and after one barrier
+// every wavefront fetches the 32 registers of a strip with eight 16-byte LDS reads.  A wavefront owns U
+// consecutive rows and walks along them strip by strip: per strip it requests the 2U weight loads, reloads
+// its activation registers from LDS and decodes each row as soon as that row's two loads have landed.  The
+// per-lane partial sums of a row are carried across the strips in a register, so a row is reduced across
+// the wavefront once, with DPP adds, and no wavefront ever waits for another one after the barrier.
+// Measured on MI355X: v_cndmask and ds_bpermute cost several times a plain add, so selects are written as
+// masks or multiplications by 0/1; row base addresses are wave-uniform (scalar registers), so a weight load
+// costs no vector arithmetic; the activation loads are issued before the first weight loads because memory
+// queues are served in order and the whole workgroup waits for the staged activations.
 //
-// LDS layout per (strip slot, batch column): float4 xs[8][64] (register quad jj of lane l at [jj][l]), then
-// float2 sums[64] = (bias_sum, x_sum) of lane l.  After that, for the cross-strip sum, float part[S][wps*U][NB].
+// LDS layout per (strip, batch column): float4 xs[8][64] (register quad jj of lane l at [jj][l]), then
+// float2 sums[64] = (bias_sum, x_sum) of lane l.
 template <int NB, int U>
 __global__ __launch_bounds__(1024) void q3h_gemv_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
                                                         uint16_t *__restrict__ Y, int rows, int cols, int nbk, int nstrips,
-                                                        int S, int wps)
+                                                        int T, int G)
 {
     extern __shared__ __align__(16) uint8_t lds[];
-    constexpr int SLOT_BYTES = 8 * 64 * 16 + 64 * 8;          // xs + sums of one (strip slot, batch column)
+    constexpr int SLOT_BYTES = 8 * 64 * 16 + 64 * 8;          // xs + sums of one (strip, batch column)
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction: keep it scalar
-    const int slot = wave / wps, sub = wave - slot * wps;      // which strip of the pass, which row group
-    const int rows_per_wg = wps * U;
-    const int r0 = blockIdx.x * rows_per_wg + sub * U;         // first row of this wavefront
+    const int rbase = (blockIdx.x * (blockDim.x >> 6) + wave) * (G * U); // first row of this wavefront: G groups of U rows
     const int64_t row_stride = (int64_t)nbk * 32;
-    float *part = reinterpret_cast<float *>(lds + (size_t)S * NB * SLOT_BYTES);
 
-    float tot[NB][U];
+    // weights of U rows of one strip: wave-uniform row base + per-lane offset, streamed once (nontemporal);
+    // rows past the end repeat the last row and are not stored
+    auto load_step = [&](WRegs<KIND_Q3H>(&w)[U], int r0, int t) {
+        const int n_t = min(64, nbk - t * 64);                // blocks in this strip (ragged at the end of a row)
+        const uint32_t lane_off = (lane < n_t ? lane : 0) * 16;   // lanes past the end redo block 0: loads stay in bounds
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint8_t *p0 = packed + (int64_t)min(r0 + u, rows - 1) * row_stride + (int64_t)t * 2048;
+            const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + lane_off));
+            const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + n_t * 16 + lane_off));
+            w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
+            w[u].d[4] = c.x; w[u].d[5] = c.y; w[u].d[6] = c.z; w[u].d[7] = c.w;
+        }
+    };
+
+    float part[NB][U];                                        // per-lane partial sums of a row group, carried across strips
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int u = 0; u < U; ++u) tot[b][u] = 0.f;
+        for (int u = 0; u < U; ++u) part[b][u] = 0.f;
 
-    for (int t0 = 0; t0 < nstrips; t0 += S) {                  // one pass unless the row is longer than S strips
-        const int t = t0 + slot;
-        const float strip_keep = t < nstrips ? 1.0f : 0.0f;    // wavefronts without a strip redo the last one, result dropped
-        const int tc = t < nstrips ? t : nstrips - 1;
-        const int n_t = min(64, nbk - tc * 64);                // blocks in this strip (ragged at the end of a row)
-        const uint32_t lane_off = (lane < n_t ? lane : 0) * 16;   // lanes past the end redo block 0: loads stay in bounds
+    for (int t0 = 0; t0 < nstrips; t0 += T) {                 // one pass unless the row is longer than T strips (then G is 1)
+        const int nt = min(T, nstrips - t0);                  // strips staged in this pass
 
-        // 1. request this thread's first chunk of activations BEFORE the weights: memory queues are served in
-        //    order, and everything else in the workgroup waits for the staged activations.
-        //    Thread c of the strip's wps*64 threads takes 16-value chunks c, c + wps*64, ...;
-        //    chunk = (batch column c/256, block blk = (c%256)/4, quarter qd = c%4) -> decode slots 4qd..4qd+3.
-        const int tid_s = sub * 64 + lane;
-        const int nchunks = 256 * NB;
+        // 1. request this thread's first chunk of activations BEFORE any weights.
+        //    Chunk c of a pass = (batch column, strip, block blk, quarter qd) with qd fastest: 16 activations
+        //    that feed decode slots 4qd..4qd+3 of lane blk.
+        const int nchunks = NB * nt * 256;
         auto chunk_src = [&](int c) {
-            const int bcol = c >> 8, cc = c & 255;
-            const int ccl = (cc >> 2) < n_t ? cc : 0;          // chunks past the end of the row read chunk 0 and are zeroed
-            return reinterpret_cast<const uint4 *>(X + (int64_t)bcol * cols + (int64_t)tc * 4096 + ccl * 16);
+            const int cc = c & 255, ts = (c >> 8) % nt, bcol = (c >> 8) / nt;
+            const int n_t = min(64, nbk - (t0 + ts) * 64);
+            const int ccl = (cc >> 2) < n_t ? cc : 0;         // chunks past the end of the row read chunk 0 and are zeroed
+            return reinterpret_cast<const uint4 *>(X + (int64_t)bcol * cols + (int64_t)(t0 + ts) * 4096 + ccl * 16);
         };
         auto chunk_put = [&](int c, const uint4 q0, const uint4 q1) {
-            const int bcol = c >> 8, cc = c & 255, blk = cc >> 2, qd = cc & 3;
+            const int cc = c & 255, ts = (c >> 8) % nt, bcol = (c >> 8) / nt, blk = cc >> 2, qd = cc & 3;
+            const int n_t = min(64, nbk - (t0 + ts) * 64);
             const uint32_t live = blk < n_t ? 0xFFFFFFFFu : 0u;   // columns past the end of the row count as zero
             const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
             const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
@@ -366,7 +378,7 @@ __global__ __launch_bounds__(1024) void q3h_gemv_kernel(const uint8_t *__restric
                 se = dot2(as_h2(e[m]), ones, se);
                 so = dot2(as_h2(o[m]), ones, so);
             }
-            uint8_t *sl = lds + (size_t)(slot * NB + bcol) * SLOT_BYTES;
+            uint8_t *sl = lds + (size_t)(ts * NB + bcol) * SLOT_BYTES;
             *reinterpret_cast<uint4 *>(sl + (qd * 64 + blk) * 16) = make_uint4(e[0], e[1], e[2], e[3]);
             *reinterpret_cast<uint4 *>(sl + ((4 + qd) * 64 + blk) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
             float bs = IFLOW_Q3H_BIAS1 * se + IFLOW_Q3H_BIAS2 * so, xs = se + so;
@@ -374,86 +386,80 @@ __global__ __launch_bounds__(1024) void q3h_gemv_kernel(const uint8_t *__restric
             bs += dpp_f32<0x4E, 0xF>(bs); xs += dpp_f32<0x4E, 0xF>(xs);              // sit in one quad of lanes
             if (qd == 0) *reinterpret_cast<float2 *>(sl + 8 * 64 * 16 + blk * 8) = make_float2(bs, xs);
         };
-        const bool has_chunk = tid_s < nchunks;                // whole wavefronts have a first chunk or not
-        const uint4 *src0 = chunk_src(has_chunk ? tid_s : 0);
+        const int c0 = threadIdx.x;
+        const bool has_chunk = c0 < nchunks;                  // whole wavefronts have a first chunk or not
+        const uint4 *src0 = chunk_src(has_chunk ? c0 : 0);
         const uint4 xq0 = src0[0], xq1 = src0[1];
 
-        // 2. request the weights of all U rows: scalar row base + per-lane offset
+        // 2. request the weights of the first step (first row group, first strip of the pass)
         WRegs<KIND_Q3H> w[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = min(r0 + u, rows - 1);               // rows past the end repeat the last one and are not stored
-            const uint8_t *p0 = packed + (int64_t)r * row_stride + (int64_t)tc * 2048;
-            const uint8_t *p1 = p0 + n_t * 16;
-            const uint4 a = *reinterpret_cast<const uint4 *>(p0 + lane_off);
-            const uint4 c = *reinterpret_cast<const uint4 *>(p1 + lane_off);
-            w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
-            w[u].d[4] = c.x; w[u].d[5] = c.y; w[u].d[6] = c.z; w[u].d[7] = c.w;
-        }
+        load_step(w, rbase, t0);
 
-        // stage: permute the activations into decode order in LDS
-        if (t0 > 0) __syncthreads();                           // the previous pass is done with LDS
-        if (has_chunk) chunk_put(tid_s, xq0, xq1);
+        // 3. stage: permute the activations into decode order in LDS
+        if (t0 > 0) __syncthreads();                          // the previous pass is done with LDS
+        if (has_chunk) chunk_put(c0, xq0, xq1);
 #pragma unroll 1
-        for (int c = tid_s + wps * 64; c < nchunks; c += wps * 64) {
+        for (int c = c0 + blockDim.x; c < nchunks; c += blockDim.x) {
             const uint4 *src = chunk_src(c);
             chunk_put(c, src[0], src[1]);
         }
         __syncthreads();
 
-        // 3. this lane's activations, in decode order
+        // 4. steps = (row group, strip): activation registers from LDS, then each row as its loads land, while
+        //    the next step's weights are already requested
         XRegs<KIND_Q3H> xr[NB];
+        const int nsteps = G * nt;
+        int g = 0, ts = 0;
+#pragma unroll 1
+        for (int step = 0; step < nsteps; ++step) {
+            const int r0 = rbase + g * U;
+            if (nt > 1 || step == 0) {                        // a single strip stays in registers for all row groups
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const uint8_t *sl = lds + (size_t)(slot * NB + b) * SLOT_BYTES;
+                for (int b = 0; b < NB; ++b) {
+                    const uint8_t *sl = lds + (size_t)(ts * NB + b) * SLOT_BYTES;
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
-                xr[b].v[4 * jj] = as_h2(q.x); xr[b].v[4 * jj + 1] = as_h2(q.y);
-                xr[b].v[4 * jj + 2] = as_h2(q.z); xr[b].v[4 * jj + 3] = as_h2(q.w);
+                    for (int jj = 0; jj < 8; ++jj) {
+                        const uint4 q = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
+                        xr[b].v[4 * jj] = as_h2(q.x); xr[b].v[4 * jj + 1] = as_h2(q.y);
+                        xr[b].v[4 * jj + 2] = as_h2(q.z); xr[b].v[4 * jj + 3] = as_h2(q.w);
+                    }
+                    const float2 sm = *reinterpret_cast<const float2 *>(sl + 8 * 64 * 16 + lane * 8);
+                    xr[b].bias_sum = sm.x; xr[b].x_sum = sm.y;
+                }
             }
-            const float2 sm = *reinterpret_cast<const float2 *>(sl + 8 * 64 * 16 + lane * 8);
-            xr[b].bias_sum = sm.x; xr[b].x_sum = sm.y;
-        }
-
-        // 4. decode and multiply, row by row as the loads land; lanes past the end see x = 0 and add nothing
+            float v[NB][U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float acc[NB];
-            lane_dot<KIND_Q3H, NB>(w[u], xr, acc);
-            const half2_t so = as_h2(q3h_header(w[u].d));
-            const float s = (float)so.x, o = (float)so.y;
+            for (int u = 0; u < U; ++u) {
+                float acc[NB];
+                lane_dot<KIND_Q3H, NB>(w[u], xr, acc);
+                const half2_t so = as_h2(q3h_header(w[u].d));
+                const float s = (float)so.x, o = (float)so.y;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const float v = __builtin_fmaf(s, acc[b] - xr[b].bias_sum, o * xr[b].x_sum);
-                tot[b][u] = __builtin_fmaf(strip_keep, wave_sum_to_lane63(v), tot[b][u]);   // valid in lane 63
+                for (int b = 0; b < NB; ++b)                  // lanes past the end of a ragged strip see x = 0 and add nothing
+                    v[b][u] = part[b][u] + __builtin_fmaf(s, acc[b] - xr[b].bias_sum, o * xr[b].x_sum);
             }
-        }
-    }
+            // next step's weights (wave-uniform control flow only)
+            int gn = g, tn = ts + 1;
+            if (tn == nt) { tn = 0; gn = g + 1; }
+            if (step + 1 < nsteps) load_step(w, rbase + gn * U, t0 + tn);
 
-    if (S == 1) {
-        if (lane == 63) {
+            const bool group_done = ts == nt - 1 && t0 + nt == nstrips;
+            if (group_done) {                                 // one reduction per row; lane 63 holds the sums
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+                for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (r0 + u < rows) Y[(int64_t)b * rows + r0 + u] = as_u16((half_t)tot[b][u]);
-        }
-    } else {                                                   // add the strips of a row up through LDS
-        if (lane == 63) {
+                    for (int u = 0; u < U; ++u) {
+                        const float sum = wave_sum_to_lane63(v[b][u]);
+                        if (lane == 63 && r0 + u < rows) Y[(int64_t)b * rows + r0 + u] = as_u16((half_t)sum);
+                        part[b][u] = 0.f;
+                    }
+            } else {
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+                for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int u = 0; u < U; ++u) part[(slot * rows_per_wg + sub * U + u) * NB + b] = tot[b][u];
-        }
-        __syncthreads();
-        const int i = threadIdx.x;                             // (row in workgroup, batch column)
-        if (i < rows_per_wg * NB) {
-            const int rr = i / NB, b = i - rr * NB;
-            float sum = 0.f;
-            for (int s2 = 0; s2 < S; ++s2) sum += part[(s2 * rows_per_wg + rr) * NB + b];
-            const int r = blockIdx.x * rows_per_wg + rr;
-            if (r < rows) Y[(int64_t)b * rows + r] = as_u16((half_t)sum);
+                    for (int u = 0; u < U; ++u) part[b][u] = v[b][u];
+            }
+            g = gn; ts = tn;
         }
     }
 }
@@ -479,30 +485,50 @@ static int env_int(const char *name, int dflt)
     return e ? atoi(e) : dflt;
 }
 
-// Q3H launch geometry.  S strips of a row per workgroup (all of them when LDS allows), wps wavefronts per strip,
-// U rows per wavefront: a workgroup covers wps*U rows and has S*wps <= 16 wavefronts.
+// Q3H launch geometry: a workgroup of `waves` wavefronts covers waves*U rows and stages the activations of
+// up to T strips (8.5 KiB of LDS per strip and batch column, at most 152 KiB).  Longer rows get larger
+// workgroups: the staging is paid once per workgroup, and LDS then limits the workgroups per CU.
+template <int NB, int U>
+static hipError_t q3h_launch_u(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y,
+                               int waves, int G, hipStream_t s)
+{
+    constexpr int SLOT = 8 * 64 * 16 + 64 * 8;
+    const int nbk = (int)(cols / 64);
+    const int nstrips = (nbk + 63) / 64;
+    int T = (152 * 1024) / (SLOT * NB);
+    if (T > nstrips) T = nstrips;
+    const size_t lds = (size_t)T * NB * SLOT;
+    static bool attr_done = false;                            // raise the dynamic-LDS cap once per instantiation
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    if (T < nstrips) G = 1;                                   // multi-pass rows: partial sums live in registers, one group only
+    const int64_t rows_per_wg = (int64_t)waves * U * G;
+    const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
+    hipLaunchKernelGGL((q3h_gemv_kernel<NB, U>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                       static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, nstrips, T, G);
+    return hipGetLastError();
+}
+
 template <int NB>
 static hipError_t q3h_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y, hipStream_t s)
 {
-    const int nbk = (int)(cols / 64);
-    const int nstrips = (nbk + 63) / 64;
-    int S = 7 / NB;                                           // LDS: 8.5 KiB per strip and batch column, kept under 64 KiB
-    if (S > nstrips) S = nstrips;
-    static const int dbg_wps = env_int("IFLOW_DEBUG_WPS", 0), dbg_u = env_int("IFLOW_DEBUG_U", 0);
-    int wps = 16 / S;
-    if (wps > 4) wps = 4;
-    int U = 4;
-    if (rows * nstrips <= 8192) U = 2;                        // small matrices: more, shorter wavefronts
-    if (dbg_wps > 0) wps = dbg_wps;
+    const int nstrips = (int)((cols / 64 + 63) / 64);
+    static const int dbg_w = env_int("IFLOW_DEBUG_WAVES", 0), dbg_u = env_int("IFLOW_DEBUG_U", 0), dbg_g = env_int("IFLOW_DEBUG_G", 0);
+    int waves = (nstrips >= 3 || rows <= 8192) ? 8 : 4;
+    int U = 2;
+    if (dbg_w > 0 && dbg_w <= 16) waves = dbg_w;
     if (dbg_u > 0) U = dbg_u;
-    const int64_t grid = (rows + (int64_t)wps * U - 1) / ((int64_t)wps * U);
-    const size_t lds = (size_t)S * NB * (8 * 64 * 16 + 64 * 8) + (size_t)S * wps * U * NB * 4;
-    const dim3 block(64 * S * wps);
-#define IFLOW_Q3H_GO(UU) hipLaunchKernelGGL((q3h_gemv_kernel<NB, UU>), dim3((unsigned)grid), block, lds, s, \
-        static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, nstrips, S, wps)
-    if (U == 1) IFLOW_Q3H_GO(1); else if (U == 2) IFLOW_Q3H_GO(2); else IFLOW_Q3H_GO(4);
-#undef IFLOW_Q3H_GO
-    return hipGetLastError();
+    int G = (int)(rows / U / 2560);                           // tall matrices: several row groups per wavefront, staging paid once
+    if (G < 1) G = 1;
+    if (G > 3) G = 3;
+    if (dbg_g > 0) G = dbg_g;
+    if (U == 1) return q3h_launch_u<NB, 1>(packed, rows, cols, X, Y, waves, G, s);
+    if (U == 2) return q3h_launch_u<NB, 2>(packed, rows, cols, X, Y, waves, G, s);
+    return q3h_launch_u<NB, 4>(packed, rows, cols, X, Y, waves, G, s);
 }
 
 template <int F, int NB>
