@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--format", default="Q3H_B64")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies before the timed region (reference for HBM counters)")
     return ap.parse_args()
 
 
@@ -106,6 +108,14 @@ def main():
     ys = [torch.empty((rows,), dtype=torch.float16, device=dev) for _, rows, _ in shapes]
     torch.cuda.synchronize()
 
+    if args.calibrate_copy:      # a plain copy of known size: 1 GiB read + 1 GiB written per launch (far beyond the caches)
+        src = torch.ones(256 * 2**20, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            iflow.calibration_copy(src, dst, src.numel() * 4)
+        torch.cuda.synchronize()
+        del src, dst
+
     step_bytes = sum(algorithmic_bytes(r, c, bpw) for _, r, c in shapes)
     launches_per_step = len(shapes)
 
@@ -156,13 +166,16 @@ def main():
     bytes_per_launch = step_bytes / launches_per_step
     achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
 
+    # HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, calibrated), if present
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", "qgemv_q3h_7b_traffic.json")
-    if os.path.exists(tfile):
-        try:
-            traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    tfile = os.path.join(ROOT, "profiles", "q3h_gemv_7b_layer_hbm_traffic.txt")
+    if args.format == "Q3H_B64" and os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("hbm_bytes_per_launch"):
+                try:
+                    traffic = int(float(line.split("=")[1].split()[0]))
+                except (ValueError, IndexError):
+                    traffic = None
 
     out = {
         "metric": "achieved HBM GB/s (% of peak) of 3.5-bit fused dequant-GEMV, 7B shapes, batch 1",
@@ -177,7 +190,7 @@ def main():
                    "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": launches_per_step},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "iflow::qgemv_kernel<Q3H_B64, batch 1>", "avg_launch_us": round(us_per_launch, 3),
+                     "kernel": "iflow::q3h_gemv_kernel<1, 2>", "avg_launch_us": round(us_per_launch, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},
     }
     if not args.no_cpu_baseline:

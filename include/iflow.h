@@ -118,6 +118,12 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
 iflow_status_t iflow_unpack_logical(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                                     uint8_t *levels, uint16_t *scale16, uint16_t *offset16, void *stream);
 
+/* Measurement helper (no counterpart in the paper): a plain device copy of `bytes` bytes (a positive multiple of
+ * 16; src and dst device, 16-byte aligned, not overlapping) made of the same 16-byte-per-lane nontemporal loads as
+ * the weight stream.  Profilers scale their bytes-per-dispatch counters by what they report for this transfer of
+ * exactly known size. */
+iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -119,7 +119,19 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     if (batch <= 0 || batch > (1LL << 30)) return IFLOW_ERR_SHAPE;
     if (!packed || !X || !Y) return IFLOW_ERR_NULL;
     if (!aligned16(packed) || !aligned16(X) || !aligned16(Y)) return IFLOW_ERR_ALIGN;
+    // One backend, two kernels: up to a few activation vectors ride along with the weight stream on the vector
+    // units; from 32 rows on the product is a dense contraction and runs on the matrix cores (64-column chunks).
+    if (batch >= 32 && cols % 64 == 0)
+        return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, (hipStream_t)stream));
     return device_status(iflow::launch_qgemv((int)format, packed, rows, cols, X, batch, Y, (hipStream_t)stream));
+}
+
+iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst) return IFLOW_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return IFLOW_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_calibration_copy(src, dst, bytes, (hipStream_t)stream));
 }
 
 iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,

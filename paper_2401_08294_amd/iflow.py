@@ -53,6 +53,7 @@ def lib():
         L.iflow_qgemv.argtypes = [C.c_int, p, i64, i64, p, p, p]
         L.iflow_qgemm.argtypes = [C.c_int, p, i64, i64, p, i64, p, p]
         L.iflow_unpack_logical.argtypes = [C.c_int, p, i64, i64, p, p, p, p]
+        L.iflow_calibration_copy.argtypes = [p, p, sz, p]
         _lib = L
     return _lib
 
@@ -120,3 +121,7 @@ def qgemm(fmt: int, packed, rows: int, cols: int, X, batch: int, Y, stream=None)
 def unpack_logical(fmt: int, packed, rows: int, cols: int, levels, scale16, offset16, stream=None) -> None:
     _check(lib().iflow_unpack_logical(fmt, _ptr(packed), rows, cols, _ptr(levels), _ptr(scale16), _ptr(offset16),
                                       _stream(stream)), "iflow_unpack_logical")
+
+
+def calibration_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(lib().iflow_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "iflow_calibration_copy")

@@ -134,6 +134,36 @@ def test_small_batch(gpu, orc, name, batch):
     check_all(torch, iflow, orc, name, w, x, "batch")
 
 
+# ---- large batches run on the matrix cores (128 x 64 tiles, 64-column chunks): ragged in every dimension ----
+@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("batch,rows,nchunks", [(32, 64, 1), (100, 200, 69), (512, 70, 3)])
+def test_large_batch_mfma(gpu, orc, name, batch, rows, nchunks):
+    torch, iflow = gpu
+    cols = 64 * nchunks
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 71 + batch, outlier_prob=0.001)
+    x = synth.activations(batch, cols, synth.BASE_SEED + 72)
+    e = check_all(torch, iflow, orc, name, w, x, "mfma")
+    assert e <= 6e-4        # exact fp16 weights, fp32 accumulation: only the fp16 rounding of the output is left
+
+
+def test_batch512_full_size_sampled_rows(gpu, orc):
+    """The prefill-like case of the benchmark configs: 4096 x 4096, batch 512, Q3H, checked on sampled weight rows."""
+    torch, iflow = gpu
+    rows, cols, batch = 4096, 4096, 512
+    fmt, ofmt = iflow.Q3H_B64, orc.Q3H_B64
+    say(f"[case] batch512 full-size rows={rows} cols={cols}")
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 81)
+    x = synth.activations(batch, cols, synth.BASE_SEED + 82)
+    packed, _ = gpu_quantize(torch, iflow, fmt, w)
+    y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x)
+    idx = synth.sample_rows(rows, 96, synth.BASE_SEED + 83)
+    q, s, o = orc.quantize(ofmt, w[idx])
+    yref = orc.gemm(orc.dequant(ofmt, q, s, o), x.view(np.uint16), threads=8)
+    e = rel_err(y[:, idx], yref)
+    say(f"        max rel err on {len(idx)} sampled rows x {batch} {e:.3e}")
+    assert np.isfinite(y).all() and e <= 6e-4
+
+
 # ---- degenerate values ---------------------------------------------------------------------------------
 @pytest.mark.parametrize("name", NAMES)
 def test_degenerate_blocks(gpu, orc, name):
