@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=160)
     ap.add_argument("--ring", type=int, default=16, help="distinct layers in the weight ring (16 = 1.5 GiB packed)")
     ap.add_argument("--format", default="Q3H_B64")
+    ap.add_argument("--launches", type=int, default=4, choices=(4, 7),
+                    help="launches per layer: 7 = one per matrix; 4 = q,k,v in one iflow_qgemv_multi launch, o, gate+up in one, down")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -117,14 +119,24 @@ def main():
         del src, dst
 
     step_bytes = sum(algorithmic_bytes(r, c, bpw) for _, r, c in shapes)
-    launches_per_step = len(shapes)
+    launches_per_step = args.launches
 
     stream = torch.cuda.Stream()
     raw = stream.cuda_stream
 
+    # projections that read the same activation vector and may share a launch: (q, k, v) and (gate, up)
+    groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches == 4 else [[i] for i in range(len(shapes))]
+
     def one_step(layer):
-        for (rows, cols, packed), y in zip(ring[layer], ys):
-            iflow.qgemv(fmt, packed, rows, cols, xs[cols], y, stream=raw)
+        mats = ring[layer]
+        for g in groups:
+            cols = mats[g[0]][1]
+            if len(g) == 1:
+                rows, _, packed = mats[g[0]]
+                iflow.qgemv(fmt, packed, rows, cols, xs[cols], ys[g[0]], stream=raw)
+            else:
+                iflow.qgemv_multi(fmt, [mats[i][2] for i in g], [mats[i][0] for i in g], cols, xs[cols],
+                                  [ys[i] for i in g], stream=raw)
 
     graph = None
     with torch.cuda.stream(stream):
@@ -186,7 +198,8 @@ def main():
         "config": {"workload": "llama2-7b decoder-layer linears (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
                                f"{args.format}, batch 1, ring of {args.ring} distinct layers "
                                f"({args.ring * step_bytes / 2**30:.2f} GiB packed), "
-                               + ("HIP-graph replay" if graph is not None else "eager launches"),
+                               + ("HIP-graph replay" if graph is not None else "eager launches")
+                               + (", 4 launches per layer (q+k+v, o, gate+up, down)" if args.launches == 4 else ", 7 launches per layer"),
                    "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": launches_per_step},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,

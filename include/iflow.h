@@ -104,6 +104,14 @@ iflow_status_t iflow_dequant(iflow_format_t format, const void *packed, int64_t 
 iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                            const uint16_t *x, uint16_t *y, void *stream);
 
+/* Several projections of ONE activation vector in one launch: y_i = W'_i x for i < count (1..8), e.g. the q, k, v
+ * or the gate, up matrices of a decoder layer, which the decode step applies to the same input.  All matrices have
+ * `cols` columns; matrix i has rows[i] rows, its own packed buffer packed[i] and its own output y[i] ([rows[i]] fp16).
+ * `packed`, `rows` and `y` are HOST arrays of `count` entries (of device pointers / sizes); they are read during the
+ * call and need not outlive it.  Results are those of `count` iflow_qgemv calls. */
+iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
+                                 int64_t cols, const uint16_t *x, uint16_t *const *y, void *stream);
+
 /* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
  * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].
  *   X [batch][cols] fp16, Y [batch][rows] fp16, both device.

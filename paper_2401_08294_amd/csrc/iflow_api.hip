@@ -126,6 +126,23 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     return device_status(iflow::launch_qgemv((int)format, packed, rows, cols, X, batch, Y, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
+                                 int64_t cols, const uint16_t *x, uint16_t *const *y, void *stream)
+{
+    iflow::FormatInfo fi;
+    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
+    if (count < 1 || count > 8) return IFLOW_ERR_SHAPE;
+    if (!packed || !rows || !x || !y) return IFLOW_ERR_NULL;
+    if (!aligned16(x)) return IFLOW_ERR_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        iflow_status_t st = check_shape(format, rows[i], cols, &fi);
+        if (st != IFLOW_OK) return st;
+        if (!packed[i] || !y[i]) return IFLOW_ERR_NULL;
+        if (!aligned16(packed[i]) || !aligned16(y[i])) return IFLOW_ERR_ALIGN;
+    }
+    return device_status(iflow::launch_qgemv_multi((int)format, count, packed, rows, cols, x, y, (hipStream_t)stream));
+}
+
 iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, void *stream)
 {
     if (!src || !dst) return IFLOW_ERR_NULL;

@@ -300,6 +300,16 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
     }
 }
 
+// Up to eight matrices per launch (see q3h_gemv_kernel).
+constexpr int IFLOW_MAX_GROUP = 8;
+struct GemvGroup {
+    const uint8_t *packed[IFLOW_MAX_GROUP];
+    uint16_t *y[IFLOW_MAX_GROUP];
+    int rows[IFLOW_MAX_GROUP];
+    int wg_end[IFLOW_MAX_GROUP];                              // one past the last workgroup of matrix i
+    int count;
+};
+
 // ---- Q3H: workgroup-shared activations ----------------------------------------------------------------
 // The activations are the same for every wavefront, and arranging a strip of them for the decode costs
 // about as much as one row of weights.  So a workgroup does it once: its threads permute the activations
@@ -316,17 +326,30 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
 //
 // LDS layout per (strip, batch column): float4 xs[8][64] (register quad jj of lane l at [jj][l]), then
 // float2 sums[64] = (bias_sum, x_sum) of lane l.
-template <int NB, int U>
-__global__ __launch_bounds__(1024) void q3h_gemv_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
-                                                        uint16_t *__restrict__ Y, int rows, int cols, int nbk, int nstrips,
-                                                        int T, int G)
+//
+// One launch can serve several weight matrices that share the activation vector and the number of columns
+// (the q/k/v or the gate/up projections of a decoder layer): workgroup ranges are assigned to the matrices
+// in order, each matrix keeps its own packed buffer and output vector.
+template <int NB, int U, bool MULTI>
+__global__ __launch_bounds__(1024) void q3h_gemv_kernel(const GemvGroup grp, const uint16_t *__restrict__ X,
+                                                        int cols, int nbk, int nstrips, int T, int G)
 {
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int SLOT_BYTES = 8 * 64 * 16 + 64 * 8;          // xs + sums of one (strip, batch column)
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction: keep it scalar
-    const int rbase = (blockIdx.x * (blockDim.x >> 6) + wave) * (G * U); // first row of this wavefront: G groups of U rows
+    int m = 0;                                                // which matrix this workgroup belongs to
+    if (MULTI) {
+#pragma unroll
+        for (int i = 0; i + 1 < IFLOW_MAX_GROUP; ++i)
+            if (i + 1 < grp.count && (int)blockIdx.x >= grp.wg_end[i]) m = i + 1;
+    }
+    const int wg = blockIdx.x - (m ? grp.wg_end[m - 1] : 0);
+    const uint8_t *__restrict__ packed = grp.packed[m];
+    uint16_t *__restrict__ Y = grp.y[m];
+    const int rows = grp.rows[m];
+    const int rbase = (wg * (blockDim.x >> 6) + wave) * (G * U);         // first row of this wavefront: G groups of U rows
     const int64_t row_stride = (int64_t)nbk * 32;
 
     // weights of U rows of one strip: wave-uniform row base + per-lane offset, streamed once (nontemporal);
@@ -485,12 +508,8 @@ static int env_int(const char *name, int dflt)
     return e ? atoi(e) : dflt;
 }
 
-// Q3H launch geometry: a workgroup of `waves` wavefronts covers waves*U rows and stages the activations of
-// up to T strips (8.5 KiB of LDS per strip and batch column, at most 152 KiB).  Longer rows get larger
-// workgroups: the staging is paid once per workgroup, and LDS then limits the workgroups per CU.
 template <int NB, int U>
-static hipError_t q3h_launch_u(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y,
-                               int waves, int G, hipStream_t s)
+static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, int waves, int G, hipStream_t s)
 {
     constexpr int SLOT = 8 * 64 * 16 + 64 * 8;
     const int nbk = (int)(cols / 64);
@@ -500,42 +519,64 @@ static hipError_t q3h_launch_u(const void *packed, int64_t rows, int64_t cols, c
     const size_t lds = (size_t)T * NB * SLOT;
     static bool attr_done = false;                            // raise the dynamic-LDS cap once per instantiation
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     if (T < nstrips) G = 1;                                   // multi-pass rows: partial sums live in registers, one group only
     const int64_t rows_per_wg = (int64_t)waves * U * G;
-    const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
-    hipLaunchKernelGGL((q3h_gemv_kernel<NB, U>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                       static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, nstrips, T, G);
+    int64_t grid = 0;
+    for (int i = 0; i < grp.count; ++i) {
+        grid += (grp.rows[i] + rows_per_wg - 1) / rows_per_wg;
+        grp.wg_end[i] = (int)grid;
+    }
+    if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    if (grp.count == 1)
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp, X, (int)cols, nbk, nstrips, T, G);
+    else
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, true>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp, X, (int)cols, nbk, nstrips, T, G);
     return hipGetLastError();
 }
 
+// Q3H launch geometry: a workgroup of `waves` wavefronts covers waves*U*G rows and stages the activations of
+// up to T strips (8.5 KiB of LDS per strip and batch column, at most 152 KiB).  Long rows and small problems
+// get larger workgroups (the staging is paid once per workgroup); tall problems let a wavefront walk several
+// row groups.
 template <int NB>
-static hipError_t q3h_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y, hipStream_t s)
+static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t *X, hipStream_t s)
 {
     const int nstrips = (int)((cols / 64 + 63) / 64);
+    int64_t rows = 0;
+    for (int i = 0; i < grp.count; ++i) rows += grp.rows[i];
     static const int dbg_w = env_int("IFLOW_DEBUG_WAVES", 0), dbg_u = env_int("IFLOW_DEBUG_U", 0), dbg_g = env_int("IFLOW_DEBUG_G", 0);
     int waves = (nstrips >= 3 || rows <= 8192) ? 8 : 4;
     int U = 2;
     if (dbg_w > 0 && dbg_w <= 16) waves = dbg_w;
     if (dbg_u > 0) U = dbg_u;
-    int G = (int)(rows / U / 2560);                           // tall matrices: several row groups per wavefront, staging paid once
+    int G = (int)(rows / U / 2560);                           // tall problems: several row groups per wavefront, staging paid once
     if (G < 1) G = 1;
     if (G > 3) G = 3;
     if (dbg_g > 0) G = dbg_g;
-    if (U == 1) return q3h_launch_u<NB, 1>(packed, rows, cols, X, Y, waves, G, s);
-    if (U == 2) return q3h_launch_u<NB, 2>(packed, rows, cols, X, Y, waves, G, s);
-    return q3h_launch_u<NB, 4>(packed, rows, cols, X, Y, waves, G, s);
+    if (U == 1) return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
+    if (U == 2) return q3h_launch_u<NB, 2>(grp, cols, X, waves, G, s);
+    return q3h_launch_u<NB, 4>(grp, cols, X, waves, G, s);
 }
 
 template <int F, int NB>
 static hipError_t gemv_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, uint16_t *Y, hipStream_t s)
 {
     typedef Fmt<F> T;
-    if (T::kind == KIND_Q3H) return q3h_launch<NB>(packed, rows, cols, X, Y, s);
+    if (T::kind == KIND_Q3H) {
+        GemvGroup grp = {};
+        grp.packed[0] = static_cast<const uint8_t *>(packed); grp.y[0] = Y; grp.rows[0] = (int)rows; grp.count = 1;
+        return q3h_launch<NB>(grp, cols, X, s);
+    }
     typedef Geo<T::kind> G;
     const int nbk = (int)(cols / T::block);
     const int nstrips = (int)((cols + 64 * G::WPL - 1) / (64 * G::WPL));
@@ -568,6 +609,24 @@ static hipError_t gemv_batch(const void *packed, int64_t rows, int64_t cols, con
         case 3: e = gemv_launch<F, 3>(packed, rows, cols, Xb, Yb, s); break;
         default: e = gemv_launch<F, 4>(packed, rows, cols, Xb, Yb, s); break;
         }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_qgemv_multi(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols,
+                              const uint16_t *x, uint16_t *const *y, hipStream_t s)
+{
+    if (format == IFLOW_Q3H_B64) {                            // one launch for all matrices
+        GemvGroup grp = {};
+        for (int i = 0; i < count; ++i) {
+            grp.packed[i] = static_cast<const uint8_t *>(packed[i]); grp.y[i] = y[i]; grp.rows[i] = (int)rows[i];
+        }
+        grp.count = count;
+        return q3h_launch<1>(grp, cols, x, s);
+    }
+    for (int i = 0; i < count; ++i) {                         // the other formats: one launch per matrix
+        hipError_t e = launch_qgemv(format, packed[i], rows[i], cols, x, 1, y[i], s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -54,6 +54,7 @@ def lib():
         L.iflow_qgemm.argtypes = [C.c_int, p, i64, i64, p, i64, p, p]
         L.iflow_unpack_logical.argtypes = [C.c_int, p, i64, i64, p, p, p, p]
         L.iflow_calibration_copy.argtypes = [p, p, sz, p]
+        L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
         _lib = L
     return _lib
 
@@ -125,3 +126,12 @@ def unpack_logical(fmt: int, packed, rows: int, cols: int, levels, scale16, offs
 
 def calibration_copy(src, dst, nbytes: int, stream=None) -> None:
     _check(lib().iflow_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "iflow_calibration_copy")
+
+
+def qgemv_multi(fmt: int, packed_list, rows_list, cols: int, x, y_list, stream=None) -> None:
+    """y_list[i] = W'_i x for matrices that share x and cols; one launch for Q3H."""
+    n = len(packed_list)
+    pk = (C.c_void_p * n)(*[_ptr(t) for t in packed_list])
+    ys = (C.c_void_p * n)(*[_ptr(t) for t in y_list])
+    rs = (C.c_int64 * n)(*[int(r) for r in rows_list])
+    _check(lib().iflow_qgemv_multi(fmt, n, pk, rs, cols, _ptr(x), ys, _stream(stream)), "iflow_qgemv_multi")

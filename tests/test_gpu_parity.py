@@ -164,6 +164,39 @@ def test_batch512_full_size_sampled_rows(gpu, orc):
     assert np.isfinite(y).all() and e <= 6e-4
 
 
+# ---- several projections of one activation vector in one launch -----------------------------------------
+@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B64"])
+def test_qgemv_multi_matches_single_launches(gpu, orc, name):
+    torch, iflow = gpu
+    fmt, ofmt = iflow.FORMATS[name], orc.FORMATS[name]
+    cols = 4096 + 64 * 5
+    row_counts = [100, 37, 256, 1]
+    say(f"[case] multi fmt={name} rows={row_counts} cols={cols}")
+    x = synth.activations(1, cols, synth.BASE_SEED + 91)
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    packs, ys, refs = [], [], []
+    for i, rows in enumerate(row_counts):
+        w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 92 + i)
+        packed, _ = gpu_quantize(torch, iflow, fmt, w)
+        packs.append(packed)
+        ys.append(torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda"))
+        q, s, o = orc.quantize(ofmt, w)
+        refs.append(orc.gemm(orc.dequant(ofmt, q, s, o), x.view(np.uint16))[0])
+    iflow.qgemv_multi(fmt, packs, row_counts, cols, xd, ys)
+    torch.cuda.synchronize()
+    for packed, rows, y, ref in zip(packs, row_counts, ys, refs):
+        single = torch.empty((rows,), dtype=torch.float16, device="cuda")
+        iflow.qgemv(fmt, packed, rows, cols, xd, single)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert not np.isnan(got).any()
+        assert rel_err(got.astype(np.float64)[None, :], ref[None, :]) <= TOL
+        assert np.array_equal(got.view(np.uint16), single.cpu().numpy().view(np.uint16))   # same arithmetic per row
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.qgemv_multi(fmt, packs * 3, row_counts * 3, cols, xd, ys * 3)          # more than eight matrices
+    assert ei.value.status == iflow.ERR_SHAPE
+
+
 # ---- degenerate values ---------------------------------------------------------------------------------
 @pytest.mark.parametrize("name", NAMES)
 def test_degenerate_blocks(gpu, orc, name):
