@@ -331,7 +331,7 @@ struct GemvGroup {
 // (the q/k/v or the gate/up projections of a decoder layer): workgroup ranges are assigned to the matrices
 // in order, each matrix keeps its own packed buffer and output vector.
 template <int NB, int U, bool MULTI>
-__global__ __launch_bounds__(1024) void q3h_gemv_kernel(const GemvGroup grp, const uint16_t *__restrict__ X,
+__global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const GemvGroup grp, const uint16_t *__restrict__ X,
                                                         int cols, int nbk, int nstrips, int T, int G)
 {
     extern __shared__ __align__(16) uint8_t lds[];
@@ -556,9 +556,10 @@ static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t 
     for (int i = 0; i < grp.count; ++i) rows += grp.rows[i];
     static const int dbg_w = env_int("IFLOW_DEBUG_WAVES", 0), dbg_u = env_int("IFLOW_DEBUG_U", 0), dbg_g = env_int("IFLOW_DEBUG_G", 0);
     int waves = (nstrips >= 3 || rows <= 8192) ? 8 : 4;
-    int U = 2;
+    int U = NB <= 2 ? 2 : 1;                                  // 32 activation registers per batch column: fewer rows in flight
     if (dbg_w > 0 && dbg_w <= 16) waves = dbg_w;
     if (dbg_u > 0) U = dbg_u;
+    if (NB > 2 && waves > 8) waves = 8;                       // those instantiations are built for at most 512 threads
     int G = (int)(rows / U / 2560);                           // tall problems: several row groups per wavefront, staging paid once
     if (G < 1) G = 1;
     if (G > 3) G = 3;

@@ -266,6 +266,81 @@ def test_full_size_sampled_rows(gpu, orc, rows, cols, sigma):
     assert np.array_equal(y2, 2 * y)
 
 
+# ---- 70B-shaped layers (config 4): sampled rows, batch 1 and 8 ----------------------------------------------
+@pytest.mark.parametrize("rows,cols", [(28672, 8192), (8192, 28672)])
+def test_70b_shapes_sampled_rows(gpu, orc, rows, cols):
+    torch, iflow = gpu
+    fmt, ofmt = iflow.Q3H_B64, orc.Q3H_B64
+    say(f"[case] 70B-shape rows={rows} cols={cols}")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + rows)
+    wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.015
+    n = iflow.packed_bytes(fmt, rows, cols)
+    packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+    iflow.quantize(fmt, wd, rows, cols, packed, n)
+    idx = synth.sample_rows(rows, 64, synth.BASE_SEED + 57)
+    w_rows = wd[torch.from_numpy(idx).cuda()].cpu().numpy()          # the oracle sees the same fp32 bits as the GPU quantizer
+    del wd
+    q, s, o = orc.quantize(ofmt, w_rows)
+    row_bytes = orc.packed_bytes(ofmt, 1, cols)
+    got = packed.cpu().numpy().reshape(rows, row_bytes)[idx]
+    assert np.array_equal(got, orc.pack_device(ofmt, q, s, o).reshape(len(idx), row_bytes))
+    ref_deq = orc.dequant(ofmt, q, s, o)
+    for batch in (1, 8):
+        x = synth.activations(batch, cols, synth.BASE_SEED + 58 + batch)
+        y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x)
+        yref = orc.gemm(ref_deq, x.view(np.uint16), threads=8)
+        e = rel_err(y[:, idx], yref)
+        say(f"        batch {batch}: max rel err on {len(idx)} sampled rows {e:.3e}")
+        assert np.isfinite(y).all() and e <= TOL
+
+
+# ---- a captured decode-step weight stream (config 5, two layers deep) replays to the eager result -------------
+def test_hip_graph_replay_matches_eager(gpu, orc):
+    torch, iflow = gpu
+    fmt = iflow.Q3H_B64
+    shapes = [(512, 1024), (512, 1024), (1408, 1024), (1024, 1408)]      # q/k, gate-like, down-like slices
+    say("[case] graph replay of two layers x four linears")
+    layers = []
+    for layer in range(2):
+        mats = []
+        for i, (rows, cols) in enumerate(shapes):
+            w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 200 + 10 * layer + i)
+            packed, _ = gpu_quantize(torch, iflow, fmt, w)
+            mats.append((rows, cols, packed))
+        layers.append(mats)
+    xs = {c: torch.from_numpy(synth.activations(1, c, synth.BASE_SEED + 300 + c).view(np.int16)).cuda() for c in (1024, 1408)}
+    ys = [[torch.zeros((rows,), dtype=torch.float16, device="cuda") for rows, _, _ in mats] for mats in layers]
+
+    stream = torch.cuda.Stream()
+
+    def run_all():
+        for mats, outs in zip(layers, ys):
+            iflow.qgemv_multi(fmt, [mats[0][2], mats[1][2]], [mats[0][0], mats[1][0]], 1024, xs[1024], outs[:2], stream=stream.cuda_stream)
+            for (rows, cols, packed), y in list(zip(mats, outs))[2:]:
+                iflow.qgemv(fmt, packed, rows, cols, xs[cols], y, stream=stream.cuda_stream)
+
+    with torch.cuda.stream(stream):
+        run_all()
+        stream.synchronize()
+        eager = [[y.clone() for y in outs] for outs in ys]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run_all()
+        for rep in range(3):                                   # replays with eager work and synchronisation in between
+            for outs in ys:
+                for y in outs:
+                    y.zero_()
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            for outs, ref in zip(ys, eager):
+                for y, r in zip(outs, ref):
+                    assert torch.equal(y, r), f"replay {rep} differs from the eager result"
+            run_all()
+            stream.synchronize()
+
+
 # ---- unit vectors tie the product to the dequantizer; argument errors come back as codes ----------------
 def test_unit_vector_returns_column(gpu, orc):
     torch, iflow = gpu
