@@ -5,6 +5,9 @@
 
 namespace {
 
+// smallest batch that goes to the 16-wide MFMA kernel (below it, the vector kernel with that many columns is faster)
+constexpr int64_t IFLOW_SMALL_MFMA_MIN_BATCH = 3;
+
 thread_local int g_last_hip_error = 0;
 
 iflow_status_t device_status(hipError_t e)
@@ -119,11 +122,21 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     if (batch <= 0 || batch > (1LL << 30)) return IFLOW_ERR_SHAPE;
     if (!packed || !X || !Y) return IFLOW_ERR_NULL;
     if (!aligned16(packed) || !aligned16(X) || !aligned16(Y)) return IFLOW_ERR_ALIGN;
-    // One backend, two kernels: up to a few activation vectors ride along with the weight stream on the vector
-    // units; from 32 rows on the product is a dense contraction and runs on the matrix cores (64-column chunks).
+    // One backend, three kernels chosen by batch: a few activation vectors ride along with the weight stream on the
+    // vector units; 3.5-bit weights with up to 31 vectors stream once per 16 vectors through 16x16x16 MFMAs; from 32
+    // vectors on the product is a dense contraction on LDS tiles (64-column chunks).
+    hipStream_t hs = (hipStream_t)stream;
     if (batch >= 32 && cols % 64 == 0)
-        return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, (hipStream_t)stream));
-    return device_status(iflow::launch_qgemv((int)format, packed, rows, cols, X, batch, Y, (hipStream_t)stream));
+        return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, hs));
+    if (format == IFLOW_Q3H_B64 && batch >= IFLOW_SMALL_MFMA_MIN_BATCH) {
+        for (int64_t b0 = 0; b0 < batch; b0 += 16) {
+            const int64_t nb = batch - b0 < 16 ? batch - b0 : 16;
+            hipError_t e = iflow::launch_qgemm_small((int)format, packed, rows, cols, X + b0 * cols, nb, Y + b0 * rows, hs);
+            if (e != hipSuccess) return device_status(e);
+        }
+        return IFLOW_OK;
+    }
+    return device_status(iflow::launch_qgemv((int)format, packed, rows, cols, X, batch, Y, hs));
 }
 
 iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
