@@ -331,9 +331,12 @@ struct GemvGroup {
 // (the q/k/v or the gate/up projections of a decoder layer): workgroup ranges are assigned to the matrices
 // in order, each matrix keeps its own packed buffer and output vector.
 template <int NB, int U, bool MULTI>
-__global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const GemvGroup grp, const uint16_t *__restrict__ X,
-                                                        int cols, int nbk, int nstrips, int T, int G)
+__global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const uint8_t *__restrict__ packed0, uint16_t *__restrict__ y0,
+                                                        const uint16_t *__restrict__ X, int rows0, int cols, int nbk, int nstrips,
+                                                        int T, int G, int waves, const GemvGroup grp)
 {
+    // The single-matrix arguments come first so that they fit the kernel-argument registers the hardware can preload
+    // at wavefront start (no scalar load, no wait, before the first address is formed); `grp` is read only when MULTI.
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int SLOT_BYTES = 8 * 64 * 16 + 64 * 8;          // xs + sums of one (strip, batch column)
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -345,11 +348,11 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const Ge
         for (int i = 0; i + 1 < IFLOW_MAX_GROUP; ++i)
             if (i + 1 < grp.count && (int)blockIdx.x >= grp.wg_end[i]) m = i + 1;
     }
-    const int wg = blockIdx.x - (m ? grp.wg_end[m - 1] : 0);
-    const uint8_t *__restrict__ packed = grp.packed[m];
-    uint16_t *__restrict__ Y = grp.y[m];
-    const int rows = grp.rows[m];
-    const int rbase = (wg * (blockDim.x >> 6) + wave) * (G * U);         // first row of this wavefront: G groups of U rows
+    const int wg = MULTI ? blockIdx.x - (m ? grp.wg_end[m - 1] : 0) : blockIdx.x;
+    const uint8_t *__restrict__ packed = MULTI ? grp.packed[m] : packed0;
+    uint16_t *__restrict__ Y = MULTI ? grp.y[m] : y0;
+    const int rows = MULTI ? grp.rows[m] : rows0;
+    const int rbase = (wg * waves + wave) * (G * U);          // first row of this wavefront: G groups of U rows
     const int64_t row_stride = (int64_t)nbk * 32;
 
     // weights of U rows of one strip: wave-uniform row base + per-lane offset, streamed once (nontemporal);
@@ -422,7 +425,7 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const Ge
         if (t0 > 0) __syncthreads();                          // the previous pass is done with LDS
         if (has_chunk) chunk_put(c0, xq0, xq1);
 #pragma unroll 1
-        for (int c = c0 + blockDim.x; c < nchunks; c += blockDim.x) {
+        for (int c = c0 + waves * 64; c < nchunks; c += waves * 64) {
             const uint4 *src = chunk_src(c);
             chunk_put(c, src[0], src[1]);
         }
@@ -537,10 +540,10 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
     if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     if (grp.count == 1)
         hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                           grp, X, (int)cols, nbk, nstrips, T, G);
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, grp);
     else
         hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, true>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                           grp, X, (int)cols, nbk, nstrips, T, G);
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, grp);
     return hipGetLastError();
 }
 
