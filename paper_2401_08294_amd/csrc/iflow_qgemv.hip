@@ -36,6 +36,15 @@ template <int KIND> struct XRegs {
 
 __device__ __forceinline__ float dot2(half2_t a, half2_t b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
 
+// All ones when a < b, else zero, as a value the optimizer cannot see through: used as an AND mask where a select
+// would compile to v_cndmask_b32, which is several times slower than an AND on this part.
+__device__ __forceinline__ uint32_t mask_lt(int a, int b)
+{
+    uint32_t m = (uint32_t)((a - b) >> 31);
+    asm volatile("" : "+v"(m));
+    return m;
+}
+
 template <int KIND>
 __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restrict__ x, int k0)
 {
@@ -359,7 +368,8 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
     // rows past the end repeat the last row and are not stored
     auto load_step = [&](WRegs<KIND_Q3H>(&w)[U], int r0, int t) {
         const int n_t = min(64, nbk - t * 64);                // blocks in this strip (ragged at the end of a row)
-        const uint32_t lane_off = (lane < n_t ? lane : 0) * 16;   // lanes past the end redo block 0: loads stay in bounds
+        // lanes past the end redo block 0 so that loads stay in bounds
+        const uint32_t lane_off = (uint32_t)(lane * 16) & mask_lt(lane, n_t);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint8_t *p0 = packed + (int64_t)min(r0 + u, rows - 1) * row_stride + (int64_t)t * 2048;
@@ -380,19 +390,20 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         const int nt = min(T, nstrips - t0);                  // strips staged in this pass
 
         // 1. request this thread's first chunk of activations BEFORE any weights.
-        //    Chunk c of a pass = (batch column, strip, block blk, quarter qd) with qd fastest: 16 activations
-        //    that feed decode slots 4qd..4qd+3 of lane blk.
+        //    Chunk c of a pass = (strip, batch column, block blk, quarter qd) with qd fastest: 16 activations
+        //    that feed decode slots 4qd..4qd+3 of lane blk.  (NB is a compile-time constant: no integer division on
+        //    the way to the first load.)
         const int nchunks = NB * nt * 256;
         auto chunk_src = [&](int c) {
-            const int cc = c & 255, ts = (c >> 8) % nt, bcol = (c >> 8) / nt;
+            const int cc = c & 255, ts = (c >> 8) / NB, bcol = (c >> 8) % NB;
             const int n_t = min(64, nbk - (t0 + ts) * 64);
-            const int ccl = (cc >> 2) < n_t ? cc : 0;         // chunks past the end of the row read chunk 0 and are zeroed
+            const int ccl = cc & (int)mask_lt(cc >> 2, n_t);  // chunks past the end of the row read chunk 0 and are zeroed
             return reinterpret_cast<const uint4 *>(X + (int64_t)bcol * cols + (int64_t)(t0 + ts) * 4096 + ccl * 16);
         };
         auto chunk_put = [&](int c, const uint4 q0, const uint4 q1) {
-            const int cc = c & 255, ts = (c >> 8) % nt, bcol = (c >> 8) / nt, blk = cc >> 2, qd = cc & 3;
+            const int cc = c & 255, ts = (c >> 8) / NB, bcol = (c >> 8) % NB, blk = cc >> 2, qd = cc & 3;
             const int n_t = min(64, nbk - (t0 + ts) * 64);
-            const uint32_t live = blk < n_t ? 0xFFFFFFFFu : 0u;   // columns past the end of the row count as zero
+            const uint32_t live = mask_lt(blk, n_t);              // all ones inside the row: columns past its end count as zero
             const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
             const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
             uint32_t e[4], o[4];
@@ -414,7 +425,7 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         };
         const int c0 = threadIdx.x;
         const bool has_chunk = c0 < nchunks;                  // whole wavefronts have a first chunk or not
-        const uint4 *src0 = chunk_src(has_chunk ? c0 : 0);
+        const uint4 *src0 = chunk_src(c0 & (int)mask_lt(c0, nchunks));
         const uint4 xq0 = src0[0], xq1 = src0[1];
 
         // 2. request the weights of the first step (first row group, first strip of the pass)
