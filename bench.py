@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=160)
     ap.add_argument("--ring", type=int, default=16, help="distinct layers in the weight ring (16 = 1.5 GiB packed)")
     ap.add_argument("--format", default="Q3H_B64")
-    ap.add_argument("--launches", type=int, default=4, choices=(4, 7),
+    ap.add_argument("--launches", type=int, default=4, choices=(1, 4, 7),
                     help="launches per layer: 7 = one per matrix; 4 = q,k,v in one iflow_qgemv_multi launch, o, gate+up in one, down")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -125,10 +125,19 @@ def main():
     raw = stream.cuda_stream
 
     # projections that read the same activation vector and may share a launch: (q, k, v) and (gate, up)
-    groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches == 4 else [[i] for i in range(len(shapes))]
+    groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches in (1, 4) else [[i] for i in range(len(shapes))]
+    if args.launches == 1:       # one chained launch per layer: o reads q's output, gate/up read o's, down reads gate's
+        assert args.format == "Q3H_B64", "the chained launch exists for the 3.5-bit format"
+        chain_ws_bytes = iflow.qgemv_chain_workspace_bytes([r for _, r, _ in shapes])
+        chain_ws = torch.zeros(chain_ws_bytes, dtype=torch.uint8, device=dev)
+        chain_x = [xs[shapes[0][2]], ys[0], ys[3], ys[4]]
 
     def one_step(layer):
         mats = ring[layer]
+        if args.launches == 1:
+            phases = [(mats[g[0]][1], chain_x[i], [(mats[j][2], mats[j][0], ys[j]) for j in g]) for i, g in enumerate(groups)]
+            iflow.qgemv_chain(fmt, phases, chain_ws, chain_ws_bytes, stream=raw)
+            return
         for g in groups:
             cols = mats[g[0]][1]
             if len(g) == 1:
@@ -199,13 +208,17 @@ def main():
                                f"{args.format}, batch 1, ring of {args.ring} distinct layers "
                                f"({args.ring * step_bytes / 2**30:.2f} GiB packed), "
                                + ("HIP-graph replay" if graph is not None else "eager launches")
-                               + (", 4 launches per layer (q+k+v, o, gate+up, down)" if args.launches == 4 else ", 7 launches per layer"),
+                               + {1: ", 1 chained launch per layer (q+k+v -> o -> gate+up -> down, each phase reading the previous one's output)",
+                                  4: ", 4 launches per layer (q+k+v, o, gate+up, down)", 7: ", 7 launches per layer"}[args.launches],
                    "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": launches_per_step},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": "iflow::q3h_gemv_kernel<1, 2>", "avg_launch_us": round(us_per_launch, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},
     }
+    if args.launches == 1:
+        iflow.qgemv_chain_check(chain_ws, stream=raw)          # raises if a phase ever gave up waiting for its input
+        out["roofline"]["kernel"] = "iflow::q3h_chain_kernel"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.format)
     print(json.dumps(out))

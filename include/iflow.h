@@ -63,7 +63,8 @@ typedef enum {
     IFLOW_ERR_SHAPE = 3,    /* rows, cols or batch <= 0, cols not a multiple of the block size, or a size above 2^30 */
     IFLOW_ERR_SIZE = 4,     /* an output buffer is smaller than required */
     IFLOW_ERR_ALIGN = 5,    /* a device pointer is not 16-byte aligned */
-    IFLOW_ERR_DEVICE = 6    /* a HIP call failed; see iflow_last_hip_error() */
+    IFLOW_ERR_DEVICE = 6,   /* a HIP call failed; see iflow_last_hip_error() */
+    IFLOW_ERR_TIMEOUT = 7   /* iflow_qgemv_chain_check: a phase of a chained launch gave up waiting for its input */
 } iflow_status_t;
 
 /* Version of the packed layout described above (1). */
@@ -111,6 +112,38 @@ iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t ro
  * call and need not outlive it.  Results are those of `count` iflow_qgemv calls. */
 iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
                                  int64_t cols, const uint16_t *x, uint16_t *const *y, void *stream);
+
+/* A chain of batch-1 products in ONE launch (3.5-bit format only): the decode step applies its projections one
+ * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and
+ * at 7B sizes each product is so short that the idle time between dependent launches costs as much as a third of
+ * the weight stream.  The chain is a list of `nphases` (1..IFLOW_CHAIN_MAX_PHASES) phases.  Phase p multiplies
+ * counts[p] (1..IFLOW_CHAIN_MAX_GROUP) matrices, all with cols[p] columns (<= 65536), with the activation vector x[p]; the matrices of all
+ * phases are listed in order in packed / rows / y (at most IFLOW_CHAIN_MAX_MATRICES in total).  x[p] is either
+ *   - an input of the call: device memory that none of this call's outputs of phases <= p overlaps, or
+ *   - exactly the output y[i] of a matrix of an EARLIER phase with rows[i] == cols[p]: the phase then waits, inside
+ *     the launch, until that output is complete.  Any other overlap is IFLOW_ERR_SHAPE.
+ * Every y[i] receives what iflow_qgemv would have written, so the chain equals the sequence of iflow_qgemv_multi
+ * calls it replaces.  All arrays are HOST arrays read during the call; pointers in them are device pointers.
+ *
+ * workspace: device memory of at least iflow_qgemv_chain_workspace_bytes() bytes, 16-byte aligned, owned by the
+ * caller, ZEROED before its first use and then left alone: it carries the hand-over words and a launch counter
+ * from call to call.  Zero it again before using it for a chain with different shapes.  Calls that share a
+ * workspace must be ordered (same stream); concurrent chains need a workspace each.
+ *
+ * The launch keeps one workgroup per compute unit resident and its phases wait for each other, so it wants the
+ * device to itself: if other work holds compute units for long, or two chains run at once, a wait can exceed its
+ * bound (tens of milliseconds); the launch then still ends, the outputs are unspecified, and the workspace records
+ * it.  iflow_qgemv_chain_check() synchronises the stream and returns IFLOW_ERR_TIMEOUT in that case (the record
+ * stays until the workspace is zeroed again), IFLOW_OK otherwise. */
+#define IFLOW_CHAIN_MAX_PHASES 8
+#define IFLOW_CHAIN_MAX_GROUP 4
+#define IFLOW_CHAIN_MAX_MATRICES 16
+#define IFLOW_CHAIN_WS_HEADER 4096
+iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes);
+iflow_status_t iflow_qgemv_chain(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                 const uint16_t *const *x, const void *const *packed, const int64_t *rows,
+                                 uint16_t *const *y, void *workspace, size_t workspace_bytes, void *stream);
+iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream);
 
 /* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
  * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].

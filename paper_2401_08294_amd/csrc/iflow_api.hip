@@ -51,6 +51,7 @@ const char *iflow_status_string(iflow_status_t status)
     case IFLOW_ERR_SIZE: return "output buffer too small";
     case IFLOW_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case IFLOW_ERR_DEVICE: return "HIP call failed (see iflow_last_hip_error)";
+    case IFLOW_ERR_TIMEOUT: return "a chained launch gave up waiting for an earlier phase's output";
     default: return "unknown status";
     }
 }
@@ -154,6 +155,71 @@ iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *c
         if (!aligned16(packed[i]) || !aligned16(y[i])) return IFLOW_ERR_ALIGN;
     }
     return device_status(iflow::launch_qgemv_multi((int)format, count, packed, rows, cols, x, y, (hipStream_t)stream));
+}
+
+iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes)
+{
+    if (!rows || !bytes) return IFLOW_ERR_NULL;
+    if (nmatrices < 1 || nmatrices > IFLOW_CHAIN_MAX_MATRICES) return IFLOW_ERR_SHAPE;
+    for (int i = 0; i < nmatrices; ++i)
+        if (rows[i] <= 0 || rows[i] > (1LL << 30)) return IFLOW_ERR_SHAPE;
+    *bytes = iflow::chain_workspace_bytes(nmatrices, rows);
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_qgemv_chain(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                 const uint16_t *const *x, const void *const *packed, const int64_t *rows,
+                                 uint16_t *const *y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    iflow::FormatInfo fi;
+    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
+    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;      // the chained launch exists for the 3.5-bit format only
+    if (nphases < 1 || nphases > IFLOW_CHAIN_MAX_PHASES) return IFLOW_ERR_SHAPE;
+    if (!counts || !cols || !x || !packed || !rows || !y || !workspace) return IFLOW_ERR_NULL;
+    int total = 0;
+    for (int p = 0; p < nphases; ++p) {
+        if (counts[p] < 1 || counts[p] > IFLOW_CHAIN_MAX_GROUP || counts[p] > IFLOW_CHAIN_MAX_MATRICES - total) return IFLOW_ERR_SHAPE;
+        total += counts[p];
+    }
+    int x_src[IFLOW_CHAIN_MAX_PHASES];
+    int m = 0;
+    for (int p = 0; p < nphases; ++p) {
+        if (!x[p]) return IFLOW_ERR_NULL;
+        if (!aligned16(x[p])) return IFLOW_ERR_ALIGN;
+        if (cols[p] > 65536) return IFLOW_ERR_SHAPE;
+        const int first = m;
+        for (int j = 0; j < counts[p]; ++j, ++m) {
+            iflow_status_t st = check_shape(format, rows[m], cols[p], &fi);
+            if (st != IFLOW_OK) return st;
+            if (!packed[m] || !y[m]) return IFLOW_ERR_NULL;
+            if (!aligned16(packed[m]) || !aligned16(y[m])) return IFLOW_ERR_ALIGN;
+        }
+        // the activations are either an output of an earlier phase, whole, or memory that no output of this call
+        // up to and including this phase overlaps
+        x_src[p] = -1;
+        const uintptr_t xb = reinterpret_cast<uintptr_t>(x[p]), xe = xb + (uintptr_t)cols[p] * 2;
+        for (int i = 0; i < m; ++i) {
+            const uintptr_t yb = reinterpret_cast<uintptr_t>(y[i]), ye = yb + (uintptr_t)rows[i] * 2;
+            if (xb >= ye || yb >= xe) continue;
+            if (i < first && xb == yb && rows[i] == cols[p] && x_src[p] < 0) x_src[p] = i;
+            else return IFLOW_ERR_SHAPE;
+        }
+    }
+    if (workspace_bytes < iflow::chain_workspace_bytes(total, rows)) return IFLOW_ERR_SIZE;
+    if (!aligned16(workspace)) return IFLOW_ERR_ALIGN;
+    hipError_t e = iflow::launch_qgemv_chain(nphases, counts, cols, x, packed, rows, y, x_src, workspace, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // more rows in the chain than the kernel's 32-bit indices cover
+    return device_status(e);
+}
+
+iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream)
+{
+    if (!workspace) return IFLOW_ERR_NULL;
+    uint32_t head[2] = {0, 0};
+    hipError_t e = hipMemcpyAsync(head, workspace, sizeof(head), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return device_status(e);
+    return head[1] ? IFLOW_ERR_TIMEOUT : IFLOW_OK;
 }
 
 iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, void *stream)

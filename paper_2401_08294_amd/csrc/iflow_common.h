@@ -107,6 +107,10 @@ hipError_t launch_unpack(int format, const void *packed, int64_t rows, int64_t c
 hipError_t launch_calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_qgemv_multi(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols,
                               const uint16_t *x, uint16_t *const *y, hipStream_t s);
+size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
+hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
+                              const void *const *packed, const int64_t *rows, uint16_t *const *y,
+                              const int *x_src, void *workspace, hipStream_t s);
 hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int64_t cols,
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64_t cols,

@@ -1,0 +1,435 @@
+// A chain of Q3H matrix-vector products in ONE launch: phase after phase, each phase a group of matrices that
+// share an activation vector, and a phase may take as its activations the output of a matrix of an earlier
+// phase (q/k/v -> o -> gate/up -> down of a decoder layer).  At batch 1 a 7B-sized product lasts a few
+// microseconds, of which a launch boundary costs 1.6 us of idle memory system plus the ramp of a fresh grid;
+// here the grid stays resident, and the weights of the next phase are already on their way while the outputs
+// of the current one are handed over.
+//
+// Resident grid: one workgroup of 16 wavefronts per compute unit.  Each phase's rows are cut into equal
+// contiguous ranges, one per workgroup; wavefront w of a workgroup takes rows w, w + 16, ... of the range and
+// walks each row strip by strip (a strip = 64 blocks = 4096 columns, one block per lane, as in the
+// single-product kernel).  A wavefront keeps S steps (row, strip) of weights in flight in S register sets and
+// requests step k + S as soon as step k is decoded, across phase boundaries: weights do not depend on the
+// activations, so the memory system keeps streaming while a phase waits for its input.
+//
+// Hand-over without a grid barrier: outputs that a later phase consumes travel through the caller's workspace
+// as 32-bit words (fp16 value, 16-bit tag), written by the lane that holds the row sum with one write-through
+// store and read with cache-bypassing loads.  The tag comes from a launch counter kept in the workspace, so a
+// word is its own "ready" flag: a consumer simply re-reads until every word of the vector carries this launch's
+// tag.  There are no atomics on shared counters and no fences; one memory round trip separates the last producer
+// from the first consumer.  The words are stored in the order in which the consumer's threads want them (below),
+// so that their loads coalesce.  The counter advances once per launch, after every workgroup has finished, so a
+// word left by the previous launch never carries the current tag; a workspace that changes hands between chains
+// of different shapes has to be zeroed in between (tags repeat every 65535 launches).  Every wait is bounded:
+// when the budget runs out the workgroup raises the error word of the workspace and carries on, so the launch
+// always ends (iflow_qgemv_chain_check reports it).
+#include "iflow_lane.h"
+
+#include <stdlib.h>
+
+#include <type_traits>
+
+namespace iflow {
+
+constexpr int CHAIN_WAVES = 16;                                // wavefronts per workgroup
+constexpr int CHAIN_SLOT_BYTES = 8 * 64 * 16 + 64 * 8;        // staged activations of one strip (as in q3h_gemv_kernel)
+constexpr int CHAIN_MAX_STRIPS = 16;                           // columns <= 65536
+constexpr int CHAIN_MAX_GROUP = 4;                             // matrices per phase
+constexpr int CHAIN_MAX_GRID = 960;
+constexpr int CHAIN_POLL_BUDGET = 1 << 17;                     // re-reads before a wait is given up (tens of milliseconds)
+// workspace header, in 32-bit words: [0] launch counter, [1] error, [64, 64 + grid) per-workgroup "done" marks;
+// tagged outputs start at byte IFLOW_CHAIN_WS_HEADER
+constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_SEEN = 64;
+
+// Kernel arguments.  Everything a wavefront needs when it enters a phase sits in one 64-byte descriptor, and
+// everything about a matrix in one 32-byte descriptor: a scalar load each, instead of a chain of dependent loads
+// (a scalar load costs a few hundred nanoseconds of latency, and a phase of a 7B layer lasts a few microseconds).
+struct ChainPhase {
+    const uint16_t *x;          // activations when they are an input of the launch
+    int first, count;           // matrices [first, first + count)
+    int nbk, nstrips;           // blocks and strips per row
+    int x_src;                  // matrix whose output is this phase's activation vector, or -1
+    int rows_per_wg;
+    int total;                  // rows of the phase, all its matrices together
+    int x_tag_word;             // tagged output of matrix x_src, in 32-bit words from the workspace start
+    int mstart[CHAIN_MAX_GROUP];    // first row of each matrix within the phase; INT_MAX past `count`
+    int pad_[2];
+};
+struct ChainMatrix {
+    const uint8_t *packed;
+    uint16_t *y;
+    int rows;
+    int start;                  // first row of the matrix within its phase
+    int tag_word;               // its tagged output, in 32-bit words from the workspace start
+    int pad_;
+};
+struct ChainArgs {
+    int nphases, pad_;
+    ChainPhase ph[IFLOW_CHAIN_MAX_PHASES];
+    ChainMatrix mat[IFLOW_CHAIN_MAX_MATRICES];
+};
+static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 32, "descriptor sizes");
+
+// Position of output r inside a matrix's tagged vector, in 32-bit words.  A consumer thread stages one chunk of 16
+// activations with eight 8-byte loads; the pair (2i, 2i+1) of chunk c of a strip sits at 8-byte word i * 256 + c,
+// so the loads of neighbouring threads read neighbouring words.
+__device__ __forceinline__ int chain_tag_word(int r)
+{
+    const int g = r >> 1;
+    return 2 * ((g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255)) + (r & 1);
+}
+
+// Wave-uniform values are pinned to scalar registers explicitly: the cursor below is updated under (uniform) control
+// flow deep inside the step loop, and whatever the compiler cannot prove uniform there becomes vector loads of the
+// kernel arguments.
+#define IFLOW_UNI(v) __builtin_amdgcn_readfirstlane(v)
+
+template <int S>
+__global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint32_t *__restrict__ ws)
+{
+    extern __shared__ __align__(16) uint8_t xs[];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wg = blockIdx.x;
+
+    // ---- weight requests: a cursor over this wavefront's steps of all phases, all of it in scalar registers -----
+    // Per phase the steps of a wavefront are padded to a multiple of S with empty steps, so that step k of the whole
+    // sequence always lives in register set k mod S and the step loop can be unrolled by S with fixed registers
+    // (one copy of the loop per starting register set is more than the compiler's register allocation copes with).
+    // (Control flow here is kept single-exit on purpose: it stays wave-uniform only as long as the compiler sees that.)
+    int lp = -1, lj = 0, l_real = 0, l_pad = 0, li = 0, lt = 0, l_nstrips = 1, l_nbk = 0, l_row0 = 0, l_first = 0;
+    int l_ms1 = 0x7FFFFFFF, l_ms2 = 0x7FFFFFFF, l_ms3 = 0x7FFFFFFF;
+    int lm_lo = 0, lm_hi = 0;                                  // rows [lm_lo, lm_hi) of the phase belong to the matrix at lm_pk:
+    const uint8_t *lm_pk = a.mat[0].packed;                    // looked up again only when the cursor leaves that range
+    auto phase_steps = [&](const ChainPhase &ph, int &rbeg, int &nrows) {     // rows of this wavefront in a phase
+        rbeg = IFLOW_UNI(wg * ph.rows_per_wg);
+        const int rend = min(rbeg + ph.rows_per_wg, ph.total);
+        nrows = IFLOW_UNI(max(0, (rend - rbeg - wave + CHAIN_WAVES - 1) / CHAIN_WAVES));
+    };
+    auto enter_phase = [&]() {                                 // advance lp to the next phase in which this wavefront has rows
+        bool found = false;
+        do {
+            lp = IFLOW_UNI(lp + 1);
+            if (lp < a.nphases) {
+                const ChainPhase ph = a.ph[lp];
+                int rbeg, nrows;
+                phase_steps(ph, rbeg, nrows);
+                if (nrows > 0) {
+                    found = true;
+                    l_nstrips = IFLOW_UNI(ph.nstrips); l_nbk = IFLOW_UNI(ph.nbk); l_row0 = IFLOW_UNI(rbeg + wave);
+                    l_first = IFLOW_UNI(ph.first);
+                    l_ms1 = IFLOW_UNI(ph.mstart[1]); l_ms2 = IFLOW_UNI(ph.mstart[2]); l_ms3 = IFLOW_UNI(ph.mstart[3]);
+                    l_real = IFLOW_UNI(nrows * l_nstrips); l_pad = IFLOW_UNI((l_real + S - 1) / S * S);
+                    lj = 0; li = 0; lt = 0; lm_lo = 0; lm_hi = 0;
+                }
+            }
+        } while (!found && lp < a.nphases);
+    };
+    // The two loads of a step are issued unconditionally, empty steps included (all lanes then read the first 16
+    // bytes of the first matrix): with the same number of loads on every path the compiler can tell exactly how
+    // many younger loads may still be in flight when a register set is decoded, instead of waiting for all of them.
+    auto request = [&](WRegs<KIND_Q3H> &w) {                   // request the step under the cursor, then advance it
+        const bool have = lp < a.nphases && lj < l_real;
+        const uint8_t *p0 = a.mat[0].packed;
+        int n_t = 0;
+        if (have) {
+            const int R = IFLOW_UNI(l_row0 + li * CHAIN_WAVES);
+            if (R >= lm_hi) {                                  // which matrix of the phase the row belongs to
+                const int m = IFLOW_UNI(l_first + (R >= l_ms1) + (R >= l_ms2) + (R >= l_ms3));
+                const ChainMatrix mt = a.mat[m];
+                lm_lo = IFLOW_UNI(mt.start); lm_hi = IFLOW_UNI(lm_lo + mt.rows); lm_pk = mt.packed;
+            }
+            n_t = min(64, l_nbk - lt * 64);
+            p0 = lm_pk + (int64_t)(R - lm_lo) * ((int64_t)l_nbk * 32) + (int64_t)lt * 2048;
+        }
+        const uint32_t lane_off = (uint32_t)(lane * 16) & mask_lt(lane, n_t);   // lanes past a ragged end redo block 0
+        const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + lane_off));
+        const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + n_t * 16 + lane_off));
+        w.d[0] = c0.x; w.d[1] = c0.y; w.d[2] = c0.z; w.d[3] = c0.w;
+        w.d[4] = c1.x; w.d[5] = c1.y; w.d[6] = c1.z; w.d[7] = c1.w;
+        if (have) {
+            lt = IFLOW_UNI(lt + 1);
+            if (lt == l_nstrips) { lt = 0; li = IFLOW_UNI(li + 1); }
+        }
+        if (lp < a.nphases) {
+            lj = IFLOW_UNI(lj + 1);
+            if (lj == l_pad) enter_phase();
+        }
+    };
+
+    // ---- activations of a phase into LDS, in decode order ---------------------------------------------------
+    // Chunk c = (strip ts, block blk, quarter qd), qd fastest: 16 activations that feed decode slots 4qd..4qd+3 of
+    // lane blk.  n[k] holds the pair (x[2k], x[2k+1]) of the chunk.
+    auto chunk_put = [&](int c, const uint32_t (&n)[8]) {
+        const int cc = c & 255, ts = c >> 8, blk = cc >> 2, qd = cc & 3;
+        const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
+        uint32_t e[4], o[4];
+        float se = 0.f, so = 0.f;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            e[m] = __builtin_amdgcn_perm(n[2 * m + 1], n[2 * m], 0x05040100u);    // (x[4m], x[4m+2])
+            o[m] = __builtin_amdgcn_perm(n[2 * m + 1], n[2 * m], 0x07060302u);    // (x[4m+1], x[4m+3])
+            se = dot2(as_h2(e[m]), ones, se);
+            so = dot2(as_h2(o[m]), ones, so);
+        }
+        uint8_t *sl = xs + (size_t)ts * CHAIN_SLOT_BYTES;
+        *reinterpret_cast<uint4 *>(sl + (qd * 64 + blk) * 16) = make_uint4(e[0], e[1], e[2], e[3]);
+        *reinterpret_cast<uint4 *>(sl + ((4 + qd) * 64 + blk) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+        float bs = IFLOW_Q3H_BIAS1 * se + IFLOW_Q3H_BIAS2 * so, sx = se + so;
+        bs += dpp_f32<0xB1, 0xF>(bs); sx += dpp_f32<0xB1, 0xF>(sx);              // the four quarters of a block
+        bs += dpp_f32<0x4E, 0xF>(bs); sx += dpp_f32<0x4E, 0xF>(sx);              // sit in one quad of lanes
+        if (qd == 0) *reinterpret_cast<float2 *>(sl + 8 * 64 * 16 + blk * 8) = make_float2(bs, sx);
+    };
+    // source of a chunk of launch-input activations; chunks past the end of the row read chunk 0 of their strip
+    auto chunk_src = [&](const uint16_t *x, int c, int nbk) {
+        const int cc = c & 255, ts = c >> 8;
+        const int n_t = min(64, nbk - ts * 64);
+        const int ccl = cc & (int)mask_lt(cc >> 2, n_t);
+        return reinterpret_cast<const uint4 *>(x + (int64_t)ts * 4096 + ccl * 16);
+    };
+    auto chunk_live = [&](int c, int nbk) { return mask_lt((c & 255) >> 2, min(64, nbk - (c >> 8) * 64)); };
+    auto put_plain = [&](int c, int nbk, const uint4 q0, const uint4 q1) {
+        const uint32_t live = chunk_live(c, nbk);              // columns past the end of the row count as zero
+        const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
+        chunk_put(c, n);
+    };
+
+    // The first phase's activations are an input of the launch.  Their first chunk is requested BEFORE any weights,
+    // because memory requests of a wavefront are served in order and the whole workgroup waits for the staged
+    // activations; then S steps of weights; then the chunk is put in place.
+    WRegs<KIND_Q3H> w[S];
+    // The launch counter, the oldest load of the wavefront (so it never has to be waited for alone).  A plain cached
+    // load: the word was last written by the previous launch, and changes again only when this one is over.
+    const uint32_t counter = __hip_atomic_load(ws, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    {
+        const ChainPhase ph0 = a.ph[0];
+        const bool wg_has0 = wg * ph0.rows_per_wg < ph0.total;
+        const int nchunks0 = wg_has0 ? ph0.nstrips * 256 : 0;
+        const uint4 *src0 = chunk_src(ph0.x, tid & (int)mask_lt(tid, nchunks0), ph0.nbk);   // threads without a chunk read chunk 0
+        const uint4 xq0 = src0[0], xq1 = src0[1];
+        enter_phase();
+#pragma unroll
+        for (int j = 0; j < S; ++j) request(w[j]);
+        // (whole wavefronts have a chunk or not: loop bounds and conditions are written on the wavefront's first chunk)
+        if (wave * 64 < nchunks0) put_plain(tid, ph0.nbk, xq0, xq1);
+#pragma unroll 1
+        for (int cw = wave * 64 + 1024; cw < nchunks0; cw += 1024) {
+            const uint4 *src = chunk_src(ph0.x, cw + lane, ph0.nbk);
+            put_plain(cw + lane, ph0.nbk, src[0], src[1]);
+        }
+    }
+    // Every wavefront of the launch reads the same counter (it is advanced only after all workgroups are done), and
+    // tags its outputs with it, 1..65535; 0 marks a word that was never written.
+    const uint32_t tag = (counter % 65535u + 1u) << 16;
+
+    bool failed = false;
+    XRegs<KIND_Q3H> xr[1];
+    for (int p = 0; p < a.nphases; p = IFLOW_UNI(p + 1)) {
+        const ChainPhase ph = a.ph[p];
+        const int nbk = IFLOW_UNI(ph.nbk), nstrips = IFLOW_UNI(ph.nstrips);
+        int rbeg, n;                                           // first row of the workgroup, rows of this wavefront
+        phase_steps(ph, rbeg, n);
+        if (rbeg < ph.total) {                                 // else: no rows for this workgroup (uniform over the workgroup)
+            // 1. stage the activations (those of the first phase are already on their way)
+            const int nchunks = nstrips * 256;
+            if (p > 0 && ph.x_src < 0) {
+#pragma unroll 1
+                for (int cw = wave * 64; cw < nchunks; cw += 1024) {
+                    const uint4 *src = chunk_src(ph.x, cw + lane, nbk);
+                    put_plain(cw + lane, nbk, src[0], src[1]);
+                }
+            } else if (p > 0) {
+                const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + ph.x_tag_word);
+#pragma unroll 1
+                for (int cw = wave * 64; cw < nchunks; cw += 1024) {
+                    const int c = cw + lane;
+                    // chunks past the end of the row were never written: their lanes read chunk 0 and ignore it
+                    const bool live = chunk_live(c, nbk) != 0;
+                    const uint64_t *src = base + (c >> 8) * 2048 + (live ? (c & 255) : 0);
+                    uint32_t n8[8];
+                    int budget = failed ? 1 : CHAIN_POLL_BUDGET;
+                    bool again;                                // the wavefront re-reads as long as any of its lanes has to
+                    do {
+                        uint64_t wd[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            wd[i] = __hip_atomic_load(src + i * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        bool ok = true;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const uint32_t lo = (uint32_t)wd[i], hi = (uint32_t)(wd[i] >> 32);
+                            ok = ok && ((lo ^ tag) >> 16) == 0 && ((hi ^ tag) >> 16) == 0;
+                            n8[i] = (lo & 0xFFFFu) | (hi << 16);
+                        }
+                        again = __builtin_amdgcn_ballot_w64(live && !ok) != 0;
+                        if (again) {
+                            budget = IFLOW_UNI(budget - 1);
+                            if (budget <= 0) {
+                                failed = true;
+                                again = false;
+                                if (lane == 0) __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            } else {
+                                __builtin_amdgcn_s_sleep(2);
+                            }
+                        }
+                    } while (again);
+                    if (!live)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) n8[i] = 0;
+                    chunk_put(c, n8);
+                }
+            }
+            __syncthreads();
+
+            // 2. this wavefront's steps; step j of the phase uses register set j mod S
+            auto load_xr = [&](int ts) {
+                const uint8_t *sl = xs + (size_t)ts * CHAIN_SLOT_BYTES;
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const uint4 q = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
+                    xr[0].v[4 * jj] = as_h2(q.x); xr[0].v[4 * jj + 1] = as_h2(q.y);
+                    xr[0].v[4 * jj + 2] = as_h2(q.z); xr[0].v[4 * jj + 3] = as_h2(q.w);
+                }
+                const float2 sm = *reinterpret_cast<const float2 *>(sl + 8 * 64 * 16 + lane * 8);
+                xr[0].bias_sum = sm.x; xr[0].x_sum = sm.y;
+            };
+            if (nstrips == 1 && n > 0) load_xr(0);             // a single strip stays in registers for all rows
+            float part = 0.f;                                  // per-lane partial sum of the current row, carried across strips
+            const int nreal = IFLOW_UNI(n * nstrips);
+            int i = 0, t = 0;
+            int cm_lo = 0, cm_hi = 0, cm_tw = 0;               // the matrix that the finished rows belong to, as for the requests
+            uint16_t *cm_y = a.mat[0].y;
+            auto body = [&](auto stage, int j) {
+                constexpr int st = decltype(stage)::value;
+                const bool real = j < nreal;                   // an empty step only passes its register set on
+                float v = 0.f;
+                if (real) {
+                    if (nstrips > 1) load_xr(t);
+                    float acc[1];
+                    lane_dot<KIND_Q3H, 1>(w[st], xr, acc);
+                    const half2_t so = as_h2(q3h_header(w[st].d));
+                    v = part + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
+                }
+                request(w[st]);                                // step j + S of the sequence takes over the register set
+                const bool last = real && t == nstrips - 1;    // the row is complete: one reduction, lane 63 publishes it
+                if (last) {
+                    const float sum = wave_sum_to_lane63(v);
+                    const int R = IFLOW_UNI(rbeg + wave + i * CHAIN_WAVES);
+                    if (R >= cm_hi) {
+                        const int m = IFLOW_UNI(ph.first + (R >= ph.mstart[1]) + (R >= ph.mstart[2]) + (R >= ph.mstart[3]));
+                        const ChainMatrix mt = a.mat[m];
+                        cm_lo = IFLOW_UNI(mt.start); cm_hi = IFLOW_UNI(cm_lo + mt.rows); cm_tw = IFLOW_UNI(mt.tag_word); cm_y = mt.y;
+                    }
+                    const int r = R - cm_lo, tw = cm_tw;
+                    uint16_t *yp = cm_y;
+                    if (lane == 63) {
+                        const uint32_t h = as_u16((half_t)sum);
+                        yp[r] = (uint16_t)h;                   // the caller's plain fp16 output
+                        __hip_atomic_store(ws + tw + chain_tag_word(r), h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+                // (plain selects: written as stores under branches, these end up in scratch memory)
+                part = last ? 0.f : (real ? v : part);
+                i = IFLOW_UNI(i + (last ? 1 : 0));
+                t = IFLOW_UNI(last ? 0 : t + (real ? 1 : 0));
+            };
+#pragma unroll 1
+            for (int j = 0; j < nreal; j += S) {
+                body(std::integral_constant<int, 0>{}, j);
+                if constexpr (S > 1) body(std::integral_constant<int, 1>{}, j + 1);
+                if constexpr (S > 2) body(std::integral_constant<int, 2>{}, j + 2);
+                if constexpr (S > 3) body(std::integral_constant<int, 3>{}, j + 3);
+            }
+            __syncthreads();                                   // the staged activations are no longer needed
+        }
+    }
+
+    // ---- once every workgroup is done, the launch counter advances -------------------------------------------------
+    __syncthreads();
+    if (tid == 0) __hip_atomic_store(ws + CHAIN_WS_SEEN + wg, counter + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (wg == 0 && wave == 0) {
+        int budget = CHAIN_POLL_BUDGET;
+        for (;;) {
+            bool ok = true;
+            for (int i = lane; i < (int)gridDim.x; i += 64)
+                ok = ok && __hip_atomic_load(ws + CHAIN_WS_SEEN + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == counter + 1;
+            if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
+            if (--budget <= 0) {
+                if (lane == 0) __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (lane == 0) __hip_atomic_store(ws, counter + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ---- host side ------------------------------------------------------------------------------------------------
+size_t chain_workspace_bytes(int nmatrices, const int64_t *rows)
+{
+    size_t bytes = IFLOW_CHAIN_WS_HEADER;
+    for (int i = 0; i < nmatrices; ++i) bytes += (size_t)((rows[i] + 4095) / 4096) * 4096 * 4;
+    return bytes;
+}
+
+// Launch geometry: as many workgroups as the device has compute units (each workgroup fills one: 1024 threads
+// and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
+// concurrently.  Returns hipErrorInvalidValue for shapes outside the kernel's limits.
+hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
+                              const void *const *packed, const int64_t *rows, uint16_t *const *y,
+                              const int *x_src, void *workspace, hipStream_t s)
+{
+    static int grid = 0;
+    static const int depth = getenv("IFLOW_DEBUG_CHAIN_S") ? atoi(getenv("IFLOW_DEBUG_CHAIN_S")) : 2;
+    if (grid == 0) {
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<3>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e != hipSuccess) return e;
+        if (cus < 1) return hipErrorInvalidDevice;
+        grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
+    }
+    ChainArgs a = {};
+    a.nphases = nphases;
+    int m = 0, max_strips = 1;
+    size_t word = IFLOW_CHAIN_WS_HEADER / 4;
+    for (int p = 0; p < nphases; ++p) {
+        ChainPhase &ph = a.ph[p];
+        ph.x = x[p]; ph.first = m; ph.count = counts[p];
+        for (int j = 0; j < CHAIN_MAX_GROUP; ++j) ph.mstart[j] = 0x7FFFFFFF;
+        ph.nbk = (int)(cols[p] / 64); ph.nstrips = (ph.nbk + 63) / 64;
+        ph.x_src = x_src[p];
+        ph.x_tag_word = x_src[p] >= 0 ? a.mat[x_src[p]].tag_word : 0;
+        if (ph.nstrips > CHAIN_MAX_STRIPS || counts[p] > CHAIN_MAX_GROUP) return hipErrorInvalidValue;
+        if (ph.nstrips > max_strips) max_strips = ph.nstrips;
+        int64_t v = 0;
+        for (int j = 0; j < counts[p]; ++j, ++m) {
+            a.mat[m].packed = static_cast<const uint8_t *>(packed[m]); a.mat[m].y = y[m]; a.mat[m].rows = (int)rows[m];
+            a.mat[m].start = (int)v;
+            a.mat[m].tag_word = (int)word;
+            ph.mstart[j] = (int)v;
+            word += (size_t)((rows[m] + 4095) / 4096) * 4096;
+            v += rows[m];
+        }
+        const int64_t rpw = (v + grid - 1) / grid;
+        if (v > 0x3FFFFFFF || word > 0x3FFFFFFF) return hipErrorInvalidValue;
+        ph.total = (int)v; ph.rows_per_wg = (int)rpw;
+    }
+    const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES;
+    if (depth == 3)
+        hipLaunchKernelGGL((q3h_chain_kernel<3>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, a,
+                           static_cast<uint32_t *>(workspace));
+    else
+        hipLaunchKernelGGL((q3h_chain_kernel<2>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, a,
+                           static_cast<uint32_t *>(workspace));
+    return hipGetLastError();
+}
+
+}  // namespace iflow

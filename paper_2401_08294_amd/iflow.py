@@ -17,7 +17,8 @@ Q8_B32, Q8_B64, Q4_B32, Q4_B64, Q3H_B64 = range(5)
 FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B64, "Q3H_B64": Q3H_B64}
 BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 4.0}
 
-OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE = range(7)
+OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE, ERR_TIMEOUT = range(8)
+CHAIN_MAX_PHASES, CHAIN_MAX_MATRICES = 8, 16
 
 
 class IflowError(RuntimeError):
@@ -55,6 +56,10 @@ def lib():
         L.iflow_unpack_logical.argtypes = [C.c_int, p, i64, i64, p, p, p, p]
         L.iflow_calibration_copy.argtypes = [p, p, sz, p]
         L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
+        L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
+        L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
+                                        C.POINTER(i64), C.POINTER(p), p, sz, p]
+        L.iflow_qgemv_chain_check.argtypes = [p, p]
         _lib = L
     return _lib
 
@@ -135,3 +140,32 @@ def qgemv_multi(fmt: int, packed_list, rows_list, cols: int, x, y_list, stream=N
     ys = (C.c_void_p * n)(*[_ptr(t) for t in y_list])
     rs = (C.c_int64 * n)(*[int(r) for r in rows_list])
     _check(lib().iflow_qgemv_multi(fmt, n, pk, rs, cols, _ptr(x), ys, _stream(stream)), "iflow_qgemv_multi")
+
+
+def qgemv_chain_workspace_bytes(rows_list) -> int:
+    n = len(rows_list)
+    rs = (C.c_int64 * n)(*[int(r) for r in rows_list])
+    out = C.c_size_t(0)
+    _check(lib().iflow_qgemv_chain_workspace_bytes(n, rs, C.byref(out)), "iflow_qgemv_chain_workspace_bytes")
+    return int(out.value)
+
+
+def qgemv_chain(fmt: int, phases, workspace, workspace_bytes: int, stream=None) -> None:
+    """One launch for a chain of batch-1 products.  `phases` is a list of (cols, x, [(packed, rows, y), ...]);
+    x may be the y tensor of a matrix of an earlier phase.  `workspace`: zeroed once, uint8 device tensor."""
+    nph = len(phases)
+    mats = [m for (_, _, ms) in phases for m in ms]
+    n = len(mats)
+    counts = (C.c_int * nph)(*[len(ms) for (_, _, ms) in phases])
+    cols = (C.c_int64 * nph)(*[int(c) for (c, _, _) in phases])
+    xs = (C.c_void_p * nph)(*[_ptr(x) for (_, x, _) in phases])
+    pk = (C.c_void_p * n)(*[_ptr(m[0]) for m in mats])
+    rs = (C.c_int64 * n)(*[int(m[1]) for m in mats])
+    ys = (C.c_void_p * n)(*[_ptr(m[2]) for m in mats])
+    _check(lib().iflow_qgemv_chain(fmt, nph, counts, cols, xs, pk, rs, ys, _ptr(workspace), workspace_bytes,
+                                   _stream(stream)), "iflow_qgemv_chain")
+
+
+def qgemv_chain_check(workspace, stream=None) -> None:
+    """Synchronises the stream; raises IflowError(ERR_TIMEOUT) if a chained launch gave up a wait."""
+    _check(lib().iflow_qgemv_chain_check(_ptr(workspace), _stream(stream)), "iflow_qgemv_chain_check")

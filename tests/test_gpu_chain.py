@@ -1,0 +1,157 @@
+"""GPU parity of the chained launch (iflow_qgemv_chain): every phase against the CPU oracle and against the
+single-product kernel on the same inputs; repeated launches, HIP-graph replays, decoder-layer shapes."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2401_08294_amd import synth
+from test_gpu_parity import TOL, gpu, gpu_quantize, rel_err, say  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def build_chain(torch, iflow, spec, seed, sigma=0.02):
+    """spec: list of phases (cols, src, [rows...]) with src None (fresh input) or (phase, matrix) of an earlier
+    phase.  Returns device phases for iflow.qgemv_chain plus host copies of the weights."""
+    fmt = iflow.Q3H_B64
+    phases, host = [], []
+    for p, (cols, src, row_list) in enumerate(spec):
+        mats, hw = [], []
+        for j, rows in enumerate(row_list):
+            w = synth.weights(rows, cols, sigma, seed + 100 * p + j)
+            packed, _ = gpu_quantize(torch, iflow, fmt, w)
+            y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
+            mats.append((packed, rows, y))
+            hw.append(w)
+        if src is None:
+            x = torch.from_numpy(synth.activations(1, cols, seed + 7 + p)[0].view(np.int16)).cuda().view(torch.float16)
+        else:
+            x = phases[src[0]][2][src[1]][2]
+            assert x.numel() == cols
+        phases.append((cols, x, mats))
+        host.append(hw)
+    rows_all = [m[1] for ph in phases for m in ph[2]]
+    nbytes = iflow.qgemv_chain_workspace_bytes(rows_all)
+    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
+    return phases, host, ws, nbytes
+
+
+def check_phases(torch, iflow, orc, phases, host, what):
+    """Every output against the oracle (given the activations the GPU actually used) and against iflow_qgemv."""
+    fmt, ofmt = iflow.Q3H_B64, orc.FORMATS["Q3H_B64"]
+    for p, (cols, x, mats) in enumerate(phases):
+        xh = x.cpu().numpy().view(np.uint16)[None, :]
+        for j, (packed, rows, y) in enumerate(mats):
+            got = y.cpu().numpy()
+            assert np.isfinite(got).all(), f"{what}: phase {p} matrix {j} has non-finite outputs"
+            q, s, o = orc.quantize(ofmt, host[p][j])
+            ref = orc.gemm(orc.dequant(ofmt, q, s, o), xh)[0]
+            e = rel_err(got.astype(np.float64)[None, :], ref[None, :])
+            assert e <= TOL, f"{what}: phase {p} matrix {j} rel err {e}"
+            single = torch.empty((rows,), dtype=torch.float16, device="cuda")
+            iflow.qgemv(fmt, packed, rows, cols, x, single)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.view(np.uint16), single.cpu().numpy().view(np.uint16)), f"{what}: phase {p} matrix {j}"
+
+
+SPEC_RAGGED = [
+    (1408, None, [1024, 37, 2048]),        # 22 blocks: one ragged strip; an odd matrix in the middle
+    (1024, (0, 0), [4160]),                # consumes the first output
+    (4160, (1, 0), [100, 64]),             # 65 blocks: a second strip of one block
+    (2048, (0, 2), [77]),                  # consumes an output from three phases back
+    (128, None, [5]),                      # a fresh input in the middle of the chain; most workgroups have no rows
+]
+
+
+def test_chain_ragged_phases_and_relaunch(gpu, orc):
+    torch, iflow = gpu
+    say("[case] chain ragged spec, three launches with new inputs")
+    phases, host, ws, nbytes = build_chain(torch, iflow, SPEC_RAGGED, synth.BASE_SEED + 500, sigma=0.03)
+    for it in range(3):
+        if it:
+            for p, (cols, x, _) in enumerate(phases):
+                if SPEC_RAGGED[p][1] is None:
+                    x.copy_(torch.from_numpy(synth.activations(1, cols, synth.BASE_SEED + 600 + 10 * it + p)[0].view(np.int16)).cuda().view(torch.float16))
+            for _, _, mats in phases:
+                for m in mats:
+                    m[2].fill_(float("nan"))
+        iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
+        iflow.qgemv_chain_check(ws)
+        check_phases(torch, iflow, orc, phases, host, f"launch {it}")
+
+
+def test_chain_single_phase_is_qgemv(gpu, orc):
+    torch, iflow = gpu
+    say("[case] chain of one phase, 1024x1024")
+    phases, host, ws, nbytes = build_chain(torch, iflow, [(1024, None, [1024])], synth.BASE_SEED + 520)
+    iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
+    iflow.qgemv_chain_check(ws)
+    check_phases(torch, iflow, orc, phases, host, "single")
+
+
+def layer_spec(hidden, ffn):
+    return [(hidden, None, [hidden, hidden, hidden]), (hidden, (0, 0), [hidden]),
+            (hidden, (1, 0), [ffn, ffn]), (ffn, (2, 0), [hidden])]
+
+
+def test_chain_decoder_layer_7b_and_graph_replay(gpu, orc):
+    torch, iflow = gpu
+    say("[case] chain 7B decoder layer: q/k/v -> o -> gate/up -> down, eager then five HIP-graph replays")
+    spec = layer_spec(4096, 11008)
+    phases, host, ws, nbytes = build_chain(torch, iflow, spec, synth.BASE_SEED + 540, sigma=0.012)
+    fmt = iflow.Q3H_B64
+
+    def reference():                       # the launches the chain replaces, on the same buffers
+        outs = []
+        for cols, x, mats in phases:
+            ys = [torch.empty((m[1],), dtype=torch.float16, device="cuda") for m in mats]
+            outs.append(ys)
+        for p, (cols, x, mats) in enumerate(phases):
+            src = spec[p][1]
+            xin = x if src is None else outs[src[0]][src[1]]
+            iflow.qgemv_multi(fmt, [m[0] for m in mats], [m[1] for m in mats], cols, xin, outs[p])
+        torch.cuda.synchronize()
+        return [[y.cpu().numpy().view(np.uint16) for y in ys] for ys in outs]
+
+    def compare(what):
+        ref = reference()
+        for p, (_, _, mats) in enumerate(phases):
+            for j, m in enumerate(mats):
+                got = m[2].cpu().numpy().view(np.uint16)
+                assert np.array_equal(got, ref[p][j]), f"{what}: phase {p} matrix {j}: {(got != ref[p][j]).sum()} of {got.size} differ"
+
+    iflow.qgemv_chain(fmt, phases, ws, nbytes)
+    iflow.qgemv_chain_check(ws)
+    compare("eager")
+    # sampled rows of the last phase against the oracle
+    ofmt = orc.FORMATS["Q3H_B64"]
+    cols, x, mats = phases[3]
+    idx = synth.sample_rows(mats[0][1], 48, synth.BASE_SEED + 541)
+    q, s, o = orc.quantize(ofmt, host[3][0][idx])
+    ref = orc.gemm(orc.dequant(ofmt, q, s, o), x.cpu().numpy().view(np.uint16)[None, :])[0]
+    got = mats[0][2].cpu().numpy().astype(np.float64)[idx]
+    full = mats[0][2].cpu().numpy().astype(np.float64)
+    rms = np.sqrt(np.mean(full ** 2))
+    assert float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms))) <= TOL
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            iflow.qgemv_chain(fmt, phases, ws, nbytes, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(5):
+        x0 = phases[0][1]
+        x0.copy_(torch.from_numpy(synth.activations(1, 4096, synth.BASE_SEED + 560 + rep)[0].view(np.int16)).cuda().view(torch.float16))
+        for _, _, mats in phases:
+            for m in mats:
+                m[2].fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        if rep % 2:
+            graph.replay()                 # back-to-back replays: the second starts from the first one's workspace
+        torch.cuda.synchronize()
+        iflow.qgemv_chain_check(ws)
+        compare(f"replay {rep}")
