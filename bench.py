@@ -36,8 +36,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=160)
     ap.add_argument("--ring", type=int, default=16, help="distinct layers in the weight ring (16 = 1.5 GiB packed)")
     ap.add_argument("--format", default="Q3H_B64")
-    ap.add_argument("--launches", type=int, default=4, choices=(1, 4, 7),
+    ap.add_argument("--launches", type=int, default=1, choices=(1, 4, 7),
                     help="launches per layer: 7 = one per matrix; 4 = q,k,v in one iflow_qgemv_multi launch, o, gate+up in one, down")
+    ap.add_argument("--layers-per-launch", type=int, default=8, choices=(1, 2, 4, 8),
+                    help="with --launches 1: chain this many layers into one launch (the next layer's q/k/v read down's output)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -119,7 +121,8 @@ def main():
         del src, dst
 
     step_bytes = sum(algorithmic_bytes(r, c, bpw) for _, r, c in shapes)
-    launches_per_step = args.launches
+    if args.launches != 1:
+        args.layers_per_launch = 1
 
     stream = torch.cuda.Stream()
     raw = stream.cuda_stream
@@ -128,16 +131,27 @@ def main():
     groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches in (1, 4) else [[i] for i in range(len(shapes))]
     if args.launches == 1:       # one chained launch per layer: o reads q's output, gate/up read o's, down reads gate's
         assert args.format == "Q3H_B64", "the chained launch exists for the 3.5-bit format"
-        chain_ws_bytes = iflow.qgemv_chain_workspace_bytes([r for _, r, _ in shapes])
+        chain_ws_bytes = iflow.qgemv_chain_workspace_bytes([r for _, r, _ in shapes] * args.layers_per_launch)
         chain_ws = torch.zeros(chain_ws_bytes, dtype=torch.uint8, device=dev)
-        chain_x = [xs[shapes[0][2]], ys[0], ys[3], ys[4]]
+        # outputs of the further layers of a multi-layer launch; layer l's q/k/v read layer l-1's down output
+        ys_l = [ys] + [[torch.empty_like(y) for y in ys] for _ in range(args.layers_per_launch - 1)]
+        if args.layers_per_launch > 1:     # no norms between the products here: start small so that fp16 holds the growth
+            xs[shapes[0][2]].mul_(2.0 ** -10)            # (each layer grows the values about 4.4-fold)
+
+    launch_count = [0]
+
+    def chain_launch(layer, count):
+        """One launch for `count` consecutive layers starting at ring position `layer`."""
+        phases = []
+        for l in range(count):
+            m_l, y_l = ring[(layer + l) % args.ring], ys_l[l]
+            x_l = [xs[shapes[0][2]] if l == 0 else ys_l[l - 1][6], y_l[0], y_l[3], y_l[4]]
+            phases += [(m_l[g[0]][1], x_l[i], [(m_l[j][2], m_l[j][0], y_l[j]) for j in g]) for i, g in enumerate(groups)]
+        iflow.qgemv_chain(fmt, phases, chain_ws, chain_ws_bytes, stream=raw)
+        launch_count[0] += 1
 
     def one_step(layer):
         mats = ring[layer]
-        if args.launches == 1:
-            phases = [(mats[g[0]][1], chain_x[i], [(mats[j][2], mats[j][0], ys[j]) for j in g]) for i, g in enumerate(groups)]
-            iflow.qgemv_chain(fmt, phases, chain_ws, chain_ws_bytes, stream=raw)
-            return
         for g in groups:
             cols = mats[g[0]][1]
             if len(g) == 1:
@@ -146,28 +160,45 @@ def main():
             else:
                 iflow.qgemv_multi(fmt, [mats[i][2] for i in g], [mats[i][0] for i in g], cols, xs[cols],
                                   [ys[i] for i in g], stream=raw)
+            launch_count[0] += 1
+
+    def advance(layer, budget):
+        """Run at most `budget` steps (layers) starting at ring position `layer`; returns how many were run."""
+        if args.launches == 1:
+            count = min(args.layers_per_launch, budget)
+            chain_launch(layer, count)
+            return count
+        one_step(layer)
+        return 1
 
     graph = None
+    graph_launches = 0
     with torch.cuda.stream(stream):
-        for layer in range(min(2, args.ring)):      # load code objects before capture
-            one_step(layer)
+        layer = 0
+        while layer < min(2 * args.layers_per_launch, args.ring):      # load code objects before capture
+            layer += advance(layer, args.ring - layer)
         stream.synchronize()
         if not args.no_graph:
             graph = torch.cuda.CUDAGraph()
+            launch_count[0] = 0
             with torch.cuda.graph(graph, stream=stream):
-                for layer in range(args.ring):
-                    one_step(layer)
+                layer = 0
+                while layer < args.ring:
+                    layer += advance(layer, args.ring - layer)
+            graph_launches = launch_count[0]
 
         def run(nsteps, start_layer=0):
+            """Exactly nsteps steps: whole ring trips by graph replay, the rest by direct launches."""
             done, layer = 0, start_layer
             while done < nsteps:
                 if graph is not None and layer == 0 and nsteps - done >= args.ring:
                     graph.replay()
+                    launch_count[0] += graph_launches
                     done += args.ring
                 else:
-                    one_step(layer)
-                    done += 1
-                    layer = (layer + 1) % args.ring
+                    n = advance(layer, min(nsteps - done, args.ring - layer))
+                    done += n
+                    layer = (layer + n) % args.ring
             return layer
 
         run(args.warmup)
@@ -175,6 +206,7 @@ def main():
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
+        launch_count[0] = 0
         run(args.steps)
         e1.record(stream)
         e1.synchronize()
@@ -183,13 +215,15 @@ def main():
 
     ms_per_step = ms / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    launches_per_step = launch_count[0] / args.steps            # a chained launch covers several layers (steps)
     us_per_launch = ms_per_step * 1e3 / launches_per_step
     bytes_per_launch = step_bytes / launches_per_step
     achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
 
     # HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, calibrated), if present
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", "q3h_gemv_7b_layer_hbm_traffic.txt")
+    tfile = os.path.join(ROOT, "profiles", "q3h_chain_7b_layers_hbm_traffic.txt" if args.launches == 1 and args.layers_per_launch == 8
+                         else "q3h_gemv_7b_layer_hbm_traffic.txt" if args.launches == 4 else "none")
     if args.format == "Q3H_B64" and os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("hbm_bytes_per_launch"):
@@ -208,9 +242,10 @@ def main():
                                f"{args.format}, batch 1, ring of {args.ring} distinct layers "
                                f"({args.ring * step_bytes / 2**30:.2f} GiB packed), "
                                + ("HIP-graph replay" if graph is not None else "eager launches")
-                               + {1: ", 1 chained launch per layer (q+k+v -> o -> gate+up -> down, each phase reading the previous one's output)",
+                               + {1: f", 1 chained launch per {args.layers_per_launch} layer(s) (q+k+v -> o -> gate+up -> down -> next layer's q+k+v ..., "
+                                     "each phase reading the previous one's output)",
                                   4: ", 4 launches per layer (q+k+v, o, gate+up, down)", 7: ", 7 launches per layer"}[args.launches],
-                   "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": launches_per_step},
+                   "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": round(launches_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": "iflow::q3h_gemv_kernel<1, 2>", "avg_launch_us": round(us_per_launch, 3),

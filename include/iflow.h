@@ -135,9 +135,9 @@ iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *c
  * bound (tens of milliseconds); the launch then still ends, the outputs are unspecified, and the workspace records
  * it.  iflow_qgemv_chain_check() synchronises the stream and returns IFLOW_ERR_TIMEOUT in that case (the record
  * stays until the workspace is zeroed again), IFLOW_OK otherwise. */
-#define IFLOW_CHAIN_MAX_PHASES 8
+#define IFLOW_CHAIN_MAX_PHASES 32
 #define IFLOW_CHAIN_MAX_GROUP 4
-#define IFLOW_CHAIN_MAX_MATRICES 16
+#define IFLOW_CHAIN_MAX_MATRICES 56
 #define IFLOW_CHAIN_WS_HEADER 4096
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes);
 iflow_status_t iflow_qgemv_chain(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,

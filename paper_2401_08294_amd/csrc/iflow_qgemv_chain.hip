@@ -69,6 +69,7 @@ struct ChainArgs {
     ChainMatrix mat[IFLOW_CHAIN_MAX_MATRICES];
 };
 static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 32, "descriptor sizes");
+static_assert(sizeof(ChainArgs) + 8 <= 4096, "kernel arguments are limited to 4 KiB");
 
 // Position of output r inside a matrix's tagged vector, in 32-bit words.  A consumer thread stages one chunk of 16
 // activations with eight 8-byte loads; the pair (2i, 2i+1) of chunk c of a strip sits at 8-byte word i * 256 + c,

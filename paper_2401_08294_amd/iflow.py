@@ -18,7 +18,7 @@ FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B6
 BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 4.0}
 
 OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE, ERR_TIMEOUT = range(8)
-CHAIN_MAX_PHASES, CHAIN_MAX_MATRICES = 8, 16
+CHAIN_MAX_PHASES, CHAIN_MAX_MATRICES = 32, 56
 
 
 class IflowError(RuntimeError):

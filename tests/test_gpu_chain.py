@@ -90,6 +90,23 @@ def test_chain_single_phase_is_qgemv(gpu, orc):
     check_phases(torch, iflow, orc, phases, host, "single")
 
 
+def test_chain_of_32_phases_many_launches(gpu, orc):
+    """The longest chain the entry point takes, each phase feeding the next, launched many times in a row."""
+    torch, iflow = gpu
+    say("[case] chain of 32 dependent phases, 512 <-> 320 columns, 40 launches")
+    spec = [(512, None, [320])]
+    for p in range(1, 32):
+        spec.append((320, (p - 1, 0), [512]) if p % 2 else (512, (p - 1, 0), [320]))
+    phases, host, ws, nbytes = build_chain(torch, iflow, spec, synth.BASE_SEED + 700, sigma=0.05)
+    for it in range(40):
+        iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
+    iflow.qgemv_chain_check(ws)
+    check_phases(torch, iflow, orc, phases, host, "after 40 launches")
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.qgemv_chain(iflow.Q3H_B64, phases + [phases[0]], ws, nbytes)
+    assert ei.value.status == iflow.ERR_SHAPE
+
+
 def layer_spec(hidden, ffn):
     return [(hidden, None, [hidden, hidden, hidden]), (hidden, (0, 0), [hidden]),
             (hidden, (1, 0), [ffn, ffn]), (ffn, (2, 0), [hidden])]
