@@ -150,11 +150,11 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
         w.d[0] = c0.x; w.d[1] = c0.y; w.d[2] = c0.z; w.d[3] = c0.w;
         w.d[4] = c1.x; w.d[5] = c1.y; w.d[6] = c1.z; w.d[7] = c1.w;
         if (have) {
-            lt = IFLOW_UNI(lt + 1);
-            if (lt == l_nstrips) { lt = 0; li = IFLOW_UNI(li + 1); }
+            lt += 1;
+            if (lt == l_nstrips) { lt = 0; li += 1; }
         }
         if (lp < a.nphases) {
-            lj = IFLOW_UNI(lj + 1);
+            lj += 1;
             if (lj == l_pad) enter_phase();
         }
     };
@@ -332,8 +332,8 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 }
                 // (plain selects: written as stores under branches, these end up in scratch memory)
                 part = last ? 0.f : (real ? v : part);
-                i = IFLOW_UNI(i + (last ? 1 : 0));
-                t = IFLOW_UNI(last ? 0 : t + (real ? 1 : 0));
+                i += last ? 1 : 0;
+                t = last ? 0 : t + (real ? 1 : 0);
             };
 #pragma unroll 1
             for (int j = 0; j < nreal; j += S) {
