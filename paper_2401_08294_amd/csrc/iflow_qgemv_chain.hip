@@ -80,10 +80,25 @@ __device__ __forceinline__ int chain_tag_word(int r)
     return 2 * ((g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255)) + (r & 1);
 }
 
-// Wave-uniform values are pinned to scalar registers explicitly: the cursor below is updated under (uniform) control
-// flow deep inside the step loop, and whatever the compiler cannot prove uniform there becomes vector loads of the
-// kernel arguments.
+// The step loop is bound by instruction issue (one scalar unit serves the sixteen wavefronts of a compute unit), so
+// the bookkeeping of a step is kept to a handful of scalar instructions: a wavefront walks its rows segment by
+// segment, a segment being consecutive rows of the wavefront (16 apart) inside one matrix and one 4096-row strip of
+// its tagged output, so that within a segment every pointer advances by a constant.  Everything else (finding the
+// matrix of a row, entering a phase) happens once per segment.  The walk exists twice: for the requests, S steps
+// ahead, and for the consumption.
 #define IFLOW_UNI(v) __builtin_amdgcn_readfirstlane(v)
+
+struct ChainWalk {
+    int p;                      // phase; nphases when the walk is over
+    int rows_left;              // rows of this wavefront in phase p that no segment covers yet
+    int R;                      // the first of them, in the phase's row space
+    int seg_left;               // rows left in the current segment, the current one included
+    int first, ms1, ms2, ms3;   // matrices of the phase (see ChainPhase)
+    int nbk, nstrips, nlast;    // blocks per row, strips per row, blocks in the last strip
+    const uint8_t *wptr;        // weights of the current row (requests: of its current strip)
+    uint16_t *yptr;             // output of the current row
+    uint32_t *tptr;             // tagged output of the current row
+};
 
 template <int S>
 __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint32_t *__restrict__ ws)
@@ -91,71 +106,95 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
     extern __shared__ __align__(16) uint8_t xs[];
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = IFLOW_UNI(tid >> 6);
     const int wg = blockIdx.x;
+    const int nphases = a.nphases;
 
-    // ---- weight requests: a cursor over this wavefront's steps of all phases, all of it in scalar registers -----
+    // rows of this wavefront in a phase: first row of the workgroup, number of rows of the wavefront
+    auto phase_rows = [&](int rows_per_wg, int total, int &rbeg, int &nrows) {
+        rbeg = wg * rows_per_wg;
+        const int rend = min(rbeg + rows_per_wg, total);
+        nrows = max(0, (rend - rbeg - wave + CHAIN_WAVES - 1) / CHAIN_WAVES);
+    };
+    auto walk_phase = [&](ChainWalk &k, int p) {               // phase constants; k.rows_left / k.R are set by the caller
+        const ChainPhase ph = a.ph[p];
+        k.p = p; k.first = ph.first; k.ms1 = ph.mstart[1]; k.ms2 = ph.mstart[2]; k.ms3 = ph.mstart[3];
+        k.nbk = ph.nbk; k.nstrips = ph.nstrips; k.nlast = ph.nbk - (ph.nstrips - 1) * 64;
+    };
+    auto walk_segment = [&](ChainWalk &k) {                    // the segment that starts at row k.R (k.rows_left > 0)
+        const int m = k.first + (k.R >= k.ms1) + (k.R >= k.ms2) + (k.R >= k.ms3);
+        const ChainMatrix mt = a.mat[m];
+        const int r = k.R - mt.start;
+        const int n = min(k.rows_left, min((mt.rows - r + CHAIN_WAVES - 1) / CHAIN_WAVES,
+                                           (4096 - (r & 4095) + CHAIN_WAVES - 1) / CHAIN_WAVES));
+        k.wptr = mt.packed + (int64_t)r * ((int64_t)k.nbk * 32);
+        k.yptr = mt.y + r;
+        k.tptr = ws + mt.tag_word + chain_tag_word(r);
+        k.seg_left = n; k.rows_left -= n; k.R += n * CHAIN_WAVES;
+    };
+
+    // ---- requests ------------------------------------------------------------------------------------------------
     // Per phase the steps of a wavefront are padded to a multiple of S with empty steps, so that step k of the whole
     // sequence always lives in register set k mod S and the step loop can be unrolled by S with fixed registers
     // (one copy of the loop per starting register set is more than the compiler's register allocation copes with).
-    // (Control flow here is kept single-exit on purpose: it stays wave-uniform only as long as the compiler sees that.)
-    int lp = -1, lj = 0, l_real = 0, l_pad = 0, li = 0, lt = 0, l_nstrips = 1, l_nbk = 0, l_row0 = 0, l_first = 0;
-    int l_ms1 = 0x7FFFFFFF, l_ms2 = 0x7FFFFFFF, l_ms3 = 0x7FFFFFFF;
-    int lm_lo = 0, lm_hi = 0;                                  // rows [lm_lo, lm_hi) of the phase belong to the matrix at lm_pk:
-    const uint8_t *lm_pk = a.mat[0].packed;                    // looked up again only when the cursor leaves that range
-    auto phase_steps = [&](const ChainPhase &ph, int &rbeg, int &nrows) {     // rows of this wavefront in a phase
-        rbeg = IFLOW_UNI(wg * ph.rows_per_wg);
-        const int rend = min(rbeg + ph.rows_per_wg, ph.total);
-        nrows = IFLOW_UNI(max(0, (rend - rbeg - wave + CHAIN_WAVES - 1) / CHAIN_WAVES));
-    };
-    auto enter_phase = [&]() {                                 // advance lp to the next phase in which this wavefront has rows
-        bool found = false;
-        do {
-            lp = IFLOW_UNI(lp + 1);
-            if (lp < a.nphases) {
-                const ChainPhase ph = a.ph[lp];
-                int rbeg, nrows;
-                phase_steps(ph, rbeg, nrows);
-                if (nrows > 0) {
-                    found = true;
-                    l_nstrips = IFLOW_UNI(ph.nstrips); l_nbk = IFLOW_UNI(ph.nbk); l_row0 = IFLOW_UNI(rbeg + wave);
-                    l_first = IFLOW_UNI(ph.first);
-                    l_ms1 = IFLOW_UNI(ph.mstart[1]); l_ms2 = IFLOW_UNI(ph.mstart[2]); l_ms3 = IFLOW_UNI(ph.mstart[3]);
-                    l_real = IFLOW_UNI(nrows * l_nstrips); l_pad = IFLOW_UNI((l_real + S - 1) / S * S);
-                    lj = 0; li = 0; lt = 0; lm_lo = 0; lm_hi = 0;
+    // The two loads of a step are issued unconditionally: an empty step is a segment of its own whose lanes all read
+    // the first 16 bytes of the workspace.  With the same number of loads on every path the compiler can tell exactly
+    // how many younger loads may still be in flight when a register set is decoded, instead of waiting for all.
+    ChainWalk q = {};
+    q.p = -1;
+    int q_lt = 0, q_pad = 0;                                   // strip of the current row; empty steps still owed by phase q.p
+    uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
+    const uint32_t voff_full = (uint32_t)lane * 16;
+    auto request_segment = [&]() {                             // q.seg_left == 0: find what the requests do next
+        if (q.rows_left > 0) {
+            walk_segment(q);
+        } else if (q_pad > 0) {                                // the phase's empty steps: one "row" of one empty strip each
+            q.wptr = reinterpret_cast<const uint8_t *>(ws);
+            q.nstrips = 1; q.nlast = 0; q.nbk = 0; q_voff_last = 0;
+            q.seg_left = q_pad; q_pad = 0;
+        } else {
+            bool found = false;
+            do {                                               // the next phase in which this wavefront has rows
+                const int p = q.p + 1;
+                q.p = p;
+                if (p < nphases) {
+                    int rbeg, n;
+                    phase_rows(a.ph[p].rows_per_wg, a.ph[p].total, rbeg, n);
+                    if (n > 0) {
+                        walk_phase(q, p);
+                        q.rows_left = n; q.R = rbeg + wave;
+                        const int real = n * q.nstrips;
+                        q_pad = (real + S - 1) / S * S - real;
+                        q_voff_last = voff_full & mask_lt(lane, q.nlast);      // lanes past a ragged end redo block 0
+                        walk_segment(q);
+                        found = true;
+                    }
                 }
+            } while (!found && q.p < nphases);
+            if (!found) {                                      // the walk is over: empty steps from here on
+                q.wptr = reinterpret_cast<const uint8_t *>(ws);
+                q.nstrips = 1; q.nlast = 0; q.nbk = 0; q_voff_last = 0;
+                q.seg_left = 0x7FFFFFFF;
             }
-        } while (!found && lp < a.nphases);
-    };
-    // The two loads of a step are issued unconditionally, empty steps included (all lanes then read the first 16
-    // bytes of the first matrix): with the same number of loads on every path the compiler can tell exactly how
-    // many younger loads may still be in flight when a register set is decoded, instead of waiting for all of them.
-    auto request = [&](WRegs<KIND_Q3H> &w) {                   // request the step under the cursor, then advance it
-        const bool have = lp < a.nphases && lj < l_real;
-        const uint8_t *p0 = a.mat[0].packed;
-        int n_t = 0;
-        if (have) {
-            const int R = IFLOW_UNI(l_row0 + li * CHAIN_WAVES);
-            if (R >= lm_hi) {                                  // which matrix of the phase the row belongs to
-                const int m = IFLOW_UNI(l_first + (R >= l_ms1) + (R >= l_ms2) + (R >= l_ms3));
-                const ChainMatrix mt = a.mat[m];
-                lm_lo = IFLOW_UNI(mt.start); lm_hi = IFLOW_UNI(lm_lo + mt.rows); lm_pk = mt.packed;
-            }
-            n_t = min(64, l_nbk - lt * 64);
-            p0 = lm_pk + (int64_t)(R - lm_lo) * ((int64_t)l_nbk * 32) + (int64_t)lt * 2048;
         }
-        const uint32_t lane_off = (uint32_t)(lane * 16) & mask_lt(lane, n_t);   // lanes past a ragged end redo block 0
-        const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + lane_off));
-        const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + n_t * 16 + lane_off));
+        q_lt = 0;
+    };
+    auto request = [&](WRegs<KIND_Q3H> &w) {                   // request the step under the cursor, then advance it
+        const bool last_strip = q_lt == q.nstrips - 1;
+        const int n_t = last_strip ? q.nlast : 64;
+        const uint32_t voff = last_strip ? q_voff_last : voff_full;
+        const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q.wptr + voff));
+        const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q.wptr + n_t * 16 + voff));
         w.d[0] = c0.x; w.d[1] = c0.y; w.d[2] = c0.z; w.d[3] = c0.w;
         w.d[4] = c1.x; w.d[5] = c1.y; w.d[6] = c1.z; w.d[7] = c1.w;
-        if (have) {
-            lt += 1;
-            if (lt == l_nstrips) { lt = 0; li += 1; }
-        }
-        if (lp < a.nphases) {
-            lj += 1;
-            if (lj == l_pad) enter_phase();
+        if (last_strip) {                                      // on to the wavefront's next row
+            q.wptr += (int64_t)(CHAIN_WAVES * q.nbk - (q.nstrips - 1) * 64) * 32;
+            q_lt = 0;
+            q.seg_left -= 1;
+            if (q.seg_left == 0) request_segment();
+        } else {
+            q.wptr += 2048;
+            q_lt += 1;
         }
     };
 
@@ -209,7 +248,7 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
         const int nchunks0 = wg_has0 ? ph0.nstrips * 256 : 0;
         const uint4 *src0 = chunk_src(ph0.x, tid & (int)mask_lt(tid, nchunks0), ph0.nbk);   // threads without a chunk read chunk 0
         const uint4 xq0 = src0[0], xq1 = src0[1];
-        enter_phase();
+        request_segment();
 #pragma unroll
         for (int j = 0; j < S; ++j) request(w[j]);
         // (whole wavefronts have a chunk or not: loop bounds and conditions are written on the wavefront's first chunk)
@@ -226,12 +265,19 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
 
     bool failed = false;
     XRegs<KIND_Q3H> xr[1];
-    for (int p = 0; p < a.nphases; p = IFLOW_UNI(p + 1)) {
+    ChainWalk c = {};
+    for (int p = 0; p < nphases; ++p) {
         const ChainPhase ph = a.ph[p];
-        const int nbk = IFLOW_UNI(ph.nbk), nstrips = IFLOW_UNI(ph.nstrips);
+        const int nbk = ph.nbk, nstrips = ph.nstrips;
         int rbeg, n;                                           // first row of the workgroup, rows of this wavefront
-        phase_steps(ph, rbeg, n);
+        phase_rows(ph.rows_per_wg, ph.total, rbeg, n);
         if (rbeg < ph.total) {                                 // else: no rows for this workgroup (uniform over the workgroup)
+            // 0. where this wavefront's outputs go: looked up before the wait for the activations, not after it
+            if (n > 0) {
+                walk_phase(c, p);
+                c.rows_left = n; c.R = rbeg + wave;
+                walk_segment(c);
+            }
             // 1. stage the activations (those of the first phase are already on their way)
             const int nchunks = nstrips * 256;
             if (p > 0 && ph.x_src < 0) {
@@ -244,10 +290,10 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + ph.x_tag_word);
 #pragma unroll 1
                 for (int cw = wave * 64; cw < nchunks; cw += 1024) {
-                    const int c = cw + lane;
+                    const int ch = cw + lane;
                     // chunks past the end of the row were never written: their lanes read chunk 0 and ignore it
-                    const bool live = chunk_live(c, nbk) != 0;
-                    const uint64_t *src = base + (c >> 8) * 2048 + (live ? (c & 255) : 0);
+                    const bool live = chunk_live(ch, nbk) != 0;
+                    const uint64_t *src = base + (ch >> 8) * 2048 + (live ? (ch & 255) : 0);
                     uint32_t n8[8];
                     int budget = failed ? 1 : CHAIN_POLL_BUDGET;
                     bool again;                                // the wavefront re-reads as long as any of its lanes has to
@@ -265,7 +311,7 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                         }
                         again = __builtin_amdgcn_ballot_w64(live && !ok) != 0;
                         if (again) {
-                            budget = IFLOW_UNI(budget - 1);
+                            budget -= 1;
                             if (budget <= 0) {
                                 failed = true;
                                 again = false;
@@ -278,7 +324,7 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                     if (!live)
 #pragma unroll
                         for (int i = 0; i < 8; ++i) n8[i] = 0;
-                    chunk_put(c, n8);
+                    chunk_put(ch, n8);
                 }
             }
             __syncthreads();
@@ -288,19 +334,17 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 const uint8_t *sl = xs + (size_t)ts * CHAIN_SLOT_BYTES;
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) {
-                    const uint4 q = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
-                    xr[0].v[4 * jj] = as_h2(q.x); xr[0].v[4 * jj + 1] = as_h2(q.y);
-                    xr[0].v[4 * jj + 2] = as_h2(q.z); xr[0].v[4 * jj + 3] = as_h2(q.w);
+                    const uint4 qv = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
+                    xr[0].v[4 * jj] = as_h2(qv.x); xr[0].v[4 * jj + 1] = as_h2(qv.y);
+                    xr[0].v[4 * jj + 2] = as_h2(qv.z); xr[0].v[4 * jj + 3] = as_h2(qv.w);
                 }
                 const float2 sm = *reinterpret_cast<const float2 *>(sl + 8 * 64 * 16 + lane * 8);
                 xr[0].bias_sum = sm.x; xr[0].x_sum = sm.y;
             };
             if (nstrips == 1 && n > 0) load_xr(0);             // a single strip stays in registers for all rows
             float part = 0.f;                                  // per-lane partial sum of the current row, carried across strips
-            const int nreal = IFLOW_UNI(n * nstrips);
-            int i = 0, t = 0;
-            int cm_lo = 0, cm_hi = 0, cm_tw = 0;               // the matrix that the finished rows belong to, as for the requests
-            uint16_t *cm_y = a.mat[0].y;
+            const int nreal = n * nstrips;
+            int t = 0;
             auto body = [&](auto stage, int j) {
                 constexpr int st = decltype(stage)::value;
                 const bool real = j < nreal;                   // an empty step only passes its register set on
@@ -316,23 +360,17 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 const bool last = real && t == nstrips - 1;    // the row is complete: one reduction, lane 63 publishes it
                 if (last) {
                     const float sum = wave_sum_to_lane63(v);
-                    const int R = IFLOW_UNI(rbeg + wave + i * CHAIN_WAVES);
-                    if (R >= cm_hi) {
-                        const int m = IFLOW_UNI(ph.first + (R >= ph.mstart[1]) + (R >= ph.mstart[2]) + (R >= ph.mstart[3]));
-                        const ChainMatrix mt = a.mat[m];
-                        cm_lo = IFLOW_UNI(mt.start); cm_hi = IFLOW_UNI(cm_lo + mt.rows); cm_tw = IFLOW_UNI(mt.tag_word); cm_y = mt.y;
-                    }
-                    const int r = R - cm_lo, tw = cm_tw;
-                    uint16_t *yp = cm_y;
                     if (lane == 63) {
                         const uint32_t h = as_u16((half_t)sum);
-                        yp[r] = (uint16_t)h;                   // the caller's plain fp16 output
-                        __hip_atomic_store(ws + tw + chain_tag_word(r), h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        *c.yptr = (uint16_t)h;                 // the caller's plain fp16 output
+                        __hip_atomic_store(c.tptr, h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
+                    c.yptr += CHAIN_WAVES; c.tptr += 2;                // 16 rows on: eight pairs on, i.e. the next 8-byte word of the pair
+                    c.seg_left -= 1;
+                    if (c.seg_left == 0 && c.rows_left > 0) walk_segment(c);
                 }
                 // (plain selects: written as stores under branches, these end up in scratch memory)
                 part = last ? 0.f : (real ? v : part);
-                i += last ? 1 : 0;
                 t = last ? 0 : t + (real ? 1 : 0);
             };
 #pragma unroll 1
