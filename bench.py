@@ -253,7 +253,7 @@ def main():
     }
     if args.launches == 1:
         iflow.qgemv_chain_check(chain_ws, stream=raw)          # raises if a phase ever gave up waiting for its input
-        out["roofline"]["kernel"] = "iflow::q3h_chain_kernel"
+        out["roofline"]["kernel"] = "iflow::q3h_chain_kernel<2>"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.format)
     print(json.dumps(out))
