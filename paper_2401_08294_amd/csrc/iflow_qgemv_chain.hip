@@ -88,16 +88,14 @@ __device__ __forceinline__ int chain_tag_word(int r)
 // ahead, and for the consumption.
 #define IFLOW_UNI(v) __builtin_amdgcn_readfirstlane(v)
 
+// What a walk keeps in registers is only what a step needs; everything a segment change needs (which matrices the
+// phase has, where they start) is read again from the kernel arguments then, to keep the scalar register file for the
+// loop itself.
 struct ChainWalk {
     int p;                      // phase; nphases when the walk is over
     int rows_left;              // rows of this wavefront in phase p that no segment covers yet
     int R;                      // the first of them, in the phase's row space
     int seg_left;               // rows left in the current segment, the current one included
-    int first, ms1, ms2, ms3;   // matrices of the phase (see ChainPhase)
-    int nbk, nstrips, nlast;    // blocks per row, strips per row, blocks in the last strip
-    const uint8_t *wptr;        // weights of the current row (requests: of its current strip)
-    uint16_t *yptr;             // output of the current row
-    uint32_t *tptr;             // tagged output of the current row
 };
 
 template <int S>
@@ -116,20 +114,13 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
         const int rend = min(rbeg + rows_per_wg, total);
         nrows = max(0, (rend - rbeg - wave + CHAIN_WAVES - 1) / CHAIN_WAVES);
     };
-    auto walk_phase = [&](ChainWalk &k, int p) {               // phase constants; k.rows_left / k.R are set by the caller
-        const ChainPhase ph = a.ph[p];
-        k.p = p; k.first = ph.first; k.ms1 = ph.mstart[1]; k.ms2 = ph.mstart[2]; k.ms3 = ph.mstart[3];
-        k.nbk = ph.nbk; k.nstrips = ph.nstrips; k.nlast = ph.nbk - (ph.nstrips - 1) * 64;
-    };
-    auto walk_segment = [&](ChainWalk &k) {                    // the segment that starts at row k.R (k.rows_left > 0)
-        const int m = k.first + (k.R >= k.ms1) + (k.R >= k.ms2) + (k.R >= k.ms3);
-        const ChainMatrix mt = a.mat[m];
-        const int r = k.R - mt.start;
-        const int n = min(k.rows_left, min((mt.rows - r + CHAIN_WAVES - 1) / CHAIN_WAVES,
+    // the segment that starts at row k.R of phase k.p (k.rows_left > 0): its matrix, the row inside it, its length
+    auto walk_segment = [&](ChainWalk &k, int &m, int &r) {
+        const ChainPhase &ph = a.ph[k.p];
+        m = ph.first + (k.R >= ph.mstart[1]) + (k.R >= ph.mstart[2]) + (k.R >= ph.mstart[3]);
+        r = k.R - a.mat[m].start;
+        const int n = min(k.rows_left, min((a.mat[m].rows - r + CHAIN_WAVES - 1) / CHAIN_WAVES,
                                            (4096 - (r & 4095) + CHAIN_WAVES - 1) / CHAIN_WAVES));
-        k.wptr = mt.packed + (int64_t)r * ((int64_t)k.nbk * 32);
-        k.yptr = mt.y + r;
-        k.tptr = ws + mt.tag_word + chain_tag_word(r);
         k.seg_left = n; k.rows_left -= n; k.R += n * CHAIN_WAVES;
     };
 
@@ -140,61 +131,65 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
     // The two loads of a step are issued unconditionally: an empty step is a segment of its own whose lanes all read
     // the first 16 bytes of the workspace.  With the same number of loads on every path the compiler can tell exactly
     // how many younger loads may still be in flight when a register set is decoded, instead of waiting for all.
-    ChainWalk q = {};
-    q.p = -1;
-    int q_lt = 0, q_pad = 0;                                   // strip of the current row; empty steps still owed by phase q.p
+    ChainWalk q = {-1, 0, 0, 0};
+    const uint8_t *q_wptr = reinterpret_cast<const uint8_t *>(ws);     // weights of the step under the cursor
+    int q_lt = 0, q_last = 0;                                  // its strip; the last strip of a row
+    int q_nlast16 = 0;                                         // 16 x the blocks in that last strip (offset of its second plane)
+    int q_rowjump = 0;                                         // from the last strip of a row to the wavefront's next row, bytes
+    int q_pad = 0;                                             // empty steps still owed by phase q.p
     uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
     const uint32_t voff_full = (uint32_t)lane * 16;
+    auto request_empty = [&](int count) {                      // `count` empty steps: one "row" of one empty strip each
+        q_wptr = reinterpret_cast<const uint8_t *>(ws);
+        q_last = 0; q_nlast16 = 0; q_rowjump = 0; q_voff_last = 0;
+        q.seg_left = count;
+    };
     auto request_segment = [&]() {                             // q.seg_left == 0: find what the requests do next
-        if (q.rows_left > 0) {
-            walk_segment(q);
-        } else if (q_pad > 0) {                                // the phase's empty steps: one "row" of one empty strip each
-            q.wptr = reinterpret_cast<const uint8_t *>(ws);
-            q.nstrips = 1; q.nlast = 0; q.nbk = 0; q_voff_last = 0;
-            q.seg_left = q_pad; q_pad = 0;
-        } else {
-            bool found = false;
-            do {                                               // the next phase in which this wavefront has rows
-                const int p = q.p + 1;
-                q.p = p;
-                if (p < nphases) {
+        bool found = false;
+        if (q.rows_left == 0 && q_pad > 0) {
+            request_empty(q_pad);
+            q_pad = 0;
+            found = true;
+        }
+        while (!found && q.p < nphases) {
+            if (q.rows_left == 0) {                            // the next phase in which this wavefront has rows
+                q.p += 1;
+                if (q.p < nphases) {
                     int rbeg, n;
-                    phase_rows(a.ph[p].rows_per_wg, a.ph[p].total, rbeg, n);
-                    if (n > 0) {
-                        walk_phase(q, p);
-                        q.rows_left = n; q.R = rbeg + wave;
-                        const int real = n * q.nstrips;
-                        q_pad = (real + S - 1) / S * S - real;
-                        q_voff_last = voff_full & mask_lt(lane, q.nlast);      // lanes past a ragged end redo block 0
-                        walk_segment(q);
-                        found = true;
-                    }
+                    phase_rows(a.ph[q.p].rows_per_wg, a.ph[q.p].total, rbeg, n);
+                    q.rows_left = n; q.R = rbeg + wave;
+                    const int real = n * a.ph[q.p].nstrips;
+                    q_pad = (real + S - 1) / S * S - real;
                 }
-            } while (!found && q.p < nphases);
-            if (!found) {                                      // the walk is over: empty steps from here on
-                q.wptr = reinterpret_cast<const uint8_t *>(ws);
-                q.nstrips = 1; q.nlast = 0; q.nbk = 0; q_voff_last = 0;
-                q.seg_left = 0x7FFFFFFF;
+            }
+            if (q.p < nphases && q.rows_left > 0) {
+                const ChainPhase &ph = a.ph[q.p];
+                int m, r;
+                walk_segment(q, m, r);
+                const int nlast = ph.nbk - (ph.nstrips - 1) * 64;
+                q_wptr = a.mat[m].packed + (int64_t)r * ((int64_t)ph.nbk * 32);
+                q_last = ph.nstrips - 1; q_nlast16 = nlast * 16;
+                q_rowjump = (CHAIN_WAVES * ph.nbk - (ph.nstrips - 1) * 64) * 32;
+                q_voff_last = voff_full & mask_lt(lane, nlast);                // lanes past a ragged end redo block 0
+                found = true;
             }
         }
+        if (!found) request_empty(0x7FFFFFFF);                 // the walk is over: empty steps from here on
         q_lt = 0;
     };
     auto request = [&](WRegs<KIND_Q3H> &w) {                   // request the step under the cursor, then advance it
-        const bool last_strip = q_lt == q.nstrips - 1;
-        const int n_t = last_strip ? q.nlast : 64;
+        const bool last_strip = q_lt == q_last;
+        const int plane2 = last_strip ? q_nlast16 : 1024;
         const uint32_t voff = last_strip ? q_voff_last : voff_full;
-        const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q.wptr + voff));
-        const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q.wptr + n_t * 16 + voff));
+        const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q_wptr + voff));
+        const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q_wptr + plane2 + voff));
         w.d[0] = c0.x; w.d[1] = c0.y; w.d[2] = c0.z; w.d[3] = c0.w;
         w.d[4] = c1.x; w.d[5] = c1.y; w.d[6] = c1.z; w.d[7] = c1.w;
+        q_wptr += last_strip ? q_rowjump : 2048;
+        q_lt = last_strip ? 0 : q_lt + 1;
         if (last_strip) {                                      // on to the wavefront's next row
-            q.wptr += (int64_t)(CHAIN_WAVES * q.nbk - (q.nstrips - 1) * 64) * 32;
-            q_lt = 0;
             q.seg_left -= 1;
             if (q.seg_left == 0) request_segment();
-        } else {
-            q.wptr += 2048;
-            q_lt += 1;
         }
     };
 
@@ -265,7 +260,15 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
 
     bool failed = false;
     XRegs<KIND_Q3H> xr[1];
-    ChainWalk c = {};
+    ChainWalk c = {0, 0, 0, 0};
+    uint16_t *c_yptr = nullptr;                                // output and tagged output of the row being summed
+    uint32_t *c_tptr = nullptr;
+    auto consume_segment = [&]() {
+        int m, r;
+        walk_segment(c, m, r);
+        c_yptr = a.mat[m].y + r;
+        c_tptr = ws + a.mat[m].tag_word + chain_tag_word(r);
+    };
     for (int p = 0; p < nphases; ++p) {
         const ChainPhase ph = a.ph[p];
         const int nbk = ph.nbk, nstrips = ph.nstrips;
@@ -274,9 +277,8 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
         if (rbeg < ph.total) {                                 // else: no rows for this workgroup (uniform over the workgroup)
             // 0. where this wavefront's outputs go: looked up before the wait for the activations, not after it
             if (n > 0) {
-                walk_phase(c, p);
-                c.rows_left = n; c.R = rbeg + wave;
-                walk_segment(c);
+                c.p = p; c.rows_left = n; c.R = rbeg + wave;
+                consume_segment();
             }
             // 1. stage the activations (those of the first phase are already on their way)
             const int nchunks = nstrips * 256;
@@ -362,12 +364,12 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                     const float sum = wave_sum_to_lane63(v);
                     if (lane == 63) {
                         const uint32_t h = as_u16((half_t)sum);
-                        *c.yptr = (uint16_t)h;                 // the caller's plain fp16 output
-                        __hip_atomic_store(c.tptr, h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        *c_yptr = (uint16_t)h;                 // the caller's plain fp16 output
+                        __hip_atomic_store(c_tptr, h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
-                    c.yptr += CHAIN_WAVES; c.tptr += 2;                // 16 rows on: eight pairs on, i.e. the next 8-byte word of the pair
+                    c_yptr += CHAIN_WAVES; c_tptr += 2;        // 16 rows on: eight pairs on, i.e. the next 8-byte word of the pair
                     c.seg_left -= 1;
-                    if (c.seg_left == 0 && c.rows_left > 0) walk_segment(c);
+                    if (c.seg_left == 0 && c.rows_left > 0) consume_segment();
                 }
                 // (plain selects: written as stores under branches, these end up in scratch memory)
                 part = last ? 0.f : (real ? v : part);
