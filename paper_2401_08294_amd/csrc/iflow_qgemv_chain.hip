@@ -31,7 +31,8 @@
 
 namespace iflow {
 
-constexpr int CHAIN_WAVES = 16;                                // wavefronts per workgroup
+constexpr int CHAIN_WAVES = 8;                                 // wavefronts per workgroup
+constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;                  // a wavefront takes two rows per step: rows between its steps
 constexpr int CHAIN_SLOT_BYTES = 8 * 64 * 16 + 64 * 8;        // staged activations of one strip (as in q3h_gemv_kernel)
 constexpr int CHAIN_MAX_STRIPS = 16;                           // columns <= 65536
 constexpr int CHAIN_MAX_GROUP = 4;                             // matrices per phase
@@ -99,7 +100,7 @@ struct ChainWalk {
 };
 
 template <int S>
-__global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint32_t *__restrict__ ws)
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const ChainArgs a, uint32_t *__restrict__ ws)
 {
     extern __shared__ __align__(16) uint8_t xs[];
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -108,20 +109,27 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
     const int wg = blockIdx.x;
     const int nphases = a.nphases;
 
-    // rows of this wavefront in a phase: first row of the workgroup, number of rows of the wavefront
+    // A wavefront handles two adjacent rows (2i, 2i+1 of a matrix) per step, so "row" below means such a pair, named
+    // by its even row; in a phase's row space every matrix starts at an even row (odd matrices are padded by one).
+    // pairs of this wavefront in a phase: first row of the workgroup, number of pairs of the wavefront
     auto phase_rows = [&](int rows_per_wg, int total, int &rbeg, int &nrows) {
         rbeg = wg * rows_per_wg;
         const int rend = min(rbeg + rows_per_wg, total);
-        nrows = max(0, (rend - rbeg - wave + CHAIN_WAVES - 1) / CHAIN_WAVES);
+        nrows = max(0, (rend - rbeg - 2 * wave + CHAIN_STRIDE - 1) / CHAIN_STRIDE);
     };
-    // the segment that starts at row k.R of phase k.p (k.rows_left > 0): its matrix, the row inside it, its length
-    auto walk_segment = [&](ChainWalk &k, int &m, int &r) {
+    // the segment that starts at row k.R of phase k.p (k.rows_left > 0): its matrix, the row inside it, its length;
+    // `single`: the segment is the lone last row of a matrix with an odd number of rows (always a segment of its own)
+    auto walk_segment = [&](ChainWalk &k, int &m, int &r, bool &single) {
         const ChainPhase &ph = a.ph[k.p];
         m = ph.first + (k.R >= ph.mstart[1]) + (k.R >= ph.mstart[2]) + (k.R >= ph.mstart[3]);
         r = k.R - a.mat[m].start;
-        const int n = min(k.rows_left, min((a.mat[m].rows - r + CHAIN_WAVES - 1) / CHAIN_WAVES,
-                                           (4096 - (r & 4095) + CHAIN_WAVES - 1) / CHAIN_WAVES));
-        k.seg_left = n; k.rows_left -= n; k.R += n * CHAIN_WAVES;
+        const int rows_m = a.mat[m].rows;
+        int n = min(k.rows_left, min((rows_m - r + CHAIN_STRIDE - 1) / CHAIN_STRIDE,
+                                     (4096 - (r & 4095) + CHAIN_STRIDE - 1) / CHAIN_STRIDE));
+        const bool tail = r + (n - 1) * CHAIN_STRIDE == rows_m - 1;     // the segment would end in the lone row
+        single = tail && n == 1;
+        if (tail && n > 1) n -= 1;
+        k.seg_left = n; k.rows_left -= n; k.R += n * CHAIN_STRIDE;
     };
 
     // ---- requests ------------------------------------------------------------------------------------------------
@@ -136,12 +144,13 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
     int q_lt = 0, q_last = 0;                                  // its strip; the last strip of a row
     int q_nlast16 = 0;                                         // 16 x the blocks in that last strip (offset of its second plane)
     int q_rowjump = 0;                                         // from the last strip of a row to the wavefront's next row, bytes
+    int q_row1 = 0;                                            // from the first to the second row of the pair, bytes (0: no second row)
     int q_pad = 0;                                             // empty steps still owed by phase q.p
     uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
     const uint32_t voff_full = (uint32_t)lane * 16;
     auto request_empty = [&](int count) {                      // `count` empty steps: one "row" of one empty strip each
         q_wptr = reinterpret_cast<const uint8_t *>(ws);
-        q_last = 0; q_nlast16 = 0; q_rowjump = 0; q_voff_last = 0;
+        q_last = 0; q_nlast16 = 0; q_rowjump = 0; q_row1 = 0; q_voff_last = 0;
         q.seg_left = count;
     };
     auto request_segment = [&]() {                             // q.seg_left == 0: find what the requests do next
@@ -157,7 +166,7 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 if (q.p < nphases) {
                     int rbeg, n;
                     phase_rows(a.ph[q.p].rows_per_wg, a.ph[q.p].total, rbeg, n);
-                    q.rows_left = n; q.R = rbeg + wave;
+                    q.rows_left = n; q.R = rbeg + 2 * wave;
                     const int real = n * a.ph[q.p].nstrips;
                     q_pad = (real + S - 1) / S * S - real;
                 }
@@ -165,11 +174,13 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
             if (q.p < nphases && q.rows_left > 0) {
                 const ChainPhase &ph = a.ph[q.p];
                 int m, r;
-                walk_segment(q, m, r);
+                bool single;
+                walk_segment(q, m, r, single);
                 const int nlast = ph.nbk - (ph.nstrips - 1) * 64;
                 q_wptr = a.mat[m].packed + (int64_t)r * ((int64_t)ph.nbk * 32);
                 q_last = ph.nstrips - 1; q_nlast16 = nlast * 16;
-                q_rowjump = (CHAIN_WAVES * ph.nbk - (ph.nstrips - 1) * 64) * 32;
+                q_rowjump = (CHAIN_STRIDE * ph.nbk - (ph.nstrips - 1) * 64) * 32;
+                q_row1 = single ? 0 : ph.nbk * 32;
                 q_voff_last = voff_full & mask_lt(lane, nlast);                // lanes past a ragged end redo block 0
                 found = true;
             }
@@ -177,14 +188,18 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
         if (!found) request_empty(0x7FFFFFFF);                 // the walk is over: empty steps from here on
         q_lt = 0;
     };
-    auto request = [&](WRegs<KIND_Q3H> &w) {                   // request the step under the cursor, then advance it
+    auto request = [&](WRegs<KIND_Q3H> (&w)[2]) {              // request the step under the cursor, then advance it
         const bool last_strip = q_lt == q_last;
         const int plane2 = last_strip ? q_nlast16 : 1024;
         const uint32_t voff = last_strip ? q_voff_last : voff_full;
-        const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q_wptr + voff));
-        const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(q_wptr + plane2 + voff));
-        w.d[0] = c0.x; w.d[1] = c0.y; w.d[2] = c0.z; w.d[3] = c0.w;
-        w.d[4] = c1.x; w.d[5] = c1.y; w.d[6] = c1.z; w.d[7] = c1.w;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint8_t *row = q_wptr + u * q_row1;
+            const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + voff));
+            const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + plane2 + voff));
+            w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
+            w[u].d[4] = c1.x; w[u].d[5] = c1.y; w[u].d[6] = c1.z; w[u].d[7] = c1.w;
+        }
         q_wptr += last_strip ? q_rowjump : 2048;
         q_lt = last_strip ? 0 : q_lt + 1;
         if (last_strip) {                                      // on to the wavefront's next row
@@ -233,7 +248,7 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
     // The first phase's activations are an input of the launch.  Their first chunk is requested BEFORE any weights,
     // because memory requests of a wavefront are served in order and the whole workgroup waits for the staged
     // activations; then S steps of weights; then the chunk is put in place.
-    WRegs<KIND_Q3H> w[S];
+    WRegs<KIND_Q3H> w[S][2];
     // The launch counter, the oldest load of the wavefront (so it never has to be waited for alone).  A plain cached
     // load: the word was last written by the previous launch, and changes again only when this one is over.
     const uint32_t counter = __hip_atomic_load(ws, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -249,7 +264,7 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
         // (whole wavefronts have a chunk or not: loop bounds and conditions are written on the wavefront's first chunk)
         if (wave * 64 < nchunks0) put_plain(tid, ph0.nbk, xq0, xq1);
 #pragma unroll 1
-        for (int cw = wave * 64 + 1024; cw < nchunks0; cw += 1024) {
+        for (int cw = wave * 64 + 64 * CHAIN_WAVES; cw < nchunks0; cw += 64 * CHAIN_WAVES) {
             const uint4 *src = chunk_src(ph0.x, cw + lane, ph0.nbk);
             put_plain(cw + lane, ph0.nbk, src[0], src[1]);
         }
@@ -260,38 +275,44 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
 
     bool failed = false;
     XRegs<KIND_Q3H> xr[1];
-    ChainWalk c = {0, 0, 0, 0};
-    uint16_t *c_yptr = nullptr;                                // output and tagged output of the row being summed
-    uint32_t *c_tptr = nullptr;
-    auto consume_segment = [&]() {
-        int m, r;
-        walk_segment(c, m, r);
-        c_yptr = a.mat[m].y + r;
-        c_tptr = ws + a.mat[m].tag_word + chain_tag_word(r);
-    };
+    // Results are not stored row by row: lane 63's sums of the wavefront's i-th pair of rows are parked in lane i of two
+    // registers, and when the phase's steps are done lanes 0..n-1 store them all at once - two store instructions
+    // per wavefront and phase instead of two per row (in-order completion means every later load of the wavefront would
+    // otherwise queue behind a write-through store), and no output pointers to advance inside the step loop.
     for (int p = 0; p < nphases; ++p) {
         const ChainPhase ph = a.ph[p];
         const int nbk = ph.nbk, nstrips = ph.nstrips;
         int rbeg, n;                                           // first row of the workgroup, rows of this wavefront
         phase_rows(ph.rows_per_wg, ph.total, rbeg, n);
         if (rbeg < ph.total) {                                 // else: no rows for this workgroup (uniform over the workgroup)
-            // 0. where this wavefront's outputs go: looked up before the wait for the activations, not after it
-            if (n > 0) {
-                c.p = p; c.rows_left = n; c.R = rbeg + wave;
-                consume_segment();
+            // 0. where this wavefront's outputs go, lane i for its i-th pair of rows: looked up before the wait for the
+            //    activations, not after it
+            uint16_t *out_y = nullptr;
+            uint32_t *out_t = nullptr;
+            bool out_single = false;                           // the pair is the lone last row of a matrix with an odd row count
+            if (lane < n) {
+                const int R = rbeg + 2 * wave + lane * CHAIN_STRIDE;
+                const int m = ph.first + (R >= ph.mstart[1]) + (R >= ph.mstart[2]) + (R >= ph.mstart[3]);
+                const ChainMatrix mt = a.mat[m];
+                const int r = R - mt.start;
+                out_y = mt.y + r;
+                out_t = ws + mt.tag_word + chain_tag_word(r);
+                out_single = r == mt.rows - 1;
             }
+            float res0 = 0.f, res1 = 0.f;
+            int done = 0;                                      // pairs of rows summed so far
             // 1. stage the activations (those of the first phase are already on their way)
             const int nchunks = nstrips * 256;
             if (p > 0 && ph.x_src < 0) {
 #pragma unroll 1
-                for (int cw = wave * 64; cw < nchunks; cw += 1024) {
+                for (int cw = wave * 64; cw < nchunks; cw += 64 * CHAIN_WAVES) {
                     const uint4 *src = chunk_src(ph.x, cw + lane, nbk);
                     put_plain(cw + lane, nbk, src[0], src[1]);
                 }
             } else if (p > 0) {
                 const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + ph.x_tag_word);
 #pragma unroll 1
-                for (int cw = wave * 64; cw < nchunks; cw += 1024) {
+                for (int cw = wave * 64; cw < nchunks; cw += 64 * CHAIN_WAVES) {
                     const int ch = cw + lane;
                     // chunks past the end of the row were never written: their lanes read chunk 0 and ignore it
                     const bool live = chunk_live(ch, nbk) != 0;
@@ -344,35 +365,37 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 xr[0].bias_sum = sm.x; xr[0].x_sum = sm.y;
             };
             if (nstrips == 1 && n > 0) load_xr(0);             // a single strip stays in registers for all rows
-            float part = 0.f;                                  // per-lane partial sum of the current row, carried across strips
+            float part[2] = {0.f, 0.f};                        // per-lane partial sums of the two rows, carried across strips
             const int nreal = n * nstrips;
             int t = 0;
             auto body = [&](auto stage, int j) {
                 constexpr int st = decltype(stage)::value;
                 const bool real = j < nreal;                   // an empty step only passes its register set on
-                float v = 0.f;
+                float v[2] = {0.f, 0.f};
                 if (real) {
                     if (nstrips > 1) load_xr(t);
-                    float acc[1];
-                    lane_dot<KIND_Q3H, 1>(w[st], xr, acc);
-                    const half2_t so = as_h2(q3h_header(w[st].d));
-                    v = part + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        float acc[1];
+                        lane_dot<KIND_Q3H, 1>(w[st][u], xr, acc);
+                        const half2_t so = as_h2(q3h_header(w[st][u].d));
+                        v[u] = part[u] + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
+                    }
                 }
                 request(w[st]);                                // step j + S of the sequence takes over the register set
-                const bool last = real && t == nstrips - 1;    // the row is complete: one reduction, lane 63 publishes it
+                const bool last = real && t == nstrips - 1;    // the rows are complete: two reductions, lane 63 publishes
                 if (last) {
-                    const float sum = wave_sum_to_lane63(v);
-                    if (lane == 63) {
-                        const uint32_t h = as_u16((half_t)sum);
-                        *c_yptr = (uint16_t)h;                 // the caller's plain fp16 output
-                        __hip_atomic_store(c_tptr, h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                    c_yptr += CHAIN_WAVES; c_tptr += 2;        // 16 rows on: eight pairs on, i.e. the next 8-byte word of the pair
-                    c.seg_left -= 1;
-                    if (c.seg_left == 0 && c.rows_left > 0) consume_segment();
+                    const float sum0 = wave_sum_to_lane63(v[0]), sum1 = wave_sum_to_lane63(v[1]);
+                    // lane `done` of res0 / res1 <- lane 63's sums
+                    const float b0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sum0), 63));
+                    const float b1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sum1), 63));
+                    res0 = lane == done ? b0 : res0;
+                    res1 = lane == done ? b1 : res1;
+                    done += 1;
                 }
                 // (plain selects: written as stores under branches, these end up in scratch memory)
-                part = last ? 0.f : (real ? v : part);
+                part[0] = last ? 0.f : (real ? v[0] : part[0]);
+                part[1] = last ? 0.f : (real ? v[1] : part[1]);
                 t = last ? 0 : t + (real ? 1 : 0);
             };
 #pragma unroll 1
@@ -381,6 +404,18 @@ __global__ __launch_bounds__(1024) void q3h_chain_kernel(const ChainArgs a, uint
                 if constexpr (S > 1) body(std::integral_constant<int, 1>{}, j + 1);
                 if constexpr (S > 2) body(std::integral_constant<int, 2>{}, j + 2);
                 if constexpr (S > 3) body(std::integral_constant<int, 3>{}, j + 3);
+            }
+            // 3. publish: the caller's plain fp16 outputs, and the tagged words for later phases
+            if (lane < n) {
+                const uint32_t h0 = as_u16((half_t)res0), h1 = as_u16((half_t)res1);
+                if (!out_single) {
+                    *reinterpret_cast<uint32_t *>(out_y) = h0 | (h1 << 16);
+                    __hip_atomic_store(reinterpret_cast<uint64_t *>(out_t), (uint64_t)(h0 | tag) | ((uint64_t)(h1 | tag) << 32),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    *out_y = (uint16_t)h0;
+                    __hip_atomic_store(out_t, h0 | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
             __syncthreads();                                   // the staged activations are no longer needed
         }
@@ -457,10 +492,11 @@ hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *col
             a.mat[m].tag_word = (int)word;
             ph.mstart[j] = (int)v;
             word += (size_t)((rows[m] + 4095) / 4096) * 4096;
-            v += rows[m];
+            v += (rows[m] + 1) & ~(int64_t)1;                  // every matrix starts at an even row of the phase's row space
         }
-        const int64_t rpw = (v + grid - 1) / grid;
+        const int64_t rpw = ((v + grid - 1) / grid + 1) & ~(int64_t)1;
         if (v > 0x3FFFFFFF || word > 0x3FFFFFFF) return hipErrorInvalidValue;
+        if (rpw > 64 * CHAIN_STRIDE) return hipErrorInvalidValue;      // a wavefront parks one pair of rows per lane
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
     const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES;
