@@ -107,6 +107,18 @@ def test_chain_of_32_phases_many_launches(gpu, orc):
     assert ei.value.status == iflow.ERR_SHAPE
 
 
+def test_chain_with_the_most_matrices(gpu, orc):
+    """56 matrices in one launch (14 phases of four): every descriptor slot of the kernel's argument block is in use."""
+    torch, iflow = gpu
+    say("[case] chain of 14 phases x 4 matrices, 128x128")
+    spec = [(128, None, [128] * 4)] + [(128, (p - 1, p % 4), [128] * 4) for p in range(1, 14)]
+    phases, host, ws, nbytes = build_chain(torch, iflow, spec, synth.BASE_SEED + 800, sigma=0.08)
+    for it in range(3):
+        iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
+    iflow.qgemv_chain_check(ws)
+    check_phases(torch, iflow, orc, phases, host, "56 matrices")
+
+
 def layer_spec(hidden, ffn):
     return [(hidden, None, [hidden, hidden, hidden]), (hidden, (0, 0), [hidden]),
             (hidden, (1, 0), [ffn, ffn]), (ffn, (2, 0), [hidden])]
