@@ -5,16 +5,17 @@
 // here the grid stays resident, and the weights of the next phase are already on their way while the outputs
 // of the current one are handed over.
 //
-// Resident grid: one workgroup of 16 wavefronts per compute unit.  Each phase's rows are cut into equal
-// contiguous ranges, one per workgroup; wavefront w of a workgroup takes rows w, w + 16, ... of the range and
-// walks each row strip by strip (a strip = 64 blocks = 4096 columns, one block per lane, as in the
-// single-product kernel).  A wavefront keeps S steps (row, strip) of weights in flight in S register sets and
-// requests step k + S as soon as step k is decoded, across phase boundaries: weights do not depend on the
-// activations, so the memory system keeps streaming while a phase waits for its input.
+// Resident grid: one workgroup of 8 wavefronts per compute unit.  Each phase's rows are cut into equal contiguous
+// ranges, one per workgroup; wavefront w of a workgroup takes the row pairs w, w + 8, ... of the range and walks
+// each pair strip by strip (a strip = 64 blocks = 4096 columns, one block per lane, as in the single-product
+// kernel; the two rows of a pair share the activation registers).  A wavefront keeps S steps (row pair, strip) of
+// weights in flight in S register sets and requests step k + S as soon as step k is decoded, across phase
+// boundaries: weights do not depend on the activations, so the memory system keeps streaming while a phase waits
+// for its input.
 //
 // Hand-over without a grid barrier: outputs that a later phase consumes travel through the caller's workspace
-// as 32-bit words (fp16 value, 16-bit tag), written by the lane that holds the row sum with one write-through
-// store and read with cache-bypassing loads.  The tag comes from a launch counter kept in the workspace, so a
+// as 32-bit words (fp16 value, 16-bit tag), written with write-through stores once a wavefront has finished its
+// rows of the phase, and read with cache-bypassing loads.  The tag comes from a launch counter kept in the workspace, so a
 // word is its own "ready" flag: a consumer simply re-reads until every word of the vector carries this launch's
 // tag.  There are no atomics on shared counters and no fences; one memory round trip separates the last producer
 // from the first consumer.  The words are stored in the order in which the consumer's threads want them (below),
@@ -449,7 +450,7 @@ size_t chain_workspace_bytes(int nmatrices, const int64_t *rows)
     return bytes;
 }
 
-// Launch geometry: as many workgroups as the device has compute units (each workgroup fills one: 1024 threads
+// Launch geometry: as many workgroups as the device has compute units (one each: 512 threads
 // and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
 // concurrently.  Returns hipErrorInvalidValue for shapes outside the kernel's limits.
 hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
