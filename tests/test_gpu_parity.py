@@ -124,8 +124,8 @@ def test_ragged_shapes(gpu, orc, name, rows, nblocks):
 
 
 # ---- small batches (2, 3, 4 share a pass; 5 and 16 take several) ----------------------------------------
-@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B64", "Q8_B64"])
-@pytest.mark.parametrize("batch", [2, 3, 4, 5, 8, 16])
+@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("batch", [2, 3, 4, 5, 8, 16, 21])
 def test_small_batch(gpu, orc, name, batch):
     torch, iflow = gpu
     rows, cols = 300, 4096 + 64 * 3
