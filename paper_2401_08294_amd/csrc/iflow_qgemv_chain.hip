@@ -5,8 +5,8 @@
 // here the grid stays resident, and the weights of the next phase are already on their way while the outputs
 // of the current one are handed over.
 //
-// Resident grid: one workgroup of 8 wavefronts per compute unit.  Each phase's rows are cut into equal contiguous
-// ranges, one per workgroup; wavefront w of a workgroup takes the row pairs w, w + 8, ... of the range and walks
+// Resident grid: one workgroup of 12 wavefronts per compute unit.  Each phase's rows are cut into equal contiguous
+// ranges, one per workgroup; wavefront w of a workgroup takes the row pairs w, w + 12, ... of the range and walks
 // each pair strip by strip (a strip = 64 blocks = 4096 columns, one block per lane, as in the single-product
 // kernel; the two rows of a pair share the activation registers).  A wavefront keeps S steps (row pair, strip) of
 // weights in flight in S register sets and requests step k + S as soon as step k is decoded, across phase
@@ -32,7 +32,8 @@
 
 namespace iflow {
 
-constexpr int CHAIN_WAVES = 8;                                 // wavefronts per workgroup
+constexpr int CHAIN_WAVES = 12;                                // wavefronts per workgroup (measured: 8 is 3 % slower, 16 equal;
+                                                               // 12 divides the row pairs of 7B-sized phases evenly)
 constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;                  // a wavefront takes two rows per step: rows between its steps
 constexpr int CHAIN_SLOT_BYTES = 8 * 64 * 16 + 64 * 8;        // staged activations of one strip (as in q3h_gemv_kernel)
 constexpr int CHAIN_MAX_STRIPS = 16;                           // columns <= 65536
@@ -450,7 +451,7 @@ size_t chain_workspace_bytes(int nmatrices, const int64_t *rows)
     return bytes;
 }
 
-// Launch geometry: as many workgroups as the device has compute units (one each: 512 threads
+// Launch geometry: as many workgroups as the device has compute units (one each: 768 threads
 // and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
 // concurrently.  Returns hipErrorInvalidValue for shapes outside the kernel's limits.
 hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
