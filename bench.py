@@ -72,10 +72,35 @@ def cpu_baseline(fmt_name: str, reps: int = 3):
             _, used = oracle.qgemm_canonical(ofmt, rec, rows, cols, x.view(np.uint16), threads=threads)
             total_s += time.perf_counter() - t0
             total_bytes += algorithmic_bytes(rows, cols, bpw)
+    # the same oracle on one thread, one 4096 x 4096 matrix (context for the core count)
+    _, rows, cols = synth.LLAMA2_7B_LAYER[0]
+    w = synth.weights(rows, cols, SIGMA, synth.BASE_SEED + 900)
+    x = synth.activations(1, cols, synth.BASE_SEED + 950)
+    q, s, o = oracle.quantize(ofmt, w)
+    rec = oracle.pack_canonical(ofmt, q, s, o)
+    t0 = time.perf_counter()
+    oracle.qgemm_canonical(ofmt, rec, rows, cols, x.view(np.uint16), threads=1)
+    single = algorithmic_bytes(rows, cols, bpw) / (time.perf_counter() - t0) / 1e9
     return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "single_thread_value": round(single, 4),
             "sample": f"unpack + dequantize + fp64 GEMV of one layer's seven linears, {reps} passes "
                       f"({total_bytes / 1e6:.0f} MB of packed weights in {total_s:.1f} s); the multiply is row-parallel "
                       f"over {used} threads, unpack and dequantize are serial"}
+
+
+def log_environment(torch):
+    """Device, clocks and software versions to stderr (the JSON line on stdout stays alone)."""
+    import subprocess
+    p = torch.cuda.get_device_properties(0)
+    print(f"[bench] device: {p.name}, {p.multi_processor_count} CUs, {p.total_memory / 2**30:.0f} GiB, "
+          f"torch {torch.__version__}, HIP {getattr(torch.version, 'hip', None)}", file=sys.stderr)
+    for cmd in (["rocm-smi", "--showclocks", "--showperflevel", "--showpower"],):
+        try:
+            r = subprocess.run(cmd, capture_output=True, text=True, timeout=20)
+            lines = [l for l in r.stdout.splitlines() if l.strip() and not l.startswith("=")]
+            print("[bench] " + " ".join(cmd) + ":\n" + "\n".join("[bench]   " + l for l in lines[:24]), file=sys.stderr)
+        except Exception as e:  # the tool may be missing or not permitted on the box
+            print(f"[bench] {' '.join(cmd)} not available: {e}", file=sys.stderr)
 
 
 def main():
@@ -213,6 +238,42 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1)
 
+        # spread: every ring trip of a short extra pass timed on its own (the events cost a little, so this pass is
+        # not the headline), and the attainable ceiling: a kernel that only reads the same packed weights
+        spread = None
+        if graph is not None:
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(41)]
+            evs[0].record(stream)
+            for i in range(40):
+                graph.replay()
+                evs[i + 1].record(stream)
+            evs[-1].synchronize()
+            per = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 / args.ring for i in range(40))
+            spread = {"per_layer_us_min": round(per[0], 3), "per_layer_us_median": round(per[len(per) // 2], 3),
+                      "per_layer_us_max": round(per[-1], 3), "ring_trips": 40}
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        def read_ring():
+            for mats in ring:
+                for _, _, packed in mats:
+                    iflow.calibration_read(packed, packed.numel() // 16 * 16, sink, stream=raw)
+        read_ring()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        r0.record(stream)
+        for _ in range(10):
+            read_ring()
+        r1.record(stream)
+        r1.synchronize()
+        read_gbps = 10 * args.ring * sum(p.numel() // 16 * 16 for _, _, p in ring[0]) / (r0.elapsed_time(r1) * 1e-3) / 1e9
+        big = torch.empty(2**30, dtype=torch.uint8, device=dev)          # and one launch over 1 GiB: the asymptote
+        iflow.calibration_read(big, big.numel(), sink, stream=raw)
+        r0.record(stream)
+        for _ in range(5):
+            iflow.calibration_read(big, big.numel(), sink, stream=raw)
+        r1.record(stream)
+        r1.synchronize()
+        read_big_gbps = 5 * big.numel() / (r0.elapsed_time(r1) * 1e-3) / 1e9
+        del big
+
     ms_per_step = ms / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     launches_per_step = launch_count[0] / args.steps            # a chained launch covers several layers (steps)
@@ -251,6 +312,11 @@ def main():
                      "kernel": "iflow::q3h_gemv_kernel<1, 2>", "avg_launch_us": round(us_per_launch, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},
     }
+    out["spread"] = spread
+    out["stream_read_ceiling"] = {"value": round(read_gbps, 1), "unit": "GB/s", "frac_of_peak": round(read_gbps / HBM_PEAK_GBPS, 4),
+                                  "what": "iflow_calibration_read over the same packed matrices, one launch per matrix (7 per layer), eager",
+                                  "one_launch_over_1GiB": round(read_big_gbps, 1)}
+    log_environment(torch)
     if args.launches == 1:
         iflow.qgemv_chain_check(chain_ws, stream=raw)          # raises if a phase ever gave up waiting for its input
         out["roofline"]["kernel"] = "iflow::q3h_chain_kernel<2>"

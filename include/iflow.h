@@ -165,6 +165,13 @@ iflow_status_t iflow_unpack_logical(iflow_format_t format, const void *packed, i
  * exactly known size. */
 iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* Measurement helper (no counterpart in the paper): the loads of iflow_calibration_copy without its stores - a
+ * kernel that only reads `bytes` bytes (a positive multiple of 16) from `src`.  Timed over the packed weights it
+ * gives the rate the memory system delivers to a pure read of them, the ceiling for any kernel that streams them.
+ * `sink` is a device word (16-byte aligned) that is written only for one data pattern that real weights do not
+ * produce; it exists so that the loads are kept. */
+iflow_status_t iflow_calibration_read(const void *src, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -231,6 +231,14 @@ iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, 
     return device_status(iflow::launch_calibration_copy(src, dst, bytes, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_calibration_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink) return IFLOW_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return IFLOW_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(sink)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_calibration_read(src, bytes, sink, (hipStream_t)stream));
+}
+
 iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                            const uint16_t *x, uint16_t *y, void *stream)
 {

@@ -105,6 +105,7 @@ hipError_t launch_dequant(int format, const void *packed, int64_t rows, int64_t 
 hipError_t launch_unpack(int format, const void *packed, int64_t rows, int64_t cols,
                          uint8_t *levels, uint16_t *scale16, uint16_t *offset16, hipStream_t s);
 hipError_t launch_calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
+hipError_t launch_calibration_read(const void *src, size_t bytes, void *sink, hipStream_t s);
 hipError_t launch_qgemv_multi(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols,
                               const uint16_t *x, uint16_t *const *y, hipStream_t s);
 size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);

@@ -55,6 +55,7 @@ def lib():
         L.iflow_qgemm.argtypes = [C.c_int, p, i64, i64, p, i64, p, p]
         L.iflow_unpack_logical.argtypes = [C.c_int, p, i64, i64, p, p, p, p]
         L.iflow_calibration_copy.argtypes = [p, p, sz, p]
+        L.iflow_calibration_read.argtypes = [p, sz, p, p]
         L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
         L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
         L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
@@ -131,6 +132,10 @@ def unpack_logical(fmt: int, packed, rows: int, cols: int, levels, scale16, offs
 
 def calibration_copy(src, dst, nbytes: int, stream=None) -> None:
     _check(lib().iflow_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "iflow_calibration_copy")
+
+
+def calibration_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(lib().iflow_calibration_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "iflow_calibration_read")
 
 
 def qgemv_multi(fmt: int, packed_list, rows_list, cols: int, x, y_list, stream=None) -> None:
