@@ -89,18 +89,25 @@ def cpu_baseline(fmt_name: str, reps: int = 3):
 
 
 def log_environment(torch):
-    """Device, clocks and software versions to stderr (the JSON line on stdout stays alone)."""
-    import subprocess
+    """Device, clocks and software versions to stderr (the JSON line on stdout stays alone).  The clocks come from
+    the driver's sysfs files: a process that holds the GPU starts no other program."""
+    import glob
     p = torch.cuda.get_device_properties(0)
     print(f"[bench] device: {p.name}, {p.multi_processor_count} CUs, {p.total_memory / 2**30:.0f} GiB, "
           f"torch {torch.__version__}, HIP {getattr(torch.version, 'hip', None)}", file=sys.stderr)
-    for cmd in (["rocm-smi", "--showclocks", "--showperflevel", "--showpower"],):
+    for dev in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
         try:
-            r = subprocess.run(cmd, capture_output=True, text=True, timeout=20)
-            lines = [l for l in r.stdout.splitlines() if l.strip() and not l.startswith("=")]
-            print("[bench] " + " ".join(cmd) + ":\n" + "\n".join("[bench]   " + l for l in lines[:24]), file=sys.stderr)
-        except Exception as e:  # the tool may be missing or not permitted on the box
-            print(f"[bench] {' '.join(cmd)} not available: {e}", file=sys.stderr)
+            if open(dev + "/vendor").read().strip() != "0x1002":
+                continue
+            for name in ("pp_dpm_sclk", "pp_dpm_mclk", "power_dpm_force_performance_level"):
+                try:
+                    text = open(f"{dev}/{name}").read().split("\n")
+                except OSError:
+                    continue
+                cur = [l.strip() for l in text if l.strip().endswith("*")] or [l.strip() for l in text if l.strip()][:1]
+                print(f"[bench]   {dev.split('/')[4]} {name}: {' '.join(cur)}", file=sys.stderr)
+        except OSError as e:              # sysfs may be hidden on the box
+            print(f"[bench]   {dev}: {e}", file=sys.stderr)
 
 
 def main():

@@ -184,3 +184,59 @@ def test_chain_decoder_layer_7b_and_graph_replay(gpu, orc):
         torch.cuda.synchronize()
         iflow.qgemv_chain_check(ws)
         compare(f"replay {rep}")
+
+
+def test_chain_decoder_layer_70b_shapes(gpu, orc):
+    """A 70B-shaped layer (hidden 8192, grouped k/v of 1024 rows, feed-forward 28672): seven strips of activations in
+    the last phase, 57344 rows in the widest one.  Weights are drawn on the device (the host generator would take
+    minutes for 0.86 G weights); every output must equal, bit for bit, what the separate launches give, and sampled
+    rows of the first and last phase are checked against the oracle."""
+    torch, iflow = gpu
+    fmt, ofmt = iflow.Q3H_B64, orc.FORMATS["Q3H_B64"]
+    hidden, kv, ffn = 8192, 1024, 28672
+    say(f"[case] chain 70B-shaped layer hidden={hidden} kv={kv} ffn={ffn}")
+    spec = [(hidden, None, [hidden, kv, kv]), (hidden, (0, 0), [hidden]),
+            (hidden, (1, 0), [ffn, ffn]), (ffn, (2, 0), [hidden])]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 900)
+    phases, kept = [], {}
+    for p, (cols, src, row_list) in enumerate(spec):
+        mats = []
+        for j, rows in enumerate(row_list):
+            wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.01
+            n = iflow.packed_bytes(fmt, rows, cols)
+            packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+            iflow.quantize(fmt, wd, rows, cols, packed, n)
+            if (p, j) in ((0, 0), (3, 0)):
+                idx = synth.sample_rows(rows, 32, synth.BASE_SEED + 901 + p)
+                kept[(p, j)] = (idx, wd[torch.from_numpy(idx).cuda()].cpu().numpy())
+            del wd
+            mats.append((packed, rows, torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")))
+        if src is None:
+            x = torch.from_numpy(synth.activations(1, cols, synth.BASE_SEED + 902)[0].view(np.int16)).cuda().view(torch.float16)
+        else:
+            x = phases[src[0]][2][src[1]][2]
+        phases.append((cols, x, mats))
+    nbytes = iflow.qgemv_chain_workspace_bytes([m[1] for ph in phases for m in ph[2]])
+    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
+    for it in range(2):
+        iflow.qgemv_chain(fmt, phases, ws, nbytes)
+    iflow.qgemv_chain_check(ws)
+    xin = phases[0][1]
+    for p, (cols, _, mats) in enumerate(phases):
+        ys = [torch.empty((m[1],), dtype=torch.float16, device="cuda") for m in mats]
+        iflow.qgemv_multi(fmt, [m[0] for m in mats], [m[1] for m in mats], cols, xin, ys)
+        torch.cuda.synchronize()
+        for j, m in enumerate(mats):
+            got, ref = m[2].cpu().numpy().view(np.uint16), ys[j].cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, ref), f"phase {p} matrix {j}: {(got != ref).sum()} of {got.size} differ"
+            if (p, j) in kept:
+                idx, w_rows = kept[(p, j)]
+                q, s, o = orc.quantize(ofmt, w_rows)
+                want = orc.gemm(orc.dequant(ofmt, q, s, o), xin.cpu().numpy().view(np.uint16)[None, :])[0]
+                full = m[2].cpu().numpy().astype(np.float64)
+                rms = np.sqrt(np.mean(full ** 2))
+                e = float(np.max(np.abs(full[idx] - want) / np.maximum(np.abs(want), rms)))
+                say(f"        phase {p}: max rel err on {len(idx)} sampled rows {e:.3e}")
+                assert np.isfinite(full).all() and e <= TOL
+        xin = ys[0]
