@@ -42,6 +42,7 @@ def parse():
                     help="with --launches 1: chain this many layers into one launch (the next layer's q/k/v read down's output)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the context figures for batches > 1 and the cache-hot case")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed region (reference for HBM counters)")
     return ap.parse_args()
@@ -281,6 +282,43 @@ def main():
         read_big_gbps = 5 * big.numel() / (r0.elapsed_time(r1) * 1e-3) / 1e9
         del big
 
+        # context figures for the other paths of the library (never the headline): batches 2..16 and 512 over a ring of
+        # the 16 distinct gate matrices (344 MiB packed, beyond the caches), and the small parity case that stays cache-hot
+        other = None
+        if not args.no_extras:
+            gate = [mats[4] for mats in ring]
+            g_rows, g_cols = gate[0][0], gate[0][1]
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+            def time_gemm(mats, rows, cols, batch, reps):
+                X = torch.randn((batch, cols), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+                Y = torch.empty((batch, rows), dtype=torch.float16, device=dev)
+                for _, _, packed in mats[:2]:
+                    iflow.qgemm(fmt, packed, rows, cols, X, batch, Y, stream=raw)
+                t0.record(stream)
+                for _ in range(reps):
+                    for _, _, packed in mats:
+                        iflow.qgemm(fmt, packed, rows, cols, X, batch, Y, stream=raw)
+                t1.record(stream)
+                t1.synchronize()
+                return t0.elapsed_time(t1) * 1e3 / (reps * len(mats))            # us per product
+
+            other = {"what": f"{args.format}, {g_rows}x{g_cols}, ring of {len(gate)} matrices, eager launches, us per product", "batch": {}}
+            for batch in (1, 2, 4, 8, 16):
+                us = time_gemm(gate, g_rows, g_cols, batch, 12)
+                nbytes = g_rows * g_cols * bpw / 8 + 2 * batch * (g_rows + g_cols)
+                other["batch"][str(batch)] = {"us": round(us, 2), "GB/s": round(nbytes / us / 1e3, 1)}
+            us = time_gemm(gate, g_rows, g_cols, 512, 4)
+            tf = 2.0 * 512 * g_rows * g_cols / us / 1e6
+            other["batch"]["512"] = {"us": round(us, 2), "TFLOP/s": round(tf, 1), "frac_of_f16_mfma_peak": round(tf / 2500.0, 4)}
+            w1 = torch.randn((1024, 1024), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+            n1 = iflow.packed_bytes(fmt, 1024, 1024)
+            p1 = torch.empty(n1, dtype=torch.uint8, device=dev)
+            iflow.quantize(fmt, w1, 1024, 1024, p1, n1)
+            us = time_gemm([(1024, 1024, p1)], 1024, 1024, 1, 400)
+            other["cache_hot_1024x1024_batch1"] = {"us": round(us, 2), "GB/s": round((n1 + 4096) / us / 1e3, 1),
+                                                   "note": "0.5 MiB of codes, resident in cache: launch-bound, not an HBM figure"}
+
     ms_per_step = ms / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     launches_per_step = launch_count[0] / args.steps            # a chained launch covers several layers (steps)
@@ -323,6 +361,7 @@ def main():
     out["stream_read_ceiling"] = {"value": round(read_gbps, 1), "unit": "GB/s", "frac_of_peak": round(read_gbps / HBM_PEAK_GBPS, 4),
                                   "what": "iflow_calibration_read over the same packed matrices, one launch per matrix (7 per layer), eager",
                                   "one_launch_over_1GiB": round(read_big_gbps, 1)}
+    out["other_paths"] = other
     log_environment(torch)
     if args.launches == 1:
         iflow.qgemv_chain_check(chain_ws, stream=raw)          # raises if a phase ever gave up waiting for its input

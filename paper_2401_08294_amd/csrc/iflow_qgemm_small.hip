@@ -10,8 +10,10 @@
 // registers, permuted once into the decoder's element order.  Weights are fully dequantized before the MFMA
 // (the four blocks of a step have different scales): Eq.5 and Eq.2 of the paper with the single-rounded fp16
 // fused multiply-add, i.e. exactly the values iflow_dequant produces.
-// A workgroup is sixteen wavefronts = sixteen column groups = one 4096-column strip; longer rows take one pass per
-// strip with the accumulators kept in registers.  The sixteen partial 16 x 16 tiles are added up through LDS.
+// A workgroup is sixteen wavefronts = sixteen column groups = one 4096-column strip.  The grid is resident (at most one
+// workgroup per compute unit) and a workgroup walks over groups of sixteen rows, strip by strip, with the strip's
+// activations held in registers for all of them; the sixteen partial 16 x 16 tiles of a step are added up through LDS
+// in a fixed order (so results do not vary from run to run), one workgroup barrier per step.
 #include "iflow_common.h"
 
 namespace iflow {
@@ -26,67 +28,193 @@ template <> struct SmallRaw<KIND_Q3H> { uint32_t d[8]; uint32_t hdr[2]; };   // 
 template <> struct SmallRaw<KIND_Q4>  { uint32_t d[8]; uint32_t hdr[2]; };   // 32 code bytes
 template <> struct SmallRaw<KIND_Q8>  { uint32_t d[16]; uint32_t hdr[2]; };  // 64 code bytes
 
-template <int F, int G>
+// LDS of a workgroup: the activation staging area of each wavefront (eight batch rows of its 256 columns at a time,
+// rows 528 bytes apart so that sixteen lanes reading 16 bytes each from eight different rows hit different banks), two
+// buffers for the partial tiles of a round, and the running sums of the rounds when a row spans several strips.
+constexpr int SMALL_XROW = 528;
+constexpr int SMALL_XBYTES = 16 * 8 * SMALL_XROW;
+constexpr int SMALL_RED_FLOATS = 16 * 4 * 64;
+constexpr int SMALL_SETS = 2;                                 // register sets of weights in flight per wavefront (even)
+constexpr int SMALL_MAX_ROUNDS = 16;                          // rounds per workgroup when there is more than one strip
+constexpr int SMALL_LDS_BYTES = SMALL_XBYTES + 2 * SMALL_RED_FLOATS * 4 + SMALL_MAX_ROUNDS * 256 * 4;
+
+// A grid of at most one workgroup per compute unit; workgroup b takes the groups of sixteen rows group0 + b,
+// group0 + b + gridDim.x, ... below `ngroups` ("rounds").  Per strip the activations are loaded once, with loads
+// in which neighbouring lanes read neighbouring addresses, turned through LDS into the operand layout and kept in
+// registers for all rounds; the weights of the round after next are requested while a round is decoded.
+template <int F, int S>
 __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
                                                           uint16_t *__restrict__ Y, int rows, int cols, int batch, int nbk64, int nstrips,
-                                                          int64_t header_offset)
+                                                          int64_t header_offset, int group0, int ngroups)
 {
     typedef Fmt<F> T;
     constexpr int KIND = T::kind;
     constexpr int HPL = 64 / T::block;                        // block headers per lane (1, or 2 for the 32-wide formats)
-    __shared__ float red[16][4][64];                          // partial tiles: [wavefront][accumulator register][lane]
+    extern __shared__ __align__(16) uint8_t lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = lane & 15, g = lane >> 4;
-    const int r0 = blockIdx.x * (16 * G);                     // G groups of sixteen rows per workgroup: activations loaded once for all
-    const int bj = min(i, batch - 1);                         // batch columns past the end repeat the last one and are not stored
+    uint8_t *xst = lds + wave * (8 * SMALL_XROW);
+    float *red = reinterpret_cast<float *>(lds + SMALL_XBYTES);                       // [2][wavefront][register][lane]
+    float *part = red + 2 * SMALL_RED_FLOATS;                                         // [round][256]
+    const int first = group0 + (int)blockIdx.x;
+    const int rounds = (ngroups - first + (int)gridDim.x - 1) / (int)gridDim.x;       // >= 1: the grid never exceeds the groups
+    const int total = nstrips * rounds;                       // steps (strip, round) of this workgroup, strips outermost
 
-    float4_t acc[G];
-#pragma unroll
-    for (int rg = 0; rg < G; ++rg) acc[rg] = (float4_t){0.f, 0.f, 0.f, 0.f};
-
-    for (int t = 0; t < nstrips; ++t) {                       // one pass per 4096-column strip
-        const int kb = t * 64 + wave * 4 + g;                 // this lane's 64-column group
-        const bool live = kb < nbk64;                         // ragged last strip: dead lanes add nothing (their activations are zeroed)
-        const int kbc = live ? kb : t * 64;                   // ... and redo the strip's first group so that loads stay in bounds
+    // weights of step k = (strip, round): the lane's 64 columns of row (group * 16 + i); steps past the end repeat the last one,
+    // rows past the end the last row, dead column groups of a ragged strip the strip's first group: every load stays in bounds
+    // The loads go out with four neighbouring lanes on one row (lane = 4 * row + column group: sixteen lanes touch four
+    // 64-byte pieces instead of sixteen); round_body moves every word to the lane the MFMA layout wants it in.
+    const int il = lane >> 2, gl = lane & 3;
+    const int from = 4 * (4 * i + g);                         // ds_bpermute address of the lane that loaded block (i, g)
+    auto load_step = [&](SmallRaw<KIND> &raw, int t, int r) {
+        const bool beyond = t >= nstrips;                     // past the last step: every lane re-reads the matrix's first bytes
+        if (beyond) { t = nstrips - 1; r = rounds - 1; }
+        const int kb = t * 64 + wave * 4 + gl;
+        const int kbc = kb < nbk64 ? kb : t * 64;
         const int n_t = min(64, nbk64 - t * 64);
-
-        // activations of batch column bj for this column group
-        const uint4 *xsrc = reinterpret_cast<const uint4 *>(X + (int64_t)bj * cols + (int64_t)kbc * 64);
-        uint32_t n[32];
+        const int group = min(first + r * (int)gridDim.x, ngroups - 1);
+        const int64_t row = min(group * 16 + il, rows - 1);
+        if (KIND == KIND_Q3H) {                               // two planes of the strip, 16 bytes each
+            const uint8_t *p0 = packed + row * ((int64_t)nbk64 * 32) + (int64_t)t * 2048 + (kbc & 63) * 16;
+            const uint8_t *p1 = p0 + n_t * 16;
+            if (beyond) { p0 = packed; p1 = packed; }
+            const u32x4_t wa = *reinterpret_cast<const u32x4_t *>(p0);
+            const u32x4_t wc = *reinterpret_cast<const u32x4_t *>(p1);
+            raw.d[0] = wa.x; raw.d[1] = wa.y; raw.d[2] = wa.z; raw.d[3] = wa.w;
+            raw.d[4] = wc.x; raw.d[5] = wc.y; raw.d[6] = wc.z; raw.d[7] = wc.w;
+        } else {                                              // code bytes row-major, then the headers
+            constexpr int BYTES = KIND == KIND_Q4 ? 32 : 64;
+            const uint8_t *p0 = packed + row * ((int64_t)nbk64 * BYTES) + (int64_t)kbc * BYTES;
+            if (beyond) p0 = packed;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const uint4 v = xsrc[q];
-            n[4 * q] = v.x; n[4 * q + 1] = v.y; n[4 * q + 2] = v.z; n[4 * q + 3] = v.w;
+            for (int q = 0; q < BYTES / 16; ++q) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(p0 + (beyond ? 0 : q * 16));
+                raw.d[4 * q] = v.x; raw.d[4 * q + 1] = v.y; raw.d[4 * q + 2] = v.z; raw.d[4 * q + 3] = v.w;
+            }
+            const uint32_t *hp = reinterpret_cast<const uint32_t *>(packed + header_offset) + (beyond ? 0 : (row * nbk64 + kbc) * HPL);
+#pragma unroll
+            for (int h = 0; h < HPL; ++h) raw.hdr[h] = hp[h];
         }
-        // weights of the lane's 64 columns for each row group; rows past the end repeat the last row
-        SmallRaw<KIND> raw[G];
+    };
+
+    const half2_t m1025 = {(half_t)-1025.0f, (half_t)-1025.0f}, m1024 = {(half_t)-1024.0f, (half_t)-1024.0f};
+    const half2_t m11 = {(half_t)-11.0f, (half_t)-11.0f}, m64 = {(half_t)-64.0f, (half_t)-64.0f};
+    half4_t xq[16];                                           // MFMA B operands of the current strip
+
+    // one round: dequantize the lane's block, sixteen MFMA steps, add the sixteen wavefronts' tiles up through LDS
+    auto round_body = [&](const SmallRaw<KIND> &raw, int t, int r, int which) {
+        uint32_t d[KIND == KIND_Q8 ? 16 : 8], hdr[2];
 #pragma unroll
-        for (int rg = 0; rg < G; ++rg) {
-            const int64_t row = min(r0 + 16 * rg + i, rows - 1);
-            if (KIND == KIND_Q3H) {                           // two planes of the strip, 16 bytes each
-                const uint8_t *p0 = packed + row * ((int64_t)nbk64 * 32) + (int64_t)t * 2048 + (kbc & 63) * 16;
-                const u32x4_t wa = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p0));
-                const u32x4_t wc = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p0 + n_t * 16));
-                raw[rg].d[0] = wa.x; raw[rg].d[1] = wa.y; raw[rg].d[2] = wa.z; raw[rg].d[3] = wa.w;
-                raw[rg].d[4] = wc.x; raw[rg].d[5] = wc.y; raw[rg].d[6] = wc.z; raw[rg].d[7] = wc.w;
-            } else {                                          // code bytes row-major, then the headers
-                constexpr int BYTES = KIND == KIND_Q4 ? 32 : 64;
-                const uint8_t *p0 = packed + row * ((int64_t)nbk64 * BYTES) + (int64_t)kbc * BYTES;
+        for (int w = 0; w < (KIND == KIND_Q8 ? 16 : 8); ++w) d[w] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)raw.d[w]);
+        if (KIND != KIND_Q3H) {
 #pragma unroll
-                for (int q = 0; q < BYTES / 16; ++q) {
-                    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p0 + q * 16));
-                    raw[rg].d[4 * q] = v.x; raw[rg].d[4 * q + 1] = v.y; raw[rg].d[4 * q + 2] = v.z; raw[rg].d[4 * q + 3] = v.w;
+            for (int h = 0; h < HPL; ++h) hdr[h] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)raw.hdr[h]);
+        }
+        float4_t acc = {0.f, 0.f, 0.f, 0.f};
+        if (KIND == KIND_Q3H) {
+            uint32_t h = d[0] & 0xC000C000u;                  // header from the spare bits of the eight words
+#pragma unroll
+            for (int w = 1; w < 8; ++w) h = (d[w] & 0xC000C000u) | (h >> 2);
+            const half2_t so = as_h2(h);
+            const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+#pragma unroll
+                for (int hs = 0; hs < 2; ++hs) {              // decode slot s = 2w + hs: weights 4s .. 4s+3
+                    const uint32_t hc = ((d[w] >> (7 * hs)) & 0x007F007Fu) | 0x64006400u;
+                    const half2_t q1 = q3h_high_digit(hc) + m1025;                    // floor(c/11), exact
+                    const half2_t c = as_h2(hc) + m1024;                              // c, exact
+                    const half2_t q2 = __builtin_elementwise_fma(q1, m11, c);         // c mod 11, exact
+                    const half2_t w1 = __builtin_elementwise_fma(q1, s2, o2);         // (w[4s], w[4s+2])   Eq.2, one rounding
+                    const half2_t w2 = __builtin_elementwise_fma(q2, s2, o2);         // (w[4s+1], w[4s+3])
+                    const half4_t a = __builtin_shufflevector(w1, w2, 0, 1, 2, 3);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a, xq[2 * w + hs], acc, 0, 0, 0);
                 }
-                const uint32_t *hp = reinterpret_cast<const uint32_t *>(packed + header_offset) + (row * nbk64 + kbc) * HPL;
+            }
+        } else if (KIND == KIND_Q4) {
 #pragma unroll
-                for (int h = 0; h < HPL; ++h) raw[rg].hdr[h] = hp[h];
+            for (int w = 0; w < 8; ++w) {                     // word w: weights 8w .. 8w+7, nibble order v0 v2 v4 v6 v1 v3 v5 v7
+                const half2_t so = as_h2(hdr[HPL == 2 ? w >> 2 : 0]);
+                const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
+                const uint32_t dw = d[w], e = dw >> 8;
+                const half2_t q0 = as_h2((dw & 0x000F000Fu) | 0x64006400u) + m1024;   // (v0, v1)
+                const half2_t q1 = as_h2((dw & 0x00F000F0u) | 0x54005400u) + m64;     // (v2, v3)
+                const half2_t q2 = as_h2((e & 0x000F000Fu) | 0x64006400u) + m1024;    // (v4, v5)
+                const half2_t q3 = as_h2((e & 0x00F000F0u) | 0x54005400u) + m64;      // (v6, v7)
+                const half4_t a0 = __builtin_shufflevector(__builtin_elementwise_fma(q0, s2, o2), __builtin_elementwise_fma(q1, s2, o2), 0, 1, 2, 3);
+                const half4_t a1 = __builtin_shufflevector(__builtin_elementwise_fma(q2, s2, o2), __builtin_elementwise_fma(q3, s2, o2), 0, 1, 2, 3);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a0, xq[2 * w], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a1, xq[2 * w + 1], acc, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int w = 0; w < 16; ++w) {                    // word w: bytes = weights 4w .. 4w+3
+                const half2_t so = as_h2(hdr[HPL == 2 ? w >> 3 : 0]);
+                const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
+                const half2_t q0 = as_h2(__builtin_amdgcn_perm(0x64646464u, d[w], 0x04010400u)) + m1024;   // (b0, b1)
+                const half2_t q1 = as_h2(__builtin_amdgcn_perm(0x64646464u, d[w], 0x04030402u)) + m1024;   // (b2, b3)
+                const half4_t a0 = __builtin_shufflevector(__builtin_elementwise_fma(q0, s2, o2), __builtin_elementwise_fma(q1, s2, o2), 0, 1, 2, 3);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a0, xq[w], acc, 0, 0, 0);
             }
         }
+        // accumulator register e of lane (j, g') is D[4g' + e][j].  The buffer alternates from step to step: a wavefront that
+        // is one step ahead writes the other buffer, and nobody is two steps ahead of a reader (one barrier per step).
+        float *buf = red + which * SMALL_RED_FLOATS;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) buf[(wave * 4 + e) * 64 + lane] = acc[e];
+        __syncthreads();
+        const int tid = threadIdx.x;
+        if (tid < 256) {
+            const int e = tid >> 6, l = tid & 63;
+            float sum = (nstrips > 1 && t > 0) ? part[r * 256 + tid] : 0.f;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) sum += buf[(w * 4 + e) * 64 + l];
+            if (t + 1 < nstrips) {
+                part[r * 256 + tid] = sum;
+            } else {
+                const int rr = (first + r * (int)gridDim.x) * 16 + 4 * (l >> 4) + e, b = l & 15;
+                if (rr < rows && b < batch) Y[(int64_t)b * rows + rr] = as_u16((half_t)sum);
+            }
+        }
+    };
 
+    // activations of strip t: batch rows x the wavefront's 256 columns -> lane (j, g) holds row j, columns 64g .. 64g+63
+    auto stage = [&](int t) {
+        const int kb = t * 64 + wave * 4 + g;
+        const bool live = kb < nbk64;                         // ragged last strip: dead lanes add nothing (their activations are zeroed)
+        int c = (t * 64 + wave * 4) * 64 + (lane & 31) * 8;
+        if (c >= cols) c = 0;                                 // columns past the end: any valid address, the values are masked below
+        u32x4_t va[4], vb[4];                                  // load q: batch rows 2q and 2q+1 (vb: 8+2q, 9+2q), 512 bytes each, lane by lane
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            va[q] = *reinterpret_cast<const u32x4_t *>(X + (int64_t)min(2 * q + (lane >> 5), batch - 1) * cols + c);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            vb[q] = *reinterpret_cast<const u32x4_t *>(X + (int64_t)min(8 + 2 * q + (lane >> 5), batch - 1) * cols + c);
+        uint32_t n[32];
+#pragma unroll
+        for (int q = 0; q < 32; ++q) n[q] = 0u;
+        auto turn = [&](const u32x4_t (&v)[4], bool mine) {     // eight batch rows through the staging rows
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<u32x4_t *>(xst + (2 * q + (lane >> 5)) * SMALL_XROW + (lane & 31) * 16) = v[q];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const u32x4_t u = *reinterpret_cast<const u32x4_t *>(xst + (i & 7) * SMALL_XROW + g * 128 + q * 16);
+                n[4 * q] = mine ? u.x : n[4 * q]; n[4 * q + 1] = mine ? u.y : n[4 * q + 1];
+                n[4 * q + 2] = mine ? u.z : n[4 * q + 2]; n[4 * q + 3] = mine ? u.w : n[4 * q + 3];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();                  // the next turn overwrites the staging rows
+        };
+        turn(va, i < 8);
+        turn(vb, i >= 8);
         // MFMA B operands: the four activations of step s.  Q3H's decoder yields weights in the order (4s, 4s+2, 4s+1, 4s+3).
         const uint32_t keep = live ? 0xFFFFFFFFu : 0u;
-        half4_t xq[16];
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
             uint32_t e, o;
@@ -98,77 +226,49 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
             }
             xq[s] = __builtin_bit_cast(half4_t, make_uint2(e & keep, o & keep));
         }
+    };
+    // (t, r) of the step `ahead` (<= S) steps after (t, r)
+    auto step_after = [&](int t, int r, int ahead, int &t2, int &r2) {
+        t2 = t; r2 = r + ahead;
+#pragma unroll
+        for (int q = 0; q < S; ++q)
+            if (r2 >= rounds) { r2 -= rounds; ++t2; }
+    };
 
-        const half2_t m1025 = {(half_t)-1025.0f, (half_t)-1025.0f}, m1024 = {(half_t)-1024.0f, (half_t)-1024.0f};
-        const half2_t m11 = {(half_t)-11.0f, (half_t)-11.0f}, m64 = {(half_t)-64.0f, (half_t)-64.0f};
+    // Steps (strip, round) in order, S per trip through S register sets; a set is refilled for S steps ahead right
+    // after its use.  The last trips, where some steps or refills no longer exist, run through a guarded copy of the
+    // loop body so that the main loop has no load under a branch (the wait counters stay exact there) and nothing is
+    // requested that is not used (a wavefront ends only when its last load has returned).
+    SmallRaw<KIND> raw[S];
+    int t = 0, r = 0, t2, r2;
 #pragma unroll
-        for (int rg = 0; rg < G; ++rg) {
-            const uint32_t *d = raw[rg].d;
-            if (KIND == KIND_Q3H) {
-                // header from the spare bits of the eight words
-                uint32_t h = d[0] & 0xC000C000u;
+    for (int j = 0; j < S; ++j) {
+        step_after(0, 0, j, t2, r2);
+        load_step(raw[j], t2, r2);
+    }
+    int k = 0;
+    for (; k + 2 * S - 1 < total; k += S) {
 #pragma unroll
-                for (int w = 1; w < 8; ++w) h = (d[w] & 0xC000C000u) | (h >> 2);
-                const half2_t so = as_h2(h);
-                const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
-#pragma unroll
-                for (int w = 0; w < 8; ++w) {
-#pragma unroll
-                    for (int hs = 0; hs < 2; ++hs) {          // decode slot s = 2w + hs: weights 4s .. 4s+3
-                        const uint32_t hc = ((d[w] >> (7 * hs)) & 0x007F007Fu) | 0x64006400u;
-                        const half2_t q1 = q3h_high_digit(hc) + m1025;                    // floor(c/11), exact
-                        const half2_t c = as_h2(hc) + m1024;                              // c, exact
-                        const half2_t q2 = __builtin_elementwise_fma(q1, m11, c);         // c mod 11, exact
-                        const half2_t w1 = __builtin_elementwise_fma(q1, s2, o2);         // (w[4s], w[4s+2])   Eq.2, one rounding
-                        const half2_t w2 = __builtin_elementwise_fma(q2, s2, o2);         // (w[4s+1], w[4s+3])
-                        const half4_t a = __builtin_shufflevector(w1, w2, 0, 1, 2, 3);
-                        acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, xq[2 * w + hs], acc[rg], 0, 0, 0);
-                    }
-                }
-            } else if (KIND == KIND_Q4) {
-#pragma unroll
-                for (int w = 0; w < 8; ++w) {                 // word w: weights 8w .. 8w+7, nibble order v0 v2 v4 v6 v1 v3 v5 v7
-                    const half2_t so = as_h2(raw[rg].hdr[HPL == 2 ? w >> 2 : 0]);
-                    const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
-                    const uint32_t dw = d[w], e = dw >> 8;
-                    const half2_t q0 = as_h2((dw & 0x000F000Fu) | 0x64006400u) + m1024;   // (v0, v1)
-                    const half2_t q1 = as_h2((dw & 0x00F000F0u) | 0x54005400u) + m64;     // (v2, v3)
-                    const half2_t q2 = as_h2((e & 0x000F000Fu) | 0x64006400u) + m1024;    // (v4, v5)
-                    const half2_t q3 = as_h2((e & 0x00F000F0u) | 0x54005400u) + m64;      // (v6, v7)
-                    const half4_t a0 = __builtin_shufflevector(__builtin_elementwise_fma(q0, s2, o2), __builtin_elementwise_fma(q1, s2, o2), 0, 1, 2, 3);
-                    const half4_t a1 = __builtin_shufflevector(__builtin_elementwise_fma(q2, s2, o2), __builtin_elementwise_fma(q3, s2, o2), 0, 1, 2, 3);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a0, xq[2 * w], acc[rg], 0, 0, 0);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a1, xq[2 * w + 1], acc[rg], 0, 0, 0);
-                }
-            } else {
-#pragma unroll
-                for (int w = 0; w < 16; ++w) {                // word w: bytes = weights 4w .. 4w+3
-                    const half2_t so = as_h2(raw[rg].hdr[HPL == 2 ? w >> 3 : 0]);
-                    const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
-                    const half2_t q0 = as_h2(__builtin_amdgcn_perm(0x64646464u, d[w], 0x04010400u)) + m1024;   // (b0, b1)
-                    const half2_t q1 = as_h2(__builtin_amdgcn_perm(0x64646464u, d[w], 0x04030402u)) + m1024;   // (b2, b3)
-                    const half4_t a0 = __builtin_shufflevector(__builtin_elementwise_fma(q0, s2, o2), __builtin_elementwise_fma(q1, s2, o2), 0, 1, 2, 3);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a0, xq[w], acc[rg], 0, 0, 0);
-                }
-            }
+        for (int j = 0; j < S; ++j) {
+            if (r == 0) stage(t);
+            round_body(raw[j], t, r, j & 1);
+            step_after(t, r, S, t2, r2);
+            load_step(raw[j], t2, r2);
+            step_after(t, r, 1, t, r);
         }
     }
-
-    // add the sixteen column groups up: accumulator register e of lane (j, g') is D[4g' + e][j]
-    const int tid = threadIdx.x;
+    for (; k < total; k += S) {
 #pragma unroll
-    for (int rg = 0; rg < G; ++rg) {
-        if (rg > 0) __syncthreads();                          // the previous group's sums have been read
-#pragma unroll
-        for (int e = 0; e < 4; ++e) red[wave][e][lane] = acc[rg][e];
-        __syncthreads();
-        if (tid < 256) {
-            const int e = tid >> 6, l = tid & 63;
-            float sum = 0.f;
-#pragma unroll
-            for (int w = 0; w < 16; ++w) sum += red[w][e][l];
-            const int r = r0 + 16 * rg + 4 * (l >> 4) + e, b = l & 15;
-            if (r < rows && b < batch) Y[(int64_t)b * rows + r] = as_u16((half_t)sum);
+        for (int j = 0; j < S; ++j) {
+            if (k + j < total) {                              // (uniform over the workgroup)
+                if (r == 0) stage(t);
+                round_body(raw[j], t, r, j & 1);
+                if (k + j + S < total) {
+                    step_after(t, r, S, t2, r2);
+                    load_step(raw[j], t2, r2);
+                }
+                step_after(t, r, 1, t, r);
+            }
         }
     }
 }
@@ -177,17 +277,35 @@ template <int F>
 static hipError_t small_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s)
 {
     typedef Fmt<F> T;
+    constexpr int S = SMALL_SETS;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_small_kernel<F, S>), hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        if (n < 1) return hipErrorInvalidDevice;
+        cus = n;
+    }
     const int nbk64 = (int)(cols / 64);
     const int nstrips = (nbk64 + 63) / 64;
     const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;
-    // row groups per workgroup: measured on 7B/70B shapes, more than one group per workgroup is slower (11008 x 4096,
-    // batch 16: 18.7 us with one group, 22.1 us with two), so only very tall matrices share the activation loads
-    const int64_t G = rows / 16 / 8192;
-#define IFLOW_SMALL_GO(GG) hipLaunchKernelGGL((gemm_small_kernel<F, GG>), dim3((unsigned)((rows + 16 * GG - 1) / (16 * GG))), dim3(1024), 0, s, \
-        static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk64, nstrips, header_offset)
-    if (T::kind == KIND_Q3H && G >= 4) IFLOW_SMALL_GO(4); else if (T::kind != KIND_Q8 && G >= 2) IFLOW_SMALL_GO(2); else IFLOW_SMALL_GO(1);
-#undef IFLOW_SMALL_GO
-    return hipGetLastError();
+    const int64_t ngroups = (rows + 15) / 16;
+    if (ngroups > 0x7FFFFFF || rows > 0x7FFFFFFF) return hipErrorInvalidValue;
+    // rows spanning several strips keep a running sum per round in LDS: at most SMALL_MAX_ROUNDS rounds per launch then
+    const int64_t per_launch = nstrips > 1 ? (int64_t)cus * SMALL_MAX_ROUNDS : ngroups;
+    for (int64_t g0 = 0; g0 < ngroups; g0 += per_launch) {
+        const int64_t g1 = g0 + per_launch < ngroups ? g0 + per_launch : ngroups;
+        const int64_t grid = g1 - g0 < cus ? g1 - g0 : cus;
+        hipLaunchKernelGGL((gemm_small_kernel<F, S>), dim3((unsigned)grid), dim3(1024), SMALL_LDS_BYTES, s,
+                           static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk64, nstrips, header_offset,
+                           (int)g0, (int)g1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int64_t cols,

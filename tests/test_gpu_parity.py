@@ -134,6 +134,51 @@ def test_small_batch(gpu, orc, name, batch):
     check_all(torch, iflow, orc, name, w, x, "batch")
 
 
+# ---- small batches on tall matrices: a workgroup takes several groups of sixteen rows in turn (two or three here, so both
+#      an even and an odd count), over one strip or two ragged ones; weights drawn on the device, every output against the
+#      one-vector kernel on the same bytes, sampled rows against the oracle ---------------------------------------------
+def small_batch_tall(torch, iflow, orc, name, rows, cols, batch, seed):
+    fmt, ofmt = iflow.FORMATS[name], orc.FORMATS[name]
+    say(f"[case] small batch, tall: fmt={name} rows={rows} cols={cols} batch={batch}")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+    n = iflow.packed_bytes(fmt, rows, cols)
+    packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+    iflow.quantize(fmt, wd, rows, cols, packed, n)
+    idx = synth.sample_rows(rows, 48, seed + 1)
+    idx[:3] = [0, rows - 1, rows - 17 if rows > 17 else 0]
+    w_rows = wd[torch.from_numpy(idx).cuda()].cpu().numpy()
+    del wd
+    x = synth.activations(batch, cols, seed + 2)
+    y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x)
+    assert np.isfinite(y).all()
+    q, s, o = orc.quantize(ofmt, w_rows)
+    yref = orc.gemm(orc.dequant(ofmt, q, s, o), x.view(np.uint16))
+    rms = np.sqrt(np.mean(y ** 2, axis=-1, keepdims=True))
+    e = float(np.max(np.abs(y[:, idx] - yref) / np.maximum(np.abs(yref), rms)))
+    say(f"        max rel err on {len(idx)} sampled rows {e:.3e}")
+    assert e <= TOL
+    for b in range(batch):                                     # all rows: the one-vector kernel, same packed bytes
+        y1 = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x[b:b + 1])
+        e1 = float(np.max(np.abs(y[b] - y1[0]) / np.maximum(np.abs(y1[0]), rms[b])))
+        assert e1 <= TOL, f"vector {b}: {e1}"          # two fp16 roundings of sums taken in different orders
+
+
+@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("cols", [1024, 4096 + 64 * 3])
+def test_small_batch_tall(gpu, orc, name, cols):
+    torch, iflow = gpu
+    small_batch_tall(torch, iflow, orc, name, 16 * 256 * 2 + 16 * 100 + 5, cols, 5 if "Q8" in name else 3, synth.BASE_SEED + 940)
+    small_batch_tall(torch, iflow, orc, name, 16 * 256 + 7, cols, 16, synth.BASE_SEED + 950)
+
+
+def test_small_batch_more_rounds_than_one_launch_holds(gpu, orc):
+    """Rows spanning two strips and more than sixteen row groups per workgroup: the entry point splits the rows."""
+    torch, iflow = gpu
+    small_batch_tall(torch, iflow, orc, "Q3H_B64", 16 * 256 * 17 + 40, 4096 + 64, 4, synth.BASE_SEED + 960)
+
+
 # ---- large batches run on the matrix cores (128 x 64 tiles, 64-column chunks): ragged in every dimension ----
 @pytest.mark.parametrize("name", NAMES)
 @pytest.mark.parametrize("batch,rows,nchunks", [(32, 64, 1), (100, 200, 69), (512, 70, 3)])
