@@ -15,6 +15,7 @@ namespace iflow {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int GM_BM = 128, GM_BN = 64, GM_BK = 64, GM_LD = 72;   // tile sizes; LDS row pitch in halves (144 bytes)
 
@@ -25,7 +26,7 @@ __device__ __forceinline__ uint32_t pack_h2(half2_t v) { return as_u32(v); }
 struct Raw16 { uint32_t d[4]; uint32_t hdr; };
 
 template <int F>
-__device__ __forceinline__ void load16(const uint8_t *__restrict__ packed, int64_t header_offset, int64_t row, int nbk,
+__device__ __forceinline__ void load16(const uint8_t *packed, int64_t header_offset, int64_t row, int nbk,
                                        int kb /* 64-column chunk */, int qd, Raw16 &r)
 {
     typedef Fmt<F> T;
@@ -113,10 +114,12 @@ __device__ __forceinline__ void decode16(const Raw16 &r, int qd, uint32_t (&out)
     }
 }
 
+// (The inputs are deliberately not declared __restrict__: loads from memory the compiler knows to be read-only and
+// unaliased are free to move, and the scheduler then sinks the prefetch of a later chunk down to its use, four
+// barriers later, to save registers - which turns every chunk into a full memory round trip.)
 template <int F>
-__global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
-                                                         uint16_t *__restrict__ Y, int rows, int cols, int batch, int nbk,
-                                                         int64_t header_offset)
+__global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, const uint16_t *X, uint16_t *Y, int rows, int cols,
+                                                         int batch, int nbk, int64_t header_offset)
 {
     // two LDS stages: while the MFMAs read one, the next chunk is written into the other
     __shared__ __align__(16) uint16_t xs[2][GM_BM * GM_LD];    // activations  [128][68]
@@ -128,23 +131,25 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *__restri
     // loaders: activations - thread -> (row tid/2, 32 halves at (tid%2)*32); weights - thread -> (row tid/4, quarter tid%4)
     const int xr = tid >> 1, xh = tid & 1;
     const int64_t xrow = min(m0 + xr, batch - 1);              // rows past the batch repeat the last row, their outputs are not stored
-    const uint4 *xsrc = reinterpret_cast<const uint4 *>(X + xrow * cols + xh * 32);
+    const u32x4_t *xsrc = reinterpret_cast<const u32x4_t *>(X + xrow * cols + xh * 32);
     const int wr = tid >> 2, wq = tid & 3;
     const int64_t wrow = min(n0 + wr, rows - 1);
     const int nchunks = cols / GM_BK;
 
-    struct Stage { uint4 x[4]; Raw16 w; };
+    // (plain vector types and separately named stages: an array of structs that hold HIP's uint4 class is not split
+    // into registers completely, and the part left over is parked in LDS, with a full wait right after its load)
+    struct Stage { u32x4_t x0, x1, x2, x3; Raw16 w; };
     auto fetch = [&](Stage &st, int kb) {                      // global -> registers; chunks past the end repeat the last one
         const int kc = min(kb, nchunks - 1);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) st.x[j] = xsrc[(int64_t)kc * 8 + j];   // 64 halves per row and chunk = 8 uint4; this thread's half = 4
+        const u32x4_t *xp = xsrc + (int64_t)kc * 8;            // 64 halves per row and chunk = 8 x 16 bytes; this thread's half = 4
+        st.x0 = xp[0]; st.x1 = xp[1]; st.x2 = xp[2]; st.x3 = xp[3];
         load16<F>(packed, header_offset, wrow, nbk, kc, wq, st.w);
     };
     auto stash = [&](const Stage &st, int buf) {               // registers -> LDS, weights decoded on the way
         uint32_t wv[8];
         decode16<F>(st.w, wq, wv);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(&xs[buf][xr * GM_LD + xh * 32 + j * 8]) = st.x[j];
+        u32x4_t *xd = reinterpret_cast<u32x4_t *>(&xs[buf][xr * GM_LD + xh * 32]);
+        xd[0] = st.x0; xd[1] = st.x1; xd[2] = st.x2; xd[3] = st.x3;
         *reinterpret_cast<uint4 *>(&ws[buf][wr * GM_LD + wq * 16]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
         *reinterpret_cast<uint4 *>(&ws[buf][wr * GM_LD + wq * 16 + 8]) = make_uint4(wv[4], wv[5], wv[6], wv[7]);
     };
@@ -176,24 +181,23 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *__restri
     // before its data is needed, which covers the HBM latency with a single wavefront per SIMD).  Four chunks per
     // trip so that the register stages keep their roles without copies; chunks past the end repeat the last one
     // and are never multiplied.
-    Stage st[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) fetch(st[u], u);
-    stash(st[0], 0);
-    fetch(st[0], 4);
+    Stage sa, sb, sc, sd;
+    fetch(sa, 0); fetch(sb, 1); fetch(sc, 2); fetch(sd, 3);
+    stash(sa, 0);
+    fetch(sa, 4);
     __syncthreads();
-    for (int kb = 0; kb < nchunks; kb += 4) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = kb + u;                              // chunk multiplied in this step (wave-uniform)
-            if (c < nchunks) {
-                stash(st[(u + 1) & 3], (c + 1) & 1);           // chunk c+1 -> the other LDS stage
-                fetch(st[(u + 1) & 3], c + 5);                 // refill that register stage
-                multiply(c & 1);
-                __syncthreads();
-            }
-        }
+    // Whole trips first, without any branch around the loads: with a load under a branch the compiler can no longer
+    // count which outstanding load a register belongs to and waits for all of them, the newest request included.
+    int kb = 0;
+#define IFLOW_GEMM_STEP(ST, U)        /* chunk kb+U multiplies; chunk kb+U+1 goes to the other LDS stage; ST is refilled */ \
+    stash(ST, (kb + U + 1) & 1); fetch(ST, kb + U + 5); multiply((kb + U) & 1); __syncthreads();
+    for (; kb + 4 <= nchunks; kb += 4) {
+        IFLOW_GEMM_STEP(sb, 0) IFLOW_GEMM_STEP(sc, 1) IFLOW_GEMM_STEP(sd, 2) IFLOW_GEMM_STEP(sa, 3)
     }
+#undef IFLOW_GEMM_STEP
+#define IFLOW_GEMM_TAIL(ST, U) if (kb + U < nchunks) { stash(ST, (kb + U + 1) & 1); multiply((kb + U) & 1); __syncthreads(); }
+    IFLOW_GEMM_TAIL(sb, 0) IFLOW_GEMM_TAIL(sc, 1) IFLOW_GEMM_TAIL(sd, 2)      // the last one to three chunks
+#undef IFLOW_GEMM_TAIL
 
     // 32x32 accumulator layout: register v of lane l is D[(v/4)*8 + (l/32)*4 + v%4][l%32]
     const int col = n0 + wn * 32 + (lane & 31);
