@@ -137,14 +137,14 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
             }
         };
 
-        for (int i = 0; i < nr; i += 2 * U) {                 // two groups per trip: one computes while the other loads
-            const bool more = i + U < nr;
-            if (more) load_group(wb, i + U);
+        // Two groups per trip: one computes while the other loads.  The loads are unconditional (rows past the end
+        // repeat the last row, which is in cache by then): with a load under a branch the compiler waits for all
+        // outstanding loads at the next use instead of only for the group it needs.
+        for (int i = 0; i < nr; i += 2 * U) {
+            load_group(wb, i + U);
             compute_group(wa, i);
-            if (more) {
-                if (i + 2 * U < nr) load_group(wa, i + 2 * U);
-                compute_group(wb, i + U);
-            }
+            load_group(wa, i + 2 * U);
+            if (i + U < nr) compute_group(wb, i + U);
         }
     }
 
