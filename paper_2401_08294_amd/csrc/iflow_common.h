@@ -2,6 +2,8 @@
 // host-side launcher prototypes.  gfx950 (CDNA4) only: 64-wide wavefronts, DPP, packed fp16 math.
 #pragma once
 
+#include <mutex>
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -97,6 +99,34 @@ __device__ __forceinline__ half2_t q3h_low_digit(half2_t h1, uint32_t hc)
     const ushort2_t m11 = {0xFFF5, 0xFFF5};
     ushort2_t r = __builtin_bit_cast(ushort2_t, h1) * m11 + __builtin_bit_cast(ushort2_t, hc);
     return __builtin_bit_cast(half2_t, r);                                // 2^-20 * (2037 + q2) in each half
+}
+
+// ---- once-per-device set-up on the host -----------------------------------------------------------
+// A launcher's per-device preparation (raising a kernel's dynamic-LDS limit) runs once for each device it is called
+// on, under a lock, so that several host threads may call the library; the device's compute-unit count comes back.
+constexpr int IFLOW_MAX_DEVICES = 64;
+struct PerDevice {
+    std::mutex lock;
+    int cus[IFLOW_MAX_DEVICES] = {};
+};
+template <typename Prepare>
+inline hipError_t once_per_device(PerDevice &pd, int *cus, Prepare prepare)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= IFLOW_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(pd.lock);
+    if (pd.cus[dev] == 0) {
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = prepare();
+        if (e != hipSuccess) return e;
+        if (n < 1) return hipErrorInvalidDevice;
+        pd.cus[dev] = n;
+    }
+    *cus = pd.cus[dev];
+    return hipSuccess;
 }
 
 // ---- host-side launchers, one per translation unit ------------------------------------------------

@@ -278,17 +278,12 @@ static hipError_t small_launch(const void *packed, int64_t rows, int64_t cols, c
 {
     typedef Fmt<F> T;
     constexpr int S = SMALL_SETS;
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_small_kernel<F, S>), hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        if (n < 1) return hipErrorInvalidDevice;
-        cus = n;
-    }
+    static PerDevice pd;
+    int cus = 0;
+    hipError_t e0 = once_per_device(pd, &cus, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_small_kernel<F, S>), hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_BYTES);
+    });
+    if (e0 != hipSuccess) return e0;
     const int nbk64 = (int)(cols / 64);
     const int nstrips = (nbk64 + 63) / 64;
     const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;

@@ -364,20 +364,12 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
 // rows_per_wg chosen so that the grid has a few wavefronts per SIMD on a 256-CU part.
 static int pick_rows_per_wg(int64_t rows, int waves_per_wg)
 {
-    static const char *env = getenv("IFLOW_DEBUG_ROWS_PER_WG");
-    if (env) return atoi(env);
     const int64_t target_waves = 256 * 4 * 2;
     int64_t r = (rows * waves_per_wg + target_waves - 1) / target_waves;
     r = (r + 3) / 4 * 4;                                      // whole groups of four rows
     if (r < 4) r = 4;
     if (r > 64) r = 64;
     return (int)r;
-}
-
-static int env_int(const char *name, int dflt)
-{
-    const char *e = getenv(name);
-    return e ? atoi(e) : dflt;
 }
 
 template <int NB, int U>
@@ -389,16 +381,17 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
     int T = (152 * 1024) / (SLOT * NB);
     if (T > nstrips) T = nstrips;
     const size_t lds = (size_t)T * NB * SLOT;
-    static bool attr_done = false;                            // raise the dynamic-LDS cap once per instantiation
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false>),
+    static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
+    int cus = 0;
+    hipError_t e = once_per_device(pd, &cus, [] {
+        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true>),
+        if (r == hipSuccess)
+            r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+        return r;
+    });
+    if (e != hipSuccess) return e;
     if (T < nstrips) G = 1;                                   // multi-pass rows: partial sums live in registers, one group only
     const int64_t rows_per_wg = (int64_t)waves * U * G;
     int64_t grid = 0;
@@ -426,19 +419,14 @@ static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t 
     const int nstrips = (int)((cols / 64 + 63) / 64);
     int64_t rows = 0;
     for (int i = 0; i < grp.count; ++i) rows += grp.rows[i];
-    static const int dbg_w = env_int("IFLOW_DEBUG_WAVES", 0), dbg_u = env_int("IFLOW_DEBUG_U", 0), dbg_g = env_int("IFLOW_DEBUG_G", 0);
     int waves = (nstrips >= 3 || rows <= 8192) ? 8 : 4;
-    int U = NB <= 2 ? 2 : 1;                                  // 32 activation registers per batch column: fewer rows in flight
-    if (dbg_w > 0 && dbg_w <= 16) waves = dbg_w;
-    if (dbg_u > 0) U = dbg_u;
     if (NB > 2 && waves > 8) waves = 8;                       // those instantiations are built for at most 512 threads
-    int G = (int)(rows / U / 2560);                           // tall problems: several row groups per wavefront, staging paid once
+    int G = (int)(rows / (NB <= 2 ? 2 : 1) / 2560);           // tall problems: several row groups per wavefront, staging paid once
     if (G < 1) G = 1;
     if (G > 3) G = 3;
-    if (dbg_g > 0) G = dbg_g;
-    if (U == 1) return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
-    if (U == 2) return q3h_launch_u<NB, 2>(grp, cols, X, waves, G, s);
-    return q3h_launch_u<NB, 4>(grp, cols, X, waves, G, s);
+    // rows in flight per wavefront: two, or one where 32 activation registers per batch column leave no room
+    if (NB <= 2) return q3h_launch_u<NB, 2>(grp, cols, X, waves, G, s);
+    return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
 }
 
 template <int F, int NB>

@@ -458,22 +458,13 @@ hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *col
                               const void *const *packed, const int64_t *rows, uint16_t *const *y,
                               const int *x_src, void *workspace, hipStream_t s)
 {
-    static int grid = 0;
-    static const int depth = getenv("IFLOW_DEBUG_CHAIN_S") ? atoi(getenv("IFLOW_DEBUG_CHAIN_S")) : 2;
-    if (grid == 0) {
-        int dev = 0, cus = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<3>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
-        if (e != hipSuccess) return e;
-        if (cus < 1) return hipErrorInvalidDevice;
-        grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
-    }
+    static PerDevice pd;
+    int cus = 0;
+    hipError_t e0 = once_per_device(pd, &cus, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+    });
+    if (e0 != hipSuccess) return e0;
+    const int grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
     ChainArgs a = {};
     a.nphases = nphases;
     int m = 0, max_strips = 1;
@@ -502,12 +493,8 @@ hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *col
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
     const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES;
-    if (depth == 3)
-        hipLaunchKernelGGL((q3h_chain_kernel<3>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, a,
-                           static_cast<uint32_t *>(workspace));
-    else
-        hipLaunchKernelGGL((q3h_chain_kernel<2>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, a,
-                           static_cast<uint32_t *>(workspace));
+    hipLaunchKernelGGL((q3h_chain_kernel<2>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, a,
+                       static_cast<uint32_t *>(workspace));
     return hipGetLastError();
 }
 
