@@ -148,8 +148,11 @@ iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream);
 /* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
  * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].
  *   X [batch][cols] fp16, Y [batch][rows] fp16, both device.
- * batch 1 is iflow_qgemv; small batches stream the weights once on the vector units; larger
- * batches run on the matrix cores from dequantized fp16 tiles. */
+ * One backend, chosen by batch: 1 is iflow_qgemv; 2 (8-bit formats: up to 4) runs on the vector units with the
+ * activation vectors side by side; up to 31 the weights stream once per sixteen vectors and the multiply runs on the
+ * matrix cores (16x16x16 tiles, weights dequantized in registers); from 32 on (and cols a multiple of 64) 128 x 64
+ * output tiles run on the matrix cores from dequantized fp16 tiles in LDS.  Results of one call do not depend on
+ * how busy the device is (all sums are taken in a fixed order). */
 iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                            const uint16_t *X, int64_t batch, uint16_t *Y, void *stream);
 

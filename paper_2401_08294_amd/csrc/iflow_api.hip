@@ -125,8 +125,9 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     if (!packed || !X || !Y) return IFLOW_ERR_NULL;
     if (!aligned16(packed) || !aligned16(X) || !aligned16(Y)) return IFLOW_ERR_ALIGN;
     // One backend, three kernels chosen by batch: a few activation vectors ride along with the weight stream on the
-    // vector units; 3.5-bit weights with up to 31 vectors stream once per 16 vectors through 16x16x16 MFMAs; from 32
-    // vectors on the product is a dense contraction on LDS tiles (64-column chunks).
+    // vector units; up to 31 vectors the weights stream once per 16 vectors through 16x16x16 MFMAs; from 32 vectors
+    // on the product is a dense contraction on LDS tiles (64-column chunks).  Column counts that are not a multiple
+    // of 64 (possible with the 32-wide blocks) stay on the vector kernel, four vectors per pass.
     hipStream_t hs = (hipStream_t)stream;
     if (batch >= 32 && cols % 64 == 0)
         return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, hs));
