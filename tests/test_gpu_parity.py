@@ -179,6 +179,17 @@ def test_small_batch_more_rounds_than_one_launch_holds(gpu, orc):
     small_batch_tall(torch, iflow, orc, "Q3H_B64", 16 * 256 * 17 + 40, 4096 + 64, 4, synth.BASE_SEED + 960)
 
 
+# ---- 32-wide blocks allow column counts that are not a multiple of 64: those stay on the vector kernel at any batch ----
+@pytest.mark.parametrize("name", ["Q4_B32", "Q8_B32"])
+@pytest.mark.parametrize("batch", [3, 7, 40])
+def test_odd_block_count_batches(gpu, orc, name, batch):
+    torch, iflow = gpu
+    rows, cols = 70, 32 * 67
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 61, outlier_prob=0.001)
+    x = synth.activations(batch, cols, synth.BASE_SEED + 62)
+    check_all(torch, iflow, orc, name, w, x, "odd block count")
+
+
 # ---- large batches run on the matrix cores (128 x 64 tiles, 64-column chunks): ragged in every dimension ----
 @pytest.mark.parametrize("name", NAMES)
 @pytest.mark.parametrize("batch,rows,nchunks", [(32, 64, 1), (100, 200, 69), (512, 70, 3)])
