@@ -240,3 +240,59 @@ def test_chain_decoder_layer_70b_shapes(gpu, orc):
                 say(f"        phase {p}: max rel err on {len(idx)} sampled rows {e:.3e}")
                 assert np.isfinite(full).all() and e <= TOL
         xin = ys[0]
+
+
+def test_chain_benchmark_configuration_eight_layers(gpu, orc):
+    """The launch the benchmark times: eight 7B-shaped layers (32 dependent phases, 56 matrices, 0.81 GB of codes) in one
+    launch.  Every output must equal, bit for bit, what separate launches give on the same inputs; sampled rows of the
+    first and the last layer are checked against the oracle, given the activations the GPU actually used."""
+    torch, iflow = gpu
+    fmt, ofmt = iflow.Q3H_B64, orc.FORMATS["Q3H_B64"]
+    hidden, ffn, nlayers = 4096, 11008, 8
+    say(f"[case] chain of {nlayers} 7B-shaped layers in one launch")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 1000)
+    phases, kept = [], {}
+    x0 = torch.from_numpy((synth.activations(1, hidden, synth.BASE_SEED + 1001)[0].astype(np.float32) * 2.0 ** -10)
+                          .astype(np.float16).view(np.int16)).cuda().view(torch.float16)
+    prev_down = None
+    for layer in range(nlayers):
+        base = len(phases)
+        spec = [(hidden, None if layer == 0 else prev_down, [hidden] * 3), (hidden, (base, 0), [hidden]),
+                (hidden, (base + 1, 0), [ffn, ffn]), (ffn, (base + 2, 0), [hidden])]
+        for p, (cols, src, row_list) in enumerate(spec):
+            mats = []
+            for j, rows in enumerate(row_list):
+                wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+                n = iflow.packed_bytes(fmt, rows, cols)
+                packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+                iflow.quantize(fmt, wd, rows, cols, packed, n)
+                if layer in (0, nlayers - 1) and j == 0:
+                    idx = synth.sample_rows(rows, 16, synth.BASE_SEED + 1002 + p)
+                    kept[(base + p, j)] = (idx, wd[torch.from_numpy(idx).cuda()].cpu().numpy())
+                del wd
+                mats.append((packed, rows, torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")))
+            x = x0 if src is None else phases[src[0]][2][src[1]][2]
+            phases.append((cols, x, mats))
+        prev_down = (base + 3, 0)
+    nbytes = iflow.qgemv_chain_workspace_bytes([m[1] for ph in phases for m in ph[2]])
+    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
+    for it in range(2):
+        iflow.qgemv_chain(fmt, phases, ws, nbytes)
+    iflow.qgemv_chain_check(ws)
+    for p, (cols, x, mats) in enumerate(phases):
+        ys = [torch.empty((m[1],), dtype=torch.float16, device="cuda") for m in mats]
+        iflow.qgemv_multi(fmt, [m[0] for m in mats], [m[1] for m in mats], cols, x, ys)
+        torch.cuda.synchronize()
+        for j, m in enumerate(mats):
+            got, ref = m[2].cpu().numpy().view(np.uint16), ys[j].cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, ref), f"phase {p} matrix {j}: {(got != ref).sum()} of {got.size} differ"
+            if (p, j) in kept:
+                idx, w_rows = kept[(p, j)]
+                q, s, o = orc.quantize(ofmt, w_rows)
+                want = orc.gemm(orc.dequant(ofmt, q, s, o), x.cpu().numpy().view(np.uint16)[None, :])[0]
+                full = m[2].cpu().numpy().astype(np.float64)
+                assert np.isfinite(full).all(), f"phase {p}: non-finite outputs"
+                rms = np.sqrt(np.mean(full ** 2))
+                e = float(np.max(np.abs(full[idx] - want) / np.maximum(np.abs(want), rms)))
+                assert e <= TOL, f"phase {p}: rel err {e}"

@@ -433,3 +433,59 @@ def test_argument_errors(gpu):
     with pytest.raises(iflow.IflowError) as ei:
         iflow.qgemm(iflow.Q3H_B64, buf, 4, 128, w, 0, buf)
     assert ei.value.status == iflow.ERR_SHAPE
+
+
+# ---- the batched paths under HIP-graph replay: small-batch MFMA kernel (two launches for a split tall matrix included)
+#      and the batch-512 kernel, replayed with new activations, against eager results ----------------------------------
+@pytest.mark.parametrize("name", ["Q3H_B64", "Q8_B64"])
+def test_hip_graph_replay_of_batched_products(gpu, orc, name):
+    torch, iflow = gpu
+    fmt = iflow.FORMATS[name]
+    say(f"[case] graph replay of batched products, fmt={name}")
+    cases = [(600, 4096 + 128, 16), (16 * 256 * 2 + 9, 1024, 7), (200, 1024, 512)]
+    mats = []
+    for i, (rows, cols, batch) in enumerate(cases):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(synth.BASE_SEED + 980 + i)
+        wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        n = iflow.packed_bytes(fmt, rows, cols)
+        packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+        iflow.quantize(fmt, wd, rows, cols, packed, n)
+        X = torch.zeros((batch, cols), dtype=torch.float16, device="cuda")
+        Y = torch.zeros((batch, rows), dtype=torch.float16, device="cuda")
+        mats.append((rows, cols, batch, packed, X, Y))
+    stream = torch.cuda.Stream()
+
+    def run_all():
+        for rows, cols, batch, packed, X, Y in mats:
+            iflow.qgemm(fmt, packed, rows, cols, X, batch, Y, stream=stream.cuda_stream)
+
+    def fill(seed):
+        for i, (rows, cols, batch, packed, X, Y) in enumerate(mats):
+            X.copy_(torch.from_numpy(synth.activations(batch, cols, seed + i).view(np.int16)).cuda().view(torch.float16))
+            Y.fill_(float("nan"))
+
+    fill(synth.BASE_SEED + 985)
+    with torch.cuda.stream(stream):
+        run_all()
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            run_all()
+    for rep in range(3):
+        fill(synth.BASE_SEED + 990 + 10 * rep)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            run_all()
+        stream.synchronize()
+        eager = [m[5].cpu().numpy().view(np.uint16).copy() for m in mats]
+        for m in mats:
+            m[5].fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, m in enumerate(mats):
+            got = m[5].cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, eager[i]), f"replay {rep}, case {i}: {(got != eager[i]).sum()} outputs differ"
+            assert np.isfinite(m[5].cpu().numpy().astype(np.float32)).all()
