@@ -224,13 +224,15 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
 
     // weights of U rows of one strip: wave-uniform row base + per-lane offset, streamed once (nontemporal);
     // rows past the end repeat the last row and are not stored
-    auto load_step = [&](WRegs<KIND_Q3H>(&w)[U], int r0, int t) {
-        const int n_t = min(64, nbk - t * 64);                // blocks in this strip (ragged at the end of a row)
+    // (`none`: the request after the last step; it is issued all the same, with every lane on the matrix's first bytes,
+    // so that no load sits under a branch - see the wait counters - and nothing of any size is fetched in vain)
+    auto load_step = [&](WRegs<KIND_Q3H>(&w)[U], int r0, int t, bool none) {
+        const int n_t = none ? 0 : min(64, nbk - t * 64);     // blocks in this strip (ragged at the end of a row)
         // lanes past the end redo block 0 so that loads stay in bounds
         const uint32_t lane_off = (uint32_t)(lane * 16) & mask_lt(lane, n_t);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint8_t *p0 = packed + (int64_t)min(r0 + u, rows - 1) * row_stride + (int64_t)t * 2048;
+            const uint8_t *p0 = none ? packed : packed + (int64_t)min(r0 + u, rows - 1) * row_stride + (int64_t)t * 2048;
             const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + lane_off));
             const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + n_t * 16 + lane_off));
             w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
 
         // 2. request the weights of the first step (first row group, first strip of the pass)
         WRegs<KIND_Q3H> w[U];
-        load_step(w, rbase, t0);
+        load_step(w, rbase, t0, false);
 
         // 3. stage: permute the activations into decode order in LDS
         if (t0 > 0) __syncthreads();                          // the previous pass is done with LDS
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
             // next step's weights (wave-uniform control flow only)
             int gn = g, tn = ts + 1;
             if (tn == nt) { tn = 0; gn = g + 1; }
-            if (step + 1 < nsteps) load_step(w, rbase + gn * U, t0 + tn);
+            load_step(w, rbase + gn * U, t0 + tn, step + 1 >= nsteps);
 
             const bool group_done = ts == nt - 1 && t0 + nt == nstrips;
             if (group_done) {                                 // one reduction per row; lane 63 holds the sums
