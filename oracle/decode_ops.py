@@ -1,0 +1,61 @@
+"""Plain definitions of the modules that sit around a linear layer in one decode step, for the fused GEMV's parity tests.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/`` (and nothing in the GPU package); this module imports nothing from
+the GPU package either.
+
+arXiv 2401.08294 names these modules without formulas: its model-specification table (Section 2, the table of
+configurable modules) lists "rms" as the normalization function and "silu" as the activation function of the
+LLaMA-family models its decode step (Section 5, ``Infer()``) runs.  So the textbook definitions are written out:
+
+  rms normalization  y_k = x_k * g_k / sqrt(mean_j x_j^2 + eps)
+  silu               silu(a) = a / (1 + exp(-a))
+  gated feed-forward input  v_k = silu(a_k) * b_k      (a: "gate" projection, b: "up" projection)
+  residual           out_n = (W v)_n + r_n
+
+The fused kernel applies the normalization as (x_k * g_k) rounded to fp16, multiplied by the matrix, and the scalar
+1 / sqrt(mean x^2 + eps) applied to the fp32 row sums (the scalar commutes with the matrix product).  The functions
+below state exactly that split, in fp64, with fp16 roundings only where a value is stored as fp16.
+All fp16 inputs and outputs are uint16 bit patterns, like everywhere else in the oracle.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _f(h) -> np.ndarray:
+    return np.ascontiguousarray(h, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def _h(x) -> np.ndarray:
+    """fp64 -> fp16 bits, one rounding to nearest-even."""
+    return np.asarray(x, dtype=np.float64).astype(np.float16).view(np.uint16)
+
+
+def rms_scale(x16_bits, eps: float) -> float:
+    """1 / sqrt(mean_k x_k^2 + eps), fp64."""
+    x = _f(x16_bits)
+    return float(1.0 / np.sqrt(np.mean(x * x) + eps))
+
+
+def gain(x16_bits, g16_bits) -> np.ndarray:
+    """fp16(x_k * g_k): the product of two fp16 numbers is exact in fp64, so this is a single rounding."""
+    return _h(_f(x16_bits) * _f(g16_bits))
+
+
+def silu(a) -> np.ndarray:
+    a = np.asarray(a, dtype=np.float64)
+    return a / (1.0 + np.exp(-a))
+
+
+def silu_mul(a16_bits, b16_bits) -> np.ndarray:
+    """fp16(silu(a_k) * b_k)."""
+    return _h(silu(_f(a16_bits)) * _f(b16_bits))
+
+
+def fused_gemv(w16_bits, v16_bits, scale: float = 1.0, residual16_bits=None) -> np.ndarray:
+    """scale * (W' v) + residual in fp64 (W' fp16 [rows][cols], v fp16 [cols], residual fp16 [rows] or None)."""
+    w = _f(w16_bits)
+    y = scale * (w @ _f(v16_bits))
+    if residual16_bits is not None:
+        y = y + _f(residual16_bits)
+    return y

@@ -429,3 +429,63 @@ def test_qgemm_from_canonical_record(orc):
         full = x.astype(np.float64) @ w.astype(np.float64).T
         bound = {0: 0.01, 1: 0.01, 2: 0.12, 3: 0.15, 4: 0.25}[fmt]
         assert np.sqrt(np.mean((y - full) ** 2)) <= bound * np.sqrt(np.mean(full ** 2))
+
+
+# ---- the modules around a linear layer (oracle/decode_ops.py): pinned to library routines, closed forms and identities ----
+def _bits(x):
+    return np.asarray(x, dtype=np.float16).view(np.uint16)
+
+
+def test_rms_normalization_matches_the_library_routine_and_closed_forms():
+    import torch
+    from oracle import decode_ops as ops
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal(1000).astype(np.float16)
+    g = (1.0 + 0.1 * rng.standard_normal(1000)).astype(np.float16)
+    eps = 1e-5
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x.astype(np.float64)), (1000,),
+                                       weight=torch.from_numpy(g.astype(np.float64)), eps=eps).numpy()
+    mine = x.astype(np.float64) * g.astype(np.float64) * ops.rms_scale(_bits(x), eps)
+    assert np.max(np.abs(mine - ref)) <= 1e-12 * np.max(np.abs(ref))
+    # a constant vector: mean of squares is c^2
+    c = np.full(64, 3.0, np.float16)
+    assert abs(ops.rms_scale(_bits(c), 0.25) - 1.0 / np.sqrt(9.25)) < 1e-15
+    # scaling x by 2 halves the scale when eps is 0 (no dropped mean, no misplaced square)
+    assert abs(ops.rms_scale(_bits(2 * x), 0.0) * 2 - ops.rms_scale(_bits(x), 0.0)) < 1e-12
+    # the stored product x*g: exact in fp32, so fp32 multiply + one rounding is the same single rounding
+    want = (x.astype(np.float32) * g.astype(np.float32)).astype(np.float16).view(np.uint16)
+    assert np.array_equal(ops.gain(_bits(x), _bits(g)), want)
+    assert np.array_equal(ops.gain(_bits(x), _bits(np.ones(1000, np.float16))), _bits(x))
+
+
+def test_silu_matches_the_library_routine_and_identities():
+    import torch
+    from oracle import decode_ops as ops
+    rng = np.random.default_rng(78)
+    a = (3.0 * rng.standard_normal(2000)).astype(np.float16)
+    b = rng.standard_normal(2000).astype(np.float16)
+    ref = torch.nn.functional.silu(torch.from_numpy(a.astype(np.float64))).numpy()
+    assert np.max(np.abs(ops.silu(a.astype(np.float64)) - ref)) <= 1e-14
+    assert ops.silu(0.0) == 0.0
+    t = np.linspace(-12, 12, 97)
+    assert np.max(np.abs(ops.silu(t) - ops.silu(-t) - t)) < 1e-13          # silu(a) - silu(-a) = a
+    assert abs(float(ops.silu(30.0)) - 30.0) < 1e-10 and abs(float(ops.silu(-30.0))) < 1e-10
+    want = (ref * b.astype(np.float64)).astype(np.float16).view(np.uint16)
+    assert np.array_equal(ops.silu_mul(_bits(a), _bits(b)), want)
+    # gate and up are not interchangeable: silu acts on the first argument only
+    assert not np.array_equal(ops.silu_mul(_bits(a), _bits(b)), ops.silu_mul(_bits(b), _bits(a)))
+
+
+def test_fused_gemv_reduces_to_the_plain_product(orc):
+    from oracle import decode_ops as ops
+    rng = np.random.default_rng(79)
+    w = (0.05 * rng.standard_normal((37, 128))).astype(np.float16)
+    v = rng.standard_normal(128).astype(np.float16)
+    r = rng.standard_normal(37).astype(np.float16)
+    plain = orc.gemm(_bits(w), _bits(v))[0]
+    assert np.max(np.abs(ops.fused_gemv(_bits(w), _bits(v)) - plain)) < 1e-12
+    y = ops.fused_gemv(_bits(w), _bits(v), 0.37, _bits(r))
+    assert np.max(np.abs(y - (0.37 * plain + r.astype(np.float64)))) < 1e-12
+    # unit vector: column k of W', scaled, plus the residual
+    e = np.zeros(128, np.float16); e[5] = 1.0
+    assert np.max(np.abs(ops.fused_gemv(_bits(w), _bits(e), 2.0, _bits(r)) - (2.0 * w[:, 5].astype(np.float64) + r.astype(np.float64)))) < 1e-15
