@@ -113,6 +113,27 @@ iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t ro
 iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
                                  int64_t cols, const uint16_t *x, uint16_t *const *y, void *stream);
 
+/* iflow_qgemv_multi with the modules around the linear layer fused into the same launch (3.5-bit format only; other
+ * formats: IFLOW_ERR_FORMAT).  Section 2 lists the normalization and activation functions among the configurable
+ * modules of a decoder layer ("rms" and "silu" for the LLaMA family) and Section 5's Infer() applies them between
+ * the products; fused, the small kernels between the matrix products of a decode step disappear.
+ *   x_op = IFLOW_X_PLAIN:     y_i = W'_i x (+ residual_i)
+ *   x_op = IFLOW_X_RMS_GAIN:  rms normalization in front of the product.  aux = gains g [cols] fp16.
+ *                             y_i = fp16( (W'_i v) / sqrt(mean_k x_k^2 + eps) (+ residual_i) ), v_k = fp16(x_k g_k):
+ *                             the normalization's scalar is applied to the fp32 row sums, where it commutes with the
+ *                             product, so x is read once and no normalized copy of it is ever stored.
+ *   x_op = IFLOW_X_SILU_MUL:  the input of a gated feed-forward's last projection.  aux = second factor [cols] fp16.
+ *                             y_i = W'_i v (+ residual_i), v_k = fp16(silu(x_k) aux_k), silu(a) = a / (1 + exp(-a)),
+ *                             evaluated in fp32.
+ *   residual: HOST array of `count` device pointers ([rows[i]] fp16 each; entries may be null) or null for none;
+ *             the sum with the residual is rounded to fp16 once.  residual[i] may equal y[i] (in-place update of a
+ *             hidden state); it must not overlap x or aux.
+ * eps is used by IFLOW_X_RMS_GAIN only (must be >= 0 and finite); aux must be null for IFLOW_X_PLAIN. */
+typedef enum { IFLOW_X_PLAIN = 0, IFLOW_X_RMS_GAIN = 1, IFLOW_X_SILU_MUL = 2 } iflow_x_op_t;
+iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
+                                 int64_t cols, const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps,
+                                 const uint16_t *const *residual, uint16_t *const *y, void *stream);
+
 /* A chain of batch-1 products in ONE launch (3.5-bit format only): the decode step applies its projections one
  * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and
  * at 7B sizes each product is so short that the idle time between dependent launches costs as much as a third of

@@ -159,6 +159,41 @@ iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *c
     return device_status(iflow::launch_qgemv_multi((int)format, count, packed, rows, cols, x, y, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
+                                 int64_t cols, const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps,
+                                 const uint16_t *const *residual, uint16_t *const *y, void *stream)
+{
+    iflow::FormatInfo fi;
+    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
+    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;
+    if (count < 1 || count > 8) return IFLOW_ERR_SHAPE;
+    if (x_op != IFLOW_X_PLAIN && x_op != IFLOW_X_RMS_GAIN && x_op != IFLOW_X_SILU_MUL) return IFLOW_ERR_SHAPE;
+    if (!packed || !rows || !x || !y) return IFLOW_ERR_NULL;
+    if ((x_op == IFLOW_X_PLAIN) != (aux == nullptr)) return IFLOW_ERR_NULL;
+    if (x_op == IFLOW_X_RMS_GAIN && !(eps >= 0.0f && eps < 3.0e38f)) return IFLOW_ERR_SHAPE;
+    if (!aligned16(x) || (aux && !aligned16(aux))) return IFLOW_ERR_ALIGN;
+    auto overlaps = [](const void *p, int64_t pn, const void *q, int64_t qn) {
+        const uintptr_t a0 = (uintptr_t)p, b0 = (uintptr_t)q;
+        return a0 < b0 + (uintptr_t)qn && b0 < a0 + (uintptr_t)pn;
+    };
+    for (int i = 0; i < count; ++i) {
+        iflow_status_t st = check_shape(format, rows[i], cols, &fi);
+        if (st != IFLOW_OK) return st;
+        if (!packed[i] || !y[i]) return IFLOW_ERR_NULL;
+        if (!aligned16(packed[i]) || !aligned16(y[i])) return IFLOW_ERR_ALIGN;
+        // outputs are written while other workgroups still read x and aux
+        if (overlaps(y[i], rows[i] * 2, x, cols * 2) || (aux && overlaps(y[i], rows[i] * 2, aux, cols * 2))) return IFLOW_ERR_SHAPE;
+        if (residual && residual[i]) {
+            if (((uintptr_t)residual[i] & 1u) != 0) return IFLOW_ERR_ALIGN;
+            // a residual is read by the wavefront that later writes the same rows: equal to y[i] is fine, a shifted overlap is not
+            if (residual[i] != y[i] && overlaps(residual[i], rows[i] * 2, y[i], rows[i] * 2)) return IFLOW_ERR_SHAPE;
+            for (int j = 0; j < count; ++j)
+                if (j != i && y[j] && overlaps(residual[i], rows[i] * 2, y[j], rows[j] * 2)) return IFLOW_ERR_SHAPE;
+        }
+    }
+    return device_status(iflow::launch_qgemv_fused(count, packed, rows, cols, x, (int)x_op, aux, eps, residual, y, (hipStream_t)stream));
+}
+
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes)
 {
     if (!rows || !bytes) return IFLOW_ERR_NULL;

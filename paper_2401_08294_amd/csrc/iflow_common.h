@@ -138,6 +138,9 @@ hipError_t launch_calibration_copy(const void *src, void *dst, size_t bytes, hip
 hipError_t launch_calibration_read(const void *src, size_t bytes, void *sink, hipStream_t s);
 hipError_t launch_qgemv_multi(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols,
                               const uint16_t *x, uint16_t *const *y, hipStream_t s);
+hipError_t launch_qgemv_fused(int count, const void *const *packed, const int64_t *rows, int64_t cols, const uint16_t *x,
+                              int x_op, const uint16_t *aux, float eps, const uint16_t *const *residual, uint16_t *const *y,
+                              hipStream_t s);
 size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
 hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
                               const void *const *packed, const int64_t *rows, uint16_t *const *y,

@@ -177,6 +177,13 @@ struct GemvGroup {
     int count;
 };
 
+// What the fused variant (template parameter OPS) does to the activations on their way into LDS and to the row sums
+// on their way out; x_op values are iflow_x_op_t's.  The plain instantiations never read it.
+struct GemvOps {
+    const uint16_t *residual[IFLOW_MAX_GROUP];                // per matrix: added to the outputs, or null
+    float eps;
+};
+
 // ---- Q3H: workgroup-shared activations ----------------------------------------------------------------
 // The activations are the same for every wavefront, and arranging a strip of them for the decode costs
 // about as much as one row of weights.  So a workgroup does it once: its threads permute the activations
@@ -197,13 +204,24 @@ struct GemvGroup {
 // One launch can serve several weight matrices that share the activation vector and the number of columns
 // (the q/k/v or the gate/up projections of a decoder layer): workgroup ranges are assigned to the matrices
 // in order, each matrix keeps its own packed buffer and output vector.
-template <int NB, int U, bool MULTI>
+//
+// OPS (batch 1 only) fuses the modules around the linear layer into the same launch (Section 2 lists them as the
+// configurable pieces of a decoder layer, Section 5's Infer() runs them between the products):
+//   IFLOW_X_RMS_GAIN   the staged activations are fp16(x_k g_k) and every row sum is multiplied by
+//                      1 / sqrt(mean x^2 + eps) - rms normalization, with its scalar moved behind the product;
+//   IFLOW_X_SILU_MUL   the staged activations are fp16(silu(x_k) aux_k) - the input of a gated feed-forward's last layer;
+//   residual           out_n = fp16(row sum + residual_n).
+template <int NB, int U, bool MULTI, bool OPS = false>
 __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const uint8_t *__restrict__ packed0, uint16_t *__restrict__ y0,
                                                         const uint16_t *__restrict__ X, int rows0, int cols, int nbk, int nstrips,
-                                                        int T, int G, int waves, const GemvGroup grp)
+                                                        int T, int G, int waves, int x_op, const uint16_t *__restrict__ aux,
+                                                        const GemvGroup grp, const GemvOps ops)
 {
+    static_assert(!OPS || NB == 1, "the fused variant is built for one activation vector");
     // The single-matrix arguments come first so that they fit the kernel-argument registers the hardware can preload
     // at wavefront start (no scalar load, no wait, before the first address is formed); `grp` is read only when MULTI.
+    // x_op and aux (used by the fused variant only) are the last two that fit: the staging needs them at once, and a
+    // scalar load that misses its cache would hold up the first activation loads.
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int SLOT_BYTES = 8 * 64 * 16 + 64 * 8;          // xs + sums of one (strip, batch column)
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -246,6 +264,10 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
 #pragma unroll
         for (int u = 0; u < U; ++u) part[b][u] = 0.f;
 
+    // fused variant: lane l holds the residual of the wavefront's l-th row (read back with v_readlane at the store);
+    // ssq collects this thread's share of sum x^2; out_scale is the normalization's scalar once all of x has been seen
+    float res_lane = 0.f, ssq = 0.f, out_scale = 1.0f;
+
     for (int t0 = 0; t0 < nstrips; t0 += T) {                 // one pass unless the row is longer than T strips (then G is 1)
         const int nt = min(T, nstrips - t0);                  // strips staged in this pass
 
@@ -254,17 +276,40 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         //    that feed decode slots 4qd..4qd+3 of lane blk.  (NB is a compile-time constant: no integer division on
         //    the way to the first load.)
         const int nchunks = NB * nt * 256;
-        auto chunk_src = [&](int c) {
+        auto chunk_src_of = [&](const uint16_t *base, int c) {
             const int cc = c & 255, ts = (c >> 8) / NB, bcol = (c >> 8) % NB;
             const int n_t = min(64, nbk - (t0 + ts) * 64);
             const int ccl = cc & (int)mask_lt(cc >> 2, n_t);  // chunks past the end of the row read chunk 0 and are zeroed
-            return reinterpret_cast<const uint4 *>(X + (int64_t)bcol * cols + (int64_t)(t0 + ts) * 4096 + ccl * 16);
+            return reinterpret_cast<const uint4 *>(base + (int64_t)bcol * cols + (int64_t)(t0 + ts) * 4096 + ccl * 16);
         };
-        auto chunk_put = [&](int c, const uint4 q0, const uint4 q1) {
+        auto chunk_src = [&](int c) { return chunk_src_of(X, c); };
+        // the fused variant's second operand of a chunk (gains or the second factor); the activations themselves when there is none
+        const uint16_t *aux_base = (OPS && x_op != IFLOW_X_PLAIN) ? aux : X;
+        auto chunk_put = [&](int c, const uint4 q0, const uint4 q1, const uint4 a0, const uint4 a1) {
             const int cc = c & 255, ts = (c >> 8) / NB, bcol = (c >> 8) % NB, blk = cc >> 2, qd = cc & 3;
             const int n_t = min(64, nbk - (t0 + ts) * 64);
             const uint32_t live = mask_lt(blk, n_t);              // all ones inside the row: columns past its end count as zero
-            const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
+            uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
+            if (OPS) {
+                const uint32_t av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                if (x_op == IFLOW_X_RMS_GAIN) {           // (uniform) x_k g_k: exact product, one rounding to fp16
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        ssq = dot2(as_h2(n[k]), as_h2(n[k]), ssq);
+                        n[k] = as_u32(as_h2(n[k]) * as_h2(av[k]));
+                    }
+                } else if (x_op == IFLOW_X_SILU_MUL) {    // silu(x_k) aux_k in fp32, one rounding to fp16
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const half2_t xa = as_h2(n[k]), xb = as_h2(av[k] & live);
+                        const float g0 = (float)xa.x, g1 = (float)xa.y;
+                        // (hardware reciprocal: 1 ulp of fp32, far below the fp16 rounding that follows)
+                        const float v0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * (float)xb.x, v1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * (float)xb.y;
+                        const half2_t r = {(half_t)v0, (half_t)v1};
+                        n[k] = as_u32(r);
+                    }
+                }
+            }
             const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
             uint32_t e[4], o[4];
             float se = 0.f, so = 0.f;
@@ -287,20 +332,41 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         const bool has_chunk = c0 < nchunks;                  // whole wavefronts have a first chunk or not
         const uint4 *src0 = chunk_src(c0 & (int)mask_lt(c0, nchunks));
         const uint4 xq0 = src0[0], xq1 = src0[1];
+        const uint4 *asrc0 = OPS ? chunk_src_of(aux_base, c0 & (int)mask_lt(c0, nchunks)) : src0;
+        const uint4 aq0 = OPS ? asrc0[0] : xq0, aq1 = OPS ? asrc0[1] : xq1;
 
         // 2. request the weights of the first step (first row group, first strip of the pass)
         WRegs<KIND_Q3H> w[U];
         load_step(w, rbase, t0, false);
+        if (OPS && t0 == 0) {                                 // (no branch around the load: without a residual it reads x[0] and drops it)
+            const uint16_t *res = ops.residual[m];
+            const uint16_t *rp = res != nullptr ? res + min(rbase + min(lane, G * U - 1), rows - 1) : X;
+            const float rv = (float)as_h(*rp);
+            res_lane = res != nullptr ? rv : 0.f;
+        }
 
         // 3. stage: permute the activations into decode order in LDS
         if (t0 > 0) __syncthreads();                          // the previous pass is done with LDS
-        if (has_chunk) chunk_put(c0, xq0, xq1);
+        if (has_chunk) chunk_put(c0, xq0, xq1, aq0, aq1);
 #pragma unroll 1
         for (int c = c0 + waves * 64; c < nchunks; c += waves * 64) {
             const uint4 *src = chunk_src(c);
-            chunk_put(c, src[0], src[1]);
+            const uint4 *asrc = OPS ? chunk_src_of(aux_base, c) : src;
+            chunk_put(c, src[0], src[1], asrc[0], asrc[1]);
+        }
+        // fused normalization: the wavefronts' shares of sum x^2 go through sixteen floats behind the staged strips; the
+        // sum is complete in the pass that stages the row's last strip, which is also the pass that stores the outputs
+        float *ssq_part = reinterpret_cast<float *>(lds + (size_t)T * NB * SLOT_BYTES);
+        if (OPS && t0 + nt == nstrips) {
+            const float wsum = wave_sum_to_lane63(ssq);
+            if (lane == 63) ssq_part[wave] = wsum;
         }
         __syncthreads();
+        if (OPS && t0 + nt == nstrips && x_op == IFLOW_X_RMS_GAIN) {
+            const float mine = lane < waves ? ssq_part[lane] : 0.f;
+            const float total = wave_sum(mine);
+            out_scale = 1.0f / __builtin_sqrtf(total / (float)cols + ops.eps);
+        }
 
         // 4. steps = (row group, strip): activation registers from LDS, then each row as its loads land, while
         //    the next step's weights are already requested
@@ -346,7 +412,11 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
                 for (int b = 0; b < NB; ++b)
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const float sum = wave_sum_to_lane63(v[b][u]);
+                        float sum = wave_sum_to_lane63(v[b][u]);
+                        if (OPS) {
+                            const float res = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, res_lane), g * U + u));
+                            sum = __builtin_fmaf(sum, out_scale, res);
+                        }
                         if (lane == 63 && r0 + u < rows) Y[(int64_t)b * rows + r0 + u] = as_u16((half_t)sum);
                         part[b][u] = 0.f;
                     }
@@ -374,22 +444,23 @@ static int pick_rows_per_wg(int64_t rows, int waves_per_wg)
     return (int)r;
 }
 
-template <int NB, int U>
-static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, int waves, int G, hipStream_t s)
+template <int NB, int U, bool OPS = false>
+static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, int waves, int G, hipStream_t s, const GemvOps &ops = GemvOps(),
+                              int x_op = IFLOW_X_PLAIN, const uint16_t *aux = nullptr)
 {
     constexpr int SLOT = 8 * 64 * 16 + 64 * 8;
     const int nbk = (int)(cols / 64);
     const int nstrips = (nbk + 63) / 64;
     int T = (152 * 1024) / (SLOT * NB);
     if (T > nstrips) T = nstrips;
-    const size_t lds = (size_t)T * NB * SLOT;
+    const size_t lds = (size_t)T * NB * SLOT + (OPS ? 64 : 0);  // (fused variant: sixteen floats for the sum of squares)
     static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
-        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false>),
+        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false, OPS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (r == hipSuccess)
-            r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true>),
+            r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true, OPS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         return r;
     });
@@ -403,11 +474,11 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
     }
     if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     if (grp.count == 1)
-        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, grp);
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false, OPS>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, x_op, aux, grp, ops);
     else
-        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, true>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, grp);
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, true, OPS>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, x_op, aux, grp, ops);
     return hipGetLastError();
 }
 
@@ -415,8 +486,9 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
 // up to T strips (8.5 KiB of LDS per strip and batch column, at most 152 KiB).  Long rows and small problems
 // get larger workgroups (the staging is paid once per workgroup); tall problems let a wavefront walk several
 // row groups.
-template <int NB>
-static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t *X, hipStream_t s)
+template <int NB, bool OPS = false>
+static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t *X, hipStream_t s, const GemvOps &ops = GemvOps(),
+                            int x_op = IFLOW_X_PLAIN, const uint16_t *aux = nullptr)
 {
     const int nstrips = (int)((cols / 64 + 63) / 64);
     int64_t rows = 0;
@@ -427,7 +499,7 @@ static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t 
     if (G < 1) G = 1;
     if (G > 3) G = 3;
     // rows in flight per wavefront: two, or one where 32 activation registers per batch column leave no room
-    if (NB <= 2) return q3h_launch_u<NB, 2>(grp, cols, X, waves, G, s);
+    if (NB <= 2) return q3h_launch_u<NB, 2, OPS>(grp, cols, X, waves, G, s, ops, x_op, aux);
     return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
 }
 
@@ -493,6 +565,24 @@ hipError_t launch_qgemv_multi(int format, int count, const void *const *packed, 
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// The fused variant: `count` 3.5-bit matrices that share x, the operation on x and its second operand; a residual per
+// matrix (null: none).
+hipError_t launch_qgemv_fused(int count, const void *const *packed, const int64_t *rows, int64_t cols, const uint16_t *x,
+                              int x_op, const uint16_t *aux, float eps, const uint16_t *const *residual, uint16_t *const *y,
+                              hipStream_t s)
+{
+    if (count < 1 || count > IFLOW_MAX_GROUP) return hipErrorInvalidValue;
+    GemvGroup grp = {};
+    GemvOps ops = {};
+    for (int i = 0; i < count; ++i) {
+        grp.packed[i] = static_cast<const uint8_t *>(packed[i]); grp.y[i] = y[i]; grp.rows[i] = (int)rows[i];
+        ops.residual[i] = residual ? residual[i] : nullptr;
+    }
+    grp.count = count;
+    ops.eps = eps;
+    return q3h_launch<1, true>(grp, cols, x, s, ops, x_op, aux);
 }
 
 hipError_t launch_qgemv(int format, const void *packed, int64_t rows, int64_t cols,

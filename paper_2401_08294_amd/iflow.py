@@ -57,6 +57,8 @@ def lib():
         L.iflow_calibration_copy.argtypes = [p, p, sz, p]
         L.iflow_calibration_read.argtypes = [p, sz, p, p]
         L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
+        L.iflow_qgemv_fused.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.c_int, p, C.c_float,
+                                        C.POINTER(p), C.POINTER(p), p]
         L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
         L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
                                         C.POINTER(i64), C.POINTER(p), p, sz, p]
@@ -145,6 +147,24 @@ def qgemv_multi(fmt: int, packed_list, rows_list, cols: int, x, y_list, stream=N
     ys = (C.c_void_p * n)(*[_ptr(t) for t in y_list])
     rs = (C.c_int64 * n)(*[int(r) for r in rows_list])
     _check(lib().iflow_qgemv_multi(fmt, n, pk, rs, cols, _ptr(x), ys, _stream(stream)), "iflow_qgemv_multi")
+
+
+X_PLAIN, X_RMS_GAIN, X_SILU_MUL = 0, 1, 2
+
+
+def qgemv_fused(fmt: int, packed_list, rows_list, cols: int, x, y_list, x_op: int = X_PLAIN, aux=None, eps: float = 0.0,
+                residual_list=None, stream=None) -> None:
+    """qgemv_multi with rms normalization (aux = gains) or the silu-gated input (aux = second factor) in front of the
+    product and an optional residual per matrix behind it, in the same launch (3.5-bit format)."""
+    n = len(packed_list)
+    pk = (C.c_void_p * n)(*[_ptr(t) for t in packed_list])
+    ys = (C.c_void_p * n)(*[_ptr(t) for t in y_list])
+    rs = (C.c_int64 * n)(*[int(r) for r in rows_list])
+    res = None
+    if residual_list is not None:
+        res = (C.c_void_p * n)(*[(_ptr(t) if t is not None else None) for t in residual_list])
+    _check(lib().iflow_qgemv_fused(fmt, n, pk, rs, cols, _ptr(x), x_op, _ptr(aux) if aux is not None else None, eps, res, ys,
+                                   _stream(stream)), "iflow_qgemv_fused")
 
 
 def qgemv_chain_workspace_bytes(rows_list) -> int:

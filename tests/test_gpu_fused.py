@@ -1,0 +1,141 @@
+"""GPU parity of iflow_qgemv_fused: rms normalization or the silu-gated input in front of the 3.5-bit product and a
+residual behind it, in one launch, against the plain definitions in oracle/decode_ops.py."""
+import numpy as np
+import pytest
+
+from paper_2401_08294_amd import synth
+from test_gpu_parity import TOL, gpu, gpu_quantize, say  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def dev16(torch, bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.float16)
+
+
+def bits_of(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def err(y_bits, yref):
+    y = y_bits.view(np.float16).astype(np.float64)
+    rms = np.sqrt(np.mean(yref ** 2))
+    return float(np.max(np.abs(y - yref) / np.maximum(np.abs(yref), max(rms, 1e-30))))
+
+
+def make(torch, iflow, orc, rows, cols, seed, sigma=0.02):
+    w = synth.weights(rows, cols, sigma, seed)
+    packed, _ = gpu_quantize(torch, iflow, iflow.Q3H_B64, w)
+    q, s, o = orc.quantize(orc.Q3H_B64, w)
+    return packed, orc.dequant(orc.Q3H_B64, q, s, o)
+
+
+@pytest.mark.parametrize("rows,cols", [(300, 1024), (1000, 4096 + 64), (37, 64), (40, 18 * 4096 + 64)])
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_rms_gain_in_front_of_the_product(gpu, orc, rows, cols, with_residual):
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    say(f"[case] fused rms gain rows={rows} cols={cols} residual={with_residual}")
+    packed, wdeq = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 1100 + rows)
+    x = synth.activations(1, cols, synth.BASE_SEED + 1101)[0].view(np.uint16)
+    g = (1.0 + 0.2 * np.random.default_rng(synth.BASE_SEED + 1102).standard_normal(cols)).astype(np.float16).view(np.uint16)
+    r = synth.activations(1, rows, synth.BASE_SEED + 1103)[0].view(np.uint16) if with_residual else None
+    eps = 1e-5
+    y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
+    iflow.qgemv_fused(iflow.Q3H_B64, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_RMS_GAIN, dev16(torch, g), eps,
+                      [dev16(torch, r)] if with_residual else None)
+    torch.cuda.synchronize()
+    yref = ops.fused_gemv(wdeq, ops.gain(x, g), ops.rms_scale(x, eps), r)
+    e = err(bits_of(y), yref)
+    say(f"        max rel err {e:.3e}")
+    assert np.isfinite(y.cpu().numpy().astype(np.float32)).all() and e <= TOL
+
+
+@pytest.mark.parametrize("rows,cols", [(300, 1024), (520, 11008)])
+def test_silu_gated_input_and_in_place_residual(gpu, orc, rows, cols):
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    say(f"[case] fused silu*mul rows={rows} cols={cols}, residual in place")
+    packed, wdeq = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 1200 + rows)
+    a = (synth.activations(1, cols, synth.BASE_SEED + 1201)[0].astype(np.float32) * 2.5).astype(np.float16).view(np.uint16)
+    b = synth.activations(1, cols, synth.BASE_SEED + 1202)[0].view(np.uint16)
+    h = synth.activations(1, rows, synth.BASE_SEED + 1203)[0].view(np.uint16)
+    hidden = dev16(torch, h).clone()                           # updated in place: residual and output are the same buffer
+    iflow.qgemv_fused(iflow.Q3H_B64, [packed], [rows], cols, dev16(torch, a), [hidden], iflow.X_SILU_MUL, dev16(torch, b), 0.0, [hidden])
+    torch.cuda.synchronize()
+    yref = ops.fused_gemv(wdeq, ops.silu_mul(a, b), 1.0, h)
+    e = err(bits_of(hidden), yref)
+    say(f"        max rel err {e:.3e}")
+    assert e <= TOL
+
+
+def test_two_matrices_share_the_normalized_input_and_plain_with_residual(gpu, orc):
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    rows = [700, 333]
+    cols = 2048
+    say("[case] fused: two matrices behind one rms gain; plain product with residual")
+    mats = [make(torch, iflow, orc, r, cols, synth.BASE_SEED + 1300 + r) for r in rows]
+    x = synth.activations(1, cols, synth.BASE_SEED + 1301)[0].view(np.uint16)
+    g = (0.5 + np.random.default_rng(synth.BASE_SEED + 1302).random(cols)).astype(np.float16).view(np.uint16)
+    res1 = synth.activations(1, rows[1], synth.BASE_SEED + 1303)[0].view(np.uint16)
+    ys = [torch.full((r,), float("nan"), dtype=torch.float16, device="cuda") for r in rows]
+    iflow.qgemv_fused(iflow.Q3H_B64, [m[0] for m in mats], rows, cols, dev16(torch, x), ys, iflow.X_RMS_GAIN, dev16(torch, g), 1e-6,
+                      [None, dev16(torch, res1)])
+    torch.cuda.synchronize()
+    v, sc = ops.gain(x, g), ops.rms_scale(x, 1e-6)
+    assert err(bits_of(ys[0]), ops.fused_gemv(mats[0][1], v, sc, None)) <= TOL
+    assert err(bits_of(ys[1]), ops.fused_gemv(mats[1][1], v, sc, res1)) <= TOL
+    # no operation on x: equals iflow_qgemv when there is no residual, bit for bit
+    y0 = torch.empty((rows[0],), dtype=torch.float16, device="cuda")
+    y1 = torch.empty((rows[0],), dtype=torch.float16, device="cuda")
+    iflow.qgemv_fused(iflow.Q3H_B64, [mats[0][0]], [rows[0]], cols, dev16(torch, x), [y0])
+    iflow.qgemv(iflow.Q3H_B64, mats[0][0], rows[0], cols, dev16(torch, x), y1)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(y0), bits_of(y1))
+    res0 = synth.activations(1, rows[0], synth.BASE_SEED + 1304)[0].view(np.uint16)
+    iflow.qgemv_fused(iflow.Q3H_B64, [mats[0][0]], [rows[0]], cols, dev16(torch, x), [y0], residual_list=[dev16(torch, res0)])
+    torch.cuda.synchronize()
+    assert err(bits_of(y0), ops.fused_gemv(mats[0][1], x, 1.0, res0)) <= TOL
+
+
+def test_feed_forward_block_at_7b_size(gpu, orc):
+    """h -> rms gain -> gate, up (one launch) -> silu(gate) * up -> down + h (one launch): two launches, no other kernel.
+    Weights drawn on the device; sampled rows of each stage against the oracle, given the stage's actual inputs."""
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    fmt, ofmt = iflow.Q3H_B64, orc.Q3H_B64
+    hidden, ffn = 4096, 11008
+    say("[case] fused feed-forward block 4096 -> 2 x 11008 -> 4096")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 1400)
+    mats = []
+    for i, (rows, cols) in enumerate([(ffn, hidden), (ffn, hidden), (hidden, ffn)]):
+        wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        n = iflow.packed_bytes(fmt, rows, cols)
+        packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+        iflow.quantize(fmt, wd, rows, cols, packed, n)
+        idx = synth.sample_rows(rows, 40, synth.BASE_SEED + 1401 + i)
+        q, s, o = orc.quantize(ofmt, wd[torch.from_numpy(idx).cuda()].cpu().numpy())
+        mats.append((packed, rows, cols, idx, orc.dequant(ofmt, q, s, o)))
+        del wd
+    h = synth.activations(1, hidden, synth.BASE_SEED + 1405)[0].view(np.uint16)
+    g = (1.0 + 0.1 * np.random.default_rng(synth.BASE_SEED + 1406).standard_normal(hidden)).astype(np.float16).view(np.uint16)
+    hd, gd = dev16(torch, h), dev16(torch, g)
+    gate = torch.empty((ffn,), dtype=torch.float16, device="cuda")
+    up = torch.empty((ffn,), dtype=torch.float16, device="cuda")
+    out = torch.empty((hidden,), dtype=torch.float16, device="cuda")
+    iflow.qgemv_fused(fmt, [mats[0][0], mats[1][0]], [ffn, ffn], hidden, hd, [gate, up], iflow.X_RMS_GAIN, gd, 1e-5)
+    iflow.qgemv_fused(fmt, [mats[2][0]], [hidden], ffn, gate, [out], iflow.X_SILU_MUL, up, 0.0, [hd])
+    torch.cuda.synchronize()
+    v, sc = ops.gain(h, g), ops.rms_scale(h, 1e-5)
+    for t, m in ((gate, mats[0]), (up, mats[1])):
+        full = t.cpu().numpy().astype(np.float64)
+        want = ops.fused_gemv(m[4], v, sc, None)
+        assert np.max(np.abs(full[m[3]] - want) / np.maximum(np.abs(want), np.sqrt(np.mean(full ** 2)))) <= TOL
+    m = mats[2]
+    full = out.cpu().numpy().astype(np.float64)
+    want = ops.fused_gemv(m[4], ops.silu_mul(bits_of(gate), bits_of(up)), 1.0, h[m[3]])
+    e = float(np.max(np.abs(full[m[3]] - want) / np.maximum(np.abs(want), np.sqrt(np.mean(full ** 2)))))
+    say(f"        down + residual: max rel err on sampled rows {e:.3e}")
+    assert np.isfinite(full).all() and e <= TOL

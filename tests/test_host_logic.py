@@ -154,3 +154,31 @@ def test_q4_q8_magic_number_identities():
     for v in range(256):
         b = np.array([0x6400 | v], np.uint16).view(np.float16)[0]
         assert float(b) == 1024 + v
+
+
+def test_fused_validation_happens_before_any_launch(iflow):
+    """iflow_qgemv_fused: format, operand and overlap rules are checked on the host (no launch on any error)."""
+    L = iflow.lib()
+    base = 0x100000                                                              # aligned, never dereferenced
+
+    def call(fmt, rows, cols, x, y, x_op=0, aux=None, eps=0.0, residual=None, packed=None):
+        n = len(rows)
+        res = None if residual is None else (C.c_void_p * n)(*residual)
+        return L.iflow_qgemv_fused(fmt, n, (C.c_void_p * n)(*(packed or [base * 2] * n)), (C.c_int64 * n)(*rows), cols, x, x_op, aux,
+                                   C.c_float(eps), res, (C.c_void_p * n)(*y), None)
+
+    x, y0, y1, aux = base, base * 3, base * 4, base * 5
+    assert call(3, [8], 64, x, [y0]) == iflow.ERR_FORMAT                         # 3.5-bit format only
+    assert call(4, [8], 64, x, [y0], x_op=7, aux=aux) == iflow.ERR_SHAPE         # unknown operation
+    assert call(4, [8], 64, x, [y0], x_op=iflow.X_RMS_GAIN) == iflow.ERR_NULL    # gains missing
+    assert call(4, [8], 64, x, [y0], x_op=iflow.X_PLAIN, aux=aux) == iflow.ERR_NULL   # a second operand nobody asked for
+    assert call(4, [8], 64, x, [y0], x_op=iflow.X_RMS_GAIN, aux=aux, eps=-1.0) == iflow.ERR_SHAPE
+    assert call(4, [8], 64, x, [y0], x_op=iflow.X_RMS_GAIN, aux=aux, eps=float("nan")) == iflow.ERR_SHAPE
+    assert call(4, [8], 64, x, [y0], x_op=iflow.X_SILU_MUL, aux=aux + 2) == iflow.ERR_ALIGN
+    assert call(4, [8], 100, x, [y0]) == iflow.ERR_SHAPE                         # columns not a multiple of the block
+    assert call(4, [8] * 9, 64, x, [y0] * 9) == iflow.ERR_SHAPE                  # more than eight matrices
+    assert call(4, [8], 64, x, [x + 16]) == iflow.ERR_SHAPE                      # output inside the activations
+    assert call(4, [8], 64, x, [y0], x_op=iflow.X_SILU_MUL, aux=y0) == iflow.ERR_SHAPE    # output is the second operand
+    assert call(4, [8], 64, x, [y0], residual=[y0 + 2]) == iflow.ERR_SHAPE       # residual shifted against its own output
+    assert call(4, [8, 8], 64, x, [y0, y1], residual=[y1, None]) == iflow.ERR_SHAPE       # residual is another matrix's output
+    assert call(4, [8], 64, x, [y0], residual=[y0 + 1]) == iflow.ERR_ALIGN
