@@ -177,11 +177,11 @@ struct GemvGroup {
     int count;
 };
 
-// What the fused variant (template parameter OPS) does to the activations on their way into LDS and to the row sums
+// What the fused variant (template parameter XOP >= 0) does to the activations on their way into LDS and to the row sums
 // on their way out; x_op values are iflow_x_op_t's.  The plain instantiations never read it.
 struct GemvOps {
     const uint16_t *residual[IFLOW_MAX_GROUP];                // per matrix: added to the outputs, or null
-    float eps;
+    float eps[IFLOW_MAX_GROUP];                               // the same value for every matrix (read next to its residual, see the kernel)
 };
 
 // ---- Q3H: workgroup-shared activations ----------------------------------------------------------------
@@ -205,19 +205,27 @@ struct GemvOps {
 // (the q/k/v or the gate/up projections of a decoder layer): workgroup ranges are assigned to the matrices
 // in order, each matrix keeps its own packed buffer and output vector.
 //
-// OPS (batch 1 only) fuses the modules around the linear layer into the same launch (Section 2 lists them as the
+// XOP >= 0 (batch 1 only) fuses the modules around the linear layer into the same launch (Section 2 lists them as the
 // configurable pieces of a decoder layer, Section 5's Infer() runs them between the products):
 //   IFLOW_X_RMS_GAIN   the staged activations are fp16(x_k g_k) and every row sum is multiplied by
 //                      1 / sqrt(mean x^2 + eps) - rms normalization, with its scalar moved behind the product;
 //   IFLOW_X_SILU_MUL   the staged activations are fp16(silu(x_k) aux_k) - the input of a gated feed-forward's last layer;
 //   residual           out_n = fp16(row sum + residual_n).
-template <int NB, int U, bool MULTI, bool OPS = false>
+template <int NB, int U, bool MULTI, int XOP = -1>
 __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const uint8_t *__restrict__ packed0, uint16_t *__restrict__ y0,
                                                         const uint16_t *__restrict__ X, int rows0, int cols, int nbk, int nstrips,
-                                                        int T, int G, int waves, int x_op, const uint16_t *__restrict__ aux,
+                                                        int tgw, int x_op, const uint16_t *__restrict__ aux,
                                                         const GemvGroup grp, const GemvOps ops)
 {
+    // XOP < 0: the plain kernel.  XOP = an iflow_x_op_t: the fused variant for that operation (one instantiation each, so
+    // that a launch runs through no code of the operations it does not perform: a launch is short, and every taken
+    // branch over a block of cold code costs an instruction-cache miss)
+    constexpr bool OPS = XOP >= 0;
     static_assert(!OPS || NB == 1, "the fused variant is built for one activation vector");
+    (void)x_op;
+    // strips staged per pass, row groups per wavefront, wavefronts per workgroup: packed into one argument (8 bits each)
+    // so that the fourteen argument registers reach as far as `aux`
+    const int T = tgw & 255, G = (tgw >> 8) & 255, waves = tgw >> 16;
     // The single-matrix arguments come first so that they fit the kernel-argument registers the hardware can preload
     // at wavefront start (no scalar load, no wait, before the first address is formed); `grp` is read only when MULTI.
     // x_op and aux (used by the fused variant only) are the last two that fit: the staging needs them at once, and a
@@ -266,7 +274,9 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
 
     // fused variant: lane l holds the residual of the wavefront's l-th row (read back with v_readlane at the store);
     // ssq collects this thread's share of sum x^2; out_scale is the normalization's scalar once all of x has been seen
-    float res_lane = 0.f, ssq = 0.f, out_scale = 1.0f;
+    float ssq = 0.f, out_scale = 1.0f, fused_eps = 0.f;
+    uint16_t res_raw = 0;                                     // fp16 bits of the lane's residual (a 16-bit variable: widened where it is used)
+    uint32_t res_keep = 0;                                    // 0xFFFF when there is a residual
 
     for (int t0 = 0; t0 < nstrips; t0 += T) {                 // one pass unless the row is longer than T strips (then G is 1)
         const int nt = min(T, nstrips - t0);                  // strips staged in this pass
@@ -284,7 +294,7 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         };
         auto chunk_src = [&](int c) { return chunk_src_of(X, c); };
         // the fused variant's second operand of a chunk (gains or the second factor); the activations themselves when there is none
-        const uint16_t *aux_base = (OPS && x_op != IFLOW_X_PLAIN) ? aux : X;
+        const uint16_t *aux_base = (XOP > IFLOW_X_PLAIN) ? aux : X;
         auto chunk_put = [&](int c, const uint4 q0, const uint4 q1, const uint4 a0, const uint4 a1) {
             const int cc = c & 255, ts = (c >> 8) / NB, bcol = (c >> 8) % NB, blk = cc >> 2, qd = cc & 3;
             const int n_t = min(64, nbk - (t0 + ts) * 64);
@@ -292,13 +302,13 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
             uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
             if (OPS) {
                 const uint32_t av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-                if (x_op == IFLOW_X_RMS_GAIN) {           // (uniform) x_k g_k: exact product, one rounding to fp16
+                if (XOP == IFLOW_X_RMS_GAIN) {           // (uniform) x_k g_k: exact product, one rounding to fp16
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         ssq = dot2(as_h2(n[k]), as_h2(n[k]), ssq);
                         n[k] = as_u32(as_h2(n[k]) * as_h2(av[k]));
                     }
-                } else if (x_op == IFLOW_X_SILU_MUL) {    // silu(x_k) aux_k in fp32, one rounding to fp16
+                } else if (XOP == IFLOW_X_SILU_MUL) {    // silu(x_k) aux_k in fp32, one rounding to fp16
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         const half2_t xa = as_h2(n[k]), xb = as_h2(av[k] & live);
@@ -332,17 +342,29 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         const bool has_chunk = c0 < nchunks;                  // whole wavefronts have a first chunk or not
         const uint4 *src0 = chunk_src(c0 & (int)mask_lt(c0, nchunks));
         const uint4 xq0 = src0[0], xq1 = src0[1];
-        const uint4 *asrc0 = OPS ? chunk_src_of(aux_base, c0 & (int)mask_lt(c0, nchunks)) : src0;
-        const uint4 aq0 = OPS ? asrc0[0] : xq0, aq1 = OPS ? asrc0[1] : xq1;
+        constexpr bool HAS_AUX = XOP > IFLOW_X_PLAIN;          // the operation has a second operand
+        const uint4 *asrc0 = HAS_AUX ? chunk_src_of(aux_base, c0 & (int)mask_lt(c0, nchunks)) : src0;
+        const uint4 aq0 = HAS_AUX ? asrc0[0] : xq0, aq1 = HAS_AUX ? asrc0[1] : xq1;
 
         // 2. request the weights of the first step (first row group, first strip of the pass)
         WRegs<KIND_Q3H> w[U];
         load_step(w, rbase, t0, false);
-        if (OPS && t0 == 0) {                                 // (no branch around the load: without a residual it reads x[0] and drops it)
-            const uint16_t *res = ops.residual[m];
+        // (fused variant) The residual pointers and eps arrive by scalar loads.  Read at the top of the kernel, the wait
+        // for them (a scalar-cache miss each time a launch starts) would sit in front of the activation and weight
+        // requests above; the index is made opaque so that the reads cannot be moved up there.
+        const uint16_t *res = nullptr;
+        if (OPS) {
+            __builtin_amdgcn_sched_barrier(0);
+            int mi = m;
+            asm volatile("" : "+s"(mi));
+            fused_eps = ops.eps[mi];
+            res = ops.residual[mi];
+            // the wavefront's residuals, lane l for its l-th row (without a residual: x[0], dropped).  Requested behind the
+            // first weights and under no branch; kept as loaded and touched again only at the store, so that the only
+            // wait it shares is the one in front of the step loop, which needs the first weights anyway.
             const uint16_t *rp = res != nullptr ? res + min(rbase + min(lane, G * U - 1), rows - 1) : X;
-            const float rv = (float)as_h(*rp);
-            res_lane = res != nullptr ? rv : 0.f;
+            res_raw = *rp;
+            res_keep = res != nullptr ? 0xFFFFu : 0u;
         }
 
         // 3. stage: permute the activations into decode order in LDS
@@ -351,21 +373,22 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
 #pragma unroll 1
         for (int c = c0 + waves * 64; c < nchunks; c += waves * 64) {
             const uint4 *src = chunk_src(c);
-            const uint4 *asrc = OPS ? chunk_src_of(aux_base, c) : src;
-            chunk_put(c, src[0], src[1], asrc[0], asrc[1]);
+            const uint4 x0 = src[0], x1 = src[1];
+            const uint4 *asrc = HAS_AUX ? chunk_src_of(aux_base, c) : src;
+            chunk_put(c, x0, x1, HAS_AUX ? asrc[0] : x0, HAS_AUX ? asrc[1] : x1);
         }
         // fused normalization: the wavefronts' shares of sum x^2 go through sixteen floats behind the staged strips; the
         // sum is complete in the pass that stages the row's last strip, which is also the pass that stores the outputs
         float *ssq_part = reinterpret_cast<float *>(lds + (size_t)T * NB * SLOT_BYTES);
-        if (OPS && t0 + nt == nstrips) {
+        if (OPS && XOP == IFLOW_X_RMS_GAIN && t0 + nt == nstrips) {
             const float wsum = wave_sum_to_lane63(ssq);
             if (lane == 63) ssq_part[wave] = wsum;
         }
         __syncthreads();
-        if (OPS && t0 + nt == nstrips && x_op == IFLOW_X_RMS_GAIN) {
+        if (OPS && t0 + nt == nstrips && XOP == IFLOW_X_RMS_GAIN) {
             const float mine = lane < waves ? ssq_part[lane] : 0.f;
             const float total = wave_sum(mine);
-            out_scale = 1.0f / __builtin_sqrtf(total / (float)cols + ops.eps);
+            out_scale = 1.0f / __builtin_sqrtf(total / (float)cols + fused_eps);
         }
 
         // 4. steps = (row group, strip): activation registers from LDS, then each row as its loads land, while
@@ -414,8 +437,10 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
                     for (int u = 0; u < U; ++u) {
                         float sum = wave_sum_to_lane63(v[b][u]);
                         if (OPS) {
-                            const float res = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, res_lane), g * U + u));
-                            sum = __builtin_fmaf(sum, out_scale, res);
+                            uint16_t rr = res_raw;
+                            asm volatile("" : "+v"(rr));                      // first touched here: the load is not waited for before the loop
+                            const uint32_t rb = (uint32_t)__builtin_amdgcn_readlane((int)rr, g * U + u) & res_keep;
+                            sum = __builtin_fmaf(sum, out_scale, (float)as_h((uint16_t)rb));
                         }
                         if (lane == 63 && r0 + u < rows) Y[(int64_t)b * rows + r0 + u] = as_u16((half_t)sum);
                         part[b][u] = 0.f;
@@ -444,7 +469,7 @@ static int pick_rows_per_wg(int64_t rows, int waves_per_wg)
     return (int)r;
 }
 
-template <int NB, int U, bool OPS = false>
+template <int NB, int U, int XOP = -1>
 static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, int waves, int G, hipStream_t s, const GemvOps &ops = GemvOps(),
                               int x_op = IFLOW_X_PLAIN, const uint16_t *aux = nullptr)
 {
@@ -453,14 +478,14 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
     const int nstrips = (nbk + 63) / 64;
     int T = (152 * 1024) / (SLOT * NB);
     if (T > nstrips) T = nstrips;
-    const size_t lds = (size_t)T * NB * SLOT + (OPS ? 64 : 0);  // (fused variant: sixteen floats for the sum of squares)
+    const size_t lds = (size_t)T * NB * SLOT + (XOP >= 0 ? 64 : 0);  // (fused variant: sixteen floats for the sum of squares)
     static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
-        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false, OPS>),
+        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false, XOP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (r == hipSuccess)
-            r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true, OPS>),
+            r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true, XOP>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         return r;
     });
@@ -474,11 +499,11 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
     }
     if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     if (grp.count == 1)
-        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false, OPS>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, x_op, aux, grp, ops);
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false, XOP>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T | (G << 8) | (waves << 16), x_op, aux, grp, ops);
     else
-        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, true, OPS>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
-                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T, G, waves, x_op, aux, grp, ops);
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, true, XOP>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T | (G << 8) | (waves << 16), x_op, aux, grp, ops);
     return hipGetLastError();
 }
 
@@ -486,7 +511,7 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
 // up to T strips (8.5 KiB of LDS per strip and batch column, at most 152 KiB).  Long rows and small problems
 // get larger workgroups (the staging is paid once per workgroup); tall problems let a wavefront walk several
 // row groups.
-template <int NB, bool OPS = false>
+template <int NB, int XOP = -1>
 static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t *X, hipStream_t s, const GemvOps &ops = GemvOps(),
                             int x_op = IFLOW_X_PLAIN, const uint16_t *aux = nullptr)
 {
@@ -499,7 +524,7 @@ static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t 
     if (G < 1) G = 1;
     if (G > 3) G = 3;
     // rows in flight per wavefront: two, or one where 32 activation registers per batch column leave no room
-    if (NB <= 2) return q3h_launch_u<NB, 2, OPS>(grp, cols, X, waves, G, s, ops, x_op, aux);
+    if (NB <= 2) return q3h_launch_u<NB, 2, XOP>(grp, cols, X, waves, G, s, ops, x_op, aux);
     return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
 }
 
@@ -581,8 +606,13 @@ hipError_t launch_qgemv_fused(int count, const void *const *packed, const int64_
         ops.residual[i] = residual ? residual[i] : nullptr;
     }
     grp.count = count;
-    ops.eps = eps;
-    return q3h_launch<1, true>(grp, cols, x, s, ops, x_op, aux);
+    for (int i = 0; i < IFLOW_MAX_GROUP; ++i) ops.eps[i] = eps;
+    switch (x_op) {
+    case IFLOW_X_PLAIN:    return q3h_launch<1, IFLOW_X_PLAIN>(grp, cols, x, s, ops, x_op, aux);
+    case IFLOW_X_RMS_GAIN: return q3h_launch<1, IFLOW_X_RMS_GAIN>(grp, cols, x, s, ops, x_op, aux);
+    case IFLOW_X_SILU_MUL: return q3h_launch<1, IFLOW_X_SILU_MUL>(grp, cols, x, s, ops, x_op, aux);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_qgemv(int format, const void *packed, int64_t rows, int64_t cols,
