@@ -489,3 +489,51 @@ def test_fused_gemv_reduces_to_the_plain_product(orc):
     # unit vector: column k of W', scaled, plus the residual
     e = np.zeros(128, np.float16); e[5] = 1.0
     assert np.max(np.abs(ops.fused_gemv(_bits(w), _bits(e), 2.0, _bits(r)) - (2.0 * w[:, 5].astype(np.float64) + r.astype(np.float64)))) < 1e-15
+
+
+# ---- grouped-query attention for one decode step (oracle/attention.py) ----
+def test_gqa_decode_matches_the_library_routine_and_special_cases():
+    import torch
+    from oracle import attention as att
+    rng = np.random.default_rng(80)
+    n_heads, n_kv, d, max_seq, T = 8, 2, 16, 40, 33
+    q = rng.standard_normal((n_heads, d)).astype(np.float16)
+    k = rng.standard_normal((n_kv, max_seq, d)).astype(np.float16)
+    v = rng.standard_normal((n_kv, max_seq, d)).astype(np.float16)
+    scale = 0.3
+    got = att.gqa_decode(_bits(q), _bits(k), _bits(v), T, scale)
+    # the library's scaled dot-product attention in fp64, keys/values repeated per group (group j serves heads 4j .. 4j+3)
+    tq = torch.from_numpy(q.astype(np.float64))[None, :, None, :]
+    tk = torch.from_numpy(k[:, :T].astype(np.float64)).repeat_interleave(n_heads // n_kv, dim=0)[None]
+    tv = torch.from_numpy(v[:, :T].astype(np.float64)).repeat_interleave(n_heads // n_kv, dim=0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=scale)[0, :, 0, :].numpy()
+    assert np.max(np.abs(got - ref)) < 1e-12
+    # positions past seq_len are never read
+    k2, v2 = k.copy(), v.copy()
+    k2[:, T:] = 100.0; v2[:, T:] = -100.0
+    assert np.array_equal(att.gqa_decode(_bits(q), _bits(k2), _bits(v2), T, scale), got)
+    # one cached position: the output is that position's value, whatever the query
+    one = att.gqa_decode(_bits(q), _bits(k), _bits(v), 1, scale)
+    assert np.array_equal(one, np.repeat(v[:, 0].astype(np.float64), n_heads // n_kv, axis=0))
+    # identical keys: uniform weights, the mean of the values
+    kc = np.broadcast_to(k[:, :1], k.shape).copy()
+    uni = att.gqa_decode(_bits(q), _bits(kc), _bits(v), T, scale)
+    assert np.max(np.abs(uni - np.repeat(v[:, :T].astype(np.float64).mean(axis=1), n_heads // n_kv, axis=0))) < 1e-13
+    # the order of the cached positions does not matter
+    perm = rng.permutation(T)
+    kp, vp = k.copy(), v.copy()
+    kp[:, :T] = k[:, perm]; vp[:, :T] = v[:, perm]
+    assert np.max(np.abs(att.gqa_decode(_bits(q), _bits(kp), _bits(vp), T, scale) - got)) < 1e-13
+    # as many groups as heads is multi-head attention: head i with key/value head i
+    k8 = rng.standard_normal((n_heads, max_seq, d)).astype(np.float16)
+    v8 = rng.standard_normal((n_heads, max_seq, d)).astype(np.float16)
+    mha = att.gqa_decode(_bits(q), _bits(k8), _bits(v8), T, scale)
+    for i in (0, 5):
+        alone = att.gqa_decode(_bits(q[i:i + 1]), _bits(k8[i:i + 1]), _bits(v8[i:i + 1]), T, scale)
+        assert np.array_equal(mha[i:i + 1], alone)
+    # a dominant score: softmax saturates to the value at that position (no overflow in exp)
+    qb = np.zeros((1, d), np.float16); qb[0, 0] = 200.0
+    kb = np.zeros((1, 5, d), np.float16); kb[0, 3, 0] = 50.0
+    vb = rng.standard_normal((1, 5, d)).astype(np.float16)
+    sat = att.gqa_decode(_bits(qb), _bits(kb), _bits(vb), 5, 1.0)
+    assert np.all(np.isfinite(sat)) and np.max(np.abs(sat[0] - vb[0, 3].astype(np.float64))) < 1e-12
