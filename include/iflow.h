@@ -166,6 +166,24 @@ iflow_status_t iflow_qgemv_chain(iflow_format_t format, int nphases, const int *
                                  uint16_t *const *y, void *workspace, size_t workspace_bytes, void *stream);
 iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream);
 
+/* One decode step of grouped-query attention over an fp16 key/value cache (section "Grouped-query attention":
+ * head_i = Attention(Q_i, K^j, V^j), j the group of query head i; scaled dot-product attention; n_kv_heads == n_heads is
+ * multi-head attention).  One query position attends to all seq_len cached positions:
+ *   out[i][:] = fp16( sum_t softmax_t(scale * q[i] . K[j][t]) * V[j][t][:] ),  j = i / (n_heads / n_kv_heads).
+ *   q        [n_heads][128] fp16          (head dimension 128 only; other values: IFLOW_ERR_SHAPE)
+ *   k_cache  [n_kv_heads][max_seq][128] fp16, v_cache likewise; positions >= seq_len are not read
+ *   out      [n_heads][128] fp16
+ *   n_heads / n_kv_heads must be 1, 2, 4 or 8; n_kv_heads <= 64; 1 <= seq_len <= max_seq <= 2^20.
+ *   workspace: device memory of iflow_attn_decode_workspace_bytes(n_heads) bytes, 16-byte aligned, zeroed ONCE by the
+ *     caller before its first use (partial results of the position ranges the sequence is split into, and a counter per
+ *     kv head that the launch leaves at zero again).  Launches that share a workspace must be ordered (same stream).
+ * Everything is computed in fp32 from the fp16 inputs and rounded to fp16 once; the order of the sums is fixed, so
+ * the result does not vary from run to run.  All pointers are device pointers, 16-byte aligned. */
+iflow_status_t iflow_attn_decode_workspace_bytes(int n_heads, size_t *bytes);
+iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads,
+                                 int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
+                                 uint16_t *out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
  * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].
  *   X [batch][cols] fp16, Y [batch][rows] fp16, both device.

@@ -194,6 +194,31 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
     return device_status(iflow::launch_qgemv_fused(count, packed, rows, cols, x, (int)x_op, aux, eps, residual, y, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_attn_decode_workspace_bytes(int n_heads, size_t *bytes)
+{
+    if (!bytes) return IFLOW_ERR_NULL;
+    if (n_heads < 1 || n_heads > 512) return IFLOW_ERR_SHAPE;
+    *bytes = iflow::attn_workspace_bytes(n_heads);
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads,
+                                 int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
+                                 uint16_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (head_dim != 128) return IFLOW_ERR_SHAPE;
+    if (n_kv_heads < 1 || n_kv_heads > 64 || n_heads < 1 || n_heads > 512 || n_heads % n_kv_heads != 0) return IFLOW_ERR_SHAPE;
+    const int group = n_heads / n_kv_heads;
+    if (group != 1 && group != 2 && group != 4 && group != 8) return IFLOW_ERR_SHAPE;
+    if (seq_len < 1 || max_seq < seq_len || max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
+    if (!(scale > 0.0f && scale < 3.0e38f)) return IFLOW_ERR_SHAPE;
+    if (!q || !k_cache || !v_cache || !out || !workspace) return IFLOW_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(workspace)) return IFLOW_ERR_ALIGN;
+    if (workspace_bytes < iflow::attn_workspace_bytes(n_heads)) return IFLOW_ERR_SIZE;
+    return device_status(iflow::launch_attn_decode(q, k_cache, v_cache, n_heads, n_kv_heads, seq_len, max_seq, scale, out, workspace,
+                                                   (hipStream_t)stream));
+}
+
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes)
 {
     if (!rows || !bytes) return IFLOW_ERR_NULL;

@@ -1,0 +1,236 @@
+// One decode step of grouped-query attention over an fp16 key/value cache (arXiv 2401.08294, section "Grouped-query
+// attention": head_i = Attention(Q_i, K^j, V^j) with j the group of query head i; Attention = scaled dot-product
+// attention; with as many groups as heads it is multi-head attention).
+//
+// Next to the weight stream this is the other part of a decode step that is bound by memory: every cached key and
+// value is read once per step and used for a handful of multiply-adds.  So the kernel is laid out like the GEMV: long
+// contiguous 16-byte-per-lane reads, everything else in registers.
+//   - The cache is [kv head][position][128] fp16, so the positions of a head are one contiguous stream.  A workgroup
+//     (four wavefronts) takes one kv head and one contiguous range of positions (a "split"); the grid is
+//     kv heads x splits, a few workgroups per compute unit.
+//   - A wavefront walks its range in blocks of sixteen positions.  Sixteen lanes share a position (8 of the 128
+//     components each), so one load instruction covers four consecutive positions = 1 KB; the four lane groups of a
+//     wavefront keep separate running softmax states (maximum, sum, 128-component weighted value sum) for their
+//     positions.  The block after the current one is already requested while a block is processed.
+//   - All query heads of the group (1, 2, 4 or 8) are served from the same loaded keys and values.
+//   - Softmax is computed the streaming way: per block one rescale of the running sums to the new maximum, then
+//     exp2 of the (pre-scaled) score differences.  fp32 throughout; the output is rounded to fp16 once.
+//   - A workgroup merges its sixteen states through LDS and writes one state per (head, split) to the caller's
+//     workspace; the last workgroup of a kv head to finish (a counter per kv head in the workspace, reset by that
+//     workgroup, so the workspace is zeroed only once) merges the splits and writes the output.  With a single split
+//     the workspace is not touched.
+#include "iflow_common.h"
+
+namespace iflow {
+
+constexpr int ATT_D = 128;                                    // head dimension
+constexpr int ATT_WAVES = 4;
+constexpr int ATT_TILES = 4;                                  // tiles of four positions per block: 16 positions per wavefront and block
+constexpr int ATT_MAX_SPLITS = 64;
+constexpr int ATT_WS_HEADER = 256;                            // bytes: one counter per kv head (at most 64)
+constexpr int ATT_STATE = ATT_D + 2;                          // floats per stored state: weighted value sum, maximum, sum
+
+typedef uint32_t att_u32x4 __attribute__((ext_vector_type(4)));
+
+template <int R>
+__global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
+                                                                     const uint16_t *__restrict__ vc, uint16_t *__restrict__ out,
+                                                                     uint32_t *__restrict__ ws, int seq_len, int64_t head_stride /* halves */,
+                                                                     int chunk, int nsplit, float scale_log2e)
+{
+    __shared__ float s_acc[16][ATT_D];
+    __shared__ float s_m[16], s_l[16];
+    __shared__ int s_last;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int gq = lane >> 4, dseg = lane & 15;               // position inside a tile; which 8 of the 128 components
+    const int j = blockIdx.x / nsplit, sp = blockIdx.x - j * nsplit;
+    const int t_begin = sp * chunk, t_end = min(seq_len, t_begin + chunk);      // t_begin < seq_len by construction
+    const uint16_t *kh = kc + (int64_t)j * head_stride + dseg * 8;
+    const uint16_t *vh = vc + (int64_t)j * head_stride + dseg * 8;
+
+    // the group's queries: lane holds components 8 dseg .. 8 dseg + 7 of each
+    half2_t qr[R][4];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const att_u32x4 v = *reinterpret_cast<const att_u32x4 *>(q + (int64_t)(j * R + r) * ATT_D + dseg * 8);
+        qr[r][0] = as_h2(v.x); qr[r][1] = as_h2(v.y); qr[r][2] = as_h2(v.z); qr[r][3] = as_h2(v.w);
+    }
+    float m[R], l[R], acc[R][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        m[r] = -INFINITY; l[r] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    }
+
+    // positions past the range are loaded from the range's last position (in bounds) and their scores set to -inf
+    auto load_block = [&](att_u32x4 (&kt)[ATT_TILES], att_u32x4 (&vt)[ATT_TILES], int p0) {
+#pragma unroll
+        for (int t = 0; t < ATT_TILES; ++t) {
+            const int64_t pos = min(p0 + t * 4 + gq, t_end - 1);
+            kt[t] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(kh + pos * ATT_D));
+            vt[t] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(vh + pos * ATT_D));
+        }
+    };
+    auto process_block = [&](const att_u32x4 (&kt)[ATT_TILES], const att_u32x4 (&vt)[ATT_TILES], int p0) {
+        float vf[ATT_TILES][8];
+#pragma unroll
+        for (int t = 0; t < ATT_TILES; ++t) {
+            const half2_t a = as_h2(vt[t].x), b = as_h2(vt[t].y), c = as_h2(vt[t].z), d = as_h2(vt[t].w);
+            vf[t][0] = (float)a.x; vf[t][1] = (float)a.y; vf[t][2] = (float)b.x; vf[t][3] = (float)b.y;
+            vf[t][4] = (float)c.x; vf[t][5] = (float)c.y; vf[t][6] = (float)d.x; vf[t][7] = (float)d.y;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float s[ATT_TILES];
+            float bm = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < ATT_TILES; ++t) {
+                float d = __builtin_amdgcn_fdot2(qr[r][0], as_h2(kt[t].x), 0.f, false);
+                d = __builtin_amdgcn_fdot2(qr[r][1], as_h2(kt[t].y), d, false);
+                d = __builtin_amdgcn_fdot2(qr[r][2], as_h2(kt[t].z), d, false);
+                d = __builtin_amdgcn_fdot2(qr[r][3], as_h2(kt[t].w), d, false);
+                d = row16_sum(d) * scale_log2e;               // the score of this lane group's position, in units of log2
+                s[t] = (p0 + t * 4 + gq < t_end) ? d : -INFINITY;
+                bm = fmaxf(bm, s[t]);
+            }
+            const float m_new = fmaxf(m[r], bm);
+            // (a state that has not seen a valid position yet has maximum -inf: nothing to rescale, and no -inf - -inf)
+            const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m[r] - m_new);
+            const float base = (m_new == -INFINITY) ? 0.f : m_new;
+            l[r] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] *= alpha;
+#pragma unroll
+            for (int t = 0; t < ATT_TILES; ++t) {
+                const float p = __builtin_amdgcn_exp2f(s[t] - base);            // exp2(-inf) = 0 for masked positions
+                l[r] += p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_fmaf(p, vf[t][e], acc[r][e]);
+            }
+            m[r] = m_new;
+        }
+    };
+
+    // blocks of this wavefront: wave, wave + 4, ... of the range, two per trip so that the two register sets alternate
+    att_u32x4 ka[ATT_TILES], va[ATT_TILES], kb[ATT_TILES], vb[ATT_TILES];
+    constexpr int STEP = 16 * ATT_WAVES;                      // positions between a wavefront's consecutive blocks
+    int p0 = t_begin + wave * 16;
+    load_block(ka, va, p0);
+    load_block(kb, vb, p0 + STEP);
+    for (; p0 < t_end; p0 += 2 * STEP) {
+        process_block(ka, va, p0);
+        load_block(ka, va, p0 + 2 * STEP);
+        if (p0 + STEP < t_end) process_block(kb, vb, p0 + STEP);              // (uniform over the wavefront)
+        load_block(kb, vb, p0 + 3 * STEP);
+    }
+
+    // ---- merge the sixteen states (4 wavefronts x 4 lane groups) of each head, store or hand over -----------------------
+    const int pid = wave * 4 + gq;
+    float *part = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + ATT_WS_HEADER);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r > 0) __syncthreads();                           // the previous head's states have been read
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_acc[pid][dseg * 8 + e] = acc[r][e];
+        if (dseg == 0) { s_m[pid] = m[r]; s_l[pid] = l[r]; }
+        __syncthreads();
+        if (tid < ATT_D) {
+            float M = s_m[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) M = fmaxf(M, s_m[i]);                  // finite: the range is not empty
+            float L = 0.f, O = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float f = __builtin_amdgcn_exp2f(s_m[i] - M);
+                L = __builtin_fmaf(s_l[i], f, L);
+                O = __builtin_fmaf(s_acc[i][tid], f, O);
+            }
+            const int head = j * R + r;
+            if (nsplit == 1) {
+                out[(int64_t)head * ATT_D + tid] = as_u16((half_t)(O / L));
+            } else {
+                float *st = part + ((int64_t)head * nsplit + sp) * ATT_STATE;
+                st[tid] = O;
+                if (tid == 0) { st[ATT_D] = M; st[ATT_D + 1] = L; }
+            }
+        }
+    }
+    if (nsplit == 1) return;
+
+    // the last workgroup of this kv head merges the splits
+    __threadfence();                                          // this thread's state stores are visible device-wide ...
+    __syncthreads();                                          // ... for every thread of the workgroup, before the count goes up
+    if (tid == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(ws + j, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = old == (uint32_t)(nsplit - 1);
+        if (s_last) __hip_atomic_store(ws + j, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    if (tid < ATT_D) {
+#pragma unroll 1
+        for (int r = 0; r < R; ++r) {
+            const int head = j * R + r;
+            const float *st = part + (int64_t)head * nsplit * ATT_STATE;
+            float M = -INFINITY;
+            for (int i = 0; i < nsplit; ++i) M = fmaxf(M, __builtin_nontemporal_load(st + i * ATT_STATE + ATT_D));
+            float L = 0.f, O = 0.f;
+            for (int i = 0; i < nsplit; ++i) {
+                const float f = __builtin_amdgcn_exp2f(__builtin_nontemporal_load(st + i * ATT_STATE + ATT_D) - M);
+                L = __builtin_fmaf(__builtin_nontemporal_load(st + i * ATT_STATE + ATT_D + 1), f, L);
+                O = __builtin_fmaf(__builtin_nontemporal_load(st + i * ATT_STATE + tid), f, O);
+            }
+            out[(int64_t)head * ATT_D + tid] = as_u16((half_t)(O / L));
+        }
+    }
+}
+
+// positions per split (a multiple of 64, one block per wavefront) and number of splits for a sequence length
+static void attn_geometry(int n_kv_heads, int64_t seq_len, int cus, int *chunk, int *nsplit)
+{
+    int64_t want = (3 * (int64_t)cus + n_kv_heads - 1) / n_kv_heads;          // about three workgroups per compute unit
+    if (want < 1) want = 1;
+    if (want > ATT_MAX_SPLITS) want = ATT_MAX_SPLITS;
+    int64_t c = (seq_len + want - 1) / want;
+    c = (c + 63) / 64 * 64;
+    *chunk = (int)c;
+    *nsplit = (int)((seq_len + c - 1) / c);
+}
+
+size_t attn_workspace_bytes(int n_heads)
+{
+    return (size_t)ATT_WS_HEADER + (size_t)n_heads * ATT_MAX_SPLITS * ATT_STATE * sizeof(float);
+}
+
+hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
+                              int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s)
+{
+    static PerDevice pd;
+    int cus = 0;
+    hipError_t e = once_per_device(pd, &cus, [] { return hipSuccess; });
+    if (e != hipSuccess) return e;
+    if (n_kv_heads < 1 || n_kv_heads > 64 || n_heads % n_kv_heads != 0 || seq_len < 1 || seq_len > max_seq) return hipErrorInvalidValue;
+    const int R = n_heads / n_kv_heads;
+    int chunk = 0, nsplit = 0;
+    attn_geometry(n_kv_heads, seq_len, cus, &chunk, &nsplit);
+    if (nsplit < 1 || nsplit > ATT_MAX_SPLITS) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(n_kv_heads * nsplit)), block(64 * ATT_WAVES);
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const int64_t head_stride = max_seq * ATT_D;
+#define IFLOW_ATT_GO(RR) hipLaunchKernelGGL((attn_decode_kernel<RR>), grid, block, 0, s, q, k_cache, v_cache, out, \
+        static_cast<uint32_t *>(workspace), (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
+    switch (R) {
+    case 1: IFLOW_ATT_GO(1); break;
+    case 2: IFLOW_ATT_GO(2); break;
+    case 4: IFLOW_ATT_GO(4); break;
+    case 8: IFLOW_ATT_GO(8); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef IFLOW_ATT_GO
+    return hipGetLastError();
+}
+
+}  // namespace iflow

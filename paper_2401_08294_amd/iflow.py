@@ -59,6 +59,8 @@ def lib():
         L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
         L.iflow_qgemv_fused.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.c_int, p, C.c_float,
                                         C.POINTER(p), C.POINTER(p), p]
+        L.iflow_attn_decode_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
+        L.iflow_attn_decode.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p, sz, p]
         L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
         L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
                                         C.POINTER(i64), C.POINTER(p), p, sz, p]
@@ -165,6 +167,19 @@ def qgemv_fused(fmt: int, packed_list, rows_list, cols: int, x, y_list, x_op: in
         res = (C.c_void_p * n)(*[(_ptr(t) if t is not None else None) for t in residual_list])
     _check(lib().iflow_qgemv_fused(fmt, n, pk, rs, cols, _ptr(x), x_op, _ptr(aux) if aux is not None else None, eps, res, ys,
                                    _stream(stream)), "iflow_qgemv_fused")
+
+
+def attn_decode_workspace_bytes(n_heads: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().iflow_attn_decode_workspace_bytes(n_heads, C.byref(out)), "iflow_attn_decode_workspace_bytes")
+    return int(out.value)
+
+
+def attn_decode(q, k_cache, v_cache, n_heads: int, n_kv_heads: int, head_dim: int, seq_len: int, max_seq: int, scale: float, out,
+                workspace, workspace_bytes: int, stream=None) -> None:
+    """One decode step of grouped-query attention over an fp16 key/value cache [n_kv_heads][max_seq][head_dim]."""
+    _check(lib().iflow_attn_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), n_heads, n_kv_heads, head_dim, seq_len, max_seq, scale,
+                                   _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)), "iflow_attn_decode")
 
 
 def qgemv_chain_workspace_bytes(rows_list) -> int:

@@ -182,3 +182,22 @@ def test_fused_validation_happens_before_any_launch(iflow):
     assert call(4, [8], 64, x, [y0], residual=[y0 + 2]) == iflow.ERR_SHAPE       # residual shifted against its own output
     assert call(4, [8, 8], 64, x, [y0, y1], residual=[y1, None]) == iflow.ERR_SHAPE       # residual is another matrix's output
     assert call(4, [8], 64, x, [y0], residual=[y0 + 1]) == iflow.ERR_ALIGN
+
+
+def test_attention_validation_happens_before_any_launch(iflow):
+    L = iflow.lib()
+    base = 0x100000
+
+    def call(n_heads=32, n_kv=32, d=128, T=10, max_seq=64, scale=0.1, q=base, k=base * 2, v=base * 3, out=base * 4, ws=base * 5, ws_bytes=1 << 30):
+        return L.iflow_attn_decode(q, k, v, n_heads, n_kv, d, T, max_seq, C.c_float(scale), out, ws, ws_bytes, None)
+
+    assert call(d=64) == iflow.ERR_SHAPE                                         # head dimension 128 only
+    assert call(n_heads=30, n_kv=4) == iflow.ERR_SHAPE                           # heads not a multiple of kv heads
+    assert call(n_heads=48, n_kv=16) == iflow.ERR_SHAPE                          # three query heads per kv head
+    assert call(n_heads=128, n_kv=128) == iflow.ERR_SHAPE                        # more than 64 kv heads
+    assert call(T=0) == iflow.ERR_SHAPE and call(T=65) == iflow.ERR_SHAPE        # empty, or longer than the cache
+    assert call(scale=0.0) == iflow.ERR_SHAPE and call(scale=float("nan")) == iflow.ERR_SHAPE
+    assert call(q=None) == iflow.ERR_NULL and call(ws=None) == iflow.ERR_NULL
+    assert call(k=base * 2 + 8) == iflow.ERR_ALIGN
+    assert call(ws_bytes=1000) == iflow.ERR_SIZE
+    assert iflow.attn_decode_workspace_bytes(32) == 256 + 32 * 64 * 130 * 4
