@@ -174,9 +174,9 @@ iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream);
  *   k_cache  [n_kv_heads][max_seq][128] fp16, v_cache likewise; positions >= seq_len are not read
  *   out      [n_heads][128] fp16
  *   n_heads / n_kv_heads must be 1, 2, 4 or 8; n_kv_heads <= 64; 1 <= seq_len <= max_seq <= 2^20.
- *   workspace: device memory of iflow_attn_decode_workspace_bytes(n_heads) bytes, 16-byte aligned, zeroed ONCE by the
- *     caller before its first use (partial results of the position ranges the sequence is split into, and a counter per
- *     kv head that the launch leaves at zero again).  Launches that share a workspace must be ordered (same stream).
+ *   workspace: device memory of iflow_attn_decode_workspace_bytes(n_heads) bytes, 16-byte aligned; scratch for the
+ *     partial results of the position ranges the sequence is split into (up to 64; a second small kernel merges them),
+ *     its contents before and after the call mean nothing.  Launches that share a workspace must be ordered (same stream).
  * Everything is computed in fp32 from the fp16 inputs and rounded to fp16 once; the order of the sums is fixed, so
  * the result does not vary from run to run.  All pointers are device pointers, 16-byte aligned. */
 iflow_status_t iflow_attn_decode_workspace_bytes(int n_heads, size_t *bytes);

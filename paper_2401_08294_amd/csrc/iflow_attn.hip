@@ -16,9 +16,11 @@
 //   - Softmax is computed the streaming way: per block one rescale of the running sums to the new maximum, then
 //     exp2 of the (pre-scaled) score differences.  fp32 throughout; the output is rounded to fp16 once.
 //   - A workgroup merges its sixteen states through LDS and writes one state per (head, split) to the caller's
-//     workspace; the last workgroup of a kv head to finish (a counter per kv head in the workspace, reset by that
-//     workgroup, so the workspace is zeroed only once) merges the splits and writes the output.  With a single split
-//     the workspace is not touched.
+//     workspace; a second, small kernel (one workgroup per query head) merges the splits and writes the output.  Two
+//     launches rather than "the last workgroup to finish merges": device-wide release/acquire fences write back and
+//     invalidate whole L2 caches on this part (several microseconds per workgroup, measured), and one workgroup per
+//     kv head merging all its heads' splits one after the other is a long serial tail; the second launch costs about
+//     two microseconds and merges all heads at once.  With a single split the first kernel writes the output itself.
 #include "iflow_common.h"
 
 namespace iflow {
@@ -27,20 +29,19 @@ constexpr int ATT_D = 128;                                    // head dimension
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_TILES = 4;                                  // tiles of four positions per block: 16 positions per wavefront and block
 constexpr int ATT_MAX_SPLITS = 64;
-constexpr int ATT_WS_HEADER = 256;                            // bytes: one counter per kv head (at most 64)
-constexpr int ATT_STATE = ATT_D + 2;                          // floats per stored state: weighted value sum, maximum, sum
+// workspace: value sums O[head][component][ATT_MAX_SPLITS], then maxima M[head][ATT_MAX_SPLITS], then sums L[head][ATT_MAX_SPLITS]
+// (fp32; a thread of the merge kernel reads the splits of its component as one contiguous run)
 
 typedef uint32_t att_u32x4 __attribute__((ext_vector_type(4)));
 
 template <int R>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                                      const uint16_t *__restrict__ vc, uint16_t *__restrict__ out,
-                                                                     uint32_t *__restrict__ ws, int seq_len, int64_t head_stride /* halves */,
+                                                                     float *__restrict__ ws, int n_heads, int seq_len, int64_t head_stride /* halves */,
                                                                      int chunk, int nsplit, float scale_log2e)
 {
     __shared__ float s_acc[16][ATT_D];
     __shared__ float s_m[16], s_l[16];
-    __shared__ int s_last;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int gq = lane >> 4, dseg = lane & 15;               // position inside a tile; which 8 of the 128 components
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint1
 
     // ---- merge the sixteen states (4 wavefronts x 4 lane groups) of each head, store or hand over -----------------------
     const int pid = wave * 4 + gq;
-    float *part = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + ATT_WS_HEADER);
+    float *ws_o = ws, *ws_m = ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS, *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         if (r > 0) __syncthreads();                           // the previous head's states have been read
@@ -151,47 +152,50 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint1
             if (nsplit == 1) {
                 out[(int64_t)head * ATT_D + tid] = as_u16((half_t)(O / L));
             } else {
-                float *st = part + ((int64_t)head * nsplit + sp) * ATT_STATE;
-                st[tid] = O;
-                if (tid == 0) { st[ATT_D] = M; st[ATT_D + 1] = L; }
+                ws_o[((int64_t)head * ATT_D + tid) * ATT_MAX_SPLITS + sp] = O;
+                if (tid == 0) { ws_m[(int64_t)head * ATT_MAX_SPLITS + sp] = M; ws_l[(int64_t)head * ATT_MAX_SPLITS + sp] = L; }
             }
         }
     }
-    if (nsplit == 1) return;
+}
 
-    // the last workgroup of this kv head merges the splits
-    __threadfence();                                          // this thread's state stores are visible device-wide ...
-    __syncthreads();                                          // ... for every thread of the workgroup, before the count goes up
-    if (tid == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(ws + j, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = old == (uint32_t)(nsplit - 1);
-        if (s_last) __hip_atomic_store(ws + j, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+// Merge of the splits: one workgroup of 128 threads per query head, thread d for component d.  The states of a head lie
+// in rows of ATT_MAX_SPLITS floats, read four at a time; entries past nsplit are whatever an earlier call left there
+// and are masked by index.
+__global__ __launch_bounds__(ATT_D) void attn_merge_kernel(const float *__restrict__ ws, uint16_t *__restrict__ out, int n_heads, int nsplit)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const int head = blockIdx.x, d = threadIdx.x;
+    const f32x4 *ws_o = reinterpret_cast<const f32x4 *>(ws + ((int64_t)head * ATT_D + d) * ATT_MAX_SPLITS);
+    const f32x4 *ws_m = reinterpret_cast<const f32x4 *>(ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS + (int64_t)head * ATT_MAX_SPLITS);
+    const f32x4 *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS / 4;
+    const int n4 = (nsplit + 3) / 4;
+    float M = -INFINITY;
+#pragma unroll 4
+    for (int c = 0; c < n4; ++c) {
+        const f32x4 m4 = ws_m[c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) M = fmaxf(M, 4 * c + e < nsplit ? m4[e] : -INFINITY);
     }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    if (tid < ATT_D) {
-#pragma unroll 1
-        for (int r = 0; r < R; ++r) {
-            const int head = j * R + r;
-            const float *st = part + (int64_t)head * nsplit * ATT_STATE;
-            float M = -INFINITY;
-            for (int i = 0; i < nsplit; ++i) M = fmaxf(M, __builtin_nontemporal_load(st + i * ATT_STATE + ATT_D));
-            float L = 0.f, O = 0.f;
-            for (int i = 0; i < nsplit; ++i) {
-                const float f = __builtin_amdgcn_exp2f(__builtin_nontemporal_load(st + i * ATT_STATE + ATT_D) - M);
-                L = __builtin_fmaf(__builtin_nontemporal_load(st + i * ATT_STATE + ATT_D + 1), f, L);
-                O = __builtin_fmaf(__builtin_nontemporal_load(st + i * ATT_STATE + tid), f, O);
-            }
-            out[(int64_t)head * ATT_D + tid] = as_u16((half_t)(O / L));
+    float L = 0.f, O = 0.f;
+#pragma unroll 4
+    for (int c = 0; c < n4; ++c) {
+        const f32x4 m4 = ws_m[c], l4 = ws_l[c], o4 = ws_o[c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool in = 4 * c + e < nsplit;
+            const float f = in ? __builtin_amdgcn_exp2f(m4[e] - M) : 0.f;
+            L = __builtin_fmaf(in ? l4[e] : 0.f, f, L);
+            O = __builtin_fmaf(in ? o4[e] : 0.f, f, O);
         }
     }
+    out[(int64_t)head * ATT_D + d] = as_u16((half_t)(O / L));
 }
 
 // positions per split (a multiple of 64, one block per wavefront) and number of splits for a sequence length
 static void attn_geometry(int n_kv_heads, int64_t seq_len, int cus, int *chunk, int *nsplit)
 {
-    int64_t want = (3 * (int64_t)cus + n_kv_heads - 1) / n_kv_heads;          // about three workgroups per compute unit
+    int64_t want = (1 * (int64_t)cus + n_kv_heads - 1) / n_kv_heads;          // about one workgroup per compute unit
     if (want < 1) want = 1;
     if (want > ATT_MAX_SPLITS) want = ATT_MAX_SPLITS;
     int64_t c = (seq_len + want - 1) / want;
@@ -202,7 +206,7 @@ static void attn_geometry(int n_kv_heads, int64_t seq_len, int cus, int *chunk, 
 
 size_t attn_workspace_bytes(int n_heads)
 {
-    return (size_t)ATT_WS_HEADER + (size_t)n_heads * ATT_MAX_SPLITS * ATT_STATE * sizeof(float);
+    return (size_t)n_heads * (ATT_D + 2) * ATT_MAX_SPLITS * sizeof(float);
 }
 
 hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
@@ -221,7 +225,7 @@ hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const 
     const float scale_log2e = scale * 1.4426950408889634f;
     const int64_t head_stride = max_seq * ATT_D;
 #define IFLOW_ATT_GO(RR) hipLaunchKernelGGL((attn_decode_kernel<RR>), grid, block, 0, s, q, k_cache, v_cache, out, \
-        static_cast<uint32_t *>(workspace), (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
+        static_cast<float *>(workspace), n_heads, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
     switch (R) {
     case 1: IFLOW_ATT_GO(1); break;
     case 2: IFLOW_ATT_GO(2); break;
@@ -230,6 +234,9 @@ hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const 
     default: return hipErrorInvalidValue;
     }
 #undef IFLOW_ATT_GO
+    e = hipGetLastError();
+    if (e != hipSuccess || nsplit == 1) return e;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)n_heads), dim3(ATT_D), 0, s, static_cast<const float *>(workspace), out, n_heads, nsplit);
     return hipGetLastError();
 }
 

@@ -30,7 +30,7 @@ def run(torch, iflow, q, k, v, T, scale, ws=None):
     n_heads, n_kv, max_seq = q.shape[0], k.shape[0], k.shape[1]
     nbytes = iflow.attn_decode_workspace_bytes(n_heads)
     if ws is None:
-        ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
+        ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")       # scratch: NaN patterns to start with
     out = torch.full((n_heads, 128), float("nan"), dtype=torch.float16, device="cuda")
     iflow.attn_decode(dev16(torch, q), dev16(torch, k), dev16(torch, v), n_heads, n_kv, 128, T, max_seq, scale, out, ws, nbytes)
     torch.cuda.synchronize()
@@ -54,7 +54,7 @@ def test_attention_decode_against_the_definition(gpu, n_heads, n_kv, T, max_seq)
 
 def test_attention_peaked_softmax_and_reused_workspace(gpu):
     """Large scores (one position dominates, the running maximum moves a lot) and several launches of different lengths
-    on one workspace, which is zeroed only once."""
+    on one workspace (left as the previous launch wrote it)."""
     torch, iflow = gpu
     from oracle import attention as att
     n_heads, n_kv, max_seq = 16, 8, 3000
@@ -66,7 +66,6 @@ def test_attention_peaked_softmax_and_reused_workspace(gpu):
         ref = att.gqa_decode(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), T, 0.5)
         e = rel(got, ref)
         assert np.isfinite(got).all() and e <= TOL, f"seq_len {T}: {e}"
-    assert int(ws[:256].cpu().numpy().view(np.uint32).sum()) == 0          # every counter is back at zero
 
 
 def test_attention_graph_replay(gpu):

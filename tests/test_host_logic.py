@@ -200,4 +200,4 @@ def test_attention_validation_happens_before_any_launch(iflow):
     assert call(q=None) == iflow.ERR_NULL and call(ws=None) == iflow.ERR_NULL
     assert call(k=base * 2 + 8) == iflow.ERR_ALIGN
     assert call(ws_bytes=1000) == iflow.ERR_SIZE
-    assert iflow.attn_decode_workspace_bytes(32) == 256 + 32 * 64 * 130 * 4
+    assert iflow.attn_decode_workspace_bytes(32) == 32 * 64 * 130 * 4
