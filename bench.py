@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--layers-per-launch", type=int, default=8, choices=(1, 2, 4, 8),
                     help="with --launches 1: chain this many layers into one launch (the next layer's q/k/v read down's output)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--context", type=int, default=0,
+                    help="with --fused: also run iflow_attn_decode (32 heads of 128) over a cache of this many positions per layer, "
+                         "between the q,k,v and the o launch - a whole decoder layer, position embedding aside")
     ap.add_argument("--fused", action="store_true",
                     help="with --launches 4: rms normalization, silu-gated input and residuals fused into the four launches of a layer "
                          "(iflow_qgemv_fused), each launch reading the previous one's output")
@@ -190,6 +193,12 @@ def main():
         assert args.launches == 4 and args.format == "Q3H_B64", "--fused goes with --launches 4 and the 3.5-bit format"
         hidden_state = xs[shapes[0][2]].clone()               # the residual stream, updated in place by the o and down launches
         gains = [(1.0 + 0.1 * torch.randn((shapes[0][2],), generator=gen, device=dev, dtype=torch.float32)).to(torch.float16) for _ in range(2)]
+        attn_out = torch.empty_like(ys[0])
+        if args.context > 0:                                  # a key/value cache per ring layer (never appended to: the lengths stay fixed)
+            caches = [(torch.randn((32, args.context, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16),
+                       torch.randn((32, args.context, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)) for _ in range(args.ring)]
+            attn_ws_bytes = iflow.attn_decode_workspace_bytes(32)
+            attn_ws = torch.empty((attn_ws_bytes,), dtype=torch.uint8, device=dev)
 
     def fused_step(layer):
         """One decoder layer in four launches: norm -> q,k,v | o + residual | norm -> gate,up | silu(gate)*up -> down + residual.
@@ -198,7 +207,12 @@ def main():
         h = hidden_state
         iflow.qgemv_fused(fmt, [m[i][2] for i in (0, 1, 2)], [m[i][0] for i in (0, 1, 2)], m[0][1], h, [ys[0], ys[1], ys[2]],
                           iflow.X_RMS_GAIN, gains[0], 1e-5, stream=raw)
-        iflow.qgemv_fused(fmt, [m[3][2]], [m[3][0]], m[3][1], ys[0], [h], residual_list=[h], stream=raw)
+        o_in = ys[0]
+        if args.context > 0:
+            kc, vc = caches[layer]
+            iflow.attn_decode(ys[0], kc, vc, 32, 32, 128, args.context, args.context, 128 ** -0.5, attn_out, attn_ws, attn_ws_bytes, stream=raw)
+            o_in = attn_out
+        iflow.qgemv_fused(fmt, [m[3][2]], [m[3][0]], m[3][1], o_in, [h], residual_list=[h], stream=raw)
         iflow.qgemv_fused(fmt, [m[4][2], m[5][2]], [m[4][0], m[5][0]], m[4][1], h, [ys[4], ys[5]], iflow.X_RMS_GAIN, gains[1], 1e-5, stream=raw)
         iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [h], iflow.X_SILU_MUL, ys[5], 0.0, residual_list=[h], stream=raw)
         launch_count[0] += 4
@@ -396,7 +410,9 @@ def main():
                                + {1: f", 1 chained launch per {args.layers_per_launch} layer(s) (q+k+v -> o -> gate+up -> down -> next layer's q+k+v ..., "
                                      "each phase reading the previous one's output)",
                                   4: ", 4 launches per layer (q+k+v, o, gate+up, down)"
-                                     + (", rms normalization, silu gate and residuals fused in, each launch reading the previous one's output" if args.fused else ""),
+                                     + (", rms normalization, silu gate and residuals fused in, each launch reading the previous one's output" if args.fused else "")
+                                     + (f", attention over {args.context} cached positions per layer in between (its {2 * 32 * args.context * 128 * 2} "
+                                        "key/value bytes per layer are NOT counted in the value)" if args.fused and args.context > 0 else ""),
                                   7: ", 7 launches per layer"}[args.launches],
                    "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": round(launches_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
