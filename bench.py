@@ -417,7 +417,7 @@ def main():
                    "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": round(launches_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "iflow::q3h_gemv_kernel<1, 2>", "avg_launch_us": round(us_per_launch, 3),
+                     "kernel": "iflow::q3h_gemv_kernel<1, 2, false|true, -1>", "avg_launch_us": round(us_per_launch, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},
     }
     out["spread"] = spread
