@@ -29,8 +29,8 @@ constexpr int ATT_D = 128;                                    // head dimension
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_TILES = 4;                                  // tiles of four positions per block: 16 positions per wavefront and block
 constexpr int ATT_MAX_SPLITS = 64;
-// workspace: value sums O[head][component][ATT_MAX_SPLITS], then maxima M[head][ATT_MAX_SPLITS], then sums L[head][ATT_MAX_SPLITS]
-// (fp32; a thread of the merge kernel reads the splits of its component as one contiguous run)
+// workspace: value sums O[head][ATT_MAX_SPLITS][component], then maxima M[head][ATT_MAX_SPLITS], then sums L[head][ATT_MAX_SPLITS]
+// (fp32; a state's 128 components are contiguous: written and read by 128 neighbouring threads)
 
 typedef uint32_t att_u32x4 __attribute__((ext_vector_type(4)));
 
@@ -118,13 +118,21 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint1
     att_u32x4 ka[ATT_TILES], va[ATT_TILES], kb[ATT_TILES], vb[ATT_TILES];
     constexpr int STEP = 16 * ATT_WAVES;                      // positions between a wavefront's consecutive blocks
     int p0 = t_begin + wave * 16;
+    // (the scheduling barriers pin the order in which the two sets are requested: the wait in front of a block counts
+    // the requests issued after that block's own, and a reordered prologue would turn it into a wait for everything)
     load_block(ka, va, p0);
+    __builtin_amdgcn_sched_barrier(0);
     load_block(kb, vb, p0 + STEP);
+    __builtin_amdgcn_sched_barrier(0);
     for (; p0 < t_end; p0 += 2 * STEP) {
         process_block(ka, va, p0);
+        __builtin_amdgcn_sched_barrier(0);
         load_block(ka, va, p0 + 2 * STEP);
+        __builtin_amdgcn_sched_barrier(0);
         if (p0 + STEP < t_end) process_block(kb, vb, p0 + STEP);              // (uniform over the wavefront)
+        __builtin_amdgcn_sched_barrier(0);
         load_block(kb, vb, p0 + 3 * STEP);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- merge the sixteen states (4 wavefronts x 4 lane groups) of each head, store or hand over -----------------------
@@ -152,42 +160,201 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint1
             if (nsplit == 1) {
                 out[(int64_t)head * ATT_D + tid] = as_u16((half_t)(O / L));
             } else {
-                ws_o[((int64_t)head * ATT_D + tid) * ATT_MAX_SPLITS + sp] = O;
+                ws_o[((int64_t)head * ATT_MAX_SPLITS + sp) * ATT_D + tid] = O;
                 if (tid == 0) { ws_m[(int64_t)head * ATT_MAX_SPLITS + sp] = M; ws_l[(int64_t)head * ATT_MAX_SPLITS + sp] = L; }
             }
         }
     }
 }
 
-// Merge of the splits: one workgroup of 128 threads per query head, thread d for component d.  The states of a head lie
-// in rows of ATT_MAX_SPLITS floats, read four at a time; entries past nsplit are whatever an earlier call left there
-// and are masked by index.
+// ---- groups of four or eight query heads per kv head: scores and weighted sums on the matrix cores --------------------
+// With eight heads per loaded key the vector units bind (about 46 instructions per position in the kernel above).  But a
+// block of sixteen positions against a group of heads is two small dense contractions:
+//   S[position][head]  = sum_k K[position][k] Q[head][k]            16 x 128 x (16 heads, 4 or 8 of them real)
+//   O[head][component] = sum_position P[position][head] V[position][component]
+// and v_mfma_f32_16x16x16_f16 does each in eight instructions per block.  Operand layouts of that instruction, lane =
+// i + 16 g: A: lane holds A[i][4g..4g+3]; B: lane holds B[4g..4g+3][i]; C/D: lane holds D[4g..4g+3][i].
+//   - Scores: A = keys (row = position), B = queries (column = head).  A lane loads its position's keys in four 16-byte
+//     pieces K[position][32u + 8g .. +8]; each piece feeds two instructions, so instruction (u, h) sums over the
+//     components 32u + 8g + 4h + e - any order of k will do as long as the queries are loaded the same way.
+//   - The result D[position 4g+e][head i] is, read the other way round, P^T[head i][positions 4g..4g+3]: exactly an A
+//     operand of the second contraction (row = head, k = position).  So the probabilities never move between lanes.
+//   - The second contraction wants B = values with k = position, i.e. four values of ONE component from four
+//     consecutive positions per lane, while the cache holds a position's 128 components together.  The wavefront's
+//     16 x 128 value tile therefore crosses LDS: written as loaded (16-byte pieces), read back by columns (rows 272 bytes
+//     apart, which puts the four lane groups on different banks).
+//   - Streaming softmax per head in the lanes that hold that head's column of S; the rescale factors of heads 4g..4g+3
+//     are fetched across lanes for the accumulators, which are laid out by (head, component).
+template <int R>
+__global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
+                                                                          const uint16_t *__restrict__ vc, uint16_t *__restrict__ out,
+                                                                          float *__restrict__ ws, int n_heads, int seq_len,
+                                                                          int64_t head_stride /* halves */, int chunk, int nsplit,
+                                                                          float scale_log2e)
+{
+    static_assert(R == 4 || R == 8, "group size");
+    typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+    typedef float float4v __attribute__((ext_vector_type(4)));
+    constexpr int VROW = 272;                                 // bytes between rows of the staged value tile (a multiple of 16)
+    __shared__ __align__(16) uint8_t s_v[ATT_WAVES][16 * VROW];
+    __shared__ float s_o[ATT_WAVES][8][ATT_D];
+    __shared__ float s_m[ATT_WAVES][16], s_l[ATT_WAVES][16];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, g = lane >> 4;
+    const int j = blockIdx.x / nsplit, sp = blockIdx.x - j * nsplit;
+    const int t_begin = sp * chunk, t_end = min(seq_len, t_begin + chunk);
+    const uint16_t *kh = kc + (int64_t)j * head_stride + g * 8;
+    const uint16_t *vh = vc + (int64_t)j * head_stride + g * 8;
+
+    // queries as B operands: lane (head li, g) holds Q[head][32u + 8g + 4h + e]; heads past the group are zero
+    half4v qb[8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        att_u32x4 v = {0u, 0u, 0u, 0u};
+        if (li < R) v = *reinterpret_cast<const att_u32x4 *>(q + (int64_t)(j * R + li) * ATT_D + 32 * u + 8 * g);
+        qb[2 * u] = __builtin_bit_cast(half4v, make_uint2(v.x, v.y));
+        qb[2 * u + 1] = __builtin_bit_cast(half4v, make_uint2(v.z, v.w));
+    }
+    float m = -INFINITY, l = 0.f;                             // of head li (the maximum is the same in the four lanes of a head)
+    float4v oacc[8];                                          // oacc[c][e] = O[head 4g+e][16c + li]
+#pragma unroll
+    for (int c = 0; c < 8; ++c) oacc[c] = (float4v){0.f, 0.f, 0.f, 0.f};
+
+    auto load_block = [&](att_u32x4 (&kt)[4], att_u32x4 (&vt)[4], int p0) {
+        const int64_t pos = min(p0 + li, t_end - 1);          // past the range: its last position, masked below
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            kt[u] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(kh + pos * ATT_D + 32 * u));
+            vt[u] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(vh + pos * ATT_D + 32 * u));
+        }
+    };
+    uint8_t *myv = s_v[wave];
+    auto process_block = [&](const att_u32x4 (&kt)[4], const att_u32x4 (&vt)[4], int p0) {
+        // values -> LDS as loaded: row = position li, bytes 64u + 16g
+#pragma unroll
+        for (int u = 0; u < 4; ++u) *reinterpret_cast<att_u32x4 *>(myv + li * VROW + 64 * u + 16 * g) = vt[u];
+        // scores
+        float4v sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const half4v a0 = __builtin_bit_cast(half4v, make_uint2(kt[u].x, kt[u].y));
+            const half4v a1 = __builtin_bit_cast(half4v, make_uint2(kt[u].z, kt[u].w));
+            sacc = __builtin_amdgcn_mfma_f32_16x16x16f16(a0, qb[2 * u], sacc, 0, 0, 0);
+            sacc = __builtin_amdgcn_mfma_f32_16x16x16f16(a1, qb[2 * u + 1], sacc, 0, 0, 0);
+        }
+        float sc[4], bm = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {                         // position p0 + 4g + e, head li
+            sc[e] = (p0 + 4 * g + e < t_end) ? sacc[e] * scale_log2e : -INFINITY;
+            bm = fmaxf(bm, sc[e]);
+        }
+        bm = fmaxf(bm, __shfl_xor(bm, 16));                   // the head's maximum over the block's sixteen positions
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        const float m_new = fmaxf(m, bm);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
+        const float base = (m_new == -INFINITY) ? 0.f : m_new;
+        float p[4];
+        l *= alpha;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { p[e] = __builtin_amdgcn_exp2f(sc[e] - base); l += p[e]; }
+        m = m_new;
+        const half4v pa = {(_Float16)p[0], (_Float16)p[1], (_Float16)p[2], (_Float16)p[3]};
+        // The accumulators hold heads 4g .. 4g+3: their rescale factors live in lanes 4g .. 4g+3.  Only when some head's
+        // maximum has moved (after the first blocks of a range it rarely does): the accumulators sit in the matrix
+        // cores' own registers, and rescaling them means moving all 32 out and back.
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+            float al[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) al[e] = __shfl(alpha, 4 * g + e);
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) oacc[c][e] *= al[e];
+        }
+        // weighted sums: B = values by columns from LDS (the wavefront's own tile: LDS operations of a wavefront are served in order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const uint16_t *col = reinterpret_cast<const uint16_t *>(myv + (4 * g) * VROW) + 16 * c + li;
+            const half4v vb = {as_h(col[0]), as_h(col[VROW / 2]), as_h(col[2 * (VROW / 2)]), as_h(col[3 * (VROW / 2)])};
+            oacc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, vb, oacc[c], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                      // the next block overwrites the tile
+    };
+
+    att_u32x4 ka[4], va[4], kb[4], vb2[4];
+    constexpr int STEP = 16 * ATT_WAVES;
+    int p0 = t_begin + wave * 16;
+    load_block(ka, va, p0);                                   // (scheduling barriers: see attn_decode_kernel)
+    __builtin_amdgcn_sched_barrier(0);
+    load_block(kb, vb2, p0 + STEP);
+    __builtin_amdgcn_sched_barrier(0);
+    for (; p0 < t_end; p0 += 2 * STEP) {
+        process_block(ka, va, p0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_block(ka, va, p0 + 2 * STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        if (p0 + STEP < t_end) process_block(kb, vb2, p0 + STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        load_block(kb, vb2, p0 + 3 * STEP);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- merge the four wavefronts' states ----------------------------------------------------------------------------------
+    l += __shfl_xor(l, 16);                                   // a head's sum over its four lanes
+    l += __shfl_xor(l, 32);
+    if (g == 0) { s_m[wave][li] = m; s_l[wave][li] = l; }
+    if (4 * g < R) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s_o[wave][4 * g + e][16 * c + li] = oacc[c][e];
+    }
+    __syncthreads();
+    float *ws_o = ws, *ws_m = ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS, *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS;
+    for (int idx = tid; idx < R * ATT_D; idx += 64 * ATT_WAVES) {
+        const int r = idx >> 7, d = idx & (ATT_D - 1);
+        float M = s_m[0][r];
+#pragma unroll
+        for (int w = 1; w < ATT_WAVES; ++w) M = fmaxf(M, s_m[w][r]);            // finite: the range is not empty
+        float L = 0.f, O = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) {
+            const float f = __builtin_amdgcn_exp2f(s_m[w][r] - M);
+            L = __builtin_fmaf(s_l[w][r], f, L);
+            O = __builtin_fmaf(s_o[w][r][d], f, O);
+        }
+        const int head = j * R + r;
+        if (nsplit == 1) {
+            out[(int64_t)head * ATT_D + d] = as_u16((half_t)(O / L));
+        } else {
+            ws_o[((int64_t)head * ATT_MAX_SPLITS + sp) * ATT_D + d] = O;
+            if (d == 0) { ws_m[(int64_t)head * ATT_MAX_SPLITS + sp] = M; ws_l[(int64_t)head * ATT_MAX_SPLITS + sp] = L; }
+        }
+    }
+}
+
+// Merge of the splits: one workgroup of 128 threads per query head, thread d for component d.  Only entries below
+// nsplit are read (the rest of the workspace is whatever earlier calls left there, possibly never touched).
 __global__ __launch_bounds__(ATT_D) void attn_merge_kernel(const float *__restrict__ ws, uint16_t *__restrict__ out, int n_heads, int nsplit)
 {
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
     const int head = blockIdx.x, d = threadIdx.x;
-    const f32x4 *ws_o = reinterpret_cast<const f32x4 *>(ws + ((int64_t)head * ATT_D + d) * ATT_MAX_SPLITS);
-    const f32x4 *ws_m = reinterpret_cast<const f32x4 *>(ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS + (int64_t)head * ATT_MAX_SPLITS);
-    const f32x4 *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS / 4;
-    const int n4 = (nsplit + 3) / 4;
+    const float *ws_o = ws + (int64_t)head * ATT_MAX_SPLITS * ATT_D + d;
+    const float *ws_m = ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS + (int64_t)head * ATT_MAX_SPLITS;
+    const float *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS;
     float M = -INFINITY;
-#pragma unroll 4
-    for (int c = 0; c < n4; ++c) {
-        const f32x4 m4 = ws_m[c];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) M = fmaxf(M, 4 * c + e < nsplit ? m4[e] : -INFINITY);
-    }
+#pragma unroll 8
+    for (int i = 0; i < nsplit; ++i) M = fmaxf(M, ws_m[i]);
     float L = 0.f, O = 0.f;
-#pragma unroll 4
-    for (int c = 0; c < n4; ++c) {
-        const f32x4 m4 = ws_m[c], l4 = ws_l[c], o4 = ws_o[c];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool in = 4 * c + e < nsplit;
-            const float f = in ? __builtin_amdgcn_exp2f(m4[e] - M) : 0.f;
-            L = __builtin_fmaf(in ? l4[e] : 0.f, f, L);
-            O = __builtin_fmaf(in ? o4[e] : 0.f, f, O);
-        }
+#pragma unroll 8
+    for (int i = 0; i < nsplit; ++i) {
+        const float f = __builtin_amdgcn_exp2f(ws_m[i] - M);
+        L = __builtin_fmaf(ws_l[i], f, L);
+        O = __builtin_fmaf(ws_o[(int64_t)i * ATT_D], f, O);
     }
     out[(int64_t)head * ATT_D + d] = as_u16((half_t)(O / L));
 }
@@ -226,14 +393,17 @@ hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const 
     const int64_t head_stride = max_seq * ATT_D;
 #define IFLOW_ATT_GO(RR) hipLaunchKernelGGL((attn_decode_kernel<RR>), grid, block, 0, s, q, k_cache, v_cache, out, \
         static_cast<float *>(workspace), n_heads, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
+#define IFLOW_ATT_GO_MFMA(RR) hipLaunchKernelGGL((attn_decode_mfma_kernel<RR>), grid, block, 0, s, q, k_cache, v_cache, out, \
+        static_cast<float *>(workspace), n_heads, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
     switch (R) {
     case 1: IFLOW_ATT_GO(1); break;
     case 2: IFLOW_ATT_GO(2); break;
-    case 4: IFLOW_ATT_GO(4); break;
-    case 8: IFLOW_ATT_GO(8); break;
+    case 4: IFLOW_ATT_GO_MFMA(4); break;
+    case 8: IFLOW_ATT_GO_MFMA(8); break;
     default: return hipErrorInvalidValue;
     }
 #undef IFLOW_ATT_GO
+#undef IFLOW_ATT_GO_MFMA
     e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)n_heads), dim3(ATT_D), 0, s, static_cast<const float *>(workspace), out, n_heads, nsplit);
