@@ -12,7 +12,8 @@
 //     components each), so one load instruction covers four consecutive positions = 1 KB; the four lane groups of a
 //     wavefront keep separate running softmax states (maximum, sum, 128-component weighted value sum) for their
 //     positions.  The block after the current one is already requested while a block is processed.
-//   - All query heads of the group (1, 2, 4 or 8) are served from the same loaded keys and values.
+//   - All query heads of a group are served from the same loaded keys and values: one or two heads by the kernel
+//     described here, on the vector units; four or eight by attn_decode_mfma_kernel further down, on the matrix cores.
 //   - Softmax is computed the streaming way: per block one rescale of the running sums to the new maximum, then
 //     exp2 of the (pre-scaled) score differences.  fp32 throughout; the output is rounded to fp16 once.
 //   - A workgroup merges its sixteen states through LDS and writes one state per (head, split) to the caller's
