@@ -68,6 +68,30 @@ def test_attention_peaked_softmax_and_reused_workspace(gpu):
         assert np.isfinite(got).all() and e <= TOL, f"seq_len {T}: {e}"
 
 
+def test_attention_one_workspace_for_different_head_counts(gpu):
+    """One workspace, sized for the largest head count, serves launches of different head counts, group sizes and lengths
+    one after the other with no host synchronization between them: stream order alone keeps a launch's partial results
+    apart from the next one's."""
+    torch, iflow = gpu
+    from oracle import attention as att
+    nbytes = iflow.attn_decode_workspace_bytes(64)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    scale = 1.0 / np.sqrt(128.0)
+    cases = [(64, 8, 2000), (32, 32, 900), (8, 4, 1500), (64, 8, 1999), (16, 4, 2048), (32, 32, 901)]
+    pending = []
+    for n, (n_heads, n_kv, T) in enumerate(cases):
+        say(f"[case] attention, shared workspace, heads={n_heads} kv_heads={n_kv} seq_len={T}")
+        q, k, v = make(n_heads, n_kv, 2048, synth.BASE_SEED + 1650 + n)
+        out = torch.full((n_heads, 128), float("nan"), dtype=torch.float16, device="cuda")
+        iflow.attn_decode(dev16(torch, q), dev16(torch, k), dev16(torch, v), n_heads, n_kv, 128, T, 2048, scale, out, ws, nbytes)
+        pending.append((q, k, v, T, out))
+    torch.cuda.synchronize()
+    for q, k, v, T, out in pending:
+        ref = att.gqa_decode(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), T, scale)
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all() and rel(got, ref) <= TOL, f"heads {q.shape[0]}, seq_len {T}"
+
+
 def test_attention_graph_replay(gpu):
     torch, iflow = gpu
     from oracle import attention as att
