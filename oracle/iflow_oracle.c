@@ -24,7 +24,9 @@
  *     gets all levels 0;
  *   - blocks are runs of Bs consecutive elements of a row of the row-major [rows][cols] matrix;
  *   - in Eq.4 the even element is the high base-11 digit; Eq.5's q1 is the even element;
- *   - Eq.2 is evaluated exactly and rounded ONCE to fp16 (round to nearest even).
+ *   - Eq.2 is evaluated exactly and rounded ONCE to fp16 (round to nearest even);
+ *   - the 6-, 5- and 3-bit formats take Table 3's block sizes (64, 64, 32); the 2-bit format, which the feature list of
+ *     Section 1 names but Table 3 does not list, takes block size 32 like the 3-bit one (3 bits per weight stored).
  * All fp32 arithmetic below is plain IEEE single precision: compile with -ffp-contract=off and
  * without -ffast-math.
  */
@@ -36,15 +38,29 @@
 #include <omp.h>
 #endif
 
-/* ---- formats: names from the header rows of Table 3 ---------------------------------------- */
-enum { ORC_Q8_B32 = 0, ORC_Q8_B64 = 1, ORC_Q4_B32 = 2, ORC_Q4_B64 = 3, ORC_Q3H_B64 = 4, ORC_NFMT = 5 };
+/* ---- formats: names from the header rows of Table 3 (and Section 1's list for the 2-bit one) ----------- */
+enum { ORC_Q8_B32 = 0, ORC_Q8_B64 = 1, ORC_Q4_B32 = 2, ORC_Q4_B64 = 3, ORC_Q3H_B64 = 4,
+       ORC_Q6_B64 = 5, ORC_Q5_B64 = 6, ORC_Q3_B32 = 7, ORC_Q2_B32 = 8, ORC_NFMT = 9 };
 
-/* L = number of steps between min and max; Bs = block size; bits7 = 1 when Eq.4 pairs are stored */
-static int fmt_L(int f)  { return (f == ORC_Q8_B32 || f == ORC_Q8_B64) ? 255 : (f == ORC_Q4_B32 || f == ORC_Q4_B64) ? 15 : 10; }
-static int fmt_Bs(int f) { return (f == ORC_Q8_B32 || f == ORC_Q4_B32) ? 32 : 64; }
+/* k = bits of a level in Eq.1 (0 for the 3.5-bit format, whose levels come from Eq.3 and are stored as Eq.4 pairs) */
+static int fmt_bits(int f)
+{
+    switch (f) {
+    case ORC_Q8_B32: case ORC_Q8_B64: return 8;
+    case ORC_Q6_B64: return 6;
+    case ORC_Q5_B64: return 5;
+    case ORC_Q4_B32: case ORC_Q4_B64: return 4;
+    case ORC_Q3_B32: return 3;
+    case ORC_Q2_B32: return 2;
+    default: return 0;
+    }
+}
+/* L = number of steps between min and max: 2^k - 1 (Eq.1) or 10 (Eq.3); Bs = block size */
+static int fmt_L(int f)  { return f == ORC_Q3H_B64 ? 10 : (1 << fmt_bits(f)) - 1; }
+static int fmt_Bs(int f) { return (f == ORC_Q8_B32 || f == ORC_Q4_B32 || f == ORC_Q3_B32 || f == ORC_Q2_B32) ? 32 : 64; }
 static int fmt_ok(int f) { return f >= 0 && f < ORC_NFMT; }
-/* bytes of codes in one block: 8-bit -> Bs, 4-bit -> Bs/2, 3.5-bit -> 32 codes * 7 bits = 28 */
-static int fmt_code_bytes(int f) { int L = fmt_L(f), Bs = fmt_Bs(f); return L == 255 ? Bs : L == 15 ? Bs / 2 : (Bs / 2) * 7 / 8; }
+/* bytes of codes in one block: k-bit levels -> Bs * k / 8; 3.5-bit -> 32 codes * 7 bits = 28 */
+static int fmt_code_bytes(int f) { return f == ORC_Q3H_B64 ? 28 : fmt_Bs(f) * fmt_bits(f) / 8; }
 
 int orc_format_levels(int f)     { return fmt_ok(f) ? fmt_L(f) + 1 : -1; }
 int orc_format_block(int f)      { return fmt_ok(f) ? fmt_Bs(f) : -1; }
@@ -137,6 +153,8 @@ uint16_t orc_dequant_value(int q, uint16_t scale_h, uint16_t offset_h)
  *   8-bit : byte j = q[j]
  *   4-bit : byte j = q[2j] | q[2j+1] << 4
  *   3.5-bit: 32 Eq.4 codes as a little-endian bit stream, code j in bits [7j, 7j+7)
+ *   6-, 5-, 3-, 2-bit: the levels as a little-endian bit stream, level j in bits [kj, kj+k)
+ *   (the 8- and 4-bit rules above are this same stream for k = 8 and 4)
  */
 int orc_pack_canonical(int f, const uint8_t *q, const uint16_t *scale, const uint16_t *offset,
                        int64_t rows, int64_t cols, uint8_t *out)
@@ -152,10 +170,12 @@ int orc_pack_canonical(int f, const uint8_t *q, const uint16_t *scale, const uin
         memset(cd, 0, cb);
         if (L == 255) for (int j = 0; j < Bs; ++j) cd[j] = qb[j];
         else if (L == 15) for (int j = 0; j < Bs / 2; ++j) cd[j] = (uint8_t)(qb[2 * j] | (qb[2 * j + 1] << 4));
-        else for (int j = 0; j < Bs / 2; ++j) {
+        else if (L == 10) for (int j = 0; j < Bs / 2; ++j) {
             int c = orc_pair_encode(qb[2 * j], qb[2 * j + 1]);
             for (int t = 0; t < 7; ++t) if ((c >> t) & 1) { int bit = 7 * j + t; cd[bit >> 3] |= (uint8_t)(1u << (bit & 7)); }
         }
+        else for (int j = 0, k = fmt_bits(f); j < Bs; ++j)
+            for (int t = 0; t < k; ++t) if ((qb[j] >> t) & 1) { int bit = k * j + t; cd[bit >> 3] |= (uint8_t)(1u << (bit & 7)); }
     }
     return 0;
 }
@@ -173,11 +193,16 @@ int orc_unpack_canonical(int f, const uint8_t *in, int64_t rows, int64_t cols,
         scale[b] = (uint16_t)(rec[0] | (rec[1] << 8)); offset[b] = (uint16_t)(rec[2] | (rec[3] << 8));
         if (L == 255) for (int j = 0; j < Bs; ++j) qb[j] = cd[j];
         else if (L == 15) for (int j = 0; j < Bs / 2; ++j) { qb[2 * j] = cd[j] & 15; qb[2 * j + 1] = cd[j] >> 4; }
-        else for (int j = 0; j < Bs / 2; ++j) {
+        else if (L == 10) for (int j = 0; j < Bs / 2; ++j) {
             int c = 0, q1, q2;
             for (int t = 0; t < 7; ++t) { int bit = 7 * j + t; c |= ((cd[bit >> 3] >> (bit & 7)) & 1) << t; }
             orc_pair_decode(c, &q1, &q2);
             qb[2 * j] = (uint8_t)q1; qb[2 * j + 1] = (uint8_t)q2;
+        }
+        else for (int j = 0, k = fmt_bits(f); j < Bs; ++j) {
+            int v = 0;
+            for (int t = 0; t < k; ++t) { int bit = k * j + t; v |= ((cd[bit >> 3] >> (bit & 7)) & 1) << t; }
+            qb[j] = (uint8_t)v;
         }
     }
     return 0;
@@ -199,6 +224,12 @@ int orc_unpack_canonical(int f, const uint8_t *in, int64_t rows, int64_t cols,
  *   consecutive weights v0..v7 form one 32-bit word whose nibbles, from the least significant,
  *   are v0 v2 v4 v6 v1 v3 v5 v7.
  * 8-bit: first all code bytes in natural order (cols bytes per row), then all headers as for 4-bit.
+ * 6-, 5-, 3-, 2-bit: the level's bits are split over bit planes, stored one after the other (each plane: all rows, row
+ *   after row), then all headers as for 4-bit.  Planes, from the level's least significant bits: 6-bit = 4 + 2 bits,
+ *   5-bit = 4 + 1, 3-bit = 2 + 1, 2-bit = 2.  A plane of width w stores cols*w/8 bytes per row as little-endian 32-bit
+ *   words; a word holds the plane's bits of n = 32/w consecutive weights u0..u(n-1): u(e) sits at bit
+ *   (e/2)*w + 16*(e%2) - the even weights in the low half, the odd ones in the high half, each in order.
+ *   (For w = 4 this is the 4-bit format's nibble order.)
  */
 static void put32(uint8_t *p, uint32_t v) { p[0] = v & 255; p[1] = (v >> 8) & 255; p[2] = (v >> 16) & 255; p[3] = (uint8_t)(v >> 24); }
 
@@ -225,6 +256,30 @@ int orc_pack_device(int f, const uint8_t *q, const uint16_t *scale, const uint16
                     put32(strip_base + plane * n_t * 16 + j_in * 16 + word * 4, W);
                 }
             }
+        return 0;
+    }
+    if (L != 255 && L != 15) {                         /* bit planes */
+        int k = fmt_bits(f);
+        int widths[2] = { k >= 5 ? 4 : 2, k == 6 ? 2 : (k == 5 || k == 3) ? 1 : 0 };
+        uint8_t *plane = out;
+        memset(out, 0, (size_t)(rows * cols * k / 8));
+        for (int p = 0, shift = 0; p < 2 && widths[p]; shift += widths[p], ++p) {
+            int w = widths[p], n = 32 / w;
+            for (int64_t r = 0; r < rows; ++r)
+                for (int64_t c = 0; c < cols; ++c) {
+                    uint32_t v = ((uint32_t)q[r * cols + c] >> shift) & ((1u << w) - 1u);
+                    int e = (int)(c % n);
+                    int bit = (e / 2) * w + 16 * (e % 2);
+                    uint8_t *word = plane + (r * (cols / n) + c / n) * 4;
+                    uint32_t old = (uint32_t)word[0] | (uint32_t)word[1] << 8 | (uint32_t)word[2] << 16 | (uint32_t)word[3] << 24;
+                    put32(word, old | v << bit);
+                }
+            plane += rows * cols * w / 8;
+        }
+        for (int64_t b = 0; b < rows * nbk; ++b) {
+            plane[4 * b] = scale[b] & 255; plane[4 * b + 1] = scale[b] >> 8;
+            plane[4 * b + 2] = offset[b] & 255; plane[4 * b + 3] = offset[b] >> 8;
+        }
         return 0;
     }
     int64_t code_bytes_row = (L == 255) ? cols : cols / 2;

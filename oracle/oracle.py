@@ -19,8 +19,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "iflow_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-Q8_B32, Q8_B64, Q4_B32, Q4_B64, Q3H_B64 = range(5)
-FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B64, "Q3H_B64": Q3H_B64}
+Q8_B32, Q8_B64, Q4_B32, Q4_B64, Q3H_B64, Q6_B64, Q5_B64, Q3_B32, Q2_B32 = range(9)
+FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B64, "Q3H_B64": Q3H_B64,
+           "Q6_B64": Q6_B64, "Q5_B64": Q5_B64, "Q3_B32": Q3_B32, "Q2_B32": Q2_B32}
 
 
 def build(force: bool = False) -> str:
