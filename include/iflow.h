@@ -18,7 +18,7 @@
  * Packed device layout, version 1 (sizes are exact: no padding anywhere)
  *   Every block stores its codes plus two fp16 numbers (remark after Table 3):
  *       scale  = fp16((max - min) / L)      offset = fp16(min)
- *   with L = 255 (8-bit), 15 (4-bit), 10 (3.5-bit, Eq.3).
+ *   with L = 2^k - 1 for k-bit levels (Eq.1: 255, 63, 31, 15, 7, 3) and 10 for 3.5-bit (Eq.3).
  *
  *   IFLOW_Q3H_B64 - 32 bytes per block of 64 weights.  The 64 levels q0..q63 give 32 pair codes
  *     c[j] = q[2j]*11 + q[2j+1] (Eq.4, 0..120).  With S, O the 16-bit patterns of scale and offset
@@ -36,6 +36,13 @@
  *     the least significant, are v0 v2 v4 v6 v1 v3 v5 v7.
  *   IFLOW_Q8_B32 / IFLOW_Q8_B64 - first all levels as bytes in natural order (cols bytes per
  *     row); then the headers as for 4-bit.
+ *   IFLOW_Q6_B64 / IFLOW_Q5_B64 / IFLOW_Q3_B32 / IFLOW_Q2_B32 - a level's bits are split over bit planes, stored one
+ *     after the other (each plane: all rows, row after row); then the headers as for 4-bit.  Planes, from the level's
+ *     least significant bits: 6-bit = 4 + 2 bits, 5-bit = 4 + 1, 3-bit = 2 + 1, 2-bit = 2.  A plane of width w stores
+ *     cols*w/8 bytes per row as little-endian 32-bit words; a word holds the plane's bits of n = 32/w consecutive
+ *     weights u0..u(n-1), u(e) at bit (e/2)*w + 16*(e%2): the even weights in the low half, the odd ones in the high
+ *     half, each in order.  (For w = 4 this is the 4-bit format's nibble order.  A kernel turns a field of either half
+ *     into an fp16 number with one AND-OR, so a plane costs about one instruction per weight and product.)
  */
 #ifndef IFLOW_H
 #define IFLOW_H
@@ -47,13 +54,18 @@
 extern "C" {
 #endif
 
-/* Formats: names and block sizes from the header rows of Table 3. */
+/* Formats: names and block sizes from the header rows of Table 3.  The 2-bit format is in Section 1's list of supported
+ * quantizations but not in Table 3: it takes the 3-bit format's block size here. */
 typedef enum {
     IFLOW_Q8_B32 = 0,   /* 8-bit levels, block 32: 9   bits/weight */
     IFLOW_Q8_B64 = 1,   /* 8-bit levels, block 64: 8.5 bits/weight */
     IFLOW_Q4_B32 = 2,   /* 4-bit levels, block 32: 5   bits/weight */
     IFLOW_Q4_B64 = 3,   /* 4-bit levels, block 64: 4.5 bits/weight */
-    IFLOW_Q3H_B64 = 4   /* 3.5-bit ("Q3H"): 11 levels, two weights per 7-bit code, block 64: 4 bits/weight */
+    IFLOW_Q3H_B64 = 4,  /* 3.5-bit ("Q3H"): 11 levels, two weights per 7-bit code, block 64: 4 bits/weight */
+    IFLOW_Q6_B64 = 5,   /* 6-bit levels, block 64: 6.5 bits/weight */
+    IFLOW_Q5_B64 = 6,   /* 5-bit levels, block 64: 5.5 bits/weight */
+    IFLOW_Q3_B32 = 7,   /* 3-bit levels, block 32: 4   bits/weight */
+    IFLOW_Q2_B32 = 8    /* 2-bit levels, block 32: 3   bits/weight */
 } iflow_format_t;
 
 typedef enum {
@@ -76,12 +88,12 @@ const char *iflow_status_string(iflow_status_t status);
 /* hipError_t (as int) of the most recent failed HIP call made by this library on the calling thread; 0 if none. */
 int iflow_last_hip_error(void);
 
-/* Block size (32 or 64), number of levels (256, 16 or 11), or -1 for an unknown format.  Table 3 / Eq.1 / Eq.3. */
+/* Block size (32 or 64), number of levels (2^k for k-bit levels, 11 for 3.5-bit), or -1 for an unknown format.  Table 3 / Eq.1 / Eq.3. */
 int iflow_format_block(iflow_format_t format);
 int iflow_format_levels(iflow_format_t format);
 
 /* Bytes of the packed matrix: rows*cols/block * (code bytes per block + 4).  This is Table 3's "actual
- * bits/weight" (9, 8.5, 5, 4.5, 4) times rows*cols/8.  `bytes` is a host pointer. */
+ * bits/weight" (9, 8.5, 6.5, 5.5, 5, 4.5, 4, 4; 3 for the 2-bit format) times rows*cols/8.  `bytes` is a host pointer. */
 iflow_status_t iflow_packed_bytes(iflow_format_t format, int64_t rows, int64_t cols, size_t *bytes);
 
 /* Eq.1 (Eq.3 for Q3H) per block, then Eq.4 packing, into the device layout.

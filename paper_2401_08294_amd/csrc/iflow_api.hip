@@ -131,7 +131,9 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     hipStream_t hs = (hipStream_t)stream;
     if (batch >= 32 && cols % 64 == 0)
         return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, hs));
-    if (cols % 64 == 0 && batch >= (format == IFLOW_Q8_B32 || format == IFLOW_Q8_B64 ? IFLOW_SMALL_MFMA_MIN_BATCH_Q8 : IFLOW_SMALL_MFMA_MIN_BATCH)) {
+    // (the bit-plane formats have no kernel of the middle kind: up to 31 vectors they stay on the vector kernel)
+    if (cols % 64 == 0 && !iflow::kind_has_planes(fi.kind) &&
+        batch >= (format == IFLOW_Q8_B32 || format == IFLOW_Q8_B64 ? IFLOW_SMALL_MFMA_MIN_BATCH_Q8 : IFLOW_SMALL_MFMA_MIN_BATCH)) {
         for (int64_t b0 = 0; b0 < batch; b0 += 16) {
             const int64_t nb = batch - b0 < 16 ? batch - b0 : 16;
             hipError_t e = iflow::launch_qgemm_small((int)format, packed, rows, cols, X + b0 * cols, nb, Y + b0 * rows, hs);

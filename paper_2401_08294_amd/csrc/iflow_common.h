@@ -16,7 +16,16 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
 // ---- formats (Table 3 of the paper: bits, block size; Eq.1 / Eq.3: number of steps L) -------------
-enum Kind { KIND_Q8 = 0, KIND_Q4 = 1, KIND_Q3H = 2 };
+// The 6-, 5-, 3- and 2-bit formats store a level as bit planes (Planes: widths of the low and the high plane; the high
+// plane's value counts 2^WA); the 4-bit format is the one-plane case with its own, older code path.
+enum Kind { KIND_Q8 = 0, KIND_Q4 = 1, KIND_Q3H = 2, KIND_Q6 = 3, KIND_Q5 = 4, KIND_Q3 = 5, KIND_Q2 = 6 };
+
+template <int KIND> struct Planes { static constexpr int WA = 0, WB = 0; };
+template <> struct Planes<KIND_Q6> { static constexpr int WA = 4, WB = 2; };
+template <> struct Planes<KIND_Q5> { static constexpr int WA = 4, WB = 1; };
+template <> struct Planes<KIND_Q3> { static constexpr int WA = 2, WB = 1; };
+template <> struct Planes<KIND_Q2> { static constexpr int WA = 2, WB = 0; };
+constexpr bool kind_has_planes(int kind) { return kind >= KIND_Q6; }
 
 template <int F> struct Fmt;
 template <> struct Fmt<IFLOW_Q8_B32>  { static constexpr int kind = KIND_Q8,  block = 32, L = 255, code_bytes = 32; };
@@ -24,6 +33,10 @@ template <> struct Fmt<IFLOW_Q8_B64>  { static constexpr int kind = KIND_Q8,  bl
 template <> struct Fmt<IFLOW_Q4_B32>  { static constexpr int kind = KIND_Q4,  block = 32, L = 15,  code_bytes = 16; };
 template <> struct Fmt<IFLOW_Q4_B64>  { static constexpr int kind = KIND_Q4,  block = 64, L = 15,  code_bytes = 32; };
 template <> struct Fmt<IFLOW_Q3H_B64> { static constexpr int kind = KIND_Q3H, block = 64, L = 10,  code_bytes = 28; };
+template <> struct Fmt<IFLOW_Q6_B64>  { static constexpr int kind = KIND_Q6,  block = 64, L = 63,  code_bytes = 48; };
+template <> struct Fmt<IFLOW_Q5_B64>  { static constexpr int kind = KIND_Q5,  block = 64, L = 31,  code_bytes = 40; };
+template <> struct Fmt<IFLOW_Q3_B32>  { static constexpr int kind = KIND_Q3,  block = 32, L = 7,   code_bytes = 12; };
+template <> struct Fmt<IFLOW_Q2_B32>  { static constexpr int kind = KIND_Q2,  block = 32, L = 3,   code_bytes = 8; };
 
 struct FormatInfo { int kind, block, L, code_bytes; };
 inline bool format_info(int f, FormatInfo *fi)
@@ -34,6 +47,10 @@ inline bool format_info(int f, FormatInfo *fi)
     case IFLOW_Q4_B32:  *fi = {KIND_Q4, 32, 15, 16};  return true;
     case IFLOW_Q4_B64:  *fi = {KIND_Q4, 64, 15, 32};  return true;
     case IFLOW_Q3H_B64: *fi = {KIND_Q3H, 64, 10, 28}; return true;
+    case IFLOW_Q6_B64:  *fi = {KIND_Q6, 64, 63, 48};  return true;
+    case IFLOW_Q5_B64:  *fi = {KIND_Q5, 64, 31, 40};  return true;
+    case IFLOW_Q3_B32:  *fi = {KIND_Q3, 32, 7, 12};   return true;
+    case IFLOW_Q2_B32:  *fi = {KIND_Q2, 32, 3, 8};    return true;
     default: return false;
     }
 }

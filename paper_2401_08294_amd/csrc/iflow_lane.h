@@ -11,6 +11,12 @@ template <int KIND> struct Geo;
 template <> struct Geo<KIND_Q3H> { static constexpr int WPL = 64, XD = 32, WD = 8; };   // weights, x dwords, weight dwords per lane
 template <> struct Geo<KIND_Q4>  { static constexpr int WPL = 32, XD = 16, WD = 4; };
 template <> struct Geo<KIND_Q8>  { static constexpr int WPL = 16, XD = 8,  WD = 4; };
+// bit-plane formats: 32 weights per lane; d[0..] holds the low plane's words, then the high plane's
+template <> struct Geo<KIND_Q6>  { static constexpr int WPL = 32, XD = 16, WD = 6; };   // 4 + 2 words
+template <> struct Geo<KIND_Q5>  { static constexpr int WPL = 32, XD = 16, WD = 5; };   // 4 + 1
+template <> struct Geo<KIND_Q3>  { static constexpr int WPL = 32, XD = 16, WD = 3; };   // 2 + 1
+template <> struct Geo<KIND_Q2>  { static constexpr int WPL = 32, XD = 16, WD = 2; };   // 2
+
 
 // Activations of one lane for one batch column, arranged for the format's decode, plus the two
 // constants that undo the conversion bias: bias_sum = sum_k bias_k x_k and x_sum = sum_k x_k.
@@ -30,6 +36,34 @@ __device__ __forceinline__ uint32_t mask_lt(int a, int b)
     return m;
 }
 
+// ---- bit planes ------------------------------------------------------------------------------------
+// A plane word holds fields of W bits, the even weights' in its low half and the odd weights' in its high half, so
+// field i of a word pairs with the activation pair (x[2i], x[2i+1]) of the word's weights.  A field at bit p < 8 of both
+// halves becomes the fp16 pair (B + v_even, B + v_odd), B = 2^(10-p), with one AND-OR: the field lands in the mantissa
+// of an fp16 number whose exponent makes bit p count 1.  Fields at bits 8..15 are reached through one shift by 8.
+// plane_bias<W>(i): the B of field i of a word, as the decode below places it.
+template <int W> __device__ __forceinline__ constexpr float plane_bias(int i) { return (float)(1024 >> (W * (i & (8 / W - 1)))); }
+
+// sum over a word's fields of (bias + value) . x-pair, for NB columns; the word's first pair is xr[b].v[J0]
+template <int W, int KIND, int NB, int J0>
+__device__ __forceinline__ void plane_word_dot(uint32_t d, const XRegs<KIND> (&xr)[NB], float (&acc)[NB])
+{
+    constexpr int PER_BYTE = 8 / W;                           // fields in the low 8 bits of a half: 2, 4 or 8
+    constexpr uint32_t ONES = (1u << W) - 1u;
+    const uint32_t e = d >> 8;
+#pragma unroll
+    for (int i = 0; i < PER_BYTE; ++i) {
+        const uint32_t mask = (ONES << (W * i)) * 0x00010001u;
+        const uint32_t magic = (uint32_t)((25 - W * i) << 10) * 0x00010001u;
+        const half2_t lo = as_h2((d & mask) | magic), hi = as_h2((e & mask) | magic);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            acc[b] = dot2(lo, xr[b].v[J0 + i], acc[b]);
+            acc[b] = dot2(hi, xr[b].v[J0 + PER_BYTE + i], acc[b]);
+        }
+    }
+}
+
 template <int KIND>
 __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restrict__ x, int k0)
 {
@@ -41,7 +75,7 @@ __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restri
         n[4 * j] = q.x; n[4 * j + 1] = q.y; n[4 * j + 2] = q.z; n[4 * j + 3] = q.w;
     }
     const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
-    if (KIND == KIND_Q3H) {
+    if constexpr (KIND == KIND_Q3H) {
         // decode slot m works on weights 4m..4m+3 and produces (q[4m], q[4m+2]) and (q[4m+1], q[4m+3]):
         // v[m] = (x[4m], x[4m+2]), v[16+m] = (x[4m+1], x[4m+3])
         float se = 0.f, so = 0.f;
@@ -54,7 +88,7 @@ __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restri
         }
         xr.bias_sum = IFLOW_Q3H_BIAS1 * se + IFLOW_Q3H_BIAS2 * so;
         xr.x_sum = se + so;
-    } else if (KIND == KIND_Q4) {
+    } else if constexpr (KIND == KIND_Q4) {
         // word g of the lane covers weights 8g..8g+7; slots 0 and 2 are biased by 1024, slots 1 and 3 by 64
         float sa = 0.f, sb = 0.f;
 #pragma unroll
@@ -64,6 +98,21 @@ __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restri
         }
         xr.bias_sum = 1024.0f * sa + 64.0f * sb;
         xr.x_sum = sa + sb;
+    } else if constexpr (kind_has_planes(KIND)) {
+        // natural pairs; pair j meets field j % (16 / WA) of a low-plane word and field j % (16 / WB) of a high-plane word
+        constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;
+        float sb = 0.f, sx = 0.f;
+#pragma unroll
+        for (int j = 0; j < XD; ++j) {
+            xr.v[j] = as_h2(n[j]);
+            const float pair = dot2(xr.v[j], ones, 0.f);
+            float bias = plane_bias<WA>(j % (16 / WA));
+            if constexpr (WB > 0) bias += (float)(1 << WA) * plane_bias<WB>(j % (16 / WB));
+            sb = __builtin_fmaf(bias, pair, sb);
+            sx += pair;
+        }
+        xr.bias_sum = sb;
+        xr.x_sum = sx;
     } else {
         float sx = 0.f;
 #pragma unroll
@@ -80,7 +129,7 @@ template <int KIND> struct WRegs { uint32_t d[Geo<KIND>::WD]; uint32_t hdr; };
 template <int KIND, int NB>
 __device__ __forceinline__ void lane_dot(const WRegs<KIND> &w, const XRegs<KIND> (&xr)[NB], float (&acc)[NB])
 {
-    if (KIND == KIND_Q3H) {
+    if constexpr (KIND == KIND_Q3H) {
         float a1[NB], a2[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) { a1[b] = 0.f; a2[b] = 0.f; }
@@ -102,7 +151,7 @@ __device__ __forceinline__ void lane_dot(const WRegs<KIND> &w, const XRegs<KIND>
         }
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(a2[b], IFLOW_Q3H_SCALE2, a1[b]);
-    } else if (KIND == KIND_Q4) {
+    } else if constexpr (KIND == KIND_Q4) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[b] = 0.f;
 #pragma unroll
@@ -120,6 +169,23 @@ __device__ __forceinline__ void lane_dot(const WRegs<KIND> &w, const XRegs<KIND>
                 acc[b] = dot2(t3, xr[b].v[4 * g + 3], acc[b]);
             }
         }
+    } else if constexpr (kind_has_planes(KIND)) {
+        // level = low plane + 2^WA * high plane: two biased sums, combined once
+        constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;
+        // a lane's 32 weights take WA words of the low plane (d[0..WA-1]) and WB words of the high plane (d[WA..])
+        float lo[NB], hi[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) { lo[b] = 0.f; hi[b] = 0.f; }
+        plane_word_dot<WA, KIND, NB, 0>(w.d[0], xr, lo);
+        plane_word_dot<WA, KIND, NB, 16 / WA>(w.d[1], xr, lo);
+        if constexpr (WA == 4) {
+            plane_word_dot<WA, KIND, NB, 8>(w.d[2], xr, lo);
+            plane_word_dot<WA, KIND, NB, 12>(w.d[3], xr, lo);
+        }
+        if constexpr (WB > 0) plane_word_dot<WB, KIND, NB, 0>(w.d[WA], xr, hi);
+        if constexpr (WB == 2) plane_word_dot<WB, KIND, NB, 8>(w.d[WA + 1], xr, hi);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[b] = WB ? __builtin_fmaf(hi[b], (float)(1 << WA), lo[b]) : lo[b];
     } else {
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[b] = 0.f;

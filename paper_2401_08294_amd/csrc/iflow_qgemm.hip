@@ -25,12 +25,28 @@ __device__ __forceinline__ uint32_t pack_h2(half2_t v) { return as_u32(v); }
 // the code words and the block header bits this thread can see.
 struct Raw16 { uint32_t d[4]; uint32_t hdr; };
 
+// (bit-plane formats: d[0..1] = the low plane's 8 or 4 bytes, d[2] = the high plane's word; `plane_b` = where the high
+// plane starts in the packed matrix)
 template <int F>
-__device__ __forceinline__ void load16(const uint8_t *packed, int64_t header_offset, int64_t row, int nbk,
+__device__ __forceinline__ void load16(const uint8_t *packed, int64_t header_offset, int64_t plane_b, int64_t row, int nbk,
                                        int kb /* 64-column chunk */, int qd, Raw16 &r)
 {
     typedef Fmt<F> T;
-    if (T::kind == KIND_Q3H) {
+    if constexpr (kind_has_planes(T::kind)) {
+        constexpr int WA = Planes<T::kind>::WA, WB = Planes<T::kind>::WB;
+        const int64_t cols = (int64_t)nbk * T::block;
+        const int k0 = kb * 64 + qd * 16;
+        r.hdr = *reinterpret_cast<const uint32_t *>(packed + header_offset + (row * nbk + k0 / T::block) * 4);
+        r.d[1] = 0; r.d[2] = 0; r.d[3] = 0;
+        if constexpr (WA == 4) {
+            const uint2 two = *reinterpret_cast<const uint2 *>(packed + row * (cols / 2) + k0 / 2);
+            r.d[0] = two.x; r.d[1] = two.y;
+        } else {
+            r.d[0] = *reinterpret_cast<const uint32_t *>(packed + row * (cols / 4) + k0 / 4);
+        }
+        if constexpr (WB == 2) r.d[2] = *reinterpret_cast<const uint32_t *>(packed + plane_b + row * (cols / 4) + k0 / 4);
+        if constexpr (WB == 1) r.d[2] = *reinterpret_cast<const uint32_t *>(packed + plane_b + row * (cols / 8) + (k0 / 32) * 4);
+    } else if (T::kind == KIND_Q3H) {
         // words 2qd, 2qd+1 of the block: plane qd/2, 8 bytes at offset (qd%2)*8 inside the block's 16 bytes
         const int t = kb >> 6, jin = kb & 63;
         const int n_t = min(64, nbk - (t << 6));
@@ -50,12 +66,53 @@ __device__ __forceinline__ void load16(const uint8_t *packed, int64_t header_off
     }
 }
 
+// The 8 / W fields in the low byte of both halves of a plane word, as exact fp16 pairs (even weight, odd weight).
+template <int W>
+__device__ __forceinline__ void plane_byte_fields(uint32_t word, half2_t *v)
+{
+#pragma unroll
+    for (int i = 0; i < 8 / W; ++i) {
+        const uint32_t mask = (((1u << W) - 1u) << (W * i)) * 0x00010001u;
+        const uint32_t magic = (uint32_t)((25 - W * i) << 10) * 0x00010001u;            // bit W i counts 1
+        const half_t bias = (half_t)(float)(1024 >> (W * i));
+        const half2_t b2 = {bias, bias};
+        v[i] = as_h2((word & mask) | magic) - b2;
+    }
+}
+// Sixteen consecutive weights' fields of a W-bit plane: W bytes of each half, `first` = the byte they start at.
+template <int W>
+__device__ __forceinline__ void plane_fields16(const uint32_t *words, int first, half2_t (&v)[8])
+{
+    if constexpr (W == 4) {
+        plane_byte_fields<4>(words[0], &v[0]); plane_byte_fields<4>(words[0] >> 8, &v[2]);
+        plane_byte_fields<4>(words[1], &v[4]); plane_byte_fields<4>(words[1] >> 8, &v[6]);
+    } else if constexpr (W == 2) {
+        plane_byte_fields<2>(words[0], &v[0]); plane_byte_fields<2>(words[0] >> 8, &v[4]);
+    } else {
+        plane_byte_fields<1>(words[0] >> (8 * first), &v[0]);
+    }
+}
+
 // Eq.5 and Eq.2: the sixteen weights as eight fp16 pairs in natural order, bit-identical to iflow_dequant.
 template <int F>
 __device__ __forceinline__ void decode16(const Raw16 &r, int qd, uint32_t (&out)[8])
 {
     typedef Fmt<F> T;
-    if (T::kind == KIND_Q3H) {
+    if constexpr (kind_has_planes(T::kind)) {
+        constexpr int WA = Planes<T::kind>::WA, WB = Planes<T::kind>::WB;
+        const half2_t so = as_h2(r.hdr);
+        const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
+        half2_t lo[8], hi[8];
+        plane_fields16<WA>(&r.d[0], 0, lo);
+        if constexpr (WB > 0) plane_fields16<WB>(&r.d[2], qd & 1, hi);                 // a 1-bit word serves two quarters
+        const half2_t up = {(half_t)(float)(1 << WA), (half_t)(float)(1 << WA)};
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            half2_t level = lo[m];
+            if constexpr (WB > 0) level = __builtin_elementwise_fma(hi[m], up, lo[m]);   // exact: an integer below 64
+            out[m] = pack_h2(__builtin_elementwise_fma(level, s2, o2));                  // Eq.2, one rounding
+        }
+    } else if (T::kind == KIND_Q3H) {
         // header: word i carries scale bits 2i,2i+1 at 14-15 and offset bits at 30-31; the four threads of a
         // block sit in one quad of lanes and OR their parts together
         uint32_t h = 0;
@@ -135,6 +192,7 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
     const int wr = tid >> 2, wq = tid & 3;
     const int64_t wrow = min(n0 + wr, rows - 1);
     const int nchunks = cols / GM_BK;
+    const int64_t plane_b = (int64_t)rows * cols * Planes<Fmt<F>::kind>::WA / 8;   // bit-plane formats: start of the high plane
 
     // (plain vector types and separately named stages: an array of structs that hold HIP's uint4 class is not split
     // into registers completely, and the part left over is parked in LDS, with a full wait right after its load)
@@ -143,7 +201,7 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
         const int kc = min(kb, nchunks - 1);
         const u32x4_t *xp = xsrc + (int64_t)kc * 8;            // 64 halves per row and chunk = 8 x 16 bytes; this thread's half = 4
         st.x0 = xp[0]; st.x1 = xp[1]; st.x2 = xp[2]; st.x3 = xp[3];
-        load16<F>(packed, header_offset, wrow, nbk, kc, wq, st.w);
+        load16<F>(packed, header_offset, plane_b, wrow, nbk, kc, wq, st.w);
     };
     auto stash = [&](const Stage &st, int buf) {               // registers -> LDS, weights decoded on the way
         uint32_t wv[8];
@@ -232,6 +290,10 @@ hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64
     case IFLOW_Q4_B32: return gemm_one<IFLOW_Q4_B32>(packed, rows, cols, X, batch, Y, s);
     case IFLOW_Q4_B64: return gemm_one<IFLOW_Q4_B64>(packed, rows, cols, X, batch, Y, s);
     case IFLOW_Q3H_B64: return gemm_one<IFLOW_Q3H_B64>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q6_B64: return gemm_one<IFLOW_Q6_B64>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q5_B64: return gemm_one<IFLOW_Q5_B64>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q3_B32: return gemm_one<IFLOW_Q3_B32>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q2_B32: return gemm_one<IFLOW_Q2_B32>(packed, rows, cols, X, batch, Y, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -80,12 +80,20 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
 
         // where this lane's codes (and, for Q4/Q8, its header) sit inside a row
         int64_t code_off, row_stride, hdr_off = 0;
+        int64_t code_off_b = 0, row_stride_b = 0;             // bit-plane formats: the high plane
         int plane1 = 0;
-        if (KIND == KIND_Q3H) {
+        if constexpr (KIND == KIND_Q3H) {
             const int n_t = min(64, nbk - t * 64);
             row_stride = (int64_t)nbk * 32;
             code_off = (int64_t)t * 2048 + lane_a * 16;
             plane1 = n_t * 16;
+        } else if constexpr (kind_has_planes(KIND)) {
+            constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;
+            row_stride = (int64_t)cols * WA / 8;
+            code_off = (int64_t)k0 * WA / 8;
+            row_stride_b = (int64_t)cols * WB / 8;
+            code_off_b = (int64_t)rows * cols * WA / 8 + (int64_t)k0 * WB / 8;
+            hdr_off = header_offset + (int64_t)(k0 / T::block) * 4;
         } else {
             row_stride = (KIND == KIND_Q4) ? cols / 2 : cols;
             code_off = (KIND == KIND_Q4) ? k0 / 2 : k0;
@@ -98,13 +106,33 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + min(i + u, nr - 1);        // rows past the end repeat the last one and are dropped below
                 const uint8_t *p = lane_base + (int64_t)r * row_stride;
-                uint4 a = *reinterpret_cast<const uint4 *>(p);
-                w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
-                if (KIND == KIND_Q3H) {
-                    uint4 c = *reinterpret_cast<const uint4 *>(p + plane1);
-                    w[u].d[4] = c.x; w[u].d[5] = c.y; w[u].d[6] = c.z; w[u].d[7] = c.w;
-                } else {
+                if constexpr (kind_has_planes(KIND)) {
+                    // 32 weights: 16 or 8 bytes of the low plane, 8, 4 or no bytes of the high plane, the block's header
+                    constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;
+                    if constexpr (WA == 4) {
+                        uint4 a = *reinterpret_cast<const uint4 *>(p);
+                        w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
+                    } else {
+                        uint2 a = *reinterpret_cast<const uint2 *>(p);
+                        w[u].d[0] = a.x; w[u].d[1] = a.y;
+                    }
+                    const uint8_t *pb = packed + code_off_b + (int64_t)r * row_stride_b;
+                    if constexpr (WB == 2) {
+                        uint2 c = *reinterpret_cast<const uint2 *>(pb);
+                        w[u].d[WA] = c.x; w[u].d[WA + 1] = c.y;
+                    } else if constexpr (WB == 1) {
+                        w[u].d[WA] = *reinterpret_cast<const uint32_t *>(pb);
+                    }
                     w[u].hdr = *reinterpret_cast<const uint32_t *>(packed + hdr_off + (int64_t)r * nbk * 4);
+                } else {
+                    uint4 a = *reinterpret_cast<const uint4 *>(p);
+                    w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
+                    if constexpr (KIND == KIND_Q3H) {
+                        uint4 c = *reinterpret_cast<const uint4 *>(p + plane1);
+                        w[u].d[4] = c.x; w[u].d[5] = c.y; w[u].d[6] = c.z; w[u].d[7] = c.w;
+                    } else {
+                        w[u].hdr = *reinterpret_cast<const uint32_t *>(packed + hdr_off + (int64_t)r * nbk * 4);
+                    }
                 }
             }
         };
@@ -124,7 +152,7 @@ __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t 
                 float acc[NB];
                 lane_dot<KIND, NB>(w[u], xr, acc);
                 uint32_t hdr;
-                if (KIND == KIND_Q3H) hdr = q3h_header(reinterpret_cast<const uint32_t(&)[8]>(w[u].d)); else hdr = w[u].hdr;
+                if constexpr (KIND == KIND_Q3H) hdr = q3h_header(reinterpret_cast<const uint32_t(&)[8]>(w[u].d)); else hdr = w[u].hdr;
                 const half2_t so = as_h2(hdr);
                 const float s = (float)so.x, o = (float)so.y;
 #pragma unroll
@@ -544,7 +572,9 @@ static hipError_t gemv_launch(const void *packed, int64_t rows, int64_t cols, co
     const int rpw = pick_rows_per_wg(rows, nw);
     const int64_t grid = (rows + rpw - 1) / rpw;
     const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;
-    constexpr int U = 4;
+    // rows in flight per wavefront; the two-plane formats hold up to six words per row, and with three or four activation
+    // vectors four rows no longer fit the 128 registers of a 1024-thread workgroup
+    constexpr int U = (kind_has_planes(T::kind) && NB >= 3) ? 2 : 4;
     if (nw == 1)
         hipLaunchKernelGGL((qgemv_kernel<F, NB, U, false>), dim3((unsigned)grid), dim3(64), 0, s,
                            static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, nbk, rpw, nstrips, header_offset);
@@ -624,6 +654,10 @@ hipError_t launch_qgemv(int format, const void *packed, int64_t rows, int64_t co
     case IFLOW_Q4_B32: return gemv_batch<IFLOW_Q4_B32>(packed, rows, cols, x, batch, y, s);
     case IFLOW_Q4_B64: return gemv_batch<IFLOW_Q4_B64>(packed, rows, cols, x, batch, y, s);
     case IFLOW_Q3H_B64: return gemv_batch<IFLOW_Q3H_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q6_B64: return gemv_batch<IFLOW_Q6_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q5_B64: return gemv_batch<IFLOW_Q5_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q3_B32: return gemv_batch<IFLOW_Q3_B32>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q2_B32: return gemv_batch<IFLOW_Q2_B32>(packed, rows, cols, x, batch, y, s);
     default: return hipErrorInvalidValue;
     }
 }

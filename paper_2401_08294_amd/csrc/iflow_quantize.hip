@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float4 *__restrict_
 
     const int64_t blk = tid / LPB;                            // global block index, row-major
     const int j = (int)(tid % LPB);                           // lane inside the block
-    if (T::kind == KIND_Q3H) {
+    if constexpr (T::kind == KIND_Q3H) {
         // Eq.4: two 7-bit pair codes per lane; lanes 2i and 2i+1 build word i of the block
         const uint32_t cA = q[0] * 11u + q[1], cB = q[2] * 11u + q[3];
         const uint32_t part = (j & 1) ? (cA << 7 | cB << 23) : (cA | cB << 16);
@@ -84,6 +84,26 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float4 *__restrict_
         if (j & 1) part <<= 8;
         const uint32_t other = (uint32_t)dpp_i32_quad_1032((int)part);
         if (live && !(j & 1)) reinterpret_cast<uint32_t *>(packed)[tid >> 1] = part | other;
+        if (live && j == 0) reinterpret_cast<uint32_t *>(packed + header_offset)[blk] = S | O << 16;
+    } else if constexpr (kind_has_planes(T::kind)) {
+        // Bit planes: a word of a W-bit plane holds 32/W consecutive weights, four per lane: the weights of 2 lanes
+        // (W = 4), 4 lanes (W = 2) or 8 lanes (W = 1).  Lane jj of such a group holds weights 4jj..4jj+3 of the word:
+        // the even ones go to fields 2jj, 2jj+1 of the low half, the odd ones to the same fields of the high half.  The
+        // group's lanes OR their parts together (quad permutes, then the mirror inside eight lanes); its first lane stores.
+        constexpr int WA = Planes<T::kind>::WA, WB = Planes<T::kind>::WB;
+        auto plane_word = [&](int W, int shift, uint32_t *plane) {
+            const uint32_t m = (1u << W) - 1u;
+            const uint32_t v0 = (q[0] >> shift) & m, v1 = (q[1] >> shift) & m, v2 = (q[2] >> shift) & m, v3 = (q[3] >> shift) & m;
+            const int lanes = 8 / W;                          // lanes per word: 2, 4 or 8
+            const int jj = j & (lanes - 1);
+            uint32_t part = (v0 | v2 << W | v1 << 16 | v3 << (16 + W)) << (2 * W * jj);
+            part |= (uint32_t)dpp_i32_quad_1032((int)part);
+            if (lanes >= 4) part |= (uint32_t)dpp_i32_quad_2301((int)part);
+            if (lanes >= 8) part |= (uint32_t)dpp_i32_half_mirror((int)part);
+            if (live && jj == 0) plane[tid / lanes] = part;
+        };
+        plane_word(WA, 0, reinterpret_cast<uint32_t *>(packed));
+        if constexpr (WB > 0) plane_word(WB, WA, reinterpret_cast<uint32_t *>(packed + n_quads * 4 * WA / 8));
         if (live && j == 0) reinterpret_cast<uint32_t *>(packed + header_offset)[blk] = S | O << 16;
     } else {
         if (live) reinterpret_cast<uint32_t *>(packed)[tid] = q[0] | q[1] << 8 | q[2] << 16 | q[3] << 24;
@@ -127,6 +147,25 @@ __global__ __launch_bounds__(256) void read_kernel(const uint8_t *__restrict__ p
             const int pos[8] = {0, 4, 1, 5, 2, 6, 3, 7};      // nibble position of weight v_e
 #pragma unroll
             for (int e = 0; e < 8; ++e) q[e] = (word >> (4 * pos[e])) & 15u;
+        } else if constexpr (kind_has_planes(T::kind)) {
+            // a plane word holds 32/W weights, eight per lane: this lane's are weights 8h..8h+7 of its word, h its index
+            // among the word's 4/W lanes; weight n of a word sits at bit (n/2)*W + 16*(n%2)
+            constexpr int WA = Planes<T::kind>::WA, WB = Planes<T::kind>::WB;
+            auto plane_bits = [&](int W, const uint32_t *plane, uint32_t (&v)[8]) {
+                const int per = 4 / W;                        // lanes per word: 1 (W = 4), 2 (W = 2), 4 (W = 1)
+                const uint32_t word = live ? plane[tid / per] : 0u;
+                const int h = (int)(tid % per);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int n = 8 * h + e;
+                    v[e] = (word >> ((n >> 1) * W + 16 * (n & 1))) & ((1u << W) - 1u);
+                }
+            };
+            uint32_t lo[8], hi[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            plane_bits(WA, reinterpret_cast<const uint32_t *>(packed), lo);
+            if constexpr (WB > 0) plane_bits(WB, reinterpret_cast<const uint32_t *>(packed + n_octs * 8 * WA / 8), hi);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q[e] = lo[e] | hi[e] << WA;
         } else {
             uint2 two = live ? reinterpret_cast<const uint2 *>(packed)[tid] : make_uint2(0u, 0u);
 #pragma unroll
@@ -191,6 +230,10 @@ hipError_t launch_quantize(int format, const float *w, int64_t rows, int64_t col
     case IFLOW_Q4_B32: return quantize_one<IFLOW_Q4_B32>(w, rows, cols, packed, s);
     case IFLOW_Q4_B64: return quantize_one<IFLOW_Q4_B64>(w, rows, cols, packed, s);
     case IFLOW_Q3H_B64: return quantize_one<IFLOW_Q3H_B64>(w, rows, cols, packed, s);
+    case IFLOW_Q6_B64: return quantize_one<IFLOW_Q6_B64>(w, rows, cols, packed, s);
+    case IFLOW_Q5_B64: return quantize_one<IFLOW_Q5_B64>(w, rows, cols, packed, s);
+    case IFLOW_Q3_B32: return quantize_one<IFLOW_Q3_B32>(w, rows, cols, packed, s);
+    case IFLOW_Q2_B32: return quantize_one<IFLOW_Q2_B32>(w, rows, cols, packed, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -203,6 +246,10 @@ hipError_t launch_dequant(int format, const void *packed, int64_t rows, int64_t 
     case IFLOW_Q4_B32: return read_one<IFLOW_Q4_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
     case IFLOW_Q4_B64: return read_one<IFLOW_Q4_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
     case IFLOW_Q3H_B64: return read_one<IFLOW_Q3H_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
+    case IFLOW_Q6_B64: return read_one<IFLOW_Q6_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
+    case IFLOW_Q5_B64: return read_one<IFLOW_Q5_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
+    case IFLOW_Q3_B32: return read_one<IFLOW_Q3_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
+    case IFLOW_Q2_B32: return read_one<IFLOW_Q2_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -216,6 +263,10 @@ hipError_t launch_unpack(int format, const void *packed, int64_t rows, int64_t c
     case IFLOW_Q4_B32: return read_one<IFLOW_Q4_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
     case IFLOW_Q4_B64: return read_one<IFLOW_Q4_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
     case IFLOW_Q3H_B64: return read_one<IFLOW_Q3H_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
+    case IFLOW_Q6_B64: return read_one<IFLOW_Q6_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
+    case IFLOW_Q5_B64: return read_one<IFLOW_Q5_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
+    case IFLOW_Q3_B32: return read_one<IFLOW_Q3_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
+    case IFLOW_Q2_B32: return read_one<IFLOW_Q2_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
     default: return hipErrorInvalidValue;
     }
 }

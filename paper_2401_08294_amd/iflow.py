@@ -13,9 +13,11 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libiflow.so")
 
-Q8_B32, Q8_B64, Q4_B32, Q4_B64, Q3H_B64 = range(5)
-FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B64, "Q3H_B64": Q3H_B64}
-BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 4.0}
+Q8_B32, Q8_B64, Q4_B32, Q4_B64, Q3H_B64, Q6_B64, Q5_B64, Q3_B32, Q2_B32 = range(9)
+FORMATS = {"Q8_B32": Q8_B32, "Q8_B64": Q8_B64, "Q4_B32": Q4_B32, "Q4_B64": Q4_B64, "Q3H_B64": Q3H_B64,
+           "Q6_B64": Q6_B64, "Q5_B64": Q5_B64, "Q3_B32": Q3_B32, "Q2_B32": Q2_B32}
+BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 4.0, Q6_B64: 6.5, Q5_B64: 5.5, Q3_B32: 4.0,
+                   Q2_B32: 3.0}
 
 OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE, ERR_TIMEOUT = range(8)
 CHAIN_MAX_PHASES, CHAIN_MAX_MATRICES = 32, 56

@@ -13,7 +13,8 @@ from paper_2401_08294_amd import synth
 pytestmark = pytest.mark.gpu
 
 TOL = 2e-3
-NAMES = ["Q3H_B64", "Q4_B64", "Q4_B32", "Q8_B64", "Q8_B32"]
+NAMES = ["Q3H_B64", "Q4_B64", "Q4_B32", "Q8_B64", "Q8_B32", "Q6_B64", "Q5_B64", "Q3_B32", "Q2_B32"]
+NAMES_WITH_MIDDLE_KERNEL = NAMES[:5]        # the formats that have the 3..31-vector kernel
 
 
 def say(*a):
@@ -165,7 +166,7 @@ def small_batch_tall(torch, iflow, orc, name, rows, cols, batch, seed):
         assert e1 <= TOL, f"vector {b}: {e1}"          # two fp16 roundings of sums taken in different orders
 
 
-@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("name", NAMES_WITH_MIDDLE_KERNEL)
 @pytest.mark.parametrize("cols", [1024, 4096 + 64 * 3])
 def test_small_batch_tall(gpu, orc, name, cols):
     torch, iflow = gpu
@@ -280,6 +281,9 @@ def test_exact_ties_round_half_away(gpu, orc):
     check_all(torch, iflow, orc, "Q3H_B64", w, x, "ties")
     w15 = np.tile(np.array([0, 0.5, 1.5, 2.5, 7.5, 14.5, 15, 3] * 8, np.float32), (4, 1))
     check_all(torch, iflow, orc, "Q4_B64", w15, x, "ties")
+    for name, L in (("Q6_B64", 63), ("Q5_B64", 31), ("Q3_B32", 7), ("Q2_B32", 3)):
+        wl = np.tile(np.array([0, 0.5, 1.5, 2.5, L - 0.5, L / 2, L, 1] * 8, np.float32), (4, 1))
+        check_all(torch, iflow, orc, name, wl, x, "ties")
 
 
 def test_outliers_config3_shape_slice(gpu, orc):

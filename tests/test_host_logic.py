@@ -40,7 +40,8 @@ def test_library_exports_every_declared_symbol(iflow):
 def test_format_queries_and_bit_budget(iflow):
     # Table 3: block sizes, levels (2^k, or 11 for Eq.3) and actual bits per weight
     expect = {"Q8_B32": (32, 256, 9), "Q8_B64": (64, 256, 8.5), "Q4_B32": (32, 16, 5), "Q4_B64": (64, 16, 4.5),
-              "Q3H_B64": (64, 11, 4)}
+              "Q3H_B64": (64, 11, 4), "Q6_B64": (64, 64, 6.5), "Q5_B64": (64, 32, 5.5), "Q3_B32": (32, 8, 4),
+              "Q2_B32": (32, 4, 3)}          # (the 2-bit format is not in Table 3: 2 bits + 32 header bits per 32 weights)
     for name, (bs, lv, bpw) in expect.items():
         f = iflow.FORMATS[name]
         assert iflow.format_block(f) == bs and iflow.format_levels(f) == lv
@@ -55,7 +56,7 @@ def test_argument_validation_happens_before_any_launch(iflow):
     assert L.iflow_packed_bytes(4, 8, 100, C.byref(sz)) == iflow.ERR_SHAPE      # cols % 64 != 0
     assert L.iflow_packed_bytes(4, 0, 64, C.byref(sz)) == iflow.ERR_SHAPE
     assert L.iflow_packed_bytes(4, 8, 1 << 31, C.byref(sz)) == iflow.ERR_SHAPE
-    assert L.iflow_packed_bytes(5, 8, 64, C.byref(sz)) == iflow.ERR_FORMAT
+    assert L.iflow_packed_bytes(9, 8, 64, C.byref(sz)) == iflow.ERR_FORMAT
     assert L.iflow_packed_bytes(4, 8, 64, None) == iflow.ERR_NULL
     good = 0x10000                                                               # aligned, never dereferenced
     assert L.iflow_quantize(4, None, 8, 64, good, 256, None) == iflow.ERR_NULL
@@ -63,7 +64,7 @@ def test_argument_validation_happens_before_any_launch(iflow):
     assert L.iflow_quantize(4, good + 8, 8, 64, good, 256, None) == iflow.ERR_ALIGN
     assert L.iflow_quantize(4, good, 8, 32, good, 256, None) == iflow.ERR_SHAPE
     assert L.iflow_dequant(4, good, 8, 64, None, None) == iflow.ERR_NULL
-    assert L.iflow_dequant(7, good, 8, 64, good, None) == iflow.ERR_FORMAT
+    assert L.iflow_dequant(9, good, 8, 64, good, None) == iflow.ERR_FORMAT
     assert L.iflow_qgemv(4, good, 8, 64, good, good + 2, None) == iflow.ERR_ALIGN
     assert L.iflow_qgemm(4, good, 8, 64, good, 0, good, None) == iflow.ERR_SHAPE
     assert L.iflow_qgemm(4, good, 8, 64, None, 3, good, None) == iflow.ERR_NULL
