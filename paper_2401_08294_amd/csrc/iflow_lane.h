@@ -212,4 +212,40 @@ __device__ __forceinline__ uint32_t q3h_header(const uint32_t (&d)[8])
     return h;
 }
 
+// ---- transpose-reduce: U per-lane partials (one per row) -> row sums ---------------------------------
+// On return, every lane with (lane & (U-1)) == u holds the sum over all 64 lanes of v[u].
+__device__ __forceinline__ float xor_lanes_16(float v) { return __shfl_xor(v, 16); }
+__device__ __forceinline__ float xor_lanes_32(float v) { return __shfl_xor(v, 32); }
+
+template <int U>
+__device__ __forceinline__ float reduce_rows(float (&v)[U], int lane)
+{
+    static_assert(U == 1 || U == 2 || U == 4, "group size");
+    float r;
+    if (U == 4) {
+        const bool b0 = lane & 1, b1 = lane & 2;
+        // keep one of each pair, hand the other to the neighbour that keeps it
+        float k0 = b0 ? v[1] : v[0], g0 = b0 ? v[0] : v[1];
+        float k1 = b0 ? v[3] : v[2], g1 = b0 ? v[2] : v[3];
+        float r0 = k0 + dpp_f32<0xB1, 0xF>(g0);          // lanes ^1
+        float r1 = k1 + dpp_f32<0xB1, 0xF>(g1);
+        float k = b1 ? r1 : r0, g = b1 ? r0 : r1;
+        r = k + dpp_f32<0x4E, 0xF>(g);                   // lanes ^2: lane & 3 == u holds the quad sum of v[u]
+    } else if (U == 2) {
+        const bool b0 = lane & 1;
+        float k = b0 ? v[1] : v[0], g = b0 ? v[0] : v[1];
+        r = k + dpp_f32<0xB1, 0xF>(g);
+        r += dpp_f32<0x4E, 0xF>(r);
+    } else {
+        r = v[0];
+        r += dpp_f32<0xB1, 0xF>(r);
+        r += dpp_f32<0x4E, 0xF>(r);
+    }
+    r += dpp_f32<0x124, 0xF>(r);                         // row_ror:4  (rotations by 4 keep lane & 3)
+    r += dpp_f32<0x128, 0xF>(r);                         // row_ror:8  -> sum over the 16-lane row
+    r += xor_lanes_16(r);
+    r += xor_lanes_32(r);
+    return r;
+}
+
 }  // namespace iflow

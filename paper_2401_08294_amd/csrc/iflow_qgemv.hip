@@ -19,42 +19,6 @@
 
 namespace iflow {
 
-// ---- transpose-reduce: U per-lane partials (one per row) -> row sums ---------------------------------
-// On return, every lane with (lane & (U-1)) == u holds the sum over all 64 lanes of v[u].
-__device__ __forceinline__ float xor_lanes_16(float v) { return __shfl_xor(v, 16); }
-__device__ __forceinline__ float xor_lanes_32(float v) { return __shfl_xor(v, 32); }
-
-template <int U>
-__device__ __forceinline__ float reduce_rows(float (&v)[U], int lane)
-{
-    static_assert(U == 1 || U == 2 || U == 4, "group size");
-    float r;
-    if (U == 4) {
-        const bool b0 = lane & 1, b1 = lane & 2;
-        // keep one of each pair, hand the other to the neighbour that keeps it
-        float k0 = b0 ? v[1] : v[0], g0 = b0 ? v[0] : v[1];
-        float k1 = b0 ? v[3] : v[2], g1 = b0 ? v[2] : v[3];
-        float r0 = k0 + dpp_f32<0xB1, 0xF>(g0);          // lanes ^1
-        float r1 = k1 + dpp_f32<0xB1, 0xF>(g1);
-        float k = b1 ? r1 : r0, g = b1 ? r0 : r1;
-        r = k + dpp_f32<0x4E, 0xF>(g);                   // lanes ^2: lane & 3 == u holds the quad sum of v[u]
-    } else if (U == 2) {
-        const bool b0 = lane & 1;
-        float k = b0 ? v[1] : v[0], g = b0 ? v[0] : v[1];
-        r = k + dpp_f32<0xB1, 0xF>(g);
-        r += dpp_f32<0x4E, 0xF>(r);
-    } else {
-        r = v[0];
-        r += dpp_f32<0xB1, 0xF>(r);
-        r += dpp_f32<0x4E, 0xF>(r);
-    }
-    r += dpp_f32<0x124, 0xF>(r);                         // row_ror:4  (rotations by 4 keep lane & 3)
-    r += dpp_f32<0x128, 0xF>(r);                         // row_ror:8  -> sum over the 16-lane row
-    r += xor_lanes_16(r);
-    r += xor_lanes_32(r);
-    return r;
-}
-
 template <int F, int NB, int U, bool MULTI>
 __global__ __launch_bounds__(MULTI ? 1024 : 64) void qgemv_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
                                                                   uint16_t *__restrict__ Y, int rows, int cols, int nbk, int rows_per_wg,
@@ -564,6 +528,10 @@ static hipError_t gemv_launch(const void *packed, int64_t rows, int64_t cols, co
         GemvGroup grp = {};
         grp.packed[0] = static_cast<const uint8_t *>(packed); grp.y[0] = Y; grp.rows[0] = (int)rows; grp.count = 1;
         return q3h_launch<NB>(grp, cols, X, s);
+    }
+    if (NB == 1) {                                            // one vector: rows owned by wavefronts (iflow_qgemv_rows.hip)
+        const hipError_t e = launch_qgemv_rows(F, packed, rows, cols, X, Y, s);
+        if (e != hipErrorNotSupported) return e;              // (rows too long for its staging: the kernel below)
     }
     typedef Geo<T::kind> G;
     const int nbk = (int)(cols / T::block);

@@ -124,6 +124,17 @@ def test_ragged_shapes(gpu, orc, name, rows, nblocks):
     check_all(torch, iflow, orc, name, w, x, "ragged")
 
 
+# ---- very long rows: the one-vector kernel stages a whole row of activations in LDS; beyond its limit (144 KiB: 32 strips
+#      of 2048 columns, 57 strips of 1024 for 8-bit) the launcher takes the older kernel.  Both sides of the limit. ------------
+@pytest.mark.parametrize("name,cols", [("Q4_B64", 65536), ("Q4_B64", 65536 + 2048), ("Q8_B32", 57 * 1024), ("Q8_B32", 58 * 1024 + 32),
+                                       ("Q6_B64", 65536 + 64), ("Q2_B32", 65536 - 32)])
+def test_rows_at_the_staging_limit(gpu, orc, name, cols):
+    torch, iflow = gpu
+    w = synth.weights(5, cols, 0.02, synth.BASE_SEED + 77)
+    x = synth.activations(1, cols, synth.BASE_SEED + 78)
+    check_all(torch, iflow, orc, name, w, x, "long-rows")
+
+
 # ---- small batches (2, 3, 4 share a pass; 5 and 16 take several) ----------------------------------------
 @pytest.mark.parametrize("name", NAMES)
 @pytest.mark.parametrize("batch", [2, 3, 4, 5, 8, 16, 21])
