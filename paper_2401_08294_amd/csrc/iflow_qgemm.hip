@@ -222,16 +222,26 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][p][v] = 0.f;
     const int li = lane & 31, kg = lane >> 5;
-    auto multiply = [&](int buf) {
+    // The operand fragments of a whole chunk are read into registers of their own first (twelve 16-byte LDS reads), the
+    // next chunk's decode and LDS writes are issued behind them, and only then come the eight MFMAs: left to itself the
+    // compiler reads each fragment into the same few registers right before its MFMA and waits for it there - a full LDS
+    // round trip in front of every MFMA, 1500 cycles per chunk for 256 cycles of matrix-core work.
+    half8_t af[2][4], bf[4];
+    auto read_fragments = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {                       // 16 columns per step: lane (li, kg) holds k = 8 kg .. 8 kg + 7
-            const half8_t bfrag = *reinterpret_cast<const half8_t *>(&ws[buf][(wn * 32 + li) * GM_LD + ks * 16 + kg * 8]);
+            bf[ks] = *reinterpret_cast<const half8_t *>(&ws[buf][(wn * 32 + li) * GM_LD + ks * 16 + kg * 8]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const half8_t afrag = *reinterpret_cast<const half8_t *>(&xs[buf][(wm * 64 + i * 32 + li) * GM_LD + ks * 16 + kg * 8]);
-                acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag, bfrag, acc[i][ks & 1], 0, 0, 0);
-            }
+            for (int i = 0; i < 2; ++i)
+                af[i][ks] = *reinterpret_cast<const half8_t *>(&xs[buf][(wm * 64 + i * 32 + li) * GM_LD + ks * 16 + kg * 8]);
         }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i][ks], bf[ks], acc[i][ks & 1], 0, 0, 0);
     };
 
     // Software pipeline: chunk c multiplies from one LDS stage while chunk c+1 is decoded into the other and chunks
@@ -248,12 +258,14 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
     // count which outstanding load a register belongs to and waits for all of them, the newest request included.
     int kb = 0;
 #define IFLOW_GEMM_STEP(ST, U)        /* chunk kb+U multiplies; chunk kb+U+1 goes to the other LDS stage; ST is refilled */ \
-    stash(ST, (kb + U + 1) & 1); fetch(ST, kb + U + 5); multiply((kb + U) & 1); __syncthreads();
+    read_fragments((kb + U) & 1); __builtin_amdgcn_sched_barrier(0);                                                          \
+    stash(ST, (kb + U + 1) & 1); fetch(ST, kb + U + 5); __builtin_amdgcn_sched_barrier(0);                                    \
+    multiply(); __syncthreads();
     for (; kb + 4 <= nchunks; kb += 4) {
         IFLOW_GEMM_STEP(sb, 0) IFLOW_GEMM_STEP(sc, 1) IFLOW_GEMM_STEP(sd, 2) IFLOW_GEMM_STEP(sa, 3)
     }
 #undef IFLOW_GEMM_STEP
-#define IFLOW_GEMM_TAIL(ST, U) if (kb + U < nchunks) { stash(ST, (kb + U + 1) & 1); multiply((kb + U) & 1); __syncthreads(); }
+#define IFLOW_GEMM_TAIL(ST, U) if (kb + U < nchunks) { read_fragments((kb + U) & 1); stash(ST, (kb + U + 1) & 1); multiply(); __syncthreads(); }
     IFLOW_GEMM_TAIL(sb, 0) IFLOW_GEMM_TAIL(sc, 1) IFLOW_GEMM_TAIL(sd, 2)      // the last one to three chunks
 #undef IFLOW_GEMM_TAIL
 
