@@ -135,6 +135,17 @@ def test_rows_at_the_staging_limit(gpu, orc, name, cols):
     check_all(torch, iflow, orc, name, w, x, "long-rows")
 
 
+# ---- many short rows: one block per row, a quarter of a million rows (launch grids, row-group arithmetic) -------------------
+@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B32", "Q6_B64", "Q8_B64", "Q2_B32"])
+@pytest.mark.parametrize("batch", [1, 3])
+def test_tall_and_thin(gpu, orc, name, batch):
+    torch, iflow = gpu
+    rows, cols = 262144 + 3, 64
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 88)
+    x = synth.activations(batch, cols, synth.BASE_SEED + 89)
+    check_all(torch, iflow, orc, name, w, x, "tall-thin")
+
+
 # ---- small batches (2, 3, 4 share a pass; 5 and 16 take several) ----------------------------------------
 @pytest.mark.parametrize("name", NAMES)
 @pytest.mark.parametrize("batch", [2, 3, 4, 5, 8, 16, 21])
