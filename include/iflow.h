@@ -202,9 +202,8 @@ iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, con
  * One backend, chosen by batch: 1 is iflow_qgemv; 2 (8-bit formats: up to 4) runs on the vector units with the
  * activation vectors side by side; up to 31 the weights stream once per sixteen vectors and the multiply runs on the
  * matrix cores (16x16x16 tiles, weights dequantized in registers); from 32 on (and cols a multiple of 64) 128 x 64
- * output tiles run on the matrix cores from dequantized fp16 tiles in LDS.  The 6-, 5-, 3- and 2-bit formats have no
- * kernel of the middle kind: up to 11 vectors they take vector passes of four, from 12 on the dense kernel.  Results of
- * one call do not depend on how busy the device is (all sums are taken in a fixed order). */
+ * output tiles run on the matrix cores from dequantized fp16 tiles in LDS.  Results of one call do not depend on
+ * how busy the device is (all sums are taken in a fixed order). */
 iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                            const uint16_t *X, int64_t batch, uint16_t *Y, void *stream);
 

@@ -129,13 +129,9 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     // on the product is a dense contraction on LDS tiles (64-column chunks).  Column counts that are not a multiple
     // of 64 (possible with the 32-wide blocks) stay on the vector kernel, four vectors per pass.
     hipStream_t hs = (hipStream_t)stream;
-    // (the bit-plane formats have no kernel of the middle kind; their vector passes of four cost more than one pass of the
-    // dense kernel from about a dozen vectors on - measured on 4096 x 4096 and 11008 x 4096)
-    const int64_t mfma_from = iflow::kind_has_planes(fi.kind) ? 12 : 32;
-    if (batch >= mfma_from && cols % 64 == 0)
+    if (batch >= 32 && cols % 64 == 0)
         return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, hs));
-    if (cols % 64 == 0 && !iflow::kind_has_planes(fi.kind) &&
-        batch >= (format == IFLOW_Q8_B32 || format == IFLOW_Q8_B64 ? IFLOW_SMALL_MFMA_MIN_BATCH_Q8 : IFLOW_SMALL_MFMA_MIN_BATCH)) {
+    if (cols % 64 == 0 && batch >= (format == IFLOW_Q8_B32 || format == IFLOW_Q8_B64 ? IFLOW_SMALL_MFMA_MIN_BATCH_Q8 : IFLOW_SMALL_MFMA_MIN_BATCH)) {
         for (int64_t b0 = 0; b0 < batch; b0 += 16) {
             const int64_t nb = batch - b0 < 16 ? batch - b0 : 16;
             hipError_t e = iflow::launch_qgemm_small((int)format, packed, rows, cols, X + b0 * cols, nb, Y + b0 * rows, hs);

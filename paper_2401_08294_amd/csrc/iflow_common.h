@@ -118,6 +118,34 @@ __device__ __forceinline__ half2_t q3h_low_digit(half2_t h1, uint32_t hc)
     return __builtin_bit_cast(half2_t, r);                                // 2^-20 * (2037 + q2) in each half
 }
 
+// ---- bit planes: fields to exact fp16 integers (the dense kernels; the vector kernels multiply the biased values) ------
+// The 8 / W fields in the low byte of both halves of a plane word, as exact fp16 pairs (even weight, odd weight).
+template <int W>
+__device__ __forceinline__ void plane_byte_fields(uint32_t word, half2_t *v)
+{
+#pragma unroll
+    for (int i = 0; i < 8 / W; ++i) {
+        const uint32_t mask = (((1u << W) - 1u) << (W * i)) * 0x00010001u;
+        const uint32_t magic = (uint32_t)((25 - W * i) << 10) * 0x00010001u;            // bit W i counts 1
+        const half_t bias = (half_t)(float)(1024 >> (W * i));
+        const half2_t b2 = {bias, bias};
+        v[i] = as_h2((word & mask) | magic) - b2;
+    }
+}
+// Sixteen consecutive weights' fields of a W-bit plane: W bytes of each half, `first` = the byte they start at.
+template <int W>
+__device__ __forceinline__ void plane_fields16(const uint32_t *words, int first, half2_t (&v)[8])
+{
+    if constexpr (W == 4) {
+        plane_byte_fields<4>(words[0], &v[0]); plane_byte_fields<4>(words[0] >> 8, &v[2]);
+        plane_byte_fields<4>(words[1], &v[4]); plane_byte_fields<4>(words[1] >> 8, &v[6]);
+    } else if constexpr (W == 2) {
+        plane_byte_fields<2>(words[0], &v[0]); plane_byte_fields<2>(words[0] >> 8, &v[4]);
+    } else {
+        plane_byte_fields<1>(words[0] >> (8 * first), &v[0]);
+    }
+}
+
 // ---- once-per-device set-up on the host -----------------------------------------------------------
 // A launcher's per-device preparation (raising a kernel's dynamic-LDS limit) runs once for each device it is called
 // on, under a lock, so that several host threads may call the library; the device's compute-unit count comes back.

@@ -66,33 +66,6 @@ __device__ __forceinline__ void load16(const uint8_t *packed, int64_t header_off
     }
 }
 
-// The 8 / W fields in the low byte of both halves of a plane word, as exact fp16 pairs (even weight, odd weight).
-template <int W>
-__device__ __forceinline__ void plane_byte_fields(uint32_t word, half2_t *v)
-{
-#pragma unroll
-    for (int i = 0; i < 8 / W; ++i) {
-        const uint32_t mask = (((1u << W) - 1u) << (W * i)) * 0x00010001u;
-        const uint32_t magic = (uint32_t)((25 - W * i) << 10) * 0x00010001u;            // bit W i counts 1
-        const half_t bias = (half_t)(float)(1024 >> (W * i));
-        const half2_t b2 = {bias, bias};
-        v[i] = as_h2((word & mask) | magic) - b2;
-    }
-}
-// Sixteen consecutive weights' fields of a W-bit plane: W bytes of each half, `first` = the byte they start at.
-template <int W>
-__device__ __forceinline__ void plane_fields16(const uint32_t *words, int first, half2_t (&v)[8])
-{
-    if constexpr (W == 4) {
-        plane_byte_fields<4>(words[0], &v[0]); plane_byte_fields<4>(words[0] >> 8, &v[2]);
-        plane_byte_fields<4>(words[1], &v[4]); plane_byte_fields<4>(words[1] >> 8, &v[6]);
-    } else if constexpr (W == 2) {
-        plane_byte_fields<2>(words[0], &v[0]); plane_byte_fields<2>(words[0] >> 8, &v[4]);
-    } else {
-        plane_byte_fields<1>(words[0] >> (8 * first), &v[0]);
-    }
-}
-
 // Eq.5 and Eq.2: the sixteen weights as eight fp16 pairs in natural order, bit-identical to iflow_dequant.
 template <int F>
 __device__ __forceinline__ void decode16(const Raw16 &r, int qd, uint32_t (&out)[8])

@@ -23,7 +23,7 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // Raw bytes of a lane's 64 weights and their block header(s), per format.
-template <int KIND> struct SmallRaw;
+template <int KIND> struct SmallRaw { uint32_t d[12]; uint32_t hdr[2]; };   // bit planes: up to 8 words of the low plane, then up to 4 of the high one
 template <> struct SmallRaw<KIND_Q3H> { uint32_t d[8]; uint32_t hdr[2]; };   // (header in the spare bits of d)
 template <> struct SmallRaw<KIND_Q4>  { uint32_t d[8]; uint32_t hdr[2]; };   // 32 code bytes
 template <> struct SmallRaw<KIND_Q8>  { uint32_t d[16]; uint32_t hdr[2]; };  // 64 code bytes
@@ -50,6 +50,8 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
     typedef Fmt<F> T;
     constexpr int KIND = T::kind;
     constexpr int HPL = 64 / T::block;                        // block headers per lane (1, or 2 for the 32-wide formats)
+    constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;       // bit-plane formats: a lane's 64 weights take 2 WA + 2 WB words
+    constexpr int NWORDS = kind_has_planes(KIND) ? 2 * WA + 2 * WB : KIND == KIND_Q8 ? 16 : 8;
     extern __shared__ __align__(16) uint8_t lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
         const int n_t = min(64, nbk64 - t * 64);
         const int group = min(first + r * (int)gridDim.x, ngroups - 1);
         const int64_t row = min(group * 16 + il, rows - 1);
-        if (KIND == KIND_Q3H) {                               // two planes of the strip, 16 bytes each
+        if constexpr (KIND == KIND_Q3H) {                     // two planes of the strip, 16 bytes each
             const uint8_t *p0 = packed + row * ((int64_t)nbk64 * 32) + (int64_t)t * 2048 + (kbc & 63) * 16;
             const uint8_t *p1 = p0 + n_t * 16;
             if (beyond) { p0 = packed; p1 = packed; }
@@ -83,6 +85,26 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
             const u32x4_t wc = *reinterpret_cast<const u32x4_t *>(p1);
             raw.d[0] = wa.x; raw.d[1] = wa.y; raw.d[2] = wa.z; raw.d[3] = wa.w;
             raw.d[4] = wc.x; raw.d[5] = wc.y; raw.d[6] = wc.z; raw.d[7] = wc.w;
+        } else if constexpr (kind_has_planes(KIND)) {         // low plane, high plane (each row-major over all rows), then the headers
+            constexpr int ABYTES = 8 * WA, BBYTES = 8 * WB;   // bytes of a 64-weight block in each plane
+            const uint8_t *pa = packed + row * ((int64_t)nbk64 * ABYTES) + (int64_t)kbc * ABYTES;
+            const uint8_t *pb = packed + (int64_t)rows * nbk64 * ABYTES + row * ((int64_t)nbk64 * BBYTES) + (int64_t)kbc * BBYTES;
+            if (beyond) { pa = packed; pb = packed; }
+#pragma unroll
+            for (int q = 0; q < ABYTES / 16; ++q) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(pa + (beyond ? 0 : q * 16));
+                raw.d[4 * q] = v.x; raw.d[4 * q + 1] = v.y; raw.d[4 * q + 2] = v.z; raw.d[4 * q + 3] = v.w;
+            }
+            if constexpr (BBYTES == 16) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(pb);
+                raw.d[2 * WA] = v.x; raw.d[2 * WA + 1] = v.y; raw.d[2 * WA + 2] = v.z; raw.d[2 * WA + 3] = v.w;
+            } else if constexpr (BBYTES == 8) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(pb);
+                raw.d[2 * WA] = v.x; raw.d[2 * WA + 1] = v.y;
+            }
+            const uint32_t *hp = reinterpret_cast<const uint32_t *>(packed + header_offset) + (beyond ? 0 : (row * nbk64 + kbc) * HPL);
+#pragma unroll
+            for (int h = 0; h < HPL; ++h) raw.hdr[h] = hp[h];
         } else {                                              // code bytes row-major, then the headers
             constexpr int BYTES = KIND == KIND_Q4 ? 32 : 64;
             const uint8_t *p0 = packed + row * ((int64_t)nbk64 * BYTES) + (int64_t)kbc * BYTES;
@@ -104,15 +126,15 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
 
     // one round: dequantize the lane's block, sixteen MFMA steps, add the sixteen wavefronts' tiles up through LDS
     auto round_body = [&](const SmallRaw<KIND> &raw, int t, int r, int which) {
-        uint32_t d[KIND == KIND_Q8 ? 16 : 8], hdr[2];
+        uint32_t d[NWORDS], hdr[2];
 #pragma unroll
-        for (int w = 0; w < (KIND == KIND_Q8 ? 16 : 8); ++w) d[w] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)raw.d[w]);
+        for (int w = 0; w < NWORDS; ++w) d[w] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)raw.d[w]);
         if (KIND != KIND_Q3H) {
 #pragma unroll
             for (int h = 0; h < HPL; ++h) hdr[h] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)raw.hdr[h]);
         }
         float4_t acc = {0.f, 0.f, 0.f, 0.f};
-        if (KIND == KIND_Q3H) {
+        if constexpr (KIND == KIND_Q3H) {
             uint32_t h = d[0] & 0xC000C000u;                  // header from the spare bits of the eight words
 #pragma unroll
             for (int w = 1; w < 8; ++w) h = (d[w] & 0xC000C000u) | (h >> 2);
@@ -132,7 +154,31 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
                     acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a, xq[2 * w + hs], acc, 0, 0, 0);
                 }
             }
-        } else if (KIND == KIND_Q4) {
+        } else if constexpr (kind_has_planes(KIND)) {
+            // sixteen weights at a time: the fields of both planes as exact fp16 integers, level = high * 2^WA + low, Eq.2
+            const half2_t up = {(half_t)(float)(1 << WA), (half_t)(float)(1 << WA)};
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const half2_t so = as_h2(hdr[HPL == 2 ? gq >> 1 : 0]);
+                const half2_t s2 = {so.x, so.x}, o2 = {so.y, so.y};
+                half2_t lo[8], hi[8];
+                plane_fields16<WA>(&d[WA == 4 ? 2 * gq : gq], 0, lo);
+                if constexpr (WB == 2) plane_fields16<2>(&d[2 * WA + gq], 0, hi);
+                if constexpr (WB == 1) plane_fields16<1>(&d[2 * WA + (gq >> 1)], gq & 1, hi);
+                half2_t wv[8];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    half2_t level = lo[m];
+                    if constexpr (WB > 0) level = __builtin_elementwise_fma(hi[m], up, lo[m]);
+                    wv[m] = __builtin_elementwise_fma(level, s2, o2);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const half4_t a = __builtin_shufflevector(wv[2 * j], wv[2 * j + 1], 0, 1, 2, 3);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a, xq[4 * gq + j], acc, 0, 0, 0);
+                }
+            }
+        } else if constexpr (KIND == KIND_Q4) {
 #pragma unroll
             for (int w = 0; w < 8; ++w) {                     // word w: weights 8w .. 8w+7, nibble order v0 v2 v4 v6 v1 v3 v5 v7
                 const half2_t so = as_h2(hdr[HPL == 2 ? w >> 2 : 0]);
@@ -313,6 +359,10 @@ hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int6
     case IFLOW_Q4_B32: return small_launch<IFLOW_Q4_B32>(packed, rows, cols, X, batch, Y, s);
     case IFLOW_Q4_B64: return small_launch<IFLOW_Q4_B64>(packed, rows, cols, X, batch, Y, s);
     case IFLOW_Q3H_B64: return small_launch<IFLOW_Q3H_B64>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q6_B64: return small_launch<IFLOW_Q6_B64>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q5_B64: return small_launch<IFLOW_Q5_B64>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q3_B32: return small_launch<IFLOW_Q3_B32>(packed, rows, cols, X, batch, Y, s);
+    case IFLOW_Q2_B32: return small_launch<IFLOW_Q2_B32>(packed, rows, cols, X, batch, Y, s);
     default: return hipErrorInvalidValue;
     }
 }
