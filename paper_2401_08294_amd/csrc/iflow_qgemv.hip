@@ -529,8 +529,8 @@ static hipError_t gemv_launch(const void *packed, int64_t rows, int64_t cols, co
         grp.packed[0] = static_cast<const uint8_t *>(packed); grp.y[0] = Y; grp.rows[0] = (int)rows; grp.count = 1;
         return q3h_launch<NB>(grp, cols, X, s);
     }
-    if (NB == 1) {                                            // one vector: rows owned by wavefronts (iflow_qgemv_rows.hip)
-        const hipError_t e = launch_qgemv_rows(F, packed, rows, cols, X, Y, s);
+    if (NB <= 2) {                                            // one or two vectors: rows owned by wavefronts (iflow_qgemv_rows.hip)
+        const hipError_t e = launch_qgemv_rows(F, packed, rows, cols, X, NB, Y, s);
         if (e != hipErrorNotSupported) return e;              // (rows too long for its staging: the kernel below)
     }
     typedef Geo<T::kind> G;

@@ -26,7 +26,7 @@ template <int KIND> struct RowsGeo {
 
 constexpr int ROWS_LDS_LIMIT = 144 * 1024;
 
-template <int F, int U>
+template <int F, int U, int NB>
 __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
                                                         uint16_t *__restrict__ Y, int rows, int cols, int nbk, int nstrips,
                                                         int groups /* of U rows per wavefront */, int64_t header_offset)
@@ -41,18 +41,19 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), waves = blockDim.x >> 6;
 
     // ---- stage the activations: item (strip, lane) -> converted registers -> LDS ----------------------------------
-    for (int item = tid; item < nstrips * 64; item += blockDim.x) {
-        const int t = item >> 6, l = item & 63;
+    for (int item = tid; item < NB * nstrips * 64; item += blockDim.x) {      // slot (strip t, vector b) = t * NB + b
+        const int tb = item >> 6, l = item & 63;
+        const int t = tb / NB, b = tb - t * NB;
         const int k0 = (t * 64 + l) * G::WPL;
         XRegs<KIND> xr;
         if (k0 < cols) {
-            load_x<KIND>(xr, X, k0);
+            load_x<KIND>(xr, X + (int64_t)b * cols, k0);
         } else {                                              // past the end of the last strip: contributes nothing
 #pragma unroll
             for (int j = 0; j < G::XD; ++j) xr.v[j] = as_h2(0u);
             xr.bias_sum = 0.f; xr.x_sum = 0.f;
         }
-        uint8_t *slot = lds + (size_t)t * RG::SLOT;
+        uint8_t *slot = lds + (size_t)tb * RG::SLOT;
 #pragma unroll
         for (int q = 0; q < RG::XQ; ++q) {
             const u32x4 v = {as_u32(xr.v[4 * q]), as_u32(xr.v[4 * q + 1]), as_u32(xr.v[4 * q + 2]), as_u32(xr.v[4 * q + 3])};
@@ -122,9 +123,11 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     };
 
     WRegs<KIND> wa[U], wb[U];
-    float acc[U];
+    float acc[NB][U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc[u] = 0.f;
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[b][u] = 0.f;
     {
         int r0, t;
         step_row(0, r0, t);
@@ -135,27 +138,35 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     auto compute_step = [&](const WRegs<KIND>(&w)[U], int k) {
         int r0, t;
         step_row(k, r0, t);
-        XRegs<KIND> xr[1];
-        const uint8_t *slot = lds + (size_t)t * RG::SLOT;
+        XRegs<KIND> xr[NB];
 #pragma unroll
-        for (int q = 0; q < RG::XQ; ++q) {
-            const u32x4 v = reinterpret_cast<const u32x4 *>(slot)[q * 64 + lane];
-            xr[0].v[4 * q] = as_h2(v.x); xr[0].v[4 * q + 1] = as_h2(v.y); xr[0].v[4 * q + 2] = as_h2(v.z); xr[0].v[4 * q + 3] = as_h2(v.w);
+        for (int b = 0; b < NB; ++b) {
+            const uint8_t *slot = lds + (size_t)(t * NB + b) * RG::SLOT;
+#pragma unroll
+            for (int q = 0; q < RG::XQ; ++q) {
+                const u32x4 v = reinterpret_cast<const u32x4 *>(slot)[q * 64 + lane];
+                xr[b].v[4 * q] = as_h2(v.x); xr[b].v[4 * q + 1] = as_h2(v.y); xr[b].v[4 * q + 2] = as_h2(v.z); xr[b].v[4 * q + 3] = as_h2(v.w);
+            }
+            const float2 sums = reinterpret_cast<const float2 *>(slot + RG::XQ * 64 * 16)[lane];
+            xr[b].bias_sum = sums.x; xr[b].x_sum = sums.y;
         }
-        const float2 sums = reinterpret_cast<const float2 *>(slot + RG::XQ * 64 * 16)[lane];
-        xr[0].bias_sum = sums.x; xr[0].x_sum = sums.y;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float a[1];
-            lane_dot<KIND, 1>(w[u], xr, a);
+            float a[NB];
+            lane_dot<KIND, NB>(w[u], xr, a);
             const half2_t so = as_h2(w[u].hdr);
-            acc[u] += __builtin_fmaf((float)so.x, a[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                acc[b][u] += __builtin_fmaf((float)so.x, a[b] - xr[b].bias_sum, (float)so.y * xr[b].x_sum);
         }
         if (t == nstrips - 1) {                               // the rows end here: reduce, store, start over
-            const float r = reduce_rows<U>(acc, lane);
-            if (lane < U && r0 + lane < rows) Y[r0 + lane] = as_u16((half_t)r);
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc[u] = 0.f;
+            for (int b = 0; b < NB; ++b) {
+                const float r = reduce_rows<U>(acc[b], lane);
+                if (lane < U && r0 + lane < rows) Y[(int64_t)b * rows + r0 + lane] = as_u16((half_t)r);
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[b][u] = 0.f;
+            }
         }
     };
 
@@ -171,7 +182,7 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     }
 }
 
-template <int F, int U>
+template <int F, int U, int NB>
 static hipError_t rows_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *x, uint16_t *y, hipStream_t s)
 {
     typedef Fmt<F> T;
@@ -179,12 +190,12 @@ static hipError_t rows_launch(const void *packed, int64_t rows, int64_t cols, co
     typedef RowsGeo<T::kind> RG;
     const int nbk = (int)(cols / T::block);
     const int nstrips = (int)((cols + 64 * G::WPL - 1) / (64 * G::WPL));
-    const size_t lds = (size_t)nstrips * RG::SLOT;
+    const size_t lds = (size_t)NB * nstrips * RG::SLOT;
     if (lds > (size_t)ROWS_LDS_LIMIT) return hipErrorNotSupported;
     static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<F, U>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<F, U, NB>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    ROWS_LDS_LIMIT);
     });
     if (e != hipSuccess) return e;
@@ -199,24 +210,33 @@ static hipError_t rows_launch(const void *packed, int64_t rows, int64_t cols, co
     const int64_t rows_per_wg = (int64_t)waves * groups * U;
     const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
     const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;
-    hipLaunchKernelGGL((gemv_rows_kernel<F, U>), dim3((unsigned)grid), dim3(64 * waves), lds, s, static_cast<const uint8_t *>(packed), x, y,
+    hipLaunchKernelGGL((gemv_rows_kernel<F, U, NB>), dim3((unsigned)grid), dim3(64 * waves), lds, s, static_cast<const uint8_t *>(packed), x, y,
                        (int)rows, (int)cols, nbk, nstrips, groups, header_offset);
     return hipGetLastError();
 }
 
-// One activation vector, any format but IFLOW_Q3H_B64.  hipErrorNotSupported: the row is too long for the staged
-// activations to fit in LDS (beyond about 60000 columns) - the caller then takes the older kernel.
-hipError_t launch_qgemv_rows(int format, const void *packed, int64_t rows, int64_t cols, const uint16_t *x, uint16_t *y, hipStream_t s)
+template <int F>
+static hipError_t rows_batch(const void *packed, int64_t rows, int64_t cols, const uint16_t *x, int batch, uint16_t *y, hipStream_t s)
 {
+    return batch == 1 ? rows_launch<F, 2, 1>(packed, rows, cols, x, y, s) : rows_launch<F, 2, 2>(packed, rows, cols, x, y, s);
+}
+
+// One or two activation vectors (x: [batch][cols], y: [batch][rows]), any format but IFLOW_Q3H_B64.  hipErrorNotSupported:
+// the rows are too long for the staged activations to fit in LDS (beyond about 60000 columns for one vector, half that
+// for two) - the caller then takes the older kernel.
+hipError_t launch_qgemv_rows(int format, const void *packed, int64_t rows, int64_t cols, const uint16_t *x, int batch, uint16_t *y,
+                             hipStream_t s)
+{
+    if (batch < 1 || batch > 2) return hipErrorInvalidValue;
     switch (format) {
-    case IFLOW_Q8_B32: return rows_launch<IFLOW_Q8_B32, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q8_B64: return rows_launch<IFLOW_Q8_B64, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q4_B32: return rows_launch<IFLOW_Q4_B32, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q4_B64: return rows_launch<IFLOW_Q4_B64, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q6_B64: return rows_launch<IFLOW_Q6_B64, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q5_B64: return rows_launch<IFLOW_Q5_B64, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q3_B32: return rows_launch<IFLOW_Q3_B32, 2>(packed, rows, cols, x, y, s);
-    case IFLOW_Q2_B32: return rows_launch<IFLOW_Q2_B32, 2>(packed, rows, cols, x, y, s);
+    case IFLOW_Q8_B32: return rows_batch<IFLOW_Q8_B32>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q8_B64: return rows_batch<IFLOW_Q8_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q4_B32: return rows_batch<IFLOW_Q4_B32>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q4_B64: return rows_batch<IFLOW_Q4_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q6_B64: return rows_batch<IFLOW_Q6_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q5_B64: return rows_batch<IFLOW_Q5_B64>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q3_B32: return rows_batch<IFLOW_Q3_B32>(packed, rows, cols, x, batch, y, s);
+    case IFLOW_Q2_B32: return rows_batch<IFLOW_Q2_B32>(packed, rows, cols, x, batch, y, s);
     default: return hipErrorInvalidValue;
     }
 }

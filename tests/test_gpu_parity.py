@@ -125,13 +125,16 @@ def test_ragged_shapes(gpu, orc, name, rows, nblocks):
 
 
 # ---- very long rows: the one-vector kernel stages a whole row of activations in LDS; beyond its limit (144 KiB: 32 strips
-#      of 2048 columns, 57 strips of 1024 for 8-bit) the launcher takes the older kernel.  Both sides of the limit. ------------
-@pytest.mark.parametrize("name,cols", [("Q4_B64", 65536), ("Q4_B64", 65536 + 2048), ("Q8_B32", 57 * 1024), ("Q8_B32", 58 * 1024 + 32),
-                                       ("Q6_B64", 65536 + 64), ("Q2_B32", 65536 - 32)])
-def test_rows_at_the_staging_limit(gpu, orc, name, cols):
+#      of 2048 columns, 57 strips of 1024 for 8-bit; half as many with two vectors) the launcher takes the older kernel.
+#      Both sides of the limit. ------------
+@pytest.mark.parametrize("name,cols,batch", [("Q4_B64", 65536, 1), ("Q4_B64", 65536 + 2048, 1), ("Q8_B32", 57 * 1024, 1),
+                                             ("Q8_B32", 58 * 1024 + 32, 1), ("Q6_B64", 65536 + 64, 1), ("Q2_B32", 65536 - 32, 1),
+                                             ("Q4_B64", 32768, 2), ("Q4_B64", 32768 + 64, 2), ("Q8_B64", 28 * 1024 + 64, 2),
+                                             ("Q5_B64", 65536, 2)])
+def test_rows_at_the_staging_limit(gpu, orc, name, cols, batch):
     torch, iflow = gpu
     w = synth.weights(5, cols, 0.02, synth.BASE_SEED + 77)
-    x = synth.activations(1, cols, synth.BASE_SEED + 78)
+    x = synth.activations(batch, cols, synth.BASE_SEED + 78)
     check_all(torch, iflow, orc, name, w, x, "long-rows")
 
 
