@@ -370,29 +370,32 @@ def main():
                 us = t0.elapsed_time(t1) * 1e3 / (6 * nring)
                 other["attention_decode"]["cases"][f"{n_heads}/{n_kv} heads, {T} positions"] = {"us": round(us, 2), "GB/s": round(kv_bytes / us / 1e3, 1)}
                 del caches
-            # the other block formats of Table 3 (and the 2-bit one), one activation vector, same matrix shape: the
-            # vector kernel they share; copies of one packed matrix at 16 distinct addresses
-            other["other_formats_batch1"] = {"what": f"{g_rows}x{g_cols}, ring of 16 packed copies, eager launches, us per product and "
-                                                     "GB/s of packed bytes", "formats": {}}
+            # the other block formats of Table 3 (and the 2-bit one) on the same matrix shape, 1 to 16 activation vectors:
+            # copies of one packed matrix at 16 distinct addresses
+            other["other_formats"] = {"what": f"{g_rows}x{g_cols}, ring of 16 packed copies, eager launches; per format and number of "
+                                              "activation vectors: us per product, GB/s of packed bytes", "formats": {}}
             wg = torch.randn((g_rows, g_cols), generator=gen, device=dev, dtype=torch.float32) * SIGMA
-            Xo = torch.randn((1, g_cols), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
-            Yo = torch.empty((1, g_rows), dtype=torch.float16, device=dev)
             for oname in ("Q8_B64", "Q6_B64", "Q5_B64", "Q4_B64", "Q3_B32", "Q2_B32"):
                 ofmt = iflow.FORMATS[oname]
                 nb_o = iflow.packed_bytes(ofmt, g_rows, g_cols)
                 first = torch.empty(nb_o, dtype=torch.uint8, device=dev)
                 iflow.quantize(ofmt, wg, g_rows, g_cols, first, nb_o, stream=raw)
                 copies = [first] + [first.clone() for _ in range(15)]
-                for pk in copies[:2]:
-                    iflow.qgemm(ofmt, pk, g_rows, g_cols, Xo, 1, Yo, stream=raw)
-                t0.record(stream)
-                for _ in range(12):
-                    for pk in copies:
-                        iflow.qgemm(ofmt, pk, g_rows, g_cols, Xo, 1, Yo, stream=raw)
-                t1.record(stream)
-                t1.synchronize()
-                us = t0.elapsed_time(t1) * 1e3 / (12 * 16)
-                other["other_formats_batch1"]["formats"][oname] = {"us": round(us, 2), "GB/s": round(nb_o / us / 1e3, 1)}
+                per_batch = {}
+                for ob in (1, 2, 4, 8, 16):
+                    Xo = torch.randn((ob, g_cols), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+                    Yo = torch.empty((ob, g_rows), dtype=torch.float16, device=dev)
+                    for pk in copies[:2]:
+                        iflow.qgemm(ofmt, pk, g_rows, g_cols, Xo, ob, Yo, stream=raw)
+                    t0.record(stream)
+                    for _ in range(8):
+                        for pk in copies:
+                            iflow.qgemm(ofmt, pk, g_rows, g_cols, Xo, ob, Yo, stream=raw)
+                    t1.record(stream)
+                    t1.synchronize()
+                    us = t0.elapsed_time(t1) * 1e3 / (8 * 16)
+                    per_batch[str(ob)] = {"us": round(us, 2), "GB/s": round(nb_o / us / 1e3, 1)}
+                other["other_formats"]["formats"][oname] = per_batch
                 del copies, first
             del wg
             w1 = torch.randn((1024, 1024), generator=gen, device=dev, dtype=torch.float32) * SIGMA
