@@ -347,15 +347,29 @@ __global__ __launch_bounds__(ATT_D) void attn_merge_kernel(const float *__restri
     const float *ws_o = ws + (int64_t)head * ATT_MAX_SPLITS * ATT_D + d;
     const float *ws_m = ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS + (int64_t)head * ATT_MAX_SPLITS;
     const float *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS;
-    float M = -INFINITY;
-#pragma unroll 8
-    for (int i = 0; i < nsplit; ++i) M = fmaxf(M, ws_m[i]);
-    float L = 0.f, O = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < nsplit; ++i) {
-        const float f = __builtin_amdgcn_exp2f(ws_m[i] - M);
-        L = __builtin_fmaf(ws_l[i], f, L);
-        O = __builtin_fmaf(ws_o[(int64_t)i * ATT_D], f, O);
+    // eight ranges at a time, every load of a batch issued before anything waits (maxima, sums and value sums do not depend
+    // on each other's addresses): one memory round trip per batch instead of one for the maxima and one for the rest
+    float M = -INFINITY, L = 0.f, O = 0.f;
+    for (int i0 = 0; i0 < nsplit; i0 += 8) {
+        float m[8], l[8], o[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = min(i0 + u, nsplit - 1);            // past the end: the last range again (not added below)
+            m[u] = ws_m[i]; l[u] = ws_l[i]; o[u] = ws_o[(int64_t)i * ATT_D];
+        }
+        float mb = m[0];
+#pragma unroll
+        for (int u = 1; u < 8; ++u) mb = fmaxf(mb, m[u]);     // (a repeated range does not change the maximum)
+        const float m_new = fmaxf(M, mb);                     // finite: no range is empty
+        const float keep = __builtin_amdgcn_exp2f(M - m_new); // 0 for the first batch
+        L *= keep; O *= keep;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float f = i0 + u < nsplit ? __builtin_amdgcn_exp2f(m[u] - m_new) : 0.f;
+            L = __builtin_fmaf(l[u], f, L);
+            O = __builtin_fmaf(o[u], f, O);
+        }
+        M = m_new;
     }
     out[(int64_t)head * ATT_D + d] = as_u16((half_t)(O / L));
 }
