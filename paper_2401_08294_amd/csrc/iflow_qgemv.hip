@@ -2,15 +2,20 @@
 // stream) and up to four activation vectors per pass.  Eq.5 and Eq.2 of the paper are applied in
 // registers; the dequantized weights never exist in memory.
 //
+// Two kernels live here.  q3h_gemv_kernel (further down) is the 3.5-bit format's: activations staged once per
+// workgroup, rows owned by wavefronts; the other formats' counterpart of it is in iflow_qgemv_rows.hip.  qgemv_kernel
+// (first) is the older, format-generic one that the launchers fall back to - rows too long for the staging, three or
+// four vectors when the column count rules out the MFMA kernels:
+//
 // Mapping ("activation-stationary"): a wavefront owns one strip of the reduction dimension, 64 lanes x
 // WPL consecutive weights, and walks down the rows.  Each lane keeps the activations of its own
 // WPL columns in registers for the whole walk, so the inner loop touches memory only for weights:
-// one (Q4, Q8) or two (Q3H) 16-byte loads per lane and row, 1 KiB of consecutive bytes per wavefront
-// load.  Because the levels of a lane all share one block header,
+// one to three loads per lane and row (16 bytes of codes, or a lane's share of each bit plane, and the header).
+// Because the levels of a lane all share one block header,
 //     sum_k (q_k * s + o) x_k  =  s * sum_k q_k x_k  +  o * sum_k x_k ,
 // the per-weight work is one packed conversion and one dot2 step; scale and offset are applied once per
 // lane and row.  Levels are converted to fp16 by OR-ing them into the mantissa of a power of two
-// (1024 + q, 64 + q), and the known bias times sum(x) is removed together with the header.
+// (1024 + q, 64 + q, ...), and the known bias times sum(x) is removed together with the header.
 // Row sums are reduced across the wavefront with DPP, across the wavefronts of a workgroup (one per
 // strip) through LDS.
 #include <stdlib.h>
