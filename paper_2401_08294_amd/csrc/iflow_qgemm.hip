@@ -1,7 +1,7 @@
 // Dequantize-and-multiply on the matrix cores for batches large enough to make the product a dense
 // contraction: Y[b][n] = sum_k w'[n][k] X[b][k].
 //
-// A workgroup of four wavefronts owns a 128 (batch) x 64 (weight rows) tile of Y and walks along K in
+// A workgroup of four wavefronts owns a 128 (batch; 64 for batches up to 64) x 64 (weight rows) tile of Y and walks along K in
 // chunks of 64 columns, i.e. one quantization block per weight row (two for the 32-wide formats).  Per chunk
 // it (1) copies the 128 x 64 fp16 activation tile into LDS, (2) decodes its 64 packed blocks into fp16
 // weights in LDS - Eq.5 and Eq.2 of the paper, with the same single-rounded fp16 fused multiply-add as the
@@ -17,7 +17,7 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int GM_BM = 128, GM_BN = 64, GM_BK = 64, GM_LD = 72;   // tile sizes; LDS row pitch in halves (144 bytes)
+constexpr int GM_BN = 64, GM_BK = 64, GM_LD = 72;   // weight rows and columns per tile (batch rows: a template parameter); LDS row pitch in halves (144 bytes)
 
 __device__ __forceinline__ uint32_t pack_h2(half2_t v) { return as_u32(v); }
 
@@ -147,21 +147,22 @@ __device__ __forceinline__ void decode16(const Raw16 &r, int qd, uint32_t (&out)
 // (The inputs are deliberately not declared __restrict__: loads from memory the compiler knows to be read-only and
 // unaliased are free to move, and the scheduler then sinks the prefetch of a later chunk down to its use, four
 // barriers later, to save registers - which turns every chunk into a full memory round trip.)
-template <int F>
+template <int F, int MT>
 __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, const uint16_t *X, uint16_t *Y, int rows, int cols,
                                                          int batch, int nbk, int64_t header_offset)
 {
     // two LDS stages: while the MFMAs read one, the next chunk is written into the other
-    __shared__ __align__(16) uint16_t xs[2][GM_BM * GM_LD];    // activations  [128][68]
+    constexpr int BM = 64 * MT;                                // batch rows per workgroup: 128, or 64 where that gives the part more workgroups
+    __shared__ __align__(16) uint16_t xs[2][BM * GM_LD];       // activations  [BM][72]
     __shared__ __align__(16) uint16_t ws[2][GM_BN * GM_LD];    // weights      [64][68]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n0 = blockIdx.x * GM_BN, m0 = blockIdx.y * GM_BM;
+    const int n0 = blockIdx.x * GM_BN, m0 = blockIdx.y * BM;
     const int wm = wave >> 1, wn = wave & 1;                   // this wavefront: batch rows wm*64.., weight rows wn*32..
 
     // loaders: activations - thread -> (row tid/2, 32 halves at (tid%2)*32); weights - thread -> (row tid/4, quarter tid%4)
-    const int xr = tid >> 1, xh = tid & 1;
+    const int xr = MT == 2 ? tid >> 1 : tid >> 2, xh = MT == 2 ? tid & 1 : tid & 3;   // (MT == 1: row tid/4, 16 halves at (tid%4)*16)
     const int64_t xrow = min(m0 + xr, batch - 1);              // rows past the batch repeat the last row, their outputs are not stored
-    const u32x4_t *xsrc = reinterpret_cast<const u32x4_t *>(X + xrow * cols + xh * 32);
+    const u32x4_t *xsrc = reinterpret_cast<const u32x4_t *>(X + xrow * cols + xh * (16 * MT));
     const int wr = tid >> 2, wq = tid & 3;
     const int64_t wrow = min(n0 + wr, rows - 1);
     const int nchunks = cols / GM_BK;
@@ -173,23 +174,25 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
     auto fetch = [&](Stage &st, int kb) {                      // global -> registers; chunks past the end repeat the last one
         const int kc = min(kb, nchunks - 1);
         const u32x4_t *xp = xsrc + (int64_t)kc * 8;            // 64 halves per row and chunk = 8 x 16 bytes; this thread's half = 4
-        st.x0 = xp[0]; st.x1 = xp[1]; st.x2 = xp[2]; st.x3 = xp[3];
+        st.x0 = xp[0]; st.x1 = xp[1];
+        if constexpr (MT == 2) { st.x2 = xp[2]; st.x3 = xp[3]; }
         load16<F>(packed, header_offset, plane_b, wrow, nbk, kc, wq, st.w);
     };
     auto stash = [&](const Stage &st, int buf) {               // registers -> LDS, weights decoded on the way
         uint32_t wv[8];
         decode16<F>(st.w, wq, wv);
-        u32x4_t *xd = reinterpret_cast<u32x4_t *>(&xs[buf][xr * GM_LD + xh * 32]);
-        xd[0] = st.x0; xd[1] = st.x1; xd[2] = st.x2; xd[3] = st.x3;
+        u32x4_t *xd = reinterpret_cast<u32x4_t *>(&xs[buf][xr * GM_LD + xh * (16 * MT)]);
+        xd[0] = st.x0; xd[1] = st.x1;
+        if constexpr (MT == 2) { xd[2] = st.x2; xd[3] = st.x3; }
         *reinterpret_cast<uint4 *>(&ws[buf][wr * GM_LD + wq * 16]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
         *reinterpret_cast<uint4 *>(&ws[buf][wr * GM_LD + wq * 16 + 8]) = make_uint4(wv[4], wv[5], wv[6], wv[7]);
     };
 
     // four independent accumulator chains per wavefront (two output tiles x even/odd k-steps), summed at the end:
     // a chain's next MFMA then never waits for its previous one
-    float16_t acc[2][2];
+    float16_t acc[MT][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
@@ -199,21 +202,21 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
     // next chunk's decode and LDS writes are issued behind them, and only then come the eight MFMAs: left to itself the
     // compiler reads each fragment into the same few registers right before its MFMA and waits for it there - a full LDS
     // round trip in front of every MFMA, 1500 cycles per chunk for 256 cycles of matrix-core work.
-    half8_t af[2][4], bf[4];
+    half8_t af[MT][4], bf[4];
     auto read_fragments = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {                       // 16 columns per step: lane (li, kg) holds k = 8 kg .. 8 kg + 7
             bf[ks] = *reinterpret_cast<const half8_t *>(&ws[buf][(wn * 32 + li) * GM_LD + ks * 16 + kg * 8]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                af[i][ks] = *reinterpret_cast<const half8_t *>(&xs[buf][(wm * 64 + i * 32 + li) * GM_LD + ks * 16 + kg * 8]);
+            for (int i = 0; i < MT; ++i)
+                af[i][ks] = *reinterpret_cast<const half8_t *>(&xs[buf][(wm * 32 * MT + i * 32 + li) * GM_LD + ks * 16 + kg * 8]);
         }
     };
     auto multiply = [&]() {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MT; ++i)
                 acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i][ks], bf[ks], acc[i][ks & 1], 0, 0, 0);
     };
 
@@ -245,10 +248,10 @@ __global__ __launch_bounds__(256) void qgemm_mfma_kernel(const uint8_t *packed, 
     // 32x32 accumulator layout: register v of lane l is D[(v/4)*8 + (l/32)*4 + v%4][l%32]
     const int col = n0 + wn * 32 + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int brow = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            const int brow = m0 + wm * 32 * MT + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
             if (brow < batch && col < rows) Y[(int64_t)brow * rows + col] = as_u16((half_t)(acc[i][0][v] + acc[i][1][v]));
         }
 }
@@ -259,10 +262,20 @@ static hipError_t gemm_one(const void *packed, int64_t rows, int64_t cols, const
     typedef Fmt<F> T;
     const int nbk = (int)(cols / T::block);
     const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;
-    const dim3 grid((unsigned)((rows + GM_BN - 1) / GM_BN), (unsigned)((batch + GM_BM - 1) / GM_BM));
+    // 128 batch rows per workgroup; 64 for batches that would leave half of a 128-row tile empty (32-64 vectors: 25 us instead
+    // of 33 on 4096 x 4096).  With more vectors the smaller tile only adds workgroups that re-read the weights (measured:
+    // 36.7 against 34.7 us at 512 vectors).
+    const int64_t nx = (rows + GM_BN - 1) / GM_BN;
+    const bool small_tiles = batch <= 64;
+    const int bm = small_tiles ? 64 : 128;
+    const dim3 grid((unsigned)nx, (unsigned)((batch + bm - 1) / bm));
     if (grid.y > 65535u) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((qgemm_mfma_kernel<F>), grid, dim3(256), 0, s,
-                       static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk, header_offset);
+    if (small_tiles)
+        hipLaunchKernelGGL((qgemm_mfma_kernel<F, 1>), grid, dim3(256), 0, s,
+                           static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk, header_offset);
+    else
+        hipLaunchKernelGGL((qgemm_mfma_kernel<F, 2>), grid, dim3(256), 0, s,
+                           static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk, header_offset);
     return hipGetLastError();
 }
 
