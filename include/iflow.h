@@ -121,7 +121,9 @@ iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t ro
  * or the gate, up matrices of a decoder layer, which the decode step applies to the same input.  All matrices have
  * `cols` columns; matrix i has rows[i] rows, its own packed buffer packed[i] and its own output y[i] ([rows[i]] fp16).
  * `packed`, `rows` and `y` are HOST arrays of `count` entries (of device pointers / sizes); they are read during the
- * call and need not outlive it.  Results are those of `count` iflow_qgemv calls. */
+ * call and need not outlive it.  Results are those of `count` iflow_qgemv calls, bit for bit.  (Every format takes one
+ * launch; rows of more than about 60000 columns, which the one-launch kernels of the formats other than 3.5-bit cannot
+ * stage, fall back to one launch per matrix.) */
 iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
                                  int64_t cols, const uint16_t *x, uint16_t *const *y, void *stream);
 

@@ -199,6 +199,8 @@ hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64
                              const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemv_rows(int format, const void *packed, int64_t rows, int64_t cols, const uint16_t *x, int batch, uint16_t *y,
                              hipStream_t s);
+hipError_t launch_qgemv_rows_multi(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols, const uint16_t *x,
+                                   uint16_t *const *y, hipStream_t s);
 hipError_t launch_qgemv(int format, const void *packed, int64_t rows, int64_t cols,
                         const uint16_t *x, int64_t batch, uint16_t *y, hipStream_t s);
 

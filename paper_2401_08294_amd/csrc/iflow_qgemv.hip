@@ -588,7 +588,11 @@ hipError_t launch_qgemv_multi(int format, int count, const void *const *packed, 
         grp.count = count;
         return q3h_launch<1>(grp, cols, x, s);
     }
-    for (int i = 0; i < count; ++i) {                         // the other formats: one launch per matrix
+    if (count > 1) {                                          // the other formats: one launch too, unless the rows are too long to stage
+        const hipError_t e = launch_qgemv_rows_multi(format, count, packed, rows, cols, x, y, s);
+        if (e != hipErrorNotSupported) return e;
+    }
+    for (int i = 0; i < count; ++i) {                         // (one launch per matrix)
         hipError_t e = launch_qgemv(format, packed[i], rows[i], cols, x, 1, y[i], s);
         if (e != hipSuccess) return e;
     }

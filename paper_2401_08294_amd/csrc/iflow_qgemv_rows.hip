@@ -26,12 +26,34 @@ template <int KIND> struct RowsGeo {
 
 constexpr int ROWS_LDS_LIMIT = 144 * 1024;
 
-template <int F, int U, int NB>
-__global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
-                                                        uint16_t *__restrict__ Y, int rows, int cols, int nbk, int nstrips,
-                                                        int groups /* of U rows per wavefront */, int64_t header_offset)
+// Up to eight matrices that share the activation vector(s) and the column count in one launch (the q/k/v or the gate/up
+// projections of a decoder layer): workgroup ranges are dealt to the matrices in order.
+constexpr int ROWS_MAX_GROUP = 8;
+struct RowsGroup {
+    const uint8_t *packed[ROWS_MAX_GROUP];
+    uint16_t *y[ROWS_MAX_GROUP];
+    int rows[ROWS_MAX_GROUP];
+    int wg_end[ROWS_MAX_GROUP];                                // one past the last workgroup of matrix i
+    int count;
+};
+
+template <int F, int U, int NB, bool MULTI>
+__global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
+                                                        uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips,
+                                                        int groups /* of U rows per wavefront */, const RowsGroup grp)
 {
     typedef Fmt<F> T;
+    int mi = 0;                                                // which matrix this workgroup belongs to
+    if (MULTI) {
+#pragma unroll
+        for (int i = 0; i + 1 < ROWS_MAX_GROUP; ++i)
+            if (i + 1 < grp.count && (int)blockIdx.x >= grp.wg_end[i]) mi = i + 1;
+    }
+    const int wg = MULTI ? blockIdx.x - (mi ? grp.wg_end[mi - 1] : 0) : blockIdx.x;
+    const uint8_t *__restrict__ packed = MULTI ? grp.packed[mi] : packed0;
+    uint16_t *__restrict__ Y = MULTI ? grp.y[mi] : y0;
+    const int rows = MULTI ? grp.rows[mi] : rows0;
+    const int64_t header_offset = (int64_t)rows * nbk * T::code_bytes;
     constexpr int KIND = T::kind;
     typedef Geo<KIND> G;
     typedef RowsGeo<KIND> RG;
@@ -113,7 +135,7 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     };
 
     // ---- the walk: steps (group, strip) of this wavefront, one set of weights ahead ---------------------------------
-    const int rbase = (blockIdx.x * waves + wave) * groups * U;
+    const int rbase = (wg * waves + wave) * groups * U;
     const int nsteps = groups * nstrips;
     auto step_row = [&](int k, int &r0, int &t) {
         const int kk = min(k, nsteps - 1);
@@ -182,8 +204,8 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     }
 }
 
-template <int F, int U, int NB>
-static hipError_t rows_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *x, uint16_t *y, hipStream_t s)
+template <int F, int U, int NB, bool MULTI>
+static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hipStream_t s)
 {
     typedef Fmt<F> T;
     typedef Geo<T::kind> G;
@@ -195,10 +217,12 @@ static hipError_t rows_launch(const void *packed, int64_t rows, int64_t cols, co
     static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<F, U, NB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<F, U, NB, MULTI>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    ROWS_LDS_LIMIT);
     });
     if (e != hipSuccess) return e;
+    int64_t rows = 0;
+    for (int i = 0; i < grp.count; ++i) rows += grp.rows[i];
     // wavefronts per workgroup and groups of U rows per wavefront: enough workgroups to fill the part a few times over,
     // but not so many that the staging (paid once per workgroup) outweighs the rows it serves
     // (measured over 4096 x 4096, 11008 x 4096 and 4096 x 11008 in four formats: every choice of 2-8 wavefronts, 1-2 groups
@@ -208,17 +232,37 @@ static hipError_t rows_launch(const void *packed, int64_t rows, int64_t cols, co
     if (groups < 1) groups = 1;
     if (groups > 4) groups = 4;
     const int64_t rows_per_wg = (int64_t)waves * groups * U;
-    const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
-    const int64_t header_offset = rows * (cols / T::block) * (int64_t)T::code_bytes;
-    hipLaunchKernelGGL((gemv_rows_kernel<F, U, NB>), dim3((unsigned)grid), dim3(64 * waves), lds, s, static_cast<const uint8_t *>(packed), x, y,
-                       (int)rows, (int)cols, nbk, nstrips, groups, header_offset);
+    int64_t grid = 0;
+    for (int i = 0; i < grp.count; ++i) {
+        grid += (grp.rows[i] + rows_per_wg - 1) / rows_per_wg;
+        grp.wg_end[i] = (int)grid;
+    }
+    if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemv_rows_kernel<F, U, NB, MULTI>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x, grp.y[0],
+                       grp.rows[0], (int)cols, nbk, nstrips, groups, grp);
     return hipGetLastError();
 }
 
 template <int F>
-static hipError_t rows_batch(const void *packed, int64_t rows, int64_t cols, const uint16_t *x, int batch, uint16_t *y, hipStream_t s)
+static hipError_t rows_batch(const RowsGroup &grp, int64_t cols, const uint16_t *x, int batch, hipStream_t s)
 {
-    return batch == 1 ? rows_launch<F, 2, 1>(packed, rows, cols, x, y, s) : rows_launch<F, 2, 2>(packed, rows, cols, x, y, s);
+    if (grp.count > 1) return rows_launch<F, 2, 1, true>(grp, cols, x, s);            // (several matrices: one vector only)
+    return batch == 1 ? rows_launch<F, 2, 1, false>(grp, cols, x, s) : rows_launch<F, 2, 2, false>(grp, cols, x, s);
+}
+
+static hipError_t rows_dispatch(int format, const RowsGroup &grp, int64_t cols, const uint16_t *x, int batch, hipStream_t s)
+{
+    switch (format) {
+    case IFLOW_Q8_B32: return rows_batch<IFLOW_Q8_B32>(grp, cols, x, batch, s);
+    case IFLOW_Q8_B64: return rows_batch<IFLOW_Q8_B64>(grp, cols, x, batch, s);
+    case IFLOW_Q4_B32: return rows_batch<IFLOW_Q4_B32>(grp, cols, x, batch, s);
+    case IFLOW_Q4_B64: return rows_batch<IFLOW_Q4_B64>(grp, cols, x, batch, s);
+    case IFLOW_Q6_B64: return rows_batch<IFLOW_Q6_B64>(grp, cols, x, batch, s);
+    case IFLOW_Q5_B64: return rows_batch<IFLOW_Q5_B64>(grp, cols, x, batch, s);
+    case IFLOW_Q3_B32: return rows_batch<IFLOW_Q3_B32>(grp, cols, x, batch, s);
+    case IFLOW_Q2_B32: return rows_batch<IFLOW_Q2_B32>(grp, cols, x, batch, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // One or two activation vectors (x: [batch][cols], y: [batch][rows]), any format but IFLOW_Q3H_B64.  hipErrorNotSupported:
@@ -228,17 +272,23 @@ hipError_t launch_qgemv_rows(int format, const void *packed, int64_t rows, int64
                              hipStream_t s)
 {
     if (batch < 1 || batch > 2) return hipErrorInvalidValue;
-    switch (format) {
-    case IFLOW_Q8_B32: return rows_batch<IFLOW_Q8_B32>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q8_B64: return rows_batch<IFLOW_Q8_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q4_B32: return rows_batch<IFLOW_Q4_B32>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q4_B64: return rows_batch<IFLOW_Q4_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q6_B64: return rows_batch<IFLOW_Q6_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q5_B64: return rows_batch<IFLOW_Q5_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q3_B32: return rows_batch<IFLOW_Q3_B32>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q2_B32: return rows_batch<IFLOW_Q2_B32>(packed, rows, cols, x, batch, y, s);
-    default: return hipErrorInvalidValue;
+    RowsGroup grp = {};
+    grp.packed[0] = static_cast<const uint8_t *>(packed); grp.y[0] = y; grp.rows[0] = (int)rows; grp.count = 1;
+    return rows_dispatch(format, grp, cols, x, batch, s);
+}
+
+// `count` (1-8) matrices of one format that share x (one vector) and the column count, in one launch; same results as
+// separate launches, bit for bit (a row's arithmetic does not depend on which workgroup runs it).
+hipError_t launch_qgemv_rows_multi(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols, const uint16_t *x,
+                                   uint16_t *const *y, hipStream_t s)
+{
+    if (count < 1 || count > ROWS_MAX_GROUP) return hipErrorInvalidValue;
+    RowsGroup grp = {};
+    for (int i = 0; i < count; ++i) {
+        grp.packed[i] = static_cast<const uint8_t *>(packed[i]); grp.y[i] = y[i]; grp.rows[i] = (int)rows[i];
     }
+    grp.count = count;
+    return rows_dispatch(format, grp, cols, x, 1, s);
 }
 
 }  // namespace iflow

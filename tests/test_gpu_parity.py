@@ -247,7 +247,7 @@ def test_batch512_full_size_sampled_rows(gpu, orc):
 
 
 # ---- several projections of one activation vector in one launch -----------------------------------------
-@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B64"])
+@pytest.mark.parametrize("name", ["Q3H_B64", "Q4_B64", "Q8_B32", "Q6_B64", "Q3_B32", "Q2_B32"])
 def test_qgemv_multi_matches_single_launches(gpu, orc, name):
     torch, iflow = gpu
     fmt, ofmt = iflow.FORMATS[name], orc.FORMATS[name]
