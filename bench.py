@@ -426,7 +426,8 @@ def main():
                     traffic = None
 
     out = {
-        "metric": "achieved HBM GB/s (% of peak) of 3.5-bit fused dequant-GEMV, 7B shapes, batch 1",
+        "metric": "achieved HBM GB/s (% of peak) of 3.5-bit fused dequant-GEMV, 7B shapes, batch 1" if args.format == "Q3H_B64"
+                  else f"achieved HBM GB/s (% of peak) of {args.format} fused dequant-GEMV, 7B shapes, batch 1 (context; the headline is the 3.5-bit format)",
         "value": round(value, 1), "unit": "GB/s", "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 x u7-pair codes, f32 accumulate",
