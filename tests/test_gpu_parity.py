@@ -149,6 +149,30 @@ def test_tall_and_thin(gpu, orc, name, batch):
     check_all(torch, iflow, orc, name, w, x, "tall-thin")
 
 
+# ---- a seeded sweep over shapes and batch sizes on both sides of every kernel-selection threshold (1 | 2 | 3..31 | 32..64 |
+#      65..; column counts that are and are not multiples of 64 for the 32-wide blocks) -----------------------------------------
+def _sweep_cases():
+    rng = np.random.default_rng(synth.BASE_SEED + 4242)
+    batches = [1, 2, 3, 4, 5, 11, 12, 16, 17, 31, 32, 33, 64, 65, 130]
+    cases = []
+    for name in NAMES:
+        for _ in range(4):
+            rows = int(rng.integers(1, 300))
+            nblocks = int(rng.integers(1, 141))
+            batch = int(rng.choice(batches))
+            cases.append((name, rows, nblocks, batch))
+    return cases
+
+
+@pytest.mark.parametrize("name,rows,nblocks,batch", _sweep_cases())
+def test_seeded_shape_sweep(gpu, orc, name, rows, nblocks, batch):
+    torch, iflow = gpu
+    cols = nblocks * iflow.format_block(iflow.FORMATS[name])
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 17 * rows + nblocks, outlier_prob=0.001)
+    x = synth.activations(batch, cols, synth.BASE_SEED + batch)
+    check_all(torch, iflow, orc, name, w, x, "sweep")
+
+
 # ---- small batches (2, 3, 4 share a pass; 5 and 16 take several) ----------------------------------------
 @pytest.mark.parametrize("name", NAMES)
 @pytest.mark.parametrize("batch", [2, 3, 4, 5, 8, 16, 21])
