@@ -230,7 +230,7 @@ def test_small_batch_more_rounds_than_one_launch_holds(gpu, orc):
 
 
 # ---- 32-wide blocks allow column counts that are not a multiple of 64: those stay on the vector kernel at any batch ----
-@pytest.mark.parametrize("name", ["Q4_B32", "Q8_B32"])
+@pytest.mark.parametrize("name", ["Q4_B32", "Q8_B32", "Q3_B32", "Q2_B32"])
 @pytest.mark.parametrize("batch", [3, 7, 40])
 def test_odd_block_count_batches(gpu, orc, name, batch):
     torch, iflow = gpu
