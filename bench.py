@@ -370,6 +370,48 @@ def main():
                 us = t0.elapsed_time(t1) * 1e3 / (6 * nring)
                 other["attention_decode"]["cases"][f"{n_heads}/{n_kv} heads, {T} positions"] = {"us": round(us, 2), "GB/s": round(kv_bytes / us / 1e3, 1)}
                 del caches
+            # a whole decode step per layer: normalization, gate and residuals fused into the four launches, attention over 1024
+            # cached positions in between (HIP-graph replay over the ring; key/value bytes are not counted in the GB/s)
+            if args.format == "Q3H_B64" and not args.fused:
+                ctx = 1024
+                hs = xs[shapes[0][2]].clone()
+                gn = [(1.0 + 0.1 * torch.randn((shapes[0][2],), generator=gen, device=dev, dtype=torch.float32)).to(torch.float16) for _ in range(2)]
+                ao = torch.empty_like(ys[0])
+                kvs = [(torch.randn((32, ctx, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16),
+                        torch.randn((32, ctx, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)) for _ in range(args.ring)]
+                awb2 = iflow.attn_decode_workspace_bytes(32)
+                aws2 = torch.empty((awb2,), dtype=torch.uint8, device=dev)
+
+                def decode_layer(layer):
+                    m = ring[layer]
+                    iflow.qgemv_fused(fmt, [m[i][2] for i in (0, 1, 2)], [m[i][0] for i in (0, 1, 2)], m[0][1], hs, [ys[0], ys[1], ys[2]],
+                                      iflow.X_RMS_GAIN, gn[0], 1e-5, stream=raw)
+                    iflow.attn_decode(ys[0], kvs[layer][0], kvs[layer][1], 32, 32, 128, ctx, ctx, 128 ** -0.5, ao, aws2, awb2, stream=raw)
+                    iflow.qgemv_fused(fmt, [m[3][2]], [m[3][0]], m[3][1], ao, [hs], residual_list=[hs], stream=raw)
+                    iflow.qgemv_fused(fmt, [m[4][2], m[5][2]], [m[4][0], m[5][0]], m[4][1], hs, [ys[4], ys[5]], iflow.X_RMS_GAIN, gn[1], 1e-5, stream=raw)
+                    iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [hs], iflow.X_SILU_MUL, ys[5], 0.0, residual_list=[hs], stream=raw)
+
+                for layer in range(2):
+                    decode_layer(layer)
+                stream.synchronize()
+                dgraph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(dgraph, stream=stream):
+                    for layer in range(args.ring):
+                        decode_layer(layer)
+                for _ in range(3):
+                    dgraph.replay()
+                t0.record(stream)
+                for _ in range(20):
+                    dgraph.replay()
+                t1.record(stream)
+                t1.synchronize()
+                us_layer = t0.elapsed_time(t1) * 1e3 / (20 * args.ring)
+                other["decode_step_with_attention"] = {
+                    "what": "per decoder layer: rms-norm + q,k,v | attention over 1024 cached positions (32 heads) | o + residual | rms-norm + "
+                            "gate,up | silu(gate)*up + down + residual: 4 fused launches + attention, HIP-graph replay over the ring",
+                    "us_per_layer": round(us_layer, 2), "weight_GB/s": round(step_bytes / us_layer / 1e3, 1),
+                    "tokens_per_s_32_layers": round(1e6 / (32 * us_layer), 1)}
+                del kvs
             # the other block formats of Table 3 (and the 2-bit one) on the same matrix shape, 1 to 16 activation vectors:
             # copies of one packed matrix at 16 distinct addresses
             other["other_formats"] = {"what": f"{g_rows}x{g_cols}, ring of 16 packed copies, eager launches; per format and number of "
