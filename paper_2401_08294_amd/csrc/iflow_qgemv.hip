@@ -18,7 +18,6 @@
 // (1024 + q, 64 + q, ...), and the known bias times sum(x) is removed together with the header.
 // Row sums are reduced across the wavefront with DPP, across the wavefronts of a workgroup (one per
 // strip) through LDS.
-#include <stdlib.h>
 
 #include "iflow_lane.h"
 

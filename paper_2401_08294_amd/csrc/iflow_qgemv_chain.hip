@@ -26,7 +26,6 @@
 // always ends (iflow_qgemv_chain_check reports it).
 #include "iflow_lane.h"
 
-#include <stdlib.h>
 
 #include <type_traits>
 
