@@ -202,3 +202,14 @@ def test_attention_validation_happens_before_any_launch(iflow):
     assert call(k=base * 2 + 8) == iflow.ERR_ALIGN
     assert call(ws_bytes=1000) == iflow.ERR_SIZE
     assert iflow.attn_decode_workspace_bytes(32) == 32 * 64 * 130 * 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N above 1 exits with a message and runs nothing (one GPU only)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stdout + res.stderr)
+    assert not any(line.startswith("{") for line in res.stdout.splitlines())
