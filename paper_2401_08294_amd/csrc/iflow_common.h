@@ -3,6 +3,7 @@
 #pragma once
 
 #include <mutex>
+#include <type_traits>
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -38,21 +39,36 @@ template <> struct Fmt<IFLOW_Q5_B64>  { static constexpr int kind = KIND_Q5,  bl
 template <> struct Fmt<IFLOW_Q3_B32>  { static constexpr int kind = KIND_Q3,  block = 32, L = 7,   code_bytes = 12; };
 template <> struct Fmt<IFLOW_Q2_B32>  { static constexpr int kind = KIND_Q2,  block = 32, L = 3,   code_bytes = 8; };
 
+// Host side: run fn(std::integral_constant<int, F>) for the format's compile-time tag; hipErrorInvalidValue for an unknown
+// format.  `with_q3h`: whether the 3.5-bit format is among the formats fn is instantiated for.
+template <bool with_q3h = true, typename Fn>
+inline hipError_t for_format(int format, Fn fn)
+{
+    switch (format) {
+    case IFLOW_Q8_B32: return fn(std::integral_constant<int, IFLOW_Q8_B32>{});
+    case IFLOW_Q8_B64: return fn(std::integral_constant<int, IFLOW_Q8_B64>{});
+    case IFLOW_Q4_B32: return fn(std::integral_constant<int, IFLOW_Q4_B32>{});
+    case IFLOW_Q4_B64: return fn(std::integral_constant<int, IFLOW_Q4_B64>{});
+    case IFLOW_Q3H_B64:
+        if constexpr (with_q3h) return fn(std::integral_constant<int, IFLOW_Q3H_B64>{});
+        else return hipErrorInvalidValue;
+    case IFLOW_Q6_B64: return fn(std::integral_constant<int, IFLOW_Q6_B64>{});
+    case IFLOW_Q5_B64: return fn(std::integral_constant<int, IFLOW_Q5_B64>{});
+    case IFLOW_Q3_B32: return fn(std::integral_constant<int, IFLOW_Q3_B32>{});
+    case IFLOW_Q2_B32: return fn(std::integral_constant<int, IFLOW_Q2_B32>{});
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// the same traits for a format known only at run time (host side)
 struct FormatInfo { int kind, block, L, code_bytes; };
 inline bool format_info(int f, FormatInfo *fi)
 {
-    switch (f) {
-    case IFLOW_Q8_B32:  *fi = {KIND_Q8, 32, 255, 32}; return true;
-    case IFLOW_Q8_B64:  *fi = {KIND_Q8, 64, 255, 64}; return true;
-    case IFLOW_Q4_B32:  *fi = {KIND_Q4, 32, 15, 16};  return true;
-    case IFLOW_Q4_B64:  *fi = {KIND_Q4, 64, 15, 32};  return true;
-    case IFLOW_Q3H_B64: *fi = {KIND_Q3H, 64, 10, 28}; return true;
-    case IFLOW_Q6_B64:  *fi = {KIND_Q6, 64, 63, 48};  return true;
-    case IFLOW_Q5_B64:  *fi = {KIND_Q5, 64, 31, 40};  return true;
-    case IFLOW_Q3_B32:  *fi = {KIND_Q3, 32, 7, 12};   return true;
-    case IFLOW_Q2_B32:  *fi = {KIND_Q2, 32, 3, 8};    return true;
-    default: return false;
-    }
+    return for_format(f, [&](auto tag) {
+        typedef Fmt<decltype(tag)::value> T;
+        *fi = {T::kind, T::block, T::L, T::code_bytes};
+        return hipSuccess;
+    }) == hipSuccess;
 }
 
 // ---- bit casts ----------------------------------------------------------------------------------

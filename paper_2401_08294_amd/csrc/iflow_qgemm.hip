@@ -282,18 +282,7 @@ static hipError_t gemm_one(const void *packed, int64_t rows, int64_t cols, const
 hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64_t cols,
                              const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s)
 {
-    switch (format) {
-    case IFLOW_Q8_B32: return gemm_one<IFLOW_Q8_B32>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q8_B64: return gemm_one<IFLOW_Q8_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q4_B32: return gemm_one<IFLOW_Q4_B32>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q4_B64: return gemm_one<IFLOW_Q4_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q3H_B64: return gemm_one<IFLOW_Q3H_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q6_B64: return gemm_one<IFLOW_Q6_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q5_B64: return gemm_one<IFLOW_Q5_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q3_B32: return gemm_one<IFLOW_Q3_B32>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q2_B32: return gemm_one<IFLOW_Q2_B32>(packed, rows, cols, X, batch, Y, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format(format, [&](auto f) { return gemm_one<decltype(f)::value>(packed, rows, cols, X, batch, Y, s); });
 }
 
 }  // namespace iflow

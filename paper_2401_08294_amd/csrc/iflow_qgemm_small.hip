@@ -353,18 +353,7 @@ hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int6
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s)
 {
     if (batch < 1 || batch > 16 || cols % 64 != 0) return hipErrorInvalidValue;
-    switch (format) {
-    case IFLOW_Q8_B32: return small_launch<IFLOW_Q8_B32>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q8_B64: return small_launch<IFLOW_Q8_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q4_B32: return small_launch<IFLOW_Q4_B32>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q4_B64: return small_launch<IFLOW_Q4_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q3H_B64: return small_launch<IFLOW_Q3H_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q6_B64: return small_launch<IFLOW_Q6_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q5_B64: return small_launch<IFLOW_Q5_B64>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q3_B32: return small_launch<IFLOW_Q3_B32>(packed, rows, cols, X, batch, Y, s);
-    case IFLOW_Q2_B32: return small_launch<IFLOW_Q2_B32>(packed, rows, cols, X, batch, Y, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format(format, [&](auto f) { return small_launch<decltype(f)::value>(packed, rows, cols, X, batch, Y, s); });
 }
 
 }  // namespace iflow

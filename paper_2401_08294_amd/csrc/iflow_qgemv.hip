@@ -624,18 +624,7 @@ hipError_t launch_qgemv_fused(int count, const void *const *packed, const int64_
 hipError_t launch_qgemv(int format, const void *packed, int64_t rows, int64_t cols,
                         const uint16_t *x, int64_t batch, uint16_t *y, hipStream_t s)
 {
-    switch (format) {
-    case IFLOW_Q8_B32: return gemv_batch<IFLOW_Q8_B32>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q8_B64: return gemv_batch<IFLOW_Q8_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q4_B32: return gemv_batch<IFLOW_Q4_B32>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q4_B64: return gemv_batch<IFLOW_Q4_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q3H_B64: return gemv_batch<IFLOW_Q3H_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q6_B64: return gemv_batch<IFLOW_Q6_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q5_B64: return gemv_batch<IFLOW_Q5_B64>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q3_B32: return gemv_batch<IFLOW_Q3_B32>(packed, rows, cols, x, batch, y, s);
-    case IFLOW_Q2_B32: return gemv_batch<IFLOW_Q2_B32>(packed, rows, cols, x, batch, y, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format(format, [&](auto f) { return gemv_batch<decltype(f)::value>(packed, rows, cols, x, batch, y, s); });
 }
 
 }  // namespace iflow

@@ -252,17 +252,7 @@ static hipError_t rows_batch(const RowsGroup &grp, int64_t cols, const uint16_t 
 
 static hipError_t rows_dispatch(int format, const RowsGroup &grp, int64_t cols, const uint16_t *x, int batch, hipStream_t s)
 {
-    switch (format) {
-    case IFLOW_Q8_B32: return rows_batch<IFLOW_Q8_B32>(grp, cols, x, batch, s);
-    case IFLOW_Q8_B64: return rows_batch<IFLOW_Q8_B64>(grp, cols, x, batch, s);
-    case IFLOW_Q4_B32: return rows_batch<IFLOW_Q4_B32>(grp, cols, x, batch, s);
-    case IFLOW_Q4_B64: return rows_batch<IFLOW_Q4_B64>(grp, cols, x, batch, s);
-    case IFLOW_Q6_B64: return rows_batch<IFLOW_Q6_B64>(grp, cols, x, batch, s);
-    case IFLOW_Q5_B64: return rows_batch<IFLOW_Q5_B64>(grp, cols, x, batch, s);
-    case IFLOW_Q3_B32: return rows_batch<IFLOW_Q3_B32>(grp, cols, x, batch, s);
-    case IFLOW_Q2_B32: return rows_batch<IFLOW_Q2_B32>(grp, cols, x, batch, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format<false>(format, [&](auto f) { return rows_batch<decltype(f)::value>(grp, cols, x, batch, s); });
 }
 
 // One or two activation vectors (x: [batch][cols], y: [batch][rows]), any format but IFLOW_Q3H_B64.  hipErrorNotSupported:

@@ -224,51 +224,18 @@ static hipError_t read_one(const void *packed, int64_t rows, int64_t cols, uint1
 
 hipError_t launch_quantize(int format, const float *w, int64_t rows, int64_t cols, void *packed, hipStream_t s)
 {
-    switch (format) {
-    case IFLOW_Q8_B32: return quantize_one<IFLOW_Q8_B32>(w, rows, cols, packed, s);
-    case IFLOW_Q8_B64: return quantize_one<IFLOW_Q8_B64>(w, rows, cols, packed, s);
-    case IFLOW_Q4_B32: return quantize_one<IFLOW_Q4_B32>(w, rows, cols, packed, s);
-    case IFLOW_Q4_B64: return quantize_one<IFLOW_Q4_B64>(w, rows, cols, packed, s);
-    case IFLOW_Q3H_B64: return quantize_one<IFLOW_Q3H_B64>(w, rows, cols, packed, s);
-    case IFLOW_Q6_B64: return quantize_one<IFLOW_Q6_B64>(w, rows, cols, packed, s);
-    case IFLOW_Q5_B64: return quantize_one<IFLOW_Q5_B64>(w, rows, cols, packed, s);
-    case IFLOW_Q3_B32: return quantize_one<IFLOW_Q3_B32>(w, rows, cols, packed, s);
-    case IFLOW_Q2_B32: return quantize_one<IFLOW_Q2_B32>(w, rows, cols, packed, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format(format, [&](auto f) { return quantize_one<decltype(f)::value>(w, rows, cols, packed, s); });
 }
 
 hipError_t launch_dequant(int format, const void *packed, int64_t rows, int64_t cols, uint16_t *w16, hipStream_t s)
 {
-    switch (format) {
-    case IFLOW_Q8_B32: return read_one<IFLOW_Q8_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q8_B64: return read_one<IFLOW_Q8_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q4_B32: return read_one<IFLOW_Q4_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q4_B64: return read_one<IFLOW_Q4_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q3H_B64: return read_one<IFLOW_Q3H_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q6_B64: return read_one<IFLOW_Q6_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q5_B64: return read_one<IFLOW_Q5_B64, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q3_B32: return read_one<IFLOW_Q3_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    case IFLOW_Q2_B32: return read_one<IFLOW_Q2_B32, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format(format, [&](auto f) { return read_one<decltype(f)::value, false>(packed, rows, cols, w16, nullptr, nullptr, nullptr, s); });
 }
 
 hipError_t launch_unpack(int format, const void *packed, int64_t rows, int64_t cols,
                          uint8_t *levels, uint16_t *scale16, uint16_t *offset16, hipStream_t s)
 {
-    switch (format) {
-    case IFLOW_Q8_B32: return read_one<IFLOW_Q8_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q8_B64: return read_one<IFLOW_Q8_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q4_B32: return read_one<IFLOW_Q4_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q4_B64: return read_one<IFLOW_Q4_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q3H_B64: return read_one<IFLOW_Q3H_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q6_B64: return read_one<IFLOW_Q6_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q5_B64: return read_one<IFLOW_Q5_B64, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q3_B32: return read_one<IFLOW_Q3_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    case IFLOW_Q2_B32: return read_one<IFLOW_Q2_B32, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s);
-    default: return hipErrorInvalidValue;
-    }
+    return for_format(format, [&](auto f) { return read_one<decltype(f)::value, true>(packed, rows, cols, nullptr, levels, scale16, offset16, s); });
 }
 
 }  // namespace iflow
