@@ -581,3 +581,55 @@ def test_gqa_decode_matches_the_library_routine_and_special_cases():
     vb = rng.standard_normal((1, 5, d)).astype(np.float16)
     sat = att.gqa_decode(_bits(qb), _bits(kb), _bits(vb), 5, 1.0)
     assert np.all(np.isfinite(sat)) and np.max(np.abs(sat[0] - vb[0, 3].astype(np.float64))) < 1e-12
+
+
+# ---- rotary position embedding (oracle/rope.py): pinned to complex multiplication and to the properties that define it ----
+def test_rope_is_a_complex_rotation_with_the_published_properties():
+    from oracle import rope as R
+    rng = np.random.default_rng(90)
+    d, base = 128, 10000.0
+    x = rng.standard_normal((5, d))
+    # (1) position 0 is the identity, in both pairings
+    for mode in (R.ADJACENT, R.HALVES):
+        assert np.array_equal(R.rotate_fp64(x, 0, base, mode), x)
+    # (2) the pair (a, b) as the complex number a + ib is multiplied by exp(i p base^(-2i/d)) - numpy's complex exponential
+    for p in (1, 7, 1000, 123457):
+        z = (x[:, 0::2] + 1j * x[:, 1::2]) * np.exp(1j * p * base ** (-2.0 * np.arange(d // 2) / d))
+        got = R.rotate_fp64(x, p, base, R.ADJACENT)
+        assert np.max(np.abs(got[:, 0::2] - z.real)) < 1e-9 and np.max(np.abs(got[:, 1::2] - z.imag)) < 1e-9
+    # (3) the first pair turns by p radians (frequency 1), the last one by p * base^(-(d-2)/d)
+    e = np.zeros(d); e[0] = 1.0
+    r = R.rotate_fp64(e, 3, base, R.ADJACENT)
+    assert abs(r[0] - np.cos(3.0)) < 1e-15 and abs(r[1] - np.sin(3.0)) < 1e-15 and not r[2:].any()
+    e = np.zeros(d); e[d - 2] = 1.0
+    r = R.rotate_fp64(e, 5, base, R.ADJACENT)
+    assert abs(r[d - 2] - np.cos(5.0 * base ** (-(d - 2) / d))) < 1e-15
+    # (4) rotations compose: position p1 then p2 is position p1 + p2; every pair keeps its length
+    a = R.rotate_fp64(R.rotate_fp64(x, 11, base, R.ADJACENT), 30, base, R.ADJACENT)
+    assert np.max(np.abs(a - R.rotate_fp64(x, 41, base, R.ADJACENT))) < 1e-12
+    r = R.rotate_fp64(x, 999, base, R.ADJACENT)
+    assert np.max(np.abs(r[:, 0::2] ** 2 + r[:, 1::2] ** 2 - x[:, 0::2] ** 2 - x[:, 1::2] ** 2)) < 1e-12
+    # (5) what it is for: the score of a rotated query and a rotated key depends on the distance of their positions only
+    q, k = rng.standard_normal(d), rng.standard_normal(d)
+    s1 = R.rotate_fp64(q, 100, base, R.ADJACENT) @ R.rotate_fp64(k, 90, base, R.ADJACENT)
+    s2 = R.rotate_fp64(q, 4010, base, R.ADJACENT) @ R.rotate_fp64(k, 4000, base, R.ADJACENT)
+    assert abs(s1 - s2) < 1e-9
+    # (6) the two pairings are the same rotation on permuted components: (2i, 2i+1) <-> (i, i + d/2)
+    perm = np.concatenate([np.arange(0, d, 2), np.arange(1, d, 2)])        # adjacent order -> halves order
+    h = R.rotate_fp64(x[:, perm], 77, base, R.HALVES)
+    assert np.max(np.abs(h - R.rotate_fp64(x, 77, base, R.ADJACENT)[:, perm])) < 1e-15
+    # (7) the step: queries come back rotated, row `position` of the caches receives the rotated keys and the plain values,
+    #     every other row is left alone
+    n_heads, n_kv, max_seq, pos = 4, 2, 6, 3
+    q16 = _bits(rng.standard_normal((n_heads, d))); k16 = _bits(rng.standard_normal((n_kv, d))); v16 = _bits(rng.standard_normal((n_kv, d)))
+    kc = _bits(rng.standard_normal((n_kv, max_seq, d))).copy(); vc = _bits(rng.standard_normal((n_kv, max_seq, d))).copy()
+    kc0, vc0 = kc.copy(), vc.copy()
+    qr = R.rope_append(q16, k16, v16, pos, base, R.HALVES, kc, vc)
+    assert np.array_equal(qr, R.rope(q16, pos, base, R.HALVES)) and np.array_equal(kc[:, pos], R.rope(k16, pos, base, R.HALVES))
+    assert np.array_equal(vc[:, pos], v16)
+    keep = np.arange(max_seq) != pos
+    assert np.array_equal(kc[:, keep], kc0[:, keep]) and np.array_equal(vc[:, keep], vc0[:, keep])
+    # stored values are the exact rotation rounded once: within half an fp16 step of it
+    exact = R.rotate_fp64(q16.view(np.float16).astype(np.float64), pos, base, R.HALVES)
+    got = qr.view(np.float16).astype(np.float64)
+    assert np.all(np.abs(got - exact) <= np.maximum(np.abs(exact), 2.0 ** -14) * 2.0 ** -11)
