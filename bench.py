@@ -386,6 +386,8 @@ def main():
                     m = ring[layer]
                     iflow.qgemv_fused(fmt, [m[i][2] for i in (0, 1, 2)], [m[i][0] for i in (0, 1, 2)], m[0][1], hs, [ys[0], ys[1], ys[2]],
                                       iflow.X_RMS_GAIN, gn[0], 1e-5, stream=raw)
+                    iflow.rope_append(ys[0], ys[1], ys[2], 32, 32, 128, ctx - 1, ctx, 10000.0, iflow.ROPE_HALVES, kvs[layer][0], kvs[layer][1],
+                                      stream=raw)
                     iflow.attn_decode(ys[0], kvs[layer][0], kvs[layer][1], 32, 32, 128, ctx, ctx, 128 ** -0.5, ao, aws2, awb2, stream=raw)
                     iflow.qgemv_fused(fmt, [m[3][2]], [m[3][0]], m[3][1], ao, [hs], residual_list=[hs], stream=raw)
                     iflow.qgemv_fused(fmt, [m[4][2], m[5][2]], [m[4][0], m[5][0]], m[4][1], hs, [ys[4], ys[5]], iflow.X_RMS_GAIN, gn[1], 1e-5, stream=raw)
@@ -407,8 +409,9 @@ def main():
                 t1.synchronize()
                 us_layer = t0.elapsed_time(t1) * 1e3 / (20 * args.ring)
                 other["decode_step_with_attention"] = {
-                    "what": "per decoder layer: rms-norm + q,k,v | attention over 1024 cached positions (32 heads) | o + residual | rms-norm + "
-                            "gate,up | silu(gate)*up + down + residual: 4 fused launches + attention, HIP-graph replay over the ring",
+                    "what": "per decoder layer: rms-norm + q,k,v | rotary embedding + cache append | attention over 1024 cached positions "
+                            "(32 heads) | o + residual | rms-norm + gate,up | silu(gate)*up + down + residual: 4 fused launches + rope_append "
+                            "+ attention, HIP-graph replay over the ring",
                     "us_per_layer": round(us_layer, 2), "weight_GB/s": round(step_bytes / us_layer / 1e3, 1),
                     "tokens_per_s_32_layers": round(1e6 / (32 * us_layer), 1)}
                 del kvs

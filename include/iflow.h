@@ -198,6 +198,23 @@ iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, con
                                  int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
                                  uint16_t *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Rotary position embedding for one decode step, and the step's append to the key/value cache (Section 2's table of
+ * configurable modules: position_embedding = "rope"): the launch that sits between the q/k/v projections and
+ * iflow_attn_decode.  Pair i (0..63) of a head's 128 components at position p is rotated by the angle p * base^(-2i/128):
+ * (a, b) -> (a cos - b sin, a sin + b cos); IFLOW_ROPE_ADJACENT pairs components (2i, 2i+1), IFLOW_ROPE_HALVES pairs
+ * (i, i + 64).
+ *   q        [n_heads][128] fp16: rotated IN PLACE
+ *   k_new    [n_kv_heads][128] fp16, this step's keys (unrotated); v_new likewise, this step's values
+ *   k_cache  [n_kv_heads][max_seq][128] fp16: row `position` of every head receives the rotated keys;
+ *   v_cache  likewise: row `position` receives v_new unchanged.  No other row is touched.
+ *   0 <= position < max_seq <= 2^20; head_dim must be 128; base > 1 (10000 for the LLaMA family).
+ * Angles, sines, cosines and the rotation are computed in fp64 and rounded to fp16 once, so that positions in the
+ * hundreds of thousands are as exact as position 1.  All pointers are device pointers, 16-byte aligned. */
+typedef enum { IFLOW_ROPE_ADJACENT = 0, IFLOW_ROPE_HALVES = 1 } iflow_rope_pairing_t;
+iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads,
+                                 int head_dim, int64_t position, int64_t max_seq, float base, iflow_rope_pairing_t pair_mode,
+                                 uint16_t *k_cache, uint16_t *v_cache, void *stream);
+
 /* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
  * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].
  *   X [batch][cols] fp16, Y [batch][rows] fp16, both device.

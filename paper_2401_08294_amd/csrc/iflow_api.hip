@@ -219,6 +219,21 @@ iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, con
                                                    (hipStream_t)stream));
 }
 
+iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads,
+                                 int head_dim, int64_t position, int64_t max_seq, float base, iflow_rope_pairing_t pair_mode,
+                                 uint16_t *k_cache, uint16_t *v_cache, void *stream)
+{
+    if (head_dim != 128) return IFLOW_ERR_SHAPE;
+    if (n_heads < 1 || n_heads > 65536 || n_kv_heads < 1 || n_kv_heads > 65536) return IFLOW_ERR_SHAPE;
+    if (position < 0 || position >= max_seq || max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
+    if (!(base > 1.0f && base < 3.0e38f)) return IFLOW_ERR_SHAPE;
+    if (pair_mode != IFLOW_ROPE_ADJACENT && pair_mode != IFLOW_ROPE_HALVES) return IFLOW_ERR_SHAPE;
+    if (!q || !k_new || !v_new || !k_cache || !v_cache) return IFLOW_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_rope_append(q, k_new, v_new, n_heads, n_kv_heads, position, max_seq, (double)base, (int)pair_mode,
+                                                   k_cache, v_cache, (hipStream_t)stream));
+}
+
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes)
 {
     if (!rows || !bytes) return IFLOW_ERR_NULL;

@@ -63,6 +63,7 @@ def lib():
                                         C.POINTER(p), C.POINTER(p), p]
         L.iflow_attn_decode_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
         L.iflow_attn_decode.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p, sz, p]
+        L.iflow_rope_append.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, C.c_int, p, p, p]
         L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
         L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
                                         C.POINTER(i64), C.POINTER(p), p, sz, p]
@@ -154,6 +155,7 @@ def qgemv_multi(fmt: int, packed_list, rows_list, cols: int, x, y_list, stream=N
 
 
 X_PLAIN, X_RMS_GAIN, X_SILU_MUL = 0, 1, 2
+ROPE_ADJACENT, ROPE_HALVES = 0, 1
 
 
 def qgemv_fused(fmt: int, packed_list, rows_list, cols: int, x, y_list, x_op: int = X_PLAIN, aux=None, eps: float = 0.0,
@@ -182,6 +184,14 @@ def attn_decode(q, k_cache, v_cache, n_heads: int, n_kv_heads: int, head_dim: in
     """One decode step of grouped-query attention over an fp16 key/value cache [n_kv_heads][max_seq][head_dim]."""
     _check(lib().iflow_attn_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), n_heads, n_kv_heads, head_dim, seq_len, max_seq, scale,
                                    _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)), "iflow_attn_decode")
+
+
+def rope_append(q, k_new, v_new, n_heads: int, n_kv_heads: int, head_dim: int, position: int, max_seq: int, base: float,
+                pair_mode: int, k_cache, v_cache, stream=None) -> None:
+    """Rotary position embedding of one decode step: q rotated in place, rotated k_new and v_new written to row `position`
+    of the caches [n_kv_heads][max_seq][head_dim]."""
+    _check(lib().iflow_rope_append(_ptr(q), _ptr(k_new), _ptr(v_new), n_heads, n_kv_heads, head_dim, position, max_seq, base,
+                                   pair_mode, _ptr(k_cache), _ptr(v_cache), _stream(stream)), "iflow_rope_append")
 
 
 def qgemv_chain_workspace_bytes(rows_list) -> int:

@@ -204,6 +204,23 @@ def test_attention_validation_happens_before_any_launch(iflow):
     assert iflow.attn_decode_workspace_bytes(32) == 32 * 64 * 130 * 4
 
 
+def test_rope_validation_happens_before_any_launch(iflow):
+    L = iflow.lib()
+    base = 0x100000
+
+    def call(n_heads=32, n_kv=8, d=128, pos=5, max_seq=64, theta=10000.0, mode=0, q=base, k=base * 2, v=base * 3, kc=base * 4, vc=base * 5):
+        return L.iflow_rope_append(q, k, v, n_heads, n_kv, d, pos, max_seq, C.c_float(theta), mode, kc, vc, None)
+
+    assert call(d=64) == iflow.ERR_SHAPE                                         # head dimension 128 only
+    assert call(n_heads=0) == iflow.ERR_SHAPE and call(n_kv=0) == iflow.ERR_SHAPE
+    assert call(pos=-1) == iflow.ERR_SHAPE and call(pos=64) == iflow.ERR_SHAPE   # the row must exist
+    assert call(max_seq=(1 << 20) + 1, pos=0) == iflow.ERR_SHAPE
+    assert call(theta=1.0) == iflow.ERR_SHAPE and call(theta=float("nan")) == iflow.ERR_SHAPE
+    assert call(mode=2) == iflow.ERR_SHAPE
+    assert call(q=None) == iflow.ERR_NULL and call(vc=None) == iflow.ERR_NULL
+    assert call(k=base * 2 + 2) == iflow.ERR_ALIGN
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py --gpus N with N above 1 exits with a message and runs nothing (one GPU only)."""
     import subprocess
