@@ -221,6 +221,21 @@ def test_rope_validation_happens_before_any_launch(iflow):
     assert call(k=base * 2 + 2) == iflow.ERR_ALIGN
 
 
+def test_public_header_is_plain_c_and_cpp(tmp_path):
+    """include/iflow.h is the boundary: it has to compile on its own as C99 and as C++11 (no HIP, no torch types)."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "iflow.h"\nint main(void) { return (int)IFLOW_Q2_B32 + (int)IFLOW_ROPE_HALVES + (int)IFLOW_X_SILU_MUL; }\n')
+    inc = os.path.join(root, "include")
+    for cc, flags in (("gcc", ["-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror"]), ("g++", ["-x", "c++", "-std=c++11", "-pedantic", "-Wall", "-Werror"])):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not installed")
+        res = subprocess.run([cc] + flags + ["-I", inc, "-fsyntax-only", str(src)], capture_output=True, text=True, timeout=120)
+        assert res.returncode == 0, res.stderr
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py --gpus N with N above 1 exits with a message and runs nothing (one GPU only)."""
     import subprocess
