@@ -336,11 +336,12 @@ def test_exact_ties_round_half_away(gpu, orc):
 
 
 def test_outliers_config3_shape_slice(gpu, orc):
-    """Config 3's value recipe (0.1 % of entries scaled by 10) on a slice of a 7B-shaped layer, batches 1..4."""
+    """Config 3's value recipe (0.1 % of entries scaled by 10) on a slice of a 7B-shaped layer, in the 8-bit, 4-bit and 3.5-bit
+    formats at the configuration's batch sizes 1, 2, 4, 8 and 16."""
     torch, iflow = gpu
     w = synth.weights(256, 11008, 0.02, synth.BASE_SEED + 3, outlier_prob=0.001)
     for name in ("Q3H_B64", "Q4_B64", "Q8_B64"):
-        for batch in (1, 4):
+        for batch in (1, 2, 4, 8, 16):
             x = synth.activations(batch, 11008, synth.BASE_SEED + 33 + batch)
             check_all(torch, iflow, orc, name, w, x, "config3-slice")
 
