@@ -221,7 +221,9 @@ iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint1
  * One backend, chosen by batch: 1 is iflow_qgemv; 2 (8-bit formats: up to 4) runs on the vector units with the
  * activation vectors side by side; up to 31 the weights stream once per sixteen vectors and the multiply runs on the
  * matrix cores (16x16x16 tiles, weights dequantized in registers); from 32 on (and cols a multiple of 64) 128 x 64
- * output tiles run on the matrix cores from dequantized fp16 tiles in LDS.  Results of one call do not depend on
+ * output tiles run on the matrix cores from dequantized fp16 tiles in LDS - or, up to 256 vectors, further passes of
+ * sixteen where a cost model of the two says those are cheaper (few vectors against long rows).  Which kernel runs
+ * depends on the shapes, the format and the device only.  Results of one call do not depend on
  * how busy the device is (all sums are taken in a fixed order). */
 iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                            const uint16_t *X, int64_t batch, uint16_t *Y, void *stream);

@@ -11,6 +11,24 @@ constexpr int64_t IFLOW_SMALL_MFMA_MIN_BATCH = 3, IFLOW_SMALL_MFMA_MIN_BATCH_Q8 
 
 thread_local int g_last_hip_error = 0;
 
+// From 32 vectors on there are two ways to run a product: the dense kernel (a workgroup per 64 weight rows and 64 or 128
+// vectors walks the whole reduction length, about 0.39 / 0.53 us per 64 columns; the part runs one such workgroup per compute
+// unit at full speed) or passes of sixteen vectors through the streaming MFMA kernel (about 2.5 us per pass plus the packed
+// bytes at 2.6 TB/s, a third slower when a row spans several 4096-column strips).  With few vectors and long rows the dense
+// kernel leaves most of the part idle for a long time - 4096 x 11008 at 32 vectors: 63 us against 28 us in two passes - so
+// the cheaper of the two is taken, by this model of them (constants measured on 7B shapes; the choice depends on shapes,
+// format and the number of compute units only, so a call always takes the same path on the same device).
+bool passes_beat_dense(const iflow::FormatInfo &fi, int64_t rows, int64_t cols, int64_t batch, int cus)
+{
+    const double packed = (double)rows * (double)(cols / fi.block) * (fi.code_bytes + 4);
+    const double pass_us = 2.5 + packed / 2.6e6 * (cols > 4096 ? 1.35 : 1.0);
+    const double passes_us = (double)((batch + 15) / 16) * pass_us;
+    const int64_t bm = batch <= 64 ? 64 : 128;
+    const double wgs = (double)((rows + 63) / 64) * (double)((batch + bm - 1) / bm);
+    const double dense_us = (double)(cols / 64) * (batch <= 64 ? 0.39 : 0.53) * (wgs > cus ? wgs / cus : 1.0);
+    return passes_us < dense_us;
+}
+
 iflow_status_t device_status(hipError_t e)
 {
     if (e == hipSuccess) return IFLOW_OK;
@@ -126,10 +144,18 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
     if (!aligned16(packed) || !aligned16(X) || !aligned16(Y)) return IFLOW_ERR_ALIGN;
     // One backend, three kernels chosen by batch: a few activation vectors ride along with the weight stream on the
     // vector units; up to 31 vectors the weights stream once per 16 vectors through 16x16x16 MFMAs; from 32 vectors
-    // on the product is a dense contraction on LDS tiles (64-column chunks).  Column counts that are not a multiple
+    // on the product is a dense contraction on LDS tiles (64-column chunks), unless passes of the streaming kernel are
+    // cheaper (few vectors, long rows: see passes_beat_dense).  Column counts that are not a multiple
     // of 64 (possible with the 32-wide blocks) stay on the vector kernel, four vectors per pass.
     hipStream_t hs = (hipStream_t)stream;
-    if (batch >= 32 && cols % 64 == 0)
+    bool dense = batch >= 32 && cols % 64 == 0;
+    if (dense && batch <= 256) {                              // (beyond that the dense kernel always wins)
+        int cus = 0;
+        const hipError_t e = iflow::device_compute_units(&cus);
+        if (e != hipSuccess) return device_status(e);
+        dense = !passes_beat_dense(fi, rows, cols, batch, cus);
+    }
+    if (dense)
         return device_status(iflow::launch_qgemm_mfma((int)format, packed, rows, cols, X, batch, Y, hs));
     if (cols % 64 == 0 && batch >= (format == IFLOW_Q8_B32 || format == IFLOW_Q8_B64 ? IFLOW_SMALL_MFMA_MIN_BATCH_Q8 : IFLOW_SMALL_MFMA_MIN_BATCH)) {
         for (int64_t b0 = 0; b0 < batch; b0 += 16) {

@@ -190,6 +190,13 @@ inline hipError_t once_per_device(PerDevice &pd, int *cus, Prepare prepare)
     return hipSuccess;
 }
 
+// the current device's compute-unit count (looked up once per device)
+inline hipError_t device_compute_units(int *cus)
+{
+    static PerDevice pd;
+    return once_per_device(pd, cus, [] { return hipSuccess; });
+}
+
 // ---- host-side launchers, one per translation unit ------------------------------------------------
 hipError_t launch_quantize(int format, const float *w, int64_t rows, int64_t cols, void *packed, hipStream_t s);
 hipError_t launch_dequant(int format, const void *packed, int64_t rows, int64_t cols, uint16_t *w16, hipStream_t s);
