@@ -190,7 +190,7 @@ def main():
         launch_count[0] += 1
 
     if args.fused:
-        assert args.launches == 4 and args.format == "Q3H_B64", "--fused goes with --launches 4 and the 3.5-bit format"
+        assert args.launches == 4, "--fused goes with --launches 4"
         hidden_state = xs[shapes[0][2]].clone()               # the residual stream, updated in place by the o and down launches
         gains = [(1.0 + 0.1 * torch.randn((shapes[0][2],), generator=gen, device=dev, dtype=torch.float32)).to(torch.float16) for _ in range(2)]
         attn_out = torch.empty_like(ys[0])

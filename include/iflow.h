@@ -127,8 +127,9 @@ iflow_status_t iflow_qgemv(iflow_format_t format, const void *packed, int64_t ro
 iflow_status_t iflow_qgemv_multi(iflow_format_t format, int count, const void *const *packed, const int64_t *rows,
                                  int64_t cols, const uint16_t *x, uint16_t *const *y, void *stream);
 
-/* iflow_qgemv_multi with the modules around the linear layer fused into the same launch (3.5-bit format only; other
- * formats: IFLOW_ERR_FORMAT).  Section 2 lists the normalization and activation functions among the configurable
+/* iflow_qgemv_multi with the modules around the linear layer fused into the same launch (every format; for the formats
+ * other than the 3.5-bit one the activations of a whole row must fit in LDS: rows longer than 63488 columns, 58368 for
+ * the 8-bit formats, are IFLOW_ERR_SHAPE).  Section 2 lists the normalization and activation functions among the configurable
  * modules of a decoder layer ("rms" and "silu" for the LLaMA family) and Section 5's Infer() applies them between
  * the products; fused, the small kernels between the matrix products of a decode step disappear.
  *   x_op = IFLOW_X_PLAIN:     y_i = W'_i x (+ residual_i)

@@ -191,7 +191,6 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
 {
     iflow::FormatInfo fi;
     if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
-    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;
     if (count < 1 || count > 8) return IFLOW_ERR_SHAPE;
     if (x_op != IFLOW_X_PLAIN && x_op != IFLOW_X_RMS_GAIN && x_op != IFLOW_X_SILU_MUL) return IFLOW_ERR_SHAPE;
     if (!packed || !rows || !x || !y) return IFLOW_ERR_NULL;
@@ -216,6 +215,11 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
             for (int j = 0; j < count; ++j)
                 if (j != i && y[j] && overlaps(residual[i], rows[i] * 2, y[j], rows[j] * 2)) return IFLOW_ERR_SHAPE;
         }
+    }
+    if (format != IFLOW_Q3H_B64) {
+        const hipError_t e = iflow::launch_qgemv_rows_fused((int)format, count, packed, rows, cols, x, (int)x_op, aux, eps, residual, y,
+                                                            (hipStream_t)stream);
+        return e == hipErrorNotSupported ? IFLOW_ERR_SHAPE : device_status(e);   // (rows too long for the staged activations)
     }
     return device_status(iflow::launch_qgemv_fused(count, packed, rows, cols, x, (int)x_op, aux, eps, residual, y, (hipStream_t)stream));
 }

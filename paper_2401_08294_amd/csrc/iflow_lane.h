@@ -64,16 +64,12 @@ __device__ __forceinline__ void plane_word_dot(uint32_t d, const XRegs<KIND> (&x
     }
 }
 
+// A lane's activations (n: its WPL values as fp16 pairs in natural order) into the order the format's decode wants, plus the
+// two sums that undo the decode's bias.
 template <int KIND>
-__device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restrict__ x, int k0)
+__device__ __forceinline__ void arrange_x(XRegs<KIND> &xr, const uint32_t (&n)[Geo<KIND>::XD])
 {
     constexpr int XD = Geo<KIND>::XD;
-    uint32_t n[XD];
-#pragma unroll
-    for (int j = 0; j < XD / 4; ++j) {
-        uint4 q = reinterpret_cast<const uint4 *>(x + k0)[j];
-        n[4 * j] = q.x; n[4 * j + 1] = q.y; n[4 * j + 2] = q.z; n[4 * j + 3] = q.w;
-    }
     const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
     if constexpr (KIND == KIND_Q3H) {
         // decode slot m works on weights 4m..4m+3 and produces (q[4m], q[4m+2]) and (q[4m+1], q[4m+3]):
@@ -120,6 +116,19 @@ __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restri
         xr.bias_sum = 1024.0f * sx;
         xr.x_sum = sx;
     }
+}
+
+template <int KIND>
+__device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restrict__ x, int k0)
+{
+    constexpr int XD = Geo<KIND>::XD;
+    uint32_t n[XD];
+#pragma unroll
+    for (int j = 0; j < XD / 4; ++j) {
+        uint4 q = reinterpret_cast<const uint4 *>(x + k0)[j];
+        n[4 * j] = q.x; n[4 * j + 1] = q.y; n[4 * j + 2] = q.z; n[4 * j + 3] = q.w;
+    }
+    arrange_x<KIND>(xr, n);
 }
 
 // Weights of one lane for one row: WD dwords of codes and the block header (scale | offset << 16).

@@ -37,12 +37,27 @@ struct RowsGroup {
     int count;
 };
 
-template <int F, int U, int NB, bool MULTI>
-__global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
-                                                        uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips,
-                                                        int groups /* of U rows per wavefront */, const RowsGroup grp)
+// What the fused variant (XOP >= 0, an iflow_x_op_t; one vector only) does besides the product - the modules Section 2
+// lists around a decoder layer's linear layers, folded into the launch:
+//   IFLOW_X_RMS_GAIN   the staged activations are fp16(x_k g_k) and every row sum is multiplied by
+//                      1 / sqrt(mean x^2 + eps): rms normalization with its scalar moved behind the product;
+//   IFLOW_X_SILU_MUL   the staged activations are fp16(silu(x_k) aux_k): the input of a gated feed-forward's last layer;
+//   residual           out_n = fp16(row sum x scale + residual_n), per matrix, or none.
+// (The same arithmetic, in the same order, as the 3.5-bit kernel's fused variant.)
+struct RowsOps {
+    const uint16_t *residual[ROWS_MAX_GROUP];
+    const uint16_t *aux;
+    float eps;
+};
+
+template <int F, int U, int NB, bool MULTI, int XOP>
+__device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
+                                               uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips, int groups,
+                                               const RowsGroup &grp, const RowsOps &ops)
 {
     typedef Fmt<F> T;
+    constexpr bool OPS = XOP >= 0;
+    static_assert(!OPS || NB == 1, "the fused variant is built for one activation vector");
     int mi = 0;                                                // which matrix this workgroup belongs to
     if (MULTI) {
 #pragma unroll
@@ -63,13 +78,40 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), waves = blockDim.x >> 6;
 
     // ---- stage the activations: item (strip, lane) -> converted registers -> LDS ----------------------------------
+    float ssq = 0.f;                                          // (rms) this thread's share of sum x^2
     for (int item = tid; item < NB * nstrips * 64; item += blockDim.x) {      // slot (strip t, vector b) = t * NB + b
         const int tb = item >> 6, l = item & 63;
         const int t = tb / NB, b = tb - t * NB;
         const int k0 = (t * 64 + l) * G::WPL;
         XRegs<KIND> xr;
         if (k0 < cols) {
-            load_x<KIND>(xr, X + (int64_t)b * cols, k0);
+            if constexpr (XOP > IFLOW_X_PLAIN) {
+                uint32_t n[G::XD], av[G::XD];
+#pragma unroll
+                for (int j = 0; j < G::XD / 4; ++j) {
+                    const uint4 q = reinterpret_cast<const uint4 *>(X + k0)[j], a = reinterpret_cast<const uint4 *>(ops.aux + k0)[j];
+                    n[4 * j] = q.x; n[4 * j + 1] = q.y; n[4 * j + 2] = q.z; n[4 * j + 3] = q.w;
+                    av[4 * j] = a.x; av[4 * j + 1] = a.y; av[4 * j + 2] = a.z; av[4 * j + 3] = a.w;
+                }
+#pragma unroll
+                for (int j = 0; j < G::XD; ++j) {
+                    if constexpr (XOP == IFLOW_X_RMS_GAIN) {  // x_k g_k: exact product, one rounding to fp16
+                        ssq = dot2(as_h2(n[j]), as_h2(n[j]), ssq);
+                        n[j] = as_u32(as_h2(n[j]) * as_h2(av[j]));
+                    } else {                                  // silu(x_k) aux_k in fp32, one rounding to fp16
+                        const half2_t xa = as_h2(n[j]), xb = as_h2(av[j]);
+                        const float g0 = (float)xa.x, g1 = (float)xa.y;
+                        // (hardware reciprocal: 1 ulp of fp32, far below the fp16 rounding that follows)
+                        const float v0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * (float)xb.x;
+                        const float v1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * (float)xb.y;
+                        const half2_t r = {(half_t)v0, (half_t)v1};
+                        n[j] = as_u32(r);
+                    }
+                }
+                arrange_x<KIND>(xr, n);
+            } else {
+                load_x<KIND>(xr, X + (int64_t)b * cols, k0);
+            }
         } else {                                              // past the end of the last strip: contributes nothing
 #pragma unroll
             for (int j = 0; j < G::XD; ++j) xr.v[j] = as_h2(0u);
@@ -155,7 +197,25 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
         step_row(0, r0, t);
         load_step(wa, r0, t);                                 // the first weights are on their way before the barrier
     }
+    // fused variant: lane l holds the residual of the wavefront's l-th row (in bounds whatever the row; read before any
+    // of these rows is stored, so the residual may be the output vector itself)
+    float res = 0.f, out_scale = 1.0f;
+    if constexpr (OPS) {
+        const uint16_t *rp = ops.residual[mi];               // (no residual: x[0], dropped - the load is under no branch)
+        const uint16_t raw = *(rp != nullptr ? rp + min(rbase + min(lane, groups * U - 1), rows - 1) : X);
+        res = rp != nullptr ? (float)as_h(raw) : 0.f;
+    }
+    float *ssq_part = reinterpret_cast<float *>(lds + (size_t)NB * nstrips * RG::SLOT);     // sixteen floats behind the strips
+    if constexpr (XOP == IFLOW_X_RMS_GAIN) {
+        const float wsum = wave_sum_to_lane63(ssq);
+        if (lane == 63) ssq_part[wave] = wsum;
+    }
     __syncthreads();
+    if constexpr (XOP == IFLOW_X_RMS_GAIN) {
+        const float mine = lane < waves ? ssq_part[lane] : 0.f;
+        const float total = wave_sum(mine);
+        out_scale = 1.0f / __builtin_sqrtf(total / (float)cols + ops.eps);
+    }
 
     auto compute_step = [&](const WRegs<KIND>(&w)[U], int k) {
         int r0, t;
@@ -184,7 +244,11 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
         if (t == nstrips - 1) {                               // the rows end here: reduce, store, start over
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const float r = reduce_rows<U>(acc[b], lane);
+                float r = reduce_rows<U>(acc[b], lane);
+                if constexpr (OPS) {                          // lane u < U holds row r0 + u, the wavefront's row (r0 - rbase) + u
+                    const float rr = __shfl(res, (r0 - rbase) + (lane & (U - 1)));
+                    r = __builtin_fmaf(r, out_scale, rr);
+                }
                 if (lane < U && r0 + lane < rows) Y[(int64_t)b * rows + r0 + lane] = as_u16((half_t)r);
 #pragma unroll
                 for (int u = 0; u < U; ++u) acc[b][u] = 0.f;
@@ -205,20 +269,38 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
 }
 
 template <int F, int U, int NB, bool MULTI>
-static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hipStream_t s)
+__global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
+                                                        uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips,
+                                                        int groups /* of U rows per wavefront */, const RowsGroup grp)
+{
+    gemv_rows_body<F, U, NB, MULTI, -1>(packed0, X, y0, rows0, cols, nbk, nstrips, groups, grp, RowsOps{});
+}
+
+template <int F, int U, bool MULTI, int XOP>
+__global__ __launch_bounds__(512) void gemv_rows_fused_kernel(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
+                                                              uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips,
+                                                              int groups, const RowsGroup grp, const RowsOps ops)
+{
+    gemv_rows_body<F, U, 1, MULTI, XOP>(packed0, X, y0, rows0, cols, nbk, nstrips, groups, grp, ops);
+}
+
+template <int F, int U, int NB, bool MULTI, int XOP = -1>
+static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hipStream_t s, const RowsOps &ops = RowsOps{})
 {
     typedef Fmt<F> T;
     typedef Geo<T::kind> G;
     typedef RowsGeo<T::kind> RG;
     const int nbk = (int)(cols / T::block);
     const int nstrips = (int)((cols + 64 * G::WPL - 1) / (64 * G::WPL));
-    const size_t lds = (size_t)NB * nstrips * RG::SLOT;
+    const size_t lds = (size_t)NB * nstrips * RG::SLOT + (XOP >= 0 ? 64 : 0);
     if (lds > (size_t)ROWS_LDS_LIMIT) return hipErrorNotSupported;
     static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<F, U, NB, MULTI>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   ROWS_LDS_LIMIT);
+        const void *fn;
+        if constexpr (XOP >= 0) fn = reinterpret_cast<const void *>(gemv_rows_fused_kernel<F, U, MULTI, XOP>);
+        else fn = reinterpret_cast<const void *>(gemv_rows_kernel<F, U, NB, MULTI>);
+        return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ROWS_LDS_LIMIT);
     });
     if (e != hipSuccess) return e;
     int64_t rows = 0;
@@ -238,8 +320,12 @@ static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hi
         grp.wg_end[i] = (int)grid;
     }
     if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemv_rows_kernel<F, U, NB, MULTI>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x, grp.y[0],
-                       grp.rows[0], (int)cols, nbk, nstrips, groups, grp);
+    if constexpr (XOP >= 0)
+        hipLaunchKernelGGL((gemv_rows_fused_kernel<F, U, MULTI, XOP>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x,
+                           grp.y[0], grp.rows[0], (int)cols, nbk, nstrips, groups, grp, ops);
+    else
+        hipLaunchKernelGGL((gemv_rows_kernel<F, U, NB, MULTI>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x, grp.y[0],
+                           grp.rows[0], (int)cols, nbk, nstrips, groups, grp);
     return hipGetLastError();
 }
 
@@ -279,6 +365,40 @@ hipError_t launch_qgemv_rows_multi(int format, int count, const void *const *pac
     }
     grp.count = count;
     return rows_dispatch(format, grp, cols, x, 1, s);
+}
+
+template <int F, int XOP>
+static hipError_t rows_fused_count(const RowsGroup &grp, int64_t cols, const uint16_t *x, const RowsOps &ops, hipStream_t s)
+{
+    return grp.count > 1 ? rows_launch<F, 2, 1, true, XOP>(grp, cols, x, s, ops) : rows_launch<F, 2, 1, false, XOP>(grp, cols, x, s, ops);
+}
+
+// The fused variant for any format but IFLOW_Q3H_B64: `count` (1-8) matrices that share x (one vector), the operation on
+// x and its second operand; a residual per matrix (null: none).  hipErrorNotSupported: rows too long for LDS (see above).
+hipError_t launch_qgemv_rows_fused(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols,
+                                   const uint16_t *x, int x_op, const uint16_t *aux, float eps, const uint16_t *const *residual,
+                                   uint16_t *const *y, hipStream_t s)
+{
+    if (count < 1 || count > ROWS_MAX_GROUP) return hipErrorInvalidValue;
+    if (x_op > IFLOW_X_PLAIN && aux == nullptr) return hipErrorInvalidValue;
+    RowsGroup grp = {};
+    RowsOps ops = {};
+    for (int i = 0; i < count; ++i) {
+        grp.packed[i] = static_cast<const uint8_t *>(packed[i]); grp.y[i] = y[i]; grp.rows[i] = (int)rows[i];
+        ops.residual[i] = residual ? residual[i] : nullptr;
+    }
+    grp.count = count;
+    ops.aux = aux;
+    ops.eps = eps;
+    return for_format<false>(format, [&](auto f) {
+        constexpr int F = decltype(f)::value;
+        switch (x_op) {
+        case IFLOW_X_PLAIN:    return rows_fused_count<F, IFLOW_X_PLAIN>(grp, cols, x, ops, s);
+        case IFLOW_X_RMS_GAIN: return rows_fused_count<F, IFLOW_X_RMS_GAIN>(grp, cols, x, ops, s);
+        case IFLOW_X_SILU_MUL: return rows_fused_count<F, IFLOW_X_SILU_MUL>(grp, cols, x, ops, s);
+        default: return hipErrorInvalidValue;
+        }
+    });
 }
 
 }  // namespace iflow

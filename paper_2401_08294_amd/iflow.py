@@ -161,7 +161,7 @@ ROPE_ADJACENT, ROPE_HALVES = 0, 1
 def qgemv_fused(fmt: int, packed_list, rows_list, cols: int, x, y_list, x_op: int = X_PLAIN, aux=None, eps: float = 0.0,
                 residual_list=None, stream=None) -> None:
     """qgemv_multi with rms normalization (aux = gains) or the silu-gated input (aux = second factor) in front of the
-    product and an optional residual per matrix behind it, in the same launch (3.5-bit format)."""
+    product and an optional residual per matrix behind it, in the same launch."""
     n = len(packed_list)
     pk = (C.c_void_p * n)(*[_ptr(t) for t in packed_list])
     ys = (C.c_void_p * n)(*[_ptr(t) for t in y_list])

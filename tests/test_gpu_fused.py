@@ -1,10 +1,11 @@
-"""GPU parity of iflow_qgemv_fused: rms normalization or the silu-gated input in front of the 3.5-bit product and a
-residual behind it, in one launch, against the plain definitions in oracle/decode_ops.py."""
+"""GPU parity of iflow_qgemv_fused: rms normalization or the silu-gated input in front of the product and a residual
+behind it, in one launch, against the plain definitions in oracle/decode_ops.py (the 3.5-bit format at many shapes,
+every other format at ragged ones)."""
 import numpy as np
 import pytest
 
 from paper_2401_08294_amd import synth
-from test_gpu_parity import TOL, gpu, gpu_quantize, say  # noqa: F401
+from test_gpu_parity import NAMES, TOL, gpu, gpu_quantize, say  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
@@ -23,11 +24,11 @@ def err(y_bits, yref):
     return float(np.max(np.abs(y - yref) / np.maximum(np.abs(yref), max(rms, 1e-30))))
 
 
-def make(torch, iflow, orc, rows, cols, seed, sigma=0.02):
+def make(torch, iflow, orc, rows, cols, seed, sigma=0.02, name="Q3H_B64"):
     w = synth.weights(rows, cols, sigma, seed)
-    packed, _ = gpu_quantize(torch, iflow, iflow.Q3H_B64, w)
-    q, s, o = orc.quantize(orc.Q3H_B64, w)
-    return packed, orc.dequant(orc.Q3H_B64, q, s, o)
+    packed, _ = gpu_quantize(torch, iflow, iflow.FORMATS[name], w)
+    q, s, o = orc.quantize(orc.FORMATS[name], w)
+    return packed, orc.dequant(orc.FORMATS[name], q, s, o)
 
 
 @pytest.mark.parametrize("rows,cols", [(300, 1024), (1000, 4096 + 64), (37, 64), (40, 18 * 4096 + 64)])
@@ -139,3 +140,78 @@ def test_feed_forward_block_at_7b_size(gpu, orc):
     e = float(np.max(np.abs(full[m[3]] - want) / np.maximum(np.abs(want), np.sqrt(np.mean(full ** 2)))))
     say(f"        down + residual: max rel err on sampled rows {e:.3e}")
     assert np.isfinite(full).all() and e <= TOL
+
+
+OTHER_FORMATS = [n for n in NAMES if n != "Q3H_B64"]
+
+
+@pytest.mark.parametrize("name", OTHER_FORMATS)
+def test_other_formats_rms_gain_two_matrices_and_residual(gpu, orc, name):
+    """Ragged in every direction: a last strip of two blocks, row counts that fill neither a group nor a workgroup."""
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    fmt = iflow.FORMATS[name]
+    rows, cols = [301, 77], 4096 + 128
+    say(f"[case] fused rms gain {name} rows={rows} cols={cols}")
+    mats = [make(torch, iflow, orc, r, cols, synth.BASE_SEED + 1500 + r, name=name) for r in rows]
+    x = synth.activations(1, cols, synth.BASE_SEED + 1501)[0].view(np.uint16)
+    g = (1.0 + 0.2 * np.random.default_rng(synth.BASE_SEED + 1502).standard_normal(cols)).astype(np.float16).view(np.uint16)
+    res1 = synth.activations(1, rows[1], synth.BASE_SEED + 1503)[0].view(np.uint16)
+    ys = [torch.full((r,), float("nan"), dtype=torch.float16, device="cuda") for r in rows]
+    iflow.qgemv_fused(fmt, [m[0] for m in mats], rows, cols, dev16(torch, x), ys, iflow.X_RMS_GAIN, dev16(torch, g), 1e-5,
+                      [None, dev16(torch, res1)])
+    torch.cuda.synchronize()
+    v, sc = ops.gain(x, g), ops.rms_scale(x, 1e-5)
+    e0 = err(bits_of(ys[0]), ops.fused_gemv(mats[0][1], v, sc, None))
+    e1 = err(bits_of(ys[1]), ops.fused_gemv(mats[1][1], v, sc, res1))
+    say(f"        max rel err {e0:.3e} {e1:.3e}")
+    assert e0 <= TOL and e1 <= TOL
+    # one matrix per launch gives the same bits
+    y_alone = torch.full((rows[1],), float("nan"), dtype=torch.float16, device="cuda")
+    iflow.qgemv_fused(fmt, [mats[1][0]], [rows[1]], cols, dev16(torch, x), [y_alone], iflow.X_RMS_GAIN, dev16(torch, g), 1e-5,
+                      [dev16(torch, res1)])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(y_alone), bits_of(ys[1]))
+
+
+@pytest.mark.parametrize("name", OTHER_FORMATS)
+def test_other_formats_silu_gate_in_place_residual_and_plain(gpu, orc, name):
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    fmt = iflow.FORMATS[name]
+    rows, cols = 520, 11008
+    say(f"[case] fused silu*mul {name} rows={rows} cols={cols}, residual in place; plain")
+    packed, wdeq = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 1600, name=name)
+    a = (synth.activations(1, cols, synth.BASE_SEED + 1601)[0].astype(np.float32) * 2.5).astype(np.float16).view(np.uint16)
+    b = synth.activations(1, cols, synth.BASE_SEED + 1602)[0].view(np.uint16)
+    h = synth.activations(1, rows, synth.BASE_SEED + 1603)[0].view(np.uint16)
+    hidden = dev16(torch, h).clone()
+    iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, a), [hidden], iflow.X_SILU_MUL, dev16(torch, b), 0.0, [hidden])
+    torch.cuda.synchronize()
+    e = err(bits_of(hidden), ops.fused_gemv(wdeq, ops.silu_mul(a, b), 1.0, h))
+    say(f"        max rel err {e:.3e}")
+    assert e <= TOL
+    # no operation and no residual: iflow_qgemv's bits; with a residual: the definition
+    y0 = torch.empty((rows,), dtype=torch.float16, device="cuda")
+    y1 = torch.empty((rows,), dtype=torch.float16, device="cuda")
+    iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, b), [y0])
+    iflow.qgemv(fmt, packed, rows, cols, dev16(torch, b), y1)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(y0), bits_of(y1))
+    iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, b), [y0], residual_list=[dev16(torch, h)])
+    torch.cuda.synchronize()
+    assert err(bits_of(y0), ops.fused_gemv(wdeq, b, 1.0, h)) <= TOL
+
+
+def test_other_formats_rows_too_long_for_the_staged_activations_are_refused(gpu):
+    """Beyond what fits in LDS the fused call of the other formats returns a shape error before any launch."""
+    torch, iflow = gpu
+    fmt = iflow.FORMATS["Q4_B64"]
+    rows, cols = 8, 65536
+    n = iflow.packed_bytes(fmt, rows, cols)
+    packed = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    x = torch.zeros(cols, dtype=torch.float16, device="cuda")
+    y = torch.zeros(rows, dtype=torch.float16, device="cuda")
+    with pytest.raises(iflow.IflowError) as info:
+        iflow.qgemv_fused(fmt, [packed], [rows], cols, x, [y], residual_list=[y])
+    assert info.value.status == iflow.ERR_SHAPE

@@ -169,7 +169,8 @@ def test_fused_validation_happens_before_any_launch(iflow):
                                    C.c_float(eps), res, (C.c_void_p * n)(*y), None)
 
     x, y0, y1, aux = base, base * 3, base * 4, base * 5
-    assert call(3, [8], 64, x, [y0]) == iflow.ERR_FORMAT                         # 3.5-bit format only
+    assert call(9, [8], 64, x, [y0]) == iflow.ERR_FORMAT                         # no such format
+    assert call(3, [8], 65536, x, [y0]) == iflow.ERR_SHAPE                       # 4-bit rows too long to stage in LDS
     assert call(4, [8], 64, x, [y0], x_op=7, aux=aux) == iflow.ERR_SHAPE         # unknown operation
     assert call(4, [8], 64, x, [y0], x_op=iflow.X_RMS_GAIN) == iflow.ERR_NULL    # gains missing
     assert call(4, [8], 64, x, [y0], x_op=iflow.X_PLAIN, aux=aux) == iflow.ERR_NULL   # a second operand nobody asked for
