@@ -11,6 +11,8 @@ LLaMA-family models its decode step (Section 5, ``Infer()``) runs.  So the textb
   silu               silu(a) = a / (1 + exp(-a))
   gated feed-forward input  v_k = silu(a_k) * b_k      (a: "gate" projection, b: "up" projection)
   residual           out_n = (W v)_n + r_n
+  gated pair         out_n = silu(scale (W_gate v)_n) * (scale (W_up v)_n)      (the gate applied where its two
+                     projections are produced, before either is stored)
 
 The fused kernel applies the normalization as (x_k * g_k) rounded to fp16, multiplied by the matrix, and the scalar
 1 / sqrt(mean x^2 + eps) applied to the fp32 row sums (the scalar commutes with the matrix product).  The functions
@@ -59,3 +61,10 @@ def fused_gemv(w16_bits, v16_bits, scale: float = 1.0, residual16_bits=None) -> 
     if residual16_bits is not None:
         y = y + _f(residual16_bits)
     return y
+
+
+def gated_gemv(w_gate16_bits, w_up16_bits, v16_bits, scale: float = 1.0) -> np.ndarray:
+    """silu(scale * (W_gate' v)) * (scale * (W_up' v)) in fp64: the gated feed-forward's hidden vector from its two
+    projections, with no rounding in between."""
+    v = _f(v16_bits)
+    return silu(scale * (_f(w_gate16_bits) @ v)) * (scale * (_f(w_up16_bits) @ v))

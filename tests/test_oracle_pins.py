@@ -535,6 +535,28 @@ def test_fused_gemv_reduces_to_the_plain_product(orc):
     assert np.max(np.abs(ops.fused_gemv(_bits(w), _bits(e), 2.0, _bits(r)) - (2.0 * w[:, 5].astype(np.float64) + r.astype(np.float64)))) < 1e-15
 
 
+def test_gated_gemv_is_the_library_feed_forward_gate(orc):
+    import torch
+    from oracle import decode_ops as ops
+    rng = np.random.default_rng(80)
+    wg = (0.3 * rng.standard_normal((29, 192))).astype(np.float16)
+    wu = (0.3 * rng.standard_normal((29, 192))).astype(np.float16)
+    v = rng.standard_normal(192).astype(np.float16)
+    t = lambda a: torch.from_numpy(a.astype(np.float64))
+    ref = (torch.nn.functional.silu(torch.nn.functional.linear(t(v), t(wg)) * 0.7) * (torch.nn.functional.linear(t(v), t(wu)) * 0.7)).numpy()
+    got = ops.gated_gemv(_bits(wg), _bits(wu), _bits(v), 0.7)
+    assert np.max(np.abs(got - ref)) <= 1e-13
+    # the two matrices are not interchangeable, and the two plain products composed by hand give the same
+    assert np.max(np.abs(got - ops.gated_gemv(_bits(wu), _bits(wg), _bits(v), 0.7))) > 1e-3
+    g, u = orc.gemm(_bits(wg), _bits(v))[0], orc.gemm(_bits(wu), _bits(v))[0]
+    assert np.max(np.abs(ops.gated_gemv(_bits(wg), _bits(wu), _bits(v)) - ops.silu(g) * u)) <= 1e-13
+    # an up projection of all ones times e_k with a gate row of large weights: silu(a) -> a
+    e = np.zeros(192, np.float16); e[3] = 1.0
+    big = np.zeros((1, 192), np.float16); big[0, 3] = 40.0
+    one = np.zeros((1, 192), np.float16); one[0, 3] = 1.0
+    assert abs(float(ops.gated_gemv(_bits(big), _bits(one), _bits(e))[0]) - 40.0) < 1e-10
+
+
 # ---- grouped-query attention for one decode step (oracle/attention.py) ----
 def test_gqa_decode_matches_the_library_routine_and_special_cases():
     import torch
