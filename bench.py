@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--fused", action="store_true",
                     help="with --launches 4: rms normalization, silu-gated input and residuals fused into the four launches of a layer "
                          "(iflow_qgemv_fused), each launch reading the previous one's output")
+    ap.add_argument("--separate-gate", action="store_true",
+                    help="with --fused: store gate and up and apply silu(gate)*up in front of the down product (iflow_qgemv_fused "
+                         "with IFLOW_X_SILU_MUL) instead of producing the gated vector in the gate/up launch (iflow_qgemv_gated)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the context figures for batches > 1 and the cache-hot case")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -201,7 +204,8 @@ def main():
             attn_ws = torch.empty((attn_ws_bytes,), dtype=torch.uint8, device=dev)
 
     def fused_step(layer):
-        """One decoder layer in four launches: norm -> q,k,v | o + residual | norm -> gate,up | silu(gate)*up -> down + residual.
+        """One decoder layer in four launches: norm -> q,k,v | o + residual | norm -> silu(gate)*up | down + residual
+        (--separate-gate: norm -> gate,up | silu(gate)*up -> down + residual).
         (q's output stands in for the attention output, which is not part of this library.)"""
         m = ring[layer]
         h = hidden_state
@@ -213,8 +217,12 @@ def main():
             iflow.attn_decode(ys[0], kc, vc, 32, 32, 128, args.context, args.context, 128 ** -0.5, attn_out, attn_ws, attn_ws_bytes, stream=raw)
             o_in = attn_out
         iflow.qgemv_fused(fmt, [m[3][2]], [m[3][0]], m[3][1], o_in, [h], residual_list=[h], stream=raw)
-        iflow.qgemv_fused(fmt, [m[4][2], m[5][2]], [m[4][0], m[5][0]], m[4][1], h, [ys[4], ys[5]], iflow.X_RMS_GAIN, gains[1], 1e-5, stream=raw)
-        iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [h], iflow.X_SILU_MUL, ys[5], 0.0, residual_list=[h], stream=raw)
+        if args.separate_gate:
+            iflow.qgemv_fused(fmt, [m[4][2], m[5][2]], [m[4][0], m[5][0]], m[4][1], h, [ys[4], ys[5]], iflow.X_RMS_GAIN, gains[1], 1e-5, stream=raw)
+            iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [h], iflow.X_SILU_MUL, ys[5], 0.0, residual_list=[h], stream=raw)
+        else:
+            iflow.qgemv_gated(fmt, m[4][2], m[5][2], m[4][0], m[4][1], h, ys[4], iflow.X_RMS_GAIN, gains[1], 1e-5, stream=raw)
+            iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [h], residual_list=[h], stream=raw)
         launch_count[0] += 4
 
     def one_step(layer):
@@ -390,8 +398,8 @@ def main():
                                       stream=raw)
                     iflow.attn_decode(ys[0], kvs[layer][0], kvs[layer][1], 32, 32, 128, ctx, ctx, 128 ** -0.5, ao, aws2, awb2, stream=raw)
                     iflow.qgemv_fused(fmt, [m[3][2]], [m[3][0]], m[3][1], ao, [hs], residual_list=[hs], stream=raw)
-                    iflow.qgemv_fused(fmt, [m[4][2], m[5][2]], [m[4][0], m[5][0]], m[4][1], hs, [ys[4], ys[5]], iflow.X_RMS_GAIN, gn[1], 1e-5, stream=raw)
-                    iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [hs], iflow.X_SILU_MUL, ys[5], 0.0, residual_list=[hs], stream=raw)
+                    iflow.qgemv_gated(fmt, m[4][2], m[5][2], m[4][0], m[4][1], hs, ys[4], iflow.X_RMS_GAIN, gn[1], 1e-5, stream=raw)
+                    iflow.qgemv_fused(fmt, [m[6][2]], [m[6][0]], m[6][1], ys[4], [hs], residual_list=[hs], stream=raw)
 
                 for layer in range(2):
                     decode_layer(layer)
@@ -410,7 +418,7 @@ def main():
                 us_layer = t0.elapsed_time(t1) * 1e3 / (20 * args.ring)
                 other["decode_step_with_attention"] = {
                     "what": "per decoder layer: rms-norm + q,k,v | rotary embedding + cache append | attention over 1024 cached positions "
-                            "(32 heads) | o + residual | rms-norm + gate,up | silu(gate)*up + down + residual: 4 fused launches + rope_append "
+                            "(32 heads) | o + residual | rms-norm + silu(gate)*up | down + residual: 4 fused launches + rope_append "
                             "+ attention, HIP-graph replay over the ring",
                     "us_per_layer": round(us_layer, 2), "weight_GB/s": round(step_bytes / us_layer / 1e3, 1),
                     "tokens_per_s_32_layers": round(1e6 / (32 * us_layer), 1)}

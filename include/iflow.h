@@ -149,6 +149,18 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
                                  int64_t cols, const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps,
                                  const uint16_t *const *residual, uint16_t *const *y, void *stream);
 
+/* The two first projections of a gated feed-forward and its gate in one launch (Section 2's module table: activation
+ * "silu" of the LLaMA family's feed-forward; Section 5's Infer() applies it between the products): with
+ * W_gate and W_up both [rows][cols] in `format`,
+ *   y_n = fp16( silu(c (W'_gate v)_n) * (c (W'_up v)_n) ),   silu(a) = a / (1 + exp(-a)) in fp32,
+ * where x_op = IFLOW_X_PLAIN: v = x, c = 1 (aux must be null), or x_op = IFLOW_X_RMS_GAIN: v_k = fp16(x_k aux_k),
+ * c = 1 / sqrt(mean_k x_k^2 + eps) as in iflow_qgemv_fused (IFLOW_X_SILU_MUL: IFLOW_ERR_SHAPE).  Neither projection is
+ * stored or rounded on its own; the next product (the "down" projection) reads y as a plain activation vector.
+ * x [cols], aux [cols], y [rows] fp16; y must not overlap x or aux.  Row-length limits as for iflow_qgemv_fused. */
+iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate, const void *packed_up, int64_t rows,
+                                 int64_t cols, const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps,
+                                 uint16_t *y, void *stream);
+
 /* A chain of batch-1 products in ONE launch (3.5-bit format only): the decode step applies its projections one
  * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and
  * at 7B sizes each product is so short that the idle time between dependent launches costs as much as a third of

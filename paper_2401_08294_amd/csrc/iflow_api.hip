@@ -224,6 +224,29 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
     return device_status(iflow::launch_qgemv_fused(count, packed, rows, cols, x, (int)x_op, aux, eps, residual, y, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols,
+                                 const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps, uint16_t *y, void *stream)
+{
+    iflow::FormatInfo fi;
+    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
+    if (x_op != IFLOW_X_PLAIN && x_op != IFLOW_X_RMS_GAIN) return IFLOW_ERR_SHAPE;
+    if (!packed_gate || !packed_up || !x || !y) return IFLOW_ERR_NULL;
+    if ((x_op == IFLOW_X_PLAIN) != (aux == nullptr)) return IFLOW_ERR_NULL;
+    if (x_op == IFLOW_X_RMS_GAIN && !(eps >= 0.0f && eps < 3.0e38f)) return IFLOW_ERR_SHAPE;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (!aligned16(packed_gate) || !aligned16(packed_up) || !aligned16(x) || !aligned16(y) || (aux && !aligned16(aux))) return IFLOW_ERR_ALIGN;
+    auto overlaps = [](const void *p, int64_t pn, const void *q, int64_t qn) {
+        const uintptr_t a0 = (uintptr_t)p, b0 = (uintptr_t)q;
+        return a0 < b0 + (uintptr_t)qn && b0 < a0 + (uintptr_t)pn;
+    };
+    // outputs are written while other workgroups still read x and aux
+    if (overlaps(y, rows * 2, x, cols * 2) || (aux && overlaps(y, rows * 2, aux, cols * 2))) return IFLOW_ERR_SHAPE;
+    const hipError_t e = iflow::launch_qgemv_gated((int)format, packed_gate, packed_up, rows, cols, x, (int)x_op, aux, eps, y,
+                                                   (hipStream_t)stream);
+    return e == hipErrorNotSupported ? IFLOW_ERR_SHAPE : device_status(e);       // (rows too long for the staged activations)
+}
+
 iflow_status_t iflow_attn_decode_workspace_bytes(int n_heads, size_t *bytes)
 {
     if (!bytes) return IFLOW_ERR_NULL;

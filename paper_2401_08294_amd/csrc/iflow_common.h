@@ -212,6 +212,10 @@ hipError_t launch_qgemv_fused(int count, const void *const *packed, const int64_
 hipError_t launch_qgemv_rows_fused(int format, int count, const void *const *packed, const int64_t *rows, int64_t cols,
                                    const uint16_t *x, int x_op, const uint16_t *aux, float eps, const uint16_t *const *residual,
                                    uint16_t *const *y, hipStream_t s);
+hipError_t launch_qgemv_gated(int format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols, const uint16_t *x,
+                              int x_op, const uint16_t *aux, float eps, uint16_t *y, hipStream_t s);
+hipError_t launch_qgemv_rows_gated(int format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols,
+                                   const uint16_t *x, int x_op, const uint16_t *aux, float eps, uint16_t *y, hipStream_t s);
 hipError_t launch_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads, int64_t position,
                               int64_t max_seq, double base, int pair_mode, uint16_t *k_cache, uint16_t *v_cache, hipStream_t s);
 size_t attn_workspace_bytes(int n_heads);

@@ -207,7 +207,10 @@ struct GemvOps {
 //                      1 / sqrt(mean x^2 + eps) - rms normalization, with its scalar moved behind the product;
 //   IFLOW_X_SILU_MUL   the staged activations are fp16(silu(x_k) aux_k) - the input of a gated feed-forward's last layer;
 //   residual           out_n = fp16(row sum + residual_n).
-template <int NB, int U, bool MULTI, int XOP = -1>
+// GATED (with XOP = plain or rms gain, one matrix pair): a wavefront's two rows in flight are row n of a "gate" matrix
+// and row n of an "up" matrix (grp.packed[0] and [1], both rows0 x cols), and the one output is
+// fp16(silu(gate sum x scale) (up sum x scale)) - the gated feed-forward's hidden vector without storing its two factors.
+template <int NB, int U, bool MULTI, int XOP = -1, bool GATED = false>
 __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const uint8_t *__restrict__ packed0, uint16_t *__restrict__ y0,
                                                         const uint16_t *__restrict__ X, int rows0, int cols, int nbk, int nstrips,
                                                         int tgw, int x_op, const uint16_t *__restrict__ aux,
@@ -218,6 +221,8 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
     // branch over a block of cold code costs an instruction-cache miss)
     constexpr bool OPS = XOP >= 0;
     static_assert(!OPS || NB == 1, "the fused variant is built for one activation vector");
+    static_assert(!GATED || (OPS && !MULTI && U == 2), "the gated variant: one pair of matrices, two rows in flight");
+    constexpr int RPG = GATED ? 1 : U;                        // output rows per row group
     (void)x_op;
     // strips staged per pass, row groups per wavefront, wavefronts per workgroup: packed into one argument (8 bits each)
     // so that the fourteen argument registers reach as far as `aux`
@@ -241,7 +246,8 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
     const uint8_t *__restrict__ packed = MULTI ? grp.packed[m] : packed0;
     uint16_t *__restrict__ Y = MULTI ? grp.y[m] : y0;
     const int rows = MULTI ? grp.rows[m] : rows0;
-    const int rbase = (wg * waves + wave) * (G * U);          // first row of this wavefront: G groups of U rows
+    const int rbase = (wg * waves + wave) * (G * RPG);        // first row of this wavefront: G groups of U rows
+    const uint8_t *__restrict__ packed_up = GATED ? grp.packed[1] : nullptr;
     const int64_t row_stride = (int64_t)nbk * 32;
 
     // weights of U rows of one strip: wave-uniform row base + per-lane offset, streamed once (nontemporal);
@@ -254,7 +260,8 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         const uint32_t lane_off = (uint32_t)(lane * 16) & mask_lt(lane, n_t);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint8_t *p0 = none ? packed : packed + (int64_t)min(r0 + u, rows - 1) * row_stride + (int64_t)t * 2048;
+            const uint8_t *mat = (GATED && u == 1) ? packed_up : packed;
+            const uint8_t *p0 = none ? packed : mat + (int64_t)min(GATED ? r0 : r0 + u, rows - 1) * row_stride + (int64_t)t * 2048;
             const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + lane_off));
             const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + n_t * 16 + lane_off));
             w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
@@ -394,7 +401,7 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
         int g = 0, ts = 0;
 #pragma unroll 1
         for (int step = 0; step < nsteps; ++step) {
-            const int r0 = rbase + g * U;
+            const int r0 = rbase + g * RPG;
             if (nt > 1 || step == 0) {                        // a single strip stays in registers for all row groups
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
@@ -423,10 +430,16 @@ __global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const ui
             // next step's weights (wave-uniform control flow only)
             int gn = g, tn = ts + 1;
             if (tn == nt) { tn = 0; gn = g + 1; }
-            load_step(w, rbase + gn * U, t0 + tn, step + 1 >= nsteps);
+            load_step(w, rbase + gn * RPG, t0 + tn, step + 1 >= nsteps);
 
             const bool group_done = ts == nt - 1 && t0 + nt == nstrips;
-            if (group_done) {                                 // one reduction per row; lane 63 holds the sums
+            if (GATED && group_done) {                        // both factors of output r0 end up in lane 63
+                const float gate = wave_sum_to_lane63(v[0][0]) * out_scale, up = wave_sum_to_lane63(v[0][U - 1]) * out_scale;
+                const float hv = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+                if (lane == 63 && r0 < rows) Y[r0] = as_u16((half_t)hv);
+#pragma unroll
+                for (int u = 0; u < U; ++u) part[0][u] = 0.f;
+            } else if (group_done) {                          // one reduction per row; lane 63 holds the sums
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -465,7 +478,7 @@ static int pick_rows_per_wg(int64_t rows, int waves_per_wg)
     return (int)r;
 }
 
-template <int NB, int U, int XOP = -1>
+template <int NB, int U, int XOP = -1, bool GATED = false>
 static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, int waves, int G, hipStream_t s, const GemvOps &ops = GemvOps(),
                               int x_op = IFLOW_X_PLAIN, const uint16_t *aux = nullptr)
 {
@@ -478,23 +491,28 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
     static PerDevice pd;                                      // raise the dynamic-LDS cap once per instantiation and device
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
-        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false, XOP>),
+        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, false, XOP, GATED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
-        if (r == hipSuccess)
-            r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true, XOP>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if constexpr (!GATED) {
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_gemv_kernel<NB, U, true, XOP>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        }
         return r;
     });
     if (e != hipSuccess) return e;
     if (T < nstrips) G = 1;                                   // multi-pass rows: partial sums live in registers, one group only
-    const int64_t rows_per_wg = (int64_t)waves * U * G;
+    const int64_t rows_per_wg = (int64_t)waves * (GATED ? 1 : U) * G;
     int64_t grid = 0;
-    for (int i = 0; i < grp.count; ++i) {
+    for (int i = 0; i < (GATED ? 1 : grp.count); ++i) {       // (gated: the pair's two matrices are one set of output rows)
         grid += (grp.rows[i] + rows_per_wg - 1) / rows_per_wg;
         grp.wg_end[i] = (int)grid;
     }
     if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    if (grp.count == 1)
+    if constexpr (GATED)
+        hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false, XOP, true>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
+                           grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T | (G << 8) | (waves << 16), x_op, aux, grp, ops);
+    else if (grp.count == 1)
         hipLaunchKernelGGL((q3h_gemv_kernel<NB, U, false, XOP>), dim3((unsigned)grid), dim3(64 * waves), lds, s,
                            grp.packed[0], grp.y[0], X, grp.rows[0], (int)cols, nbk, nstrips, T | (G << 8) | (waves << 16), x_op, aux, grp, ops);
     else
@@ -507,7 +525,7 @@ static hipError_t q3h_launch_u(GemvGroup grp, int64_t cols, const uint16_t *X, i
 // up to T strips (8.5 KiB of LDS per strip and batch column, at most 152 KiB).  Long rows and small problems
 // get larger workgroups (the staging is paid once per workgroup); tall problems let a wavefront walk several
 // row groups.
-template <int NB, int XOP = -1>
+template <int NB, int XOP = -1, bool GATED = false>
 static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t *X, hipStream_t s, const GemvOps &ops = GemvOps(),
                             int x_op = IFLOW_X_PLAIN, const uint16_t *aux = nullptr)
 {
@@ -520,8 +538,8 @@ static hipError_t q3h_launch(const GemvGroup &grp, int64_t cols, const uint16_t 
     if (G < 1) G = 1;
     if (G > 3) G = 3;
     // rows in flight per wavefront: two, or one where 32 activation registers per batch column leave no room
-    if (NB <= 2) return q3h_launch_u<NB, 2, XOP>(grp, cols, X, waves, G, s, ops, x_op, aux);
-    return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
+    if constexpr (NB <= 2) return q3h_launch_u<NB, 2, XOP, GATED>(grp, cols, X, waves, G, s, ops, x_op, aux);
+    else return q3h_launch_u<NB, 1>(grp, cols, X, waves, G, s);
 }
 
 template <int F, int NB>
@@ -617,6 +635,23 @@ hipError_t launch_qgemv_fused(int count, const void *const *packed, const int64_
     case IFLOW_X_PLAIN:    return q3h_launch<1, IFLOW_X_PLAIN>(grp, cols, x, s, ops, x_op, aux);
     case IFLOW_X_RMS_GAIN: return q3h_launch<1, IFLOW_X_RMS_GAIN>(grp, cols, x, s, ops, x_op, aux);
     case IFLOW_X_SILU_MUL: return q3h_launch<1, IFLOW_X_SILU_MUL>(grp, cols, x, s, ops, x_op, aux);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// The gated pair: y_n = silu(scale (W_gate' v)_n) (scale (W_up' v)_n), v and scale as x_op (plain or rms gain) says.
+hipError_t launch_qgemv_gated(int format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols, const uint16_t *x,
+                              int x_op, const uint16_t *aux, float eps, uint16_t *y, hipStream_t s)
+{
+    if (format != IFLOW_Q3H_B64) return launch_qgemv_rows_gated(format, packed_gate, packed_up, rows, cols, x, x_op, aux, eps, y, s);
+    GemvGroup grp = {};
+    GemvOps ops = {};
+    grp.packed[0] = static_cast<const uint8_t *>(packed_gate); grp.packed[1] = static_cast<const uint8_t *>(packed_up);
+    grp.y[0] = y; grp.y[1] = y; grp.rows[0] = (int)rows; grp.rows[1] = (int)rows; grp.count = 2;
+    for (int i = 0; i < IFLOW_MAX_GROUP; ++i) ops.eps[i] = eps;
+    switch (x_op) {
+    case IFLOW_X_PLAIN:    return q3h_launch<1, IFLOW_X_PLAIN, true>(grp, cols, x, s, ops, x_op, aux);
+    case IFLOW_X_RMS_GAIN: return q3h_launch<1, IFLOW_X_RMS_GAIN, true>(grp, cols, x, s, ops, x_op, aux);
     default: return hipErrorInvalidValue;
     }
 }

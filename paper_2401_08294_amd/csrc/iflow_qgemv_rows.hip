@@ -43,6 +43,9 @@ struct RowsGroup {
 //                      1 / sqrt(mean x^2 + eps): rms normalization with its scalar moved behind the product;
 //   IFLOW_X_SILU_MUL   the staged activations are fp16(silu(x_k) aux_k): the input of a gated feed-forward's last layer;
 //   residual           out_n = fp16(row sum x scale + residual_n), per matrix, or none.
+//   GATED              (one pair of matrices, XOP plain or rms gain) the wavefront's two rows in flight are row n of a
+//                      "gate" and row n of an "up" matrix (grp.packed[0], [1]); out_n = fp16(silu(gate sum x scale)
+//                      (up sum x scale)), the gated feed-forward's hidden vector without storing its two factors.
 // (The same arithmetic, in the same order, as the 3.5-bit kernel's fused variant.)
 struct RowsOps {
     const uint16_t *residual[ROWS_MAX_GROUP];
@@ -50,7 +53,7 @@ struct RowsOps {
     float eps;
 };
 
-template <int F, int U, int NB, bool MULTI, int XOP>
+template <int F, int U, int NB, bool MULTI, int XOP, bool GATED = false>
 __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
                                                uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips, int groups,
                                                const RowsGroup &grp, const RowsOps &ops)
@@ -58,6 +61,8 @@ __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packe
     typedef Fmt<F> T;
     constexpr bool OPS = XOP >= 0;
     static_assert(!OPS || NB == 1, "the fused variant is built for one activation vector");
+    static_assert(!GATED || (OPS && !MULTI && U == 2), "the gated variant: one pair of matrices, two rows in flight");
+    constexpr int RPG = GATED ? 1 : U;                         // output rows per group
     int mi = 0;                                                // which matrix this workgroup belongs to
     if (MULTI) {
 #pragma unroll
@@ -66,6 +71,7 @@ __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packe
     }
     const int wg = MULTI ? blockIdx.x - (mi ? grp.wg_end[mi - 1] : 0) : blockIdx.x;
     const uint8_t *__restrict__ packed = MULTI ? grp.packed[mi] : packed0;
+    const uint8_t *__restrict__ packed_up = GATED ? grp.packed[1] : nullptr;
     uint16_t *__restrict__ Y = MULTI ? grp.y[mi] : y0;
     const int rows = MULTI ? grp.rows[mi] : rows0;
     const int64_t header_offset = (int64_t)rows * nbk * T::code_bytes;
@@ -150,8 +156,9 @@ __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packe
         const int64_t hdr_off = header_offset + ((int64_t)t * hdr_per_strip + la * G::WPL / T::block) * 4;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t r = min(r0 + u, rows - 1);
-            const uint8_t *p = packed + r * row_stride + code_off;
+            const int64_t r = min(GATED ? r0 : r0 + u, rows - 1);
+            const uint8_t *mat = (GATED && u == 1) ? packed_up : packed;
+            const uint8_t *p = mat + r * row_stride + code_off;
             if constexpr (kind_has_planes(KIND)) {
                 constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;
                 if constexpr (WA == 4) {
@@ -161,7 +168,7 @@ __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packe
                     const uint2 a = *reinterpret_cast<const uint2 *>(p);
                     w[u].d[0] = a.x; w[u].d[1] = a.y;
                 }
-                const uint8_t *pb = packed + r * row_stride_b + code_off_b;
+                const uint8_t *pb = mat + r * row_stride_b + code_off_b;
                 if constexpr (WB == 2) {
                     const uint2 c = *reinterpret_cast<const uint2 *>(pb);
                     w[u].d[WA] = c.x; w[u].d[WA + 1] = c.y;
@@ -172,18 +179,18 @@ __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packe
                 const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
                 w[u].d[0] = a.x; w[u].d[1] = a.y; w[u].d[2] = a.z; w[u].d[3] = a.w;
             }
-            w[u].hdr = *reinterpret_cast<const uint32_t *>(packed + hdr_off + r * (int64_t)nbk * 4);
+            w[u].hdr = *reinterpret_cast<const uint32_t *>(mat + hdr_off + r * (int64_t)nbk * 4);
         }
     };
 
     // ---- the walk: steps (group, strip) of this wavefront, one set of weights ahead ---------------------------------
-    const int rbase = (wg * waves + wave) * groups * U;
+    const int rbase = (wg * waves + wave) * groups * RPG;
     const int nsteps = groups * nstrips;
     auto step_row = [&](int k, int &r0, int &t) {
         const int kk = min(k, nsteps - 1);
         const int g = kk / nstrips;
         t = kk - g * nstrips;
-        r0 = rbase + g * U;
+        r0 = rbase + g * RPG;
     };
 
     WRegs<KIND> wa[U], wb[U];
@@ -241,7 +248,14 @@ __device__ __forceinline__ void gemv_rows_body(const uint8_t *__restrict__ packe
             for (int b = 0; b < NB; ++b)
                 acc[b][u] += __builtin_fmaf((float)so.x, a[b] - xr[b].bias_sum, (float)so.y * xr[b].x_sum);
         }
-        if (t == nstrips - 1) {                               // the rows end here: reduce, store, start over
+        if (GATED && t == nstrips - 1) {                      // even lanes hold the gate's sum, odd lanes the up projection's
+            const float mine = reduce_rows<U>(acc[0], lane) * out_scale;
+            const float other = dpp_f32<0xB1, 0xF>(mine);     // (lanes ^ 1)
+            const float hv = mine * __builtin_amdgcn_rcpf(1.0f + __expf(-mine)) * other;
+            if (lane == 0 && r0 < rows) Y[r0] = as_u16((half_t)hv);
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[0][u] = 0.f;
+        } else if (t == nstrips - 1) {                        // the rows end here: reduce, store, start over
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 float r = reduce_rows<U>(acc[b], lane);
@@ -276,15 +290,15 @@ __global__ __launch_bounds__(512) void gemv_rows_kernel(const uint8_t *__restric
     gemv_rows_body<F, U, NB, MULTI, -1>(packed0, X, y0, rows0, cols, nbk, nstrips, groups, grp, RowsOps{});
 }
 
-template <int F, int U, bool MULTI, int XOP>
+template <int F, int U, bool MULTI, int XOP, bool GATED = false>
 __global__ __launch_bounds__(512) void gemv_rows_fused_kernel(const uint8_t *__restrict__ packed0, const uint16_t *__restrict__ X,
                                                               uint16_t *__restrict__ y0, int rows0, int cols, int nbk, int nstrips,
                                                               int groups, const RowsGroup grp, const RowsOps ops)
 {
-    gemv_rows_body<F, U, 1, MULTI, XOP>(packed0, X, y0, rows0, cols, nbk, nstrips, groups, grp, ops);
+    gemv_rows_body<F, U, 1, MULTI, XOP, GATED>(packed0, X, y0, rows0, cols, nbk, nstrips, groups, grp, ops);
 }
 
-template <int F, int U, int NB, bool MULTI, int XOP = -1>
+template <int F, int U, int NB, bool MULTI, int XOP = -1, bool GATED = false>
 static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hipStream_t s, const RowsOps &ops = RowsOps{})
 {
     typedef Fmt<F> T;
@@ -298,7 +312,7 @@ static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hi
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] {
         const void *fn;
-        if constexpr (XOP >= 0) fn = reinterpret_cast<const void *>(gemv_rows_fused_kernel<F, U, MULTI, XOP>);
+        if constexpr (XOP >= 0) fn = reinterpret_cast<const void *>(gemv_rows_fused_kernel<F, U, MULTI, XOP, GATED>);
         else fn = reinterpret_cast<const void *>(gemv_rows_kernel<F, U, NB, MULTI>);
         return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ROWS_LDS_LIMIT);
     });
@@ -313,15 +327,15 @@ static hipError_t rows_launch(RowsGroup grp, int64_t cols, const uint16_t *x, hi
     int groups = (int)(rows / ((int64_t)cus * 2 * waves * U));
     if (groups < 1) groups = 1;
     if (groups > 4) groups = 4;
-    const int64_t rows_per_wg = (int64_t)waves * groups * U;
+    const int64_t rows_per_wg = (int64_t)waves * groups * (GATED ? 1 : U);
     int64_t grid = 0;
-    for (int i = 0; i < grp.count; ++i) {
+    for (int i = 0; i < (GATED ? 1 : grp.count); ++i) {       // (gated: the pair's two matrices are one set of output rows)
         grid += (grp.rows[i] + rows_per_wg - 1) / rows_per_wg;
         grp.wg_end[i] = (int)grid;
     }
     if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     if constexpr (XOP >= 0)
-        hipLaunchKernelGGL((gemv_rows_fused_kernel<F, U, MULTI, XOP>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x,
+        hipLaunchKernelGGL((gemv_rows_fused_kernel<F, U, MULTI, XOP, GATED>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x,
                            grp.y[0], grp.rows[0], (int)cols, nbk, nstrips, groups, grp, ops);
     else
         hipLaunchKernelGGL((gemv_rows_kernel<F, U, NB, MULTI>), dim3((unsigned)grid), dim3(64 * waves), lds, s, grp.packed[0], x, grp.y[0],
@@ -396,6 +410,27 @@ hipError_t launch_qgemv_rows_fused(int format, int count, const void *const *pac
         case IFLOW_X_PLAIN:    return rows_fused_count<F, IFLOW_X_PLAIN>(grp, cols, x, ops, s);
         case IFLOW_X_RMS_GAIN: return rows_fused_count<F, IFLOW_X_RMS_GAIN>(grp, cols, x, ops, s);
         case IFLOW_X_SILU_MUL: return rows_fused_count<F, IFLOW_X_SILU_MUL>(grp, cols, x, ops, s);
+        default: return hipErrorInvalidValue;
+        }
+    });
+}
+
+// The gated pair for any format but IFLOW_Q3H_B64: y_n = silu(scale (W_gate' v)_n) (scale (W_up' v)_n).
+hipError_t launch_qgemv_rows_gated(int format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols,
+                                   const uint16_t *x, int x_op, const uint16_t *aux, float eps, uint16_t *y, hipStream_t s)
+{
+    if (x_op == IFLOW_X_RMS_GAIN && aux == nullptr) return hipErrorInvalidValue;
+    RowsGroup grp = {};
+    RowsOps ops = {};
+    grp.packed[0] = static_cast<const uint8_t *>(packed_gate); grp.packed[1] = static_cast<const uint8_t *>(packed_up);
+    grp.y[0] = y; grp.y[1] = y; grp.rows[0] = (int)rows; grp.rows[1] = (int)rows; grp.count = 2;
+    ops.aux = aux;
+    ops.eps = eps;
+    return for_format<false>(format, [&](auto f) {
+        constexpr int F = decltype(f)::value;
+        switch (x_op) {
+        case IFLOW_X_PLAIN:    return rows_launch<F, 2, 1, false, IFLOW_X_PLAIN, true>(grp, cols, x, s, ops);
+        case IFLOW_X_RMS_GAIN: return rows_launch<F, 2, 1, false, IFLOW_X_RMS_GAIN, true>(grp, cols, x, s, ops);
         default: return hipErrorInvalidValue;
         }
     });

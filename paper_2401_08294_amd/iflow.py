@@ -59,6 +59,7 @@ def lib():
         L.iflow_calibration_copy.argtypes = [p, p, sz, p]
         L.iflow_calibration_read.argtypes = [p, sz, p, p]
         L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
+        L.iflow_qgemv_gated.argtypes = [C.c_int, p, p, i64, i64, p, C.c_int, p, C.c_float, p, p]
         L.iflow_qgemv_fused.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.c_int, p, C.c_float,
                                         C.POINTER(p), C.POINTER(p), p]
         L.iflow_attn_decode_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
@@ -171,6 +172,14 @@ def qgemv_fused(fmt: int, packed_list, rows_list, cols: int, x, y_list, x_op: in
         res = (C.c_void_p * n)(*[(_ptr(t) if t is not None else None) for t in residual_list])
     _check(lib().iflow_qgemv_fused(fmt, n, pk, rs, cols, _ptr(x), x_op, _ptr(aux) if aux is not None else None, eps, res, ys,
                                    _stream(stream)), "iflow_qgemv_fused")
+
+
+def qgemv_gated(fmt: int, packed_gate, packed_up, rows: int, cols: int, x, y, x_op: int = X_PLAIN, aux=None, eps: float = 0.0,
+                stream=None) -> None:
+    """y = silu(c W_gate' v) * (c W_up' v): a gated feed-forward's two first projections and its gate in one launch
+    (v, c: x itself and 1, or the rms-normalized x with gains `aux`)."""
+    _check(lib().iflow_qgemv_gated(fmt, _ptr(packed_gate), _ptr(packed_up), rows, cols, _ptr(x), x_op,
+                                   _ptr(aux) if aux is not None else None, eps, _ptr(y), _stream(stream)), "iflow_qgemv_gated")
 
 
 def attn_decode_workspace_bytes(n_heads: int) -> int:

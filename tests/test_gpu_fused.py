@@ -215,3 +215,54 @@ def test_other_formats_rows_too_long_for_the_staged_activations_are_refused(gpu)
     with pytest.raises(iflow.IflowError) as info:
         iflow.qgemv_fused(fmt, [packed], [rows], cols, x, [y], residual_list=[y])
     assert info.value.status == iflow.ERR_SHAPE
+
+
+def gated_excess(y_bits, w_gate, w_up, v_bits, scale):
+    """Largest |y - silu(g) u| as a multiple of what the product tolerance allows for a product of two row sums: each
+    factor may be off by TOL relative to max(|factor|, rms of its vector) (the bar every plain product is held to), which
+    first-order propagation through silu(g) u turns into TOL (|silu'(g)| max(|g|, rms g) |u| + |silu(g)| max(|u|, rms u)),
+    plus half an fp16 ulp of the result for the one rounding at the store."""
+    from oracle import decode_ops as ops
+    g, u = ops.fused_gemv(w_gate, v_bits, scale), ops.fused_gemv(w_up, v_bits, scale)
+    sig = 1.0 / (1.0 + np.exp(-g))
+    dsilu = sig * (1.0 + g * (1.0 - sig))
+    yref = ops.gated_gemv(w_gate, w_up, v_bits, scale)
+    assert np.max(np.abs(yref - ops.silu(g) * u)) <= 1e-12
+    allowed = TOL * (np.abs(dsilu) * np.maximum(np.abs(g), np.sqrt(np.mean(g * g))) * np.abs(u)
+                     + np.abs(ops.silu(g)) * np.maximum(np.abs(u), np.sqrt(np.mean(u * u)))) + 2.0 ** -11 * np.abs(yref) + 2.0 ** -25
+    y = y_bits.view(np.float16).astype(np.float64)
+    return float(np.max(np.abs(y - yref) / allowed))
+
+
+@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("rows,cols,normalized", [(301, 4096 + 128, True), (5200, 256, False), (77, 11008, True)])
+def test_gated_pair_of_projections(gpu, orc, name, rows, cols, normalized):
+    """iflow_qgemv_gated: silu(gate) * up from the two products in one launch; ragged strips and rows, several row groups
+    per wavefront (5200 rows), three strips (11008 columns)."""
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    fmt = iflow.FORMATS[name]
+    say(f"[case] gated pair {name} rows={rows} cols={cols} rms={normalized}")
+    # gate sums of a few units, so that silu is neither the identity nor zero
+    gate = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 1700 + rows, sigma=2.0 / np.sqrt(cols), name=name)
+    up = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 1701 + rows, name=name)
+    x = synth.activations(1, cols, synth.BASE_SEED + 1702)[0].view(np.uint16)
+    y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
+    if normalized:
+        g = (1.0 + 0.2 * np.random.default_rng(synth.BASE_SEED + 1703).standard_normal(cols)).astype(np.float16).view(np.uint16)
+        iflow.qgemv_gated(fmt, gate[0], up[0], rows, cols, dev16(torch, x), y, iflow.X_RMS_GAIN, dev16(torch, g), 1e-5)
+        v, scale = ops.gain(x, g), ops.rms_scale(x, 1e-5)
+    else:
+        iflow.qgemv_gated(fmt, gate[0], up[0], rows, cols, dev16(torch, x), y)
+        v, scale = x, 1.0
+    torch.cuda.synchronize()
+    e = gated_excess(bits_of(y), gate[1], up[1], v, scale)
+    say(f"        largest error / allowed error {e:.3f}")
+    assert np.isfinite(y.cpu().numpy().astype(np.float32)).all() and e <= 1.0
+    # swapping the two matrices is a different function (the gate acts on the first)
+    if not normalized:
+        y2 = torch.empty_like(y)
+        iflow.qgemv_gated(fmt, up[0], gate[0], rows, cols, dev16(torch, x), y2)
+        torch.cuda.synchronize()
+        assert gated_excess(bits_of(y2), up[1], gate[1], x, 1.0) <= 1.0
+        assert not np.array_equal(bits_of(y), bits_of(y2))

@@ -186,6 +186,24 @@ def test_fused_validation_happens_before_any_launch(iflow):
     assert call(4, [8], 64, x, [y0], residual=[y0 + 1]) == iflow.ERR_ALIGN
 
 
+def test_gated_validation_happens_before_any_launch(iflow):
+    L = iflow.lib()
+    base = 0x100000
+
+    def call(fmt=4, rows=8, cols=64, gate=base, up=base * 2, x=base * 3, y=base * 4, x_op=0, aux=None, eps=0.0):
+        return L.iflow_qgemv_gated(fmt, gate, up, rows, cols, x, x_op, aux, C.c_float(eps), y, None)
+
+    assert call(fmt=9) == iflow.ERR_FORMAT
+    assert call(x_op=iflow.X_SILU_MUL, aux=base * 5) == iflow.ERR_SHAPE          # the gate is this call's own
+    assert call(up=None) == iflow.ERR_NULL and call(y=None) == iflow.ERR_NULL
+    assert call(x_op=iflow.X_RMS_GAIN) == iflow.ERR_NULL and call(aux=base * 5) == iflow.ERR_NULL
+    assert call(x_op=iflow.X_RMS_GAIN, aux=base * 5, eps=-1.0) == iflow.ERR_SHAPE
+    assert call(cols=100) == iflow.ERR_SHAPE and call(rows=0) == iflow.ERR_SHAPE
+    assert call(up=base * 2 + 8) == iflow.ERR_ALIGN
+    assert call(y=base * 3 + 64) == iflow.ERR_SHAPE                              # output inside the activations
+    assert call(fmt=3, cols=65536) == iflow.ERR_SHAPE                            # 4-bit rows too long to stage in LDS
+
+
 def test_attention_validation_happens_before_any_launch(iflow):
     L = iflow.lib()
     base = 0x100000
