@@ -235,7 +235,8 @@ def gated_excess(y_bits, w_gate, w_up, v_bits, scale):
 
 
 @pytest.mark.parametrize("name", NAMES)
-@pytest.mark.parametrize("rows,cols,normalized", [(301, 4096 + 128, True), (5200, 256, False), (77, 11008, True)])
+@pytest.mark.parametrize("rows,cols,normalized", [(301, 4096 + 128, True), (5200, 256, False), (77, 11008, True), (1, 64, True),
+                                                  (3, 192, False)])
 def test_gated_pair_of_projections(gpu, orc, name, rows, cols, normalized):
     """iflow_qgemv_gated: silu(gate) * up from the two products in one launch; ragged strips and rows, several row groups
     per wavefront (5200 rows), three strips (11008 columns)."""
@@ -266,3 +267,24 @@ def test_gated_pair_of_projections(gpu, orc, name, rows, cols, normalized):
         torch.cuda.synchronize()
         assert gated_excess(bits_of(y2), up[1], gate[1], x, 1.0) <= 1.0
         assert not np.array_equal(bits_of(y), bits_of(y2))
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_fused_smallest_shapes(gpu, orc, name):
+    """One row of one or two blocks: every lane but the first few is past the end of the strip."""
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    fmt = iflow.FORMATS[name]
+    for rows, cols in ((1, 64), (2, 128)):
+        say(f"[case] fused smallest {name} rows={rows} cols={cols}")
+        packed, wdeq = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 1900 + cols, sigma=0.1, name=name)
+        x = synth.activations(1, cols, synth.BASE_SEED + 1901)[0].view(np.uint16)
+        g = (1.0 + 0.2 * np.random.default_rng(synth.BASE_SEED + 1902).standard_normal(cols)).astype(np.float16).view(np.uint16)
+        r = synth.activations(1, rows, synth.BASE_SEED + 1903)[0].view(np.uint16)
+        y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
+        iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_RMS_GAIN, dev16(torch, g), 1e-5, [dev16(torch, r)])
+        torch.cuda.synchronize()
+        assert err(bits_of(y), ops.fused_gemv(wdeq, ops.gain(x, g), ops.rms_scale(x, 1e-5), r)) <= TOL
+        iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_SILU_MUL, dev16(torch, g), 0.0)
+        torch.cuda.synchronize()
+        assert err(bits_of(y), ops.fused_gemv(wdeq, ops.silu_mul(x, g), 1.0, None)) <= TOL
