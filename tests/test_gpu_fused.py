@@ -288,3 +288,28 @@ def test_fused_smallest_shapes(gpu, orc, name):
         iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_SILU_MUL, dev16(torch, g), 0.0)
         torch.cuda.synchronize()
         assert err(bits_of(y), ops.fused_gemv(wdeq, ops.silu_mul(x, g), 1.0, None)) <= TOL
+
+
+def test_gated_pair_rows_longer_than_one_staging_pass(gpu, orc):
+    """73 792 columns: the 3.5-bit kernel stages them in two passes and carries the partial sums; the other formats'
+    kernel has no second pass and the call is refused before any launch."""
+    torch, iflow = gpu
+    from oracle import decode_ops as ops
+    rows, cols = 40, 18 * 4096 + 64
+    say(f"[case] gated pair Q3H_B64 rows={rows} cols={cols} (two staging passes)")
+    gate = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 2000, sigma=2.0 / np.sqrt(cols))
+    up = make(torch, iflow, orc, rows, cols, synth.BASE_SEED + 2001)
+    x = synth.activations(1, cols, synth.BASE_SEED + 2002)[0].view(np.uint16)
+    g = (1.0 + 0.2 * np.random.default_rng(synth.BASE_SEED + 2003).standard_normal(cols)).astype(np.float16).view(np.uint16)
+    y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
+    iflow.qgemv_gated(iflow.Q3H_B64, gate[0], up[0], rows, cols, dev16(torch, x), y, iflow.X_RMS_GAIN, dev16(torch, g), 1e-5)
+    torch.cuda.synchronize()
+    e = gated_excess(bits_of(y), gate[1], up[1], ops.gain(x, g), ops.rms_scale(x, 1e-5))
+    say(f"        largest error / allowed error {e:.3f}")
+    assert e <= 1.0
+    fmt = iflow.FORMATS["Q4_B64"]
+    n = iflow.packed_bytes(fmt, rows, cols)
+    packed = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    with pytest.raises(iflow.IflowError) as info:
+        iflow.qgemv_gated(fmt, packed, packed, rows, cols, dev16(torch, x), y)
+    assert info.value.status == iflow.ERR_SHAPE
