@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--separate-gate", action="store_true",
                     help="with --fused: store gate and up and apply silu(gate)*up in front of the down product (iflow_qgemv_fused "
                          "with IFLOW_X_SILU_MUL) instead of producing the gated vector in the gate/up launch (iflow_qgemv_gated)")
+    ap.add_argument("--large-shapes", action="store_true",
+                    help="also time one and eight activation vectors on 70B-shaped matrices (8192x8192, 28672x8192, 8192x28672) in the "
+                         "3.5-, 4- and 8-bit formats (other_paths.large_shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the context figures for batches > 1 and the cache-hot case")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -451,6 +454,46 @@ def main():
                 other["other_formats"]["formats"][oname] = per_batch
                 del copies, first
             del wg
+            # 70B-shaped matrices (one and eight activation vectors): launches long enough not to be bound by their own
+            # start-up; copies of one packed matrix, at least 1.2 GB of them, replayed from a HIP graph
+            if args.large_shapes:
+                other["large_shapes"] = {"what": "70B-shaped matrices, sigma 0.015, copies of one packed matrix (>= 1.2 GB in all), HIP-graph "
+                                             "replay; per format, shape and number of activation vectors: us per product, GB/s of packed "
+                                             "bytes, fraction of the HBM peak", "formats": {}}
+            for oname in (("Q3H_B64", "Q4_B64", "Q8_B64") if args.large_shapes else ()):
+                ofmt = iflow.FORMATS[oname]
+                per_shape = {}
+                for l_rows, l_cols in ((8192, 8192), (28672, 8192), (8192, 28672)):
+                    wl = torch.randn((l_rows, l_cols), generator=gen, device=dev, dtype=torch.float32) * 0.015
+                    nb_l = iflow.packed_bytes(ofmt, l_rows, l_cols)
+                    first = torch.empty(nb_l, dtype=torch.uint8, device=dev)
+                    iflow.quantize(ofmt, wl, l_rows, l_cols, first, nb_l, stream=raw)
+                    del wl
+                    copies = [first] + [first.clone() for _ in range(max(1, int(1.2e9 // nb_l)))]
+                    per_batch = {}
+                    for ob in (1, 8):
+                        Xl = torch.randn((ob, l_cols), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+                        Yl = torch.empty((ob, l_rows), dtype=torch.float16, device=dev)
+                        for pk in copies[:2]:
+                            iflow.qgemm(ofmt, pk, l_rows, l_cols, Xl, ob, Yl, stream=raw)
+                        stream.synchronize()
+                        lgraph = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(lgraph, stream=stream):
+                            for pk in copies:
+                                iflow.qgemm(ofmt, pk, l_rows, l_cols, Xl, ob, Yl, stream=raw)
+                        lgraph.replay()
+                        t0.record(stream)
+                        for _ in range(6):
+                            lgraph.replay()
+                        t1.record(stream)
+                        t1.synchronize()
+                        us = t0.elapsed_time(t1) * 1e3 / (6 * len(copies))
+                        per_batch[str(ob)] = {"us": round(us, 2), "GB/s": round(nb_l / us / 1e3, 1),
+                                              "frac_of_hbm_peak": round(nb_l / us / 1e3 / HBM_PEAK_GBPS, 4)}
+                        del lgraph
+                    per_shape[f"{l_rows}x{l_cols}"] = per_batch
+                    del copies, first
+                other["large_shapes"]["formats"][oname] = per_shape
             w1 = torch.randn((1024, 1024), generator=gen, device=dev, dtype=torch.float32) * SIGMA
             n1 = iflow.packed_bytes(fmt, 1024, 1024)
             p1 = torch.empty(n1, dtype=torch.uint8, device=dev)
