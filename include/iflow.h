@@ -211,6 +211,19 @@ iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, con
                                  int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
                                  uint16_t *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* iflow_attn_decode for callers that cannot allocate device memory or hand a workspace over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same results, bit
+ * for bit; the partial results of the position ranges go to a device array that is part of the library's code object
+ * (IFLOW_ATTN_STATIC_MAX_HEADS * 130 * 64 floats = 4 259 840 bytes, held by every device the library is loaded on
+ * until the process ends) instead of a workspace.  n_heads above IFLOW_ATTN_STATIC_MAX_HEADS is IFLOW_ERR_SIZE.  The call
+ * allocates nothing and frees nothing.  Every call on a device shares that device's array: calls must be ordered (one
+ * stream, or events between streams); calls that overlap on one device race and their outputs are unspecified.  Nothing
+ * in the array has to be cleared between calls (a call reads only what it has written itself). */
+#define IFLOW_ATTN_STATIC_MAX_HEADS 128
+iflow_status_t iflow_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads,
+                                        int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
+                                        uint16_t *out, void *stream);
+
 /* Rotary position embedding for one decode step, and the step's append to the key/value cache (Section 2's table of
  * configurable modules: position_embedding = "rope"): the launch that sits between the q/k/v projections and
  * iflow_attn_decode.  Pair i (0..63) of a head's 128 components at position p is rotated by the angle p * base^(-2i/128):

@@ -272,6 +272,23 @@ iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, con
                                                    (hipStream_t)stream));
 }
 
+iflow_status_t iflow_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads,
+                                        int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
+                                        uint16_t *out, void *stream)
+{
+    if (head_dim != 128) return IFLOW_ERR_SHAPE;
+    if (n_kv_heads < 1 || n_kv_heads > 64 || n_heads < 1 || n_heads > 512 || n_heads % n_kv_heads != 0) return IFLOW_ERR_SHAPE;
+    const int group = n_heads / n_kv_heads;
+    if (group != 1 && group != 2 && group != 4 && group != 8) return IFLOW_ERR_SHAPE;
+    if (seq_len < 1 || max_seq < seq_len || max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
+    if (!(scale > 0.0f && scale < 3.0e38f)) return IFLOW_ERR_SHAPE;
+    if (!q || !k_cache || !v_cache || !out) return IFLOW_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return IFLOW_ERR_ALIGN;
+    if (n_heads > IFLOW_ATTN_STATIC_MAX_HEADS) return IFLOW_ERR_SIZE;      // more partial results than the library's own array holds
+    return device_status(iflow::launch_attn_decode_static(q, k_cache, v_cache, n_heads, n_kv_heads, seq_len, max_seq, scale, out,
+                                                          (hipStream_t)stream));
+}
+
 iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads,
                                  int head_dim, int64_t position, int64_t max_seq, float base, iflow_rope_pairing_t pair_mode,
                                  uint16_t *k_cache, uint16_t *v_cache, void *stream)

@@ -425,4 +425,36 @@ hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const 
     return hipGetLastError();
 }
 
+// ---- the same call for callers that cannot allocate ------------------------------------------------------------
+// The partial results of the position ranges live in a file-scope device array instead of a caller's workspace.  In
+// host code the array's name is only a handle: its device address is asked for once per device (each device holds its
+// own copy at its own address) and only that address is ever handed to a kernel.
+constexpr int ATT_STATIC_MAX_HEADS = IFLOW_ATTN_STATIC_MAX_HEADS;
+static __device__ __align__(256) float scratch[(size_t)ATT_STATIC_MAX_HEADS * (ATT_D + 2) * ATT_MAX_SPLITS];
+
+hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
+                                     int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s)
+{
+    static std::mutex lock;
+    static float *address[IFLOW_MAX_DEVICES] = {};
+    if (n_heads < 1 || n_heads > ATT_STATIC_MAX_HEADS) return hipErrorInvalidValue;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= IFLOW_MAX_DEVICES) return hipErrorInvalidDevice;
+    float *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> hold(lock);
+        if (!address[dev]) {
+            void *sym = nullptr;
+            e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!sym) return hipErrorInvalidSymbol;
+            address[dev] = static_cast<float *>(sym);
+        }
+        ptr = address[dev];
+    }
+    return launch_attn_decode(q, k_cache, v_cache, n_heads, n_kv_heads, seq_len, max_seq, scale, out, ptr, s);
+}
+
 }  // namespace iflow

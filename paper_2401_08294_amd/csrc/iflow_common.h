@@ -221,6 +221,8 @@ hipError_t launch_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t
 size_t attn_workspace_bytes(int n_heads);
 hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
                               int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s);
+hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
+                                     int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s);
 size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
 hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
                               const void *const *packed, const int64_t *rows, uint16_t *const *y,

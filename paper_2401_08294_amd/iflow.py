@@ -21,6 +21,7 @@ BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 
 
 OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE, ERR_TIMEOUT = range(8)
 CHAIN_MAX_PHASES, CHAIN_MAX_MATRICES = 32, 56
+ATTN_STATIC_MAX_HEADS = 128
 
 
 class IflowError(RuntimeError):
@@ -64,6 +65,7 @@ def lib():
                                         C.POINTER(p), C.POINTER(p), p]
         L.iflow_attn_decode_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
         L.iflow_attn_decode.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p, sz, p]
+        L.iflow_attn_decode_static.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p]
         L.iflow_rope_append.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, C.c_int, p, p, p]
         L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
         L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
@@ -193,6 +195,13 @@ def attn_decode(q, k_cache, v_cache, n_heads: int, n_kv_heads: int, head_dim: in
     """One decode step of grouped-query attention over an fp16 key/value cache [n_kv_heads][max_seq][head_dim]."""
     _check(lib().iflow_attn_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), n_heads, n_kv_heads, head_dim, seq_len, max_seq, scale,
                                    _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)), "iflow_attn_decode")
+
+
+def attn_decode_static(q, k_cache, v_cache, n_heads: int, n_kv_heads: int, head_dim: int, seq_len: int, max_seq: int, scale: float,
+                       out, stream=None) -> None:
+    """attn_decode without a workspace argument: the partial results live in an array inside the library (no allocation)."""
+    _check(lib().iflow_attn_decode_static(_ptr(q), _ptr(k_cache), _ptr(v_cache), n_heads, n_kv_heads, head_dim, seq_len, max_seq,
+                                          scale, _ptr(out), _stream(stream)), "iflow_attn_decode_static")
 
 
 def rope_append(q, k_new, v_new, n_heads: int, n_kv_heads: int, head_dim: int, position: int, max_seq: int, base: float,
