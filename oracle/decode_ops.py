@@ -14,9 +14,13 @@ LLaMA-family models its decode step (Section 5, ``Infer()``) runs.  So the textb
   gated pair         out_n = silu(scale (W_gate v)_n) * (scale (W_up v)_n)      (the gate applied where its two
                      projections are produced, before either is stored)
 
-The fused kernel applies the normalization as (x_k * g_k) rounded to fp16, multiplied by the matrix, and the scalar
-1 / sqrt(mean x^2 + eps) applied to the fp32 row sums (the scalar commutes with the matrix product).  The functions
-below state exactly that split, in fp64, with fp16 roundings only where a value is stored as fp16.
+The definitions that parity is judged by are the unsplit ones - ``rms_linear``, ``silu_linear``, ``gated_rms`` - evaluated
+in fp64 from the fp16 inputs with no rounding anywhere in between: they know nothing of how a kernel orders the work.
+
+A second, narrower set (``gain``, ``rms_scale``, ``silu_mul``, ``fused_gemv``, ``gated_gemv``) states one particular
+evaluation order with its fp16 roundings - normalization as fp16(x_k g_k) in front of the matrix and the scalar
+1 / sqrt(mean x^2 + eps) behind it (the scalar commutes with the matrix product), the gated input rounded to fp16 before the
+product.  Tests use it only as an additional, tighter check of where a kernel's error comes from; it decides nothing.
 All fp16 inputs and outputs are uint16 bit patterns, like everywhere else in the oracle.
 """
 from __future__ import annotations
@@ -32,6 +36,38 @@ def _h(x) -> np.ndarray:
     """fp64 -> fp16 bits, one rounding to nearest-even."""
     return np.asarray(x, dtype=np.float64).astype(np.float16).view(np.uint16)
 
+
+# ---- the definitions (no intermediate rounding) ---------------------------------------------------------------------
+
+def rms_norm(x16_bits, g16_bits, eps: float) -> np.ndarray:
+    """x_k g_k / sqrt(mean_j x_j^2 + eps) in fp64."""
+    x = _f(x16_bits)
+    return x * _f(g16_bits) / np.sqrt(np.mean(x * x) + eps)
+
+
+def rms_linear(w16_bits, x16_bits, g16_bits, eps: float, residual16_bits=None) -> np.ndarray:
+    """W' rms_norm(x; g, eps) (+ residual) in fp64: a linear layer behind an rms normalization."""
+    y = _f(w16_bits) @ rms_norm(x16_bits, g16_bits, eps)
+    if residual16_bits is not None:
+        y = y + _f(residual16_bits)
+    return y
+
+
+def silu_linear(w16_bits, a16_bits, b16_bits, residual16_bits=None) -> np.ndarray:
+    """W' (silu(a) * b) (+ residual) in fp64: the last projection of a gated feed-forward from its two hidden vectors."""
+    y = _f(w16_bits) @ (silu(_f(a16_bits)) * _f(b16_bits))
+    if residual16_bits is not None:
+        y = y + _f(residual16_bits)
+    return y
+
+
+def gated_rms(w_gate16_bits, w_up16_bits, x16_bits, g16_bits=None, eps: float = 0.0) -> np.ndarray:
+    """silu(W_gate' n) * (W_up' n) in fp64, n = rms_norm(x; g, eps), or n = x when g16_bits is None."""
+    n = _f(x16_bits) if g16_bits is None else rms_norm(x16_bits, g16_bits, eps)
+    return silu(_f(w_gate16_bits) @ n) * (_f(w_up16_bits) @ n)
+
+
+# ---- one evaluation order with its fp16 roundings (secondary checks only) -------------------------------------------
 
 def rms_scale(x16_bits, eps: float) -> float:
     """1 / sqrt(mean_k x_k^2 + eps), fp64."""

@@ -557,6 +557,52 @@ def test_gated_gemv_is_the_library_feed_forward_gate(orc):
     assert abs(float(ops.gated_gemv(_bits(big), _bits(one), _bits(e))[0]) - 40.0) < 1e-10
 
 
+def test_unsplit_layer_definitions_are_the_library_compositions(orc):
+    """rms_linear / silu_linear / gated_rms - the definitions GPU parity is judged by - against torch's own rms_norm, linear
+    and silu composed in fp64, and against special cases a dropped term, a swapped operand or a misplaced eps would break."""
+    import torch
+    import torch.nn.functional as F
+    from oracle import decode_ops as ops
+    rng = np.random.default_rng(81)
+    rows, cols = 23, 320
+    w = (0.2 * rng.standard_normal((rows, cols))).astype(np.float16)
+    w2 = (0.2 * rng.standard_normal((rows, cols))).astype(np.float16)
+    x = (2.0 * rng.standard_normal(cols)).astype(np.float16)
+    g = (1.0 + 0.3 * rng.standard_normal(cols)).astype(np.float16)
+    r = rng.standard_normal(rows).astype(np.float16)
+    a = (2.0 * rng.standard_normal(cols)).astype(np.float16)
+    t = lambda v: torch.from_numpy(v.astype(np.float64))
+    eps = 1e-3
+    n_ref = F.rms_norm(t(x), (cols,), weight=t(g), eps=eps)
+    assert np.max(np.abs(ops.rms_norm(_bits(x), _bits(g), eps) - n_ref.numpy())) <= 1e-13
+    ref = (F.linear(n_ref, t(w)) + t(r)).numpy()
+    assert np.max(np.abs(ops.rms_linear(_bits(w), _bits(x), _bits(g), eps, _bits(r)) - ref)) <= 1e-12
+    assert np.max(np.abs(ops.rms_linear(_bits(w), _bits(x), _bits(g), eps) - F.linear(n_ref, t(w)).numpy())) <= 1e-12
+    ref = (F.linear(F.silu(t(a)) * t(x), t(w)) + t(r)).numpy()
+    assert np.max(np.abs(ops.silu_linear(_bits(w), _bits(a), _bits(x), _bits(r)) - ref)) <= 1e-12
+    assert np.max(np.abs(ops.silu_linear(_bits(w), _bits(a), _bits(x)) - ops.silu_linear(_bits(w), _bits(x), _bits(a)))) > 1e-3
+    ref = (F.silu(F.linear(n_ref, t(w))) * F.linear(n_ref, t(w2))).numpy()
+    assert np.max(np.abs(ops.gated_rms(_bits(w), _bits(w2), _bits(x), _bits(g), eps) - ref)) <= 1e-12
+    ref = (F.silu(F.linear(t(x), t(w))) * F.linear(t(x), t(w2))).numpy()
+    assert np.max(np.abs(ops.gated_rms(_bits(w), _bits(w2), _bits(x)) - ref)) <= 1e-11
+    # special cases: unit gains and eps = 0 on a vector of +-c: the normalized vector is sign(x), so W n = W sign(x) exactly
+    c = np.where(rng.random(cols) < 0.5, -3.0, 3.0).astype(np.float16)
+    ones = np.ones(cols, np.float16)
+    want = orc.gemm(_bits(w), _bits(np.sign(c).astype(np.float16)))[0]
+    assert np.max(np.abs(ops.rms_linear(_bits(w), _bits(c), _bits(ones), 0.0) - want)) <= 1e-12
+    # eps sits under the root, next to the mean: mean x^2 = 9, eps = 7 -> divide by 4
+    assert np.max(np.abs(ops.rms_linear(_bits(w), _bits(c), _bits(ones), 7.0) - 0.75 * want)) <= 1e-12
+    # scaling x leaves the normalized product unchanged when eps = 0; the gains act per column (not per row)
+    assert np.max(np.abs(ops.rms_linear(_bits(w), _bits(2 * x), _bits(g), 0.0) - ops.rms_linear(_bits(w), _bits(x), _bits(g), 0.0))) <= 1e-12
+    e5 = np.zeros(cols, np.float16); e5[5] = 1.0
+    only5 = ops.rms_linear(_bits(w), _bits(x), _bits(e5), 0.0)
+    assert np.max(np.abs(only5 - w[:, 5].astype(np.float64) * float(x[5]) * ops.rms_scale(_bits(x), 0.0))) <= 1e-13
+    # the split evaluation order (fp16(x g) in front, scalar behind) agrees with the definition up to that one rounding
+    split = ops.fused_gemv(_bits(w), ops.gain(_bits(x), _bits(g)), ops.rms_scale(_bits(x), eps), _bits(r))
+    full = ops.rms_linear(_bits(w), _bits(x), _bits(g), eps, _bits(r))
+    assert 0 < np.max(np.abs(split - full)) <= 2.0 ** -11 * np.sum(np.abs(w.astype(np.float64)), axis=1).max() * 8.0
+
+
 # ---- grouped-query attention for one decode step (oracle/attention.py) ----
 def test_gqa_decode_matches_the_library_routine_and_special_cases():
     import torch
