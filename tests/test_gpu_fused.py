@@ -46,10 +46,10 @@ def test_rms_gain_in_front_of_the_product(gpu, orc, rows, cols, with_residual):
     iflow.qgemv_fused(iflow.Q3H_B64, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_RMS_GAIN, dev16(torch, g), eps,
                       [dev16(torch, r)] if with_residual else None)
     torch.cuda.synchronize()
-    yref = ops.fused_gemv(wdeq, ops.gain(x, g), ops.rms_scale(x, eps), r)
-    e = err(bits_of(y), yref)
-    say(f"        max rel err {e:.3e}")
-    assert np.isfinite(y.cpu().numpy().astype(np.float32)).all() and e <= TOL
+    e = err(bits_of(y), ops.rms_linear(wdeq, x, g, eps, r))                  # the definition: no rounding between norm and product
+    e_split = err(bits_of(y), ops.fused_gemv(wdeq, ops.gain(x, g), ops.rms_scale(x, eps), r))
+    say(f"        max rel err {e:.3e} against the definition, {e_split:.3e} against the evaluation order with fp16(x g)")
+    assert np.isfinite(y.cpu().numpy().astype(np.float32)).all() and e <= TOL and e_split <= TOL
 
 
 @pytest.mark.parametrize("rows,cols", [(300, 1024), (520, 11008)])
@@ -64,10 +64,10 @@ def test_silu_gated_input_and_in_place_residual(gpu, orc, rows, cols):
     hidden = dev16(torch, h).clone()                           # updated in place: residual and output are the same buffer
     iflow.qgemv_fused(iflow.Q3H_B64, [packed], [rows], cols, dev16(torch, a), [hidden], iflow.X_SILU_MUL, dev16(torch, b), 0.0, [hidden])
     torch.cuda.synchronize()
-    yref = ops.fused_gemv(wdeq, ops.silu_mul(a, b), 1.0, h)
-    e = err(bits_of(hidden), yref)
-    say(f"        max rel err {e:.3e}")
-    assert e <= TOL
+    e = err(bits_of(hidden), ops.silu_linear(wdeq, a, b, h))
+    e_split = err(bits_of(hidden), ops.fused_gemv(wdeq, ops.silu_mul(a, b), 1.0, h))
+    say(f"        max rel err {e:.3e} against the definition, {e_split:.3e} against the evaluation order with fp16(silu(a) b)")
+    assert e <= TOL and e_split <= TOL
 
 
 def test_two_matrices_share_the_normalized_input_and_plain_with_residual(gpu, orc):
@@ -84,9 +84,8 @@ def test_two_matrices_share_the_normalized_input_and_plain_with_residual(gpu, or
     iflow.qgemv_fused(iflow.Q3H_B64, [m[0] for m in mats], rows, cols, dev16(torch, x), ys, iflow.X_RMS_GAIN, dev16(torch, g), 1e-6,
                       [None, dev16(torch, res1)])
     torch.cuda.synchronize()
-    v, sc = ops.gain(x, g), ops.rms_scale(x, 1e-6)
-    assert err(bits_of(ys[0]), ops.fused_gemv(mats[0][1], v, sc, None)) <= TOL
-    assert err(bits_of(ys[1]), ops.fused_gemv(mats[1][1], v, sc, res1)) <= TOL
+    assert err(bits_of(ys[0]), ops.rms_linear(mats[0][1], x, g, 1e-6)) <= TOL
+    assert err(bits_of(ys[1]), ops.rms_linear(mats[1][1], x, g, 1e-6, res1)) <= TOL
     # no operation on x: equals iflow_qgemv when there is no residual, bit for bit
     y0 = torch.empty((rows[0],), dtype=torch.float16, device="cuda")
     y1 = torch.empty((rows[0],), dtype=torch.float16, device="cuda")
@@ -129,14 +128,13 @@ def test_feed_forward_block_at_7b_size(gpu, orc):
     iflow.qgemv_fused(fmt, [mats[0][0], mats[1][0]], [ffn, ffn], hidden, hd, [gate, up], iflow.X_RMS_GAIN, gd, 1e-5)
     iflow.qgemv_fused(fmt, [mats[2][0]], [hidden], ffn, gate, [out], iflow.X_SILU_MUL, up, 0.0, [hd])
     torch.cuda.synchronize()
-    v, sc = ops.gain(h, g), ops.rms_scale(h, 1e-5)
     for t, m in ((gate, mats[0]), (up, mats[1])):
         full = t.cpu().numpy().astype(np.float64)
-        want = ops.fused_gemv(m[4], v, sc, None)
+        want = ops.rms_linear(m[4], h, g, 1e-5)
         assert np.max(np.abs(full[m[3]] - want) / np.maximum(np.abs(want), np.sqrt(np.mean(full ** 2)))) <= TOL
     m = mats[2]
     full = out.cpu().numpy().astype(np.float64)
-    want = ops.fused_gemv(m[4], ops.silu_mul(bits_of(gate), bits_of(up)), 1.0, h[m[3]])
+    want = ops.silu_linear(m[4], bits_of(gate), bits_of(up), h[m[3]])
     e = float(np.max(np.abs(full[m[3]] - want) / np.maximum(np.abs(want), np.sqrt(np.mean(full ** 2)))))
     say(f"        down + residual: max rel err on sampled rows {e:.3e}")
     assert np.isfinite(full).all() and e <= TOL
@@ -161,9 +159,8 @@ def test_other_formats_rms_gain_two_matrices_and_residual(gpu, orc, name):
     iflow.qgemv_fused(fmt, [m[0] for m in mats], rows, cols, dev16(torch, x), ys, iflow.X_RMS_GAIN, dev16(torch, g), 1e-5,
                       [None, dev16(torch, res1)])
     torch.cuda.synchronize()
-    v, sc = ops.gain(x, g), ops.rms_scale(x, 1e-5)
-    e0 = err(bits_of(ys[0]), ops.fused_gemv(mats[0][1], v, sc, None))
-    e1 = err(bits_of(ys[1]), ops.fused_gemv(mats[1][1], v, sc, res1))
+    e0 = err(bits_of(ys[0]), ops.rms_linear(mats[0][1], x, g, 1e-5))
+    e1 = err(bits_of(ys[1]), ops.rms_linear(mats[1][1], x, g, 1e-5, res1))
     say(f"        max rel err {e0:.3e} {e1:.3e}")
     assert e0 <= TOL and e1 <= TOL
     # one matrix per launch gives the same bits
@@ -188,7 +185,7 @@ def test_other_formats_silu_gate_in_place_residual_and_plain(gpu, orc, name):
     hidden = dev16(torch, h).clone()
     iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, a), [hidden], iflow.X_SILU_MUL, dev16(torch, b), 0.0, [hidden])
     torch.cuda.synchronize()
-    e = err(bits_of(hidden), ops.fused_gemv(wdeq, ops.silu_mul(a, b), 1.0, h))
+    e = err(bits_of(hidden), ops.silu_linear(wdeq, a, b, h))
     say(f"        max rel err {e:.3e}")
     assert e <= TOL
     # no operation and no residual: iflow_qgemv's bits; with a residual: the definition
@@ -217,16 +214,20 @@ def test_other_formats_rows_too_long_for_the_staged_activations_are_refused(gpu)
     assert info.value.status == iflow.ERR_SHAPE
 
 
-def gated_excess(y_bits, w_gate, w_up, v_bits, scale):
-    """Largest |y - silu(g) u| as a multiple of what the product tolerance allows for a product of two row sums: each
+def gated_excess(y_bits, w_gate, w_up, x_bits, g_bits=None, eps=0.0):
+    """The reference is the definition silu(W_gate n) (W_up n) with n = rms_norm(x; g, eps) (n = x without gains), no
+    rounding in between.  Largest |y - silu(g) u| as a multiple of what the product tolerance allows for a product of two row sums: each
     factor may be off by TOL relative to max(|factor|, rms of its vector) (the bar every plain product is held to), which
     first-order propagation through silu(g) u turns into TOL (|silu'(g)| max(|g|, rms g) |u| + |silu(g)| max(|u|, rms u)),
     plus half an fp16 ulp of the result for the one rounding at the store."""
     from oracle import decode_ops as ops
-    g, u = ops.fused_gemv(w_gate, v_bits, scale), ops.fused_gemv(w_up, v_bits, scale)
+    if g_bits is None:
+        g, u = ops.fused_gemv(w_gate, x_bits), ops.fused_gemv(w_up, x_bits)
+    else:
+        g, u = ops.rms_linear(w_gate, x_bits, g_bits, eps), ops.rms_linear(w_up, x_bits, g_bits, eps)
     sig = 1.0 / (1.0 + np.exp(-g))
     dsilu = sig * (1.0 + g * (1.0 - sig))
-    yref = ops.gated_gemv(w_gate, w_up, v_bits, scale)
+    yref = ops.gated_rms(w_gate, w_up, x_bits, g_bits, eps)
     assert np.max(np.abs(yref - ops.silu(g) * u)) <= 1e-12
     allowed = TOL * (np.abs(dsilu) * np.maximum(np.abs(g), np.sqrt(np.mean(g * g))) * np.abs(u)
                      + np.abs(ops.silu(g)) * np.maximum(np.abs(u), np.sqrt(np.mean(u * u)))) + 2.0 ** -11 * np.abs(yref) + 2.0 ** -25
@@ -252,12 +253,11 @@ def test_gated_pair_of_projections(gpu, orc, name, rows, cols, normalized):
     if normalized:
         g = (1.0 + 0.2 * np.random.default_rng(synth.BASE_SEED + 1703).standard_normal(cols)).astype(np.float16).view(np.uint16)
         iflow.qgemv_gated(fmt, gate[0], up[0], rows, cols, dev16(torch, x), y, iflow.X_RMS_GAIN, dev16(torch, g), 1e-5)
-        v, scale = ops.gain(x, g), ops.rms_scale(x, 1e-5)
     else:
+        g = None
         iflow.qgemv_gated(fmt, gate[0], up[0], rows, cols, dev16(torch, x), y)
-        v, scale = x, 1.0
     torch.cuda.synchronize()
-    e = gated_excess(bits_of(y), gate[1], up[1], v, scale)
+    e = gated_excess(bits_of(y), gate[1], up[1], x, g, 1e-5)
     say(f"        largest error / allowed error {e:.3f}")
     assert np.isfinite(y.cpu().numpy().astype(np.float32)).all() and e <= 1.0
     # swapping the two matrices is a different function (the gate acts on the first)
@@ -265,7 +265,7 @@ def test_gated_pair_of_projections(gpu, orc, name, rows, cols, normalized):
         y2 = torch.empty_like(y)
         iflow.qgemv_gated(fmt, up[0], gate[0], rows, cols, dev16(torch, x), y2)
         torch.cuda.synchronize()
-        assert gated_excess(bits_of(y2), up[1], gate[1], x, 1.0) <= 1.0
+        assert gated_excess(bits_of(y2), up[1], gate[1], x) <= 1.0
         assert not np.array_equal(bits_of(y), bits_of(y2))
 
 
@@ -284,10 +284,10 @@ def test_fused_smallest_shapes(gpu, orc, name):
         y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
         iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_RMS_GAIN, dev16(torch, g), 1e-5, [dev16(torch, r)])
         torch.cuda.synchronize()
-        assert err(bits_of(y), ops.fused_gemv(wdeq, ops.gain(x, g), ops.rms_scale(x, 1e-5), r)) <= TOL
+        assert err(bits_of(y), ops.rms_linear(wdeq, x, g, 1e-5, r)) <= TOL
         iflow.qgemv_fused(fmt, [packed], [rows], cols, dev16(torch, x), [y], iflow.X_SILU_MUL, dev16(torch, g), 0.0)
         torch.cuda.synchronize()
-        assert err(bits_of(y), ops.fused_gemv(wdeq, ops.silu_mul(x, g), 1.0, None)) <= TOL
+        assert err(bits_of(y), ops.silu_linear(wdeq, x, g)) <= TOL
 
 
 def test_gated_pair_rows_longer_than_one_staging_pass(gpu, orc):
@@ -304,7 +304,7 @@ def test_gated_pair_rows_longer_than_one_staging_pass(gpu, orc):
     y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
     iflow.qgemv_gated(iflow.Q3H_B64, gate[0], up[0], rows, cols, dev16(torch, x), y, iflow.X_RMS_GAIN, dev16(torch, g), 1e-5)
     torch.cuda.synchronize()
-    e = gated_excess(bits_of(y), gate[1], up[1], ops.gain(x, g), ops.rms_scale(x, 1e-5))
+    e = gated_excess(bits_of(y), gate[1], up[1], x, g, 1e-5)
     say(f"        largest error / allowed error {e:.3f}")
     assert e <= 1.0
     fmt = iflow.FORMATS["Q4_B64"]

@@ -80,10 +80,9 @@ def test_three_decode_steps_stage_by_stage(gpu, orc, name):
         run = layer.launches(h, kc, vc, position)
         h0 = bits_of(h).copy()
         run[0](); sync()
-        vin, sc = ops.gain(h0, layer.g1), ops.rms_scale(h0, EPS)
         q0, k0, v0 = bits_of(layer.q).copy(), bits_of(layer.k).copy(), bits_of(layer.v).copy()
         for got, key in ((q0, "q"), (k0, "k"), (v0, "v")):
-            assert err(got, ops.fused_gemv(layer.w[key][1], vin, sc, None)) <= TOL, key
+            assert err(got, ops.rms_linear(layer.w[key][1], h0, layer.g1, EPS)) <= TOL, key
         okc, ovc = bits_of(kc).copy(), bits_of(vc).copy()
         run[1](); sync()
         q_rot = R.rope_append(q0.reshape(N_HEADS, D), k0.reshape(N_KV, D), v0.reshape(N_KV, D), position, BASE, iflow.ROPE_HALVES, okc, ovc)
@@ -96,7 +95,7 @@ def test_three_decode_steps_stage_by_stage(gpu, orc, name):
         assert err(bits_of(h), ops.fused_gemv(layer.w["o"][1], ao, 1.0, h0)) <= TOL
         h1 = bits_of(h).copy()
         run[4](); sync()
-        assert gated_excess(bits_of(layer.hv), layer.w["gate"][1], layer.w["up"][1], ops.gain(h1, layer.g2), ops.rms_scale(h1, EPS)) <= 1.0
+        assert gated_excess(bits_of(layer.hv), layer.w["gate"][1], layer.w["up"][1], h1, layer.g2, EPS) <= 1.0
         hv = bits_of(layer.hv).copy()
         run[5](); sync()
         assert err(bits_of(h), ops.fused_gemv(layer.w["down"][1], hv, 1.0, h1)) <= TOL

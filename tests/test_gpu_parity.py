@@ -376,6 +376,68 @@ def test_full_size_sampled_rows(gpu, orc, rows, cols, sigma):
     assert np.array_equal(y2, 2 * y)
 
 
+# ---- config 3 at its full 7B shapes: 8-bit, 4-bit and one bit-plane format, one to sixteen vectors, outliers ----
+@pytest.mark.parametrize("name", ["Q4_B64", "Q8_B64", "Q6_B64"])
+@pytest.mark.parametrize("rows,cols", [(4096, 4096), (11008, 4096), (4096, 11008)])
+def test_config3_full_size_sampled_rows(gpu, orc, name, rows, cols):
+    """The launches the benchmark times for the formats other than 3.5-bit (thousands of rows and several strips at once:
+    more than one row group per wavefront), checked on sampled rows: packed bytes and fp16 weights bit-exact, products at 1,
+    2, 4, 8 and 16 vectors within tolerance, every output finite."""
+    torch, iflow = gpu
+    fmt, ofmt = iflow.FORMATS[name], orc.FORMATS[name]
+    say(f"[case] config-3 full size fmt={name} rows={rows} cols={cols}, 0.1 % outliers x 10")
+    w = synth.weights(rows, cols, 0.02, synth.BASE_SEED + 3000 + rows + cols, outlier_prob=0.001)
+    packed, got_bytes = gpu_quantize(torch, iflow, fmt, w)
+    idx = synth.sample_rows(rows, 96, synth.BASE_SEED + 3001)
+    q, s, o = orc.quantize(ofmt, w[idx])
+    lv, sc, of = gpu_unpack(torch, iflow, fmt, packed, rows, cols)     # layout-independent: levels and headers of the sampled rows
+    assert np.array_equal(lv[idx], q) and np.array_equal(sc[idx], s) and np.array_equal(of[idx], o)
+    del lv, sc, of
+    if name == "Q3H_B64":                                              # (formats whose rows are contiguous in the packed buffer)
+        row_bytes = orc.packed_bytes(ofmt, 1, cols)
+        assert np.array_equal(got_bytes.reshape(rows, row_bytes)[idx], orc.pack_device(ofmt, q, s, o).reshape(len(idx), row_bytes))
+    ref_deq = orc.dequant(ofmt, q, s, o)
+    deq = gpu_dequant(torch, iflow, fmt, packed, rows, cols)
+    assert np.array_equal(deq[idx], ref_deq)
+    del deq
+    for batch in (1, 2, 4, 8, 16):
+        x = synth.activations(batch, cols, synth.BASE_SEED + 3002 + batch)
+        y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x)
+        yref = orc.gemm(ref_deq, x.view(np.uint16), threads=8)
+        e = rel_err(y[:, idx], yref)
+        say(f"        batch {batch}: max rel err on {len(idx)} sampled rows {e:.3e}")
+        assert np.isfinite(y).all() and e <= TOL
+
+
+@pytest.mark.parametrize("name", ["Q4_B64", "Q8_B64"])
+def test_config3_formats_at_a_70b_shape(gpu, orc, name):
+    """28672 x 8192, one vector, in the 4- and 8-bit formats: the launch geometry of the tallest matrix the benchmark times."""
+    torch, iflow = gpu
+    fmt, ofmt = iflow.FORMATS[name], orc.FORMATS[name]
+    rows, cols = 28672, 8192
+    say(f"[case] 70B-shape fmt={name} rows={rows} cols={cols}, 0.1 % outliers x 10")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 3100)
+    wd = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.015
+    wd = torch.where(torch.rand((rows, cols), generator=gen, device="cuda") < 0.001, wd * 10.0, wd)
+    n = iflow.packed_bytes(fmt, rows, cols)
+    packed = torch.empty(n, dtype=torch.uint8, device="cuda")
+    iflow.quantize(fmt, wd, rows, cols, packed, n)
+    idx = synth.sample_rows(rows, 64, synth.BASE_SEED + 3101)
+    w_rows = wd[torch.from_numpy(idx).cuda()].cpu().numpy()
+    del wd
+    q, s, o = orc.quantize(ofmt, w_rows)
+    lv, sc, of = gpu_unpack(torch, iflow, fmt, packed, rows, cols)
+    assert np.array_equal(lv[idx], q) and np.array_equal(sc[idx], s) and np.array_equal(of[idx], o)
+    del lv, sc, of
+    ref_deq = orc.dequant(ofmt, q, s, o)
+    x = synth.activations(1, cols, synth.BASE_SEED + 3102)
+    y = gpu_gemm(torch, iflow, fmt, packed, rows, cols, x)
+    e = rel_err(y[:, idx], orc.gemm(ref_deq, x.view(np.uint16), threads=8))
+    say(f"        max rel err on {len(idx)} sampled rows {e:.3e}")
+    assert np.isfinite(y).all() and e <= TOL
+
+
 # ---- 70B-shaped layers (config 4): sampled rows, batch 1 and 8 ----------------------------------------------
 @pytest.mark.parametrize("rows,cols", [(28672, 8192), (8192, 28672)])
 def test_70b_shapes_sampled_rows(gpu, orc, rows, cols):
