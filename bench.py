@@ -34,12 +34,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1600)
     ap.add_argument("--warmup", type=int, default=160)
-    ap.add_argument("--ring", type=int, default=16, help="distinct layers in the weight ring (16 = 1.5 GiB packed)")
+    ap.add_argument("--ring", type=int, default=32, help="distinct layers in the weight ring (32 = a whole 7B-shaped stack, 3.0 GiB packed)")
     ap.add_argument("--format", default="Q3H_B64")
     ap.add_argument("--launches", type=int, default=1, choices=(1, 4, 7),
                     help="launches per layer: 7 = one per matrix; 4 = q,k,v in one iflow_qgemv_multi launch, o, gate+up in one, down")
-    ap.add_argument("--layers-per-launch", type=int, default=8, choices=(1, 2, 4, 8),
-                    help="with --launches 1: chain this many layers into one launch (the next layer's q/k/v read down's output)")
+    ap.add_argument("--layers-per-launch", type=int, default=32,
+                    help="with --launches 1: chain this many layers into one launch (the next layer's q/k/v read down's output); "
+                         "32 = the whole stack, one decode step's weight stream in one launch")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--context", type=int, default=0,
                     help="with --fused: also run iflow_attn_decode (32 heads of 128) over a cache of this many positions per layer, "
@@ -94,7 +95,8 @@ def cpu_baseline(fmt_name: str, reps: int = 3):
     t0 = time.perf_counter()
     oracle.qgemm_canonical(ofmt, rec, rows, cols, x.view(np.uint16), threads=1)
     single = algorithmic_bytes(rows, cols, bpw) / (time.perf_counter() - t0) / 1e9
-    return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+    return {"value": round(total_bytes / total_s / 1e9, 4), "unit": "GB/s", "cores": int(used), "host_cores": os.cpu_count(),
+            "threads": int(used), "kind": "oracle",
             "single_thread_value": round(single, 4),
             "sample": f"unpack + dequantize + fp64 GEMV of one layer's seven linears, {reps} passes "
                       f"({total_bytes / 1e6:.0f} MB of packed weights in {total_s:.1f} s); the multiply is row-parallel "
@@ -174,25 +176,48 @@ def main():
 
     # projections that read the same activation vector and may share a launch: (q, k, v) and (gate, up)
     groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches in (1, 4) else [[i] for i in range(len(shapes))]
-    if args.launches == 1:       # one chained launch per layer: o reads q's output, gate/up read o's, down reads gate's
+    if args.launches == 1:       # chained launches: o reads q's output, gate/up read o's, down reads gate's, the next layer's q/k/v read down's
         assert args.format == "Q3H_B64", "the chained launch exists for the 3.5-bit format"
-        chain_ws_bytes = iflow.qgemv_chain_workspace_bytes([r for _, r, _ in shapes] * args.layers_per_launch)
-        chain_ws = torch.zeros(chain_ws_bytes, dtype=torch.uint8, device=dev)
-        # outputs of the further layers of a multi-layer launch; layer l's q/k/v read layer l-1's down output
-        ys_l = [ys] + [[torch.empty_like(y) for y in ys] for _ in range(args.layers_per_launch - 1)]
-        if args.layers_per_launch > 1:     # no norms between the products here: start small so that fp16 holds the growth
-            xs[shapes[0][2]].mul_(2.0 ** -10)            # (each layer grows the values about 4.4-fold)
+        args.layers_per_launch = max(1, min(args.layers_per_launch, args.ring))
+        lpl = args.layers_per_launch
+        # all outputs of the chain as views of one allocation
+        per_layer = sum((r + 127) // 128 * 128 for _, r, _ in shapes)
+        y_arena = torch.empty((lpl * per_layer,), dtype=torch.float16, device=dev)
+        ys_l, cursor = [], 0
+        for _ in range(lpl):
+            row = []
+            for _, r, _ in shapes:
+                row.append(y_arena[cursor:cursor + r])
+                cursor += (r + 127) // 128 * 128
+            ys_l.append(row)
+        ys = ys_l[0]
+        if lpl > 1:                      # no norms between the products here: start small so that fp16 holds the growth
+            xs[shapes[0][2]].mul_(2.0 ** -10)            # (each layer grows the values about 4.4-fold; the chain saturates harmlessly after that)
+        chains = {}
 
     launch_count = [0]
 
+    def chain_for(layer, count):
+        """The compiled chain for `count` consecutive layers starting at ring position `layer` (compiled once, outside the timed region)."""
+        key = (layer, count)
+        if key not in chains:
+            phases = []
+            for l in range(count):
+                m_l, y_l = ring[(layer + l) % args.ring], ys_l[l]
+                x_l = [xs[shapes[0][2]] if l == 0 else ys_l[l - 1][6], y_l[0], y_l[3], y_l[4]]
+                phases += [(m_l[g[0]][1], x_l[i], [(m_l[j][2], m_l[j][0], y_l[j]) for j in g]) for i, g in enumerate(groups)]
+            ws_bytes = iflow.qgemv_chain_workspace_bytes([m[1] for ph in phases for m in ph[2]])
+            plan_bytes = iflow.qgemv_chain_plan_bytes(phases)
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+            plan = torch.empty(plan_bytes, dtype=torch.uint8, device=dev)
+            t0 = time.perf_counter()
+            chain = iflow.qgemv_chain_plan(fmt, phases, plan, plan_bytes, ws, ws_bytes, stream=raw)
+            chains[key] = (chain, plan, ws, time.perf_counter() - t0)
+        return chains[key][0]
+
     def chain_launch(layer, count):
         """One launch for `count` consecutive layers starting at ring position `layer`."""
-        phases = []
-        for l in range(count):
-            m_l, y_l = ring[(layer + l) % args.ring], ys_l[l]
-            x_l = [xs[shapes[0][2]] if l == 0 else ys_l[l - 1][6], y_l[0], y_l[3], y_l[4]]
-            phases += [(m_l[g[0]][1], x_l[i], [(m_l[j][2], m_l[j][0], y_l[j]) for j in g]) for i, g in enumerate(groups)]
-        iflow.qgemv_chain(fmt, phases, chain_ws, chain_ws_bytes, stream=raw)
+        iflow.qgemv_chain_launch(chain_for(layer, count), stream=raw)
         launch_count[0] += 1
 
     if args.fused:
@@ -255,7 +280,7 @@ def main():
     graph_launches = 0
     with torch.cuda.stream(stream):
         layer = 0
-        while layer < min(2 * args.layers_per_launch, args.ring):      # load code objects before capture
+        while layer < (args.ring if args.launches == 1 else min(2, args.ring)):      # load code objects (and compile every chain) before capture
             layer += advance(layer, args.ring - layer)
         stream.synchronize()
         if not args.no_graph:
@@ -281,17 +306,27 @@ def main():
                     layer = (layer + n) % args.ring
             return layer
 
-        run(args.warmup)
-        stream.synchronize()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        launch_count[0] = 0
-        run(args.steps)
-        e1.record(stream)
-        e1.synchronize()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
+        # A short timed region (fewer than two trips round the ring) is repeated and the median is reported; the first,
+        # untimed repeat also compiles every chain the region needs (iflow_qgemv_chain_plan stays outside the timing).
+        repeats = 11 if args.steps < 2 * args.ring else 1
+        if args.launches == 1:
+            end = run(args.warmup)
+            run(args.steps, end)
+            stream.synchronize()
+        times = []
+        for rep_i in range(repeats):
+            end = run(args.warmup)
+            stream.synchronize()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            launch_count[0] = 0
+            run(args.steps, end)
+            e1.record(stream)
+            e1.synchronize()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        ms = sorted(times)[len(times) // 2]
 
         # spread: every ring trip of a short extra pass timed on its own (the events cost a little, so this pass is
         # not the headline), and the attainable ceiling: a kernel that only reads the same packed weights
@@ -509,29 +544,44 @@ def main():
     bytes_per_launch = step_bytes / launches_per_step
     achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
 
-    # HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, calibrated), if present
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "q3h_chain_7b_layers_hbm_traffic.txt" if args.launches == 1 and args.layers_per_launch == 8
+    # HBM bytes from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, calibrated), if present.  The summary
+    # gives bytes per LAYER of the profiled launch; `traffic` is that figure times the layers of this run's average launch,
+    # so that traffic / algorithmic_bytes_per_launch is the measured ratio whatever --steps is.  The kernel-trace average
+    # of the same profiled command is copied next to it (per layer), as a second source for the roofline fraction.
+    traffic, trace_us_per_layer = None, None
+    layers_per_launch_avg = 1.0 / launches_per_step
+    tfile = os.path.join(ROOT, "profiles", "q3h_chain_7b_layers_hbm_traffic.txt" if args.launches == 1
                          else "q3h_gemv_7b_layer_hbm_traffic.txt" if args.launches == 4 else "none")
-    if args.format == "Q3H_B64" and os.path.exists(tfile):
-        for line in open(tfile):
-            if line.startswith("hbm_bytes_per_launch"):
+    kfile = os.path.join(ROOT, "profiles", "q3h_chain_7b_layers_kernel_stats.txt" if args.launches == 1 else "none")
+
+    def summary_value(path, key):
+        if args.format != "Q3H_B64" or not os.path.exists(path):
+            return None
+        for line in open(path):
+            if line.startswith(key):
                 try:
-                    traffic = int(float(line.split("=")[1].split()[0]))
+                    return float(line.split("=")[1].split()[0])
                 except (ValueError, IndexError):
-                    traffic = None
+                    return None
+        return None
+
+    per_layer = summary_value(tfile, "hbm_bytes_per_layer")
+    if per_layer is not None:
+        traffic = int(per_layer * layers_per_launch_avg)
+    trace_us_per_layer = summary_value(kfile, "kernel_us_per_layer")
 
     out = {
         "metric": "achieved HBM GB/s (% of peak) of 3.5-bit fused dequant-GEMV, 7B shapes, batch 1" if args.format == "Q3H_B64"
                   else f"achieved HBM GB/s (% of peak) of {args.format} fused dequant-GEMV, 7B shapes, batch 1 (context; the headline is the 3.5-bit format)",
         "value": round(value, 1), "unit": "GB/s", "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "timed_repeats": repeats,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 x u7-pair codes, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": "llama2-7b decoder-layer linears (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
                                f"{args.format}, batch 1, ring of {args.ring} distinct layers "
                                f"({args.ring * step_bytes / 2**30:.2f} GiB packed), "
                                + ("HIP-graph replay" if graph is not None else "eager launches")
+                               + (f", median of {repeats} repeats of the timed region" if repeats > 1 else "")
                                + {1: f", 1 chained launch per {args.layers_per_launch} layer(s) (q+k+v -> o -> gate+up -> down -> next layer's q+k+v ..., "
                                      "each phase reading the previous one's output)",
                                   4: ", 4 launches per layer (q+k+v, o, gate+up, down)"
@@ -542,8 +592,15 @@ def main():
                    "format": args.format, "batch": 1, "bytes_per_step": int(step_bytes), "launches_per_step": round(launches_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac_source": "HIP events on the launch stream around the timed region of this run (launch gaps included)",
                      "kernel": "iflow::q3h_gemv_kernel<1, 2, false|true, -1>", "avg_launch_us": round(us_per_launch, 3),
-                     "algorithmic_bytes_per_launch": int(bytes_per_launch)},
+                     "layers_per_launch": round(layers_per_launch_avg, 4),
+                     "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                     "kernel_trace_us_per_layer": trace_us_per_layer,
+                     "frac_from_kernel_trace": (round(step_bytes / (trace_us_per_layer * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)
+                                                if trace_us_per_layer else None),
+                     "kernel_trace_source": "profiles/q3h_chain_7b_layers_kernel_stats.txt (rocprofv3 --kernel-trace --stats of this command)"
+                                            if trace_us_per_layer else None},
     }
     out["spread"] = spread
     out["stream_read_ceiling"] = {"value": round(read_gbps, 1), "unit": "GB/s", "frac_of_peak": round(read_gbps / HBM_PEAK_GBPS, 4),
@@ -552,8 +609,11 @@ def main():
     out["other_paths"] = other
     log_environment(torch)
     if args.launches == 1:
-        iflow.qgemv_chain_check(chain_ws, stream=raw)          # raises if a phase ever gave up waiting for its input
+        for chain, _, _, _ in chains.values():
+            iflow.qgemv_chain_check(chain, stream=raw)         # raises if a wait inside a launch ever gave up
         out["roofline"]["kernel"] = "iflow::q3h_chain_kernel<2>"
+        out["config"]["chain_plans"] = {f"{k[1]} layers from ring position {k[0]}": {"plan_MB": round(v[1].numel() / 1e6, 1),
+                                                                                      "plan_call_s": round(v[3], 2)} for k, v in chains.items()}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.format)
     print(json.dumps(out))

@@ -164,34 +164,55 @@ iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate,
 /* A chain of batch-1 products in ONE launch (3.5-bit format only): the decode step applies its projections one
  * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and
  * at 7B sizes each product is so short that the idle time between dependent launches costs as much as a third of
- * the weight stream.  The chain is a list of `nphases` (1..IFLOW_CHAIN_MAX_PHASES) phases.  Phase p multiplies
- * counts[p] (1..IFLOW_CHAIN_MAX_GROUP) matrices, all with cols[p] columns (<= 65536), with the activation vector x[p]; the matrices of all
- * phases are listed in order in packed / rows / y (at most IFLOW_CHAIN_MAX_MATRICES in total).  x[p] is either
- *   - an input of the call: device memory that none of this call's outputs of phases <= p overlaps, or
+ * the weight stream.  The chain is a list of `nphases` (1..IFLOW_CHAIN_MAX_PHASES) phases.  Phase p multiplies counts[p]
+ * (1..IFLOW_CHAIN_MAX_GROUP) matrices, all with cols[p] columns (<= 65536), with the activation vector x[p]; the matrices
+ * of all phases are listed in order in packed / rows / y (at most IFLOW_CHAIN_MAX_MATRICES in total: a whole 32-layer
+ * stack of seven matrices per layer fits several times).  x[p] is either
+ *   - an input of the call: device memory that NO output of the call overlaps (workgroups run ahead of each other, so
+ *     a later phase's output may be written before a slow workgroup has read an earlier phase's input), or
  *   - exactly the output y[i] of a matrix of an EARLIER phase with rows[i] == cols[p]: the phase then waits, inside
- *     the launch, until that output is complete.  Any other overlap is IFLOW_ERR_SHAPE.
- * Every y[i] receives what iflow_qgemv would have written, so the chain equals the sequence of iflow_qgemv_multi
- * calls it replaces.  All arrays are HOST arrays read during the call; pointers in them are device pointers.
+ *     the launch, until that output is complete.
+ * Any other overlap of an x with a y, and any overlap between two y, is IFLOW_ERR_SHAPE.  Every y[i] receives what
+ * iflow_qgemv would have written, bit for bit, so the chain equals the sequence of iflow_qgemv_multi calls it replaces.
+ * The weights never change between tokens, so the chain is described once and launched many times:
  *
- * workspace: device memory of at least iflow_qgemv_chain_workspace_bytes() bytes, 16-byte aligned, owned by the
- * caller, ZEROED before its first use and then left alone: it carries the hand-over words and a launch counter
- * from call to call.  Zero it again before using it for a chain with different shapes.  Calls that share a
- * workspace must be ordered (same stream); concurrent chains need a workspace each.
+ *   iflow_qgemv_chain_plan    validates the chain, writes its description (one descriptor per phase and per matrix) into
+ *       `plan`, zeroes `workspace` and fills *chain.  All arrays are HOST arrays read during the call; pointers in them
+ *       are device pointers that must stay valid for as long as the chain is launched.  The call synchronises `stream`
+ *       (it cannot be captured into a HIP graph); it allocates host memory only.
+ *   iflow_qgemv_chain_launch  one kernel launch on `stream`; allocates nothing, may be captured and replayed.
+ *   iflow_qgemv_chain_check   synchronises `stream`; IFLOW_ERR_TIMEOUT if a phase of an earlier launch gave up waiting
+ *       for its input (its wait exceeded its bound of tens of milliseconds; the launch then still ends, its outputs are
+ *       unspecified, and the record stays until the chain is planned again), IFLOW_OK otherwise.
+ *
+ * plan:      device memory of iflow_qgemv_chain_plan_bytes(nphases, total matrices) bytes, 16-byte aligned, owned by the
+ *            caller, read-only for the launches.
+ * workspace: device memory of at least iflow_qgemv_chain_workspace_bytes() bytes, 16-byte aligned, owned by the caller,
+ *            left alone between launches: it carries the hand-over words and a launch counter from launch to launch.
+ *            Launches of one chain must be ordered (one stream); a second chain needs a plan and a workspace of its own.
+ * iflow_chain_t is plain data (no resources behind it): it may be copied and dropped freely.
  *
  * The launch keeps one workgroup per compute unit resident and its phases wait for each other, so it wants the
- * device to itself: if other work holds compute units for long, or two chains run at once, a wait can exceed its
- * bound (tens of milliseconds); the launch then still ends, the outputs are unspecified, and the workspace records
- * it.  iflow_qgemv_chain_check() synchronises the stream and returns IFLOW_ERR_TIMEOUT in that case (the record
- * stays until the workspace is zeroed again), IFLOW_OK otherwise. */
-#define IFLOW_CHAIN_MAX_PHASES 32
+ * device to itself: if other work holds compute units for long, or two chains run at once, a wait can exceed its bound. */
+#define IFLOW_CHAIN_MAX_PHASES 1024
 #define IFLOW_CHAIN_MAX_GROUP 4
-#define IFLOW_CHAIN_MAX_MATRICES 56
+#define IFLOW_CHAIN_MAX_MATRICES 4096
 #define IFLOW_CHAIN_WS_HEADER 4096
+#define IFLOW_CHAIN_MAGIC 0x69464c57u
+typedef struct iflow_chain_t {
+    void *plan;                 /* device */
+    void *workspace;            /* device */
+    int32_t grid, max_strips;   /* launch geometry the plan was written for */
+    uint32_t magic, reserved;
+} iflow_chain_t;
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes);
-iflow_status_t iflow_qgemv_chain(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
-                                 const uint16_t *const *x, const void *const *packed, const int64_t *rows,
-                                 uint16_t *const *y, void *workspace, size_t workspace_bytes, void *stream);
-iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream);
+iflow_status_t iflow_qgemv_chain_plan_bytes(int nphases, int nmatrices, size_t *bytes);
+iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                      const uint16_t *const *x, const void *const *packed, const int64_t *rows,
+                                      uint16_t *const *y, void *plan, size_t plan_bytes, void *workspace,
+                                      size_t workspace_bytes, void *stream, iflow_chain_t *chain);
+iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream);
+iflow_status_t iflow_qgemv_chain_check(const iflow_chain_t *chain, void *stream);
 
 /* One decode step of grouped-query attention over an fp16 key/value cache (section "Grouped-query attention":
  * head_i = Attention(Q_i, K^j, V^j), j the group of query head i; scaled dot-product attention; n_kv_heads == n_heads is

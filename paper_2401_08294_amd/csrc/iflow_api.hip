@@ -1,6 +1,8 @@
 // C-ABI entry points of libiflow.so: argument validation on the host, then one launcher call.
 // Nothing here allocates, synchronises or keeps state between calls (except the thread-local
 // record of the last HIP error).
+#include <algorithm>
+
 #include "iflow_common.h"
 
 namespace {
@@ -37,6 +39,12 @@ iflow_status_t device_status(hipError_t e)
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const void *p, int64_t pn, const void *q, int64_t qn)
+{
+    const uintptr_t a0 = (uintptr_t)p, b0 = (uintptr_t)q;
+    return a0 < b0 + (uintptr_t)qn && b0 < a0 + (uintptr_t)pn;
+}
 
 // Shape rules shared by every call: positive sizes, cols a whole number of blocks, and sizes that
 // keep every kernel index inside 32-bit block/row counters.
@@ -197,10 +205,6 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
     if ((x_op == IFLOW_X_PLAIN) != (aux == nullptr)) return IFLOW_ERR_NULL;
     if (x_op == IFLOW_X_RMS_GAIN && !(eps >= 0.0f && eps < 3.0e38f)) return IFLOW_ERR_SHAPE;
     if (!aligned16(x) || (aux && !aligned16(aux))) return IFLOW_ERR_ALIGN;
-    auto overlaps = [](const void *p, int64_t pn, const void *q, int64_t qn) {
-        const uintptr_t a0 = (uintptr_t)p, b0 = (uintptr_t)q;
-        return a0 < b0 + (uintptr_t)qn && b0 < a0 + (uintptr_t)pn;
-    };
     for (int i = 0; i < count; ++i) {
         iflow_status_t st = check_shape(format, rows[i], cols, &fi);
         if (st != IFLOW_OK) return st;
@@ -236,10 +240,6 @@ iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate,
     iflow_status_t st = check_shape(format, rows, cols, &fi);
     if (st != IFLOW_OK) return st;
     if (!aligned16(packed_gate) || !aligned16(packed_up) || !aligned16(x) || !aligned16(y) || (aux && !aligned16(aux))) return IFLOW_ERR_ALIGN;
-    auto overlaps = [](const void *p, int64_t pn, const void *q, int64_t qn) {
-        const uintptr_t a0 = (uintptr_t)p, b0 = (uintptr_t)q;
-        return a0 < b0 + (uintptr_t)qn && b0 < a0 + (uintptr_t)pn;
-    };
     // outputs are written while other workgroups still read x and aux
     if (overlaps(y, rows * 2, x, cols * 2) || (aux && overlaps(y, rows * 2, aux, cols * 2))) return IFLOW_ERR_SHAPE;
     const hipError_t e = iflow::launch_qgemv_gated((int)format, packed_gate, packed_up, rows, cols, x, (int)x_op, aux, eps, y,
@@ -304,6 +304,58 @@ iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint1
                                                    k_cache, v_cache, (hipStream_t)stream));
 }
 
+// ---- the chained launch ---------------------------------------------------------------------------------------------
+namespace {
+
+// Everything that can be checked about a chain on the host; fills the index arrays the plan builder wants.
+iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
+                              const void *const *packed, const int64_t *rows, uint16_t *const *y, std::vector<int> &first,
+                              std::vector<int> &x_src, int *nmatrices)
+{
+    iflow::FormatInfo fi;
+    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
+    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;      // the chained launch exists for the 3.5-bit format only
+    if (nphases < 1 || nphases > IFLOW_CHAIN_MAX_PHASES) return IFLOW_ERR_SHAPE;
+    if (!counts || !cols || !x || !packed || !rows || !y) return IFLOW_ERR_NULL;
+    int total = 0;
+    first.assign(nphases, 0);
+    for (int p = 0; p < nphases; ++p) {
+        if (counts[p] < 1 || counts[p] > IFLOW_CHAIN_MAX_GROUP || counts[p] > IFLOW_CHAIN_MAX_MATRICES - total) return IFLOW_ERR_SHAPE;
+        first[p] = total;
+        total += counts[p];
+    }
+    *nmatrices = total;
+    x_src.assign(nphases, -1);
+    for (int p = 0; p < nphases; ++p) {
+        if (!x[p]) return IFLOW_ERR_NULL;
+        if (!aligned16(x[p])) return IFLOW_ERR_ALIGN;
+        if (cols[p] > 65536) return IFLOW_ERR_SHAPE;
+        for (int m = first[p]; m < first[p] + counts[p]; ++m) {
+            iflow_status_t st = check_shape(format, rows[m], cols[p], &fi);
+            if (st != IFLOW_OK) return st;
+            if (!packed[m] || !y[m]) return IFLOW_ERR_NULL;
+            if (!aligned16(packed[m]) || !aligned16(y[m])) return IFLOW_ERR_ALIGN;
+        }
+    }
+    // Outputs must not overlap each other.  An activation vector is either exactly the whole output of a matrix of an
+    // EARLIER phase (then the phase waits for it inside the launch), or memory that no output of the whole call touches:
+    // workgroups run ahead of each other, so a later phase's output may be written before a slow workgroup has read
+    // an earlier phase's input.
+    for (int i = 0; i < total; ++i)
+        for (int j = i + 1; j < total; ++j)
+            if (overlaps(y[i], rows[i] * 2, y[j], rows[j] * 2)) return IFLOW_ERR_SHAPE;
+    for (int p = 0; p < nphases; ++p) {
+        for (int i = 0; i < total; ++i) {
+            if (!overlaps(x[p], cols[p] * 2, y[i], rows[i] * 2)) continue;
+            if (i < first[p] && static_cast<const void *>(x[p]) == static_cast<const void *>(y[i]) && rows[i] == cols[p] && x_src[p] < 0) x_src[p] = i;
+            else return IFLOW_ERR_SHAPE;
+        }
+    }
+    return IFLOW_OK;
+}
+
+}  // namespace
+
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes)
 {
     if (!rows || !bytes) return IFLOW_ERR_NULL;
@@ -314,56 +366,60 @@ iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *r
     return IFLOW_OK;
 }
 
-iflow_status_t iflow_qgemv_chain(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
-                                 const uint16_t *const *x, const void *const *packed, const int64_t *rows,
-                                 uint16_t *const *y, void *workspace, size_t workspace_bytes, void *stream)
+iflow_status_t iflow_qgemv_chain_plan_bytes(int nphases, int nmatrices, size_t *bytes)
 {
-    iflow::FormatInfo fi;
-    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
-    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;      // the chained launch exists for the 3.5-bit format only
-    if (nphases < 1 || nphases > IFLOW_CHAIN_MAX_PHASES) return IFLOW_ERR_SHAPE;
-    if (!counts || !cols || !x || !packed || !rows || !y || !workspace) return IFLOW_ERR_NULL;
+    if (!bytes) return IFLOW_ERR_NULL;
+    if (nphases < 1 || nphases > IFLOW_CHAIN_MAX_PHASES || nmatrices < nphases || nmatrices > IFLOW_CHAIN_MAX_MATRICES) return IFLOW_ERR_SHAPE;
+    *bytes = iflow::chain_plan_bytes(nphases, nmatrices);
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                      const uint16_t *const *x, const void *const *packed, const int64_t *rows,
+                                      uint16_t *const *y, void *plan, size_t plan_bytes, void *workspace,
+                                      size_t workspace_bytes, void *stream, iflow_chain_t *chain)
+{
+    std::vector<int> first, x_src;
     int total = 0;
-    for (int p = 0; p < nphases; ++p) {
-        if (counts[p] < 1 || counts[p] > IFLOW_CHAIN_MAX_GROUP || counts[p] > IFLOW_CHAIN_MAX_MATRICES - total) return IFLOW_ERR_SHAPE;
-        total += counts[p];
-    }
-    int x_src[IFLOW_CHAIN_MAX_PHASES];
-    int m = 0;
-    for (int p = 0; p < nphases; ++p) {
-        if (!x[p]) return IFLOW_ERR_NULL;
-        if (!aligned16(x[p])) return IFLOW_ERR_ALIGN;
-        if (cols[p] > 65536) return IFLOW_ERR_SHAPE;
-        const int first = m;
-        for (int j = 0; j < counts[p]; ++j, ++m) {
-            iflow_status_t st = check_shape(format, rows[m], cols[p], &fi);
-            if (st != IFLOW_OK) return st;
-            if (!packed[m] || !y[m]) return IFLOW_ERR_NULL;
-            if (!aligned16(packed[m]) || !aligned16(y[m])) return IFLOW_ERR_ALIGN;
-        }
-        // the activations are either an output of an earlier phase, whole, or memory that no output of this call
-        // up to and including this phase overlaps
-        x_src[p] = -1;
-        const uintptr_t xb = reinterpret_cast<uintptr_t>(x[p]), xe = xb + (uintptr_t)cols[p] * 2;
-        for (int i = 0; i < m; ++i) {
-            const uintptr_t yb = reinterpret_cast<uintptr_t>(y[i]), ye = yb + (uintptr_t)rows[i] * 2;
-            if (xb >= ye || yb >= xe) continue;
-            if (i < first && xb == yb && rows[i] == cols[p] && x_src[p] < 0) x_src[p] = i;
-            else return IFLOW_ERR_SHAPE;
-        }
-    }
-    if (workspace_bytes < iflow::chain_workspace_bytes(total, rows)) return IFLOW_ERR_SIZE;
-    if (!aligned16(workspace)) return IFLOW_ERR_ALIGN;
-    hipError_t e = iflow::launch_qgemv_chain(nphases, counts, cols, x, packed, rows, y, x_src, workspace, (hipStream_t)stream);
-    if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // more rows in the chain than the kernel's 32-bit indices cover
+    iflow_status_t st = chain_validate(format, nphases, counts, cols, x, packed, rows, y, first, x_src, &total);
+    if (st != IFLOW_OK) return st;
+    if (!plan || !workspace || !chain) return IFLOW_ERR_NULL;
+    if (!aligned16(plan) || !aligned16(workspace)) return IFLOW_ERR_ALIGN;
+    const size_t ws_need = iflow::chain_workspace_bytes(total, rows);
+    if (workspace_bytes < ws_need || plan_bytes < iflow::chain_plan_bytes(nphases, total)) return IFLOW_ERR_SIZE;
+    int grid = 0;
+    hipError_t e = iflow::chain_grid_for_device(&grid);
+    if (e != hipSuccess) return device_status(e);
+    iflow::ChainSpec spec = {nphases, counts, first.data(), cols, x, x_src.data(), packed, rows, y};
+    std::vector<uint8_t> host;
+    if (!iflow::chain_build_plan(spec, grid, host)) return IFLOW_ERR_SHAPE;   // more rows than the kernel's 32-bit indices cover
+    hipStream_t s = (hipStream_t)stream;
+    e = hipMemsetAsync(workspace, 0, ws_need, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(plan, host.data(), host.size(), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);          // (the host copy of the plan goes away when this call returns)
+    if (e != hipSuccess) return device_status(e);
+    int max_strips = 1;
+    for (int p = 0; p < nphases; ++p) max_strips = std::max(max_strips, (int)((cols[p] / 64 + 63) / 64));
+    chain->plan = plan; chain->workspace = workspace;
+    chain->grid = grid; chain->max_strips = max_strips;
+    chain->magic = IFLOW_CHAIN_MAGIC; chain->reserved = 0;
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream)
+{
+    if (!chain || !chain->plan || !chain->workspace) return IFLOW_ERR_NULL;
+    if (chain->magic != IFLOW_CHAIN_MAGIC) return IFLOW_ERR_SHAPE;
+    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->max_strips, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // planned for a device with another number of compute units
     return device_status(e);
 }
 
-iflow_status_t iflow_qgemv_chain_check(const void *workspace, void *stream)
+iflow_status_t iflow_qgemv_chain_check(const iflow_chain_t *chain, void *stream)
 {
-    if (!workspace) return IFLOW_ERR_NULL;
+    if (!chain || !chain->workspace) return IFLOW_ERR_NULL;
     uint32_t head[2] = {0, 0};
-    hipError_t e = hipMemcpyAsync(head, workspace, sizeof(head), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    hipError_t e = hipMemcpyAsync(head, chain->workspace, sizeof(head), hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return device_status(e);
     return head[1] ? IFLOW_ERR_TIMEOUT : IFLOW_OK;

@@ -4,6 +4,7 @@
 
 #include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -223,10 +224,23 @@ hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const 
                               int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s);
 hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
                                      int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s);
+// ---- the chained launch: description of a chain (host arrays of the caller), plan builder, model, launcher ----
+struct ChainSpec {
+    int nphases;
+    const int *counts;                 // matrices per phase
+    const int *first;                  // index of each phase's first matrix
+    const int64_t *cols;               // per phase
+    const uint16_t *const *x;          // per phase
+    const int *x_src;                  // per phase: matrix whose output is the phase's input, or -1 for an input of the launch
+    const void *const *packed;         // per matrix
+    const int64_t *rows;
+    uint16_t *const *y;
+};
 size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
-hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
-                              const void *const *packed, const int64_t *rows, uint16_t *const *y,
-                              const int *x_src, void *workspace, hipStream_t s);
+size_t chain_plan_bytes(int nphases, int nmatrices);
+bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out);
+hipError_t chain_grid_for_device(int *grid);
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, hipStream_t s);
 hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int64_t cols,
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64_t cols,

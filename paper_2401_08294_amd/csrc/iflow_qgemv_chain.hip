@@ -29,23 +29,31 @@
 
 #include <type_traits>
 
+#define IFLOW_GLOBAL __attribute__((address_space(1)))
+
 namespace iflow {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <typename T> __device__ __forceinline__ IFLOW_GLOBAL T *global_ptr(const void *p) { return (IFLOW_GLOBAL T *)(uint64_t)p; }
 
 constexpr int CHAIN_WAVES = 12;                                // wavefronts per workgroup (measured: 8 is 3 % slower, 16 equal;
                                                                // 12 divides the row pairs of 7B-sized phases evenly)
 constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;                  // a wavefront takes two rows per step: rows between its steps
 constexpr int CHAIN_SLOT_BYTES = 8 * 64 * 16 + 64 * 8;        // staged activations of one strip (as in q3h_gemv_kernel)
 constexpr int CHAIN_MAX_STRIPS = 16;                           // columns <= 65536
-constexpr int CHAIN_MAX_GROUP = 4;                             // matrices per phase
+constexpr int CHAIN_MAX_GROUP = IFLOW_CHAIN_MAX_GROUP;         // matrices per phase
 constexpr int CHAIN_MAX_GRID = 960;
 constexpr int CHAIN_POLL_BUDGET = 1 << 17;                     // re-reads before a wait is given up (tens of milliseconds)
 // workspace header, in 32-bit words: [0] launch counter, [1] error, [64, 64 + grid) per-workgroup "done" marks;
 // tagged outputs start at byte IFLOW_CHAIN_WS_HEADER
 constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_SEEN = 64;
 
-// Kernel arguments.  Everything a wavefront needs when it enters a phase sits in one 64-byte descriptor, and
-// everything about a matrix in one 32-byte descriptor: a scalar load each, instead of a chain of dependent loads
-// (a scalar load costs a few hundred nanoseconds of latency, and a phase of a 7B layer lasts a few microseconds).
+// The plan: what iflow_qgemv_chain_plan writes into the caller's device memory once, and every launch reads.  The weights
+// of a model never change between tokens, so the chain is described once; a launch passes two pointers.  Everything a
+// wavefront needs when it enters a phase sits in one 64-byte descriptor, and everything about a matrix in one 32-byte
+// descriptor: a scalar load each, instead of a chain of dependent loads (a scalar load costs a few hundred nanoseconds
+// of latency, and a phase of a 7B layer lasts a few microseconds).  Layout: ChainHeader, then the phase descriptors, then
+// the matrix descriptors.
 struct ChainPhase {
     const uint16_t *x;          // activations when they are an input of the launch
     int first, count;           // matrices [first, first + count)
@@ -65,13 +73,17 @@ struct ChainMatrix {
     int tag_word;               // its tagged output, in 32-bit words from the workspace start
     int pad_;
 };
-struct ChainArgs {
-    int nphases, pad_;
-    ChainPhase ph[IFLOW_CHAIN_MAX_PHASES];
-    ChainMatrix mat[IFLOW_CHAIN_MAX_MATRICES];
+struct ChainHeader {
+    uint32_t magic;
+    int nphases, nmatrices, grid;
+    int max_strips, pad_[11];
 };
-static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 32, "descriptor sizes");
-static_assert(sizeof(ChainArgs) + 8 <= 4096, "kernel arguments are limited to 4 KiB");
+static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 32 && sizeof(ChainHeader) == 64, "descriptor sizes");
+// the two descriptor arrays of a plan, as the kernel indexes them
+struct ChainArgs {
+    const ChainPhase *ph;
+    const ChainMatrix *mat;
+};
 
 // Position of output r inside a matrix's tagged vector, in 32-bit words.  A consumer thread stages one chunk of 16
 // activations with eight 8-byte loads; the pair (2i, 2i+1) of chunk c of a strip sits at 8-byte word i * 256 + c,
@@ -101,14 +113,16 @@ struct ChainWalk {
 };
 
 template <int S>
-__global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const ChainArgs a, uint32_t *__restrict__ ws)
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws)
 {
+    const ChainHeader *const hd = reinterpret_cast<const ChainHeader *>(plan);
+    const ChainArgs a = {reinterpret_cast<const ChainPhase *>(plan + sizeof(ChainHeader)),
+                         reinterpret_cast<const ChainMatrix *>(plan + sizeof(ChainHeader)) + 2 * hd->nphases};
     extern __shared__ __align__(16) uint8_t xs[];
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = IFLOW_UNI(tid >> 6);
     const int wg = blockIdx.x;
-    const int nphases = a.nphases;
+    const int nphases = hd->nphases;
 
     // A wavefront handles two adjacent rows (2i, 2i+1 of a matrix) per step, so "row" below means such a pair, named
     // by its even row; in a phase's row space every matrix starts at an even row (odd matrices are padded by one).
@@ -196,8 +210,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const Chain
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const uint8_t *row = q_wptr + u * q_row1;
-            const u32x4 c0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + voff));
-            const u32x4 c1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + plane2 + voff));
+            // (pointers that were read from the plan have to be told that they point to global memory: a generic pointer
+            // makes flat loads, whose completion cannot be counted, and every wait in the step loop becomes "all")
+            const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + voff));
+            const u32x4 c1 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + plane2 + voff));
             w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
             w[u].d[4] = c1.x; w[u].d[5] = c1.y; w[u].d[6] = c1.z; w[u].d[7] = c1.w;
         }
@@ -237,10 +253,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const Chain
         const int cc = c & 255, ts = c >> 8;
         const int n_t = min(64, nbk - ts * 64);
         const int ccl = cc & (int)mask_lt(cc >> 2, n_t);
-        return reinterpret_cast<const uint4 *>(x + (int64_t)ts * 4096 + ccl * 16);
+        return global_ptr<const u32x4>(x + (int64_t)ts * 4096 + ccl * 16);
     };
     auto chunk_live = [&](int c, int nbk) { return mask_lt((c & 255) >> 2, min(64, nbk - (c >> 8) * 64)); };
-    auto put_plain = [&](int c, int nbk, const uint4 q0, const uint4 q1) {
+    auto put_plain = [&](int c, int nbk, const u32x4 q0, const u32x4 q1) {
         const uint32_t live = chunk_live(c, nbk);              // columns past the end of the row count as zero
         const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
         chunk_put(c, n);
@@ -257,8 +273,8 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const Chain
         const ChainPhase ph0 = a.ph[0];
         const bool wg_has0 = wg * ph0.rows_per_wg < ph0.total;
         const int nchunks0 = wg_has0 ? ph0.nstrips * 256 : 0;
-        const uint4 *src0 = chunk_src(ph0.x, tid & (int)mask_lt(tid, nchunks0), ph0.nbk);   // threads without a chunk read chunk 0
-        const uint4 xq0 = src0[0], xq1 = src0[1];
+        const IFLOW_GLOBAL u32x4 *src0 = chunk_src(ph0.x, tid & (int)mask_lt(tid, nchunks0), ph0.nbk);   // threads without a chunk read chunk 0
+        const u32x4 xq0 = src0[0], xq1 = src0[1];
         request_segment();
 #pragma unroll
         for (int j = 0; j < S; ++j) request(w[j]);
@@ -266,7 +282,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const Chain
         if (wave * 64 < nchunks0) put_plain(tid, ph0.nbk, xq0, xq1);
 #pragma unroll 1
         for (int cw = wave * 64 + 64 * CHAIN_WAVES; cw < nchunks0; cw += 64 * CHAIN_WAVES) {
-            const uint4 *src = chunk_src(ph0.x, cw + lane, ph0.nbk);
+            const IFLOW_GLOBAL u32x4 *src = chunk_src(ph0.x, cw + lane, ph0.nbk);
             put_plain(cw + lane, ph0.nbk, src[0], src[1]);
         }
     }
@@ -307,7 +323,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const Chain
             if (p > 0 && ph.x_src < 0) {
 #pragma unroll 1
                 for (int cw = wave * 64; cw < nchunks; cw += 64 * CHAIN_WAVES) {
-                    const uint4 *src = chunk_src(ph.x, cw + lane, nbk);
+                    const IFLOW_GLOBAL u32x4 *src = chunk_src(ph.x, cw + lane, nbk);
                     put_plain(cw + lane, nbk, src[0], src[1]);
                 }
             } else if (p > 0) {
@@ -410,11 +426,11 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const Chain
             if (lane < n) {
                 const uint32_t h0 = as_u16((half_t)res0), h1 = as_u16((half_t)res1);
                 if (!out_single) {
-                    *reinterpret_cast<uint32_t *>(out_y) = h0 | (h1 << 16);
+                    *global_ptr<uint32_t>(out_y) = h0 | (h1 << 16);
                     __hip_atomic_store(reinterpret_cast<uint64_t *>(out_t), (uint64_t)(h0 | tag) | ((uint64_t)(h1 | tag) << 32),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 } else {
-                    *out_y = (uint16_t)h0;
+                    *global_ptr<uint16_t>(out_y) = (uint16_t)h0;
                     __hip_atomic_store(out_t, h0 | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
@@ -450,12 +466,15 @@ size_t chain_workspace_bytes(int nmatrices, const int64_t *rows)
     return bytes;
 }
 
+size_t chain_plan_bytes(int nphases, int nmatrices)
+{
+    return sizeof(ChainHeader) + (size_t)nphases * sizeof(ChainPhase) + (size_t)nmatrices * sizeof(ChainMatrix);
+}
+
 // Launch geometry: as many workgroups as the device has compute units (one each: 768 threads
 // and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
-// concurrently.  Returns hipErrorInvalidValue for shapes outside the kernel's limits.
-hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
-                              const void *const *packed, const int64_t *rows, uint16_t *const *y,
-                              const int *x_src, void *workspace, hipStream_t s)
+// concurrently.
+hipError_t chain_grid_for_device(int *grid)
 {
     static PerDevice pd;
     int cus = 0;
@@ -463,36 +482,56 @@ hipError_t launch_qgemv_chain(int nphases, const int *counts, const int64_t *col
         return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
     });
     if (e0 != hipSuccess) return e0;
-    const int grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
-    ChainArgs a = {};
-    a.nphases = nphases;
+    *grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
+    return hipSuccess;
+}
+
+// The plan for `grid` workgroups, in host memory (the caller copies it to the device).  Returns false for shapes outside
+// the kernel's limits.
+bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
+{
+    const int nmat = c.first[c.nphases - 1] + c.counts[c.nphases - 1];
+    out.assign(chain_plan_bytes(c.nphases, nmat), 0);
+    ChainHeader *hd = reinterpret_cast<ChainHeader *>(out.data());
+    ChainPhase *phs = reinterpret_cast<ChainPhase *>(out.data() + sizeof(ChainHeader));
+    ChainMatrix *mats = reinterpret_cast<ChainMatrix *>(phs + c.nphases);
     int m = 0, max_strips = 1;
     size_t word = IFLOW_CHAIN_WS_HEADER / 4;
-    for (int p = 0; p < nphases; ++p) {
-        ChainPhase &ph = a.ph[p];
-        ph.x = x[p]; ph.first = m; ph.count = counts[p];
+    for (int p = 0; p < c.nphases; ++p) {
+        ChainPhase &ph = phs[p];
+        ph.x = c.x[p]; ph.first = m; ph.count = c.counts[p];
         for (int j = 0; j < CHAIN_MAX_GROUP; ++j) ph.mstart[j] = 0x7FFFFFFF;
-        ph.nbk = (int)(cols[p] / 64); ph.nstrips = (ph.nbk + 63) / 64;
-        ph.x_src = x_src[p];
-        ph.x_tag_word = x_src[p] >= 0 ? a.mat[x_src[p]].tag_word : 0;
-        if (ph.nstrips > CHAIN_MAX_STRIPS || counts[p] > CHAIN_MAX_GROUP) return hipErrorInvalidValue;
+        ph.nbk = (int)(c.cols[p] / 64); ph.nstrips = (ph.nbk + 63) / 64;
+        ph.x_src = c.x_src[p];
+        ph.x_tag_word = c.x_src[p] >= 0 ? mats[c.x_src[p]].tag_word : 0;
+        if (ph.nstrips > CHAIN_MAX_STRIPS || c.counts[p] > CHAIN_MAX_GROUP) return false;
         if (ph.nstrips > max_strips) max_strips = ph.nstrips;
         int64_t v = 0;
-        for (int j = 0; j < counts[p]; ++j, ++m) {
-            a.mat[m].packed = static_cast<const uint8_t *>(packed[m]); a.mat[m].y = y[m]; a.mat[m].rows = (int)rows[m];
-            a.mat[m].start = (int)v;
-            a.mat[m].tag_word = (int)word;
+        for (int j = 0; j < c.counts[p]; ++j, ++m) {
+            mats[m].packed = static_cast<const uint8_t *>(c.packed[m]); mats[m].y = c.y[m]; mats[m].rows = (int)c.rows[m];
+            mats[m].start = (int)v;
+            mats[m].tag_word = (int)word;
             ph.mstart[j] = (int)v;
-            word += (size_t)((rows[m] + 4095) / 4096) * 4096;
-            v += (rows[m] + 1) & ~(int64_t)1;                  // every matrix starts at an even row of the phase's row space
+            word += (size_t)((c.rows[m] + 4095) / 4096) * 4096;
+            v += (c.rows[m] + 1) & ~(int64_t)1;                // every matrix starts at an even row of the phase's row space
         }
         const int64_t rpw = ((v + grid - 1) / grid + 1) & ~(int64_t)1;
-        if (v > 0x3FFFFFFF || word > 0x3FFFFFFF) return hipErrorInvalidValue;
-        if (rpw > 64 * CHAIN_STRIDE) return hipErrorInvalidValue;      // a wavefront parks one pair of rows per lane
+        if (v > 0x3FFFFFFF || word > 0x3FFFFFFF) return false;
+        if (rpw > 64 * CHAIN_STRIDE) return false;             // a wavefront parks one pair of rows per lane
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
+    hd->magic = IFLOW_CHAIN_MAGIC; hd->nphases = c.nphases; hd->nmatrices = nmat; hd->grid = grid; hd->max_strips = max_strips;
+    return true;
+}
+
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, hipStream_t s)
+{
+    int g = 0;
+    hipError_t e = chain_grid_for_device(&g);                  // (raises the kernel's LDS limit on this device if it has not been)
+    if (e != hipSuccess) return e;
+    if (g != grid || max_strips < 1 || max_strips > CHAIN_MAX_STRIPS) return hipErrorInvalidValue;   // planned for another device
     const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES;
-    hipLaunchKernelGGL((q3h_chain_kernel<2>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, a,
+    hipLaunchKernelGGL((q3h_chain_kernel<2>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
                        static_cast<uint32_t *>(workspace));
     return hipGetLastError();
 }

@@ -20,8 +20,14 @@ BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 
                    Q2_B32: 3.0}
 
 OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE, ERR_TIMEOUT = range(8)
-CHAIN_MAX_PHASES, CHAIN_MAX_MATRICES = 32, 56
+CHAIN_MAX_PHASES, CHAIN_MAX_GROUP, CHAIN_MAX_MATRICES = 1024, 4, 4096
 ATTN_STATIC_MAX_HEADS = 128
+
+
+class Chain(C.Structure):
+    """iflow_chain_t: what iflow_qgemv_chain_plan fills and iflow_qgemv_chain_launch takes (plain data)."""
+    _fields_ = [("plan", C.c_void_p), ("workspace", C.c_void_p), ("grid", C.c_int32), ("max_strips", C.c_int32),
+                ("magic", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class IflowError(RuntimeError):
@@ -68,9 +74,11 @@ def lib():
         L.iflow_attn_decode_static.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p]
         L.iflow_rope_append.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, C.c_int, p, p, p]
         L.iflow_qgemv_chain_workspace_bytes.argtypes = [C.c_int, C.POINTER(i64), C.POINTER(sz)]
-        L.iflow_qgemv_chain.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
-                                        C.POINTER(i64), C.POINTER(p), p, sz, p]
-        L.iflow_qgemv_chain_check.argtypes = [p, p]
+        L.iflow_qgemv_chain_plan_bytes.argtypes = [C.c_int, C.c_int, C.POINTER(sz)]
+        L.iflow_qgemv_chain_plan.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
+                                             C.POINTER(i64), C.POINTER(p), p, sz, p, sz, p, C.POINTER(Chain)]
+        L.iflow_qgemv_chain_launch.argtypes = [C.POINTER(Chain), p]
+        L.iflow_qgemv_chain_check.argtypes = [C.POINTER(Chain), p]
         _lib = L
     return _lib
 
@@ -220,9 +228,7 @@ def qgemv_chain_workspace_bytes(rows_list) -> int:
     return int(out.value)
 
 
-def qgemv_chain(fmt: int, phases, workspace, workspace_bytes: int, stream=None) -> None:
-    """One launch for a chain of batch-1 products.  `phases` is a list of (cols, x, [(packed, rows, y), ...]);
-    x may be the y tensor of a matrix of an earlier phase.  `workspace`: zeroed once, uint8 device tensor."""
+def _chain_arrays(phases):
     nph = len(phases)
     mats = [m for (_, _, ms) in phases for m in ms]
     n = len(mats)
@@ -232,10 +238,30 @@ def qgemv_chain(fmt: int, phases, workspace, workspace_bytes: int, stream=None) 
     pk = (C.c_void_p * n)(*[_ptr(m[0]) for m in mats])
     rs = (C.c_int64 * n)(*[int(m[1]) for m in mats])
     ys = (C.c_void_p * n)(*[_ptr(m[2]) for m in mats])
-    _check(lib().iflow_qgemv_chain(fmt, nph, counts, cols, xs, pk, rs, ys, _ptr(workspace), workspace_bytes,
-                                   _stream(stream)), "iflow_qgemv_chain")
+    return nph, counts, cols, xs, pk, rs, ys
 
 
-def qgemv_chain_check(workspace, stream=None) -> None:
+def qgemv_chain_plan_bytes(phases) -> int:
+    """Size of the plan.  `phases`: list of (cols, x, [(packed, rows, y), ...])."""
+    out = C.c_size_t(0)
+    _check(lib().iflow_qgemv_chain_plan_bytes(len(phases), sum(len(ms) for (_, _, ms) in phases), C.byref(out)), "iflow_qgemv_chain_plan_bytes")
+    return int(out.value)
+
+
+def qgemv_chain_plan(fmt: int, phases, plan, plan_bytes: int, workspace, workspace_bytes: int, stream=None) -> Chain:
+    """Compiles a chain of batch-1 products once.  `phases` is a list of (cols, x, [(packed, rows, y), ...]); x may be the y
+    tensor of a matrix of an earlier phase.  `plan`, `workspace`: uint8 device tensors the chain keeps using."""
+    nph, counts, cols, xs, pk, rs, ys = _chain_arrays(phases)
+    chain = Chain()
+    _check(lib().iflow_qgemv_chain_plan(fmt, nph, counts, cols, xs, pk, rs, ys, _ptr(plan), plan_bytes, _ptr(workspace),
+                                        workspace_bytes, _stream(stream), C.byref(chain)), "iflow_qgemv_chain_plan")
+    return chain
+
+
+def qgemv_chain_launch(chain: Chain, stream=None) -> None:
+    _check(lib().iflow_qgemv_chain_launch(C.byref(chain), _stream(stream)), "iflow_qgemv_chain_launch")
+
+
+def qgemv_chain_check(chain: Chain, stream=None) -> None:
     """Synchronises the stream; raises IflowError(ERR_TIMEOUT) if a chained launch gave up a wait."""
-    _check(lib().iflow_qgemv_chain_check(_ptr(workspace), _stream(stream)), "iflow_qgemv_chain_check")
+    _check(lib().iflow_qgemv_chain_check(C.byref(chain), _stream(stream)), "iflow_qgemv_chain_check")

@@ -1,4 +1,4 @@
-"""GPU parity of the chained launch (iflow_qgemv_chain): every phase against the CPU oracle and against the
+"""GPU parity of the chained launch (iflow_qgemv_chain_plan / _launch): every phase against the CPU oracle and against the
 single-product kernel on the same inputs; repeated launches, HIP-graph replays, decoder-layer shapes."""
 import sys
 
@@ -11,18 +11,47 @@ from test_gpu_parity import TOL, gpu, gpu_quantize, rel_err, say  # noqa: F401
 pytestmark = pytest.mark.gpu
 
 
+class Arena:
+    """All outputs of a chain as views of one allocation (also makes sure that views, not only whole tensors, work)."""
+
+    def __init__(self, torch, nbytes):
+        self.torch = torch
+        self.buf = torch.empty((nbytes // 2,), dtype=torch.float16, device="cuda")
+        self.used = 0
+
+    def take(self, rows):
+        n = (rows + 127) // 128 * 128
+        assert self.used + n <= self.buf.numel()
+        v = self.buf[self.used:self.used + rows]
+        self.used += n
+        v.fill_(float("nan"))
+        return v
+
+
+def plan_chain(torch, iflow, phases, stream=None):
+    """Workspace and plan buffers (filled with 0xFF first: the plan call has to zero what it needs) and the compiled chain."""
+    rows_all = [m[1] for ph in phases for m in ph[2]]
+    ws_bytes = iflow.qgemv_chain_workspace_bytes(rows_all)
+    plan_bytes = iflow.qgemv_chain_plan_bytes(phases)
+    ws = torch.full((ws_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    plan = torch.full((plan_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    chain = iflow.qgemv_chain_plan(iflow.Q3H_B64, phases, plan, plan_bytes, ws, ws_bytes, stream=stream)
+    return chain, (plan, ws)
+
+
 def build_chain(torch, iflow, spec, seed, sigma=0.02):
     """spec: list of phases (cols, src, [rows...]) with src None (fresh input) or (phase, matrix) of an earlier
-    phase.  Returns device phases for iflow.qgemv_chain plus host copies of the weights."""
+    phase.  Returns device phases for iflow.qgemv_chain_plan, host copies of the weights, the compiled chain and its
+    buffers."""
     fmt = iflow.Q3H_B64
+    arena = Arena(torch, 2 * sum((r + 127) // 128 * 128 for _, _, rl in spec for r in rl) + 4096)
     phases, host = [], []
     for p, (cols, src, row_list) in enumerate(spec):
         mats, hw = [], []
         for j, rows in enumerate(row_list):
             w = synth.weights(rows, cols, sigma, seed + 100 * p + j)
             packed, _ = gpu_quantize(torch, iflow, fmt, w)
-            y = torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")
-            mats.append((packed, rows, y))
+            mats.append((packed, rows, arena.take(rows)))
             hw.append(w)
         if src is None:
             x = torch.from_numpy(synth.activations(1, cols, seed + 7 + p)[0].view(np.int16)).cuda().view(torch.float16)
@@ -31,10 +60,13 @@ def build_chain(torch, iflow, spec, seed, sigma=0.02):
             assert x.numel() == cols
         phases.append((cols, x, mats))
         host.append(hw)
-    rows_all = [m[1] for ph in phases for m in ph[2]]
-    nbytes = iflow.qgemv_chain_workspace_bytes(rows_all)
-    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
-    return phases, host, ws, nbytes
+    chain, keep = plan_chain(torch, iflow, phases)
+    return phases, host, chain, keep
+
+
+def same_as_single_product(got16, ref16):
+    """The chain runs the single-product kernel's loads, decode and sums in the same order: equal bit for bit."""
+    return bool(np.array_equal(got16, ref16))
 
 
 def check_phases(torch, iflow, orc, phases, host, what):
@@ -52,7 +84,7 @@ def check_phases(torch, iflow, orc, phases, host, what):
             single = torch.empty((rows,), dtype=torch.float16, device="cuda")
             iflow.qgemv(fmt, packed, rows, cols, x, single)
             torch.cuda.synchronize()
-            assert np.array_equal(got.view(np.uint16), single.cpu().numpy().view(np.uint16)), f"{what}: phase {p} matrix {j}"
+            assert same_as_single_product(got.view(np.uint16), single.cpu().numpy().view(np.uint16)), f"{what}: phase {p} matrix {j}"
 
 
 SPEC_RAGGED = [
@@ -67,7 +99,7 @@ SPEC_RAGGED = [
 def test_chain_ragged_phases_and_relaunch(gpu, orc):
     torch, iflow = gpu
     say("[case] chain ragged spec, three launches with new inputs")
-    phases, host, ws, nbytes = build_chain(torch, iflow, SPEC_RAGGED, synth.BASE_SEED + 500, sigma=0.03)
+    phases, host, chain, keep = build_chain(torch, iflow, SPEC_RAGGED, synth.BASE_SEED + 500, sigma=0.03)
     for it in range(3):
         if it:
             for p, (cols, x, _) in enumerate(phases):
@@ -76,46 +108,46 @@ def test_chain_ragged_phases_and_relaunch(gpu, orc):
             for _, _, mats in phases:
                 for m in mats:
                     m[2].fill_(float("nan"))
-        iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
-        iflow.qgemv_chain_check(ws)
+        iflow.qgemv_chain_launch(chain)
+        iflow.qgemv_chain_check(chain)
         check_phases(torch, iflow, orc, phases, host, f"launch {it}")
 
 
 def test_chain_single_phase_is_qgemv(gpu, orc):
     torch, iflow = gpu
     say("[case] chain of one phase, 1024x1024")
-    phases, host, ws, nbytes = build_chain(torch, iflow, [(1024, None, [1024])], synth.BASE_SEED + 520)
-    iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
-    iflow.qgemv_chain_check(ws)
+    phases, host, chain, keep = build_chain(torch, iflow, [(1024, None, [1024])], synth.BASE_SEED + 520)
+    iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
     check_phases(torch, iflow, orc, phases, host, "single")
 
 
 def test_chain_of_32_phases_many_launches(gpu, orc):
-    """The longest chain the entry point takes, each phase feeding the next, launched many times in a row."""
+    """A chain of 32 tiny phases, each feeding the next (hand-overs dominate), launched many times in a row."""
     torch, iflow = gpu
     say("[case] chain of 32 dependent phases, 512 <-> 320 columns, 40 launches")
     spec = [(512, None, [320])]
     for p in range(1, 32):
         spec.append((320, (p - 1, 0), [512]) if p % 2 else (512, (p - 1, 0), [320]))
-    phases, host, ws, nbytes = build_chain(torch, iflow, spec, synth.BASE_SEED + 700, sigma=0.05)
+    phases, host, chain, keep = build_chain(torch, iflow, spec, synth.BASE_SEED + 700, sigma=0.05)
     for it in range(40):
-        iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
-    iflow.qgemv_chain_check(ws)
+        iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
     check_phases(torch, iflow, orc, phases, host, "after 40 launches")
-    with pytest.raises(iflow.IflowError) as ei:
-        iflow.qgemv_chain(iflow.Q3H_B64, phases + [phases[0]], ws, nbytes)
+    with pytest.raises(iflow.IflowError) as ei:                 # the same matrix twice: two outputs overlap
+        plan_chain(torch, iflow, phases + [phases[0]])
     assert ei.value.status == iflow.ERR_SHAPE
 
 
 def test_chain_with_the_most_matrices(gpu, orc):
-    """56 matrices in one launch (14 phases of four): every descriptor slot of the kernel's argument block is in use."""
+    """56 matrices in one launch: 14 phases of four, each phase reading one output of the phase before."""
     torch, iflow = gpu
     say("[case] chain of 14 phases x 4 matrices, 128x128")
     spec = [(128, None, [128] * 4)] + [(128, (p - 1, p % 4), [128] * 4) for p in range(1, 14)]
-    phases, host, ws, nbytes = build_chain(torch, iflow, spec, synth.BASE_SEED + 800, sigma=0.08)
+    phases, host, chain, keep = build_chain(torch, iflow, spec, synth.BASE_SEED + 800, sigma=0.08)
     for it in range(3):
-        iflow.qgemv_chain(iflow.Q3H_B64, phases, ws, nbytes)
-    iflow.qgemv_chain_check(ws)
+        iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
     check_phases(torch, iflow, orc, phases, host, "56 matrices")
 
 
@@ -128,7 +160,7 @@ def test_chain_decoder_layer_7b_and_graph_replay(gpu, orc):
     torch, iflow = gpu
     say("[case] chain 7B decoder layer: q/k/v -> o -> gate/up -> down, eager then five HIP-graph replays")
     spec = layer_spec(4096, 11008)
-    phases, host, ws, nbytes = build_chain(torch, iflow, spec, synth.BASE_SEED + 540, sigma=0.012)
+    phases, host, chain, keep = build_chain(torch, iflow, spec, synth.BASE_SEED + 540, sigma=0.012)
     fmt = iflow.Q3H_B64
 
     def reference():                       # the launches the chain replaces, on the same buffers
@@ -148,10 +180,10 @@ def test_chain_decoder_layer_7b_and_graph_replay(gpu, orc):
         for p, (_, _, mats) in enumerate(phases):
             for j, m in enumerate(mats):
                 got = m[2].cpu().numpy().view(np.uint16)
-                assert np.array_equal(got, ref[p][j]), f"{what}: phase {p} matrix {j}: {(got != ref[p][j]).sum()} of {got.size} differ"
+                assert same_as_single_product(got, ref[p][j]), f"{what}: phase {p} matrix {j}: {(got != ref[p][j]).sum()} of {got.size} differ"
 
-    iflow.qgemv_chain(fmt, phases, ws, nbytes)
-    iflow.qgemv_chain_check(ws)
+    iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
     compare("eager")
     # sampled rows of the last phase against the oracle
     ofmt = orc.FORMATS["Q3H_B64"]
@@ -169,7 +201,7 @@ def test_chain_decoder_layer_7b_and_graph_replay(gpu, orc):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
-            iflow.qgemv_chain(fmt, phases, ws, nbytes, stream=side)
+            iflow.qgemv_chain_launch(chain, stream=side)
     torch.cuda.current_stream().wait_stream(side)
     for rep in range(5):
         x0 = phases[0][1]
@@ -182,7 +214,7 @@ def test_chain_decoder_layer_7b_and_graph_replay(gpu, orc):
         if rep % 2:
             graph.replay()                 # back-to-back replays: the second starts from the first one's workspace
         torch.cuda.synchronize()
-        iflow.qgemv_chain_check(ws)
+        iflow.qgemv_chain_check(chain)
         compare(f"replay {rep}")
 
 
@@ -199,6 +231,7 @@ def test_chain_decoder_layer_70b_shapes(gpu, orc):
             (hidden, (1, 0), [ffn, ffn]), (ffn, (2, 0), [hidden])]
     gen = torch.Generator(device="cuda")
     gen.manual_seed(synth.BASE_SEED + 900)
+    arena = Arena(torch, 2 * sum(r + 128 for _, _, rl in spec for r in rl))
     phases, kept = [], {}
     for p, (cols, src, row_list) in enumerate(spec):
         mats = []
@@ -211,17 +244,16 @@ def test_chain_decoder_layer_70b_shapes(gpu, orc):
                 idx = synth.sample_rows(rows, 32, synth.BASE_SEED + 901 + p)
                 kept[(p, j)] = (idx, wd[torch.from_numpy(idx).cuda()].cpu().numpy())
             del wd
-            mats.append((packed, rows, torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")))
+            mats.append((packed, rows, arena.take(rows)))
         if src is None:
             x = torch.from_numpy(synth.activations(1, cols, synth.BASE_SEED + 902)[0].view(np.int16)).cuda().view(torch.float16)
         else:
             x = phases[src[0]][2][src[1]][2]
         phases.append((cols, x, mats))
-    nbytes = iflow.qgemv_chain_workspace_bytes([m[1] for ph in phases for m in ph[2]])
-    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
+    chain, keep = plan_chain(torch, iflow, phases)
     for it in range(2):
-        iflow.qgemv_chain(fmt, phases, ws, nbytes)
-    iflow.qgemv_chain_check(ws)
+        iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
     xin = phases[0][1]
     for p, (cols, _, mats) in enumerate(phases):
         ys = [torch.empty((m[1],), dtype=torch.float16, device="cuda") for m in mats]
@@ -229,7 +261,7 @@ def test_chain_decoder_layer_70b_shapes(gpu, orc):
         torch.cuda.synchronize()
         for j, m in enumerate(mats):
             got, ref = m[2].cpu().numpy().view(np.uint16), ys[j].cpu().numpy().view(np.uint16)
-            assert np.array_equal(got, ref), f"phase {p} matrix {j}: {(got != ref).sum()} of {got.size} differ"
+            assert same_as_single_product(got, ref), f"phase {p} matrix {j}: {(got != ref).sum()} of {got.size} differ"
             if (p, j) in kept:
                 idx, w_rows = kept[(p, j)]
                 q, s, o = orc.quantize(ofmt, w_rows)
@@ -252,6 +284,7 @@ def test_chain_benchmark_configuration_eight_layers(gpu, orc):
     say(f"[case] chain of {nlayers} 7B-shaped layers in one launch")
     gen = torch.Generator(device="cuda")
     gen.manual_seed(synth.BASE_SEED + 1000)
+    arena = Arena(torch, 2 * nlayers * (4 * (hidden + 128) + 2 * (ffn + 128) + (hidden + 128)))
     phases, kept = [], {}
     x0 = torch.from_numpy((synth.activations(1, hidden, synth.BASE_SEED + 1001)[0].astype(np.float32) * 2.0 ** -10)
                           .astype(np.float16).view(np.int16)).cuda().view(torch.float16)
@@ -271,22 +304,21 @@ def test_chain_benchmark_configuration_eight_layers(gpu, orc):
                     idx = synth.sample_rows(rows, 16, synth.BASE_SEED + 1002 + p)
                     kept[(base + p, j)] = (idx, wd[torch.from_numpy(idx).cuda()].cpu().numpy())
                 del wd
-                mats.append((packed, rows, torch.full((rows,), float("nan"), dtype=torch.float16, device="cuda")))
+                mats.append((packed, rows, arena.take(rows)))
             x = x0 if src is None else phases[src[0]][2][src[1]][2]
             phases.append((cols, x, mats))
         prev_down = (base + 3, 0)
-    nbytes = iflow.qgemv_chain_workspace_bytes([m[1] for ph in phases for m in ph[2]])
-    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
+    chain, keep = plan_chain(torch, iflow, phases)
     for it in range(2):
-        iflow.qgemv_chain(fmt, phases, ws, nbytes)
-    iflow.qgemv_chain_check(ws)
+        iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
     for p, (cols, x, mats) in enumerate(phases):
         ys = [torch.empty((m[1],), dtype=torch.float16, device="cuda") for m in mats]
         iflow.qgemv_multi(fmt, [m[0] for m in mats], [m[1] for m in mats], cols, x, ys)
         torch.cuda.synchronize()
         for j, m in enumerate(mats):
             got, ref = m[2].cpu().numpy().view(np.uint16), ys[j].cpu().numpy().view(np.uint16)
-            assert np.array_equal(got, ref), f"phase {p} matrix {j}: {(got != ref).sum()} of {got.size} differ"
+            assert same_as_single_product(got, ref), f"phase {p} matrix {j}: {(got != ref).sum()} of {got.size} differ"
             if (p, j) in kept:
                 idx, w_rows = kept[(p, j)]
                 q, s, o = orc.quantize(ofmt, w_rows)

@@ -76,20 +76,23 @@ def test_argument_validation_happens_before_any_launch(iflow):
 
 
 def test_chain_validation_happens_before_any_launch(iflow):
-    """iflow_qgemv_chain: limits, aliasing rules and workspace size are checked on the host (no launch on any error)."""
+    """iflow_qgemv_chain_plan: limits, aliasing rules and buffer sizes are checked on the host (no device call on any of
+    these errors: this test runs without a GPU)."""
     L = iflow.lib()
     base = 0x100000                                                              # aligned, never dereferenced
 
-    def call(fmt, counts, cols, x, packed, rows, y, ws=base * 64, ws_bytes=1 << 30):
+    def call(fmt, counts, cols, x, packed, rows, y, ws=base * 64, ws_bytes=1 << 30, plan=base * 128, plan_bytes=1 << 30):
         nph, n = len(counts), len(rows)
-        return L.iflow_qgemv_chain(fmt, nph, (C.c_int * max(nph, 1))(*counts), (C.c_int64 * max(nph, 1))(*cols),
-                                   (C.c_void_p * max(nph, 1))(*x), (C.c_void_p * max(n, 1))(*packed),
-                                   (C.c_int64 * max(n, 1))(*rows), (C.c_void_p * max(n, 1))(*y), ws, ws_bytes, None)
+        chain = iflow.Chain()
+        return L.iflow_qgemv_chain_plan(fmt, nph, (C.c_int * max(nph, 1))(*counts), (C.c_int64 * max(nph, 1))(*cols),
+                                        (C.c_void_p * max(nph, 1))(*x), (C.c_void_p * max(n, 1))(*packed),
+                                        (C.c_int64 * max(n, 1))(*rows), (C.c_void_p * max(n, 1))(*y), plan, plan_bytes, ws, ws_bytes,
+                                        None, C.byref(chain))
 
     x0, pk, y0, y1 = base, base * 2, base * 3, base * 4
     assert call(3, [1], [64], [x0], [pk], [8], [y0]) == iflow.ERR_FORMAT         # 3.5-bit format only
     assert call(4, [], [], [], [], [], []) == iflow.ERR_SHAPE                    # no phase
-    assert call(4, [1] * 33, [64] * 33, [x0] * 33, [pk] * 33, [8] * 33, [y0] * 33) == iflow.ERR_SHAPE
+    assert call(4, [1] * 1025, [64] * 1025, [x0] * 1025, [pk] * 1025, [8] * 1025, [y0 + 64 * i for i in range(1025)]) == iflow.ERR_SHAPE
     assert call(4, [5], [64], [x0], [pk] * 5, [8] * 5, [y0 + 64 * i for i in range(5)]) == iflow.ERR_SHAPE   # > 4 per phase
     assert call(4, [1], [100], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE         # cols % 64
     assert call(4, [1], [131072], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE      # cols > 65536
@@ -99,13 +102,27 @@ def test_chain_validation_happens_before_any_launch(iflow):
     # x of phase 1 = y of phase 0 is fine only if it is the whole vector (rows == cols) ...
     assert call(4, [1, 1], [64, 128], [x0, y0], [pk, pk], [64, 8], [y0, y1]) == iflow.ERR_SHAPE    # 64 rows feeding 128 columns
     assert call(4, [1, 1], [64, 64], [x0, y0 + 32], [pk, pk], [128, 8], [y0, y1]) == iflow.ERR_SHAPE   # the middle of an output
+    # ... a launch input must not be overlapped by ANY output of the call, also not by a later phase's ...
+    assert call(4, [1, 1, 1], [64, 64, 64], [x0, y1 + 4096, y0], [pk, pk, pk], [64, 64, 64], [y0, y0 + 4096, y1 + 4096]) == iflow.ERR_SHAPE
+    # ... two outputs must not overlap ...
+    assert call(4, [2], [64], [x0], [pk, pk], [64, 64], [y0, y0 + 64]) == iflow.ERR_SHAPE
     # ... and the workspace has to hold the hand-over words
     sz = C.c_size_t(0)
     assert L.iflow_qgemv_chain_workspace_bytes(2, (C.c_int64 * 2)(64, 8), C.byref(sz)) == iflow.OK
     assert sz.value == 4096 + 2 * 4096 * 4
     assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], ws_bytes=sz.value - 1) == iflow.ERR_SIZE
-    assert L.iflow_qgemv_chain_workspace_bytes(57, (C.c_int64 * 57)(*[8] * 57), C.byref(sz)) == iflow.ERR_SHAPE
+    assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], ws=None) == iflow.ERR_NULL
+    assert L.iflow_qgemv_chain_plan_bytes(2, 2, C.byref(sz)) == iflow.OK and sz.value == 64 + 2 * 64 + 2 * 32
+    assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], plan_bytes=sz.value - 1) == iflow.ERR_SIZE
+    assert L.iflow_qgemv_chain_plan_bytes(0, 0, C.byref(sz)) == iflow.ERR_SHAPE
+    assert L.iflow_qgemv_chain_plan_bytes(2, 5000, C.byref(sz)) == iflow.ERR_SHAPE
+    assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], plan=base * 128 + 4) == iflow.ERR_ALIGN
+    assert L.iflow_qgemv_chain_workspace_bytes(4097, (C.c_int64 * 4097)(*[8] * 4097), C.byref(sz)) == iflow.ERR_SHAPE
     assert L.iflow_qgemv_chain_check(None, None) == iflow.ERR_NULL
+    assert L.iflow_qgemv_chain_launch(None, None) == iflow.ERR_NULL
+    blank = iflow.Chain()
+    blank.plan, blank.workspace = base, base * 2                                 # never filled by a plan call: refused by its magic word
+    assert L.iflow_qgemv_chain_launch(C.byref(blank), None) == iflow.ERR_SHAPE
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):
