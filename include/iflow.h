@@ -203,7 +203,7 @@ typedef struct iflow_chain_t {
     void *plan;                 /* device */
     void *workspace;            /* device */
     int32_t grid, max_strips;   /* launch geometry the plan was written for */
-    uint32_t magic, reserved;
+    uint32_t magic, fused;      /* fused: the plan uses the modules of iflow_qgemv_chain_plan_fused */
 } iflow_chain_t;
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes);
 iflow_status_t iflow_qgemv_chain_plan_bytes(int nphases, int nmatrices, size_t *bytes);
@@ -211,6 +211,26 @@ iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const 
                                       const uint16_t *const *x, const void *const *packed, const int64_t *rows,
                                       uint16_t *const *y, void *plan, size_t plan_bytes, void *workspace,
                                       size_t workspace_bytes, void *stream, iflow_chain_t *chain);
+/* iflow_qgemv_chain_plan with the modules that sit between the products of a decoder layer (Section 2's module table:
+ * normalization "rms", activation "silu"; Section 5's Infer() applies them between the products) inside the same launch,
+ * so that a launch can run whole layers: e.g. o + residual -> rms norm -> silu(gate) * up -> down + residual -> rms norm ->
+ * the next layer's q, k, v as four phases.  Arguments as iflow_qgemv_chain_plan, plus (each array may be null = none):
+ *   x_op     per phase: IFLOW_X_PLAIN, or IFLOW_X_RMS_GAIN: the phase multiplies the rms-normalized input,
+ *            y = (W' v) / sqrt(mean_k x_k^2 + eps[p]) with v_k = fp16(x_k aux[p]_k), as in iflow_qgemv_fused
+ *            (aux[p]: the gains, [cols[p]] fp16, an input of the launch that no output overlaps).  IFLOW_X_SILU_MUL:
+ *            IFLOW_ERR_SHAPE (use a gated phase).
+ *   gated    per phase: nonzero = the phase has exactly two matrices of equal size, the gate and the up projection of a
+ *            gated feed-forward, and ONE output y[gate] = fp16(silu(c (W'_gate v)_n) * (c (W'_up v)_n)) ([rows] fp16; c the
+ *            normalization's scalar or 1), as in iflow_qgemv_gated; y[up] must be null.  Later phases may take y[gate] as input.
+ *   residual per matrix: null, or a vector [rows[m]] fp16 added to the output before its one rounding to fp16: an input of
+ *            the launch that no output overlaps (4-byte aligned), or exactly the output y[i] of a matrix of an earlier phase
+ *            (not the phase's own input's producer or later: it must be complete when the phase starts).  Not for gated phases.
+ * A plan without any module is the plan of iflow_qgemv_chain_plan (same kernel, same bits). */
+iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                            const uint16_t *const *x, const iflow_x_op_t *x_op, const uint16_t *const *aux,
+                                            const float *eps, const int *gated, const void *const *packed, const int64_t *rows,
+                                            const uint16_t *const *residual, uint16_t *const *y, void *plan, size_t plan_bytes,
+                                            void *workspace, size_t workspace_bytes, void *stream, iflow_chain_t *chain);
 iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream);
 iflow_status_t iflow_qgemv_chain_check(const iflow_chain_t *chain, void *stream);
 

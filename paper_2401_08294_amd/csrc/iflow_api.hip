@@ -308,9 +308,17 @@ iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint1
 namespace {
 
 // Everything that can be checked about a chain on the host; fills the index arrays the plan builder wants.
+struct ChainOps {                      // the modules around the products; every pointer may be null (bare products)
+    const iflow_x_op_t *x_op;
+    const uint16_t *const *aux;
+    const float *eps;
+    const int *gated;
+    const uint16_t *const *residual;
+};
+
 iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *counts, const int64_t *cols, const uint16_t *const *x,
-                              const void *const *packed, const int64_t *rows, uint16_t *const *y, std::vector<int> &first,
-                              std::vector<int> &x_src, int *nmatrices)
+                              const void *const *packed, const int64_t *rows, uint16_t *const *y, const ChainOps &ops,
+                              std::vector<int> &first, std::vector<int> &x_src, std::vector<int> &residual_src, int *nmatrices)
 {
     iflow::FormatInfo fi;
     if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
@@ -330,11 +338,25 @@ iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *cou
         if (!x[p]) return IFLOW_ERR_NULL;
         if (!aligned16(x[p])) return IFLOW_ERR_ALIGN;
         if (cols[p] > 65536) return IFLOW_ERR_SHAPE;
+        const bool gated = ops.gated && ops.gated[p];
+        if (gated && (counts[p] != 2 || rows[first[p]] != rows[first[p] + 1])) return IFLOW_ERR_SHAPE;   // a gate and an up matrix of equal size
         for (int m = first[p]; m < first[p] + counts[p]; ++m) {
             iflow_status_t st = check_shape(format, rows[m], cols[p], &fi);
             if (st != IFLOW_OK) return st;
-            if (!packed[m] || !y[m]) return IFLOW_ERR_NULL;
-            if (!aligned16(packed[m]) || !aligned16(y[m])) return IFLOW_ERR_ALIGN;
+            const bool no_output = gated && m == first[p] + 1;                   // the up matrix of a gated pair has no output of its own
+            if (!packed[m] || (!y[m] && !no_output)) return IFLOW_ERR_NULL;
+            if (no_output && y[m]) return IFLOW_ERR_SHAPE;
+            if (!aligned16(packed[m]) || (y[m] && !aligned16(y[m]))) return IFLOW_ERR_ALIGN;
+            if (gated && ops.residual && ops.residual[m]) return IFLOW_ERR_SHAPE;
+        }
+        if (ops.x_op) {
+            if (ops.x_op[p] == IFLOW_X_RMS_GAIN) {
+                if (!ops.aux || !ops.aux[p] || !ops.eps) return IFLOW_ERR_NULL;
+                if (!aligned16(ops.aux[p])) return IFLOW_ERR_ALIGN;
+                if (!(ops.eps[p] >= 0.0f && ops.eps[p] < 3.0e38f)) return IFLOW_ERR_SHAPE;
+            } else if (ops.x_op[p] != IFLOW_X_PLAIN) {
+                return IFLOW_ERR_SHAPE;                                          // (the gated input comes from a gated phase, not from an x_op)
+            }
         }
     }
     // Outputs must not overlap each other.  An activation vector is either exactly the whole output of a matrix of an
@@ -343,12 +365,28 @@ iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *cou
     // an earlier phase's input.
     for (int i = 0; i < total; ++i)
         for (int j = i + 1; j < total; ++j)
-            if (overlaps(y[i], rows[i] * 2, y[j], rows[j] * 2)) return IFLOW_ERR_SHAPE;
+            if (y[i] && y[j] && overlaps(y[i], rows[i] * 2, y[j], rows[j] * 2)) return IFLOW_ERR_SHAPE;
     for (int p = 0; p < nphases; ++p) {
         for (int i = 0; i < total; ++i) {
+            if (!y[i]) continue;
+            if (ops.x_op && ops.x_op[p] == IFLOW_X_RMS_GAIN && overlaps(ops.aux[p], cols[p] * 2, y[i], rows[i] * 2)) return IFLOW_ERR_SHAPE;
             if (!overlaps(x[p], cols[p] * 2, y[i], rows[i] * 2)) continue;
             if (i < first[p] && static_cast<const void *>(x[p]) == static_cast<const void *>(y[i]) && rows[i] == cols[p] && x_src[p] < 0) x_src[p] = i;
             else return IFLOW_ERR_SHAPE;
+        }
+    }
+    // a residual is an input of the launch that no output overlaps, or exactly the output of a matrix of an earlier phase
+    residual_src.assign(total, -1);
+    for (int p = 0; p < nphases && ops.residual; ++p) {
+        for (int m = first[p]; m < first[p] + counts[p]; ++m) {
+            if (!ops.residual[m]) continue;
+            if ((reinterpret_cast<uintptr_t>(ops.residual[m]) & 3u) != 0) return IFLOW_ERR_ALIGN;
+            for (int i = 0; i < total; ++i) {
+                if (!y[i] || !overlaps(ops.residual[m], rows[m] * 2, y[i], rows[i] * 2)) continue;
+                if (i < first[p] && static_cast<const void *>(ops.residual[m]) == static_cast<const void *>(y[i]) && rows[i] == rows[m] &&
+                    residual_src[m] < 0) residual_src[m] = i;
+                else return IFLOW_ERR_SHAPE;
+            }
         }
     }
     return IFLOW_OK;
@@ -374,14 +412,16 @@ iflow_status_t iflow_qgemv_chain_plan_bytes(int nphases, int nmatrices, size_t *
     return IFLOW_OK;
 }
 
-iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
-                                      const uint16_t *const *x, const void *const *packed, const int64_t *rows,
-                                      uint16_t *const *y, void *plan, size_t plan_bytes, void *workspace,
-                                      size_t workspace_bytes, void *stream, iflow_chain_t *chain)
+iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                            const uint16_t *const *x, const iflow_x_op_t *x_op, const uint16_t *const *aux,
+                                            const float *eps, const int *gated, const void *const *packed, const int64_t *rows,
+                                            const uint16_t *const *residual, uint16_t *const *y, void *plan, size_t plan_bytes,
+                                            void *workspace, size_t workspace_bytes, void *stream, iflow_chain_t *chain)
 {
-    std::vector<int> first, x_src;
+    std::vector<int> first, x_src, residual_src;
     int total = 0;
-    iflow_status_t st = chain_validate(format, nphases, counts, cols, x, packed, rows, y, first, x_src, &total);
+    const ChainOps ops = {x_op, aux, eps, gated, residual};
+    iflow_status_t st = chain_validate(format, nphases, counts, cols, x, packed, rows, y, ops, first, x_src, residual_src, &total);
     if (st != IFLOW_OK) return st;
     if (!plan || !workspace || !chain) return IFLOW_ERR_NULL;
     if (!aligned16(plan) || !aligned16(workspace)) return IFLOW_ERR_ALIGN;
@@ -390,7 +430,10 @@ iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const 
     int grid = 0;
     hipError_t e = iflow::chain_grid_for_device(&grid);
     if (e != hipSuccess) return device_status(e);
-    iflow::ChainSpec spec = {nphases, counts, first.data(), cols, x, x_src.data(), packed, rows, y};
+    std::vector<int> xop_int(nphases, IFLOW_X_PLAIN);
+    for (int p = 0; p < nphases && x_op; ++p) xop_int[p] = (int)x_op[p];
+    iflow::ChainSpec spec = {nphases, counts, first.data(), cols, x, x_src.data(), packed, rows, y,
+                             xop_int.data(), aux, eps, gated, residual, residual_src.data()};
     std::vector<uint8_t> host;
     if (!iflow::chain_build_plan(spec, grid, host)) return IFLOW_ERR_SHAPE;   // more rows than the kernel's 32-bit indices cover
     hipStream_t s = (hipStream_t)stream;
@@ -400,17 +443,29 @@ iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const 
     if (e != hipSuccess) return device_status(e);
     int max_strips = 1;
     for (int p = 0; p < nphases; ++p) max_strips = std::max(max_strips, (int)((cols[p] / 64 + 63) / 64));
+    bool fused = false;
+    for (int p = 0; p < nphases; ++p) fused = fused || (x_op && x_op[p] != IFLOW_X_PLAIN) || (gated && gated[p]);
+    for (int m = 0; m < total && residual; ++m) fused = fused || residual[m] != nullptr;
     chain->plan = plan; chain->workspace = workspace;
     chain->grid = grid; chain->max_strips = max_strips;
-    chain->magic = IFLOW_CHAIN_MAGIC; chain->reserved = 0;
+    chain->magic = IFLOW_CHAIN_MAGIC; chain->fused = fused ? 1u : 0u;
     return IFLOW_OK;
+}
+
+iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
+                                      const uint16_t *const *x, const void *const *packed, const int64_t *rows,
+                                      uint16_t *const *y, void *plan, size_t plan_bytes, void *workspace,
+                                      size_t workspace_bytes, void *stream, iflow_chain_t *chain)
+{
+    return iflow_qgemv_chain_plan_fused(format, nphases, counts, cols, x, nullptr, nullptr, nullptr, nullptr, packed, rows, nullptr, y,
+                                        plan, plan_bytes, workspace, workspace_bytes, stream, chain);
 }
 
 iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream)
 {
     if (!chain || !chain->plan || !chain->workspace) return IFLOW_ERR_NULL;
     if (chain->magic != IFLOW_CHAIN_MAGIC) return IFLOW_ERR_SHAPE;
-    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->max_strips, (hipStream_t)stream);
+    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->max_strips, chain->fused != 0, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // planned for a device with another number of compute units
     return device_status(e);
 }

@@ -235,12 +235,19 @@ struct ChainSpec {
     const void *const *packed;         // per matrix
     const int64_t *rows;
     uint16_t *const *y;
+    // the modules around the products (all four may be null: bare products)
+    const int *x_op;                   // per phase: iflow_x_op_t
+    const uint16_t *const *aux;        // per phase: gains of IFLOW_X_RMS_GAIN
+    const float *eps;                  // per phase
+    const int *gated;                  // per phase: 1 = the phase's two matrices are the gate and up projections of a gated feed-forward
+    const uint16_t *const *residual;   // per matrix, entries may be null
+    const int *residual_src;           // per matrix: the matrix whose output is the residual, or -1 for an input of the launch
 };
 size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
 size_t chain_plan_bytes(int nphases, int nmatrices);
 bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out);
 hipError_t chain_grid_for_device(int *grid);
-hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, hipStream_t s);
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, hipStream_t s);
 hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int64_t cols,
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64_t cols,

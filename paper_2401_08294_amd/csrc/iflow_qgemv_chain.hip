@@ -52,8 +52,8 @@ constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_SEEN = 64;
 // of a model never change between tokens, so the chain is described once; a launch passes two pointers.  Everything a
 // wavefront needs when it enters a phase sits in one 64-byte descriptor, and everything about a matrix in one 32-byte
 // descriptor: a scalar load each, instead of a chain of dependent loads (a scalar load costs a few hundred nanoseconds
-// of latency, and a phase of a 7B layer lasts a few microseconds).  Layout: ChainHeader, then the phase descriptors, then
-// the matrix descriptors.
+// of latency, and a phase of a 7B layer lasts a few microseconds).  Layout: ChainHeader, the phase descriptors, the matrix
+// descriptors, the phases' operation records.
 struct ChainPhase {
     const uint16_t *x;          // activations when they are an input of the launch
     int first, count;           // matrices [first, first + count)
@@ -68,21 +68,34 @@ struct ChainPhase {
 struct ChainMatrix {
     const uint8_t *packed;
     uint16_t *y;
-    int rows;
+    int rows;                   // rows in the phase's row space; a gated pair: 2 x rows (row 2n = gate row n, row 2n+1 = up row n)
     int start;                  // first row of the matrix within its phase
     int tag_word;               // its tagged output, in 32-bit words from the workspace start
-    int pad_;
+    int gated;                  // 1: `packed` is the gate and `packed2` the up matrix of a gated feed-forward, one output per row pair
+    const uint8_t *packed2;
+    const uint16_t *residual;   // added to the output: an input of the launch ([rows] fp16) ...
+    int residual_tag_word;      // ... or the tagged output of an earlier matrix (0: none)
+    int pad_[3];
+};
+// what only the fused variant of the kernel reads about a phase
+struct ChainPhaseOps {
+    const uint16_t *aux;        // IFLOW_X_RMS_GAIN: the gains [cols] fp16 (an input of the launch)
+    float eps;
+    int x_op;                   // iflow_x_op_t
+    float inv_cols;
+    int pad_[3];
 };
 struct ChainHeader {
     uint32_t magic;
     int nphases, nmatrices, grid;
-    int max_strips, pad_[11];
+    int max_strips, fused, pad_[10];
 };
-static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 32 && sizeof(ChainHeader) == 64, "descriptor sizes");
+static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 64 && sizeof(ChainHeader) == 64 && sizeof(ChainPhaseOps) == 32, "descriptor sizes");
 // the two descriptor arrays of a plan, as the kernel indexes them
 struct ChainArgs {
     const ChainPhase *ph;
     const ChainMatrix *mat;
+    const ChainPhaseOps *ops;
 };
 
 // Position of output r inside a matrix's tagged vector, in 32-bit words.  A consumer thread stages one chunk of 16
@@ -112,12 +125,19 @@ struct ChainWalk {
     int seg_left;               // rows left in the current segment, the current one included
 };
 
-template <int S>
+// FUSED: the variant that also runs the modules between the products of a decoder layer (Section 2's module table: "rms"
+// normalization, "silu" activation; Section 5's Infer() applies them between the products): rms gains folded into the
+// staging of a phase's activations and the normalization's scalar into its outputs, the gate of a gated feed-forward
+// applied where its two projections are summed, residuals added at the store.  The plain variant is the code without any
+// of it (a launch of bare products pays nothing for the modules).
+template <int S, bool FUSED>
 __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws)
 {
     const ChainHeader *const hd = reinterpret_cast<const ChainHeader *>(plan);
     const ChainArgs a = {reinterpret_cast<const ChainPhase *>(plan + sizeof(ChainHeader)),
-                         reinterpret_cast<const ChainMatrix *>(plan + sizeof(ChainHeader)) + 2 * hd->nphases};
+                         reinterpret_cast<const ChainMatrix *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * sizeof(ChainPhase)),
+                         reinterpret_cast<const ChainPhaseOps *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * sizeof(ChainPhase) +
+                                                                 (size_t)hd->nmatrices * sizeof(ChainMatrix))};
     extern __shared__ __align__(16) uint8_t xs[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = IFLOW_UNI(tid >> 6);
@@ -159,7 +179,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
     int q_lt = 0, q_last = 0;                                  // its strip; the last strip of a row
     int q_nlast16 = 0;                                         // 16 x the blocks in that last strip (offset of its second plane)
     int q_rowjump = 0;                                         // from the last strip of a row to the wavefront's next row, bytes
-    int q_row1 = 0;                                            // from the first to the second row of the pair, bytes (0: no second row)
+    std::conditional_t<FUSED, int64_t, int> q_row1 = 0;        // from the first to the second row of the pair, bytes (0: no second row)
     int q_pad = 0;                                             // empty steps still owed by phase q.p
     uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
     const uint32_t voff_full = (uint32_t)lane * 16;
@@ -196,6 +216,13 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                 q_last = ph.nstrips - 1; q_nlast16 = nlast * 16;
                 q_rowjump = (CHAIN_STRIDE * ph.nbk - (ph.nstrips - 1) * 64) * 32;
                 q_row1 = single ? 0 : ph.nbk * 32;
+                if constexpr (FUSED) {
+                    if (a.mat[m].gated) {                      // rows 2n, 2n+1 of the row space are row n of the gate and of the up matrix
+                        q_wptr = a.mat[m].packed + (int64_t)(r >> 1) * ((int64_t)ph.nbk * 32);
+                        q_rowjump = ((CHAIN_STRIDE / 2) * ph.nbk - (ph.nstrips - 1) * 64) * 32;
+                        q_row1 = a.mat[m].packed2 - a.mat[m].packed;
+                    }
+                }
                 q_voff_last = voff_full & mask_lt(lane, nlast);                // lanes past a ragged end redo block 0
                 found = true;
             }
@@ -209,7 +236,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
         const uint32_t voff = last_strip ? q_voff_last : voff_full;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const uint8_t *row = q_wptr + u * q_row1;
+            const uint8_t *row = q_wptr + (int64_t)u * q_row1;
             // (pointers that were read from the plan have to be told that they point to global memory: a generic pointer
             // makes flat loads, whose completion cannot be counted, and every wait in the step loop becomes "all")
             const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + voff));
@@ -256,9 +283,25 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
         return global_ptr<const u32x4>(x + (int64_t)ts * 4096 + ccl * 16);
     };
     auto chunk_live = [&](int c, int nbk) { return mask_lt((c & 255) >> 2, min(64, nbk - (c >> 8) * 64)); };
-    auto put_plain = [&](int c, int nbk, const u32x4 q0, const u32x4 q1) {
+    // rms normalization, first half: v_k = fp16(x_k g_k) goes to LDS, x_k^2 is summed; the scalar 1 / sqrt(mean + eps)
+    // commutes with the product and is applied to the row sums
+    float sumsq = 0.f;
+    auto apply_gain = [&](uint32_t (&n)[8], const uint16_t *aux, int c, int nbk) {
+        const IFLOW_GLOBAL u32x4 *gs = chunk_src(aux, c, nbk);
+        const u32x4 g0 = gs[0], g1 = gs[1];
+        const uint32_t g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            sumsq = dot2(as_h2(n[i]), as_h2(n[i]), sumsq);
+            n[i] = as_u32(as_h2(n[i]) * as_h2(g[i]));          // an exact product rounded once (packed fp16 multiply)
+        }
+    };
+    auto put_plain = [&](int c, int nbk, const u32x4 q0, const u32x4 q1, const ChainPhaseOps *op) {
         const uint32_t live = chunk_live(c, nbk);              // columns past the end of the row count as zero
-        const uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
+        uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
+        if constexpr (FUSED) {
+            if (op->x_op == IFLOW_X_RMS_GAIN) apply_gain(n, op->aux, c, nbk);
+        }
         chunk_put(c, n);
     };
 
@@ -279,11 +322,11 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
 #pragma unroll
         for (int j = 0; j < S; ++j) request(w[j]);
         // (whole wavefronts have a chunk or not: loop bounds and conditions are written on the wavefront's first chunk)
-        if (wave * 64 < nchunks0) put_plain(tid, ph0.nbk, xq0, xq1);
+        if (wave * 64 < nchunks0) put_plain(tid, ph0.nbk, xq0, xq1, a.ops);
 #pragma unroll 1
         for (int cw = wave * 64 + 64 * CHAIN_WAVES; cw < nchunks0; cw += 64 * CHAIN_WAVES) {
             const IFLOW_GLOBAL u32x4 *src = chunk_src(ph0.x, cw + lane, ph0.nbk);
-            put_plain(cw + lane, ph0.nbk, src[0], src[1]);
+            put_plain(cw + lane, ph0.nbk, src[0], src[1], a.ops);
         }
     }
     // Every wavefront of the launch reads the same counter (it is advanced only after all workgroups are done), and
@@ -307,6 +350,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
             uint16_t *out_y = nullptr;
             uint32_t *out_t = nullptr;
             bool out_single = false;                           // the pair is the lone last row of a matrix with an odd row count
+            bool out_gated = false;                            // the pair is (gate row, up row): one output, silu(gate) * up
+            const uint16_t *res_plain = nullptr;               // where the pair's residuals come from: a launch input ...
+            const uint64_t *res_tagged = nullptr;              // ... or the tagged output of an earlier matrix
             if (lane < n) {
                 const int R = rbeg + 2 * wave + lane * CHAIN_STRIDE;
                 const int m = ph.first + (R >= ph.mstart[1]) + (R >= ph.mstart[2]) + (R >= ph.mstart[3]);
@@ -315,6 +361,17 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                 out_y = mt.y + r;
                 out_t = ws + mt.tag_word + chain_tag_word(r);
                 out_single = r == mt.rows - 1;
+                if constexpr (FUSED) {
+                    if (mt.gated) {
+                        out_gated = true; out_single = true;
+                        out_y = mt.y + (r >> 1);
+                        out_t = ws + mt.tag_word + chain_tag_word(r >> 1);
+                    } else if (mt.residual_tag_word) {
+                        res_tagged = reinterpret_cast<const uint64_t *>(ws + mt.residual_tag_word + chain_tag_word(r));
+                    } else if (mt.residual) {
+                        res_plain = mt.residual + r;
+                    }
+                }
             }
             float res0 = 0.f, res1 = 0.f;
             int done = 0;                                      // pairs of rows summed so far
@@ -324,7 +381,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
 #pragma unroll 1
                 for (int cw = wave * 64; cw < nchunks; cw += 64 * CHAIN_WAVES) {
                     const IFLOW_GLOBAL u32x4 *src = chunk_src(ph.x, cw + lane, nbk);
-                    put_plain(cw + lane, nbk, src[0], src[1]);
+                    put_plain(cw + lane, nbk, src[0], src[1], a.ops + p);
                 }
             } else if (p > 0) {
                 const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + ph.x_tag_word);
@@ -364,10 +421,50 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                     if (!live)
 #pragma unroll
                         for (int i = 0; i < 8; ++i) n8[i] = 0;
+                    if constexpr (FUSED) {
+                        if (a.ops[p].x_op == IFLOW_X_RMS_GAIN) apply_gain(n8, a.ops[p].aux, ch, nbk);
+                    }
                     chunk_put(ch, n8);
                 }
             }
+            // the normalization's scalar: every wavefront's share of sum x^2 through LDS (behind the staged strips), added
+            // up in a fixed order by everybody
+            float out_scale = 1.0f;
+            float *const sq_slot = reinterpret_cast<float *>(xs + (size_t)hd->max_strips * CHAIN_SLOT_BYTES);
+            if constexpr (FUSED) {
+                const float wsum = wave_sum(sumsq);
+                if (lane == 0) sq_slot[wave] = wsum;
+                sumsq = 0.f;
+            }
             __syncthreads();
+            uint32_t resid = 0;                                // the pair's residuals (two fp16)
+            if constexpr (FUSED) {
+                if (a.ops[p].x_op == IFLOW_X_RMS_GAIN) {
+                    float tot = 0.f;
+#pragma unroll
+                    for (int i = 0; i < CHAIN_WAVES; ++i) tot += sq_slot[i];
+                    out_scale = 1.0f / __builtin_sqrtf(tot * a.ops[p].inv_cols + a.ops[p].eps);
+                }
+                // Residuals are read after the barrier: the phase's own input is complete then, and with it every output
+                // of the phases before its producer.  A tagged residual is still checked (and re-read a bounded number of times).
+                if (res_tagged) {
+                    int budget = failed ? 1 : CHAIN_POLL_BUDGET;
+                    for (;;) {
+                        const uint64_t wd = __hip_atomic_load(res_tagged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const uint32_t lo = (uint32_t)wd, hi = (uint32_t)(wd >> 32);
+                        resid = (lo & 0xFFFFu) | (hi << 16);
+                        if (((lo ^ tag) >> 16) == 0 && (out_single || ((hi ^ tag) >> 16) == 0)) break;
+                        if (--budget <= 0) {
+                            failed = true;
+                            __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                } else if (res_plain) {
+                    resid = out_single ? (uint32_t)*global_ptr<const uint16_t>(res_plain) : *global_ptr<const uint32_t>(res_plain);
+                }
+            }
 
             // 2. this wavefront's steps; step j of the phase uses register set j mod S
             auto load_xr = [&](int ts) {
@@ -424,6 +521,15 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
             }
             // 3. publish: the caller's plain fp16 outputs, and the tagged words for later phases
             if (lane < n) {
+                if constexpr (FUSED) {
+                    res0 *= out_scale; res1 *= out_scale;
+                    if (out_gated) {                           // silu(gate) * up in fp32, rounded once
+                        res0 = res0 * __builtin_amdgcn_rcpf(1.0f + __expf(-res0)) * res1;
+                    } else {
+                        res0 += (float)as_h((uint16_t)(resid & 0xFFFFu));
+                        res1 += (float)as_h((uint16_t)(resid >> 16));
+                    }
+                }
                 const uint32_t h0 = as_u16((half_t)res0), h1 = as_u16((half_t)res1);
                 if (!out_single) {
                     *global_ptr<uint32_t>(out_y) = h0 | (h1 << 16);
@@ -468,7 +574,7 @@ size_t chain_workspace_bytes(int nmatrices, const int64_t *rows)
 
 size_t chain_plan_bytes(int nphases, int nmatrices)
 {
-    return sizeof(ChainHeader) + (size_t)nphases * sizeof(ChainPhase) + (size_t)nmatrices * sizeof(ChainMatrix);
+    return sizeof(ChainHeader) + (size_t)nphases * (sizeof(ChainPhase) + sizeof(ChainPhaseOps)) + (size_t)nmatrices * sizeof(ChainMatrix);
 }
 
 // Launch geometry: as many workgroups as the device has compute units (one each: 768 threads
@@ -479,7 +585,9 @@ hipError_t chain_grid_for_device(int *grid)
     static PerDevice pd;
     int cus = 0;
     hipError_t e0 = once_per_device(pd, &cus, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
     });
     if (e0 != hipSuccess) return e0;
     *grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
@@ -495,11 +603,19 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
     ChainHeader *hd = reinterpret_cast<ChainHeader *>(out.data());
     ChainPhase *phs = reinterpret_cast<ChainPhase *>(out.data() + sizeof(ChainHeader));
     ChainMatrix *mats = reinterpret_cast<ChainMatrix *>(phs + c.nphases);
+    ChainPhaseOps *ops = reinterpret_cast<ChainPhaseOps *>(mats + nmat);
+    bool fused = false;
     int m = 0, max_strips = 1;
     size_t word = IFLOW_CHAIN_WS_HEADER / 4;
     for (int p = 0; p < c.nphases; ++p) {
         ChainPhase &ph = phs[p];
-        ph.x = c.x[p]; ph.first = m; ph.count = c.counts[p];
+        const bool gated = c.gated && c.gated[p];
+        ph.x = c.x[p]; ph.first = m; ph.count = gated ? 1 : c.counts[p];
+        ops[p].x_op = c.x_op ? c.x_op[p] : IFLOW_X_PLAIN;
+        ops[p].aux = c.aux ? c.aux[p] : nullptr;
+        ops[p].eps = c.eps ? c.eps[p] : 0.0f;
+        ops[p].inv_cols = 1.0f / (float)c.cols[p];
+        fused = fused || gated || ops[p].x_op != IFLOW_X_PLAIN;
         for (int j = 0; j < CHAIN_MAX_GROUP; ++j) ph.mstart[j] = 0x7FFFFFFF;
         ph.nbk = (int)(c.cols[p] / 64); ph.nstrips = (ph.nbk + 63) / 64;
         ph.x_src = c.x_src[p];
@@ -511,8 +627,22 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
             mats[m].packed = static_cast<const uint8_t *>(c.packed[m]); mats[m].y = c.y[m]; mats[m].rows = (int)c.rows[m];
             mats[m].start = (int)v;
             mats[m].tag_word = (int)word;
-            ph.mstart[j] = (int)v;
             word += (size_t)((c.rows[m] + 4095) / 4096) * 4096;
+            if (gated) {                                       // the pair (gate, up) is one matrix of 2 x rows in the row space;
+                if (j == 0) {                                  // the up matrix keeps an (unused) descriptor of its own
+                    mats[m].rows = (int)(2 * c.rows[m]); mats[m].gated = 1;
+                    mats[m].packed2 = static_cast<const uint8_t *>(c.packed[m + 1]);
+                    ph.mstart[0] = 0;
+                    v = 2 * c.rows[m];
+                }
+                continue;
+            }
+            ph.mstart[j] = (int)v;
+            if (c.residual && c.residual[m]) {
+                fused = true;
+                if (c.residual_src[m] >= 0) mats[m].residual_tag_word = mats[c.residual_src[m]].tag_word;
+                else mats[m].residual = c.residual[m];
+            }
             v += (c.rows[m] + 1) & ~(int64_t)1;                // every matrix starts at an even row of the phase's row space
         }
         const int64_t rpw = ((v + grid - 1) / grid + 1) & ~(int64_t)1;
@@ -521,18 +651,23 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
     hd->magic = IFLOW_CHAIN_MAGIC; hd->nphases = c.nphases; hd->nmatrices = nmat; hd->grid = grid; hd->max_strips = max_strips;
+    hd->fused = fused ? 1 : 0;
     return true;
 }
 
-hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, hipStream_t s)
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, hipStream_t s)
 {
     int g = 0;
     hipError_t e = chain_grid_for_device(&g);                  // (raises the kernel's LDS limit on this device if it has not been)
     if (e != hipSuccess) return e;
     if (g != grid || max_strips < 1 || max_strips > CHAIN_MAX_STRIPS) return hipErrorInvalidValue;   // planned for another device
-    const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES;
-    hipLaunchKernelGGL((q3h_chain_kernel<2>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
-                       static_cast<uint32_t *>(workspace));
+    const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES + 64;      // (+ the wavefronts' shares of sum x^2)
+    if (fused)
+        hipLaunchKernelGGL((q3h_chain_kernel<2, true>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
+                           static_cast<uint32_t *>(workspace));
+    else
+        hipLaunchKernelGGL((q3h_chain_kernel<2, false>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
+                           static_cast<uint32_t *>(workspace));
     return hipGetLastError();
 }
 

@@ -27,7 +27,7 @@ ATTN_STATIC_MAX_HEADS = 128
 class Chain(C.Structure):
     """iflow_chain_t: what iflow_qgemv_chain_plan fills and iflow_qgemv_chain_launch takes (plain data)."""
     _fields_ = [("plan", C.c_void_p), ("workspace", C.c_void_p), ("grid", C.c_int32), ("max_strips", C.c_int32),
-                ("magic", C.c_uint32), ("reserved", C.c_uint32)]
+                ("magic", C.c_uint32), ("fused", C.c_uint32)]
 
 
 class IflowError(RuntimeError):
@@ -77,6 +77,9 @@ def lib():
         L.iflow_qgemv_chain_plan_bytes.argtypes = [C.c_int, C.c_int, C.POINTER(sz)]
         L.iflow_qgemv_chain_plan.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(p),
                                              C.POINTER(i64), C.POINTER(p), p, sz, p, sz, p, C.POINTER(Chain)]
+        L.iflow_qgemv_chain_plan_fused.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64), C.POINTER(p), C.POINTER(C.c_int),
+                                                   C.POINTER(p), C.POINTER(C.c_float), C.POINTER(C.c_int), C.POINTER(p), C.POINTER(i64),
+                                                   C.POINTER(p), C.POINTER(p), p, sz, p, sz, p, C.POINTER(Chain)]
         L.iflow_qgemv_chain_launch.argtypes = [C.POINTER(Chain), p]
         L.iflow_qgemv_chain_check.argtypes = [C.POINTER(Chain), p]
         _lib = L
@@ -244,7 +247,7 @@ def _chain_arrays(phases):
 def qgemv_chain_plan_bytes(phases) -> int:
     """Size of the plan.  `phases`: list of (cols, x, [(packed, rows, y), ...])."""
     out = C.c_size_t(0)
-    _check(lib().iflow_qgemv_chain_plan_bytes(len(phases), sum(len(ms) for (_, _, ms) in phases), C.byref(out)), "iflow_qgemv_chain_plan_bytes")
+    _check(lib().iflow_qgemv_chain_plan_bytes(len(phases), sum(len(ph[2]) for ph in phases), C.byref(out)), "iflow_qgemv_chain_plan_bytes")
     return int(out.value)
 
 
@@ -255,6 +258,24 @@ def qgemv_chain_plan(fmt: int, phases, plan, plan_bytes: int, workspace, workspa
     chain = Chain()
     _check(lib().iflow_qgemv_chain_plan(fmt, nph, counts, cols, xs, pk, rs, ys, _ptr(plan), plan_bytes, _ptr(workspace),
                                         workspace_bytes, _stream(stream), C.byref(chain)), "iflow_qgemv_chain_plan")
+    return chain
+
+
+def qgemv_chain_plan_fused(fmt: int, phases, plan, plan_bytes: int, workspace, workspace_bytes: int, stream=None) -> Chain:
+    """qgemv_chain_plan with the modules between the products.  `phases` is a list of (cols, x, mats, ops): mats a list of
+    (packed, rows, y) or (packed, rows, y, residual) (y None for the up matrix of a gated pair), ops a dict with any of
+    x_op (X_PLAIN / X_RMS_GAIN), aux (the gains), eps, gated (bool)."""
+    nph, counts, cols, xs, pk, rs, ys = _chain_arrays([(c, x, ms) for (c, x, ms, _) in phases])
+    mats = [m for (_, _, ms, _) in phases for m in ms]
+    n = len(mats)
+    x_op = (C.c_int * nph)(*[int(o.get("x_op", X_PLAIN)) for (_, _, _, o) in phases])
+    aux = (C.c_void_p * nph)(*[_ptr(o.get("aux")) for (_, _, _, o) in phases])
+    eps = (C.c_float * nph)(*[float(o.get("eps", 0.0)) for (_, _, _, o) in phases])
+    gated = (C.c_int * nph)(*[int(bool(o.get("gated", False))) for (_, _, _, o) in phases])
+    res = (C.c_void_p * n)(*[_ptr(m[3]) if len(m) > 3 else None for m in mats])
+    chain = Chain()
+    _check(lib().iflow_qgemv_chain_plan_fused(fmt, nph, counts, cols, xs, x_op, aux, eps, gated, pk, rs, res, ys, _ptr(plan), plan_bytes,
+                                              _ptr(workspace), workspace_bytes, _stream(stream), C.byref(chain)), "iflow_qgemv_chain_plan_fused")
     return chain
 
 

@@ -112,7 +112,7 @@ def test_chain_validation_happens_before_any_launch(iflow):
     assert sz.value == 4096 + 2 * 4096 * 4
     assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], ws_bytes=sz.value - 1) == iflow.ERR_SIZE
     assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], ws=None) == iflow.ERR_NULL
-    assert L.iflow_qgemv_chain_plan_bytes(2, 2, C.byref(sz)) == iflow.OK and sz.value == 64 + 2 * 64 + 2 * 32
+    assert L.iflow_qgemv_chain_plan_bytes(2, 2, C.byref(sz)) == iflow.OK and sz.value == 64 + 2 * (64 + 32) + 2 * 64
     assert call(4, [1, 1], [64, 64], [x0, y0], [pk, pk], [64, 8], [y0, y1], plan_bytes=sz.value - 1) == iflow.ERR_SIZE
     assert L.iflow_qgemv_chain_plan_bytes(0, 0, C.byref(sz)) == iflow.ERR_SHAPE
     assert L.iflow_qgemv_chain_plan_bytes(2, 5000, C.byref(sz)) == iflow.ERR_SHAPE
@@ -123,6 +123,45 @@ def test_chain_validation_happens_before_any_launch(iflow):
     blank = iflow.Chain()
     blank.plan, blank.workspace = base, base * 2                                 # never filled by a plan call: refused by its magic word
     assert L.iflow_qgemv_chain_launch(C.byref(blank), None) == iflow.ERR_SHAPE
+
+
+def test_fused_chain_validation_happens_before_any_launch(iflow):
+    """iflow_qgemv_chain_plan_fused: the rules for gains, gated pairs and residuals, checked on the host."""
+    L = iflow.lib()
+    base = 0x100000
+
+    def call(counts, cols, x, packed, rows, y, x_op=None, aux=None, eps=None, gated=None, residual=None):
+        nph, n = len(counts), len(rows)
+        chain = iflow.Chain()
+        arr = lambda t, v, k: (t * k)(*v) if v is not None else None
+        return L.iflow_qgemv_chain_plan_fused(4, nph, (C.c_int * nph)(*counts), (C.c_int64 * nph)(*cols), (C.c_void_p * nph)(*x),
+                                              arr(C.c_int, x_op, nph), arr(C.c_void_p, aux, nph), arr(C.c_float, eps, nph),
+                                              arr(C.c_int, gated, nph), (C.c_void_p * n)(*packed), (C.c_int64 * n)(*rows),
+                                              arr(C.c_void_p, residual, n), (C.c_void_p * n)(*y), None, 1 << 20, base * 64, 1 << 30,
+                                              None, C.byref(chain))
+
+    x0, g0, pk, y0, y1, r0 = base, base + 0x1000, base * 2, base * 3, base * 4, base * 5
+    ok_then_null = iflow.ERR_NULL                      # every check passed; the null plan pointer is what is reported
+    assert call([1], [64], [x0], [pk], [8], [y0], x_op=[1], aux=[g0], eps=[1e-5]) == ok_then_null
+    assert call([1], [64], [x0], [pk], [8], [y0], x_op=[1], aux=[None], eps=[1e-5]) == iflow.ERR_NULL
+    assert call([1], [64], [x0], [pk], [8], [y0], x_op=[1], aux=[g0 + 2], eps=[1e-5]) == iflow.ERR_ALIGN
+    assert call([1], [64], [x0], [pk], [8], [y0], x_op=[1], aux=[g0], eps=[-1.0]) == iflow.ERR_SHAPE
+    assert call([1], [64], [x0], [pk], [8], [y0], x_op=[1], aux=[y0], eps=[0.0]) == iflow.ERR_SHAPE      # gains overlapped by an output
+    assert call([1], [64], [x0], [pk], [8], [y0], x_op=[2], aux=[g0], eps=[0.0]) == iflow.ERR_SHAPE      # silu*mul is a gated phase's job
+    # a gated phase: two matrices of equal size, one output
+    assert call([2], [64], [x0], [pk, pk], [8, 8], [y0, None], gated=[1]) == ok_then_null
+    assert call([2], [64], [x0], [pk, pk], [8, 8], [y0, y1], gated=[1]) == iflow.ERR_SHAPE
+    assert call([2], [64], [x0], [pk, pk], [8, 16], [y0, None], gated=[1]) == iflow.ERR_SHAPE
+    assert call([1], [64], [x0], [pk], [8], [y0], gated=[1]) == iflow.ERR_SHAPE
+    assert call([2], [64], [x0], [pk, pk], [8, 8], [y0, None], gated=[0]) == iflow.ERR_NULL               # not gated: every matrix has an output
+    assert call([2], [64], [x0], [pk, pk], [8, 8], [y0, None], gated=[1], residual=[r0, None]) == iflow.ERR_SHAPE
+    # residuals: a launch input, or exactly an earlier phase's output
+    assert call([1], [64], [x0], [pk], [8], [y0], residual=[r0]) == ok_then_null
+    assert call([1], [64], [x0], [pk], [8], [y0], residual=[r0 + 2]) == iflow.ERR_ALIGN
+    assert call([1], [64], [x0], [pk], [8], [y0], residual=[y0]) == iflow.ERR_SHAPE                       # its own output
+    assert call([1, 1], [64, 64], [x0, x0], [pk, pk], [8, 8], [y0, y1], residual=[None, y0]) == ok_then_null
+    assert call([1, 1], [64, 64], [x0, x0], [pk, pk], [16, 8], [y0, y1], residual=[None, y0]) == iflow.ERR_SHAPE   # another length
+    assert call([1, 1], [64, 64], [x0, x0], [pk, pk], [8, 8], [y0, y1], residual=[y1, None]) == iflow.ERR_SHAPE    # a later phase's output
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):
