@@ -460,6 +460,100 @@ def main():
                             "+ attention, HIP-graph replay over the ring",
                     "us_per_layer": round(us_layer, 2), "weight_GB/s": round(step_bytes / us_layer / 1e3, 1),
                     "tokens_per_s_32_layers": round(1e6 / (32 * us_layer), 1)}
+                # the same decode step with the layer's products and modules in ONE chained launch per layer:
+                # [attention output] -> o + residual -> rms-norm + silu(gate)*up -> down + residual -> rms-norm + the NEXT layer's q,k,v;
+                # per layer: rope_append, attention, one chained launch (HIP-graph replay over the ring)
+                hid, ffn_rows = shapes[0][2], shapes[4][1]
+                hsA, hsB = hs.clone(), torch.empty_like(hs)
+                h1b = torch.empty_like(hs)
+                ab = torch.empty((ffn_rows,), dtype=torch.float16, device=dev)
+                qb, kb, vb = torch.empty_like(hs), torch.empty_like(hs), torch.empty_like(hs)
+                layer_chains = []
+                for layer in range(args.ring):
+                    m, mn = ring[layer], ring[(layer + 1) % args.ring]
+                    h_in, h_out = (hsA, hsB) if layer % 2 == 0 else (hsB, hsA)
+                    phs = [(m[3][1], ao, [(m[3][2], m[3][0], h1b, h_in)], {}),
+                           (m[4][1], h1b, [(m[4][2], m[4][0], ab), (m[5][2], m[5][0], None)],
+                            {"x_op": iflow.X_RMS_GAIN, "aux": gn[1], "eps": 1e-5, "gated": True}),
+                           (m[6][1], ab, [(m[6][2], m[6][0], h_out, h1b)], {}),
+                           (mn[0][1], h_out, [(mn[0][2], mn[0][0], qb), (mn[1][2], mn[1][0], kb), (mn[2][2], mn[2][0], vb)],
+                            {"x_op": iflow.X_RMS_GAIN, "aux": gn[0], "eps": 1e-5})]
+                    wsb = iflow.qgemv_chain_workspace_bytes([mm[1] for ph in phs for mm in ph[2]])
+                    plb = iflow.qgemv_chain_plan_bytes(phs)
+                    wst = torch.empty(wsb, dtype=torch.uint8, device=dev)
+                    plt = torch.empty(plb, dtype=torch.uint8, device=dev)
+                    layer_chains.append((iflow.qgemv_chain_plan_fused(fmt, phs, plt, plb, wst, wsb, stream=raw), plt, wst))
+
+                def decode_layer_chained(layer):
+                    iflow.rope_append(qb, kb, vb, 32, 32, 128, ctx - 1, ctx, 10000.0, iflow.ROPE_HALVES, kvs[layer][0], kvs[layer][1], stream=raw)
+                    iflow.attn_decode(qb, kvs[layer][0], kvs[layer][1], 32, 32, 128, ctx, ctx, 128 ** -0.5, ao, aws2, awb2, stream=raw)
+                    iflow.qgemv_chain_launch(layer_chains[layer][0], stream=raw)
+
+                m0 = ring[0]
+                iflow.qgemv_fused(fmt, [m0[i][2] for i in (0, 1, 2)], [m0[i][0] for i in (0, 1, 2)], m0[0][1], hsA, [qb, kb, vb],
+                                  iflow.X_RMS_GAIN, gn[0], 1e-5, stream=raw)      # the first layer's q,k,v
+                for layer in range(2):
+                    decode_layer_chained(layer)
+                stream.synchronize()
+                cgraph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(cgraph, stream=stream):
+                    for layer in range(args.ring):
+                        decode_layer_chained(layer)
+                for _ in range(3):
+                    cgraph.replay()
+                t0.record(stream)
+                for _ in range(20):
+                    cgraph.replay()
+                t1.record(stream)
+                t1.synchronize()
+                for ch, _, _ in layer_chains:
+                    iflow.qgemv_chain_check(ch, stream=raw)
+                us_layer_c = t0.elapsed_time(t1) * 1e3 / (20 * args.ring)
+                other["decode_step_with_attention_chained"] = {
+                    "what": "per decoder layer: rotary embedding + cache append | attention over 1024 cached positions (32 heads) | ONE chained "
+                            "launch: o + residual -> rms-norm + silu(gate)*up -> down + residual -> rms-norm + the next layer's q,k,v "
+                            "(iflow_qgemv_chain_plan_fused); HIP-graph replay over the ring",
+                    "us_per_layer": round(us_layer_c, 2), "weight_GB/s": round(step_bytes / us_layer_c / 1e3, 1),
+                    "tokens_per_s_32_layers": round(1e6 / (32 * us_layer_c), 1)}
+                # and without the attention: the whole stack, modules included, in one launch (q's output stands in for the attention's)
+                arena2 = torch.empty((args.ring * (5 * hid + ffn_rows + 6 * 128),), dtype=torch.float16, device=dev)
+                cur2 = [0]
+
+                def take2(nrows):
+                    v = arena2[cur2[0]:cur2[0] + nrows]
+                    cur2[0] += (nrows + 127) // 128 * 128
+                    return v
+
+                phs_all, hcur = [], hsA
+                for layer in range(args.ring):
+                    m = ring[layer]
+                    q_l, k_l, v_l, h1_l, a_l, h2_l = take2(hid), take2(hid), take2(hid), take2(hid), take2(ffn_rows), take2(hid)
+                    phs_all += [(m[0][1], hcur, [(m[0][2], m[0][0], q_l), (m[1][2], m[1][0], k_l), (m[2][2], m[2][0], v_l)],
+                                 {"x_op": iflow.X_RMS_GAIN, "aux": gn[0], "eps": 1e-5}),
+                                (m[3][1], q_l, [(m[3][2], m[3][0], h1_l, hcur)], {}),
+                                (m[4][1], h1_l, [(m[4][2], m[4][0], a_l), (m[5][2], m[5][0], None)],
+                                 {"x_op": iflow.X_RMS_GAIN, "aux": gn[1], "eps": 1e-5, "gated": True}),
+                                (m[6][1], a_l, [(m[6][2], m[6][0], h2_l, h1_l)], {})]
+                    hcur = h2_l
+                wsb = iflow.qgemv_chain_workspace_bytes([mm[1] for ph in phs_all for mm in ph[2]])
+                plb = iflow.qgemv_chain_plan_bytes(phs_all)
+                wst = torch.empty(wsb, dtype=torch.uint8, device=dev)
+                plt = torch.empty(plb, dtype=torch.uint8, device=dev)
+                all_chain = iflow.qgemv_chain_plan_fused(fmt, phs_all, plt, plb, wst, wsb, stream=raw)
+                for _ in range(2):
+                    iflow.qgemv_chain_launch(all_chain, stream=raw)
+                t0.record(stream)
+                for _ in range(10):
+                    iflow.qgemv_chain_launch(all_chain, stream=raw)
+                t1.record(stream)
+                t1.synchronize()
+                iflow.qgemv_chain_check(all_chain, stream=raw)
+                us_layer_f = t0.elapsed_time(t1) * 1e3 / (10 * args.ring)
+                other["fused_stack_in_one_launch"] = {
+                    "what": f"{args.ring} decoder layers in ONE chained launch with their modules (rms-norm + q,k,v | o + residual | rms-norm + "
+                            "silu(gate)*up | down + residual; q's output stands in for the attention's), eager launches",
+                    "us_per_layer": round(us_layer_f, 2), "weight_GB/s": round(step_bytes / us_layer_f / 1e3, 1),
+                    "frac_of_hbm_peak": round(step_bytes / us_layer_f / 1e3 / HBM_PEAK_GBPS, 4)}
                 del kvs
             # the other block formats of Table 3 (and the 2-bit one) on the same matrix shape, 1 to 16 activation vectors:
             # copies of one packed matrix at 16 distinct addresses

@@ -286,9 +286,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
     // rms normalization, first half: v_k = fp16(x_k g_k) goes to LDS, x_k^2 is summed; the scalar 1 / sqrt(mean + eps)
     // commutes with the product and is applied to the row sums
     float sumsq = 0.f;
-    auto apply_gain = [&](uint32_t (&n)[8], const uint16_t *aux, int c, int nbk) {
-        const IFLOW_GLOBAL u32x4 *gs = chunk_src(aux, c, nbk);
-        const u32x4 g0 = gs[0], g1 = gs[1];
+    auto apply_gain = [&](uint32_t (&n)[8], const u32x4 g0, const u32x4 g1) {
         const uint32_t g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -300,7 +298,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
         const uint32_t live = chunk_live(c, nbk);              // columns past the end of the row count as zero
         uint32_t n[8] = {q0.x & live, q0.y & live, q0.z & live, q0.w & live, q1.x & live, q1.y & live, q1.z & live, q1.w & live};
         if constexpr (FUSED) {
-            if (op->x_op == IFLOW_X_RMS_GAIN) apply_gain(n, op->aux, c, nbk);
+            if (op->x_op == IFLOW_X_RMS_GAIN) {
+                const IFLOW_GLOBAL u32x4 *gs = chunk_src(op->aux, c, nbk);
+                apply_gain(n, gs[0], gs[1]);
+            }
         }
         chunk_put(c, n);
     };
@@ -392,6 +393,13 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                     const bool live = chunk_live(ch, nbk) != 0;
                     const uint64_t *src = base + (ch >> 8) * 2048 + (live ? (ch & 255) : 0);
                     uint32_t n8[8];
+                    u32x4 gain0 = {0, 0, 0, 0}, gain1 = {0, 0, 0, 0};  // the gains are requested before the wait for the activations
+                    if constexpr (FUSED) {
+                        if (a.ops[p].x_op == IFLOW_X_RMS_GAIN) {
+                            const IFLOW_GLOBAL u32x4 *gs = chunk_src(a.ops[p].aux, ch, nbk);
+                            gain0 = gs[0]; gain1 = gs[1];
+                        }
+                    }
                     int budget = failed ? 1 : CHAIN_POLL_BUDGET;
                     bool again;                                // the wavefront re-reads as long as any of its lanes has to
                     do {
@@ -422,7 +430,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
 #pragma unroll
                         for (int i = 0; i < 8; ++i) n8[i] = 0;
                     if constexpr (FUSED) {
-                        if (a.ops[p].x_op == IFLOW_X_RMS_GAIN) apply_gain(n8, a.ops[p].aux, ch, nbk);
+                        if (a.ops[p].x_op == IFLOW_X_RMS_GAIN) apply_gain(n8, gain0, gain1);
                     }
                     chunk_put(ch, n8);
                 }

@@ -328,3 +328,27 @@ def test_chain_benchmark_configuration_eight_layers(gpu, orc):
                 rms = np.sqrt(np.mean(full ** 2))
                 e = float(np.max(np.abs(full[idx] - want) / np.maximum(np.abs(want), rms)))
                 assert e <= TOL, f"phase {p}: rel err {e}"
+
+
+def test_chain_check_reports_a_recorded_timeout(gpu, orc):
+    """The error path of iflow_qgemv_chain_check, forced from the host: the word a phase raises when its bounded wait expires
+    is set with a device copy (no kernel waits for anything), the check reports IFLOW_ERR_TIMEOUT until the chain is planned
+    again, and planning again clears it."""
+    torch, iflow = gpu
+    say("[case] chain check: error word set by the host")
+    phases, host, chain, keep = build_chain(torch, iflow, [(256, None, [64])], synth.BASE_SEED + 1200)
+    plan, ws = keep
+    iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)                             # a normal launch: no record
+    ws.view(torch.int32)[1] = 1                                # what a phase writes when it gives up its wait
+    torch.cuda.synchronize()
+    with pytest.raises(iflow.IflowError) as ei:
+        iflow.qgemv_chain_check(chain)
+    assert ei.value.status == iflow.ERR_TIMEOUT
+    iflow.qgemv_chain_launch(chain)                            # the record stays: later launches do not clear it
+    with pytest.raises(iflow.IflowError):
+        iflow.qgemv_chain_check(chain)
+    chain2 = iflow.qgemv_chain_plan(iflow.Q3H_B64, phases, plan, plan.numel(), ws, ws.numel())
+    iflow.qgemv_chain_launch(chain2)
+    iflow.qgemv_chain_check(chain2)
+    check_phases(torch, iflow, orc, phases, host, "after planning again")
