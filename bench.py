@@ -705,7 +705,7 @@ def main():
     if args.launches == 1:
         for chain, _, _, _ in chains.values():
             iflow.qgemv_chain_check(chain, stream=raw)         # raises if a wait inside a launch ever gave up
-        out["roofline"]["kernel"] = "iflow::q3h_chain_kernel<2>"
+        out["roofline"]["kernel"] = "iflow::q3h_chain_kernel<2, false>"
         out["config"]["chain_plans"] = {f"{k[1]} layers from ring position {k[0]}": {"plan_MB": round(v[1].numel() / 1e6, 1),
                                                                                       "plan_call_s": round(v[3], 2)} for k, v in chains.items()}
     if not args.no_cpu_baseline:
