@@ -224,7 +224,8 @@ iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const 
  *            normalization's scalar or 1), as in iflow_qgemv_gated; y[up] must be null.  Later phases may take y[gate] as input.
  *   residual per matrix: null, or a vector [rows[m]] fp16 added to the output before its one rounding to fp16: an input of
  *            the launch that no output overlaps (4-byte aligned), or exactly the output y[i] of a matrix of an earlier phase
- *            (not the phase's own input's producer or later: it must be complete when the phase starts).  Not for gated phases.
+ *            (any earlier phase: its hand-over words are read at the store, with the same bounded re-read as a phase's
+ *            input).  Not for gated phases.
  * A plan without any module is the plan of iflow_qgemv_chain_plan (same kernel, same bits). */
 iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, const int *counts, const int64_t *cols,
                                             const uint16_t *const *x, const iflow_x_op_t *x_op, const uint16_t *const *aux,
