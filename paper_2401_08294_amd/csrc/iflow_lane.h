@@ -211,13 +211,17 @@ __device__ __forceinline__ void lane_dot(const WRegs<KIND> &w, const XRegs<KIND>
     }
 }
 
-// The block header of a Q3H lane is spread over the eight words: bits 14-15 hold two scale bits, bits
-// 30-31 two offset bits; shifting the running value right by two before each merge lines them up.
+// The block header of a Q3H lane is spread over the eight words: bits 14-15 of word i hold scale bits 2i, 2i+1, bits
+// 30-31 the same two offset bits.  The bytes that carry them (1 and 3 of every word) are gathered from two words at a
+// time, words i and i+4, so that four registers hold them in the byte order of the result; each register then
+// contributes the top two bits of all its bytes at once: 11 instructions where one mask-and-merge per word takes 15.
 __device__ __forceinline__ uint32_t q3h_header(const uint32_t (&d)[8])
 {
-    uint32_t h = d[0] & 0xC000C000u;
-#pragma unroll
-    for (int i = 1; i < 8; ++i) h = (d[i] & 0xC000C000u) | (h >> 2);
+    constexpr uint32_t sel = 0x07030501u;                  // (second.b1, first.b1, second.b3, first.b3)
+    uint32_t h = __builtin_amdgcn_perm(d[4], d[0], sel) >> 6 & 0x03030303u;
+    h = (__builtin_amdgcn_perm(d[5], d[1], sel) >> 4 & 0x0C0C0C0Cu) | h;
+    h = (__builtin_amdgcn_perm(d[6], d[2], sel) >> 2 & 0x30303030u) | h;
+    h = (__builtin_amdgcn_perm(d[7], d[3], sel) & 0xC0C0C0C0u) | h;
     return h;
 }
 

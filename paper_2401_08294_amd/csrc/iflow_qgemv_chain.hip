@@ -130,9 +130,45 @@ struct ChainWalk {
 // staging of a phase's activations and the normalization's scalar into its outputs, the gate of a gated feed-forward
 // applied where its two projections are summed, residuals added at the store.  The plain variant is the code without any
 // of it (a launch of bare products pays nothing for the modules).
+#ifndef IFLOW_CHAIN_SETS
+#define IFLOW_CHAIN_SETS 2
+#endif
+#ifndef IFLOW_CHAIN_EARLY
+#define IFLOW_CHAIN_EARLY 0
+#endif
+constexpr int CHAIN_SETS = IFLOW_CHAIN_SETS;
+
+// The sums over all 64 lanes of two per-lane values, in the summation tree of wave_sum_to_lane63 (lanes ^1, ^2, the halves
+// and the mirror of a 16-lane row, rows 0+1 and 2+3, then the two halves), so the results are bit-identical to two
+// separate reductions: the four row totals of a and of b are brought side by side with one swap of the upper half of one
+// register with the lower half of the other, after which both values finish in the same two instructions.  Lane 31 of the
+// result holds the sum of a, lane 63 the sum of b.
+__device__ __forceinline__ int pair_sums(float a, float b)
+{
+    a = row16_sum(a);
+    b = row16_sum(b);
+    // a <- rows (a0, a1, b0, b1), b <- rows (a2, a3, b2, b3); then rows 1 and 3 += lane 15 of the row before.  (Written
+    // as instructions: this compiler's builtin for the swap loses its second result.  The idle cycles are what a
+    // cross-lane read of a register written by the instruction before needs.)
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\ts_nop 0" : "+v"(a), "+v"(b));
+    const float lo = a, hi = b;
+    return __builtin_bit_cast(int, hi + lo);
+}
+
+// lane `slot` of keep0 / keep1 <- value0 / value1 (all three uniform).  The lane select goes through m0: a lane write may
+// name only one ordinary scalar register.
+__device__ __forceinline__ void park(float &keep0, float &keep1, int value0, int value1, int slot)
+{
+    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
+                 : "+v"(keep0), "+v"(keep1) : "s"(value0), "s"(value1), "s"(slot) : "m0");
+}
+
 template <int S, bool FUSED>
 __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws)
 {
+    constexpr bool EARLY = IFLOW_CHAIN_EARLY != 0;
     const ChainHeader *const hd = reinterpret_cast<const ChainHeader *>(plan);
     const ChainArgs a = {reinterpret_cast<const ChainPhase *>(plan + sizeof(ChainHeader)),
                          reinterpret_cast<const ChainMatrix *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * sizeof(ChainPhase)),
@@ -321,7 +357,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
         const u32x4 xq0 = src0[0], xq1 = src0[1];
         request_segment();
 #pragma unroll
-        for (int j = 0; j < S; ++j) request(w[j]);
+        for (int j = 0; j < S - (EARLY ? 1 : 0); ++j) request(w[j]);
         // (whole wavefronts have a chunk or not: loop bounds and conditions are written on the wavefront's first chunk)
         if (wave * 64 < nchunks0) put_plain(tid, ph0.nbk, xq0, xq1, a.ops);
 #pragma unroll 1
@@ -494,6 +530,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                 constexpr int st = decltype(stage)::value;
                 const bool real = j < nreal;                   // an empty step only passes its register set on
                 float v[2] = {0.f, 0.f};
+                if constexpr (EARLY) request(w[(st + S - 1) % S]);   // step j + S - 1: into the set decoded one step ago
                 if (real) {
                     if (nstrips > 1) load_xr(t);
 #pragma unroll
@@ -504,15 +541,12 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                         v[u] = part[u] + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
                     }
                 }
-                request(w[st]);                                // step j + S of the sequence takes over the register set
+                if constexpr (!EARLY) request(w[st]);          // step j + S of the sequence takes over the register set
                 const bool last = real && t == nstrips - 1;    // the rows are complete: two reductions, lane 63 publishes
                 if (last) {
-                    const float sum0 = wave_sum_to_lane63(v[0]), sum1 = wave_sum_to_lane63(v[1]);
-                    // lane `done` of res0 / res1 <- lane 63's sums
-                    const float b0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sum0), 63));
-                    const float b1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sum1), 63));
-                    res0 = lane == done ? b0 : res0;
-                    res1 = lane == done ? b1 : res1;
+                    // lane `done` of res0 / res1 <- the two row sums (same summation tree as wave_sum_to_lane63)
+                    const int both_lo = pair_sums(v[0], v[1]);
+                    park(res0, res1, __builtin_amdgcn_readlane(both_lo, 31), __builtin_amdgcn_readlane(both_lo, 63), done);
                     done += 1;
                 }
                 // (plain selects: written as stores under branches, these end up in scratch memory)
@@ -593,9 +627,9 @@ hipError_t chain_grid_for_device(int *grid)
     static PerDevice pd;
     int cus = 0;
     hipError_t e0 = once_per_device(pd, &cus, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<CHAIN_SETS, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (e != hipSuccess) return e;
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<CHAIN_SETS, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
     });
     if (e0 != hipSuccess) return e0;
     *grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
@@ -671,10 +705,10 @@ hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_str
     if (g != grid || max_strips < 1 || max_strips > CHAIN_MAX_STRIPS) return hipErrorInvalidValue;   // planned for another device
     const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES + 64;      // (+ the wavefronts' shares of sum x^2)
     if (fused)
-        hipLaunchKernelGGL((q3h_chain_kernel<2, true>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
+        hipLaunchKernelGGL((q3h_chain_kernel<CHAIN_SETS, true>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
                            static_cast<uint32_t *>(workspace));
     else
-        hipLaunchKernelGGL((q3h_chain_kernel<2, false>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
+        hipLaunchKernelGGL((q3h_chain_kernel<CHAIN_SETS, false>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
                            static_cast<uint32_t *>(workspace));
     return hipGetLastError();
 }
