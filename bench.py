@@ -394,27 +394,28 @@ def main():
             tf = 2.0 * 512 * g_rows * g_cols / us / 1e6
             other["batch"]["512"] = {"us": round(us, 2), "TFLOP/s": round(tf, 1), "frac_of_f16_mfma_peak": round(tf / 2500.0, 4)}
             # decode-step attention over an fp16 key/value cache: 7B-shaped (32 heads, 32 kv heads) and 70B-shaped (64 / 8)
-            other["attention_decode"] = {"what": "iflow_attn_decode, head dimension 128, ring of caches beyond the on-chip caches, "
-                                                 "eager launches, us per call and GB/s of key/value bytes", "cases": {}}
-            for n_heads, n_kv, T in ((32, 32, 1024), (32, 32, 4096), (64, 8, 4096)):
-                kv_bytes = 2 * n_kv * T * 128 * 2
+            other["attention_decode"] = {"what": "iflow_attn_decode, ring of caches beyond the on-chip caches, eager launches, us per call and "
+                                                 "GB/s of key/value bytes; heads / key-value heads x head dimension", "cases": {}}
+            # (7B: 32/32 x 128; 70B: 64/8 x 128; Falcon-40B-shaped: 128/8 x 64, sixteen query heads per key/value head; multi-query: 71/1 x 64)
+            for n_heads, n_kv, hd, T in ((32, 32, 128, 1024), (32, 32, 128, 4096), (64, 8, 128, 4096), (128, 8, 64, 4096), (71, 1, 64, 16384)):
+                kv_bytes = 2 * n_kv * T * hd * 2
                 nring = max(4, min(32, (768 * 2**20) // kv_bytes))
-                caches = [(torch.randn((n_kv, T, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16),
-                           torch.randn((n_kv, T, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)) for _ in range(nring)]
-                qv = torch.randn((n_heads, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
-                ov = torch.empty((n_heads, 128), dtype=torch.float16, device=dev)
+                caches = [(torch.randn((n_kv, T, hd), generator=gen, device=dev, dtype=torch.float32).to(torch.float16),
+                           torch.randn((n_kv, T, hd), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)) for _ in range(nring)]
+                qv = torch.randn((n_heads, hd), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+                ov = torch.empty((n_heads, hd), dtype=torch.float16, device=dev)
                 awb = iflow.attn_decode_workspace_bytes(n_heads)
                 aws = torch.empty((awb,), dtype=torch.uint8, device=dev)
                 for kc, vc in caches[:2]:
-                    iflow.attn_decode(qv, kc, vc, n_heads, n_kv, 128, T, T, 128 ** -0.5, ov, aws, awb, stream=raw)
+                    iflow.attn_decode(qv, kc, vc, n_heads, n_kv, hd, T, T, hd ** -0.5, ov, aws, awb, stream=raw)
                 t0.record(stream)
                 for _ in range(6):
                     for kc, vc in caches:
-                        iflow.attn_decode(qv, kc, vc, n_heads, n_kv, 128, T, T, 128 ** -0.5, ov, aws, awb, stream=raw)
+                        iflow.attn_decode(qv, kc, vc, n_heads, n_kv, hd, T, T, hd ** -0.5, ov, aws, awb, stream=raw)
                 t1.record(stream)
                 t1.synchronize()
                 us = t0.elapsed_time(t1) * 1e3 / (6 * nring)
-                other["attention_decode"]["cases"][f"{n_heads}/{n_kv} heads, {T} positions"] = {"us": round(us, 2), "GB/s": round(kv_bytes / us / 1e3, 1)}
+                other["attention_decode"]["cases"][f"{n_heads}/{n_kv} heads x {hd}, {T} positions"] = {"us": round(us, 2), "GB/s": round(kv_bytes / us / 1e3, 1)}
                 del caches
             # a whole decode step per layer: normalization, gate and residuals fused into the four launches, attention over 1024
             # cached positions in between (HIP-graph replay over the ring; key/value bytes are not counted in the GB/s)

@@ -239,10 +239,11 @@ iflow_status_t iflow_qgemv_chain_check(const iflow_chain_t *chain, void *stream)
  * head_i = Attention(Q_i, K^j, V^j), j the group of query head i; scaled dot-product attention; n_kv_heads == n_heads is
  * multi-head attention).  One query position attends to all seq_len cached positions:
  *   out[i][:] = fp16( sum_t softmax_t(scale * q[i] . K[j][t]) * V[j][t][:] ),  j = i / (n_heads / n_kv_heads).
- *   q        [n_heads][128] fp16          (head dimension 128 only; other values: IFLOW_ERR_SHAPE)
- *   k_cache  [n_kv_heads][max_seq][128] fp16, v_cache likewise; positions >= seq_len are not read
- *   out      [n_heads][128] fp16
- *   n_heads / n_kv_heads must be 1, 2, 4 or 8; n_kv_heads <= 64; 1 <= seq_len <= max_seq <= 2^20.
+ *   q        [n_heads][head_dim] fp16     (head_dim 64 or 128; other values: IFLOW_ERR_SHAPE)
+ *   k_cache  [n_kv_heads][max_seq][head_dim] fp16, v_cache likewise; positions >= seq_len are not read
+ *   out      [n_heads][head_dim] fp16
+ *   n_heads a multiple of n_kv_heads, any ratio (1: multi-head; n_kv_heads == 1: multi-query; the keys and values are read
+ *   once per sixteen query heads of a group); n_heads <= 512; n_kv_heads <= 64; 1 <= seq_len <= max_seq <= 2^20.
  *   workspace: device memory of iflow_attn_decode_workspace_bytes(n_heads) bytes, 16-byte aligned; scratch for the
  *     partial results of the position ranges the sequence is split into (up to 64; a second small kernel merges them),
  *     its contents before and after the call mean nothing.  Launches that share a workspace must be ordered (same stream).
@@ -268,14 +269,14 @@ iflow_status_t iflow_attn_decode_static(const uint16_t *q, const uint16_t *k_cac
 
 /* Rotary position embedding for one decode step, and the step's append to the key/value cache (Section 2's table of
  * configurable modules: position_embedding = "rope"): the launch that sits between the q/k/v projections and
- * iflow_attn_decode.  Pair i (0..63) of a head's 128 components at position p is rotated by the angle p * base^(-2i/128):
- * (a, b) -> (a cos - b sin, a sin + b cos); IFLOW_ROPE_ADJACENT pairs components (2i, 2i+1), IFLOW_ROPE_HALVES pairs
- * (i, i + 64).
- *   q        [n_heads][128] fp16: rotated IN PLACE
- *   k_new    [n_kv_heads][128] fp16, this step's keys (unrotated); v_new likewise, this step's values
- *   k_cache  [n_kv_heads][max_seq][128] fp16: row `position` of every head receives the rotated keys;
+ * iflow_attn_decode.  Pair i (0 .. d/2 - 1) of a head's d = head_dim components at position p is rotated by the angle
+ * p * base^(-2i/d): (a, b) -> (a cos - b sin, a sin + b cos); IFLOW_ROPE_ADJACENT pairs components (2i, 2i+1),
+ * IFLOW_ROPE_HALVES pairs (i, i + d/2).
+ *   q        [n_heads][d] fp16: rotated IN PLACE
+ *   k_new    [n_kv_heads][d] fp16, this step's keys (unrotated); v_new likewise, this step's values
+ *   k_cache  [n_kv_heads][max_seq][d] fp16: row `position` of every head receives the rotated keys;
  *   v_cache  likewise: row `position` receives v_new unchanged.  No other row is touched.
- *   0 <= position < max_seq <= 2^20; head_dim must be 128; base > 1 (10000 for the LLaMA family).
+ *   0 <= position < max_seq <= 2^20; head_dim a multiple of 8 from 16 to 256; base > 1 (10000 for the LLaMA family).
  * Angles, sines, cosines and the rotation are computed in fp64 and rounded to fp16 once, so that positions in the
  * hundreds of thousands are as exact as position 1.  All pointers are device pointers, 16-byte aligned. */
 typedef enum { IFLOW_ROPE_ADJACENT = 0, IFLOW_ROPE_HALVES = 1 } iflow_rope_pairing_t;

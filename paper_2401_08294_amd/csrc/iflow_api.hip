@@ -259,16 +259,14 @@ iflow_status_t iflow_attn_decode(const uint16_t *q, const uint16_t *k_cache, con
                                  int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
                                  uint16_t *out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (head_dim != 128) return IFLOW_ERR_SHAPE;
+    if (head_dim != 64 && head_dim != 128) return IFLOW_ERR_SHAPE;
     if (n_kv_heads < 1 || n_kv_heads > 64 || n_heads < 1 || n_heads > 512 || n_heads % n_kv_heads != 0) return IFLOW_ERR_SHAPE;
-    const int group = n_heads / n_kv_heads;
-    if (group != 1 && group != 2 && group != 4 && group != 8) return IFLOW_ERR_SHAPE;
     if (seq_len < 1 || max_seq < seq_len || max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
     if (!(scale > 0.0f && scale < 3.0e38f)) return IFLOW_ERR_SHAPE;
     if (!q || !k_cache || !v_cache || !out || !workspace) return IFLOW_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(workspace)) return IFLOW_ERR_ALIGN;
     if (workspace_bytes < iflow::attn_workspace_bytes(n_heads)) return IFLOW_ERR_SIZE;
-    return device_status(iflow::launch_attn_decode(q, k_cache, v_cache, n_heads, n_kv_heads, seq_len, max_seq, scale, out, workspace,
+    return device_status(iflow::launch_attn_decode(q, k_cache, v_cache, n_heads, n_kv_heads, head_dim, seq_len, max_seq, scale, out, workspace,
                                                    (hipStream_t)stream));
 }
 
@@ -276,16 +274,14 @@ iflow_status_t iflow_attn_decode_static(const uint16_t *q, const uint16_t *k_cac
                                         int n_kv_heads, int head_dim, int64_t seq_len, int64_t max_seq, float scale,
                                         uint16_t *out, void *stream)
 {
-    if (head_dim != 128) return IFLOW_ERR_SHAPE;
+    if (head_dim != 64 && head_dim != 128) return IFLOW_ERR_SHAPE;
     if (n_kv_heads < 1 || n_kv_heads > 64 || n_heads < 1 || n_heads > 512 || n_heads % n_kv_heads != 0) return IFLOW_ERR_SHAPE;
-    const int group = n_heads / n_kv_heads;
-    if (group != 1 && group != 2 && group != 4 && group != 8) return IFLOW_ERR_SHAPE;
     if (seq_len < 1 || max_seq < seq_len || max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
     if (!(scale > 0.0f && scale < 3.0e38f)) return IFLOW_ERR_SHAPE;
     if (!q || !k_cache || !v_cache || !out) return IFLOW_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return IFLOW_ERR_ALIGN;
     if (n_heads > IFLOW_ATTN_STATIC_MAX_HEADS) return IFLOW_ERR_SIZE;      // more partial results than the library's own array holds
-    return device_status(iflow::launch_attn_decode_static(q, k_cache, v_cache, n_heads, n_kv_heads, seq_len, max_seq, scale, out,
+    return device_status(iflow::launch_attn_decode_static(q, k_cache, v_cache, n_heads, n_kv_heads, head_dim, seq_len, max_seq, scale, out,
                                                           (hipStream_t)stream));
 }
 
@@ -293,14 +289,14 @@ iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint1
                                  int head_dim, int64_t position, int64_t max_seq, float base, iflow_rope_pairing_t pair_mode,
                                  uint16_t *k_cache, uint16_t *v_cache, void *stream)
 {
-    if (head_dim != 128) return IFLOW_ERR_SHAPE;
+    if (head_dim < 16 || head_dim > 256 || head_dim % 8 != 0) return IFLOW_ERR_SHAPE;   // rows of the caches stay 16-byte aligned
     if (n_heads < 1 || n_heads > 65536 || n_kv_heads < 1 || n_kv_heads > 65536) return IFLOW_ERR_SHAPE;
     if (position < 0 || position >= max_seq || max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
     if (!(base > 1.0f && base < 3.0e38f)) return IFLOW_ERR_SHAPE;
     if (pair_mode != IFLOW_ROPE_ADJACENT && pair_mode != IFLOW_ROPE_HALVES) return IFLOW_ERR_SHAPE;
     if (!q || !k_new || !v_new || !k_cache || !v_cache) return IFLOW_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return IFLOW_ERR_ALIGN;
-    return device_status(iflow::launch_rope_append(q, k_new, v_new, n_heads, n_kv_heads, position, max_seq, (double)base, (int)pair_mode,
+    return device_status(iflow::launch_rope_append(q, k_new, v_new, n_heads, n_kv_heads, head_dim, position, max_seq, (double)base, (int)pair_mode,
                                                    k_cache, v_cache, (hipStream_t)stream));
 }
 

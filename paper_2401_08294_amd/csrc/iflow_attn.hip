@@ -186,59 +186,65 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(const uint1
 //     apart, which puts the four lane groups on different banks).
 //   - Streaming softmax per head in the lanes that hold that head's column of S; the rescale factors of heads 4g..4g+3
 //     are fetched across lanes for the accumulators, which are laid out by (head, component).
-template <int R>
+// RMAX (4, 8 or 16) is the number of query heads a workgroup serves from one pass over its keys and values: a group of up
+// to RMAX heads takes one pass, a larger group (the paper's multi-query models: every head shares one key/value head) is
+// cut into pieces of RMAX heads along the grid's second dimension.  D (64 or 128) is the head dimension: D / 32 pieces of
+// 16 bytes per lane and position, D / 16 column groups of the weighted sum.
+template <int RMAX, int D>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                                           const uint16_t *__restrict__ vc, uint16_t *__restrict__ out,
-                                                                          float *__restrict__ ws, int n_heads, int seq_len,
+                                                                          float *__restrict__ ws, int n_heads, int group, int seq_len,
                                                                           int64_t head_stride /* halves */, int chunk, int nsplit,
                                                                           float scale_log2e)
 {
-    static_assert(R == 4 || R == 8, "group size");
+    static_assert((RMAX == 4 || RMAX == 8 || RMAX == 16) && (D == 64 || D == 128), "group piece and head dimension");
     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
     typedef float float4v __attribute__((ext_vector_type(4)));
-    constexpr int VROW = 272;                                 // bytes between rows of the staged value tile (a multiple of 16)
+    constexpr int NU = D / 32, NC = D / 16;
+    constexpr int VROW = 2 * D + 16;                          // bytes between rows of the staged value tile (a multiple of 16)
     __shared__ __align__(16) uint8_t s_v[ATT_WAVES][16 * VROW];
-    __shared__ float s_o[ATT_WAVES][8][ATT_D];
+    __shared__ float s_o[ATT_WAVES][RMAX][D];
     __shared__ float s_m[ATT_WAVES][16], s_l[ATT_WAVES][16];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, g = lane >> 4;
     const int j = blockIdx.x / nsplit, sp = blockIdx.x - j * nsplit;
+    const int r0 = blockIdx.y * RMAX, rr = min(RMAX, group - r0);     // this workgroup's heads of the group: r0 .. r0 + rr - 1
     const int t_begin = sp * chunk, t_end = min(seq_len, t_begin + chunk);
     const uint16_t *kh = kc + (int64_t)j * head_stride + g * 8;
     const uint16_t *vh = vc + (int64_t)j * head_stride + g * 8;
 
-    // queries as B operands: lane (head li, g) holds Q[head][32u + 8g + 4h + e]; heads past the group are zero
-    half4v qb[8];
+    // queries as B operands: lane (head li, g) holds Q[head][32u + 8g + 4h + e]; heads past the piece are zero
+    half4v qb[2 * NU];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < NU; ++u) {
         att_u32x4 v = {0u, 0u, 0u, 0u};
-        if (li < R) v = *reinterpret_cast<const att_u32x4 *>(q + (int64_t)(j * R + li) * ATT_D + 32 * u + 8 * g);
+        if (li < rr) v = *reinterpret_cast<const att_u32x4 *>(q + (int64_t)(j * group + r0 + li) * D + 32 * u + 8 * g);
         qb[2 * u] = __builtin_bit_cast(half4v, make_uint2(v.x, v.y));
         qb[2 * u + 1] = __builtin_bit_cast(half4v, make_uint2(v.z, v.w));
     }
     float m = -INFINITY, l = 0.f;                             // of head li (the maximum is the same in the four lanes of a head)
-    float4v oacc[8];                                          // oacc[c][e] = O[head 4g+e][16c + li]
+    float4v oacc[NC];                                         // oacc[c][e] = O[head 4g+e][16c + li]
 #pragma unroll
-    for (int c = 0; c < 8; ++c) oacc[c] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < NC; ++c) oacc[c] = (float4v){0.f, 0.f, 0.f, 0.f};
 
-    auto load_block = [&](att_u32x4 (&kt)[4], att_u32x4 (&vt)[4], int p0) {
+    auto load_block = [&](att_u32x4 (&kt)[NU], att_u32x4 (&vt)[NU], int p0) {
         const int64_t pos = min(p0 + li, t_end - 1);          // past the range: its last position, masked below
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            kt[u] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(kh + pos * ATT_D + 32 * u));
-            vt[u] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(vh + pos * ATT_D + 32 * u));
+        for (int u = 0; u < NU; ++u) {
+            kt[u] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(kh + pos * D + 32 * u));
+            vt[u] = __builtin_nontemporal_load(reinterpret_cast<const att_u32x4 *>(vh + pos * D + 32 * u));
         }
     };
     uint8_t *myv = s_v[wave];
-    auto process_block = [&](const att_u32x4 (&kt)[4], const att_u32x4 (&vt)[4], int p0) {
+    auto process_block = [&](const att_u32x4 (&kt)[NU], const att_u32x4 (&vt)[NU], int p0) {
         // values -> LDS as loaded: row = position li, bytes 64u + 16g
 #pragma unroll
-        for (int u = 0; u < 4; ++u) *reinterpret_cast<att_u32x4 *>(myv + li * VROW + 64 * u + 16 * g) = vt[u];
+        for (int u = 0; u < NU; ++u) *reinterpret_cast<att_u32x4 *>(myv + li * VROW + 64 * u + 16 * g) = vt[u];
         // scores
         float4v sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < NU; ++u) {
             const half4v a0 = __builtin_bit_cast(half4v, make_uint2(kt[u].x, kt[u].y));
             const half4v a1 = __builtin_bit_cast(half4v, make_uint2(kt[u].z, kt[u].w));
             sacc = __builtin_amdgcn_mfma_f32_16x16x16f16(a0, qb[2 * u], sacc, 0, 0, 0);
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const 
 #pragma unroll
             for (int e = 0; e < 4; ++e) al[e] = __shfl(alpha, 4 * g + e);
 #pragma unroll
-            for (int c = 0; c < 8; ++c)
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) oacc[c][e] *= al[e];
         }
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const 
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < NC; ++c) {
             const uint16_t *col = reinterpret_cast<const uint16_t *>(myv + (4 * g) * VROW) + 16 * c + li;
             const half4v vb = {as_h(col[0]), as_h(col[VROW / 2]), as_h(col[2 * (VROW / 2)]), as_h(col[3 * (VROW / 2)])};
             oacc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, vb, oacc[c], 0, 0, 0);
@@ -287,7 +293,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const 
         __builtin_amdgcn_wave_barrier();                      // the next block overwrites the tile
     };
 
-    att_u32x4 ka[4], va[4], kb[4], vb2[4];
+    att_u32x4 ka[NU], va[NU], kb[NU], vb2[NU];
     constexpr int STEP = 16 * ATT_WAVES;
     int p0 = t_begin + wave * 16;
     load_block(ka, va, p0);                                   // (scheduling barriers: see attn_decode_kernel)
@@ -309,16 +315,16 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const 
     l += __shfl_xor(l, 16);                                   // a head's sum over its four lanes
     l += __shfl_xor(l, 32);
     if (g == 0) { s_m[wave][li] = m; s_l[wave][li] = l; }
-    if (4 * g < R) {
+    if (4 * g < RMAX) {
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int e = 0; e < 4; ++e) s_o[wave][4 * g + e][16 * c + li] = oacc[c][e];
     }
     __syncthreads();
     float *ws_o = ws, *ws_m = ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS, *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS;
-    for (int idx = tid; idx < R * ATT_D; idx += 64 * ATT_WAVES) {
-        const int r = idx >> 7, d = idx & (ATT_D - 1);
+    for (int idx = tid; idx < rr * D; idx += 64 * ATT_WAVES) {
+        const int r = idx / D, d = idx & (D - 1);
         float M = s_m[0][r];
 #pragma unroll
         for (int w = 1; w < ATT_WAVES; ++w) M = fmaxf(M, s_m[w][r]);            // finite: the range is not empty
@@ -329,9 +335,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const 
             L = __builtin_fmaf(s_l[w][r], f, L);
             O = __builtin_fmaf(s_o[w][r][d], f, O);
         }
-        const int head = j * R + r;
+        const int head = j * group + r0 + r;
         if (nsplit == 1) {
-            out[(int64_t)head * ATT_D + d] = as_u16((half_t)(O / L));
+            out[(int64_t)head * D + d] = as_u16((half_t)(O / L));
         } else {
             ws_o[((int64_t)head * ATT_MAX_SPLITS + sp) * ATT_D + d] = O;
             if (d == 0) { ws_m[(int64_t)head * ATT_MAX_SPLITS + sp] = M; ws_l[(int64_t)head * ATT_MAX_SPLITS + sp] = L; }
@@ -339,11 +345,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_mfma_kernel(const 
     }
 }
 
-// Merge of the splits: one workgroup of 128 threads per query head, thread d for component d.  Only entries below
+// Merge of the splits: one workgroup per query head, thread d for component d (a state keeps 128 slots whatever the head
+// dimension).  Only entries below
 // nsplit are read (the rest of the workspace is whatever earlier calls left there, possibly never touched).
 __global__ __launch_bounds__(ATT_D) void attn_merge_kernel(const float *__restrict__ ws, uint16_t *__restrict__ out, int n_heads, int nsplit)
 {
-    const int head = blockIdx.x, d = threadIdx.x;
+    const int head = blockIdx.x, d = threadIdx.x, head_dim = blockDim.x;
     const float *ws_o = ws + (int64_t)head * ATT_MAX_SPLITS * ATT_D + d;
     const float *ws_m = ws + (int64_t)n_heads * ATT_D * ATT_MAX_SPLITS + (int64_t)head * ATT_MAX_SPLITS;
     const float *ws_l = ws_m + (int64_t)n_heads * ATT_MAX_SPLITS;
@@ -371,7 +378,7 @@ __global__ __launch_bounds__(ATT_D) void attn_merge_kernel(const float *__restri
         }
         M = m_new;
     }
-    out[(int64_t)head * ATT_D + d] = as_u16((half_t)(O / L));
+    out[(int64_t)head * head_dim + d] = as_u16((half_t)(O / L));
 }
 
 // positions per split (a multiple of 64, one block per wavefront) and number of splits for a sequence length
@@ -392,36 +399,41 @@ size_t attn_workspace_bytes(int n_heads)
 }
 
 hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
-                              int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s)
+                              int head_dim, int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s)
 {
     static PerDevice pd;
     int cus = 0;
     hipError_t e = once_per_device(pd, &cus, [] { return hipSuccess; });
     if (e != hipSuccess) return e;
     if (n_kv_heads < 1 || n_kv_heads > 64 || n_heads % n_kv_heads != 0 || seq_len < 1 || seq_len > max_seq) return hipErrorInvalidValue;
+    if (head_dim != 64 && head_dim != 128) return hipErrorInvalidValue;
     const int R = n_heads / n_kv_heads;
     int chunk = 0, nsplit = 0;
     attn_geometry(n_kv_heads, seq_len, cus, &chunk, &nsplit);
     if (nsplit < 1 || nsplit > ATT_MAX_SPLITS) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(n_kv_heads * nsplit)), block(64 * ATT_WAVES);
+    const dim3 block(64 * ATT_WAVES);
     const float scale_log2e = scale * 1.4426950408889634f;
-    const int64_t head_stride = max_seq * ATT_D;
-#define IFLOW_ATT_GO(RR) hipLaunchKernelGGL((attn_decode_kernel<RR>), grid, block, 0, s, q, k_cache, v_cache, out, \
-        static_cast<float *>(workspace), n_heads, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
-#define IFLOW_ATT_GO_MFMA(RR) hipLaunchKernelGGL((attn_decode_mfma_kernel<RR>), grid, block, 0, s, q, k_cache, v_cache, out, \
-        static_cast<float *>(workspace), n_heads, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
-    switch (R) {
-    case 1: IFLOW_ATT_GO(1); break;
-    case 2: IFLOW_ATT_GO(2); break;
-    case 4: IFLOW_ATT_GO_MFMA(4); break;
-    case 8: IFLOW_ATT_GO_MFMA(8); break;
-    default: return hipErrorInvalidValue;
-    }
+    const int64_t head_stride = max_seq * head_dim;
+#define IFLOW_ATT_GO(RR) hipLaunchKernelGGL((attn_decode_kernel<RR>), dim3((unsigned)(n_kv_heads * nsplit)), block, 0, s, q, k_cache, \
+        v_cache, out, static_cast<float *>(workspace), n_heads, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
+#define IFLOW_ATT_GO_MFMA(RMAX, DD) hipLaunchKernelGGL((attn_decode_mfma_kernel<RMAX, DD>), \
+        dim3((unsigned)(n_kv_heads * nsplit), (unsigned)((R + RMAX - 1) / RMAX)), block, 0, s, q, k_cache, v_cache, out, \
+        static_cast<float *>(workspace), n_heads, R, (int)seq_len, head_stride, chunk, nsplit, scale_log2e)
+    // one or two heads per key/value head at 128 components: the vector kernel; everything else on the matrix cores, in
+    // pieces of 4, 8 or 16 heads
+    if (head_dim == 128 && R == 1) IFLOW_ATT_GO(1);
+    else if (head_dim == 128 && R == 2) IFLOW_ATT_GO(2);
+    else if (head_dim == 128 && R <= 4) IFLOW_ATT_GO_MFMA(4, 128);
+    else if (head_dim == 128 && R <= 8) IFLOW_ATT_GO_MFMA(8, 128);
+    else if (head_dim == 128) IFLOW_ATT_GO_MFMA(16, 128);
+    else if (R <= 4) IFLOW_ATT_GO_MFMA(4, 64);
+    else if (R <= 8) IFLOW_ATT_GO_MFMA(8, 64);
+    else IFLOW_ATT_GO_MFMA(16, 64);
 #undef IFLOW_ATT_GO
 #undef IFLOW_ATT_GO_MFMA
     e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)n_heads), dim3(ATT_D), 0, s, static_cast<const float *>(workspace), out, n_heads, nsplit);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)n_heads), dim3((unsigned)head_dim), 0, s, static_cast<const float *>(workspace), out, n_heads, nsplit);
     return hipGetLastError();
 }
 
@@ -433,7 +445,7 @@ constexpr int ATT_STATIC_MAX_HEADS = IFLOW_ATTN_STATIC_MAX_HEADS;
 static __device__ __align__(256) float scratch[(size_t)ATT_STATIC_MAX_HEADS * (ATT_D + 2) * ATT_MAX_SPLITS];
 
 hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
-                                     int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s)
+                                     int head_dim, int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s)
 {
     static std::mutex lock;
     static float *address[IFLOW_MAX_DEVICES] = {};
@@ -454,7 +466,7 @@ hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache,
         }
         ptr = address[dev];
     }
-    return launch_attn_decode(q, k_cache, v_cache, n_heads, n_kv_heads, seq_len, max_seq, scale, out, ptr, s);
+    return launch_attn_decode(q, k_cache, v_cache, n_heads, n_kv_heads, head_dim, seq_len, max_seq, scale, out, ptr, s);
 }
 
 }  // namespace iflow

@@ -217,13 +217,13 @@ hipError_t launch_qgemv_gated(int format, const void *packed_gate, const void *p
                               int x_op, const uint16_t *aux, float eps, uint16_t *y, hipStream_t s);
 hipError_t launch_qgemv_rows_gated(int format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols,
                                    const uint16_t *x, int x_op, const uint16_t *aux, float eps, uint16_t *y, hipStream_t s);
-hipError_t launch_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads, int64_t position,
+hipError_t launch_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads, int head_dim, int64_t position,
                               int64_t max_seq, double base, int pair_mode, uint16_t *k_cache, uint16_t *v_cache, hipStream_t s);
 size_t attn_workspace_bytes(int n_heads);
 hipError_t launch_attn_decode(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
-                              int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s);
+                              int head_dim, int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, void *workspace, hipStream_t s);
 hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache, int n_heads, int n_kv_heads,
-                                     int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s);
+                                     int head_dim, int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s);
 // ---- the chained launch: description of a chain (host arrays of the caller), plan builder, model, launcher ----
 struct ChainSpec {
     int nphases;

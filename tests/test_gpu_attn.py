@@ -18,21 +18,21 @@ def rel(got, ref):
     return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))))
 
 
-def make(n_heads, n_kv, max_seq, seed, q_scale=1.0):
+def make(n_heads, n_kv, max_seq, seed, q_scale=1.0, d=128):
     rng = np.random.default_rng(seed)
-    q = (q_scale * rng.standard_normal((n_heads, 128))).astype(np.float16)
-    k = rng.standard_normal((n_kv, max_seq, 128)).astype(np.float16)
-    v = rng.standard_normal((n_kv, max_seq, 128)).astype(np.float16)
+    q = (q_scale * rng.standard_normal((n_heads, d))).astype(np.float16)
+    k = rng.standard_normal((n_kv, max_seq, d)).astype(np.float16)
+    v = rng.standard_normal((n_kv, max_seq, d)).astype(np.float16)
     return q, k, v
 
 
 def run(torch, iflow, q, k, v, T, scale, ws=None):
-    n_heads, n_kv, max_seq = q.shape[0], k.shape[0], k.shape[1]
+    n_heads, n_kv, max_seq, d = q.shape[0], k.shape[0], k.shape[1], q.shape[1]
     nbytes = iflow.attn_decode_workspace_bytes(n_heads)
     if ws is None:
         ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")       # scratch: NaN patterns to start with
-    out = torch.full((n_heads, 128), float("nan"), dtype=torch.float16, device="cuda")
-    iflow.attn_decode(dev16(torch, q), dev16(torch, k), dev16(torch, v), n_heads, n_kv, 128, T, max_seq, scale, out, ws, nbytes)
+    out = torch.full((n_heads, d), float("nan"), dtype=torch.float16, device="cuda")
+    iflow.attn_decode(dev16(torch, q), dev16(torch, k), dev16(torch, v), n_heads, n_kv, d, T, max_seq, scale, out, ws, nbytes)
     torch.cuda.synchronize()
     return out.cpu().numpy().astype(np.float64), ws
 
@@ -45,6 +45,28 @@ def test_attention_decode_against_the_definition(gpu, n_heads, n_kv, T, max_seq)
     say(f"[case] attention decode heads={n_heads} kv_heads={n_kv} seq_len={T} max_seq={max_seq}")
     q, k, v = make(n_heads, n_kv, max_seq, synth.BASE_SEED + 1500 + T)
     scale = 1.0 / np.sqrt(128.0)
+    got, _ = run(torch, iflow, q, k, v, T, scale)
+    ref = att.gqa_decode(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), T, scale)
+    e = rel(got, ref)
+    say(f"        max rel err {e:.3e}")
+    assert np.isfinite(got).all() and e <= TOL
+
+
+@pytest.mark.parametrize("n_heads,n_kv,d,T,max_seq", [
+    (128, 8, 64, 1000, 1024),      # sixteen 64-component query heads per key/value head (the paper's Falcon-40B: Table 3, Table 5)
+    (71, 1, 64, 777, 1024),        # multi-query attention: every head shares one key/value head (five pieces of sixteen heads)
+    (32, 32, 64, 130, 200),        # multi-head attention at 64 components
+    (16, 8, 64, 1, 64), (24, 8, 64, 65, 128), (40, 8, 64, 4096, 4096),       # groups of 2, 3 and 5 at 64 components
+    (24, 8, 128, 300, 512), (48, 8, 128, 1000, 1024), (56, 8, 128, 129, 256), (128, 8, 128, 2049, 4096),   # groups of 3, 6, 7 and 16 at 128
+    (40, 2, 128, 555, 1024), (33, 1, 128, 64, 64),                           # groups of 20 and 33: several pieces, the last ragged
+])
+def test_attention_other_head_dimensions_and_group_sizes(gpu, n_heads, n_kv, d, T, max_seq):
+    """Section "Grouped-query attention": H heads in G groups, any ratio; head dimension 64 next to 128."""
+    torch, iflow = gpu
+    from oracle import attention as att
+    say(f"[case] attention decode heads={n_heads} kv_heads={n_kv} head_dim={d} seq_len={T} max_seq={max_seq}")
+    q, k, v = make(n_heads, n_kv, max_seq, synth.BASE_SEED + 1700 + T + n_heads, d=d)
+    scale = 1.0 / np.sqrt(float(d))
     got, _ = run(torch, iflow, q, k, v, T, scale)
     ref = att.gqa_decode(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), T, scale)
     e = rel(got, ref)

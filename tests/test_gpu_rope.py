@@ -49,29 +49,33 @@ def close_bits(got16, ref16):
                                                           (8, 1, 123457, 131072), (2, 2, (1 << 20) - 1, 1 << 20)])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_rope_append_against_the_definition(gpu, n_heads, n_kv, position, max_seq, mode):
+    check_rope_append(gpu, n_heads, n_kv, position, max_seq, mode, 128)
+
+
+def check_rope_append(gpu, n_heads, n_kv, position, max_seq, mode, d):
     torch, iflow = gpu
     from oracle import rope as R
-    say(f"[case] rope_append heads={n_heads} kv_heads={n_kv} position={position} max_seq={max_seq} pairing={mode}")
+    say(f"[case] rope_append heads={n_heads} kv_heads={n_kv} head_dim={d} position={position} max_seq={max_seq} pairing={mode}")
     rng = np.random.default_rng(synth.BASE_SEED + 1800 + position % 1000 + mode)
     base = 10000.0
     rows = min(max_seq, 6)                                      # the test's caches hold a window of rows around `position`
-    q = rng.standard_normal((n_heads, 128)).astype(np.float16)
-    k = rng.standard_normal((n_kv, 128)).astype(np.float16)
-    v = rng.standard_normal((n_kv, 128)).astype(np.float16)
+    q = rng.standard_normal((n_heads, d)).astype(np.float16)
+    k = rng.standard_normal((n_kv, d)).astype(np.float16)
+    v = rng.standard_normal((n_kv, d)).astype(np.float16)
     # device caches of the full size would be up to 2 x 256 MB here: fine on the device, but compare only a window on the host
-    kc = torch.zeros((n_kv, max_seq, 128), dtype=torch.float16, device="cuda")
-    vc = torch.zeros((n_kv, max_seq, 128), dtype=torch.float16, device="cuda")
+    kc = torch.zeros((n_kv, max_seq, d), dtype=torch.float16, device="cuda")
+    vc = torch.zeros((n_kv, max_seq, d), dtype=torch.float16, device="cuda")
     lo = max(0, min(position - 2, max_seq - rows))
-    window_k = rng.standard_normal((n_kv, rows, 128)).astype(np.float16)
-    window_v = rng.standard_normal((n_kv, rows, 128)).astype(np.float16)
+    window_k = rng.standard_normal((n_kv, rows, d)).astype(np.float16)
+    window_v = rng.standard_normal((n_kv, rows, d)).astype(np.float16)
     kc[:, lo:lo + rows] = torch.from_numpy(window_k).cuda()
     vc[:, lo:lo + rows] = torch.from_numpy(window_v).cuda()
     qd = dev16(torch, q.view(np.uint16))
-    iflow.rope_append(qd, dev16(torch, k.view(np.uint16)), dev16(torch, v.view(np.uint16)), n_heads, n_kv, 128, position, max_seq, base,
+    iflow.rope_append(qd, dev16(torch, k.view(np.uint16)), dev16(torch, v.view(np.uint16)), n_heads, n_kv, d, position, max_seq, base,
                       mode, kc, vc)
     torch.cuda.synchronize()
     kref, vref = window_k.view(np.uint16).copy(), window_v.view(np.uint16).copy()
-    full_k = np.zeros((n_kv, rows, 128), np.uint16); full_v = np.zeros((n_kv, rows, 128), np.uint16)
+    full_k = np.zeros((n_kv, rows, d), np.uint16); full_v = np.zeros((n_kv, rows, d), np.uint16)
     full_k[:], full_v[:] = kref, vref
     # the oracle works on the window, with the position relative to it
     qref = R.rope(q.view(np.uint16), position, base, mode)
@@ -90,6 +94,14 @@ def test_rope_append_against_the_definition(gpu, n_heads, n_kv, position, max_se
         assert not kc[:, :lo].any().item() and not vc[:, :lo].any().item()
     if lo + rows < max_seq:
         assert not kc[:, lo + rows:].any().item() and not vc[:, lo + rows:].any().item()
+
+
+@pytest.mark.parametrize("d,n_heads,n_kv,position,max_seq", [(64, 128, 8, 1000, 2048), (64, 71, 1, 4095, 4096), (96, 12, 4, 77, 128),
+                                                            (256, 8, 2, 30000, 32768), (16, 4, 4, 3, 8)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_rope_append_other_head_dimensions(gpu, d, n_heads, n_kv, position, max_seq, mode):
+    """Head dimensions other than 128 (64: the paper's Falcon models)."""
+    check_rope_append(gpu, n_heads, n_kv, position, max_seq, mode, d)
 
 
 def test_decode_steps_with_rope_and_attention(gpu):

@@ -267,9 +267,9 @@ def test_attention_validation_happens_before_any_launch(iflow):
     def call(n_heads=32, n_kv=32, d=128, T=10, max_seq=64, scale=0.1, q=base, k=base * 2, v=base * 3, out=base * 4, ws=base * 5, ws_bytes=1 << 30):
         return L.iflow_attn_decode(q, k, v, n_heads, n_kv, d, T, max_seq, C.c_float(scale), out, ws, ws_bytes, None)
 
-    assert call(d=64) == iflow.ERR_SHAPE                                         # head dimension 128 only
+    assert call(d=96) == iflow.ERR_SHAPE and call(d=256) == iflow.ERR_SHAPE      # head dimensions 64 and 128
     assert call(n_heads=30, n_kv=4) == iflow.ERR_SHAPE                           # heads not a multiple of kv heads
-    assert call(n_heads=48, n_kv=16) == iflow.ERR_SHAPE                          # three query heads per kv head
+    assert call(n_heads=1024, n_kv=8) == iflow.ERR_SHAPE                         # more than 512 heads
     assert call(n_heads=128, n_kv=128) == iflow.ERR_SHAPE                        # more than 64 kv heads
     assert call(T=0) == iflow.ERR_SHAPE and call(T=65) == iflow.ERR_SHAPE        # empty, or longer than the cache
     assert call(scale=0.0) == iflow.ERR_SHAPE and call(scale=float("nan")) == iflow.ERR_SHAPE
@@ -286,7 +286,7 @@ def test_rope_validation_happens_before_any_launch(iflow):
     def call(n_heads=32, n_kv=8, d=128, pos=5, max_seq=64, theta=10000.0, mode=0, q=base, k=base * 2, v=base * 3, kc=base * 4, vc=base * 5):
         return L.iflow_rope_append(q, k, v, n_heads, n_kv, d, pos, max_seq, C.c_float(theta), mode, kc, vc, None)
 
-    assert call(d=64) == iflow.ERR_SHAPE                                         # head dimension 128 only
+    assert call(d=8) == iflow.ERR_SHAPE and call(d=260) == iflow.ERR_SHAPE and call(d=100) == iflow.ERR_SHAPE   # 16..256, a multiple of 8
     assert call(n_heads=0) == iflow.ERR_SHAPE and call(n_kv=0) == iflow.ERR_SHAPE
     assert call(pos=-1) == iflow.ERR_SHAPE and call(pos=64) == iflow.ERR_SHAPE   # the row must exist
     assert call(max_seq=(1 << 20) + 1, pos=0) == iflow.ERR_SHAPE
