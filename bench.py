@@ -177,7 +177,7 @@ def main():
     # projections that read the same activation vector and may share a launch: (q, k, v) and (gate, up)
     groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches in (1, 4) else [[i] for i in range(len(shapes))]
     if args.launches == 1:       # chained launches: o reads q's output, gate/up read o's, down reads gate's, the next layer's q/k/v read down's
-        assert args.format == "Q3H_B64", "the chained launch exists for the 3.5-bit format"
+        assert args.format in ("Q3H_B64", "Q4_B64", "Q4_B32", "Q8_B64", "Q8_B32"), "the chained launch exists for the 3.5-, 4- and 8-bit formats"
         args.layers_per_launch = max(1, min(args.layers_per_launch, args.ring))
         lpl = args.layers_per_launch
         # all outputs of the chain as views of one allocation
@@ -584,6 +584,59 @@ def main():
                 other["other_formats"]["formats"][oname] = per_batch
                 del copies, first
             del wg
+            # config 3's other two formats through the chained launch: 8 distinct 7B-shaped layers per format, one launch per
+            # pass over them (every product reading its predecessor's output), eager launches of ~0.3 ms each
+            if args.format == "Q3H_B64" and not args.fused:
+                other["formats_chained"] = {"what": "q+k+v -> o -> gate+up -> down -> next layer's q+k+v ..., 8 distinct 7B-shaped layers in ONE chained "
+                                                    "launch, eager; us per layer, GB/s of the format's algorithmic bytes, fraction of the HBM peak", "formats": {}}
+                for oname in ("Q4_B64", "Q8_B64"):
+                    ofmt = iflow.FORMATS[oname]
+                    nl = 8
+                    ring_o = []
+                    for _ in range(nl):
+                        mats_o = []
+                        for _, rows, cols in shapes:
+                            w = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+                            nb_o = iflow.packed_bytes(ofmt, rows, cols)
+                            pk = torch.empty(nb_o, dtype=torch.uint8, device=dev)
+                            iflow.quantize(ofmt, w, rows, cols, pk, nb_o, stream=raw)
+                            mats_o.append((rows, cols, pk))
+                            del w
+                        ring_o.append(mats_o)
+                    layer_bytes = sum(m[2].numel() + 2 * m[1] + 2 * m[0] for m in ring_o[0])
+                    per_l = sum((r + 127) // 128 * 128 for _, r, _ in shapes)
+                    ya = torch.empty((nl * per_l,), dtype=torch.float16, device=dev)
+                    yl, cur = [], 0
+                    for _ in range(nl):
+                        row = []
+                        for _, r, _ in shapes:
+                            row.append(ya[cur:cur + r])
+                            cur += (r + 127) // 128 * 128
+                        yl.append(row)
+                    # (no norms between the products: start small so that fp16 holds the growth over eight layers)
+                    x_first = (torch.randn((shapes[0][2],), generator=gen, device=dev, dtype=torch.float32) * 2.0 ** -10).to(torch.float16)
+                    phs = []
+                    for l in range(nl):
+                        m_l, y_l = ring_o[l], yl[l]
+                        x_l = [x_first if l == 0 else yl[l - 1][6], y_l[0], y_l[3], y_l[4]]
+                        phs += [(m_l[g[0]][1], x_l[i], [(m_l[j][2], m_l[j][0], y_l[j]) for j in g]) for i, g in enumerate([[0, 1, 2], [3], [4, 5], [6]])]
+                    wsb = iflow.qgemv_chain_workspace_bytes([m[1] for ph in phs for m in ph[2]])
+                    plb = iflow.qgemv_chain_plan_bytes(phs)
+                    wst = torch.empty(wsb, dtype=torch.uint8, device=dev)
+                    plt = torch.empty(plb, dtype=torch.uint8, device=dev)
+                    ch = iflow.qgemv_chain_plan(ofmt, phs, plt, plb, wst, wsb, stream=raw)
+                    for _ in range(3):
+                        iflow.qgemv_chain_launch(ch, stream=raw)
+                    t0.record(stream)
+                    for _ in range(20):
+                        iflow.qgemv_chain_launch(ch, stream=raw)
+                    t1.record(stream)
+                    t1.synchronize()
+                    iflow.qgemv_chain_check(ch, stream=raw)
+                    us_l = t0.elapsed_time(t1) * 1e3 / (20 * nl)
+                    other["formats_chained"]["formats"][oname] = {"us_per_layer": round(us_l, 2), "GB/s": round(layer_bytes / us_l / 1e3, 1),
+                                                                  "frac_of_hbm_peak": round(layer_bytes / us_l / 1e3 / HBM_PEAK_GBPS, 4)}
+                    del ring_o, phs, ch, wst, plt, ya
             # 70B-shaped matrices (one and eight activation vectors): launches long enough not to be bound by their own
             # start-up; copies of one packed matrix, at least 1.2 GB of them, replayed from a HIP graph
             if args.large_shapes:
@@ -706,7 +759,7 @@ def main():
     if args.launches == 1:
         for chain, _, _, _ in chains.values():
             iflow.qgemv_chain_check(chain, stream=raw)         # raises if a wait inside a launch ever gave up
-        out["roofline"]["kernel"] = "iflow::q3h_chain_kernel<2, false>"
+        out["roofline"]["kernel"] = f"iflow::chain_kernel<2, false, {fmt}>"
         out["config"]["chain_plans"] = {f"{k[1]} layers from ring position {k[0]}": {"plan_MB": round(v[1].numel() / 1e6, 1),
                                                                                       "plan_call_s": round(v[3], 2)} for k, v in chains.items()}
     if not args.no_cpu_baseline:

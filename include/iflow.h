@@ -161,11 +161,13 @@ iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate,
                                  int64_t cols, const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps,
                                  uint16_t *y, void *stream);
 
-/* A chain of batch-1 products in ONE launch (3.5-bit format only): the decode step applies its projections one
+/* A chain of batch-1 products in ONE launch (the 3.5-, 4- and 8-bit formats, Table 3's Q3H, Q4_B32/B64, Q8_B32/B64; the
+ * bit-plane formats are IFLOW_ERR_FORMAT): the decode step applies its projections one
  * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and
  * at 7B sizes each product is so short that the idle time between dependent launches costs as much as a third of
  * the weight stream.  The chain is a list of `nphases` (1..IFLOW_CHAIN_MAX_PHASES) phases.  Phase p multiplies counts[p]
- * (1..IFLOW_CHAIN_MAX_GROUP) matrices, all with cols[p] columns (<= 65536), with the activation vector x[p]; the matrices
+ * (1..IFLOW_CHAIN_MAX_GROUP) matrices, all with cols[p] columns (<= 65536; 8-bit formats <= 61440: a row's activations are staged in LDS), with the
+ * activation vector x[p]; the matrices
  * of all phases are listed in order in packed / rows / y (at most IFLOW_CHAIN_MAX_MATRICES in total: a whole 32-layer
  * stack of seven matrices per layer fits several times).  x[p] is either
  *   - an input of the call: device memory that NO output of the call overlaps (workgroups run ahead of each other, so
@@ -204,6 +206,7 @@ typedef struct iflow_chain_t {
     void *workspace;            /* device */
     int32_t grid, max_strips;   /* launch geometry the plan was written for */
     uint32_t magic, fused;      /* fused: the plan uses the modules of iflow_qgemv_chain_plan_fused */
+    int32_t format, reserved;   /* the chain's iflow_format_t */
 } iflow_chain_t;
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes);
 iflow_status_t iflow_qgemv_chain_plan_bytes(int nphases, int nmatrices, size_t *bytes);

@@ -318,7 +318,7 @@ iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *cou
 {
     iflow::FormatInfo fi;
     if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
-    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;      // the chained launch exists for the 3.5-bit format only
+    if (!iflow::chain_supports_format((int)format)) return IFLOW_ERR_FORMAT;    // 3.5-, 4- and 8-bit formats (not the bit-plane ones)
     if (nphases < 1 || nphases > IFLOW_CHAIN_MAX_PHASES) return IFLOW_ERR_SHAPE;
     if (!counts || !cols || !x || !packed || !rows || !y) return IFLOW_ERR_NULL;
     int total = 0;
@@ -333,7 +333,7 @@ iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *cou
     for (int p = 0; p < nphases; ++p) {
         if (!x[p]) return IFLOW_ERR_NULL;
         if (!aligned16(x[p])) return IFLOW_ERR_ALIGN;
-        if (cols[p] > 65536) return IFLOW_ERR_SHAPE;
+        if (cols[p] > iflow::chain_max_cols((int)format)) return IFLOW_ERR_SHAPE;   // a row's activations have to fit the kernel's LDS
         const bool gated = ops.gated && ops.gated[p];
         if (gated && (counts[p] != 2 || rows[first[p]] != rows[first[p] + 1])) return IFLOW_ERR_SHAPE;   // a gate and an up matrix of equal size
         for (int m = first[p]; m < first[p] + counts[p]; ++m) {
@@ -428,7 +428,7 @@ iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, 
     if (e != hipSuccess) return device_status(e);
     std::vector<int> xop_int(nphases, IFLOW_X_PLAIN);
     for (int p = 0; p < nphases && x_op; ++p) xop_int[p] = (int)x_op[p];
-    iflow::ChainSpec spec = {nphases, counts, first.data(), cols, x, x_src.data(), packed, rows, y,
+    iflow::ChainSpec spec = {(int)format, nphases, counts, first.data(), cols, x, x_src.data(), packed, rows, y,
                              xop_int.data(), aux, eps, gated, residual, residual_src.data()};
     std::vector<uint8_t> host;
     if (!iflow::chain_build_plan(spec, grid, host)) return IFLOW_ERR_SHAPE;   // more rows than the kernel's 32-bit indices cover
@@ -438,13 +438,14 @@ iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, 
     if (e == hipSuccess) e = hipStreamSynchronize(s);          // (the host copy of the plan goes away when this call returns)
     if (e != hipSuccess) return device_status(e);
     int max_strips = 1;
-    for (int p = 0; p < nphases; ++p) max_strips = std::max(max_strips, (int)((cols[p] / 64 + 63) / 64));
+    for (int p = 0; p < nphases; ++p) max_strips = std::max(max_strips, iflow::chain_strips((int)format, cols[p]));
     bool fused = false;
     for (int p = 0; p < nphases; ++p) fused = fused || (x_op && x_op[p] != IFLOW_X_PLAIN) || (gated && gated[p]);
     for (int m = 0; m < total && residual; ++m) fused = fused || residual[m] != nullptr;
     chain->plan = plan; chain->workspace = workspace;
     chain->grid = grid; chain->max_strips = max_strips;
     chain->magic = IFLOW_CHAIN_MAGIC; chain->fused = fused ? 1u : 0u;
+    chain->format = (int32_t)format; chain->reserved = 0;
     return IFLOW_OK;
 }
 
@@ -461,7 +462,8 @@ iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream
 {
     if (!chain || !chain->plan || !chain->workspace) return IFLOW_ERR_NULL;
     if (chain->magic != IFLOW_CHAIN_MAGIC) return IFLOW_ERR_SHAPE;
-    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->max_strips, chain->fused != 0, (hipStream_t)stream);
+    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->max_strips, chain->fused != 0, (int)chain->format,
+                                       (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // planned for a device with another number of compute units
     return device_status(e);
 }

@@ -226,6 +226,7 @@ hipError_t launch_attn_decode_static(const uint16_t *q, const uint16_t *k_cache,
                                      int head_dim, int64_t seq_len, int64_t max_seq, float scale, uint16_t *out, hipStream_t s);
 // ---- the chained launch: description of a chain (host arrays of the caller), plan builder, model, launcher ----
 struct ChainSpec {
+    int format;                        // iflow_format_t
     int nphases;
     const int *counts;                 // matrices per phase
     const int *first;                  // index of each phase's first matrix
@@ -247,7 +248,10 @@ size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
 size_t chain_plan_bytes(int nphases, int nmatrices);
 bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out);
 hipError_t chain_grid_for_device(int *grid);
-hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, hipStream_t s);
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, int format, hipStream_t s);
+bool chain_supports_format(int format);
+int64_t chain_max_cols(int format);
+int chain_strips(int format, int64_t cols);
 hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int64_t cols,
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64_t cols,

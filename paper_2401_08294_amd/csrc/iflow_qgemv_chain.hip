@@ -39,8 +39,14 @@ template <typename T> __device__ __forceinline__ IFLOW_GLOBAL T *global_ptr(cons
 constexpr int CHAIN_WAVES = 12;                                // wavefronts per workgroup (measured: 8 is 3 % slower, 16 equal;
                                                                // 12 divides the row pairs of 7B-sized phases evenly)
 constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;                  // a wavefront takes two rows per step: rows between its steps
-constexpr int CHAIN_SLOT_BYTES = 8 * 64 * 16 + 64 * 8;        // staged activations of one strip (as in q3h_gemv_kernel)
-constexpr int CHAIN_MAX_STRIPS = 16;                           // columns <= 65536
+// A strip is what the 64 lanes of a wavefront cover of a row in one step: 64 x (weights per lane) columns - 4096 for the
+// 3.5-bit format (a block per lane), 2048 for the 4-bit and 1024 for the 8-bit formats (16 bytes of codes per lane).
+// Staged activations of one strip: the lanes' registers in decode order, 16 bytes per lane and quarter, then the two sums
+// per lane that undo the decode's bias (as in the single-product kernels).
+template <int KIND> constexpr int chain_strip_cols() { return 64 * Geo<KIND>::WPL; }
+template <int KIND> constexpr int chain_slot_bytes() { return Geo<KIND>::XD / 4 * 1024 + 512; }
+constexpr int CHAIN_LDS_BYTES = 152 * 1024;
+constexpr int CHAIN_MAX_COLS = 65536;
 constexpr int CHAIN_MAX_GROUP = IFLOW_CHAIN_MAX_GROUP;         // matrices per phase
 constexpr int CHAIN_MAX_GRID = 960;
 constexpr int CHAIN_POLL_BUDGET = 1 << 17;                     // re-reads before a wait is given up (tens of milliseconds)
@@ -57,7 +63,7 @@ constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_SEEN = 64;
 struct ChainPhase {
     const uint16_t *x;          // activations when they are an input of the launch
     int first, count;           // matrices [first, first + count)
-    int nbk, nstrips;           // blocks and strips per row
+    int nbk, nstrips;           // blocks (of the format's block size) and strips per row
     int x_src;                  // matrix whose output is this phase's activation vector, or -1
     int rows_per_wg;
     int total;                  // rows of the phase, all its matrices together
@@ -75,7 +81,8 @@ struct ChainMatrix {
     const uint8_t *packed2;
     const uint16_t *residual;   // added to the output: an input of the launch ([rows] fp16) ...
     int residual_tag_word;      // ... or the tagged output of an earlier matrix (0: none)
-    int pad_[3];
+    uint32_t hdr_off4;          // formats that keep the block headers behind the codes: where they start, in 4-byte units from `packed`
+    int pad_[2];
 };
 // what only the fused variant of the kernel reads about a phase
 struct ChainPhaseOps {
@@ -88,7 +95,7 @@ struct ChainPhaseOps {
 struct ChainHeader {
     uint32_t magic;
     int nphases, nmatrices, grid;
-    int max_strips, fused, pad_[10];
+    int max_strips, fused, format, pad_[9];
 };
 static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 64 && sizeof(ChainHeader) == 64 && sizeof(ChainPhaseOps) == 32, "descriptor sizes");
 // the two descriptor arrays of a plan, as the kernel indexes them
@@ -137,6 +144,12 @@ struct ChainWalk {
 #define IFLOW_CHAIN_EARLY 0
 #endif
 constexpr int CHAIN_SETS = IFLOW_CHAIN_SETS;
+#ifndef IFLOW_CHAIN_SETS_OTHER
+#define IFLOW_CHAIN_SETS_OTHER 4
+#endif
+// Register sets (steps of weights in flight) per wavefront: a step of the 3.5-bit format is 4 KB (two rows of a 2 KB
+// strip), a step of the 4- and 8-bit formats 2 KB, so those keep twice as many steps in flight for the same bytes.
+constexpr int chain_sets(int format) { return format == IFLOW_Q3H_B64 ? CHAIN_SETS : IFLOW_CHAIN_SETS_OTHER; }
 
 // The sums over all 64 lanes of two per-lane values, in the summation tree of wave_sum_to_lane63 (lanes ^1, ^2, the halves
 // and the mirror of a 16-lane row, rows 0+1 and 2+3, then the two halves), so the results are bit-identical to two
@@ -165,10 +178,20 @@ __device__ __forceinline__ void park(float &keep0, float &keep1, int value0, int
                  : "+v"(keep0), "+v"(keep1) : "s"(value0), "s"(value1), "s"(slot) : "m0");
 }
 
-template <int S, bool FUSED>
-__global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws)
+template <int S, bool FUSED, int F>
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws)
 {
     constexpr bool EARLY = IFLOW_CHAIN_EARLY != 0;
+    using T = Fmt<F>;
+    constexpr int KIND = T::kind;
+    using G = Geo<KIND>;
+    constexpr bool Q3H = KIND == KIND_Q3H;
+    static_assert(Q3H || KIND == KIND_Q4 || KIND == KIND_Q8, "formats of the chained launch");
+    constexpr int XQ = G::XD / 4;                              // 16-byte quarters of a lane's staged activations
+    constexpr int CHAIN_SLOT_BYTES = chain_slot_bytes<KIND>();
+    constexpr int STRIP_COLS = chain_strip_cols<KIND>();
+    constexpr int ROW_BITS = Q3H ? 4 : (KIND == KIND_Q4 ? 4 : 8);  // code bits per weight in a row's code stream (Q3H: the whole block)
+    constexpr int HDR_PER_STRIP = STRIP_COLS / T::block;       // block headers per strip (formats with headers behind the codes)
     const ChainHeader *const hd = reinterpret_cast<const ChainHeader *>(plan);
     const ChainArgs a = {reinterpret_cast<const ChainPhase *>(plan + sizeof(ChainHeader)),
                          reinterpret_cast<const ChainMatrix *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * sizeof(ChainPhase)),
@@ -219,9 +242,16 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
     int q_pad = 0;                                             // empty steps still owed by phase q.p
     uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
     const uint32_t voff_full = (uint32_t)lane * 16;
+    // formats whose block headers sit behind the codes: the same walk over the headers (4 bytes per block)
+    const uint8_t *q_hptr = reinterpret_cast<const uint8_t *>(ws);
+    int q_hrowjump = 0;
+    std::conditional_t<FUSED, int64_t, int> q_hrow1 = 0;
+    uint32_t q_hoff_last = 0;
+    const uint32_t hoff_full = (uint32_t)(lane * G::WPL / T::block) * 4;
     auto request_empty = [&](int count) {                      // `count` empty steps: one "row" of one empty strip each
         q_wptr = reinterpret_cast<const uint8_t *>(ws);
         q_last = 0; q_nlast16 = 0; q_rowjump = 0; q_row1 = 0; q_voff_last = 0;
+        q_hptr = q_wptr; q_hrowjump = 0; q_hrow1 = 0; q_hoff_last = 0;
         q.seg_left = count;
     };
     auto request_segment = [&]() {                             // q.seg_left == 0: find what the requests do next
@@ -247,40 +277,78 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                 int m, r;
                 bool single;
                 walk_segment(q, m, r, single);
-                const int nlast = ph.nbk - (ph.nstrips - 1) * 64;
-                q_wptr = a.mat[m].packed + (int64_t)r * ((int64_t)ph.nbk * 32);
-                q_last = ph.nstrips - 1; q_nlast16 = nlast * 16;
-                q_rowjump = (CHAIN_STRIDE * ph.nbk - (ph.nstrips - 1) * 64) * 32;
-                q_row1 = single ? 0 : ph.nbk * 32;
-                if constexpr (FUSED) {
-                    if (a.mat[m].gated) {                      // rows 2n, 2n+1 of the row space are row n of the gate and of the up matrix
-                        q_wptr = a.mat[m].packed + (int64_t)(r >> 1) * ((int64_t)ph.nbk * 32);
-                        q_rowjump = ((CHAIN_STRIDE / 2) * ph.nbk - (ph.nstrips - 1) * 64) * 32;
-                        q_row1 = a.mat[m].packed2 - a.mat[m].packed;
+                q_last = ph.nstrips - 1;
+                if constexpr (Q3H) {
+                    const int nlast = ph.nbk - (ph.nstrips - 1) * 64;
+                    q_wptr = a.mat[m].packed + (int64_t)r * ((int64_t)ph.nbk * 32);
+                    q_nlast16 = nlast * 16;
+                    q_rowjump = (CHAIN_STRIDE * ph.nbk - (ph.nstrips - 1) * 64) * 32;
+                    q_row1 = single ? 0 : ph.nbk * 32;
+                    if constexpr (FUSED) {
+                        if (a.mat[m].gated) {                  // rows 2n, 2n+1 of the row space are row n of the gate and of the up matrix
+                            q_wptr = a.mat[m].packed + (int64_t)(r >> 1) * ((int64_t)ph.nbk * 32);
+                            q_rowjump = ((CHAIN_STRIDE / 2) * ph.nbk - (ph.nstrips - 1) * 64) * 32;
+                            q_row1 = a.mat[m].packed2 - a.mat[m].packed;
+                        }
                     }
+                    q_voff_last = voff_full & mask_lt(lane, nlast);            // lanes past a ragged end redo block 0
+                } else {
+                    // a row: cols * ROW_BITS / 8 bytes of codes, 1024 per strip; its headers: 4 bytes per block, behind all codes
+                    const int cols = ph.nbk * T::block;
+                    const int row_bytes = cols * ROW_BITS / 8, hrow_bytes = ph.nbk * 4;
+                    const int nlast = (cols - (ph.nstrips - 1) * STRIP_COLS) / G::WPL;     // lanes of the last strip
+                    const uint8_t *headers = a.mat[m].packed + (int64_t)a.mat[m].hdr_off4 * 4;
+                    q_wptr = a.mat[m].packed + (int64_t)r * row_bytes;
+                    q_hptr = headers + (int64_t)r * hrow_bytes;
+                    q_rowjump = CHAIN_STRIDE * row_bytes - (ph.nstrips - 1) * 1024;
+                    q_hrowjump = CHAIN_STRIDE * hrow_bytes - (ph.nstrips - 1) * HDR_PER_STRIP * 4;
+                    q_row1 = single ? 0 : row_bytes;
+                    q_hrow1 = single ? 0 : hrow_bytes;
+                    if constexpr (FUSED) {
+                        if (a.mat[m].gated) {                  // both matrices have the same shape: one distance for codes and headers
+                            q_wptr = a.mat[m].packed + (int64_t)(r >> 1) * row_bytes;
+                            q_hptr = headers + (int64_t)(r >> 1) * hrow_bytes;
+                            q_rowjump = (CHAIN_STRIDE / 2) * row_bytes - (ph.nstrips - 1) * 1024;
+                            q_hrowjump = (CHAIN_STRIDE / 2) * hrow_bytes - (ph.nstrips - 1) * HDR_PER_STRIP * 4;
+                            q_row1 = a.mat[m].packed2 - a.mat[m].packed;
+                            q_hrow1 = q_row1;
+                        }
+                    }
+                    q_voff_last = voff_full & mask_lt(lane, nlast);            // lanes past a ragged end redo lane 0 (their
+                    q_hoff_last = hoff_full & mask_lt(lane, nlast);            // staged activations are zero)
                 }
-                q_voff_last = voff_full & mask_lt(lane, nlast);                // lanes past a ragged end redo block 0
                 found = true;
             }
         }
         if (!found) request_empty(0x7FFFFFFF);                 // the walk is over: empty steps from here on
         q_lt = 0;
     };
-    auto request = [&](WRegs<KIND_Q3H> (&w)[2]) {              // request the step under the cursor, then advance it
+    auto request = [&](WRegs<KIND> (&w)[2]) {                  // request the step under the cursor, then advance it
         const bool last_strip = q_lt == q_last;
-        const int plane2 = last_strip ? q_nlast16 : 1024;
         const uint32_t voff = last_strip ? q_voff_last : voff_full;
+        // (pointers that were read from the plan have to be told that they point to global memory: a generic pointer
+        // makes flat loads, whose completion cannot be counted, and every wait in the step loop becomes "all")
+        if constexpr (Q3H) {
+            const int plane2 = last_strip ? q_nlast16 : 1024;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const uint8_t *row = q_wptr + (int64_t)u * q_row1;
-            // (pointers that were read from the plan have to be told that they point to global memory: a generic pointer
-            // makes flat loads, whose completion cannot be counted, and every wait in the step loop becomes "all")
-            const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + voff));
-            const u32x4 c1 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + plane2 + voff));
-            w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
-            w[u].d[4] = c1.x; w[u].d[5] = c1.y; w[u].d[6] = c1.z; w[u].d[7] = c1.w;
+            for (int u = 0; u < 2; ++u) {
+                const uint8_t *row = q_wptr + (int64_t)u * q_row1;
+                const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + voff));
+                const u32x4 c1 = __builtin_nontemporal_load(global_ptr<const u32x4>(row + plane2 + voff));
+                w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
+                w[u].d[4] = c1.x; w[u].d[5] = c1.y; w[u].d[6] = c1.z; w[u].d[7] = c1.w;
+            }
+        } else {
+            const uint32_t hoff = last_strip ? q_hoff_last : hoff_full;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(q_wptr + (int64_t)u * q_row1 + voff));
+                w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
+                w[u].hdr = *global_ptr<const uint32_t>(q_hptr + (int64_t)u * q_hrow1 + hoff);
+            }
+            q_hptr += last_strip ? q_hrowjump : HDR_PER_STRIP * 4;
         }
-        q_wptr += last_strip ? q_rowjump : 2048;
+        q_wptr += last_strip ? q_rowjump : (Q3H ? 2048 : 1024);
         q_lt = last_strip ? 0 : q_lt + 1;
         if (last_strip) {                                      // on to the wavefront's next row
             q.seg_left -= 1;
@@ -341,15 +409,45 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
         }
         chunk_put(c, n);
     };
+    // ---- the same for the formats with 16 bytes of codes per lane: thread c stages the activations of lane c % 64 of strip
+    // c / 64, G::WPL consecutive values, arranged by the format's own arrange_x (the single-product kernels' layout)
+    auto slot_put = [&](int c, uint32_t (&n)[G::XD], const ChainPhaseOps *op, const uint16_t *gains_at) {
+        if constexpr (FUSED) {
+            if (op->x_op == IFLOW_X_RMS_GAIN) {
+#pragma unroll
+                for (int j = 0; j < XQ; ++j) {
+                    const u32x4 g = global_ptr<const u32x4>(gains_at)[j];
+                    const uint32_t gv[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        sumsq = dot2(as_h2(n[4 * j + e]), as_h2(n[4 * j + e]), sumsq);
+                        n[4 * j + e] = as_u32(as_h2(n[4 * j + e]) * as_h2(gv[e]));   // an exact product rounded once
+                    }
+                }
+            }
+        }
+        XRegs<KIND> t;
+        arrange_x<KIND>(t, n);
+        uint8_t *sl = xs + (size_t)(c >> 6) * CHAIN_SLOT_BYTES;
+        const int l = c & 63;
+#pragma unroll
+        for (int j = 0; j < XQ; ++j)
+            *reinterpret_cast<uint4 *>(sl + (j * 64 + l) * 16) = make_uint4(as_u32(t.v[4 * j]), as_u32(t.v[4 * j + 1]), as_u32(t.v[4 * j + 2]), as_u32(t.v[4 * j + 3]));
+        *reinterpret_cast<float2 *>(sl + XQ * 64 * 16 + l * 8) = make_float2(t.bias_sum, t.x_sum);
+    };
 
     // The first phase's activations are an input of the launch.  Their first chunk is requested BEFORE any weights,
     // because memory requests of a wavefront are served in order and the whole workgroup waits for the staged
     // activations; then S steps of weights; then the chunk is put in place.
-    WRegs<KIND_Q3H> w[S][2];
+    WRegs<KIND> w[S][2];
     // The launch counter, the oldest load of the wavefront (so it never has to be waited for alone).  A plain cached
     // load: the word was last written by the previous launch, and changes again only when this one is over.
     const uint32_t counter = __hip_atomic_load(ws, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    {
+    if constexpr (!Q3H) {                                      // (these formats stage the first phase like any other, below)
+        request_segment();
+#pragma unroll
+        for (int j = 0; j < S - (EARLY ? 1 : 0); ++j) request(w[j]);
+    } else {
         const ChainPhase ph0 = a.ph[0];
         const bool wg_has0 = wg * ph0.rows_per_wg < ph0.total;
         const int nchunks0 = wg_has0 ? ph0.nstrips * 256 : 0;
@@ -371,7 +469,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
     const uint32_t tag = (counter % 65535u + 1u) << 16;
 
     bool failed = false;
-    XRegs<KIND_Q3H> xr[1];
+    XRegs<KIND> xr[1];
     // Results are not stored row by row: lane 63's sums of the wavefront's i-th pair of rows are parked in lane i of two
     // registers, and when the phase's steps are done lanes 0..n-1 store them all at once - two store instructions
     // per wavefront and phase instead of two per row (in-order completion means every later load of the wavefront would
@@ -414,7 +512,54 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
             int done = 0;                                      // pairs of rows summed so far
             // 1. stage the activations (those of the first phase are already on their way)
             const int nchunks = nstrips * 256;
-            if (p > 0 && ph.x_src < 0) {
+            if constexpr (!Q3H) {
+                const int cols = nbk * T::block, nslots = nstrips * 64;
+                const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + ph.x_tag_word);
+#pragma unroll 1
+                for (int cw = wave * 64; cw < nslots; cw += 64 * CHAIN_WAVES) {
+                    const int c = cw + lane, k0 = c * G::WPL;
+                    const bool live = k0 < cols;                   // lanes past the end of the row stage zeros (and read lane 0's words)
+                    const int k = live ? k0 : 0;
+                    uint32_t n[G::XD];
+                    if (ph.x_src < 0) {                            // an input of the launch
+#pragma unroll
+                        for (int j = 0; j < XQ; ++j) {
+                            const u32x4 v = global_ptr<const u32x4>(ph.x + k)[j];
+                            n[4 * j] = v.x; n[4 * j + 1] = v.y; n[4 * j + 2] = v.z; n[4 * j + 3] = v.w;
+                        }
+                    } else {                                       // tagged words: pair g of the vector at 8-byte word
+                        int budget = failed ? 1 : CHAIN_POLL_BUDGET;   // (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255)
+                        bool again;
+                        do {
+                            bool ok = true;
+#pragma unroll
+                            for (int i = 0; i < G::XD; ++i) {
+                                const int g = (k >> 1) + i;
+                                const uint64_t wd = __hip_atomic_load(base + (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255),
+                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                const uint32_t lo = (uint32_t)wd, hi = (uint32_t)(wd >> 32);
+                                ok = ok && ((lo ^ tag) >> 16) == 0 && ((hi ^ tag) >> 16) == 0;
+                                n[i] = (lo & 0xFFFFu) | (hi << 16);
+                            }
+                            again = __builtin_amdgcn_ballot_w64(live && !ok) != 0;
+                            if (again) {
+                                budget -= 1;
+                                if (budget <= 0) {
+                                    failed = true;
+                                    again = false;
+                                    if (lane == 0) __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                } else {
+                                    __builtin_amdgcn_s_sleep(2);
+                                }
+                            }
+                        } while (again);
+                    }
+                    if (!live)
+#pragma unroll
+                        for (int i = 0; i < G::XD; ++i) n[i] = 0;
+                    slot_put(c, n, a.ops + p, FUSED ? a.ops[p].aux + k : nullptr);
+                }
+            } else if (p > 0 && ph.x_src < 0) {
 #pragma unroll 1
                 for (int cw = wave * 64; cw < nchunks; cw += 64 * CHAIN_WAVES) {
                     const IFLOW_GLOBAL u32x4 *src = chunk_src(ph.x, cw + lane, nbk);
@@ -514,12 +659,12 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
             auto load_xr = [&](int ts) {
                 const uint8_t *sl = xs + (size_t)ts * CHAIN_SLOT_BYTES;
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
+                for (int jj = 0; jj < XQ; ++jj) {
                     const uint4 qv = *reinterpret_cast<const uint4 *>(sl + (jj * 64 + lane) * 16);
                     xr[0].v[4 * jj] = as_h2(qv.x); xr[0].v[4 * jj + 1] = as_h2(qv.y);
                     xr[0].v[4 * jj + 2] = as_h2(qv.z); xr[0].v[4 * jj + 3] = as_h2(qv.w);
                 }
-                const float2 sm = *reinterpret_cast<const float2 *>(sl + 8 * 64 * 16 + lane * 8);
+                const float2 sm = *reinterpret_cast<const float2 *>(sl + XQ * 64 * 16 + lane * 8);
                 xr[0].bias_sum = sm.x; xr[0].x_sum = sm.y;
             };
             if (nstrips == 1 && n > 0) load_xr(0);             // a single strip stays in registers for all rows
@@ -536,8 +681,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
 #pragma unroll
                     for (int u = 0; u < 2; ++u) {
                         float acc[1];
-                        lane_dot<KIND_Q3H, 1>(w[st][u], xr, acc);
-                        const half2_t so = as_h2(q3h_header(w[st][u].d));
+                        lane_dot<KIND, 1>(w[st][u], xr, acc);
+                        half2_t so;
+                        if constexpr (Q3H) so = as_h2(q3h_header(w[st][u].d)); else so = as_h2(w[st][u].hdr);
                         v[u] = part[u] + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
                     }
                 }
@@ -560,6 +706,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void q3h_chain_kernel(const uint8
                 if constexpr (S > 1) body(std::integral_constant<int, 1>{}, j + 1);
                 if constexpr (S > 2) body(std::integral_constant<int, 2>{}, j + 2);
                 if constexpr (S > 3) body(std::integral_constant<int, 3>{}, j + 3);
+                if constexpr (S > 4) body(std::integral_constant<int, 4>{}, j + 4);
+                if constexpr (S > 5) body(std::integral_constant<int, 5>{}, j + 5);
+                if constexpr (S > 6) body(std::integral_constant<int, 6>{}, j + 6);
+                if constexpr (S > 7) body(std::integral_constant<int, 7>{}, j + 7);
             }
             // 3. publish: the caller's plain fp16 outputs, and the tagged words for later phases
             if (lane < n) {
@@ -619,6 +769,38 @@ size_t chain_plan_bytes(int nphases, int nmatrices)
     return sizeof(ChainHeader) + (size_t)nphases * (sizeof(ChainPhase) + sizeof(ChainPhaseOps)) + (size_t)nmatrices * sizeof(ChainMatrix);
 }
 
+// The formats the chained launch is built for, and their strip geometry on the host side.
+static bool chain_format(int format, int *strip_cols, int *slot_bytes, int *block, int *row_bits)
+{
+    switch (format) {
+    case IFLOW_Q3H_B64: *strip_cols = chain_strip_cols<KIND_Q3H>(); *slot_bytes = chain_slot_bytes<KIND_Q3H>(); *block = 64; *row_bits = 4; return true;
+    case IFLOW_Q4_B64: *strip_cols = chain_strip_cols<KIND_Q4>(); *slot_bytes = chain_slot_bytes<KIND_Q4>(); *block = 64; *row_bits = 4; return true;
+    case IFLOW_Q4_B32: *strip_cols = chain_strip_cols<KIND_Q4>(); *slot_bytes = chain_slot_bytes<KIND_Q4>(); *block = 32; *row_bits = 4; return true;
+    case IFLOW_Q8_B64: *strip_cols = chain_strip_cols<KIND_Q8>(); *slot_bytes = chain_slot_bytes<KIND_Q8>(); *block = 64; *row_bits = 8; return true;
+    case IFLOW_Q8_B32: *strip_cols = chain_strip_cols<KIND_Q8>(); *slot_bytes = chain_slot_bytes<KIND_Q8>(); *block = 32; *row_bits = 8; return true;
+    default: return false;
+    }
+}
+
+bool chain_supports_format(int format)
+{
+    int a, b, c, d;
+    return chain_format(format, &a, &b, &c, &d);
+}
+
+// The longest row whose activations fit the kernel's LDS in this format (whole strips, and never more than CHAIN_MAX_COLS).
+int64_t chain_max_cols(int format)
+{
+    int strip_cols, slot_bytes, block, row_bits;
+    if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return 0;
+    const int64_t by_lds = (int64_t)((CHAIN_LDS_BYTES - 64) / slot_bytes) * strip_cols;
+    return by_lds < CHAIN_MAX_COLS ? by_lds : CHAIN_MAX_COLS;
+}
+
+#define IFLOW_CHAIN_FOR_ALL(DO) \
+    DO(IFLOW_Q3H_B64, false) DO(IFLOW_Q3H_B64, true) DO(IFLOW_Q4_B64, false) DO(IFLOW_Q4_B64, true) DO(IFLOW_Q4_B32, false) DO(IFLOW_Q4_B32, true) \
+    DO(IFLOW_Q8_B64, false) DO(IFLOW_Q8_B64, true) DO(IFLOW_Q8_B32, false) DO(IFLOW_Q8_B32, true)
+
 // Launch geometry: as many workgroups as the device has compute units (one each: 768 threads
 // and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
 // concurrently.
@@ -627,9 +809,13 @@ hipError_t chain_grid_for_device(int *grid)
     static PerDevice pd;
     int cus = 0;
     hipError_t e0 = once_per_device(pd, &cus, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<CHAIN_SETS, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
-        if (e != hipSuccess) return e;
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&q3h_chain_kernel<CHAIN_SETS, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        hipError_t e = hipSuccess;
+#define IFLOW_CHAIN_ATTR(FF, FUSED) \
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<chain_sets(FF), FUSED, FF>), \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, CHAIN_LDS_BYTES);
+        IFLOW_CHAIN_FOR_ALL(IFLOW_CHAIN_ATTR)
+#undef IFLOW_CHAIN_ATTR
+        return e;
     });
     if (e0 != hipSuccess) return e0;
     *grid = cus < CHAIN_MAX_GRID ? cus : CHAIN_MAX_GRID;
@@ -640,6 +826,8 @@ hipError_t chain_grid_for_device(int *grid)
 // the kernel's limits.
 bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
 {
+    int strip_cols, slot_bytes, block, row_bits;
+    if (!chain_format(c.format, &strip_cols, &slot_bytes, &block, &row_bits)) return false;
     const int nmat = c.first[c.nphases - 1] + c.counts[c.nphases - 1];
     out.assign(chain_plan_bytes(c.nphases, nmat), 0);
     ChainHeader *hd = reinterpret_cast<ChainHeader *>(out.data());
@@ -659,16 +847,20 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
         ops[p].inv_cols = 1.0f / (float)c.cols[p];
         fused = fused || gated || ops[p].x_op != IFLOW_X_PLAIN;
         for (int j = 0; j < CHAIN_MAX_GROUP; ++j) ph.mstart[j] = 0x7FFFFFFF;
-        ph.nbk = (int)(c.cols[p] / 64); ph.nstrips = (ph.nbk + 63) / 64;
+        if (c.cols[p] < block || c.cols[p] % block != 0 || c.cols[p] > chain_max_cols(c.format) || c.counts[p] > CHAIN_MAX_GROUP) return false;
+        ph.nbk = (int)(c.cols[p] / block); ph.nstrips = (int)((c.cols[p] + strip_cols - 1) / strip_cols);
         ph.x_src = c.x_src[p];
         ph.x_tag_word = c.x_src[p] >= 0 ? mats[c.x_src[p]].tag_word : 0;
-        if (ph.nstrips > CHAIN_MAX_STRIPS || c.counts[p] > CHAIN_MAX_GROUP) return false;
         if (ph.nstrips > max_strips) max_strips = ph.nstrips;
         int64_t v = 0;
         for (int j = 0; j < c.counts[p]; ++j, ++m) {
             mats[m].packed = static_cast<const uint8_t *>(c.packed[m]); mats[m].y = c.y[m]; mats[m].rows = (int)c.rows[m];
             mats[m].start = (int)v;
             mats[m].tag_word = (int)word;
+            // (formats with the headers behind the codes: rows x cols x row_bits / 8 bytes of codes come first)
+            const int64_t code_bytes = c.rows[m] * c.cols[p] * row_bits / 8;
+            if (c.format != IFLOW_Q3H_B64 && code_bytes / 4 > 0xFFFFFFFFLL) return false;
+            mats[m].hdr_off4 = c.format != IFLOW_Q3H_B64 ? (uint32_t)(code_bytes / 4) : 0u;
             word += (size_t)((c.rows[m] + 4095) / 4096) * 4096;
             if (gated) {                                       // the pair (gate, up) is one matrix of 2 x rows in the row space;
                 if (j == 0) {                                  // the up matrix keeps an (unused) descriptor of its own
@@ -693,24 +885,37 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
     hd->magic = IFLOW_CHAIN_MAGIC; hd->nphases = c.nphases; hd->nmatrices = nmat; hd->grid = grid; hd->max_strips = max_strips;
-    hd->fused = fused ? 1 : 0;
+    hd->fused = fused ? 1 : 0; hd->format = c.format;
     return true;
 }
 
-hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, hipStream_t s)
+// strips of the widest phase of a chain (what the launch sizes its LDS by)
+int chain_strips(int format, int64_t cols)
+{
+    int strip_cols, slot_bytes, block, row_bits;
+    if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return 0;
+    return (int)((cols + strip_cols - 1) / strip_cols);
+}
+
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, int format, hipStream_t s)
 {
     int g = 0;
     hipError_t e = chain_grid_for_device(&g);                  // (raises the kernel's LDS limit on this device if it has not been)
     if (e != hipSuccess) return e;
-    if (g != grid || max_strips < 1 || max_strips > CHAIN_MAX_STRIPS) return hipErrorInvalidValue;   // planned for another device
-    const size_t lds = (size_t)max_strips * CHAIN_SLOT_BYTES + 64;      // (+ the wavefronts' shares of sum x^2)
-    if (fused)
-        hipLaunchKernelGGL((q3h_chain_kernel<CHAIN_SETS, true>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
-                           static_cast<uint32_t *>(workspace));
-    else
-        hipLaunchKernelGGL((q3h_chain_kernel<CHAIN_SETS, false>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, static_cast<const uint8_t *>(plan),
-                           static_cast<uint32_t *>(workspace));
-    return hipGetLastError();
+    int strip_cols, slot_bytes, block, row_bits;
+    if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return hipErrorInvalidValue;
+    const size_t lds = (size_t)max_strips * slot_bytes + 64;   // (+ the wavefronts' shares of sum x^2)
+    if (g != grid || max_strips < 1 || lds > (size_t)CHAIN_LDS_BYTES) return hipErrorInvalidValue;   // planned for another device
+    bool launched = false;
+#define IFLOW_CHAIN_GO(FF, FUSED) \
+    if (!launched && format == FF && fused == FUSED) { \
+        hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, \
+                           static_cast<const uint8_t *>(plan), static_cast<uint32_t *>(workspace)); \
+        launched = true; \
+    }
+    IFLOW_CHAIN_FOR_ALL(IFLOW_CHAIN_GO)
+#undef IFLOW_CHAIN_GO
+    return launched ? hipGetLastError() : hipErrorInvalidValue;
 }
 
 }  // namespace iflow

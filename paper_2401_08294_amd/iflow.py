@@ -27,7 +27,7 @@ ATTN_STATIC_MAX_HEADS = 128
 class Chain(C.Structure):
     """iflow_chain_t: what iflow_qgemv_chain_plan fills and iflow_qgemv_chain_launch takes (plain data)."""
     _fields_ = [("plan", C.c_void_p), ("workspace", C.c_void_p), ("grid", C.c_int32), ("max_strips", C.c_int32),
-                ("magic", C.c_uint32), ("fused", C.c_uint32)]
+                ("magic", C.c_uint32), ("fused", C.c_uint32), ("format", C.c_int32), ("reserved", C.c_int32)]
 
 
 class IflowError(RuntimeError):

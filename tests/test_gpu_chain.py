@@ -28,22 +28,22 @@ class Arena:
         return v
 
 
-def plan_chain(torch, iflow, phases, stream=None):
+def plan_chain(torch, iflow, phases, stream=None, fmt_name="Q3H_B64"):
     """Workspace and plan buffers (filled with 0xFF first: the plan call has to zero what it needs) and the compiled chain."""
     rows_all = [m[1] for ph in phases for m in ph[2]]
     ws_bytes = iflow.qgemv_chain_workspace_bytes(rows_all)
     plan_bytes = iflow.qgemv_chain_plan_bytes(phases)
     ws = torch.full((ws_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
     plan = torch.full((plan_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
-    chain = iflow.qgemv_chain_plan(iflow.Q3H_B64, phases, plan, plan_bytes, ws, ws_bytes, stream=stream)
+    chain = iflow.qgemv_chain_plan(iflow.FORMATS[fmt_name], phases, plan, plan_bytes, ws, ws_bytes, stream=stream)
     return chain, (plan, ws)
 
 
-def build_chain(torch, iflow, spec, seed, sigma=0.02):
+def build_chain(torch, iflow, spec, seed, sigma=0.02, fmt_name="Q3H_B64"):
     """spec: list of phases (cols, src, [rows...]) with src None (fresh input) or (phase, matrix) of an earlier
     phase.  Returns device phases for iflow.qgemv_chain_plan, host copies of the weights, the compiled chain and its
     buffers."""
-    fmt = iflow.Q3H_B64
+    fmt = iflow.FORMATS[fmt_name]
     arena = Arena(torch, 2 * sum((r + 127) // 128 * 128 for _, _, rl in spec for r in rl) + 4096)
     phases, host = [], []
     for p, (cols, src, row_list) in enumerate(spec):
@@ -60,18 +60,25 @@ def build_chain(torch, iflow, spec, seed, sigma=0.02):
             assert x.numel() == cols
         phases.append((cols, x, mats))
         host.append(hw)
-    chain, keep = plan_chain(torch, iflow, phases)
+    chain, keep = plan_chain(torch, iflow, phases, fmt_name=fmt_name)
     return phases, host, chain, keep
 
 
-def same_as_single_product(got16, ref16):
-    """The chain runs the single-product kernel's loads, decode and sums in the same order: equal bit for bit."""
-    return bool(np.array_equal(got16, ref16))
+def same_as_single_product(got16, ref16, fmt_name="Q3H_B64"):
+    """3.5-bit format: the chain runs the single-product kernel's loads, decode and sums in the same order - equal bit for
+    bit.  The 4- and 8-bit formats' single-product kernel groups its rows differently, so its fp32 sums (of biased levels:
+    large terms that cancel, which is where the 8-bit format spends most of its error budget) are added in another order: the
+    two agree to within the product tolerance."""
+    if fmt_name == "Q3H_B64":
+        return bool(np.array_equal(got16, ref16))
+    g = got16.view(np.float16).astype(np.float64)
+    r = ref16.view(np.float16).astype(np.float64)
+    return rel_err(g[None, :], r[None, :]) <= TOL
 
 
-def check_phases(torch, iflow, orc, phases, host, what):
+def check_phases(torch, iflow, orc, phases, host, what, fmt_name="Q3H_B64"):
     """Every output against the oracle (given the activations the GPU actually used) and against iflow_qgemv."""
-    fmt, ofmt = iflow.Q3H_B64, orc.FORMATS["Q3H_B64"]
+    fmt, ofmt = iflow.FORMATS[fmt_name], orc.FORMATS[fmt_name]
     for p, (cols, x, mats) in enumerate(phases):
         xh = x.cpu().numpy().view(np.uint16)[None, :]
         for j, (packed, rows, y) in enumerate(mats):
@@ -84,7 +91,7 @@ def check_phases(torch, iflow, orc, phases, host, what):
             single = torch.empty((rows,), dtype=torch.float16, device="cuda")
             iflow.qgemv(fmt, packed, rows, cols, x, single)
             torch.cuda.synchronize()
-            assert same_as_single_product(got.view(np.uint16), single.cpu().numpy().view(np.uint16)), f"{what}: phase {p} matrix {j}"
+            assert same_as_single_product(got.view(np.uint16), single.cpu().numpy().view(np.uint16), fmt_name), f"{what}: phase {p} matrix {j}"
 
 
 SPEC_RAGGED = [
@@ -111,6 +118,77 @@ def test_chain_ragged_phases_and_relaunch(gpu, orc):
         iflow.qgemv_chain_launch(chain)
         iflow.qgemv_chain_check(chain)
         check_phases(torch, iflow, orc, phases, host, f"launch {it}")
+
+
+@pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64", "Q4_B32", "Q8_B32"])
+def test_chain_other_formats_ragged_phases_and_relaunch(gpu, orc, fmt_name):
+    """The 4- and 8-bit formats of Table 3 through the same chained launch (strips of 2048 and 1024 columns, block headers
+    behind the codes): ragged strips, odd matrices, hand-overs across several phases, three launches."""
+    torch, iflow = gpu
+    say(f"[case] chain ragged spec, {fmt_name}, three launches with new inputs")
+    phases, host, chain, keep = build_chain(torch, iflow, SPEC_RAGGED, synth.BASE_SEED + 540, sigma=0.03, fmt_name=fmt_name)
+    assert chain.format == iflow.FORMATS[fmt_name]
+    for it in range(3):
+        if it:
+            for p, (cols, x, _) in enumerate(phases):
+                if SPEC_RAGGED[p][1] is None:
+                    x.copy_(torch.from_numpy(synth.activations(1, cols, synth.BASE_SEED + 640 + 10 * it + p)[0].view(np.int16)).cuda().view(torch.float16))
+            for _, _, mats in phases:
+                for m in mats:
+                    m[2].fill_(float("nan"))
+        iflow.qgemv_chain_launch(chain)
+        iflow.qgemv_chain_check(chain)
+        check_phases(torch, iflow, orc, phases, host, f"{fmt_name} launch {it}", fmt_name=fmt_name)
+
+
+@pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64"])
+def test_chain_other_formats_two_7b_layers(gpu, orc, fmt_name):
+    """Config 3's formats at the 7B layer shapes: two decoder layers (eight dependent phases) in one launch; all rows against
+    the single-product kernel, sampled rows of every output against the oracle."""
+    torch, iflow = gpu
+    say(f"[case] chain of two 7B-shaped layers, {fmt_name}")
+    hidden, ffn = 4096, 11008
+    fmt, ofmt = iflow.FORMATS[fmt_name], orc.FORMATS[fmt_name]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 560)
+    arena = Arena(torch, 2 * 2 * (5 * hidden + 2 * ffn + 7 * 128) + 4096)
+    x0 = (torch.randn((hidden,), generator=gen, device="cuda") * 2.0 ** -6).to(torch.float16)
+    phases, keepw = [], []
+    last = x0
+    for layer in range(2):
+        for rows_list, cols in (([hidden] * 3, hidden), ([hidden], hidden), ([ffn] * 2, hidden), ([hidden], ffn)):
+            mats = []
+            for rows in rows_list:
+                w = torch.randn((rows, cols), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+                nb = iflow.packed_bytes(fmt, rows, cols)
+                pk = torch.empty(nb, dtype=torch.uint8, device="cuda")
+                iflow.quantize(fmt, w, rows, cols, pk, nb)
+                keepw.append(w)
+                mats.append((pk, rows, arena.take(rows)))
+            phases.append((cols, last, mats))
+            last = mats[0][2]
+    chain, keep = plan_chain(torch, iflow, phases, fmt_name=fmt_name)
+    for it in range(2):
+        iflow.qgemv_chain_launch(chain)
+    iflow.qgemv_chain_check(chain)
+    rng = np.random.default_rng(synth.BASE_SEED + 561)
+    wi = 0
+    for p, (cols, x, mats) in enumerate(phases):
+        xh = x.cpu().numpy().view(np.uint16)[None, :]
+        for j, (pk, rows, y) in enumerate(mats):
+            got = y.cpu().numpy()
+            assert np.isfinite(got).all(), f"phase {p} matrix {j}"
+            single = torch.empty((rows,), dtype=torch.float16, device="cuda")
+            iflow.qgemv(fmt, pk, rows, cols, x, single)
+            torch.cuda.synchronize()
+            assert same_as_single_product(got.view(np.uint16), single.cpu().numpy().view(np.uint16), fmt_name), f"phase {p} matrix {j}: differs from iflow_qgemv"
+            pick = np.unique(np.concatenate([[0, 1, rows - 2, rows - 1], rng.integers(0, rows, 28)]))
+            wsel = keepw[wi][torch.from_numpy(pick).cuda()].cpu().numpy()
+            q, s_, o_ = orc.quantize(ofmt, wsel)
+            ref = orc.gemm(orc.dequant(ofmt, q, s_, o_), xh)[0]
+            e = rel_err(got.astype(np.float64)[pick][None, :], ref[None, :])
+            assert e <= TOL, f"phase {p} matrix {j}: rel err {e}"
+            wi += 1
 
 
 def test_chain_single_phase_is_qgemv(gpu, orc):

@@ -90,7 +90,11 @@ def test_chain_validation_happens_before_any_launch(iflow):
                                         None, C.byref(chain))
 
     x0, pk, y0, y1 = base, base * 2, base * 3, base * 4
-    assert call(3, [1], [64], [x0], [pk], [8], [y0]) == iflow.ERR_FORMAT         # 3.5-bit format only
+    for bit_planes in (5, 6, 7, 8):                                              # 3.5-, 4- and 8-bit formats only
+        assert call(bit_planes, [1], [64], [x0], [pk], [8], [y0]) == iflow.ERR_FORMAT
+    assert call(1, [1], [61440 + 64], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE  # 8-bit: a row's staged activations must fit LDS
+    assert call(3, [1], [65536 + 64], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE
+    assert call(3, [1], [96], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE          # cols % block (64)
     assert call(4, [], [], [], [], [], []) == iflow.ERR_SHAPE                    # no phase
     assert call(4, [1] * 1025, [64] * 1025, [x0] * 1025, [pk] * 1025, [8] * 1025, [y0 + 64 * i for i in range(1025)]) == iflow.ERR_SHAPE
     assert call(4, [5], [64], [x0], [pk] * 5, [8] * 5, [y0 + 64 * i for i in range(5)]) == iflow.ERR_SHAPE   # > 4 per phase
