@@ -28,14 +28,14 @@ def err(y_bits, yref):
     return float(np.max(np.abs(y - yref) / np.maximum(np.abs(yref), max(rms, 1e-30))))
 
 
-def quantized(torch, iflow, orc, rows, cols, seed, sigma):
+def quantized(torch, iflow, orc, rows, cols, seed, sigma, fmt_name="Q3H_B64"):
     w = synth.weights(rows, cols, sigma, seed)
-    packed, _ = gpu_quantize(torch, iflow, iflow.Q3H_B64, w)
-    q, s, o = orc.quantize(orc.Q3H_B64, w)
-    return packed, orc.dequant(orc.Q3H_B64, q, s, o)
+    packed, _ = gpu_quantize(torch, iflow, iflow.FORMATS[fmt_name], w)
+    q, s, o = orc.quantize(orc.FORMATS[fmt_name], w)
+    return packed, orc.dequant(orc.FORMATS[fmt_name], q, s, o)
 
 
-def layers_chain(torch, iflow, orc, hidden, ffn, nlayers, seed):
+def layers_chain(torch, iflow, orc, hidden, ffn, nlayers, seed, fmt_name="Q3H_B64"):
     """nlayers decoder layers as four phases each: norm -> q,k,v | o + residual | norm -> silu(gate) * up | down + residual
     (q's output stands in for the attention output).  Returns the phases, a description of what each phase computes, and
     the hidden-state input of the launch."""
@@ -48,11 +48,11 @@ def layers_chain(torch, iflow, orc, hidden, ffn, nlayers, seed):
         s0 = seed + 100 * layer
         g1 = dev16(torch, (1.0 + 0.2 * rng.standard_normal(hidden)).astype(np.float16).view(np.uint16))
         g2 = dev16(torch, (1.0 + 0.2 * rng.standard_normal(hidden)).astype(np.float16).view(np.uint16))
-        wq, wk, wv = [quantized(torch, iflow, orc, hidden, hidden, s0 + i, 1.0 / np.sqrt(hidden)) for i in range(3)]
-        wo = quantized(torch, iflow, orc, hidden, hidden, s0 + 3, 0.5 / np.sqrt(hidden))
-        wg = quantized(torch, iflow, orc, ffn, hidden, s0 + 4, 2.0 / np.sqrt(hidden))
-        wu = quantized(torch, iflow, orc, ffn, hidden, s0 + 5, 1.0 / np.sqrt(hidden))
-        wd = quantized(torch, iflow, orc, hidden, ffn, s0 + 6, 0.5 / np.sqrt(ffn))
+        wq, wk, wv = [quantized(torch, iflow, orc, hidden, hidden, s0 + i, 1.0 / np.sqrt(hidden), fmt_name) for i in range(3)]
+        wo = quantized(torch, iflow, orc, hidden, hidden, s0 + 3, 0.5 / np.sqrt(hidden), fmt_name)
+        wg = quantized(torch, iflow, orc, ffn, hidden, s0 + 4, 2.0 / np.sqrt(hidden), fmt_name)
+        wu = quantized(torch, iflow, orc, ffn, hidden, s0 + 5, 1.0 / np.sqrt(hidden), fmt_name)
+        wd = quantized(torch, iflow, orc, hidden, ffn, s0 + 6, 0.5 / np.sqrt(ffn), fmt_name)
         q, k, v = arena.take(hidden), arena.take(hidden), arena.take(hidden)
         h1, a, h2 = arena.take(hidden), arena.take(ffn), arena.take(hidden)
         phases.append((hidden, h, [(wq[0], hidden, q), (wk[0], hidden, k), (wv[0], hidden, v)], {"x_op": iflow.X_RMS_GAIN, "aux": g1, "eps": EPS}))
@@ -67,13 +67,13 @@ def layers_chain(torch, iflow, orc, hidden, ffn, nlayers, seed):
     return phases, what, h_in
 
 
-def plan_fused(torch, iflow, phases):
+def plan_fused(torch, iflow, phases, fmt_name="Q3H_B64"):
     rows_all = [m[1] for ph in phases for m in ph[2]]
     ws_bytes = iflow.qgemv_chain_workspace_bytes(rows_all)
     plan_bytes = iflow.qgemv_chain_plan_bytes(phases)
     ws = torch.full((ws_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
     plan = torch.full((plan_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
-    return iflow.qgemv_chain_plan_fused(iflow.Q3H_B64, phases, plan, plan_bytes, ws, ws_bytes), (plan, ws)
+    return iflow.qgemv_chain_plan_fused(iflow.FORMATS[fmt_name], phases, plan, plan_bytes, ws, ws_bytes), (plan, ws)
 
 
 def check(what, label):
@@ -119,6 +119,28 @@ def test_fused_layers_in_one_launch(gpu, orc, hidden, ffn, nlayers):
         iflow.qgemv_chain_launch(chain)
         iflow.qgemv_chain_check(chain)
         worst = check(what, f"launch {it}")
+        say(f"        launch {it}: largest rel err of the linear phases {worst:.3e}")
+
+
+@pytest.mark.parametrize("fmt_name,hidden,ffn,nlayers", [("Q4_B64", 1088, 4160, 2), ("Q8_B64", 1088, 4160, 2), ("Q4_B32", 256, 704, 3),
+                                                         ("Q8_B32", 2112, 1088, 1), ("Q4_B64", 4096, 11008, 1)])
+def test_fused_layers_in_one_launch_other_formats(gpu, orc, fmt_name, hidden, ffn, nlayers):
+    """The same decoder layers through the chained launch of the 4- and 8-bit formats (every module in use)."""
+    torch, iflow = gpu
+    say(f"[case] fused chain, {fmt_name}: {nlayers} layer(s), hidden={hidden} ffn={ffn}")
+    phases, what, h_in = layers_chain(torch, iflow, orc, hidden, ffn, nlayers, synth.BASE_SEED + 4500 + hidden, fmt_name)
+    chain, keep = plan_fused(torch, iflow, phases, fmt_name)
+    assert chain.fused == 1 and chain.format == iflow.FORMATS[fmt_name]
+    for it in range(2):
+        if it:
+            h_in.copy_(dev16(torch, synth.activations(1, hidden, synth.BASE_SEED + 4600 + it)[0].view(np.uint16)))
+            for _, _, mats, _ in phases:
+                for m in mats:
+                    if m[2] is not None:
+                        m[2].fill_(float("nan"))
+        iflow.qgemv_chain_launch(chain)
+        iflow.qgemv_chain_check(chain)
+        worst = check(what, f"{fmt_name} launch {it}")
         say(f"        launch {it}: largest rel err of the linear phases {worst:.3e}")
 
 
