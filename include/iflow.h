@@ -161,6 +161,18 @@ iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate,
                                  int64_t cols, const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps,
                                  uint16_t *y, void *stream);
 
+/* iflow_qgemv_fused for a small batch of activation vectors (Section 5: with dynamic batching a decode step serves several
+ * queries at once; each of them is normalized, gated and carried on by itself): one matrix, 1 <= batch <= 16 vectors,
+ *   Y[b][n] = fp16( c_b * sum_k w'[n][k] v[b][k]  (+ residual[b][n]) ),
+ * x_op = IFLOW_X_PLAIN: v = X, c_b = 1, aux null; IFLOW_X_RMS_GAIN: v[b][k] = fp16(X[b][k] aux[k]) with the gains aux [cols],
+ * c_b = 1 / sqrt(mean_k X[b][k]^2 + eps); IFLOW_X_SILU_MUL: v[b][k] = fp16(silu(X[b][k]) aux[b][k]) with aux [batch][cols],
+ * c_b = 1.  X [batch][cols], residual and Y [batch][rows], fp16, device; residual may be null, or Y itself (in place); Y must
+ * not overlap X or aux.  All nine formats; cols a multiple of 64; batch 1 is iflow_qgemv_fused, 2..16 run on the matrix
+ * cores with the weights streamed once (the kernel of iflow_qgemm); more than 16 vectors: IFLOW_ERR_SHAPE. */
+iflow_status_t iflow_qgemm_fused(iflow_format_t format, const void *packed, int64_t rows, int64_t cols, const uint16_t *X,
+                                 int64_t batch, iflow_x_op_t x_op, const uint16_t *aux, float eps, const uint16_t *residual,
+                                 uint16_t *Y, void *stream);
+
 /* A chain of batch-1 products in ONE launch (the 3.5-, 4- and 8-bit formats, Table 3's Q3H, Q4_B32/B64, Q8_B32/B64; the
  * bit-plane formats are IFLOW_ERR_FORMAT): the decode step applies its projections one
  * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and

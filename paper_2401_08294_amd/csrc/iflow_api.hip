@@ -228,6 +228,39 @@ iflow_status_t iflow_qgemv_fused(iflow_format_t format, int count, const void *c
     return device_status(iflow::launch_qgemv_fused(count, packed, rows, cols, x, (int)x_op, aux, eps, residual, y, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_qgemm_fused(iflow_format_t format, const void *packed, int64_t rows, int64_t cols, const uint16_t *X, int64_t batch,
+                                 iflow_x_op_t x_op, const uint16_t *aux, float eps, const uint16_t *residual, uint16_t *Y, void *stream)
+{
+    iflow::FormatInfo fi;
+    if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
+    if (batch < 1 || batch > 16) return IFLOW_ERR_SHAPE;
+    if (x_op != IFLOW_X_PLAIN && x_op != IFLOW_X_RMS_GAIN && x_op != IFLOW_X_SILU_MUL) return IFLOW_ERR_SHAPE;
+    if (!packed || !X || !Y) return IFLOW_ERR_NULL;
+    if ((x_op == IFLOW_X_PLAIN) != (aux == nullptr)) return IFLOW_ERR_NULL;
+    if (x_op == IFLOW_X_RMS_GAIN && !(eps >= 0.0f && eps < 3.0e38f)) return IFLOW_ERR_SHAPE;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (cols % 64 != 0) return IFLOW_ERR_SHAPE;                // (the 32-wide formats too: the batch kernel works on 64-column groups)
+    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y) || (aux && !aligned16(aux))) return IFLOW_ERR_ALIGN;
+    const int64_t aux_len = x_op == IFLOW_X_SILU_MUL ? batch * cols : cols;
+    // outputs are written while other workgroups still read X and aux
+    if (overlaps(Y, batch * rows * 2, X, batch * cols * 2) || (aux && overlaps(Y, batch * rows * 2, aux, aux_len * 2))) return IFLOW_ERR_SHAPE;
+    if (residual) {
+        if (((uintptr_t)residual & 1u) != 0) return IFLOW_ERR_ALIGN;
+        // a residual element is read by the thread that writes the same output element: equal to Y is fine, a shifted overlap is not
+        if (residual != Y && overlaps(residual, batch * rows * 2, Y, batch * rows * 2)) return IFLOW_ERR_SHAPE;
+    }
+    if (batch == 1) {
+        const void *pk[1] = {packed};
+        const int64_t rw[1] = {rows};
+        const uint16_t *rs[1] = {residual};
+        uint16_t *ys[1] = {Y};
+        return iflow_qgemv_fused(format, 1, pk, rw, cols, X, x_op, aux, eps, rs, ys, stream);
+    }
+    return device_status(iflow::launch_qgemm_small_fused((int)format, packed, rows, cols, X, batch, (int)x_op, aux, eps, residual, Y,
+                                                         (hipStream_t)stream));
+}
+
 iflow_status_t iflow_qgemv_gated(iflow_format_t format, const void *packed_gate, const void *packed_up, int64_t rows, int64_t cols,
                                  const uint16_t *x, iflow_x_op_t x_op, const uint16_t *aux, float eps, uint16_t *y, void *stream)
 {

@@ -252,6 +252,8 @@ hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_str
 bool chain_supports_format(int format);
 int64_t chain_max_cols(int format);
 int chain_strips(int format, int64_t cols);
+hipError_t launch_qgemm_small_fused(int format, const void *packed, int64_t rows, int64_t cols, const uint16_t *X, int64_t batch, int x_op,
+                                    const uint16_t *aux, float eps, const uint16_t *residual, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int64_t cols,
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s);
 hipError_t launch_qgemm_mfma(int format, const void *packed, int64_t rows, int64_t cols,

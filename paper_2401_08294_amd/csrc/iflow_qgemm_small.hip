@@ -37,15 +37,27 @@ constexpr int SMALL_RED_FLOATS = 16 * 4 * 64;
 constexpr int SMALL_SETS = 2;                                 // register sets of weights in flight per wavefront (even)
 constexpr int SMALL_MAX_ROUNDS = 16;                          // rounds per workgroup when there is more than one strip
 constexpr int SMALL_LDS_BYTES = SMALL_XBYTES + 2 * SMALL_RED_FLOATS * 4 + SMALL_MAX_ROUNDS * 256 * 4;
+constexpr int SMALL_LDS_BYTES_OPS = SMALL_LDS_BYTES + 16 * 16 * 4;        // + the wavefronts' shares of sum x^2 per activation vector
 
 // A grid of at most one workgroup per compute unit; workgroup b takes the groups of sixteen rows group0 + b,
 // group0 + b + gridDim.x, ... below `ngroups` ("rounds").  Per strip the activations are loaded once, with loads
 // in which neighbouring lanes read neighbouring addresses, turned through LDS into the operand layout and kept in
 // registers for all rounds; the weights of the round after next are requested while a round is decoded.
-template <int F, int S>
-__global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
-                                                          uint16_t *__restrict__ Y, int rows, int cols, int batch, int nbk64, int nstrips,
-                                                          int64_t header_offset, int group0, int ngroups)
+// The modules of a decoder layer around the product, per activation vector (Section 2's module table: "rms" normalization,
+// "silu" activation; Section 5: dynamic batching makes several vectors per step the served case): XOP = -1 none (the plain
+// kernel), IFLOW_X_PLAIN (residual only), IFLOW_X_RMS_GAIN (v = fp16(x g) at the staging, sum x^2 per vector, the scalar
+// 1/sqrt(mean + eps) at the store), IFLOW_X_SILU_MUL (v = fp16(silu(x) aux) at the staging, aux [batch][cols]); a residual
+// [batch][rows] is added to the fp32 sum before its one rounding.
+struct SmallOps {
+    const uint16_t *aux;
+    const uint16_t *residual;
+    float eps;
+};
+
+template <int F, int S, int XOP>
+__device__ __forceinline__ void gemm_small_body(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
+                                                uint16_t *__restrict__ Y, int rows, int cols, int batch, int nbk64, int nstrips,
+                                                int64_t header_offset, int group0, int ngroups, const SmallOps ops)
 {
     typedef Fmt<F> T;
     constexpr int KIND = T::kind;
@@ -123,6 +135,8 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
     const half2_t m1025 = {(half_t)-1025.0f, (half_t)-1025.0f}, m1024 = {(half_t)-1024.0f, (half_t)-1024.0f};
     const half2_t m11 = {(half_t)-11.0f, (half_t)-11.0f}, m64 = {(half_t)-64.0f, (half_t)-64.0f};
     half4_t xq[16];                                           // MFMA B operands of the current strip
+    float ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // (rms normalization) this lane's share of sum x^2 of the eight vectors it loads
+    float *ssq_lds = reinterpret_cast<float *>(lds + SMALL_LDS_BYTES);                // [wavefront][vector]
 
     // one round: dequantize the lane's block, sixteen MFMA steps, add the sixteen wavefronts' tiles up through LDS
     auto round_body = [&](const SmallRaw<KIND> &raw, int t, int r, int which) {
@@ -220,6 +234,15 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
                 part[r * 256 + tid] = sum;
             } else {
                 const int rr = (first + r * (int)gridDim.x) * 16 + 4 * (l >> 4) + e, b = l & 15;
+                if constexpr (XOP == IFLOW_X_RMS_GAIN) {      // the vector's normalization scalar: the wavefronts' shares in a fixed order
+                    float tot = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 16; ++w) tot += ssq_lds[w * 16 + b];
+                    sum *= 1.0f / __builtin_sqrtf(tot / (float)cols + ops.eps);
+                }
+                if constexpr (XOP >= 0) {
+                    if (ops.residual != nullptr && rr < rows && b < batch) sum += (float)as_h(ops.residual[(int64_t)b * rows + rr]);
+                }
                 if (rr < rows && b < batch) Y[(int64_t)b * rows + rr] = as_u16((half_t)sum);
             }
         }
@@ -238,6 +261,61 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             vb[q] = *reinterpret_cast<const u32x4_t *>(X + (int64_t)min(8 + 2 * q + (lane >> 5), batch - 1) * cols + c);
+        if constexpr (XOP == IFLOW_X_RMS_GAIN) {
+            // the lane's eight columns of every vector it loaded: x^2 summed (columns past the end and dead column groups
+            // were redirected to column 0: they do not count), then v = fp16(x g), an exact product rounded once
+            const bool counts = (t * 64 + wave * 4) * 64 + (lane & 31) * 8 < cols;
+            const u32x4_t gv = *reinterpret_cast<const u32x4_t *>(ops.aux + c);
+            const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t xa[4] = {va[q].x, va[q].y, va[q].z, va[q].w}, xb[4] = {vb[q].x, vb[q].y, vb[q].z, vb[q].w};
+                float sa = 0.f, sb = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    sa = __builtin_amdgcn_fdot2(as_h2(xa[e]), as_h2(xa[e]), sa, false);
+                    sb = __builtin_amdgcn_fdot2(as_h2(xb[e]), as_h2(xb[e]), sb, false);
+                    xa[e] = as_u32(as_h2(xa[e]) * as_h2(gw[e]));
+                    xb[e] = as_u32(as_h2(xb[e]) * as_h2(gw[e]));
+                }
+                ssq[q] += counts ? sa : 0.f;
+                ssq[4 + q] += counts ? sb : 0.f;
+                va[q] = (u32x4_t){xa[0], xa[1], xa[2], xa[3]};
+                vb[q] = (u32x4_t){xb[0], xb[1], xb[2], xb[3]};
+            }
+            if (t == nstrips - 1) {
+                // vector 2q + (lane >> 5) (and 8 + ...) over the wavefront's lanes: sum within each half of the wavefront
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    float v = row16_sum(ssq[q]);
+                    v += __shfl_xor(v, 16);
+                    if ((lane & 31) == 0) ssq_lds[wave * 16 + (q < 4 ? 2 * q : 8 + 2 * (q - 4)) + (lane >> 5)] = v;
+                    ssq[q] = 0.f;
+                }
+            }
+        } else if constexpr (XOP == IFLOW_X_SILU_MUL) {
+            // v = fp16(silu(x) aux) in fp32 with the hardware exp and reciprocal, one rounding
+            auto gate = [&](u32x4_t &v, int brow) {
+                const u32x4_t av = *reinterpret_cast<const u32x4_t *>(ops.aux + (int64_t)min(brow, batch - 1) * cols + c);
+                uint32_t xv[4] = {v.x, v.y, v.z, v.w};
+                const uint32_t aw[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const half2_t xa = as_h2(xv[e]), xb = as_h2(aw[e]);
+                    const float g0 = (float)xa.x, g1 = (float)xa.y;
+                    const float v0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * (float)xb.x;
+                    const float v1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * (float)xb.y;
+                    const half2_t rv = {(half_t)v0, (half_t)v1};
+                    xv[e] = as_u32(rv);
+                }
+                v = (u32x4_t){xv[0], xv[1], xv[2], xv[3]};
+            };
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                gate(va[q], 2 * q + (lane >> 5));
+                gate(vb[q], 8 + 2 * q + (lane >> 5));
+            }
+        }
         uint32_t n[32];
 #pragma unroll
         for (int q = 0; q < 32; ++q) n[q] = 0u;
@@ -319,15 +397,36 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restr
     }
 }
 
-template <int F>
-static hipError_t small_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s)
+template <int F, int S>
+__global__ __launch_bounds__(1024) void gemm_small_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
+                                                          uint16_t *__restrict__ Y, int rows, int cols, int batch, int nbk64, int nstrips,
+                                                          int64_t header_offset, int group0, int ngroups)
+{
+    gemm_small_body<F, S, -1>(packed, X, Y, rows, cols, batch, nbk64, nstrips, header_offset, group0, ngroups, SmallOps{});
+}
+
+template <int F, int S, int XOP>
+__global__ __launch_bounds__(1024) void gemm_small_fused_kernel(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ X,
+                                                                uint16_t *__restrict__ Y, int rows, int cols, int batch, int nbk64, int nstrips,
+                                                                int64_t header_offset, int group0, int ngroups, const SmallOps ops)
+{
+    gemm_small_body<F, S, XOP>(packed, X, Y, rows, cols, batch, nbk64, nstrips, header_offset, group0, ngroups, ops);
+}
+
+template <int F, int XOP>
+static hipError_t small_launch(const void *packed, int64_t rows, int64_t cols, const uint16_t *X, int64_t batch, uint16_t *Y, const SmallOps ops,
+                               hipStream_t s)
 {
     typedef Fmt<F> T;
     constexpr int S = SMALL_SETS;
+    constexpr int LDS = XOP < 0 ? SMALL_LDS_BYTES : SMALL_LDS_BYTES_OPS;
     static PerDevice pd;
     int cus = 0;
     hipError_t e0 = once_per_device(pd, &cus, [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_small_kernel<F, S>), hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_BYTES);
+        if constexpr (XOP < 0)
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_small_kernel<F, S>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        else
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_small_fused_kernel<F, S, XOP>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     });
     if (e0 != hipSuccess) return e0;
     const int nbk64 = (int)(cols / 64);
@@ -340,9 +439,14 @@ static hipError_t small_launch(const void *packed, int64_t rows, int64_t cols, c
     for (int64_t g0 = 0; g0 < ngroups; g0 += per_launch) {
         const int64_t g1 = g0 + per_launch < ngroups ? g0 + per_launch : ngroups;
         const int64_t grid = g1 - g0 < cus ? g1 - g0 : cus;
-        hipLaunchKernelGGL((gemm_small_kernel<F, S>), dim3((unsigned)grid), dim3(1024), SMALL_LDS_BYTES, s,
-                           static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk64, nstrips, header_offset,
-                           (int)g0, (int)g1);
+        if constexpr (XOP < 0)
+            hipLaunchKernelGGL((gemm_small_kernel<F, S>), dim3((unsigned)grid), dim3(1024), LDS, s,
+                               static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk64, nstrips, header_offset,
+                               (int)g0, (int)g1);
+        else
+            hipLaunchKernelGGL((gemm_small_fused_kernel<F, S, XOP>), dim3((unsigned)grid), dim3(1024), LDS, s,
+                               static_cast<const uint8_t *>(packed), X, Y, (int)rows, (int)cols, (int)batch, nbk64, nstrips, header_offset,
+                               (int)g0, (int)g1, ops);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -353,7 +457,23 @@ hipError_t launch_qgemm_small(int format, const void *packed, int64_t rows, int6
                               const uint16_t *X, int64_t batch, uint16_t *Y, hipStream_t s)
 {
     if (batch < 1 || batch > 16 || cols % 64 != 0) return hipErrorInvalidValue;
-    return for_format(format, [&](auto f) { return small_launch<decltype(f)::value>(packed, rows, cols, X, batch, Y, s); });
+    return for_format(format, [&](auto f) { return small_launch<decltype(f)::value, -1>(packed, rows, cols, X, batch, Y, SmallOps{}, s); });
+}
+
+hipError_t launch_qgemm_small_fused(int format, const void *packed, int64_t rows, int64_t cols, const uint16_t *X, int64_t batch, int x_op,
+                                    const uint16_t *aux, float eps, const uint16_t *residual, uint16_t *Y, hipStream_t s)
+{
+    if (batch < 1 || batch > 16 || cols % 64 != 0) return hipErrorInvalidValue;
+    const SmallOps ops = {aux, residual, eps};
+    return for_format(format, [&](auto f) {
+        constexpr int F = decltype(f)::value;
+        switch (x_op) {
+        case IFLOW_X_PLAIN: return small_launch<F, IFLOW_X_PLAIN>(packed, rows, cols, X, batch, Y, ops, s);
+        case IFLOW_X_RMS_GAIN: return small_launch<F, IFLOW_X_RMS_GAIN>(packed, rows, cols, X, batch, Y, ops, s);
+        case IFLOW_X_SILU_MUL: return small_launch<F, IFLOW_X_SILU_MUL>(packed, rows, cols, X, batch, Y, ops, s);
+        default: return hipErrorInvalidValue;
+        }
+    });
 }
 
 }  // namespace iflow

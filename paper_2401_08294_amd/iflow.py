@@ -69,6 +69,7 @@ def lib():
         L.iflow_qgemv_gated.argtypes = [C.c_int, p, p, i64, i64, p, C.c_int, p, C.c_float, p, p]
         L.iflow_qgemv_fused.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.c_int, p, C.c_float,
                                         C.POINTER(p), C.POINTER(p), p]
+        L.iflow_qgemm_fused.argtypes = [C.c_int, p, i64, i64, p, i64, C.c_int, p, C.c_float, p, p, p]
         L.iflow_attn_decode_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
         L.iflow_attn_decode.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p, sz, p]
         L.iflow_attn_decode_static.argtypes = [p, p, p, C.c_int, C.c_int, C.c_int, i64, i64, C.c_float, p, p]
@@ -185,6 +186,14 @@ def qgemv_fused(fmt: int, packed_list, rows_list, cols: int, x, y_list, x_op: in
         res = (C.c_void_p * n)(*[(_ptr(t) if t is not None else None) for t in residual_list])
     _check(lib().iflow_qgemv_fused(fmt, n, pk, rs, cols, _ptr(x), x_op, _ptr(aux) if aux is not None else None, eps, res, ys,
                                    _stream(stream)), "iflow_qgemv_fused")
+
+
+def qgemm_fused(fmt: int, packed, rows: int, cols: int, X, batch: int, Y, x_op: int = X_PLAIN, aux=None, eps: float = 0.0,
+                residual=None, stream=None) -> None:
+    """qgemv_fused for 1..16 activation vectors X [batch][cols] -> Y [batch][rows]: rms normalization (aux = gains [cols]) or the
+    silu-gated input (aux [batch][cols]) in front of the product, an optional residual [batch][rows] behind it."""
+    _check(lib().iflow_qgemm_fused(fmt, _ptr(packed), rows, cols, _ptr(X), batch, x_op, _ptr(aux) if aux is not None else None, eps,
+                                   _ptr(residual) if residual is not None else None, _ptr(Y), _stream(stream)), "iflow_qgemm_fused")
 
 
 def qgemv_gated(fmt: int, packed_gate, packed_up, rows: int, cols: int, x, y, x_op: int = X_PLAIN, aux=None, eps: float = 0.0,

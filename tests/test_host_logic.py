@@ -283,6 +283,27 @@ def test_attention_validation_happens_before_any_launch(iflow):
     assert iflow.attn_decode_workspace_bytes(32) == 32 * 64 * 130 * 4
 
 
+def test_batch_fused_validation_happens_before_any_launch(iflow):
+    """iflow_qgemm_fused: batch size, operands and overlap rules are checked on the host (no launch on any error)."""
+    L = iflow.lib()
+    base = 0x100000
+
+    def call(fmt=4, rows=128, cols=256, batch=4, x_op=0, aux=None, eps=0.0, res=None, pk=base, X=base * 2, Y=base * 3):
+        return L.iflow_qgemm_fused(fmt, pk, rows, cols, X, batch, x_op, aux, C.c_float(eps), res, Y, None)
+
+    assert call(fmt=9) == iflow.ERR_FORMAT
+    assert call(batch=0) == iflow.ERR_SHAPE and call(batch=17) == iflow.ERR_SHAPE
+    assert call(x_op=3) == iflow.ERR_SHAPE
+    assert call(x_op=1) == iflow.ERR_NULL and call(x_op=0, aux=base * 4) == iflow.ERR_NULL      # aux if and only if an operation
+    assert call(x_op=1, aux=base * 4, eps=-1.0) == iflow.ERR_SHAPE
+    assert call(cols=100) == iflow.ERR_SHAPE and call(fmt=2, cols=96) == iflow.ERR_SHAPE        # 64-column groups, also for block 32
+    assert call(X=None) == iflow.ERR_NULL and call(Y=None) == iflow.ERR_NULL
+    assert call(X=base * 2 + 2) == iflow.ERR_ALIGN and call(res=base * 5 + 1) == iflow.ERR_ALIGN
+    assert call(Y=base * 2 + 256) == iflow.ERR_SHAPE                                            # Y inside X
+    assert call(x_op=2, aux=base * 3 - 4 * 256 * 2 + 16) == iflow.ERR_SHAPE                     # the end of aux [batch][cols] reaches into Y
+    assert call(res=base * 3 + 64) == iflow.ERR_SHAPE                                           # residual overlaps Y, shifted
+
+
 def test_rope_validation_happens_before_any_launch(iflow):
     L = iflow.lib()
     base = 0x100000
