@@ -19,7 +19,8 @@
 // word is its own "ready" flag: a consumer simply re-reads until every word of the vector carries this launch's
 // tag.  There are no atomics on shared counters and no fences; one memory round trip separates the last producer
 // from the first consumer.  The words are stored in the order in which the consumer's threads want them (below),
-// so that their loads coalesce.  The counter advances once per launch, after every workgroup has finished, so a
+// so that their loads coalesce.  The count advances once per launch (every workgroup advances its own copy when it is
+// done, and launches of a chain are ordered), so a
 // word left by the previous launch never carries the current tag; a workspace that changes hands between chains
 // of different shapes has to be zeroed in between (tags repeat every 65535 launches).  Every wait is bounded:
 // when the budget runs out the workgroup raises the error word of the workspace and carries on, so the launch
@@ -50,7 +51,7 @@ constexpr int CHAIN_MAX_COLS = 65536;
 constexpr int CHAIN_MAX_GROUP = IFLOW_CHAIN_MAX_GROUP;         // matrices per phase
 constexpr int CHAIN_MAX_GRID = 960;
 constexpr int CHAIN_POLL_BUDGET = 1 << 17;                     // re-reads before a wait is given up (tens of milliseconds)
-// workspace header, in 32-bit words: [0] launch counter, [1] error, [64, 64 + grid) per-workgroup "done" marks;
+// workspace header, in 32-bit words: [1] error, [64, 64 + grid) the launch count, one copy per workgroup;
 // tagged outputs start at byte IFLOW_CHAIN_WS_HEADER
 constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_SEEN = 64;
 
@@ -440,9 +441,11 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // because memory requests of a wavefront are served in order and the whole workgroup waits for the staged
     // activations; then S steps of weights; then the chunk is put in place.
     WRegs<KIND> w[S][2];
-    // The launch counter, the oldest load of the wavefront (so it never has to be waited for alone).  A plain cached
-    // load: the word was last written by the previous launch, and changes again only when this one is over.
-    const uint32_t counter = __hip_atomic_load(ws, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    // The launch count, the oldest load of the wavefront (so it never has to be waited for alone): every workgroup keeps its
+    // own copy in the workspace header and advances it when it is done, so all copies read the same at the start of a launch
+    // and nobody has to wait for anybody at the end of one.  A plain cached load: the word was last written by the previous
+    // launch (the plan call zeroes them all).
+    const uint32_t counter = __hip_atomic_load(ws + CHAIN_WS_SEEN + wg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     if constexpr (!Q3H) {                                      // (these formats stage the first phase like any other, below)
         request_segment();
 #pragma unroll
@@ -464,8 +467,8 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
             put_plain(cw + lane, ph0.nbk, src[0], src[1], a.ops);
         }
     }
-    // Every wavefront of the launch reads the same counter (it is advanced only after all workgroups are done), and
-    // tags its outputs with it, 1..65535; 0 marks a word that was never written.
+    // Every wavefront of the launch reads the same count and tags its outputs with it, 1..65535; 0 marks a word that was
+    // never written.
     const uint32_t tag = (counter % 65535u + 1u) << 16;
 
     bool failed = false;
@@ -736,24 +739,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
         }
     }
 
-    // ---- once every workgroup is done, the launch counter advances -------------------------------------------------
+    // ---- the workgroup's copy of the launch count advances ----------------------------------------------------------------
     __syncthreads();
     if (tid == 0) __hip_atomic_store(ws + CHAIN_WS_SEEN + wg, counter + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (wg == 0 && wave == 0) {
-        int budget = CHAIN_POLL_BUDGET;
-        for (;;) {
-            bool ok = true;
-            for (int i = lane; i < (int)gridDim.x; i += 64)
-                ok = ok && __hip_atomic_load(ws + CHAIN_WS_SEEN + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == counter + 1;
-            if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
-            if (--budget <= 0) {
-                if (lane == 0) __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(2);
-        }
-        if (lane == 0) __hip_atomic_store(ws, counter + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
 }
 
 // ---- host side ------------------------------------------------------------------------------------------------
