@@ -318,6 +318,11 @@ iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t ro
 iflow_status_t iflow_unpack_logical(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                                     uint8_t *levels, uint16_t *scale16, uint16_t *offset16, void *stream);
 
+/* Test helper, 3.5-bit format only (others: IFLOW_ERR_FORMAT): the stored pair codes themselves, before Eq.5 takes them
+ * apart - codes [rows][cols/2] uint8, code i of a row = 11 q[2i] + q[2i+1] (Eq.4), each below 121.  Device, 16-byte aligned. */
+iflow_status_t iflow_unpack_pair_codes(iflow_format_t format, const void *packed, int64_t rows, int64_t cols, uint8_t *codes,
+                                       void *stream);
+
 /* Measurement helper (no counterpart in the paper): a plain device copy of `bytes` bytes (a positive multiple of
  * 16; src and dst device, 16-byte aligned, not overlapping) made of the same 16-byte-per-lane nontemporal loads as
  * the weight stream.  Profilers scale their bytes-per-dispatch counters by what they report for this transfer of

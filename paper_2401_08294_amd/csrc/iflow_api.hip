@@ -141,6 +141,17 @@ iflow_status_t iflow_unpack_logical(iflow_format_t format, const void *packed, i
     return device_status(iflow::launch_unpack((int)format, packed, rows, cols, levels, scale16, offset16, (hipStream_t)stream));
 }
 
+iflow_status_t iflow_unpack_pair_codes(iflow_format_t format, const void *packed, int64_t rows, int64_t cols, uint8_t *codes, void *stream)
+{
+    iflow::FormatInfo fi;
+    iflow_status_t st = check_shape(format, rows, cols, &fi);
+    if (st != IFLOW_OK) return st;
+    if (format != IFLOW_Q3H_B64) return IFLOW_ERR_FORMAT;      // only the 3.5-bit format stores pair codes
+    if (!packed || !codes) return IFLOW_ERR_NULL;
+    if (!aligned16(packed) || !aligned16(codes)) return IFLOW_ERR_ALIGN;
+    return device_status(iflow::launch_unpack_pair_codes(packed, rows, cols, codes, (hipStream_t)stream));
+}
+
 iflow_status_t iflow_qgemm(iflow_format_t format, const void *packed, int64_t rows, int64_t cols,
                            const uint16_t *X, int64_t batch, uint16_t *Y, void *stream)
 {

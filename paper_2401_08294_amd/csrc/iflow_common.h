@@ -201,6 +201,7 @@ inline hipError_t device_compute_units(int *cus)
 // ---- host-side launchers, one per translation unit ------------------------------------------------
 hipError_t launch_quantize(int format, const float *w, int64_t rows, int64_t cols, void *packed, hipStream_t s);
 hipError_t launch_dequant(int format, const void *packed, int64_t rows, int64_t cols, uint16_t *w16, hipStream_t s);
+hipError_t launch_unpack_pair_codes(const void *packed, int64_t rows, int64_t cols, uint8_t *codes, hipStream_t s);
 hipError_t launch_unpack(int format, const void *packed, int64_t rows, int64_t cols,
                          uint8_t *levels, uint16_t *scale16, uint16_t *offset16, hipStream_t s);
 hipError_t launch_calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t s);

@@ -222,6 +222,28 @@ static hipError_t read_one(const void *packed, int64_t rows, int64_t cols, uint1
     return hipGetLastError();
 }
 
+// The 3.5-bit format's stored pair codes c = 11 q[2i] + q[2i+1] (Eq.4), one byte each, in weight order: code i of a block
+// covers weights 2i, 2i+1.  One thread per word of a block: its four codes 4i .. 4i+3 sit at bits 0, 16, 7 and 23.
+__global__ __launch_bounds__(256) void q3h_codes_kernel(const uint8_t *__restrict__ packed, int64_t n_words, int nbk, uint8_t *__restrict__ codes)
+{
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (tid >= n_words) return;
+    const int64_t blk = tid / 8;
+    const int i = (int)(tid % 8);
+    const uint32_t word = *reinterpret_cast<const uint32_t *>(packed + q3h_word_offset(blk / nbk, nbk, (int)(blk % nbk), i));
+    reinterpret_cast<uint32_t *>(codes)[tid] = (word & 127u) | ((word >> 16) & 127u) << 8 | ((word >> 7) & 127u) << 16 | ((word >> 23) & 127u) << 24;
+}
+
+hipError_t launch_unpack_pair_codes(const void *packed, int64_t rows, int64_t cols, uint8_t *codes, hipStream_t s)
+{
+    const int nbk = (int)(cols / 64);
+    const int64_t n_words = rows * nbk * 8;
+    const int64_t grid = (n_words + 255) / 256;
+    if (grid > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(q3h_codes_kernel, dim3((unsigned)grid), dim3(256), 0, s, static_cast<const uint8_t *>(packed), n_words, nbk, codes);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize(int format, const float *w, int64_t rows, int64_t cols, void *packed, hipStream_t s)
 {
     return for_format(format, [&](auto f) { return quantize_one<decltype(f)::value>(w, rows, cols, packed, s); });

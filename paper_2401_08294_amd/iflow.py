@@ -63,6 +63,7 @@ def lib():
         L.iflow_qgemv.argtypes = [C.c_int, p, i64, i64, p, p, p]
         L.iflow_qgemm.argtypes = [C.c_int, p, i64, i64, p, i64, p, p]
         L.iflow_unpack_logical.argtypes = [C.c_int, p, i64, i64, p, p, p, p]
+        L.iflow_unpack_pair_codes.argtypes = [C.c_int, p, i64, i64, p, p]
         L.iflow_calibration_copy.argtypes = [p, p, sz, p]
         L.iflow_calibration_read.argtypes = [p, sz, p, p]
         L.iflow_qgemv_multi.argtypes = [C.c_int, C.c_int, C.POINTER(p), C.POINTER(i64), i64, p, C.POINTER(p), p]
@@ -150,6 +151,11 @@ def qgemm(fmt: int, packed, rows: int, cols: int, X, batch: int, Y, stream=None)
 def unpack_logical(fmt: int, packed, rows: int, cols: int, levels, scale16, offset16, stream=None) -> None:
     _check(lib().iflow_unpack_logical(fmt, _ptr(packed), rows, cols, _ptr(levels), _ptr(scale16), _ptr(offset16),
                                       _stream(stream)), "iflow_unpack_logical")
+
+
+def unpack_pair_codes(fmt: int, packed, rows: int, cols: int, codes, stream=None) -> None:
+    """The 3.5-bit format's stored pair codes [rows][cols/2] (Eq.4), uint8."""
+    _check(lib().iflow_unpack_pair_codes(fmt, _ptr(packed), rows, cols, _ptr(codes), _stream(stream)), "iflow_unpack_pair_codes")
 
 
 def calibration_copy(src, dst, nbytes: int, stream=None) -> None:

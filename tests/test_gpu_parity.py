@@ -92,6 +92,12 @@ def check_all(torch, iflow, orc, name, w, x16, tag):
     assert nbad == 0, f"{nbad} packed bytes differ, first at {int(np.flatnonzero(got_bytes != ref_bytes)[0])}"
     lv, sc, of = gpu_unpack(torch, iflow, fmt, packed, rows, cols)
     assert np.array_equal(lv, q) and np.array_equal(sc, s) and np.array_equal(of, o)
+    if name == "Q3H_B64":                                       # the stored pair codes themselves (Eq.4), via the oracle's encoder
+        table = np.array([[orc.pair_encode(a_, b_) for b_ in range(11)] for a_ in range(11)], np.uint8)
+        codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device="cuda")
+        iflow.unpack_pair_codes(fmt, packed, rows, cols, codes)
+        torch.cuda.synchronize()
+        assert np.array_equal(codes.cpu().numpy(), table[q[:, 0::2], q[:, 1::2]]), "pair codes differ"
     ref_deq = orc.dequant(orc.FORMATS[name], q, s, o)
     got_deq = gpu_dequant(torch, iflow, fmt, packed, rows, cols)
     assert np.array_equal(got_deq, ref_deq), "dequantized fp16 weights differ"

@@ -283,6 +283,15 @@ def test_attention_validation_happens_before_any_launch(iflow):
     assert iflow.attn_decode_workspace_bytes(32) == 32 * 64 * 130 * 4
 
 
+def test_unpack_pair_codes_is_for_the_pair_format_only(iflow):
+    L = iflow.lib()
+    base = 0x100000
+    assert L.iflow_unpack_pair_codes(3, base, 8, 64, base * 2, None) == iflow.ERR_FORMAT
+    assert L.iflow_unpack_pair_codes(4, base, 8, 100, base * 2, None) == iflow.ERR_SHAPE
+    assert L.iflow_unpack_pair_codes(4, base, 8, 64, None, None) == iflow.ERR_NULL
+    assert L.iflow_unpack_pair_codes(4, base + 4, 8, 64, base * 2, None) == iflow.ERR_ALIGN
+
+
 def test_batch_fused_validation_happens_before_any_launch(iflow):
     """iflow_qgemm_fused: batch size, operands and overlap rules are checked on the host (no launch on any error)."""
     L = iflow.lib()
