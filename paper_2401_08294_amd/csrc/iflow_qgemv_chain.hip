@@ -141,6 +141,9 @@ struct ChainWalk {
 #ifndef IFLOW_CHAIN_SETS
 #define IFLOW_CHAIN_SETS 2
 #endif
+#ifndef IFLOW_CHAIN_TRACE
+#define IFLOW_CHAIN_TRACE 0
+#endif
 #ifndef IFLOW_CHAIN_EARLY
 #define IFLOW_CHAIN_EARLY 0
 #endif
@@ -471,6 +474,14 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // never written.
     const uint32_t tag = (counter % 65535u + 1u) << 16;
 
+#if IFLOW_CHAIN_TRACE
+    // (development aid, off in the library: per-workgroup time stamps of a launch, 16 words per workgroup and phase, written to
+    // the buffer whose address sits at byte 32 of the plan)
+    uint32_t *const trace = *reinterpret_cast<uint32_t *const *>(plan + 32);
+#define CHAIN_MARK(p, k) do { if (lane == 0) trace[((size_t)wg * nphases + (p)) * 16 + (k)] = (uint32_t)__builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define CHAIN_MARK(p, k) do { } while (0)
+#endif
     bool failed = false;
     XRegs<KIND> xr[1];
     // Results are not stored row by row: lane 63's sums of the wavefront's i-th pair of rows are parked in lane i of two
@@ -628,7 +639,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                 if (lane == 0) sq_slot[wave] = wsum;
                 sumsq = 0.f;
             }
+            CHAIN_MARK(p, wave < 8 ? wave : 15);               // this wavefront's share of the activations is staged
             __syncthreads();
+            if (wave == 0) CHAIN_MARK(p, 8);                   // all of them are
             uint32_t resid = 0;                                // the pair's residuals (two fp16)
             if constexpr (FUSED) {
                 if (a.ops[p].x_op == IFLOW_X_RMS_GAIN) {
@@ -714,6 +727,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                 if constexpr (S > 6) body(std::integral_constant<int, 6>{}, j + 6);
                 if constexpr (S > 7) body(std::integral_constant<int, 7>{}, j + 7);
             }
+            if (wave == 0) CHAIN_MARK(p, 9);                   // steps done: wavefronts 0, 7 and 11
+            if (wave == 7) CHAIN_MARK(p, 10);
+            if (wave == 11) CHAIN_MARK(p, 11);
             // 3. publish: the caller's plain fp16 outputs, and the tagged words for later phases
             if (lane < n) {
                 if constexpr (FUSED) {
