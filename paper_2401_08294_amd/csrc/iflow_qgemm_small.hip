@@ -34,7 +34,10 @@ template <> struct SmallRaw<KIND_Q8>  { uint32_t d[16]; uint32_t hdr[2]; };  // 
 constexpr int SMALL_XROW = 528;
 constexpr int SMALL_XBYTES = 16 * 8 * SMALL_XROW;
 constexpr int SMALL_RED_FLOATS = 16 * 4 * 64;
-constexpr int SMALL_SETS = 2;                                 // register sets of weights in flight per wavefront (even)
+#ifndef IFLOW_SMALL_SETS
+#define IFLOW_SMALL_SETS 2
+#endif
+constexpr int SMALL_SETS = IFLOW_SMALL_SETS;                                 // register sets of weights in flight per wavefront (even)
 constexpr int SMALL_MAX_ROUNDS = 16;                          // rounds per workgroup when there is more than one strip
 constexpr int SMALL_LDS_BYTES = SMALL_XBYTES + 2 * SMALL_RED_FLOATS * 4 + SMALL_MAX_ROUNDS * 256 * 4;
 constexpr int SMALL_LDS_BYTES_OPS = SMALL_LDS_BYTES + 16 * 16 * 4;        // + the wavefronts' shares of sum x^2 per activation vector
