@@ -218,7 +218,8 @@ typedef struct iflow_chain_t {
     void *workspace;            /* device */
     int32_t grid, max_strips;   /* launch geometry the plan was written for */
     uint32_t magic, fused;      /* fused: the plan uses the modules of iflow_qgemv_chain_plan_fused */
-    int32_t format, reserved;   /* the chain's iflow_format_t */
+    int32_t format, lds_bytes;  /* the chain's iflow_format_t; LDS of a launch */
+    int64_t max_seq;            /* iflow_decode_stack_plan: rows of the key/value caches (0 for other plans) */
 } iflow_chain_t;
 iflow_status_t iflow_qgemv_chain_workspace_bytes(int nmatrices, const int64_t *rows, size_t *bytes);
 iflow_status_t iflow_qgemv_chain_plan_bytes(int nphases, int nmatrices, size_t *bytes);
@@ -298,6 +299,48 @@ typedef enum { IFLOW_ROPE_ADJACENT = 0, IFLOW_ROPE_HALVES = 1 } iflow_rope_pairi
 iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, int n_heads, int n_kv_heads,
                                  int head_dim, int64_t position, int64_t max_seq, float base, iflow_rope_pairing_t pair_mode,
                                  uint16_t *k_cache, uint16_t *v_cache, void *stream);
+
+/* A whole decode step of a decoder stack in ONE launch (Section 5: Infer() = one pass over all layers for the step's token;
+ * Section 2's module table for the LLaMA family: "rms" normalization, "rope" position embedding, "silu" activation with a gate;
+ * section "Grouped-query attention").  Per layer, with h the layer's input [hidden]:
+ *   q, k, v = Wq n1, Wk n1, Wv n1          n1 = rmsnorm(h; norm1, eps)
+ *   q, k rotated by the rotary embedding at `position`; k, v appended to the layer's caches at row `position`
+ *   t = attention(q; cached keys and values of positions 0 .. position)        (scale 1 / sqrt(head_dim))
+ *   h1 = h + Wo t
+ *   h2 = h1 + Wdown (silu(Wgate n2) * (Wup n2))          n2 = rmsnorm(h1; norm2, eps)
+ * and h2 is the next layer's input; the last layer's h2 is h_out.  The products are the chained launch above with its modules
+ * (iflow_qgemv_chain_plan_fused), the attention runs as two more phases of the same launch; every vector is rounded to fp16
+ * exactly where the separate calls (iflow_qgemv_fused, iflow_rope_append, iflow_attn_decode, iflow_qgemv_gated) round it, and
+ * all intermediate vectors are left in `scratch` (per layer, each rounded up to 128 elements: q [hidden], k, v
+ * [n_kv_heads * 128], t [hidden], h1 [hidden], silu(gate) * up [ffn], h2 [hidden]).
+ *   format: a format of the chained launch; head_dim must be 128, hidden = n_heads * 128, n_heads a multiple of n_kv_heads
+ *   with 1 or an even number of query heads per key/value head; hidden and ffn multiples of 64.
+ *   layers: HOST array of n_layers entries (1 .. 128); every pointer in it a device pointer, 16-byte aligned.
+ *   h_in, h_out, scratch: device; h_in is not written and must not overlap h_out or scratch.
+ * iflow_decode_stack_sizes gives the bytes of scratch, plan and workspace for a description (pointers in it are not read).
+ * iflow_decode_stack_plan is iflow_qgemv_chain_plan for this chain (same rules: synchronises, allocates host memory only);
+ * iflow_decode_stack_launch runs one step at 0 <= position < max_seq (IFLOW_ERR_SHAPE otherwise): one kernel launch,
+ * allocates nothing, may be captured; iflow_qgemv_chain_check reports a wait that gave up. */
+typedef struct iflow_decode_layer_t {
+    const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down;    /* packed matrices */
+    const uint16_t *norm1, *norm2;                              /* rms gains [hidden] fp16 */
+    uint16_t *k_cache, *v_cache;                                /* [n_kv_heads][max_seq][128] fp16 */
+} iflow_decode_layer_t;
+typedef struct iflow_decode_stack_t {
+    iflow_format_t format;
+    int32_t n_layers, hidden, ffn, n_heads, n_kv_heads, head_dim;
+    int64_t max_seq;
+    float eps, rope_base;
+    int32_t rope_pairing;                                       /* iflow_rope_pairing_t */
+    const iflow_decode_layer_t *layers;
+    const uint16_t *h_in;
+    uint16_t *h_out;
+    uint16_t *scratch;
+} iflow_decode_stack_t;
+iflow_status_t iflow_decode_stack_sizes(const iflow_decode_stack_t *stack, size_t *scratch_bytes, size_t *plan_bytes, size_t *workspace_bytes);
+iflow_status_t iflow_decode_stack_plan(const iflow_decode_stack_t *stack, void *plan, size_t plan_bytes, void *workspace,
+                                       size_t workspace_bytes, void *stream, iflow_chain_t *chain);
+iflow_status_t iflow_decode_stack_launch(const iflow_chain_t *chain, int64_t position, void *stream);
 
 /* Y = X * W'^T for a batch of activations (dynamic batching makes batch > 1 the served case,
  * Section 5): Y[b][n] = sum_k w'[n][k] * X[b][k].

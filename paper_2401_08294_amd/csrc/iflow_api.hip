@@ -473,7 +473,7 @@ iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, 
     std::vector<int> xop_int(nphases, IFLOW_X_PLAIN);
     for (int p = 0; p < nphases && x_op; ++p) xop_int[p] = (int)x_op[p];
     iflow::ChainSpec spec = {(int)format, nphases, counts, first.data(), cols, x, x_src.data(), packed, rows, y,
-                             xop_int.data(), aux, eps, gated, residual, residual_src.data()};
+                             xop_int.data(), aux, eps, gated, residual, residual_src.data(), nullptr, nullptr, 0, nullptr};
     std::vector<uint8_t> host;
     if (!iflow::chain_build_plan(spec, grid, host)) return IFLOW_ERR_SHAPE;   // more rows than the kernel's 32-bit indices cover
     hipStream_t s = (hipStream_t)stream;
@@ -489,7 +489,8 @@ iflow_status_t iflow_qgemv_chain_plan_fused(iflow_format_t format, int nphases, 
     chain->plan = plan; chain->workspace = workspace;
     chain->grid = grid; chain->max_strips = max_strips;
     chain->magic = IFLOW_CHAIN_MAGIC; chain->fused = fused ? 1u : 0u;
-    chain->format = (int32_t)format; chain->reserved = 0;
+    chain->format = (int32_t)format; chain->lds_bytes = iflow::chain_lds_bytes((int)format, max_strips);
+    chain->max_seq = 0;
     return IFLOW_OK;
 }
 
@@ -505,8 +506,8 @@ iflow_status_t iflow_qgemv_chain_plan(iflow_format_t format, int nphases, const 
 iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream)
 {
     if (!chain || !chain->plan || !chain->workspace) return IFLOW_ERR_NULL;
-    if (chain->magic != IFLOW_CHAIN_MAGIC) return IFLOW_ERR_SHAPE;
-    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->max_strips, chain->fused != 0, (int)chain->format,
+    if (chain->magic != IFLOW_CHAIN_MAGIC || chain->max_seq != 0) return IFLOW_ERR_SHAPE;   // (a decoder stack's plan needs a position)
+    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->lds_bytes, chain->fused != 0, (int)chain->format, 0,
                                        (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // planned for a device with another number of compute units
     return device_status(e);
@@ -520,6 +521,185 @@ iflow_status_t iflow_qgemv_chain_check(const iflow_chain_t *chain, void *stream)
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return device_status(e);
     return head[1] ? IFLOW_ERR_TIMEOUT : IFLOW_OK;
+}
+
+// ---- a decoder stack's decode step as one chained launch ---------------------------------------------------------------------
+namespace {
+
+constexpr int STACK_MATS = 8, STACK_PHASES = 6;               // per layer: Wq Wk Wv, the attention's output, Wo, Wgate Wup, Wdown
+constexpr int STACK_MAX_LAYERS = 128;
+
+inline int64_t round128(int64_t n) { return (n + 127) / 128 * 128; }
+
+// element offsets of a layer's intermediate vectors inside its share of the scratch buffer
+struct StackLayout {
+    int64_t q, k, v, t, h1, a, h2, per_layer;
+};
+StackLayout stack_layout(const iflow_decode_stack_t &d)
+{
+    const int64_t kvd = (int64_t)d.n_kv_heads * 128;
+    StackLayout L;
+    L.q = 0; L.k = L.q + round128(d.hidden); L.v = L.k + round128(kvd); L.t = L.v + round128(kvd);
+    L.h1 = L.t + round128(d.hidden); L.a = L.h1 + round128(d.hidden); L.h2 = L.a + round128(d.ffn);
+    L.per_layer = L.h2 + round128(d.hidden);
+    return L;
+}
+
+iflow_status_t stack_check_shape(const iflow_decode_stack_t *d)
+{
+    if (!d) return IFLOW_ERR_NULL;
+    if (!iflow::chain_supports_format((int)d->format)) return IFLOW_ERR_FORMAT;
+    if (d->n_layers < 1 || d->n_layers > STACK_MAX_LAYERS) return IFLOW_ERR_SHAPE;
+    if (d->head_dim != 128 || d->n_heads < 1 || d->n_kv_heads < 1 || d->n_heads % d->n_kv_heads != 0) return IFLOW_ERR_SHAPE;
+    const int group = d->n_heads / d->n_kv_heads;
+    if (group != 1 && (group & 1)) return IFLOW_ERR_SHAPE;
+    if ((int64_t)d->n_heads * 128 != d->hidden) return IFLOW_ERR_SHAPE;
+    const int64_t max_cols = iflow::chain_max_cols((int)d->format);
+    if (d->hidden % 64 != 0 || d->ffn < 64 || d->ffn % 64 != 0 || d->hidden > max_cols || d->ffn > max_cols) return IFLOW_ERR_SHAPE;
+    if (d->max_seq < 1 || d->max_seq > (1LL << 20)) return IFLOW_ERR_SHAPE;
+    if (d->rope_pairing != IFLOW_ROPE_ADJACENT && d->rope_pairing != IFLOW_ROPE_HALVES) return IFLOW_ERR_SHAPE;
+    if (!(d->eps >= 0.0f) || !(d->rope_base > 1.0f)) return IFLOW_ERR_SHAPE;
+    return IFLOW_OK;
+}
+
+// rows of the eight matrix entries of every layer
+void stack_rows(const iflow_decode_stack_t &d, std::vector<int64_t> &rows)
+{
+    const int64_t kvd = (int64_t)d.n_kv_heads * 128;
+    rows.resize((size_t)d.n_layers * STACK_MATS);
+    for (int l = 0; l < d.n_layers; ++l) {
+        int64_t *r = rows.data() + (size_t)l * STACK_MATS;
+        r[0] = d.hidden; r[1] = kvd; r[2] = kvd; r[3] = d.hidden; r[4] = d.hidden; r[5] = d.ffn; r[6] = d.ffn; r[7] = d.hidden;
+    }
+}
+
+size_t stack_workspace_bytes(const iflow_decode_stack_t &d, const std::vector<int64_t> &rows, int grid)
+{
+    return iflow::chain_workspace_bytes((int)rows.size(), rows.data()) +
+           (size_t)d.n_layers * iflow::chain_attn_workspace_bytes(d.n_heads, d.n_kv_heads, grid);
+}
+
+}  // namespace
+
+iflow_status_t iflow_decode_stack_sizes(const iflow_decode_stack_t *stack, size_t *scratch_bytes, size_t *plan_bytes, size_t *workspace_bytes)
+{
+    iflow_status_t st = stack_check_shape(stack);
+    if (st != IFLOW_OK) return st;
+    if (!scratch_bytes || !plan_bytes || !workspace_bytes) return IFLOW_ERR_NULL;
+    int grid = 0;
+    hipError_t e = iflow::chain_grid_for_device(&grid);
+    if (e != hipSuccess) return device_status(e);
+    if (stack->n_kv_heads > grid) return IFLOW_ERR_SHAPE;
+    std::vector<int64_t> rows;
+    stack_rows(*stack, rows);
+    *scratch_bytes = (size_t)stack->n_layers * (size_t)stack_layout(*stack).per_layer * 2;
+    *plan_bytes = iflow::chain_plan_bytes(stack->n_layers * STACK_PHASES, stack->n_layers * STACK_MATS, stack->n_layers);
+    *workspace_bytes = stack_workspace_bytes(*stack, rows, grid);
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_decode_stack_plan(const iflow_decode_stack_t *stack, void *plan, size_t plan_bytes, void *workspace,
+                                       size_t workspace_bytes, void *stream, iflow_chain_t *chain)
+{
+    iflow_status_t st = stack_check_shape(stack);
+    if (st != IFLOW_OK) return st;
+    const iflow_decode_stack_t &d = *stack;
+    if (!d.layers || !d.h_in || !d.h_out || !d.scratch || !plan || !workspace || !chain) return IFLOW_ERR_NULL;
+    if (!aligned16(d.h_in) || !aligned16(d.h_out) || !aligned16(d.scratch) || !aligned16(plan) || !aligned16(workspace)) return IFLOW_ERR_ALIGN;
+    const StackLayout L = stack_layout(d);
+    const size_t scratch_bytes = (size_t)d.n_layers * (size_t)L.per_layer * 2;
+    if (overlaps(d.h_in, (size_t)d.hidden * 2, d.h_out, (size_t)d.hidden * 2) || overlaps(d.h_in, (size_t)d.hidden * 2, d.scratch, scratch_bytes) ||
+        overlaps(d.h_out, (size_t)d.hidden * 2, d.scratch, scratch_bytes)) return IFLOW_ERR_SHAPE;
+    for (int l = 0; l < d.n_layers; ++l) {
+        const iflow_decode_layer_t &y = d.layers[l];
+        const void *ptrs[] = {y.wq, y.wk, y.wv, y.wo, y.w_gate, y.w_up, y.w_down, y.norm1, y.norm2, y.k_cache, y.v_cache};
+        for (const void *p : ptrs) {
+            if (!p) return IFLOW_ERR_NULL;
+            if (!aligned16(p)) return IFLOW_ERR_ALIGN;
+        }
+    }
+    int grid = 0;
+    hipError_t e = iflow::chain_grid_for_device(&grid);
+    if (e != hipSuccess) return device_status(e);
+    if (d.n_kv_heads > grid) return IFLOW_ERR_SHAPE;
+    std::vector<int64_t> rows;
+    stack_rows(d, rows);
+    const int nphases = d.n_layers * STACK_PHASES, nmat = d.n_layers * STACK_MATS;
+    const size_t ws_need = stack_workspace_bytes(d, rows, grid);
+    if (workspace_bytes < ws_need || plan_bytes < iflow::chain_plan_bytes(nphases, nmat, d.n_layers)) return IFLOW_ERR_SIZE;
+
+    // the chain: per layer   [norm1 -> Wq Wk Wv] [attention, first half] [second half] [Wo + h] [norm2 -> gate, up] [Wdown + h1]
+    std::vector<int> counts(nphases), first(nphases), x_src(nphases), x_op(nphases), gated(nphases), kind(nphases), attn_of(nphases);
+    std::vector<int64_t> cols(nphases);
+    std::vector<const uint16_t *> x(nphases, nullptr), aux(nphases, nullptr), residual(nmat, nullptr);
+    std::vector<float> eps(nphases, 0.0f);
+    std::vector<const void *> packed(nmat, nullptr);
+    std::vector<uint16_t *> y(nmat, nullptr);
+    std::vector<int> residual_src(nmat, -1);
+    std::vector<iflow::ChainAttnSpec> attn(d.n_layers);
+    for (int l = 0; l < d.n_layers; ++l) {
+        const iflow_decode_layer_t &w = d.layers[l];
+        const int p0 = l * STACK_PHASES, m0 = l * STACK_MATS;
+        uint16_t *base = d.scratch + (int64_t)l * L.per_layer;
+        const uint16_t *h = l == 0 ? d.h_in : d.scratch + (int64_t)(l - 1) * L.per_layer + L.h2;
+        const int h_src = l == 0 ? -1 : m0 - 1;               // the layer's input: the launch's, or the layer before's Wdown
+        const int cnt[STACK_PHASES] = {3, 1, 0, 1, 2, 1};
+        int m = m0;
+        for (int j = 0; j < STACK_PHASES; ++j) {
+            counts[p0 + j] = cnt[j]; first[p0 + j] = m; m += cnt[j];
+            x_src[p0 + j] = -1; x_op[p0 + j] = IFLOW_X_PLAIN; gated[p0 + j] = 0; kind[p0 + j] = 0; attn_of[p0 + j] = l;
+            cols[p0 + j] = d.hidden;
+        }
+        // Wq, Wk, Wv on the normalized input
+        x[p0] = h; x_src[p0] = h_src; x_op[p0] = IFLOW_X_RMS_GAIN; aux[p0] = w.norm1; eps[p0] = d.eps;
+        packed[m0 + 0] = w.wq; y[m0 + 0] = base + L.q;
+        packed[m0 + 1] = w.wk; y[m0 + 1] = base + L.k;
+        packed[m0 + 2] = w.wv; y[m0 + 2] = base + L.v;
+        // attention
+        kind[p0 + 1] = 1; kind[p0 + 2] = 2;
+        y[m0 + 3] = base + L.t;
+        attn[l] = {nullptr, nullptr, nullptr, m0 + 0, m0 + 1, m0 + 2, w.k_cache, w.v_cache, d.n_heads, d.n_kv_heads, (int)d.max_seq,
+                   (int)d.rope_pairing, 1.0f / sqrtf(128.0f), d.rope_base};
+        // Wo, plus the layer's input
+        x[p0 + 3] = base + L.t; x_src[p0 + 3] = m0 + 3;
+        packed[m0 + 4] = w.wo; y[m0 + 4] = base + L.h1; residual[m0 + 4] = h; residual_src[m0 + 4] = h_src;
+        // the gated feed-forward on the normalized h1
+        x[p0 + 4] = base + L.h1; x_src[p0 + 4] = m0 + 4; x_op[p0 + 4] = IFLOW_X_RMS_GAIN; aux[p0 + 4] = w.norm2; eps[p0 + 4] = d.eps;
+        gated[p0 + 4] = 1;
+        packed[m0 + 5] = w.w_gate; y[m0 + 5] = base + L.a;
+        packed[m0 + 6] = w.w_up; y[m0 + 6] = nullptr;
+        x[p0 + 5] = base + L.a; x_src[p0 + 5] = m0 + 5; cols[p0 + 5] = d.ffn;
+        packed[m0 + 7] = w.w_down; y[m0 + 7] = l == d.n_layers - 1 ? d.h_out : base + L.h2;
+        residual[m0 + 7] = base + L.h1; residual_src[m0 + 7] = m0 + 4;
+    }
+    iflow::ChainSpec spec = {(int)d.format, nphases, counts.data(), first.data(), cols.data(), x.data(), x_src.data(), packed.data(), rows.data(),
+                             y.data(), x_op.data(), aux.data(), eps.data(), gated.data(), residual.data(), residual_src.data(),
+                             kind.data(), attn_of.data(), d.n_layers, attn.data()};
+    std::vector<uint8_t> host;
+    if (!iflow::chain_build_plan(spec, grid, host)) return IFLOW_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    e = hipMemsetAsync(workspace, 0, ws_need, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(plan, host.data(), host.size(), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return device_status(e);
+    const int max_strips = std::max(iflow::chain_strips((int)d.format, d.hidden), iflow::chain_strips((int)d.format, d.ffn));
+    chain->plan = plan; chain->workspace = workspace;
+    chain->grid = grid; chain->max_strips = max_strips;
+    chain->magic = IFLOW_CHAIN_MAGIC; chain->fused = 1u;
+    chain->format = (int32_t)d.format; chain->lds_bytes = iflow::chain_lds_bytes((int)d.format, max_strips);
+    chain->max_seq = d.max_seq;
+    return IFLOW_OK;
+}
+
+iflow_status_t iflow_decode_stack_launch(const iflow_chain_t *chain, int64_t position, void *stream)
+{
+    if (!chain || !chain->plan || !chain->workspace) return IFLOW_ERR_NULL;
+    if (chain->magic != IFLOW_CHAIN_MAGIC || chain->max_seq < 1 || chain->fused == 0) return IFLOW_ERR_SHAPE;
+    if (position < 0 || position >= chain->max_seq) return IFLOW_ERR_SHAPE;
+    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->lds_bytes, true, (int)chain->format, (int)position,
+                                       (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;
+    return device_status(e);
 }
 
 iflow_status_t iflow_calibration_copy(const void *src, void *dst, size_t bytes, void *stream)

@@ -244,12 +244,26 @@ struct ChainSpec {
     const int *gated;                  // per phase: 1 = the phase's two matrices are the gate and up projections of a gated feed-forward
     const uint16_t *const *residual;   // per matrix, entries may be null
     const int *residual_src;           // per matrix: the matrix whose output is the residual, or -1 for an input of the launch
+    // decode attention inside the launch (may be absent: nattn = 0, kind = null)
+    const int *kind;                   // per phase: 0 products; 1 / 2: first / second half of attention attn_of[p] (kind 1 owns one
+    const int *attn_of;                //   matrix entry, the attention's output [n_heads * 128] with packed = null; kind 2 none)
+    int nattn;
+    const struct ChainAttnSpec *attn;
+};
+struct ChainAttnSpec {
+    const uint16_t *q, *k_new, *v_new; // inputs of the launch, or null with the matrix that produces them:
+    int q_src, k_src, v_src;
+    uint16_t *k_cache, *v_cache;
+    int n_heads, n_kv_heads, max_seq, pairing;
+    float scale, base;
 };
 size_t chain_workspace_bytes(int nmatrices, const int64_t *rows);
-size_t chain_plan_bytes(int nphases, int nmatrices);
+size_t chain_attn_workspace_bytes(int n_heads, int n_kv_heads, int grid);
+size_t chain_plan_bytes(int nphases, int nmatrices, int nattn = 0);
 bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out);
 hipError_t chain_grid_for_device(int *grid);
-hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, int format, hipStream_t s);
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int lds_bytes, bool fused, int format, int position, hipStream_t s);
+int chain_lds_bytes(int format, int max_strips);
 bool chain_supports_format(int format);
 int64_t chain_max_cols(int format);
 int chain_strips(int format, int64_t cols);

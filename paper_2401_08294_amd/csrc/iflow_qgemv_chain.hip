@@ -70,7 +70,8 @@ struct ChainPhase {
     int total;                  // rows of the phase, all its matrices together
     int x_tag_word;             // tagged output of matrix x_src, in 32-bit words from the workspace start
     int mstart[CHAIN_MAX_GROUP];    // first row of each matrix within the phase; INT_MAX past `count`
-    int pad_[2];
+    int kind;                   // 0: products; 1, 2: the two halves of a decode attention (below), with no rows of their own
+    int attn;                   // which attention
 };
 struct ChainMatrix {
     const uint8_t *packed;
@@ -96,14 +97,38 @@ struct ChainPhaseOps {
 struct ChainHeader {
     uint32_t magic;
     int nphases, nmatrices, grid;
-    int max_strips, fused, format, pad_[9];
+    int max_strips, fused, format, nattn, lds_bytes, pad_[7];
 };
-static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 64 && sizeof(ChainHeader) == 64 && sizeof(ChainPhaseOps) == 32, "descriptor sizes");
+// One decode step of grouped-query attention inside the launch (section "Grouped-query attention"; Section 5's Infer() runs
+// it between the q/k/v products and the output projection), head dimension 128, with the rotary position embedding of the
+// step's query and key and the step's append to the key/value cache (what iflow_rope_append and iflow_attn_decode do as
+// launches of their own).  It takes two phases.  Phase "part": workgroup (kv head j, range sp) rotates the group's queries,
+// walks its range of cached positions with a streaming softmax and leaves one partial state (maximum, sum, 128 weighted value
+// sums) per query head in the workspace, as 64-bit words (fp32 bits, launch tag); the workgroup whose range holds the step's
+// own position rotates the new key, uses it and the new value from registers and writes both into the caches.  Phase "merge":
+// every output component merges the partial states of its head's ranges and is published like any output of a product, for
+// the output projection that follows.
+struct ChainAttn {
+    const uint16_t *q, *k_new, *v_new;  // where they are inputs of the launch (else null: tagged outputs of earlier products)
+    uint16_t *k_cache, *v_cache;        // [n_kv_heads][max_seq][128] fp16
+    uint16_t *out;                      // [n_heads][128] fp16
+    int q_tag_word, k_tag_word, v_tag_word, out_tag_word;   // in 32-bit words from the workspace start
+    int part_word;                      // partial states: 64-bit words [head][nsplit][130] (128 value sums, maximum, sum)
+    int n_heads, n_kv_heads, nsplit;
+    int max_seq, pairing;               // iflow_rope_pairing_t
+    float scale_log2e;
+    int pad0_;
+    double log2_base;
+    int pad_[6];
+};
+static_assert(sizeof(ChainPhase) == 64 && sizeof(ChainMatrix) == 64 && sizeof(ChainHeader) == 64 && sizeof(ChainPhaseOps) == 32 &&
+              sizeof(ChainAttn) == 128, "descriptor sizes");
 // the two descriptor arrays of a plan, as the kernel indexes them
 struct ChainArgs {
     const ChainPhase *ph;
     const ChainMatrix *mat;
     const ChainPhaseOps *ops;
+    const ChainAttn *attn;
 };
 
 // Position of output r inside a matrix's tagged vector, in 32-bit words.  A consumer thread stages one chunk of 16
@@ -182,8 +207,264 @@ __device__ __forceinline__ void park(float &keep0, float &keep1, int value0, int
                  : "+v"(keep0), "+v"(keep1) : "s"(value0), "s"(value1), "s"(slot) : "m0");
 }
 
+// ---- decode attention inside the launch ------------------------------------------------------------------------------------
+typedef uint32_t attn_u32x4 __attribute__((ext_vector_type(4)));
+
+// eight fp16 values (four pairs, components c0 .. c0 + 7 of vector element `base`) of a vector that is either an input of the
+// launch (plain) or the tagged output of an earlier product; a tagged read repeats until all eight carry the launch's tag
+__device__ __forceinline__ attn_u32x4 chain_read8(const uint16_t *plain, const uint32_t *ws, int tag_word, int element, uint32_t tag, bool &failed)
+{
+    if (plain != nullptr) return *global_ptr<const attn_u32x4>(plain + element);
+    const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + tag_word);
+    uint32_t v[4];
+    int budget = failed ? 1 : CHAIN_POLL_BUDGET;
+    for (;;) {
+        bool ok = true;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = (element >> 1) + i;               // pair g of the vector: 8-byte word (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255)
+            const uint64_t wd = __hip_atomic_load(base + (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t lo = (uint32_t)wd, hi = (uint32_t)(wd >> 32);
+            ok = ok && ((lo ^ tag) >> 16) == 0 && ((hi ^ tag) >> 16) == 0;
+            v[i] = (lo & 0xFFFFu) | (hi << 16);
+        }
+        if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
+        if (--budget <= 0) {
+            failed = true;
+            __hip_atomic_store(const_cast<uint32_t *>(ws) + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    return (attn_u32x4){v[0], v[1], v[2], v[3]};
+}
+
+// Rotary embedding of the lane's eight components c0 .. c0 + 7 of a 128-component head (`own`), given the components the
+// pairing joins them with (`other`: c0 +- 64 .. for the pairing by halves; unused for adjacent pairs).  table[i] = (cos, sin)
+// of pair i's angle at this step's position.  fp64 arithmetic, one rounding to fp16: the values iflow_rope_append writes.
+__device__ __forceinline__ attn_u32x4 chain_rope8(attn_u32x4 own, attn_u32x4 other, int c0, int pairing, const double2 *table)
+{
+    const uint32_t o[4] = {own.x, own.y, own.z, own.w}, p[4] = {other.x, other.y, other.z, other.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const half2_t a = as_h2(o[i]), b = as_h2(p[i]);
+        const double ax = (double)(float)a.x, ay = (double)(float)a.y, bx = (double)(float)b.x, by = (double)(float)b.y;
+        double lo, hi;
+        if (pairing == IFLOW_ROPE_HALVES) {                 // component c pairs with c + 64; the pair's index is c mod 64
+            const double2 t0 = table[(c0 + 2 * i) & 63], t1 = table[(c0 + 2 * i + 1) & 63];
+            if (c0 < 64) { lo = ax * t0.x - bx * t0.y; hi = ay * t1.x - by * t1.y; }       // (a, b) = (own, partner): first of the pair
+            else         { lo = bx * t0.y + ax * t0.x; hi = by * t1.y + ay * t1.x; }       // second of the pair: partner sin + own cos
+        } else {                                            // components (2i, 2i+1) are a pair
+            const double2 t = table[(c0 >> 1) + i];
+            lo = ax * t.x - ay * t.y;
+            hi = ax * t.y + ay * t.x;
+        }
+        const half2_t rv = {(half_t)lo, (half_t)hi};
+        r[i] = as_u32(rv);
+    }
+    return (attn_u32x4){r[0], r[1], r[2], r[3]};
+}
+
+// Phase "part" for R of the query heads of a key/value head's group, heads r0 .. r0 + R - 1 of the group (a group larger than
+// two heads takes several passes over its range: the registers of the step loop stay live through this phase, which leaves
+// room for two heads' running states).  lds: at least (4 * CHAIN_WAVES) * 130 floats.
+template <int R>
+__device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *ws, float *lds, const double2 *table, uint32_t tag, int position,
+                                                int wg, int wave, int lane, int r0, bool &failed)
+{
+    const int group = at.n_heads / at.n_kv_heads;
+    constexpr int NST = 4 * CHAIN_WAVES;                       // running softmax states of a workgroup: four lane groups per wavefront
+    const int nsplit = at.nsplit;
+    if (wg >= at.n_kv_heads * nsplit) return;                  // (uniform over the workgroup)
+    const int j = wg / nsplit, sp = wg - j * nsplit;
+    const int seq_len = position + 1;
+    const int chunk = ((seq_len + nsplit - 1) / nsplit + 15) & ~15;
+    const int t_begin = sp * chunk, t_end = min(seq_len, t_begin + chunk);     // may be empty
+    const bool has_new = t_begin <= position && position < t_end;             // this range holds the step's own position
+    const int gq = lane >> 4, dseg = lane & 15, c0 = dseg * 8;
+    const int partner = at.pairing == IFLOW_ROPE_HALVES ? (c0 ^ 64) : c0;
+    float *s_acc = lds, *s_m = lds + NST * 128, *s_l = s_m + NST;
+
+    // the group's queries, rotated
+    half2_t qr[R][4];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int e = (j * group + r0 + r) * 128;
+        const attn_u32x4 own = chain_read8(at.q, ws, at.q_tag_word, e + c0, tag, failed);
+        const attn_u32x4 oth = at.pairing == IFLOW_ROPE_HALVES ? chain_read8(at.q, ws, at.q_tag_word, e + partner, tag, failed) : own;
+        const attn_u32x4 rot = chain_rope8(own, oth, c0, at.pairing, table);
+        qr[r][0] = as_h2(rot.x); qr[r][1] = as_h2(rot.y); qr[r][2] = as_h2(rot.z); qr[r][3] = as_h2(rot.w);
+    }
+    // the step's key (rotated) and value, where this range needs them; one wavefront also appends them to the caches
+    attn_u32x4 k_now = {0u, 0u, 0u, 0u}, v_now = {0u, 0u, 0u, 0u};
+    if (has_new) {
+        const attn_u32x4 own = chain_read8(at.k_new, ws, at.k_tag_word, j * 128 + c0, tag, failed);
+        const attn_u32x4 oth = at.pairing == IFLOW_ROPE_HALVES ? chain_read8(at.k_new, ws, at.k_tag_word, j * 128 + partner, tag, failed) : own;
+        k_now = chain_rope8(own, oth, c0, at.pairing, table);
+        v_now = chain_read8(at.v_new, ws, at.v_tag_word, j * 128 + c0, tag, failed);
+        if (wave == 0 && gq == 0 && r0 == 0) {
+            const int64_t row = ((int64_t)j * at.max_seq + position) * 128 + c0;
+            *global_ptr<attn_u32x4>(at.k_cache + row) = k_now;
+            *global_ptr<attn_u32x4>(at.v_cache + row) = v_now;
+        }
+    }
+    const uint16_t *kh = at.k_cache + (int64_t)j * at.max_seq * 128 + c0;
+    const uint16_t *vh = at.v_cache + (int64_t)j * at.max_seq * 128 + c0;
+
+    float m[R], l[R], acc[R][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        m[r] = -INFINITY; l[r] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    }
+    // blocks of sixteen positions, wavefront w takes blocks w, w + CHAIN_WAVES, ...; four positions per load instruction, one
+    // per lane group; positions past the range read its last position (in bounds) and are masked; the step's own position
+    // comes from registers (its cache row is being written)
+    constexpr int STEP = 16 * CHAIN_WAVES;
+    for (int p0 = t_begin + wave * 16; p0 < t_end; p0 += STEP) {
+        attn_u32x4 kt[4], vt[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int pos = min(p0 + t * 4 + gq, t_end - 1);
+            const int64_t off = (int64_t)min(pos, has_new && pos == position ? max(position - 1, 0) : pos) * 128;   // never the row being written
+            kt[t] = __builtin_nontemporal_load(global_ptr<const attn_u32x4>(kh + off));
+            vt[t] = __builtin_nontemporal_load(global_ptr<const attn_u32x4>(vh + off));
+            if (pos == position) { kt[t] = k_now; vt[t] = v_now; }
+        }
+        // scores of the four positions for every head, the running maxima brought up to date; then the values, one position
+        // at a time (converted once for all heads)
+        float sc[R][4], base[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float bm = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float d = __builtin_amdgcn_fdot2(qr[r][0], as_h2(kt[t].x), 0.f, false);
+                d = __builtin_amdgcn_fdot2(qr[r][1], as_h2(kt[t].y), d, false);
+                d = __builtin_amdgcn_fdot2(qr[r][2], as_h2(kt[t].z), d, false);
+                d = __builtin_amdgcn_fdot2(qr[r][3], as_h2(kt[t].w), d, false);
+                d = row16_sum(d) * at.scale_log2e;
+                sc[r][t] = (p0 + t * 4 + gq < t_end) ? d : -INFINITY;
+                bm = fmaxf(bm, sc[r][t]);
+            }
+            const float m_new = fmaxf(m[r], bm);
+            const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m[r] - m_new);
+            base[r] = (m_new == -INFINITY) ? 0.f : m_new;
+            l[r] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] *= alpha;
+            m[r] = m_new;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const half2_t a = as_h2(vt[t].x), b = as_h2(vt[t].y), c = as_h2(vt[t].z), d = as_h2(vt[t].w);
+            const float vf[8] = {(float)a.x, (float)a.y, (float)b.x, (float)b.y, (float)c.x, (float)c.y, (float)d.x, (float)d.y};
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float pr = __builtin_amdgcn_exp2f(sc[r][t] - base[r]);
+                l[r] += pr;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_fmaf(pr, vf[e], acc[r][e]);
+            }
+        }
+    }
+    // the workgroup's states of each head -> one partial state in the workspace (64-bit words: fp32 bits, launch tag)
+    const int pid = wave * 4 + gq, tid = wave * 64 + lane;
+    uint64_t *part = reinterpret_cast<uint64_t *>(ws + at.part_word);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r > 0) __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_acc[pid * 128 + c0 + e] = acc[r][e];
+        if (dseg == 0) { s_m[pid] = m[r]; s_l[pid] = l[r]; }
+        __syncthreads();
+        if (tid < 128) {
+            float M = s_m[0];
+            for (int i = 1; i < NST; ++i) M = fmaxf(M, s_m[i]);
+            float L = 0.f, O = 0.f;
+            if (M != -INFINITY) {                              // (an empty range leaves maximum -inf, sums zero)
+                for (int i = 0; i < NST; ++i) {
+                    const float f = __builtin_amdgcn_exp2f(s_m[i] - M);
+                    L = __builtin_fmaf(s_l[i], f, L);
+                    O = __builtin_fmaf(s_acc[i * 128 + tid], f, O);
+                }
+            }
+            uint64_t *dst = part + ((int64_t)(j * group + r0 + r) * nsplit + sp) * 130;
+            const uint64_t hi = (uint64_t)tag << 32;
+            __hip_atomic_store(dst + tid, hi | __builtin_bit_cast(uint32_t, O), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) {
+                __hip_atomic_store(dst + 128, hi | __builtin_bit_cast(uint32_t, M), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(dst + 129, hi | __builtin_bit_cast(uint32_t, L), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    __syncthreads();                                           // the states in LDS are no longer needed
+}
+
+// Phase "merge": a workgroup takes a contiguous piece of the n_heads * 128 outputs (head, component).  One thread per (range,
+// output) reads that range's partial state (re-reading until it carries the launch's tag) and leaves it in LDS - all ranges at
+// once, one memory latency - then one thread per output merges the ranges in order and publishes the output: the plain fp16
+// value and the tagged word a later phase stages from.  lds: nsplit * per_wg * 3 floats.
+__device__ __forceinline__ int chain_attn_merge_per_wg(int n_heads, int nwg)
+{
+    return ((n_heads * 128 + nwg - 1) / nwg + 1) & ~1;       // (even, so that a workgroup writes whole pairs)
+}
+__device__ __forceinline__ void chain_attn_merge(const ChainAttn &at, uint32_t *ws, float *lds, uint32_t tag, int wg, int nwg, int tid, bool &failed)
+{
+    const int total = at.n_heads * 128;
+    const int per_wg = chain_attn_merge_per_wg(at.n_heads, nwg);
+    const int o_base = wg * per_wg, n_here = min(per_wg, total - o_base);
+    if (n_here <= 0) return;                                   // (uniform over the workgroup)
+    const uint64_t *parts = reinterpret_cast<const uint64_t *>(ws + at.part_word);
+    const int nsplit = at.nsplit;
+    for (int idx = tid; idx < nsplit * n_here; idx += 64 * CHAIN_WAVES) {
+        const int i = idx / n_here, ol = idx - i * n_here, o = o_base + ol;
+        const uint64_t *src = parts + ((int64_t)(o >> 7) * nsplit + i) * 130;
+        uint64_t wo, wm, wl;
+        int budget = failed ? 1 : CHAIN_POLL_BUDGET;
+        for (;;) {
+            wo = __hip_atomic_load(src + (o & 127), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            wm = __hip_atomic_load(src + 128, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            wl = __hip_atomic_load(src + 129, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)(wo >> 32) == tag && (uint32_t)(wm >> 32) == tag && (uint32_t)(wl >> 32) == tag) break;
+            if (--budget <= 0) {
+                failed = true;
+                __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        float *dst = lds + (i * per_wg + ol) * 3;
+        dst[0] = __builtin_bit_cast(float, (uint32_t)wo);
+        dst[1] = __builtin_bit_cast(float, (uint32_t)wm);
+        dst[2] = __builtin_bit_cast(float, (uint32_t)wl);
+    }
+    __syncthreads();
+    if (tid < n_here) {
+        float M = -INFINITY, L = 0.f, O = 0.f;
+        for (int i = 0; i < nsplit; ++i) {
+            const float *st = lds + (i * per_wg + tid) * 3;
+            const float oi = st[0], mi = st[1], li = st[2];
+            const float m_new = fmaxf(M, mi);
+            if (m_new != -INFINITY) {                          // (ranges in order: the first non-empty one sets the maximum)
+                const float keep = __builtin_amdgcn_exp2f(M - m_new), f = __builtin_amdgcn_exp2f(mi - m_new);
+                L = L * keep + li * f;
+                O = O * keep + oi * f;
+                M = m_new;
+            }
+        }
+        const int o = o_base + tid;
+        const uint32_t h = as_u16((half_t)(O / L));
+        *global_ptr<uint16_t>(at.out + o) = (uint16_t)h;
+        __hip_atomic_store(ws + at.out_tag_word + chain_tag_word(o), h | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();                                           // the states in LDS are no longer needed
+}
+
 template <int S, bool FUSED, int F>
-__global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws)
+__global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws, int position)
 {
     constexpr bool EARLY = IFLOW_CHAIN_EARLY != 0;
     using T = Fmt<F>;
@@ -200,7 +481,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     const ChainArgs a = {reinterpret_cast<const ChainPhase *>(plan + sizeof(ChainHeader)),
                          reinterpret_cast<const ChainMatrix *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * sizeof(ChainPhase)),
                          reinterpret_cast<const ChainPhaseOps *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * sizeof(ChainPhase) +
-                                                                 (size_t)hd->nmatrices * sizeof(ChainMatrix))};
+                                                                 (size_t)hd->nmatrices * sizeof(ChainMatrix)),
+                         reinterpret_cast<const ChainAttn *>(plan + sizeof(ChainHeader) + (size_t)hd->nphases * (sizeof(ChainPhase) + sizeof(ChainPhaseOps)) +
+                                                             (size_t)hd->nmatrices * sizeof(ChainMatrix))};
     extern __shared__ __align__(16) uint8_t xs[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = IFLOW_UNI(tid >> 6);
@@ -488,8 +771,39 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // registers, and when the phase's steps are done lanes 0..n-1 store them all at once - two store instructions
     // per wavefront and phase instead of two per row (in-order completion means every later load of the wavefront would
     // otherwise queue behind a write-through store), and no output pointers to advance inside the step loop.
+    // (with attention in the plan: the rotary embedding's cosines and sines at this step's position, pair i of a 128-component
+    // head turning by position * base^(-2i/128), computed once per workgroup in fp64 and kept in LDS behind everything else)
+    double2 *const rope_table = reinterpret_cast<double2 *>(xs + hd->lds_bytes - 1024);
+    if constexpr (FUSED) {
+        if (hd->nattn > 0 && wave == 0) {
+            const double angle = (double)position * exp2(-(2.0 * lane / 128.0) * a.attn[0].log2_base);
+            double sn, cs;
+            sincos(angle, &sn, &cs);
+            rope_table[lane] = make_double2(cs, sn);
+        }
+    }
     for (int p = 0; p < nphases; ++p) {
         const ChainPhase ph = a.ph[p];
+        if constexpr (FUSED) {
+            if (ph.kind != 0) {                                // a half of a decode attention: every workgroup takes part
+                const ChainAttn at = a.attn[ph.attn];
+                __syncthreads();                               // (the table; LDS of the phase before is free)
+                if (ph.kind == 1) {
+                    float *const scratch = reinterpret_cast<float *>(xs);
+                    const int group = at.n_heads / at.n_kv_heads;
+                    if (group == 1) {
+                        chain_attn_part<1>(at, ws, scratch, rope_table, tag, position, wg, wave, lane, 0, failed);
+                    } else {                                   // (even by the plan's check)
+#pragma unroll 1
+                        for (int r0 = 0; r0 < group; r0 += 2)
+                            chain_attn_part<2>(at, ws, scratch, rope_table, tag, position, wg, wave, lane, r0, failed);
+                    }
+                } else {
+                    chain_attn_merge(at, ws, reinterpret_cast<float *>(xs), tag, wg, (int)gridDim.x, tid, failed);
+                }
+                continue;
+            }
+        }
         const int nbk = ph.nbk, nstrips = ph.nstrips;
         int rbeg, n;                                           // first row of the workgroup, rows of this wavefront
         phase_rows(ph.rows_per_wg, ph.total, rbeg, n);
@@ -768,9 +1082,35 @@ size_t chain_workspace_bytes(int nmatrices, const int64_t *rows)
     return bytes;
 }
 
-size_t chain_plan_bytes(int nphases, int nmatrices)
+static bool chain_format(int format, int *strip_cols, int *slot_bytes, int *block, int *row_bits);
+
+size_t chain_plan_bytes(int nphases, int nmatrices, int nattn)
 {
-    return sizeof(ChainHeader) + (size_t)nphases * (sizeof(ChainPhase) + sizeof(ChainPhaseOps)) + (size_t)nmatrices * sizeof(ChainMatrix);
+    return sizeof(ChainHeader) + (size_t)nphases * (sizeof(ChainPhase) + sizeof(ChainPhaseOps)) + (size_t)nmatrices * sizeof(ChainMatrix) +
+           (size_t)nattn * sizeof(ChainAttn);
+}
+
+// position ranges per key/value head of an attention inside the launch: about one workgroup per (head, range)
+static int chain_attn_splits(int n_kv_heads, int grid)
+{
+    const int n = grid / n_kv_heads;
+    return n < 1 ? 1 : n > 64 ? 64 : n;
+}
+
+// the partial states of one attention: 64-bit words [head][range][130]
+size_t chain_attn_workspace_bytes(int n_heads, int n_kv_heads, int grid)
+{
+    return (size_t)n_heads * chain_attn_splits(n_kv_heads, grid) * 130 * 8;
+}
+
+// Dynamic LDS of a launch: the staged activations of the widest phase (+ the shares of sum x^2) or the attention's running
+// states, whichever is larger, and the rotary embedding's table behind them.
+int chain_lds_bytes(int format, int max_strips)
+{
+    int strip_cols, slot_bytes, block, row_bits;
+    if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return 0;
+    const int x_region = max_strips * slot_bytes + 64, attn_region = 4 * CHAIN_WAVES * 130 * 4;
+    return (x_region > attn_region ? x_region : attn_region) + 1024;
 }
 
 // The formats the chained launch is built for, and their strip geometry on the host side.
@@ -797,7 +1137,7 @@ int64_t chain_max_cols(int format)
 {
     int strip_cols, slot_bytes, block, row_bits;
     if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return 0;
-    const int64_t by_lds = (int64_t)((CHAIN_LDS_BYTES - 64) / slot_bytes) * strip_cols;
+    const int64_t by_lds = (int64_t)((CHAIN_LDS_BYTES - 64 - 1024) / slot_bytes) * strip_cols;
     return by_lds < CHAIN_MAX_COLS ? by_lds : CHAIN_MAX_COLS;
 }
 
@@ -833,16 +1173,51 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
     int strip_cols, slot_bytes, block, row_bits;
     if (!chain_format(c.format, &strip_cols, &slot_bytes, &block, &row_bits)) return false;
     const int nmat = c.first[c.nphases - 1] + c.counts[c.nphases - 1];
-    out.assign(chain_plan_bytes(c.nphases, nmat), 0);
+    out.assign(chain_plan_bytes(c.nphases, nmat, c.nattn), 0);
     ChainHeader *hd = reinterpret_cast<ChainHeader *>(out.data());
     ChainPhase *phs = reinterpret_cast<ChainPhase *>(out.data() + sizeof(ChainHeader));
     ChainMatrix *mats = reinterpret_cast<ChainMatrix *>(phs + c.nphases);
     ChainPhaseOps *ops = reinterpret_cast<ChainPhaseOps *>(mats + nmat);
+    ChainAttn *attns = reinterpret_cast<ChainAttn *>(ops + c.nphases);
     bool fused = false;
     int m = 0, max_strips = 1;
     size_t word = IFLOW_CHAIN_WS_HEADER / 4;
     for (int p = 0; p < c.nphases; ++p) {
         ChainPhase &ph = phs[p];
+        if (c.kind && c.kind[p] != 0) {                        // a half of an attention: no rows; the first half owns the output's entry
+            ph.kind = c.kind[p]; ph.attn = c.attn_of[p];
+            ph.first = m; ph.count = 0; ph.x_src = -1;
+            for (int j = 0; j < CHAIN_MAX_GROUP; ++j) ph.mstart[j] = 0x7FFFFFFF;
+            ops[p].x_op = IFLOW_X_PLAIN;
+            fused = true;
+            if (c.kind[p] == 1) {
+                if (c.counts[p] != 1 || ph.attn < 0 || ph.attn >= c.nattn) return false;
+                const ChainAttnSpec &as = c.attn[ph.attn];
+                ChainAttn &at = attns[ph.attn];
+                mats[m].packed = nullptr; mats[m].y = c.y[m]; mats[m].rows = (int)c.rows[m]; mats[m].start = 0;
+                mats[m].tag_word = (int)word;
+                word += (size_t)((c.rows[m] + 4095) / 4096) * 4096;
+                at.q = as.q; at.k_new = as.k_new; at.v_new = as.v_new;
+                at.q_tag_word = as.q_src >= 0 ? mats[as.q_src].tag_word : 0;
+                at.k_tag_word = as.k_src >= 0 ? mats[as.k_src].tag_word : 0;
+                at.v_tag_word = as.v_src >= 0 ? mats[as.v_src].tag_word : 0;
+                at.k_cache = as.k_cache; at.v_cache = as.v_cache; at.out = c.y[m];
+                at.out_tag_word = mats[m].tag_word;
+                at.n_heads = as.n_heads; at.n_kv_heads = as.n_kv_heads; at.nsplit = chain_attn_splits(as.n_kv_heads, grid);
+                if (as.n_kv_heads * at.nsplit > grid) return false;
+                // the second half's LDS: a state per (range, output of the workgroup); one thread per output
+                const int per_wg = ((as.n_heads * 128 + grid - 1) / grid + 1) & ~1;
+                if (per_wg > 64 * CHAIN_WAVES || at.nsplit * per_wg * 3 > 4 * CHAIN_WAVES * 130) return false;
+                const int group = as.n_heads / as.n_kv_heads;
+                if (as.n_heads % as.n_kv_heads != 0 || (group != 1 && (group & 1))) return false;
+                at.max_seq = as.max_seq; at.pairing = as.pairing;
+                at.scale_log2e = as.scale * 1.4426950408889634f; at.log2_base = log2((double)as.base);
+                ++m;
+            } else if (c.counts[p] != 0) {
+                return false;
+            }
+            continue;
+        }
         const bool gated = c.gated && c.gated[p];
         ph.x = c.x[p]; ph.first = m; ph.count = gated ? 1 : c.counts[p];
         ops[p].x_op = c.x_op ? c.x_op[p] : IFLOW_X_PLAIN;
@@ -888,8 +1263,14 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
         if (rpw > 64 * CHAIN_STRIDE) return false;             // a wavefront parks one pair of rows per lane
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
+    // the attentions' partial states, behind all tagged vectors
+    for (int i = 0; i < c.nattn; ++i) {
+        attns[i].part_word = (int)word;
+        word += chain_attn_workspace_bytes(attns[i].n_heads, attns[i].n_kv_heads, grid) / 4;
+        if (word > 0x3FFFFFFF) return false;
+    }
     hd->magic = IFLOW_CHAIN_MAGIC; hd->nphases = c.nphases; hd->nmatrices = nmat; hd->grid = grid; hd->max_strips = max_strips;
-    hd->fused = fused ? 1 : 0; hd->format = c.format;
+    hd->fused = fused ? 1 : 0; hd->format = c.format; hd->nattn = c.nattn; hd->lds_bytes = chain_lds_bytes(c.format, max_strips);
     return true;
 }
 
@@ -901,20 +1282,18 @@ int chain_strips(int format, int64_t cols)
     return (int)((cols + strip_cols - 1) / strip_cols);
 }
 
-hipError_t launch_chain(const void *plan, void *workspace, int grid, int max_strips, bool fused, int format, hipStream_t s)
+hipError_t launch_chain(const void *plan, void *workspace, int grid, int lds_bytes, bool fused, int format, int position, hipStream_t s)
 {
     int g = 0;
     hipError_t e = chain_grid_for_device(&g);                  // (raises the kernel's LDS limit on this device if it has not been)
     if (e != hipSuccess) return e;
-    int strip_cols, slot_bytes, block, row_bits;
-    if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return hipErrorInvalidValue;
-    const size_t lds = (size_t)max_strips * slot_bytes + 64;   // (+ the wavefronts' shares of sum x^2)
-    if (g != grid || max_strips < 1 || lds > (size_t)CHAIN_LDS_BYTES) return hipErrorInvalidValue;   // planned for another device
+    if (g != grid || lds_bytes < 1 || lds_bytes > CHAIN_LDS_BYTES) return hipErrorInvalidValue;   // planned for another device
+    const size_t lds = (size_t)lds_bytes;
     bool launched = false;
 #define IFLOW_CHAIN_GO(FF, FUSED) \
     if (!launched && format == FF && fused == FUSED) { \
         hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, \
-                           static_cast<const uint8_t *>(plan), static_cast<uint32_t *>(workspace)); \
+                           static_cast<const uint8_t *>(plan), static_cast<uint32_t *>(workspace), position); \
         launched = true; \
     }
     IFLOW_CHAIN_FOR_ALL(IFLOW_CHAIN_GO)

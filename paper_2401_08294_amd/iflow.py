@@ -27,7 +27,21 @@ ATTN_STATIC_MAX_HEADS = 128
 class Chain(C.Structure):
     """iflow_chain_t: what iflow_qgemv_chain_plan fills and iflow_qgemv_chain_launch takes (plain data)."""
     _fields_ = [("plan", C.c_void_p), ("workspace", C.c_void_p), ("grid", C.c_int32), ("max_strips", C.c_int32),
-                ("magic", C.c_uint32), ("fused", C.c_uint32), ("format", C.c_int32), ("reserved", C.c_int32)]
+                ("magic", C.c_uint32), ("fused", C.c_uint32), ("format", C.c_int32), ("lds_bytes", C.c_int32),
+                ("max_seq", C.c_int64)]
+
+
+class DecodeLayer(C.Structure):
+    """iflow_decode_layer_t: the device pointers of one decoder layer."""
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm1", "norm2", "k_cache", "v_cache")]
+
+
+class DecodeStack(C.Structure):
+    """iflow_decode_stack_t."""
+    _fields_ = [("format", C.c_int), ("n_layers", C.c_int32), ("hidden", C.c_int32), ("ffn", C.c_int32), ("n_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("max_seq", C.c_int64), ("eps", C.c_float), ("rope_base", C.c_float),
+                ("rope_pairing", C.c_int32), ("layers", C.POINTER(DecodeLayer)), ("h_in", C.c_void_p), ("h_out", C.c_void_p),
+                ("scratch", C.c_void_p)]
 
 
 class IflowError(RuntimeError):
@@ -84,6 +98,9 @@ def lib():
                                                    C.POINTER(p), C.POINTER(p), p, sz, p, sz, p, C.POINTER(Chain)]
         L.iflow_qgemv_chain_launch.argtypes = [C.POINTER(Chain), p]
         L.iflow_qgemv_chain_check.argtypes = [C.POINTER(Chain), p]
+        L.iflow_decode_stack_sizes.argtypes = [C.POINTER(DecodeStack), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        L.iflow_decode_stack_plan.argtypes = [C.POINTER(DecodeStack), p, sz, p, sz, p, C.POINTER(Chain)]
+        L.iflow_decode_stack_launch.argtypes = [C.POINTER(Chain), i64, p]
         _lib = L
     return _lib
 
@@ -301,3 +318,36 @@ def qgemv_chain_launch(chain: Chain, stream=None) -> None:
 def qgemv_chain_check(chain: Chain, stream=None) -> None:
     """Synchronises the stream; raises IflowError(ERR_TIMEOUT) if a chained launch gave up a wait."""
     _check(lib().iflow_qgemv_chain_check(C.byref(chain), _stream(stream)), "iflow_qgemv_chain_check")
+
+
+def decode_stack(fmt: int, hidden: int, ffn: int, n_heads: int, n_kv_heads: int, max_seq: int, eps: float, rope_base: float,
+                 rope_pairing: int, layers=(), n_layers=None, h_in=None, h_out=None, scratch=None, head_dim: int = 128) -> DecodeStack:
+    """Fills an iflow_decode_stack_t.  `layers`: one dict per layer with the keys wq wk wv wo w_gate w_up w_down norm1 norm2
+    k_cache v_cache (tensors or addresses); for a size query give n_layers instead."""
+    n = len(layers) if n_layers is None else n_layers
+    arr = (DecodeLayer * max(len(layers), 1))()
+    for i, ly in enumerate(layers):
+        for name, _ in DecodeLayer._fields_:
+            setattr(arr[i], name, _ptr(ly[name]))
+    d = DecodeStack(fmt, n, hidden, ffn, n_heads, n_kv_heads, head_dim, max_seq, eps, rope_base, rope_pairing,
+                    C.cast(arr, C.POINTER(DecodeLayer)) if layers else None, _ptr(h_in), _ptr(h_out), _ptr(scratch))
+    d._keep = arr                                              # (the array lives as long as the description)
+    return d
+
+
+def decode_stack_sizes(stack: DecodeStack):
+    """(scratch_bytes, plan_bytes, workspace_bytes) of a description (its pointers are not read)."""
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(lib().iflow_decode_stack_sizes(C.byref(stack), C.byref(a), C.byref(b), C.byref(c)), "iflow_decode_stack_sizes")
+    return int(a.value), int(b.value), int(c.value)
+
+
+def decode_stack_plan(stack: DecodeStack, plan, plan_bytes: int, workspace, workspace_bytes: int, stream=None) -> Chain:
+    chain = Chain()
+    _check(lib().iflow_decode_stack_plan(C.byref(stack), _ptr(plan), plan_bytes, _ptr(workspace), workspace_bytes, _stream(stream),
+                                         C.byref(chain)), "iflow_decode_stack_plan")
+    return chain
+
+
+def decode_stack_launch(chain: Chain, position: int, stream=None) -> None:
+    _check(lib().iflow_decode_stack_launch(C.byref(chain), position, _stream(stream)), "iflow_decode_stack_launch")

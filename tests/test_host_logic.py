@@ -330,6 +330,54 @@ def test_rope_validation_happens_before_any_launch(iflow):
     assert call(k=base * 2 + 2) == iflow.ERR_ALIGN
 
 
+def test_decode_stack_validation_happens_before_any_launch(iflow):
+    """iflow_decode_stack_*: the description is checked on the host, in the size query, in the plan call and at the launch."""
+    L = iflow.lib()
+    base = 0x100000
+    fmt = iflow.FORMATS["Q3H_B64"]
+
+    def desc(**change):
+        args = dict(fmt=fmt, hidden=512, ffn=704, n_heads=4, n_kv_heads=2, max_seq=16, eps=1e-5, rope_base=10000.0, rope_pairing=1)
+        layer = {n: base * (i + 8) for i, (n, _) in enumerate(iflow.DecodeLayer._fields_)}
+        layer.update(change.pop("layer", {}))
+        ptrs = dict(h_in=base, h_out=base * 2, scratch=base * 3)
+        ptrs.update({k: change.pop(k) for k in list(change) if k in ptrs})
+        args.update(change)
+        return iflow.decode_stack(layers=[layer], **args, **ptrs)
+
+    def sizes(**change):
+        a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+        return L.iflow_decode_stack_sizes(C.byref(desc(**change)), C.byref(a), C.byref(b), C.byref(c))
+
+    def plan(plan_ptr=base * 40, ws=base * 50, **change):
+        return L.iflow_decode_stack_plan(C.byref(desc(**change)), plan_ptr, 1 << 30, ws, 1 << 30, None, C.byref(iflow.Chain()))
+
+    assert sizes(fmt=iflow.FORMATS["Q5_B64"]) == iflow.ERR_FORMAT and sizes(fmt=99) == iflow.ERR_FORMAT
+    assert sizes(head_dim=64) == iflow.ERR_SHAPE                                 # head dimension 128 only
+    assert sizes(n_heads=6, n_kv_heads=2, hidden=768) == iflow.ERR_SHAPE         # 1 or an even number of query heads per kv head
+    assert sizes(n_heads=4, n_kv_heads=3) == iflow.ERR_SHAPE
+    assert sizes(hidden=640) == iflow.ERR_SHAPE                                  # hidden = n_heads * 128
+    assert sizes(ffn=100) == iflow.ERR_SHAPE and sizes(ffn=0) == iflow.ERR_SHAPE and sizes(ffn=131072) == iflow.ERR_SHAPE
+    assert sizes(max_seq=0) == iflow.ERR_SHAPE and sizes(max_seq=(1 << 20) + 1) == iflow.ERR_SHAPE
+    assert sizes(rope_pairing=2) == iflow.ERR_SHAPE and sizes(rope_base=1.0) == iflow.ERR_SHAPE and sizes(eps=-1.0) == iflow.ERR_SHAPE
+    assert L.iflow_decode_stack_sizes(None, None, None, None) == iflow.ERR_NULL
+    d = desc()
+    d.n_layers = 129
+    assert L.iflow_decode_stack_sizes(C.byref(d), C.byref(C.c_size_t()), C.byref(C.c_size_t()), C.byref(C.c_size_t())) == iflow.ERR_SHAPE
+    assert plan(h_in=None) == iflow.ERR_NULL and plan(scratch=None) == iflow.ERR_NULL and plan(plan_ptr=None) == iflow.ERR_NULL
+    assert plan(layer={"wo": None}) == iflow.ERR_NULL and plan(layer={"v_cache": None}) == iflow.ERR_NULL
+    assert plan(h_out=base * 2 + 8) == iflow.ERR_ALIGN and plan(layer={"norm2": base * 16 + 2}) == iflow.ERR_ALIGN
+    assert plan(h_out=base + 512) == iflow.ERR_SHAPE                             # h_out inside h_in
+    assert plan(h_in=base * 3 + 4096) == iflow.ERR_SHAPE                         # h_in inside the scratch buffer
+    chain = iflow.Chain(plan=base, workspace=base * 2, grid=256, max_strips=1, magic=0x69464C57, fused=1, format=fmt, lds_bytes=32768, max_seq=16)
+    assert L.iflow_decode_stack_launch(None, 0, None) == iflow.ERR_NULL
+    chain.magic = 0
+    assert L.iflow_decode_stack_launch(C.byref(chain), 0, None) == iflow.ERR_SHAPE
+    chain2 = iflow.Chain(plan=base, workspace=base * 2, grid=256, max_strips=1, magic=0x69464C57, fused=1, format=fmt, lds_bytes=32768, max_seq=16)
+    for position in (-1, 16, 1 << 40):
+        assert L.iflow_decode_stack_launch(C.byref(chain2), position, None) == iflow.ERR_SHAPE
+
+
 def test_public_header_is_plain_c_and_cpp(tmp_path):
     """include/iflow.h is the boundary: it has to compile on its own as C99 and as C++11 (no HIP, no torch types)."""
     import shutil
