@@ -576,6 +576,36 @@ def main():
                             "silu(gate)*up | down + residual; q's output stands in for the attention's), eager launches",
                     "us_per_layer": round(us_layer_f, 2), "weight_GB/s": round(step_bytes / us_layer_f / 1e3, 1),
                     "frac_of_hbm_peak": round(step_bytes / us_layer_f / 1e3 / HBM_PEAK_GBPS, 4)}
+                # the whole decode step, attention included, in ONE launch (iflow_decode_stack_plan)
+                names = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+                stack_layers = []
+                for layer in range(args.ring):
+                    ly = {n: ring[layer][i][2] for i, n in enumerate(names)}
+                    ly.update(norm1=gn[0], norm2=gn[1], k_cache=kvs[layer][0], v_cache=kvs[layer][1])
+                    stack_layers.append(ly)
+                h_out_s = torch.empty_like(hs)
+                stack_args = (fmt, hid, ffn_rows, 32, 32, ctx, 1e-5, 10000.0, iflow.ROPE_HALVES)
+                sb, plb, wsb = iflow.decode_stack_sizes(iflow.decode_stack(*stack_args, n_layers=args.ring))
+                scr = torch.empty((sb // 2,), dtype=torch.float16, device=dev)
+                plt_s = torch.empty(plb, dtype=torch.uint8, device=dev)
+                wst_s = torch.empty(wsb, dtype=torch.uint8, device=dev)
+                stack = iflow.decode_stack_plan(iflow.decode_stack(*stack_args, layers=stack_layers, h_in=hsA, h_out=h_out_s, scratch=scr),
+                                                plt_s, plb, wst_s, wsb, stream=raw)
+                for _ in range(2):
+                    iflow.decode_stack_launch(stack, ctx - 1, stream=raw)
+                t0.record(stream)
+                for _ in range(10):
+                    iflow.decode_stack_launch(stack, ctx - 1, stream=raw)
+                t1.record(stream)
+                t1.synchronize()
+                iflow.qgemv_chain_check(stack, stream=raw)
+                us_layer_s = t0.elapsed_time(t1) * 1e3 / (10 * args.ring)
+                other["decode_step_in_one_launch"] = {
+                    "what": f"{args.ring} decoder layers of the decode step in ONE launch, attention included (rms-norm + q,k,v | rotary "
+                            "embedding + cache append + attention over 1024 cached positions, 32 heads, as two phases | o + residual | "
+                            "rms-norm + silu(gate)*up | down + residual), eager launches",
+                    "us_per_layer": round(us_layer_s, 2), "weight_GB/s": round(step_bytes / us_layer_s / 1e3, 1),
+                    "tokens_per_s_32_layers": round(1e6 / (32 * us_layer_s), 1)}
                 del kvs
             # the other block formats of Table 3 (and the 2-bit one) on the same matrix shape, 1 to 16 activation vectors:
             # copies of one packed matrix at 16 distinct addresses
@@ -780,7 +810,7 @@ def main():
     if args.launches == 1:
         for chain, _, _, _ in chains.values():
             iflow.qgemv_chain_check(chain, stream=raw)         # raises if a wait inside a launch ever gave up
-        out["roofline"]["kernel"] = f"iflow::chain_kernel<2, false, {fmt}>"
+        out["roofline"]["kernel"] = f"iflow::chain_kernel<2, false, {fmt}, false>"
         out["config"]["chain_plans"] = {f"{k[1]} layers from ring position {k[0]}": {"plan_MB": round(v[1].numel() / 1e6, 1),
                                                                                       "plan_call_s": round(v[3], 2)} for k, v in chains.items()}
     if not args.no_cpu_baseline:

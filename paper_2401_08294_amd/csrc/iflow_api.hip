@@ -507,7 +507,7 @@ iflow_status_t iflow_qgemv_chain_launch(const iflow_chain_t *chain, void *stream
 {
     if (!chain || !chain->plan || !chain->workspace) return IFLOW_ERR_NULL;
     if (chain->magic != IFLOW_CHAIN_MAGIC || chain->max_seq != 0) return IFLOW_ERR_SHAPE;   // (a decoder stack's plan needs a position)
-    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->lds_bytes, chain->fused != 0, (int)chain->format, 0,
+    hipError_t e = iflow::launch_chain(chain->plan, chain->workspace, chain->grid, chain->lds_bytes, chain->fused != 0, (int)chain->format, -1,
                                        (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return IFLOW_ERR_SHAPE;     // planned for a device with another number of compute units
     return device_status(e);

@@ -92,12 +92,15 @@ struct ChainPhaseOps {
     float eps;
     int x_op;                   // iflow_x_op_t
     float inv_cols;
-    int pad_[3];
+    int next_attn;              // the first phase of kind 1 behind this one (nphases: none)
+    int pad_[2];
 };
 struct ChainHeader {
     uint32_t magic;
     int nphases, nmatrices, grid;
-    int max_strips, fused, format, nattn, lds_bytes, pad_[7];
+    int max_strips, fused, format, nattn, lds_bytes;
+    int first_attn;             // the first phase of kind 1 (nphases: none)
+    int pad_[6];
 };
 // One decode step of grouped-query attention inside the launch (section "Grouped-query attention"; Section 5's Infer() runs
 // it between the q/k/v products and the output projection), head dimension 128, with the rotary position embedding of the
@@ -172,6 +175,13 @@ struct ChainWalk {
 #ifndef IFLOW_CHAIN_EARLY
 #define IFLOW_CHAIN_EARLY 0
 #endif
+// 1: the requests for weights stop in front of an attention's phases and start again behind them (nothing of the step loop is
+// live in registers during the attention, but the first weights of the output projection are requested in one burst that
+// the projection's activations then queue behind); 0: they run on through the attention.  Measured on a 7B decode step with
+// 1024 cached positions: 40.6 against 39.6 us per layer.
+#ifndef IFLOW_CHAIN_ATTN_STALL
+#define IFLOW_CHAIN_ATTN_STALL 0
+#endif
 constexpr int CHAIN_SETS = IFLOW_CHAIN_SETS;
 #ifndef IFLOW_CHAIN_SETS_OTHER
 #define IFLOW_CHAIN_SETS_OTHER 4
@@ -210,24 +220,30 @@ __device__ __forceinline__ void park(float &keep0, float &keep1, int value0, int
 // ---- decode attention inside the launch ------------------------------------------------------------------------------------
 typedef uint32_t attn_u32x4 __attribute__((ext_vector_type(4)));
 
-// eight fp16 values (four pairs, components c0 .. c0 + 7 of vector element `base`) of a vector that is either an input of the
-// launch (plain) or the tagged output of an earlier product; a tagged read repeats until all eight carry the launch's tag
-__device__ __forceinline__ attn_u32x4 chain_read8(const uint16_t *plain, const uint32_t *ws, int tag_word, int element, uint32_t tag, bool &failed)
+// Two pairs of fp16 values (elements `element`, `element` + 1 and `partner`, `partner` + 1, both even) of a vector that is
+// either an input of the launch (plain) or the tagged output of an earlier product; a tagged read repeats until all four
+// carry the launch's tag (both pairs in the same pass: one memory latency).
+__device__ __forceinline__ void chain_read_pairs(const uint16_t *plain, const uint32_t *ws, int tag_word, int element, int partner, uint32_t tag,
+                                                 bool &failed, uint32_t &own, uint32_t &other)
 {
-    if (plain != nullptr) return *global_ptr<const attn_u32x4>(plain + element);
+    if (plain != nullptr) {
+        own = *global_ptr<const uint32_t>(plain + element);
+        other = *global_ptr<const uint32_t>(plain + partner);
+        return;
+    }
+    // pair g of the vector sits at 8-byte word (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255)
     const uint64_t *base = reinterpret_cast<const uint64_t *>(ws + tag_word);
-    uint32_t v[4];
+    const int g0 = element >> 1, g1 = partner >> 1;
+    const uint64_t *src0 = base + (g0 >> 11) * 2048 + (g0 & 7) * 256 + ((g0 >> 3) & 255);
+    const uint64_t *src1 = base + (g1 >> 11) * 2048 + (g1 & 7) * 256 + ((g1 >> 3) & 255);
     int budget = failed ? 1 : CHAIN_POLL_BUDGET;
     for (;;) {
-        bool ok = true;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int g = (element >> 1) + i;               // pair g of the vector: 8-byte word (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255)
-            const uint64_t wd = __hip_atomic_load(base + (g >> 11) * 2048 + (g & 7) * 256 + ((g >> 3) & 255), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const uint32_t lo = (uint32_t)wd, hi = (uint32_t)(wd >> 32);
-            ok = ok && ((lo ^ tag) >> 16) == 0 && ((hi ^ tag) >> 16) == 0;
-            v[i] = (lo & 0xFFFFu) | (hi << 16);
-        }
+        const uint64_t w0 = __hip_atomic_load(src0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t w1 = __hip_atomic_load(src1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t lo0 = (uint32_t)w0, hi0 = (uint32_t)(w0 >> 32), lo1 = (uint32_t)w1, hi1 = (uint32_t)(w1 >> 32);
+        own = (lo0 & 0xFFFFu) | (hi0 << 16);
+        other = (lo1 & 0xFFFFu) | (hi1 << 16);
+        const bool ok = (((lo0 ^ tag) | (hi0 ^ tag) | (lo1 ^ tag) | (hi1 ^ tag)) >> 16) == 0;
         if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
         if (--budget <= 0) {
             failed = true;
@@ -236,45 +252,39 @@ __device__ __forceinline__ attn_u32x4 chain_read8(const uint16_t *plain, const u
         }
         __builtin_amdgcn_s_sleep(2);
     }
-    return (attn_u32x4){v[0], v[1], v[2], v[3]};
 }
 
-// Rotary embedding of the lane's eight components c0 .. c0 + 7 of a 128-component head (`own`), given the components the
-// pairing joins them with (`other`: c0 +- 64 .. for the pairing by halves; unused for adjacent pairs).  table[i] = (cos, sin)
-// of pair i's angle at this step's position.  fp64 arithmetic, one rounding to fp16: the values iflow_rope_append writes.
-__device__ __forceinline__ attn_u32x4 chain_rope8(attn_u32x4 own, attn_u32x4 other, int c0, int pairing, const double2 *table)
+// Rotary embedding of components c, c + 1 (c even) of a 128-component head (`own`), given the components the pairing joins
+// them with (`other`: c +- 64, c +- 64 + 1 for the pairing by halves; unused for adjacent pairs).  table[i] = (cos, sin) of
+// pair i's angle at this step's position.  fp64 arithmetic, one rounding to fp16: the values iflow_rope_append writes.
+__device__ __forceinline__ uint32_t chain_rope_pair(uint32_t own, uint32_t other, int c, int pairing, const double2 *table)
 {
-    const uint32_t o[4] = {own.x, own.y, own.z, own.w}, p[4] = {other.x, other.y, other.z, other.w};
-    uint32_t r[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const half2_t a = as_h2(o[i]), b = as_h2(p[i]);
-        const double ax = (double)(float)a.x, ay = (double)(float)a.y, bx = (double)(float)b.x, by = (double)(float)b.y;
-        double lo, hi;
-        if (pairing == IFLOW_ROPE_HALVES) {                 // component c pairs with c + 64; the pair's index is c mod 64
-            const double2 t0 = table[(c0 + 2 * i) & 63], t1 = table[(c0 + 2 * i + 1) & 63];
-            if (c0 < 64) { lo = ax * t0.x - bx * t0.y; hi = ay * t1.x - by * t1.y; }       // (a, b) = (own, partner): first of the pair
-            else         { lo = bx * t0.y + ax * t0.x; hi = by * t1.y + ay * t1.x; }       // second of the pair: partner sin + own cos
-        } else {                                            // components (2i, 2i+1) are a pair
-            const double2 t = table[(c0 >> 1) + i];
-            lo = ax * t.x - ay * t.y;
-            hi = ax * t.y + ay * t.x;
-        }
-        const half2_t rv = {(half_t)lo, (half_t)hi};
-        r[i] = as_u32(rv);
+    const half2_t a = as_h2(own), b = as_h2(other);
+    const double ax = (double)(float)a.x, ay = (double)(float)a.y, bx = (double)(float)b.x, by = (double)(float)b.y;
+    double lo, hi;
+    if (pairing == IFLOW_ROPE_HALVES) {                     // component c pairs with c + 64; the pair's index is c mod 64
+        const double2 t0 = table[c & 63], t1 = table[(c + 1) & 63];
+        if (c < 64) { lo = ax * t0.x - bx * t0.y; hi = ay * t1.x - by * t1.y; }       // (a, b) = (own, partner): first of the pair
+        else        { lo = bx * t0.y + ax * t0.x; hi = by * t1.y + ay * t1.x; }       // second of the pair: partner sin + own cos
+    } else {                                                // components (c, c + 1) are a pair
+        const double2 t = table[c >> 1];
+        lo = ax * t.x - ay * t.y;
+        hi = ax * t.y + ay * t.x;
     }
-    return (attn_u32x4){r[0], r[1], r[2], r[3]};
+    const half2_t rv = {(half_t)lo, (half_t)hi};
+    return as_u32(rv);
 }
 
 // Phase "part" for R of the query heads of a key/value head's group, heads r0 .. r0 + R - 1 of the group (a group larger than
-// two heads takes several passes over its range: the registers of the step loop stay live through this phase, which leaves
-// room for two heads' running states).  lds: at least (4 * CHAIN_WAVES) * 130 floats.
+// two heads takes several passes over its range).  lds: (4 * CHAIN_WAVES) * 130 floats for the running states, and behind
+// them CHAIN_ATTN_STAGE_BYTES for the step's rotated queries, rotated key and value.
+constexpr int CHAIN_ATTN_STATE_BYTES = 4 * CHAIN_WAVES * 130 * 4, CHAIN_ATTN_STAGE_BYTES = 64 * 16;
 template <int R>
 __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *ws, float *lds, const double2 *table, uint32_t tag, int position,
-                                                int wg, int wave, int lane, int r0, bool &failed)
+                                                int wg, int wave, int lane, int r0, bool &failed, uint32_t *marks = nullptr)
 {
     const int group = at.n_heads / at.n_kv_heads;
-    constexpr int NST = 4 * CHAIN_WAVES;                       // running softmax states of a workgroup: four lane groups per wavefront
+    constexpr int NST = 4 * CHAIN_WAVES;                       // (the LDS area holds up to this many states of 128 sums; R per wavefront are used)
     const int nsplit = at.nsplit;
     if (wg >= at.n_kv_heads * nsplit) return;                  // (uniform over the workgroup)
     const int j = wg / nsplit, sp = wg - j * nsplit;
@@ -283,34 +293,69 @@ __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *w
     const int t_begin = sp * chunk, t_end = min(seq_len, t_begin + chunk);     // may be empty
     const bool has_new = t_begin <= position && position < t_end;             // this range holds the step's own position
     const int gq = lane >> 4, dseg = lane & 15, c0 = dseg * 8;
-    const int partner = at.pairing == IFLOW_ROPE_HALVES ? (c0 ^ 64) : c0;
     float *s_acc = lds, *s_m = lds + NST * 128, *s_l = s_m + NST;
+    attn_u32x4 *const stage = reinterpret_cast<attn_u32x4 *>(reinterpret_cast<uint8_t *>(lds) + CHAIN_ATTN_STATE_BYTES);
 
-    // the group's queries, rotated
+    // The wavefront's first block of cached keys and values is requested before anything of this step is waited for: rows
+    // below the step's position do not depend on the step.  (Blocks of sixteen positions, wavefront w takes blocks w,
+    // w + CHAIN_WAVES, ...; four positions per load instruction, one per lane group; positions past the range read its last
+    // position (in bounds) and are masked; the step's own position comes from registers: its cache row is being written.)
+    const uint8_t *kh = reinterpret_cast<const uint8_t *>(at.k_cache) + (int64_t)j * at.max_seq * 256;     // (uniform; rows of 256 bytes)
+    const uint8_t *vh = reinterpret_cast<const uint8_t *>(at.v_cache) + (int64_t)j * at.max_seq * 256;
+    constexpr int STEP = 16 * CHAIN_WAVES;
+    attn_u32x4 kt[4], vt[4];
+    auto load_block = [&](int p0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int pos = min(p0 + t * 4 + gq, t_end - 1);
+            const int row = min(pos, has_new && pos == position ? max(position - 1, 0) : pos);   // never the row being written
+            const uint32_t off = (uint32_t)row * 256u + (uint32_t)c0 * 2u;                      // (max_seq <= 2^20: below 2^28)
+            kt[t] = __builtin_nontemporal_load(global_ptr<const attn_u32x4>(kh + off));
+            vt[t] = __builtin_nontemporal_load(global_ptr<const attn_u32x4>(vh + off));
+        }
+    };
+    const int p_first = t_begin + wave * 16;
+    if (p_first < t_end) load_block(p_first);
+
+    // The step's vectors, one pair of components per thread: thread u < 64 R has a pair of the group's queries (rotated), the
+    // next 64 threads the key of this head (rotated), the last 64 its value; they go to LDS for everybody, and the key and
+    // value also into the caches (by the workgroup whose range holds the step's position, on its first pass).
+    {
+        const int u = wave * 64 + lane, nq = 64 * R;
+        if (u < nq + (has_new ? 128 : 0)) {
+            const bool is_q = u < nq, is_v = u >= nq + 64;
+            const int c = (u & 63) * 2;                        // the pair's first component
+            const uint16_t *plain = is_q ? at.q : (is_v ? at.v_new : at.k_new);
+            const int tag_word = is_q ? at.q_tag_word : (is_v ? at.v_tag_word : at.k_tag_word);
+            const int e = is_q ? (j * group + r0 + (u >> 6)) * 128 : j * 128;     // the head's first element
+            uint32_t val, oth;                                 // (the partner of the pairing by halves; else the pair itself again)
+            chain_read_pairs(plain, ws, tag_word, e + c, e + (at.pairing == IFLOW_ROPE_HALVES && !is_v ? (c ^ 64) : c), tag, failed, val, oth);
+#if IFLOW_CHAIN_TRACE
+            if (marks && u == 0) marks[5] = (uint32_t)__builtin_amdgcn_s_memrealtime();     // wavefront 0 has read its pairs
+#endif
+            if (!is_v) val = chain_rope_pair(val, oth, c, at.pairing, table);
+#if IFLOW_CHAIN_TRACE
+            if (marks && u == 0) marks[6] = (uint32_t)__builtin_amdgcn_s_memrealtime();     // ... and rotated them
+#endif
+            reinterpret_cast<uint32_t *>(stage)[u] = val;
+            if (!is_q && r0 == 0) {
+                uint16_t *cache = is_v ? at.v_cache : at.k_cache;
+                *global_ptr<uint32_t>(cache + ((int64_t)j * at.max_seq + position) * 128 + c) = val;
+            }
+        }
+    }
+    __syncthreads();
+#if IFLOW_CHAIN_TRACE
+    if (marks && wave == 0 && lane == 0) marks[1] = (uint32_t)__builtin_amdgcn_s_memrealtime();   // the step's vectors are staged
+#endif
     half2_t qr[R][4];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int e = (j * group + r0 + r) * 128;
-        const attn_u32x4 own = chain_read8(at.q, ws, at.q_tag_word, e + c0, tag, failed);
-        const attn_u32x4 oth = at.pairing == IFLOW_ROPE_HALVES ? chain_read8(at.q, ws, at.q_tag_word, e + partner, tag, failed) : own;
-        const attn_u32x4 rot = chain_rope8(own, oth, c0, at.pairing, table);
+        const attn_u32x4 rot = stage[r * 16 + dseg];
         qr[r][0] = as_h2(rot.x); qr[r][1] = as_h2(rot.y); qr[r][2] = as_h2(rot.z); qr[r][3] = as_h2(rot.w);
     }
-    // the step's key (rotated) and value, where this range needs them; one wavefront also appends them to the caches
     attn_u32x4 k_now = {0u, 0u, 0u, 0u}, v_now = {0u, 0u, 0u, 0u};
-    if (has_new) {
-        const attn_u32x4 own = chain_read8(at.k_new, ws, at.k_tag_word, j * 128 + c0, tag, failed);
-        const attn_u32x4 oth = at.pairing == IFLOW_ROPE_HALVES ? chain_read8(at.k_new, ws, at.k_tag_word, j * 128 + partner, tag, failed) : own;
-        k_now = chain_rope8(own, oth, c0, at.pairing, table);
-        v_now = chain_read8(at.v_new, ws, at.v_tag_word, j * 128 + c0, tag, failed);
-        if (wave == 0 && gq == 0 && r0 == 0) {
-            const int64_t row = ((int64_t)j * at.max_seq + position) * 128 + c0;
-            *global_ptr<attn_u32x4>(at.k_cache + row) = k_now;
-            *global_ptr<attn_u32x4>(at.v_cache + row) = v_now;
-        }
-    }
-    const uint16_t *kh = at.k_cache + (int64_t)j * at.max_seq * 128 + c0;
-    const uint16_t *vh = at.v_cache + (int64_t)j * at.max_seq * 128 + c0;
+    if (has_new) { k_now = stage[16 * R + dseg]; v_now = stage[16 * R + 16 + dseg]; }
 
     float m[R], l[R], acc[R][8];
 #pragma unroll
@@ -319,19 +364,13 @@ __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *w
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
     }
-    // blocks of sixteen positions, wavefront w takes blocks w, w + CHAIN_WAVES, ...; four positions per load instruction, one
-    // per lane group; positions past the range read its last position (in bounds) and are masked; the step's own position
-    // comes from registers (its cache row is being written)
-    constexpr int STEP = 16 * CHAIN_WAVES;
-    for (int p0 = t_begin + wave * 16; p0 < t_end; p0 += STEP) {
-        attn_u32x4 kt[4], vt[4];
+    for (int p0 = p_first; p0 < t_end; p0 += STEP) {
+        if (p0 != p_first) load_block(p0);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int pos = min(p0 + t * 4 + gq, t_end - 1);
-            const int64_t off = (int64_t)min(pos, has_new && pos == position ? max(position - 1, 0) : pos) * 128;   // never the row being written
-            kt[t] = __builtin_nontemporal_load(global_ptr<const attn_u32x4>(kh + off));
-            vt[t] = __builtin_nontemporal_load(global_ptr<const attn_u32x4>(vh + off));
-            if (pos == position) { kt[t] = k_now; vt[t] = v_now; }
+        for (int t = 0; t < 4; ++t) {                          // (selects, not stores under a branch: those put the arrays into scratch memory)
+            const bool now = min(p0 + t * 4 + gq, t_end - 1) == position;
+            kt[t].x = now ? k_now.x : kt[t].x; kt[t].y = now ? k_now.y : kt[t].y; kt[t].z = now ? k_now.z : kt[t].z; kt[t].w = now ? k_now.w : kt[t].w;
+            vt[t].x = now ? v_now.x : vt[t].x; vt[t].y = now ? v_now.y : vt[t].y; vt[t].z = now ? v_now.z : vt[t].z; vt[t].w = now ? v_now.w : vt[t].w;
         }
         // scores of the four positions for every head, the running maxima brought up to date; then the values, one position
         // at a time (converted once for all heads)
@@ -370,34 +409,59 @@ __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *w
             }
         }
     }
-    // the workgroup's states of each head -> one partial state in the workspace (64-bit words: fp32 bits, launch tag)
-    const int pid = wave * 4 + gq, tid = wave * 64 + lane;
-    uint64_t *part = reinterpret_cast<uint64_t *>(ws + at.part_word);
+#if IFLOW_CHAIN_TRACE
+    if (marks && wave == 0 && lane == 0) marks[2] = (uint32_t)__builtin_amdgcn_s_memrealtime();   // wavefront 0's positions are done
+#endif
+    // The four lane groups of a wavefront hold states of different positions for the same components: merged across lanes
+    // first (lanes 16 and 32 apart; both lanes of a pair compute the same), so that a wavefront leaves one state per head.
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        if (r > 0) __syncthreads();
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s_acc[pid * 128 + c0 + e] = acc[r][e];
-        if (dseg == 0) { s_m[pid] = m[r]; s_l[pid] = l[r]; }
-        __syncthreads();
-        if (tid < 128) {
-            float M = s_m[0];
-            for (int i = 1; i < NST; ++i) M = fmaxf(M, s_m[i]);
-            float L = 0.f, O = 0.f;
-            if (M != -INFINITY) {                              // (an empty range leaves maximum -inf, sums zero)
-                for (int i = 0; i < NST; ++i) {
-                    const float f = __builtin_amdgcn_exp2f(s_m[i] - M);
-                    L = __builtin_fmaf(s_l[i], f, L);
-                    O = __builtin_fmaf(s_acc[i * 128 + tid], f, O);
-                }
+        for (int d = 16; d <= 32; d *= 2) {
+            const float m2 = __shfl_xor(m[r], d), l2 = __shfl_xor(l[r], d);
+            const float mx = fmaxf(m[r], m2);
+            const bool none = mx == -INFINITY;                 // (neither has seen a position: sums are zero)
+            const float f1 = none ? 1.0f : __builtin_amdgcn_exp2f(m[r] - mx), f2 = none ? 1.0f : __builtin_amdgcn_exp2f(m2 - mx);
+            l[r] = l[r] * f1 + l2 * f2;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] = acc[r][e] * f1 + __shfl_xor(acc[r][e], d) * f2;
+            m[r] = mx;
+        }
+    }
+    // the wavefronts' states of each head -> one partial state in the workspace (64-bit words: fp32 bits, launch tag);
+    // threads 128 r .. 128 r + 127 merge head r
+    const int tid = wave * 64 + lane;
+    uint64_t *part = reinterpret_cast<uint64_t *>(ws + at.part_word);
+    if (gq == 0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_acc[(r * CHAIN_WAVES + wave) * 128 + c0 + e] = acc[r][e];
+            if (dseg == 0) { s_m[r * CHAIN_WAVES + wave] = m[r]; s_l[r * CHAIN_WAVES + wave] = l[r]; }
+        }
+    }
+    __syncthreads();
+    if (tid < 128 * R) {
+        const int r = tid >> 7, c = tid & 127;
+        const float *sm = s_m + r * CHAIN_WAVES, *sl = s_l + r * CHAIN_WAVES, *sa = s_acc + r * CHAIN_WAVES * 128 + c;
+        float M = sm[0];
+#pragma unroll
+        for (int i = 1; i < CHAIN_WAVES; ++i) M = fmaxf(M, sm[i]);
+        float L = 0.f, O = 0.f;
+        if (M != -INFINITY) {                                  // (an empty range leaves maximum -inf, sums zero)
+#pragma unroll
+            for (int i = 0; i < CHAIN_WAVES; ++i) {
+                const float f = __builtin_amdgcn_exp2f(sm[i] - M);
+                L = __builtin_fmaf(sl[i], f, L);
+                O = __builtin_fmaf(sa[i * 128], f, O);
             }
-            uint64_t *dst = part + ((int64_t)(j * group + r0 + r) * nsplit + sp) * 130;
-            const uint64_t hi = (uint64_t)tag << 32;
-            __hip_atomic_store(dst + tid, hi | __builtin_bit_cast(uint32_t, O), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (tid == 0) {
-                __hip_atomic_store(dst + 128, hi | __builtin_bit_cast(uint32_t, M), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(dst + 129, hi | __builtin_bit_cast(uint32_t, L), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+        }
+        uint64_t *dst = part + ((int64_t)(j * group + r0 + r) * nsplit + sp) * 130;
+        const uint64_t hi = (uint64_t)tag << 32;
+        __hip_atomic_store(dst + c, hi | __builtin_bit_cast(uint32_t, O), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (c == 0) {
+            __hip_atomic_store(dst + 128, hi | __builtin_bit_cast(uint32_t, M), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 129, hi | __builtin_bit_cast(uint32_t, L), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __syncthreads();                                           // the states in LDS are no longer needed
@@ -463,7 +527,9 @@ __device__ __forceinline__ void chain_attn_merge(const ChainAttn &at, uint32_t *
     __syncthreads();                                           // the states in LDS are no longer needed
 }
 
-template <int S, bool FUSED, int F>
+// ATTN: the fused variant that also knows the two attention phases (a launch without them runs the code without them: the
+// attention's registers would otherwise cost every fused launch spills around those phases).
+template <int S, bool FUSED, int F, bool ATTN>
 __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws, int position)
 {
     constexpr bool EARLY = IFLOW_CHAIN_EARLY != 0;
@@ -520,7 +586,11 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // The two loads of a step are issued unconditionally: an empty step is a segment of its own whose lanes all read
     // the first 16 bytes of the workspace.  With the same number of loads on every path the compiler can tell exactly
     // how many younger loads may still be in flight when a register set is decoded, instead of waiting for all.
+    // (With attention in the plan the requests stop in front of an attention's phases and start again when its first half is
+    // done: nothing of the step loop is then live in registers while that half runs, which needs them all.)
     ChainWalk q = {-1, 0, 0, 0};
+    int q_limit = nphases;                                     // phases from here on are not requested yet
+    if constexpr (ATTN && IFLOW_CHAIN_ATTN_STALL) q_limit = hd->first_attn;
     const uint8_t *q_wptr = reinterpret_cast<const uint8_t *>(ws);     // weights of the step under the cursor
     int q_lt = 0, q_last = 0;                                  // its strip; the last strip of a row
     int q_nlast16 = 0;                                         // 16 x the blocks in that last strip (offset of its second plane)
@@ -550,6 +620,9 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
         }
         while (!found && q.p < nphases) {
             if (q.rows_left == 0) {                            // the next phase in which this wavefront has rows
+                if constexpr (ATTN) {
+                    if (q.p + 1 >= q_limit) break;             // (empty steps until the attention has run)
+                }
                 q.p += 1;
                 if (q.p < nphases) {
                     int rbeg, n;
@@ -759,8 +832,8 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
 
 #if IFLOW_CHAIN_TRACE
     // (development aid, off in the library: per-workgroup time stamps of a launch, 16 words per workgroup and phase, written to
-    // the buffer whose address sits at byte 32 of the plan)
-    uint32_t *const trace = *reinterpret_cast<uint32_t *const *>(plan + 32);
+    // the buffer whose address sits at byte 48 of the plan)
+    uint32_t *const trace = *reinterpret_cast<uint32_t *const *>(plan + 48);
 #define CHAIN_MARK(p, k) do { if (lane == 0) trace[((size_t)wg * nphases + (p)) * 16 + (k)] = (uint32_t)__builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define CHAIN_MARK(p, k) do { } while (0)
@@ -774,7 +847,8 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // (with attention in the plan: the rotary embedding's cosines and sines at this step's position, pair i of a 128-component
     // head turning by position * base^(-2i/128), computed once per workgroup in fp64 and kept in LDS behind everything else)
     double2 *const rope_table = reinterpret_cast<double2 *>(xs + hd->lds_bytes - 1024);
-    if constexpr (FUSED) {
+    if constexpr (ATTN) {
+        static_assert(FUSED, "the attention phases belong to the fused variant");
         if (hd->nattn > 0 && wave == 0) {
             const double angle = (double)position * exp2(-(2.0 * lane / 128.0) * a.attn[0].log2_base);
             double sn, cs;
@@ -784,23 +858,39 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     }
     for (int p = 0; p < nphases; ++p) {
         const ChainPhase ph = a.ph[p];
-        if constexpr (FUSED) {
+        if constexpr (ATTN) {
             if (ph.kind != 0) {                                // a half of a decode attention: every workgroup takes part
-                const ChainAttn at = a.attn[ph.attn];
+                const ChainAttn &at = a.attn[ph.attn];          // (read where it is: a copy would live in scratch memory)
                 __syncthreads();                               // (the table; LDS of the phase before is free)
-                if (ph.kind == 1) {
-                    float *const scratch = reinterpret_cast<float *>(xs);
-                    const int group = at.n_heads / at.n_kv_heads;
-                    if (group == 1) {
-                        chain_attn_part<1>(at, ws, scratch, rope_table, tag, position, wg, wave, lane, 0, failed);
-                    } else {                                   // (even by the plan's check)
+                // (both halves in one pass of this loop: phase p + 1 is this attention's second half, by the plan's construction)
+                float *const scratch = reinterpret_cast<float *>(xs);
+                const int group = at.n_heads / at.n_kv_heads;
+#if IFLOW_CHAIN_TRACE
+                uint32_t *const marks = trace + ((size_t)wg * nphases + p) * 16;
+                if (tid == 0) marks[0] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+#else
+                uint32_t *const marks = nullptr;
+#endif
+                if (group == 1) {
+                    chain_attn_part<1>(at, ws, scratch, rope_table, tag, position, wg, wave, lane, 0, failed, marks);
+                } else {                                       // (even by the plan's check)
 #pragma unroll 1
-                        for (int r0 = 0; r0 < group; r0 += 2)
-                            chain_attn_part<2>(at, ws, scratch, rope_table, tag, position, wg, wave, lane, r0, failed);
-                    }
-                } else {
-                    chain_attn_merge(at, ws, reinterpret_cast<float *>(xs), tag, wg, (int)gridDim.x, tid, failed);
+                    for (int r0 = 0; r0 < group; r0 += 2)
+                        chain_attn_part<2>(at, ws, scratch, rope_table, tag, position, wg, wave, lane, r0, failed);
                 }
+                CHAIN_MARK(p, 3 + (wave == 0 ? 0 : 8));           // (wavefront 0: slot 3) the partial states are written
+                chain_attn_merge(at, ws, scratch, tag, wg, (int)gridDim.x, tid, failed);
+                CHAIN_MARK(p, 4 + (wave == 0 ? 0 : 8));           // the workgroup's outputs are published
+                // The requests start again, with the first steps of the next phase that has products.  (Behind the second half,
+                // not in front of it: a wavefront's loads return in order, so the second half's reads of the partial states
+                // would wait for the weights.)
+                if constexpr (IFLOW_CHAIN_ATTN_STALL != 0) {
+                    q_limit = a.ops[p].next_attn;
+                    request_segment();
+#pragma unroll
+                    for (int j = 0; j < S; ++j) request(w[j]);
+                }
+                p += 1;
                 continue;
             }
         }
@@ -1109,7 +1199,7 @@ int chain_lds_bytes(int format, int max_strips)
 {
     int strip_cols, slot_bytes, block, row_bits;
     if (!chain_format(format, &strip_cols, &slot_bytes, &block, &row_bits)) return 0;
-    const int x_region = max_strips * slot_bytes + 64, attn_region = 4 * CHAIN_WAVES * 130 * 4;
+    const int x_region = max_strips * slot_bytes + 64, attn_region = CHAIN_ATTN_STATE_BYTES + CHAIN_ATTN_STAGE_BYTES;
     return (x_region > attn_region ? x_region : attn_region) + 1024;
 }
 
@@ -1141,9 +1231,10 @@ int64_t chain_max_cols(int format)
     return by_lds < CHAIN_MAX_COLS ? by_lds : CHAIN_MAX_COLS;
 }
 
+#define IFLOW_CHAIN_FOR_FORMAT(DO, FF) DO(FF, false, false) DO(FF, true, false) DO(FF, true, true)
 #define IFLOW_CHAIN_FOR_ALL(DO) \
-    DO(IFLOW_Q3H_B64, false) DO(IFLOW_Q3H_B64, true) DO(IFLOW_Q4_B64, false) DO(IFLOW_Q4_B64, true) DO(IFLOW_Q4_B32, false) DO(IFLOW_Q4_B32, true) \
-    DO(IFLOW_Q8_B64, false) DO(IFLOW_Q8_B64, true) DO(IFLOW_Q8_B32, false) DO(IFLOW_Q8_B32, true)
+    IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q3H_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q4_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q4_B32) \
+    IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q8_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q8_B32)
 
 // Launch geometry: as many workgroups as the device has compute units (one each: 768 threads
 // and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
@@ -1154,8 +1245,8 @@ hipError_t chain_grid_for_device(int *grid)
     int cus = 0;
     hipError_t e0 = once_per_device(pd, &cus, [] {
         hipError_t e = hipSuccess;
-#define IFLOW_CHAIN_ATTR(FF, FUSED) \
-        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<chain_sets(FF), FUSED, FF>), \
+#define IFLOW_CHAIN_ATTR(FF, FUSED, ATTN) \
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<chain_sets(FF), FUSED, FF, ATTN>), \
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, CHAIN_LDS_BYTES);
         IFLOW_CHAIN_FOR_ALL(IFLOW_CHAIN_ATTR)
 #undef IFLOW_CHAIN_ATTR
@@ -1185,6 +1276,7 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
     for (int p = 0; p < c.nphases; ++p) {
         ChainPhase &ph = phs[p];
         if (c.kind && c.kind[p] != 0) {                        // a half of an attention: no rows; the first half owns the output's entry
+            if (p == 0) return false;                          // (the first phase's activations are staged ahead of everything)
             ph.kind = c.kind[p]; ph.attn = c.attn_of[p];
             ph.first = m; ph.count = 0; ph.x_src = -1;
             for (int j = 0; j < CHAIN_MAX_GROUP; ++j) ph.mstart[j] = 0x7FFFFFFF;
@@ -1192,6 +1284,8 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
             fused = true;
             if (c.kind[p] == 1) {
                 if (c.counts[p] != 1 || ph.attn < 0 || ph.attn >= c.nattn) return false;
+                // the second half follows at once (the kernel runs both in one go)
+                if (p + 1 >= c.nphases || c.kind[p + 1] != 2 || c.attn_of[p + 1] != ph.attn) return false;
                 const ChainAttnSpec &as = c.attn[ph.attn];
                 ChainAttn &at = attns[ph.attn];
                 mats[m].packed = nullptr; mats[m].y = c.y[m]; mats[m].rows = (int)c.rows[m]; mats[m].start = 0;
@@ -1213,7 +1307,7 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
                 at.max_seq = as.max_seq; at.pairing = as.pairing;
                 at.scale_log2e = as.scale * 1.4426950408889634f; at.log2_base = log2((double)as.base);
                 ++m;
-            } else if (c.counts[p] != 0) {
+            } else if (c.counts[p] != 0 || p == 0 || c.kind[p - 1] != 1) {
                 return false;
             }
             continue;
@@ -1269,6 +1363,12 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
         word += chain_attn_workspace_bytes(attns[i].n_heads, attns[i].n_kv_heads, grid) / 4;
         if (word > 0x3FFFFFFF) return false;
     }
+    int next_attn = c.nphases;
+    for (int p = c.nphases - 1; p >= 0; --p) {
+        ops[p].next_attn = next_attn;
+        if (phs[p].kind == 1) next_attn = p;
+    }
+    hd->first_attn = next_attn;
     hd->magic = IFLOW_CHAIN_MAGIC; hd->nphases = c.nphases; hd->nmatrices = nmat; hd->grid = grid; hd->max_strips = max_strips;
     hd->fused = fused ? 1 : 0; hd->format = c.format; hd->nattn = c.nattn; hd->lds_bytes = chain_lds_bytes(c.format, max_strips);
     return true;
@@ -1282,17 +1382,20 @@ int chain_strips(int format, int64_t cols)
     return (int)((cols + strip_cols - 1) / strip_cols);
 }
 
+// position: the decode step's position for a plan with attention phases, -1 for a plan without
 hipError_t launch_chain(const void *plan, void *workspace, int grid, int lds_bytes, bool fused, int format, int position, hipStream_t s)
 {
+    const bool attn = position >= 0;
+    if (attn && !fused) return hipErrorInvalidValue;
     int g = 0;
     hipError_t e = chain_grid_for_device(&g);                  // (raises the kernel's LDS limit on this device if it has not been)
     if (e != hipSuccess) return e;
     if (g != grid || lds_bytes < 1 || lds_bytes > CHAIN_LDS_BYTES) return hipErrorInvalidValue;   // planned for another device
     const size_t lds = (size_t)lds_bytes;
     bool launched = false;
-#define IFLOW_CHAIN_GO(FF, FUSED) \
-    if (!launched && format == FF && fused == FUSED) { \
-        hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, \
+#define IFLOW_CHAIN_GO(FF, FUSED, ATTN) \
+    if (!launched && format == FF && fused == FUSED && attn == ATTN) { \
+        hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF, ATTN>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, \
                            static_cast<const uint8_t *>(plan), static_cast<uint32_t *>(workspace), position); \
         launched = true; \
     }
