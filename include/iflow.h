@@ -312,7 +312,8 @@ iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint1
  * (iflow_qgemv_chain_plan_fused), the attention runs as two more phases of the same launch; every vector is rounded to fp16
  * exactly where the separate calls (iflow_qgemv_fused, iflow_rope_append, iflow_attn_decode, iflow_qgemv_gated) round it, and
  * all intermediate vectors are left in `scratch` (per layer, each rounded up to 128 elements: q [hidden], k, v
- * [n_kv_heads * 128], t [hidden], h1 [hidden], silu(gate) * up [ffn], h2 [hidden]).
+ * [n_kv_heads * 128] as the products leave them (not rotated: the rotated key goes to the cache), t [hidden], h1 [hidden],
+ * silu(gate) * up [ffn], h2 [hidden]; the last layer's h2 goes to h_out instead).
  *   format: a format of the chained launch; head_dim must be 128, hidden = n_heads * 128, n_heads a multiple of n_kv_heads
  *   with 1 or an even number of query heads per key/value head; hidden and ffn multiples of 64.
  *   layers: HOST array of n_layers entries (1 .. 128); every pointer in it a device pointer, 16-byte aligned.
