@@ -606,6 +606,20 @@ def main():
                             "rms-norm + silu(gate)*up | down + residual), eager launches",
                     "us_per_layer": round(us_layer_s, 2), "weight_GB/s": round(step_bytes / us_layer_s / 1e3, 1),
                     "tokens_per_s_32_layers": round(1e6 / (32 * us_layer_s), 1)}
+                # the same launch at other context lengths (the caches hold 1024 rows: positions below that)
+                by_ctx = {}
+                for pos in (0, 255, 511):
+                    for _ in range(2):
+                        iflow.decode_stack_launch(stack, pos, stream=raw)
+                    t0.record(stream)
+                    for _ in range(10):
+                        iflow.decode_stack_launch(stack, pos, stream=raw)
+                    t1.record(stream)
+                    t1.synchronize()
+                    by_ctx[str(pos + 1)] = round(t0.elapsed_time(t1) * 1e3 / (10 * args.ring), 2)
+                iflow.qgemv_chain_check(stack, stream=raw)
+                by_ctx[str(ctx)] = round(us_layer_s, 2)
+                other["decode_step_in_one_launch"]["us_per_layer_by_cached_positions"] = by_ctx
                 del kvs
             # the other block formats of Table 3 (and the 2-bit one) on the same matrix shape, 1 to 16 activation vectors:
             # copies of one packed matrix at 16 distinct addresses

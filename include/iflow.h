@@ -317,7 +317,8 @@ iflow_status_t iflow_rope_append(uint16_t *q, const uint16_t *k_new, const uint1
  *   format: a format of the chained launch; head_dim must be 128, hidden = n_heads * 128, n_heads a multiple of n_kv_heads
  *   with 1 or an even number of query heads per key/value head; hidden and ffn multiples of 64.
  *   layers: HOST array of n_layers entries (1 .. 128); every pointer in it a device pointer, 16-byte aligned.
- *   h_in, h_out, scratch: device; h_in is not written and must not overlap h_out or scratch.
+ *   h_in, h_out, scratch: device; h_in is not written and must not overlap h_out or scratch.  Every layer has caches of its
+ *   own; caches, gains, h_in, h_out and scratch must not overlap each other (IFLOW_ERR_SHAPE).
  * iflow_decode_stack_sizes gives the bytes of scratch, plan and workspace for a description (pointers in it are not read).
  * iflow_decode_stack_plan is iflow_qgemv_chain_plan for this chain (same rules: synchronises, allocates host memory only);
  * iflow_decode_stack_launch runs one step at 0 <= position < max_seq (IFLOW_ERR_SHAPE otherwise): one kernel launch,

@@ -610,12 +610,28 @@ iflow_status_t iflow_decode_stack_plan(const iflow_decode_stack_t *stack, void *
     const size_t scratch_bytes = (size_t)d.n_layers * (size_t)L.per_layer * 2;
     if (overlaps(d.h_in, (size_t)d.hidden * 2, d.h_out, (size_t)d.hidden * 2) || overlaps(d.h_in, (size_t)d.hidden * 2, d.scratch, scratch_bytes) ||
         overlaps(d.h_out, (size_t)d.hidden * 2, d.scratch, scratch_bytes)) return IFLOW_ERR_SHAPE;
+    // what the launch writes (scratch, h_out, the caches' rows) must not overlap anything else it reads or writes: workgroups
+    // run ahead of each other, so no order between a write and an unrelated read can be relied on
+    const int64_t cache_bytes = (int64_t)d.n_kv_heads * d.max_seq * 128 * 2;
+    auto hits_an_output = [&](const void *p, int64_t n) {
+        return overlaps(p, n, d.scratch, (int64_t)scratch_bytes) || overlaps(p, n, d.h_out, (int64_t)d.hidden * 2);
+    };
     for (int l = 0; l < d.n_layers; ++l) {
         const iflow_decode_layer_t &y = d.layers[l];
         const void *ptrs[] = {y.wq, y.wk, y.wv, y.wo, y.w_gate, y.w_up, y.w_down, y.norm1, y.norm2, y.k_cache, y.v_cache};
         for (const void *p : ptrs) {
             if (!p) return IFLOW_ERR_NULL;
             if (!aligned16(p)) return IFLOW_ERR_ALIGN;
+        }
+        if (hits_an_output(y.norm1, (int64_t)d.hidden * 2) || hits_an_output(y.norm2, (int64_t)d.hidden * 2) ||
+            hits_an_output(y.k_cache, cache_bytes) || hits_an_output(y.v_cache, cache_bytes) ||
+            overlaps(y.k_cache, cache_bytes, y.v_cache, cache_bytes) || overlaps(y.k_cache, cache_bytes, d.h_in, (int64_t)d.hidden * 2) ||
+            overlaps(y.v_cache, cache_bytes, d.h_in, (int64_t)d.hidden * 2)) return IFLOW_ERR_SHAPE;
+        for (int m = 0; m < l; ++m) {                          // every layer has caches of its own
+            const iflow_decode_layer_t &z = d.layers[m];
+            if (overlaps(y.k_cache, cache_bytes, z.k_cache, cache_bytes) || overlaps(y.k_cache, cache_bytes, z.v_cache, cache_bytes) ||
+                overlaps(y.v_cache, cache_bytes, z.k_cache, cache_bytes) || overlaps(y.v_cache, cache_bytes, z.v_cache, cache_bytes))
+                return IFLOW_ERR_SHAPE;
         }
     }
     int grid = 0;

@@ -160,6 +160,32 @@ def test_decode_stack_at_7b_shape(gpu, orc):
     st.step_and_check(701)
 
 
+def test_decode_stack_graph_replays_equal_eager(gpu, orc):
+    """The launch captured once in a HIP graph and replayed three times, with eager work and synchronizations in between:
+    every replay gives the eager launch's results bit for bit (same position: the cache row is rewritten with the same values)."""
+    torch, iflow = gpu
+    say("[case] decode stack Q3H_B64 as a HIP graph: three replays against the eager launch")
+    st = Stack(torch, iflow, orc, "Q3H_B64", 2, 8, 4, 1408, 64, 1, synth.BASE_SEED + 3600, 33)
+    st.step_and_check(33)
+    want = (bits_of(st.h_out).copy(), bits_of(st.scratch).copy(), [bits_of(ly["k_cache"]).copy() for ly in st.layers])
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=stream):
+        iflow.decode_stack_launch(st.chain, 33, stream=stream.cuda_stream)
+    torch.cuda.synchronize()
+    for i in range(3):
+        st.h_out.zero_(); st.scratch.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        iflow.qgemv_chain_check(st.chain)
+        assert np.array_equal(bits_of(st.h_out), want[0]) and np.array_equal(bits_of(st.scratch), want[1]), i
+        for ly, kc in zip(st.layers, want[2]):
+            assert np.array_equal(bits_of(ly["k_cache"]), kc), i
+        _ = (torch.ones(1000, device="cuda") * 2).sum().item()                # eager work between the replays
+
+
 def test_decode_stack_launch_and_plan_refuse_what_they_cannot_run(gpu, orc):
     torch, iflow = gpu
     say("[case] decode stack: refused positions, shapes and launches")

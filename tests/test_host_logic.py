@@ -369,6 +369,9 @@ def test_decode_stack_validation_happens_before_any_launch(iflow):
     assert plan(h_out=base * 2 + 8) == iflow.ERR_ALIGN and plan(layer={"norm2": base * 16 + 2}) == iflow.ERR_ALIGN
     assert plan(h_out=base + 512) == iflow.ERR_SHAPE                             # h_out inside h_in
     assert plan(h_in=base * 3 + 4096) == iflow.ERR_SHAPE                         # h_in inside the scratch buffer
+    assert plan(layer={"k_cache": base * 3 + 1024}) == iflow.ERR_SHAPE           # a cache inside the scratch buffer
+    assert plan(layer={"v_cache": base * 17 + 4096}) == iflow.ERR_SHAPE          # the two caches overlap (k_cache sits at base * 17)
+    assert plan(layer={"norm1": base * 2}) == iflow.ERR_SHAPE                    # the gains are h_out
     chain = iflow.Chain(plan=base, workspace=base * 2, grid=256, max_strips=1, magic=0x69464C57, fused=1, format=fmt, lds_bytes=32768, max_seq=16)
     assert L.iflow_decode_stack_launch(None, 0, None) == iflow.ERR_NULL
     chain.magic = 0
