@@ -834,7 +834,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // (development aid, off in the library: per-workgroup time stamps of a launch, 16 words per workgroup and phase, written to
     // the buffer whose address sits at byte 48 of the plan)
     uint32_t *const trace = *reinterpret_cast<uint32_t *const *>(plan + 48);
-#define CHAIN_MARK(p, k) do { if (lane == 0) trace[((size_t)wg * nphases + (p)) * 16 + (k)] = (uint32_t)__builtin_amdgcn_s_memrealtime(); } while (0)
+#define CHAIN_MARK(p, k) do { if (trace && lane == 0) trace[((size_t)wg * nphases + (p)) * 16 + (k)] = (uint32_t)__builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define CHAIN_MARK(p, k) do { } while (0)
 #endif
@@ -866,8 +866,8 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                 float *const scratch = reinterpret_cast<float *>(xs);
                 const int group = at.n_heads / at.n_kv_heads;
 #if IFLOW_CHAIN_TRACE
-                uint32_t *const marks = trace + ((size_t)wg * nphases + p) * 16;
-                if (tid == 0) marks[0] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+                uint32_t *const marks = trace ? trace + ((size_t)wg * nphases + p) * 16 : nullptr;
+                if (marks && tid == 0) marks[0] = (uint32_t)__builtin_amdgcn_s_memrealtime();
 #else
                 uint32_t *const marks = nullptr;
 #endif
