@@ -56,6 +56,9 @@ def parse():
                          "3.5-, 4- and 8-bit formats (other_paths.large_shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the context figures for batches > 1 and the cache-hot case")
+    ap.add_argument("--steady-state", action="store_true",
+                    help="instead of the decoder layers: one chained launch of four independent 98304 x 4096 products (a wavefront's "
+                         "step loop runs 16 steps per phase: what the kernel streams when phases are long), with the clock the launch ran at")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed region (reference for HBM counters)")
     return ap.parse_args()
@@ -125,6 +128,57 @@ def log_environment(torch):
             print(f"[bench]   {dev}: {e}", file=sys.stderr)
 
 
+def chain_clock_mhz(torch, iflow, ws):
+    """The shader clock a chained launch ran at, from the stamps its first workgroup leaves in the workspace header (the
+    shader clock counter and the 100 MHz counter at its start and its end, low words); the launch must have ended."""
+    w = [int(v) & 0xFFFFFFFF for v in ws.view(torch.int32)[iflow.CHAIN_WS_CLOCKS:iflow.CHAIN_WS_CLOCKS + 4].cpu().tolist()]
+    cycles, ticks = (w[2] - w[0]) & 0xFFFFFFFF, (w[3] - w[1]) & 0xFFFFFFFF
+    return round(100.0 * cycles / ticks, 1) if ticks else None
+
+
+def steady_state(torch, iflow, dev, fmt, format_name, gen):
+    """One chained launch over four independent products of 98304 x 4096 (201 MB packed each in the 3.5-bit format; every
+    wavefront runs 16 steps per phase, so phase entries and hand-overs are a few per cent): the rate of the step loop itself,
+    and the shader clock during the launch.  Built with IFLOW_HIPCC_DEFINES=-DIFLOW_CHAIN_ABL=1 (loads only) or =2 (decode
+    only) the same command times the two halves of the loop apart."""
+    rows, cols, nph = 98304, 4096, 4
+    n = iflow.packed_bytes(fmt, rows, cols)
+    mats = []
+    for _ in range(nph):
+        w = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+        pk = torch.empty(n, dtype=torch.uint8, device=dev)
+        iflow.quantize(fmt, w, rows, cols, pk, n)
+        mats.append(pk)
+        del w
+    x = torch.randn((cols,), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+    ys = [torch.empty((rows,), dtype=torch.float16, device=dev) for _ in range(nph)]
+    phases = [(cols, x, [(mats[i], rows, ys[i])]) for i in range(nph)]
+    wsb = iflow.qgemv_chain_workspace_bytes([rows] * nph)
+    pb = iflow.qgemv_chain_plan_bytes(phases)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    plan = torch.empty(pb, dtype=torch.uint8, device=dev)
+    chain = iflow.qgemv_chain_plan(fmt, phases, plan, pb, ws, wsb)
+    for _ in range(3):
+        iflow.qgemv_chain_launch(chain)
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(7):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            iflow.qgemv_chain_launch(chain)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) / 5)
+    iflow.qgemv_chain_check(chain)
+    us = sorted(times)[len(times) // 2] * 1e3
+    gbps = n * nph / us / 1e3
+    return {"steady_state": {"what": f"{format_name}, one chained launch of {nph} independent products of {rows} x {cols} "
+                                     f"({n * nph / 1e6:.0f} MB packed), eager launches, median of 7 x 5",
+                             "us_per_launch": round(us, 1), "GB/s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                             "shader_clock_mhz": chain_clock_mhz(torch, iflow, ws)}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -140,9 +194,13 @@ def main():
     bpw = iflow.BITS_PER_WEIGHT[fmt]
     shapes = synth.LLAMA2_7B_LAYER
 
-    # ---- build the ring of quantized layers (untimed) --------------------------------------------------
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.BASE_SEED + 2)
+    if args.steady_state:
+        print(json.dumps(steady_state(torch, iflow, dev, fmt, args.format, gen)))
+        return
+
+    # ---- build the ring of quantized layers (untimed) --------------------------------------------------
     ring = []
     for layer in range(args.ring):
         mats = []
@@ -825,6 +883,10 @@ def main():
         for chain, _, _, _ in chains.values():
             iflow.qgemv_chain_check(chain, stream=raw)         # raises if a wait inside a launch ever gave up
         out["roofline"]["kernel"] = f"iflow::chain_kernel<2, false, {fmt}, false>"
+        # the clock the last launch of the longest chain ran at (the part lowers it under load: a launch's cycles are
+        # what the kernel decides, its clock is the power management's)
+        longest = max(chains, key=lambda k: k[1])
+        out["roofline"]["shader_clock_mhz_during_launch"] = chain_clock_mhz(torch, iflow, chains[longest][2])
         out["config"]["chain_plans"] = {f"{k[1]} layers from ring position {k[0]}": {"plan_MB": round(v[1].numel() / 1e6, 1),
                                                                                       "plan_call_s": round(v[3], 2)} for k, v in chains.items()}
     if not args.no_cpu_baseline:

@@ -203,6 +203,10 @@ iflow_status_t iflow_qgemm_fused(iflow_format_t format, const void *packed, int6
  *            caller, read-only for the launches.
  * workspace: device memory of at least iflow_qgemv_chain_workspace_bytes() bytes, 16-byte aligned, owned by the caller,
  *            left alone between launches: it carries the hand-over words and a launch counter from launch to launch.
+ *            Its 32-bit words IFLOW_CHAIN_WS_CLOCKS .. +3 are a diagnostic that a caller may read after a launch has ended:
+ *            the shader clock counter and the constant 100 MHz counter (low words) as the launch's first workgroup read
+ *            them when it started (+0, +1) and when it ended (+2, +3); (end - start) of the first over (end - start) of
+ *            the second, times 100, is the clock in MHz that the launch ran at.
  *            Launches of one chain must be ordered (one stream); a second chain needs a plan and a workspace of its own.
  * iflow_chain_t is plain data (no resources behind it): it may be copied and dropped freely.
  *
@@ -212,6 +216,7 @@ iflow_status_t iflow_qgemm_fused(iflow_format_t format, const void *packed, int6
 #define IFLOW_CHAIN_MAX_GROUP 4
 #define IFLOW_CHAIN_MAX_MATRICES 4096
 #define IFLOW_CHAIN_WS_HEADER 4096
+#define IFLOW_CHAIN_WS_CLOCKS 8
 #define IFLOW_CHAIN_MAGIC 0x69464c57u
 typedef struct iflow_chain_t {
     void *plan;                 /* device */

@@ -18,6 +18,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp
 # The first kernel arguments arrive in scalar registers at wavefront start instead of through a scalar load
 # (the GEMV kernel puts what it needs to form its first addresses there); worth 1-2 % on the 8 MiB matrices.
 FLAGS += ["-mllvm", "-amdgpu-kernarg-preload-count=16"]
+# Measurement builds: extra -D options from the environment (e.g. IFLOW_HIPCC_DEFINES="-DIFLOW_CHAIN_ABL=1"); the library's
+# own build passes none.
+FLAGS += os.environ.get("IFLOW_HIPCC_DEFINES", "").split()
 
 
 def sources():

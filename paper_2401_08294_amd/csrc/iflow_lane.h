@@ -134,32 +134,53 @@ __device__ __forceinline__ void load_x(XRegs<KIND> &xr, const uint16_t *__restri
 // Weights of one lane for one row: WD dwords of codes and the block header (scale | offset << 16).
 template <int KIND> struct WRegs { uint32_t d[Geo<KIND>::WD]; uint32_t hdr; };
 
+// The two constants of the 3.5-bit format's code extraction, held in registers so that (d & mask) | magic is one
+// v_and_or_b32 (an instruction takes one literal at most).  A kernel that decodes in a loop makes them once, in front of it.
+struct Q3HConsts { uint32_t cmask, magic; };
+__device__ __forceinline__ Q3HConsts q3h_consts()
+{
+    Q3HConsts k = {0x007F007Fu, 0x64006400u};
+    asm volatile("" : "+v"(k.cmask), "+v"(k.magic));
+    return k;
+}
+// a . b, as the first term of a sum: the three-operand form of the instruction with a zero addend (the accumulating form
+// the compiler picks for dot2(a, b, 0.f) needs its accumulator register cleared by a move first)
+__device__ __forceinline__ float dot2_first(half2_t a, half2_t b)
+{
+    float r;
+    asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// sum over the lane's weights of level * x (biased), for NB batch columns (3.5-bit format, constants from the caller)
+template <int NB>
+__device__ __forceinline__ void lane_dot_q3h(const WRegs<KIND_Q3H> &w, const XRegs<KIND_Q3H> (&xr)[NB], float (&acc)[NB], const Q3HConsts &k)
+{
+    float a1[NB], a2[NB];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t hc0 = (w.d[i] & k.cmask) | k.magic;                        // codes 4i, 4i+1
+        const uint32_t hc1 = ((w.d[i] >> 7) & k.cmask) | k.magic;                 // codes 4i+2, 4i+3
+        const half2_t h1a = q3h_high_digit(hc0), h1b = q3h_high_digit(hc1);
+        const half2_t h2a = q3h_low_digit(h1a, hc0), h2b = q3h_low_digit(h1b, hc1);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            a1[b] = i == 0 ? dot2_first(h1a, xr[b].v[2 * i]) : dot2(h1a, xr[b].v[2 * i], a1[b]);
+            a2[b] = i == 0 ? dot2_first(h2a, xr[b].v[16 + 2 * i]) : dot2(h2a, xr[b].v[16 + 2 * i], a2[b]);
+            a1[b] = dot2(h1b, xr[b].v[2 * i + 1], a1[b]);
+            a2[b] = dot2(h2b, xr[b].v[16 + 2 * i + 1], a2[b]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(a2[b], IFLOW_Q3H_SCALE2, a1[b]);
+}
+
 // sum over the lane's weights of level * x (biased), for NB batch columns
 template <int KIND, int NB>
 __device__ __forceinline__ void lane_dot(const WRegs<KIND> &w, const XRegs<KIND> (&xr)[NB], float (&acc)[NB])
 {
     if constexpr (KIND == KIND_Q3H) {
-        float a1[NB], a2[NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) { a1[b] = 0.f; a2[b] = 0.f; }
-        uint32_t cmask = 0x007F007Fu, magic = 0x64006400u;
-        asm volatile("" : "+v"(cmask), "+v"(magic));                              // registers, so that (d & m) | k is one v_and_or_b32
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t hc0 = (w.d[i] & cmask) | magic;                        // codes 4i, 4i+1
-            const uint32_t hc1 = ((w.d[i] >> 7) & cmask) | magic;                 // codes 4i+2, 4i+3
-            const half2_t h1a = q3h_high_digit(hc0), h1b = q3h_high_digit(hc1);
-            const half2_t h2a = q3h_low_digit(h1a, hc0), h2b = q3h_low_digit(h1b, hc1);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                a1[b] = dot2(h1a, xr[b].v[2 * i], a1[b]);
-                a2[b] = dot2(h2a, xr[b].v[16 + 2 * i], a2[b]);
-                a1[b] = dot2(h1b, xr[b].v[2 * i + 1], a1[b]);
-                a2[b] = dot2(h2b, xr[b].v[16 + 2 * i + 1], a2[b]);
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(a2[b], IFLOW_Q3H_SCALE2, a1[b]);
+        lane_dot_q3h<NB>(w, xr, acc, q3h_consts());
     } else if constexpr (KIND == KIND_Q4) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[b] = 0.f;

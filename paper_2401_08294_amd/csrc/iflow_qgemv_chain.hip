@@ -51,9 +51,10 @@ constexpr int CHAIN_MAX_COLS = 65536;
 constexpr int CHAIN_MAX_GROUP = IFLOW_CHAIN_MAX_GROUP;         // matrices per phase
 constexpr int CHAIN_MAX_GRID = 960;
 constexpr int CHAIN_POLL_BUDGET = 1 << 17;                     // re-reads before a wait is given up (tens of milliseconds)
-// workspace header, in 32-bit words: [1] error, [64, 64 + grid) the launch count, one copy per workgroup;
+// workspace header, in 32-bit words: [1] error, [8, 12) the launch's clock stamps (below), [64, 64 + grid) the launch count,
+// one copy per workgroup;
 // tagged outputs start at byte IFLOW_CHAIN_WS_HEADER
-constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_SEEN = 64;
+constexpr int CHAIN_WS_ERROR = 1, CHAIN_WS_CLOCKS = IFLOW_CHAIN_WS_CLOCKS, CHAIN_WS_SEEN = 64;
 
 // The plan: what iflow_qgemv_chain_plan writes into the caller's device memory once, and every launch reads.  The weights
 // of a model never change between tokens, so the chain is described once; a launch passes two pointers.  Everything a
@@ -174,6 +175,12 @@ struct ChainWalk {
 #endif
 #ifndef IFLOW_CHAIN_EARLY
 #define IFLOW_CHAIN_EARLY 0
+#endif
+// Measurement aid, off in the library (outputs are wrong with it on; every access stays where it is): 1 - the step loop
+// requests and waits for its weights but does not decode them; 2 - it decodes whatever its registers hold and requests
+// nothing.  Together with the clock stamps below these tell what a launch's time is made of.
+#ifndef IFLOW_CHAIN_ABL
+#define IFLOW_CHAIN_ABL 0
 #endif
 // 1: the requests for weights stop in front of an attention's phases and start again behind them (nothing of the step loop is
 // live in registers during the attention, but the first weights of the output projection are requested in one burst that
@@ -555,6 +562,13 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     const int wave = IFLOW_UNI(tid >> 6);
     const int wg = blockIdx.x;
     const int nphases = hd->nphases;
+    // Clock stamps of the launch, left in the workspace header by the first workgroup when it starts and when it ends: the
+    // shader clock counter and the constant 100 MHz counter, low words.  Their ratio is the clock the launch really ran at,
+    // which on a power-limited part is the first thing to know about a launch's duration.
+    if (wg == 0 && tid == 0) {
+        ws[CHAIN_WS_CLOCKS] = (uint32_t)__builtin_amdgcn_s_memtime();
+        ws[CHAIN_WS_CLOCKS + 1] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+    }
 
     // A wavefront handles two adjacent rows (2i, 2i+1 of a matrix) per step, so "row" below means such a pair, named
     // by its even row; in a phase's row space every matrix starts at an even row (odd matrices are padded by one).
@@ -688,7 +702,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
         const uint32_t voff = last_strip ? q_voff_last : voff_full;
         // (pointers that were read from the plan have to be told that they point to global memory: a generic pointer
         // makes flat loads, whose completion cannot be counted, and every wait in the step loop becomes "all")
-        if constexpr (Q3H) {
+        if constexpr (IFLOW_CHAIN_ABL == 2) {
+#pragma unroll
+            for (int i = 0; i < G::WD; ++i) asm volatile("" : "+v"(w[0].d[i]), "+v"(w[1].d[i]));
+        } else if constexpr (Q3H) {
             const int plane2 = last_strip ? q_nlast16 : 1024;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
@@ -840,6 +857,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
 #endif
     bool failed = false;
     XRegs<KIND> xr[1];
+    [[maybe_unused]] const Q3HConsts q3h_k = q3h_consts();       // (made once: inside the step loop they would be made again per row)
     // Results are not stored row by row: lane 63's sums of the wavefront's i-th pair of rows are parked in lane i of two
     // registers, and when the phase's steps are done lanes 0..n-1 store them all at once - two store instructions
     // per wavefront and phase instead of two per row (in-order completion means every later load of the wavefront would
@@ -1100,8 +1118,15 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                     if (nstrips > 1) load_xr(t);
 #pragma unroll
                     for (int u = 0; u < 2; ++u) {
+                        if constexpr (IFLOW_CHAIN_ABL == 1) {  // (the weights are looked at, so that their loads stay)
+                            uint32_t fold = 0;
+#pragma unroll
+                            for (int i = 0; i < G::WD; ++i) fold ^= w[st][u].d[i];
+                            v[u] = part[u] + __builtin_bit_cast(float, fold & 0x3F800000u);
+                            continue;
+                        }
                         float acc[1];
-                        lane_dot<KIND, 1>(w[st][u], xr, acc);
+                        if constexpr (Q3H) lane_dot_q3h<1>(w[st][u], xr, acc, q3h_k); else lane_dot<KIND, 1>(w[st][u], xr, acc);
                         half2_t so;
                         if constexpr (Q3H) so = as_h2(q3h_header(w[st][u].d)); else so = as_h2(w[st][u].hdr);
                         v[u] = part[u] + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
@@ -1162,6 +1187,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // ---- the workgroup's copy of the launch count advances ----------------------------------------------------------------
     __syncthreads();
     if (tid == 0) __hip_atomic_store(ws + CHAIN_WS_SEEN + wg, counter + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (wg == 0 && tid == 0) {
+        ws[CHAIN_WS_CLOCKS + 2] = (uint32_t)__builtin_amdgcn_s_memtime();
+        ws[CHAIN_WS_CLOCKS + 3] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+    }
 }
 
 // ---- host side ------------------------------------------------------------------------------------------------

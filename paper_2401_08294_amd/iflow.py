@@ -21,6 +21,7 @@ BITS_PER_WEIGHT = {Q8_B32: 9.0, Q8_B64: 8.5, Q4_B32: 5.0, Q4_B64: 4.5, Q3H_B64: 
 
 OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_SIZE, ERR_ALIGN, ERR_DEVICE, ERR_TIMEOUT = range(8)
 CHAIN_MAX_PHASES, CHAIN_MAX_GROUP, CHAIN_MAX_MATRICES = 1024, 4, 4096
+CHAIN_WS_CLOCKS = 8            # 32-bit word of the workspace where a chained launch leaves its clock stamps (IFLOW_CHAIN_WS_CLOCKS)
 ATTN_STATIC_MAX_HEADS = 128
 
 
