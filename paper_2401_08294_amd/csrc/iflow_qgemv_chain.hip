@@ -182,13 +182,6 @@ struct ChainWalk {
 #ifndef IFLOW_CHAIN_ABL
 #define IFLOW_CHAIN_ABL 0
 #endif
-// 1: the requests for weights stop in front of an attention's phases and start again behind them (nothing of the step loop is
-// live in registers during the attention, but the first weights of the output projection are requested in one burst that
-// the projection's activations then queue behind); 0: they run on through the attention.  Measured on a 7B decode step with
-// 1024 cached positions: 40.6 against 39.6 us per layer.
-#ifndef IFLOW_CHAIN_ATTN_STALL
-#define IFLOW_CHAIN_ATTN_STALL 0
-#endif
 constexpr int CHAIN_SETS = IFLOW_CHAIN_SETS;
 #ifndef IFLOW_CHAIN_SETS_OTHER
 #define IFLOW_CHAIN_SETS_OTHER 4
@@ -573,14 +566,14 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     // A wavefront handles two adjacent rows (2i, 2i+1 of a matrix) per step, so "row" below means such a pair, named
     // by its even row; in a phase's row space every matrix starts at an even row (odd matrices are padded by one).
     // pairs of this wavefront in a phase: first row of the workgroup, number of pairs of the wavefront
-    auto phase_rows = [&](int rows_per_wg, int total, int &rbeg, int &nrows) {
+    auto phase_rows = [&](int rows_per_wg, int total, int &rbeg, int &nrows) __attribute__((always_inline)) {
         rbeg = wg * rows_per_wg;
         const int rend = min(rbeg + rows_per_wg, total);
         nrows = max(0, (rend - rbeg - 2 * wave + CHAIN_STRIDE - 1) / CHAIN_STRIDE);
     };
     // the segment that starts at row k.R of phase k.p (k.rows_left > 0): its matrix, the row inside it, its length;
     // `single`: the segment is the lone last row of a matrix with an odd number of rows (always a segment of its own)
-    auto walk_segment = [&](ChainWalk &k, int &m, int &r, bool &single) {
+    auto walk_segment = [&](ChainWalk &k, int &m, int &r, bool &single) __attribute__((always_inline)) {
         const ChainPhase &ph = a.ph[k.p];
         m = ph.first + (k.R >= ph.mstart[1]) + (k.R >= ph.mstart[2]) + (k.R >= ph.mstart[3]);
         r = k.R - a.mat[m].start;
@@ -594,23 +587,25 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     };
 
     // ---- requests ------------------------------------------------------------------------------------------------
-    // Per phase the steps of a wavefront are padded to a multiple of S with empty steps, so that step k of the whole
-    // sequence always lives in register set k mod S and the step loop can be unrolled by S with fixed registers
-    // (one copy of the loop per starting register set is more than the compiler's register allocation copes with).
-    // The two loads of a step are issued unconditionally: an empty step is a segment of its own whose lanes all read
-    // the first 16 bytes of the workspace.  With the same number of loads on every path the compiler can tell exactly
-    // how many younger loads may still be in flight when a register set is decoded, instead of waiting for all.
-    // (With attention in the plan the requests stop in front of an attention's phases and start again when its first half is
-    // done: nothing of the step loop is then live in registers while that half runs, which needs them all.)
+    // A wavefront's steps of all phases form one sequence, and step k of it lives in register set k mod S: the requests
+    // run S steps ahead of the decode across phase boundaries, and the sets are refilled in the order in which they are
+    // decoded.  The two loads of a row are issued unconditionally (an empty step's lanes all read the first 16 bytes of the
+    // workspace): with the same number of loads on every path the compiler can tell exactly how many younger loads may
+    // still be in flight when a register set is decoded, instead of waiting for all.
+    // PAD: a wavefront's steps per phase are padded to a multiple of S with empty steps, so that every phase starts at set 0
+    // and the step loop is S steps unrolled once.  Without it every set always holds a step that will be used, a phase
+    // starts at whatever set the sequence has reached, and the step exists in more copies (below).  Which is faster is
+    // measured, per format: with two sets of 4 KB (3.5-bit) no padding is 3.5 % faster on 7B-shaped layers; with four sets
+    // of 2 KB (4- and 8-bit) padding is 4-7 % faster - the empty sets at the head of a short phase are weights that are not
+    // queued in front of the reads of the phase's activations.
+    constexpr bool PAD = !Q3H;
     ChainWalk q = {-1, 0, 0, 0};
-    int q_limit = nphases;                                     // phases from here on are not requested yet
-    if constexpr (ATTN && IFLOW_CHAIN_ATTN_STALL) q_limit = hd->first_attn;
     const uint8_t *q_wptr = reinterpret_cast<const uint8_t *>(ws);     // weights of the step under the cursor
     int q_lt = 0, q_last = 0;                                  // its strip; the last strip of a row
     int q_nlast16 = 0;                                         // 16 x the blocks in that last strip (offset of its second plane)
+    [[maybe_unused]] int q_pad = 0;                            // PAD: empty steps still owed by phase q.p
     int q_rowjump = 0;                                         // from the last strip of a row to the wavefront's next row, bytes
     std::conditional_t<FUSED, int64_t, int> q_row1 = 0;        // from the first to the second row of the pair, bytes (0: no second row)
-    int q_pad = 0;                                             // empty steps still owed by phase q.p
     uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
     const uint32_t voff_full = (uint32_t)lane * 16;
     // formats whose block headers sit behind the codes: the same walk over the headers (4 bytes per block)
@@ -619,31 +614,32 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     std::conditional_t<FUSED, int64_t, int> q_hrow1 = 0;
     uint32_t q_hoff_last = 0;
     const uint32_t hoff_full = (uint32_t)(lane * G::WPL / T::block) * 4;
-    auto request_empty = [&](int count) {                      // `count` empty steps: one "row" of one empty strip each
+    auto request_empty = [&](int count) __attribute__((always_inline)) {                      // `count` empty steps: one "row" of one empty strip each
         q_wptr = reinterpret_cast<const uint8_t *>(ws);
         q_last = 0; q_nlast16 = 0; q_rowjump = 0; q_row1 = 0; q_voff_last = 0;
         q_hptr = q_wptr; q_hrowjump = 0; q_hrow1 = 0; q_hoff_last = 0;
         q.seg_left = count;
     };
-    auto request_segment = [&]() {                             // q.seg_left == 0: find what the requests do next
+    auto request_segment = [&]() __attribute__((always_inline)) {                             // q.seg_left == 0: find what the requests do next
         bool found = false;
-        if (q.rows_left == 0 && q_pad > 0) {
-            request_empty(q_pad);
-            q_pad = 0;
-            found = true;
+        if constexpr (PAD) {
+            if (q.rows_left == 0 && q_pad > 0) {
+                request_empty(q_pad);
+                q_pad = 0;
+                found = true;
+            }
         }
         while (!found && q.p < nphases) {
             if (q.rows_left == 0) {                            // the next phase in which this wavefront has rows
-                if constexpr (ATTN) {
-                    if (q.p + 1 >= q_limit) break;             // (empty steps until the attention has run)
-                }
                 q.p += 1;
                 if (q.p < nphases) {
                     int rbeg, n;
                     phase_rows(a.ph[q.p].rows_per_wg, a.ph[q.p].total, rbeg, n);
                     q.rows_left = n; q.R = rbeg + 2 * wave;
-                    const int real = n * a.ph[q.p].nstrips;
-                    q_pad = (real + S - 1) / S * S - real;
+                    if constexpr (PAD) {
+                        const int real = n * a.ph[q.p].nstrips;
+                        q_pad = (real + S - 1) / S * S - real;
+                    }
                 }
             }
             if (q.p < nphases && q.rows_left > 0) {
@@ -697,7 +693,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
         if (!found) request_empty(0x7FFFFFFF);                 // the walk is over: empty steps from here on
         q_lt = 0;
     };
-    auto request = [&](WRegs<KIND> (&w)[2]) {                  // request the step under the cursor, then advance it
+    auto request = [&](WRegs<KIND> (&w)[2]) __attribute__((always_inline)) {                  // request the step under the cursor, then advance it
         const bool last_strip = q_lt == q_last;
         const uint32_t voff = last_strip ? q_voff_last : voff_full;
         // (pointers that were read from the plan have to be told that they point to global memory: a generic pointer
@@ -856,6 +852,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
 #define CHAIN_MARK(p, k) do { } while (0)
 #endif
     bool failed = false;
+    int cs = 0;                                                // this wavefront's steps so far, mod S: the register set of its next step
     XRegs<KIND> xr[1];
     [[maybe_unused]] const Q3HConsts q3h_k = q3h_consts();       // (made once: inside the step loop they would be made again per row)
     // Results are not stored row by row: lane 63's sums of the wavefront's i-th pair of rows are parked in lane i of two
@@ -899,15 +896,6 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                 CHAIN_MARK(p, 3 + (wave == 0 ? 0 : 8));           // (wavefront 0: slot 3) the partial states are written
                 chain_attn_merge(at, ws, scratch, tag, wg, (int)gridDim.x, tid, failed);
                 CHAIN_MARK(p, 4 + (wave == 0 ? 0 : 8));           // the workgroup's outputs are published
-                // The requests start again, with the first steps of the next phase that has products.  (Behind the second half,
-                // not in front of it: a wavefront's loads return in order, so the second half's reads of the partial states
-                // would wait for the weights.)
-                if constexpr (IFLOW_CHAIN_ATTN_STALL != 0) {
-                    q_limit = a.ops[p].next_attn;
-                    request_segment();
-#pragma unroll
-                    for (int j = 0; j < S; ++j) request(w[j]);
-                }
                 p += 1;
                 continue;
             }
@@ -1094,7 +1082,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
             }
 
             // 2. this wavefront's steps; step j of the phase uses register set j mod S
-            auto load_xr = [&](int ts) {
+            auto load_xr = [&](int ts) __attribute__((always_inline)) {
                 const uint8_t *sl = xs + (size_t)ts * CHAIN_SLOT_BYTES;
 #pragma unroll
                 for (int jj = 0; jj < XQ; ++jj) {
@@ -1109,30 +1097,28 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
             float part[2] = {0.f, 0.f};                        // per-lane partial sums of the two rows, carried across strips
             const int nreal = n * nstrips;
             int t = 0;
-            auto body = [&](auto stage, int j) {
-                constexpr int st = decltype(stage)::value;
-                const bool real = j < nreal;                   // an empty step only passes its register set on
+            auto body = [&](auto stage, bool real = true) __attribute__((always_inline)) {     // the next step of the phase, from register set `stage`
+                constexpr int st = decltype(stage)::value;     // (real == false: an empty step of the padding, which only passes its set on)
                 float v[2] = {0.f, 0.f};
-                if constexpr (EARLY) request(w[(st + S - 1) % S]);   // step j + S - 1: into the set decoded one step ago
-                if (real) {
-                    if (nstrips > 1) load_xr(t);
+                if constexpr (EARLY) request(w[(st + S - 1) % S]);   // into the set decoded one step ago
+                if (real && nstrips > 1) load_xr(t);
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        if constexpr (IFLOW_CHAIN_ABL == 1) {  // (the weights are looked at, so that their loads stay)
-                            uint32_t fold = 0;
+                for (int u = 0; u < 2; ++u) {
+                    if (!real) continue;
+                    if constexpr (IFLOW_CHAIN_ABL == 1) {      // (the weights are looked at, so that their loads stay)
+                        uint32_t fold = 0;
 #pragma unroll
-                            for (int i = 0; i < G::WD; ++i) fold ^= w[st][u].d[i];
-                            v[u] = part[u] + __builtin_bit_cast(float, fold & 0x3F800000u);
-                            continue;
-                        }
-                        float acc[1];
-                        if constexpr (Q3H) lane_dot_q3h<1>(w[st][u], xr, acc, q3h_k); else lane_dot<KIND, 1>(w[st][u], xr, acc);
-                        half2_t so;
-                        if constexpr (Q3H) so = as_h2(q3h_header(w[st][u].d)); else so = as_h2(w[st][u].hdr);
-                        v[u] = part[u] + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
+                        for (int i = 0; i < G::WD; ++i) fold ^= w[st][u].d[i];
+                        v[u] = part[u] + __builtin_bit_cast(float, fold & 0x3F800000u);
+                        continue;
                     }
+                    float acc[1];
+                    if constexpr (Q3H) lane_dot_q3h<1>(w[st][u], xr, acc, q3h_k); else lane_dot<KIND, 1>(w[st][u], xr, acc);
+                    half2_t so;
+                    if constexpr (Q3H) so = as_h2(q3h_header(w[st][u].d)); else so = as_h2(w[st][u].hdr);
+                    v[u] = part[u] + __builtin_fmaf((float)so.x, acc[0] - xr[0].bias_sum, (float)so.y * xr[0].x_sum);
                 }
-                if constexpr (!EARLY) request(w[st]);          // step j + S of the sequence takes over the register set
+                if constexpr (!EARLY) request(w[st]);          // the register set takes the step S further on in the sequence
                 const bool last = real && t == nstrips - 1;    // the rows are complete: two reductions, lane 63 publishes
                 if (last) {
                     // lane `done` of res0 / res1 <- the two row sums (same summation tree as wave_sum_to_lane63)
@@ -1145,17 +1131,43 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                 part[1] = last ? 0.f : (real ? v[1] : part[1]);
                 t = last ? 0 : t + (real ? 1 : 0);
             };
+            using C0 = std::integral_constant<int, 0>;
+            using C1 = std::integral_constant<int, (S > 1 ? 1 : 0)>;
+            using C2 = std::integral_constant<int, (S > 2 ? 2 : 0)>;
+            using C3 = std::integral_constant<int, (S > 3 ? 3 : 0)>;
+            static_assert(S >= 1 && S <= 4, "register sets per wavefront");
+            // The phase's first step sits in set `cs` (the wavefront's steps so far, mod S).  Up to S - 1 steps bring the
+            // sequence round to set 0, then whole rounds of S steps, then the steps left over from sets 0, 1, ...: every
+            // copy of a step names its register set at compile time, and no step is spent on padding.
+            int left = nreal;
+            if constexpr (PAD) {                               // whole rounds only, the last one filled up with empty steps
 #pragma unroll 1
-            for (int j = 0; j < nreal; j += S) {
-                body(std::integral_constant<int, 0>{}, j);
-                if constexpr (S > 1) body(std::integral_constant<int, 1>{}, j + 1);
-                if constexpr (S > 2) body(std::integral_constant<int, 2>{}, j + 2);
-                if constexpr (S > 3) body(std::integral_constant<int, 3>{}, j + 3);
-                if constexpr (S > 4) body(std::integral_constant<int, 4>{}, j + 4);
-                if constexpr (S > 5) body(std::integral_constant<int, 5>{}, j + 5);
-                if constexpr (S > 6) body(std::integral_constant<int, 6>{}, j + 6);
-                if constexpr (S > 7) body(std::integral_constant<int, 7>{}, j + 7);
+                for (int j = 0; j < nreal; j += S) {
+                    body(C0{}, true);
+                    if constexpr (S > 1) body(C1{}, j + 1 < nreal);
+                    if constexpr (S > 2) body(C2{}, j + 2 < nreal);
+                    if constexpr (S > 3) body(C3{}, j + 3 < nreal);
+                }
+                left = 0;
             }
+            if (cs > 0) {
+                if constexpr (S > 1) { if (cs <= 1 && left > 0) { body(C1{}); left -= 1; } }
+                if constexpr (S > 2) { if (cs <= 2 && left > 0) { body(C2{}); left -= 1; } }
+                if constexpr (S > 3) { if (cs <= 3 && left > 0) { body(C3{}); left -= 1; } }
+            }
+#pragma unroll 1
+            for (; left >= S; left -= S) {
+                body(C0{});
+                if constexpr (S > 1) body(C1{});
+                if constexpr (S > 2) body(C2{});
+                if constexpr (S > 3) body(C3{});
+            }
+            if (left > 0) {                                    // (only reached with the sequence at set 0)
+                body(C0{});
+                if constexpr (S > 2) { if (left > 1) body(C1{}); }
+                if constexpr (S > 3) { if (left > 2) body(C2{}); }
+            }
+            if constexpr (!PAD) cs = (cs + nreal) % S;
             if (wave == 0) CHAIN_MARK(p, 9);                   // steps done: wavefronts 0, 7 and 11
             if (wave == 7) CHAIN_MARK(p, 10);
             if (wave == 11) CHAIN_MARK(p, 11);
