@@ -934,6 +934,14 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
             }
             float res0 = 0.f, res1 = 0.f;
             int done = 0;                                      // pairs of rows summed so far
+            // A tagged residual is read here for the first time, together with the phase's activations: its producer is an
+            // earlier phase than theirs, so it is complete as a rule, and the read costs no round trip of its own (read behind
+            // the barrier it costs one, in front of the phase's first step).  It is looked at behind the barrier.
+            [[maybe_unused]] uint64_t res_first = 0;
+            if constexpr (FUSED) {
+                if (res_tagged) res_first = __hip_atomic_load(res_tagged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                else if (res_plain) res_first = out_single ? (uint64_t)*global_ptr<const uint16_t>(res_plain) : (uint64_t)*global_ptr<const uint32_t>(res_plain);
+            }
             // 1. stage the activations (those of the first phase are already on their way)
             const int nchunks = nstrips * 256;
             if constexpr (!Q3H) {
@@ -1060,12 +1068,12 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                     for (int i = 0; i < CHAIN_WAVES; ++i) tot += sq_slot[i];
                     out_scale = 1.0f / __builtin_sqrtf(tot * a.ops[p].inv_cols + a.ops[p].eps);
                 }
-                // Residuals are read after the barrier: the phase's own input is complete then, and with it every output
+                // The residuals, requested in 0: behind the barrier the phase's own input is complete, and with it every output
                 // of the phases before its producer.  A tagged residual is still checked (and re-read a bounded number of times).
                 if (res_tagged) {
                     int budget = failed ? 1 : CHAIN_POLL_BUDGET;
+                    uint64_t wd = res_first;
                     for (;;) {
-                        const uint64_t wd = __hip_atomic_load(res_tagged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         const uint32_t lo = (uint32_t)wd, hi = (uint32_t)(wd >> 32);
                         resid = (lo & 0xFFFFu) | (hi << 16);
                         if (((lo ^ tag) >> 16) == 0 && (out_single || ((hi ^ tag) >> 16) == 0)) break;
@@ -1075,9 +1083,10 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                             break;
                         }
                         __builtin_amdgcn_s_sleep(2);
+                        wd = __hip_atomic_load(res_tagged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 } else if (res_plain) {
-                    resid = out_single ? (uint32_t)*global_ptr<const uint16_t>(res_plain) : *global_ptr<const uint32_t>(res_plain);
+                    resid = (uint32_t)res_first;
                 }
             }
 
