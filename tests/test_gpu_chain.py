@@ -120,6 +120,40 @@ def test_chain_ragged_phases_and_relaunch(gpu, orc):
         check_phases(torch, iflow, orc, phases, host, f"launch {it}")
 
 
+# A wavefront's steps of all phases form one sequence over its register sets (no padding per phase in the 3.5-bit format): the
+# phases below give the wavefronts 1, 2 or 4, 3, 3 and 2 or 4 steps (row pairs x strips), so that phases start at every set and
+# end in the middle of a round, some wavefronts of a workgroup with more steps than others, one phase with rows for a few
+# workgroups only.
+SPEC_STEP_COUNTS = [
+    (1408, None, [6144]),                  # one pair of rows per wavefront, one strip
+    (6144, (0, 0), [6400]),                # two strips; the first wavefronts of a workgroup have two pairs, the others one
+    (1408, None, [18432]),                 # three pairs, one strip
+    (8256, None, [6144]),                  # one pair, three strips (the last one a single block)
+    (6144, (3, 0), [6200, 37]),            # two strips again, an odd matrix behind
+    (128, None, [5]),
+    (1408, None, [6144]),                  # and a phase behind the nearly empty one
+]
+
+
+def test_chain_phases_of_every_step_count(gpu, orc):
+    torch, iflow = gpu
+    say("[case] chain whose phases give the wavefronts 1 to 4 steps each, two launches")
+    phases, host, chain, keep = build_chain(torch, iflow, SPEC_STEP_COUNTS, synth.BASE_SEED + 520)
+    for it in range(2):
+        if it:
+            for _, _, mats in phases:
+                for m in mats:
+                    m[2].fill_(float("nan"))
+        iflow.qgemv_chain_launch(chain)
+        iflow.qgemv_chain_check(chain)
+        check_phases(torch, iflow, orc, phases, host, f"launch {it}")
+    # the launch's clock stamps (a diagnostic of the workspace header): a plausible shader clock
+    ws = keep[1]
+    w = [int(v) & 0xFFFFFFFF for v in ws.view(torch.int32)[iflow.CHAIN_WS_CLOCKS:iflow.CHAIN_WS_CLOCKS + 4].cpu().tolist()]
+    cycles, ticks = (w[2] - w[0]) & 0xFFFFFFFF, (w[3] - w[1]) & 0xFFFFFFFF
+    assert ticks > 0 and 300.0 < 100.0 * cycles / ticks < 3500.0, (w, cycles, ticks)
+
+
 @pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64", "Q4_B32", "Q8_B32"])
 def test_chain_other_formats_ragged_phases_and_relaunch(gpu, orc, fmt_name):
     """The 4- and 8-bit formats of Table 3 through the same chained launch (strips of 2048 and 1024 columns, block headers
