@@ -37,7 +37,10 @@ namespace iflow {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <typename T> __device__ __forceinline__ IFLOW_GLOBAL T *global_ptr(const void *p) { return (IFLOW_GLOBAL T *)(uint64_t)p; }
 
-constexpr int CHAIN_WAVES = 12;                                // wavefronts per workgroup (measured: 8 is 3 % slower, 16 equal;
+#ifndef IFLOW_CHAIN_WAVES
+#define IFLOW_CHAIN_WAVES 12
+#endif
+constexpr int CHAIN_WAVES = IFLOW_CHAIN_WAVES;                                // wavefronts per workgroup (measured: 8 is 3 % slower, 16 equal;
                                                                // 12 divides the row pairs of 7B-sized phases evenly)
 constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;                  // a wavefront takes two rows per step: rows between its steps
 // A strip is what the 64 lanes of a wavefront cover of a row in one step: 64 x (weights per lane) columns - 4096 for the
