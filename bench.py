@@ -707,12 +707,12 @@ def main():
                 other["other_formats"]["formats"][oname] = per_batch
                 del copies, first
             del wg
-            # config 3's other two formats through the chained launch: 8 distinct 7B-shaped layers per format, one launch per
+            # config 3's other two formats, and the bit-plane formats, through the chained launch: 8 distinct 7B-shaped layers per format, one launch per
             # pass over them (every product reading its predecessor's output), eager launches of ~0.3 ms each
             if args.format == "Q3H_B64" and not args.fused:
                 other["formats_chained"] = {"what": "q+k+v -> o -> gate+up -> down -> next layer's q+k+v ..., 8 distinct 7B-shaped layers in ONE chained "
                                                     "launch, eager; us per layer, GB/s of the format's algorithmic bytes, fraction of the HBM peak", "formats": {}}
-                for oname in ("Q4_B64", "Q8_B64"):
+                for oname in ("Q4_B64", "Q8_B64", "Q6_B64", "Q5_B64", "Q3_B32", "Q2_B32"):
                     ofmt = iflow.FORMATS[oname]
                     nl = 8
                     ring_o = []

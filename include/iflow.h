@@ -173,8 +173,7 @@ iflow_status_t iflow_qgemm_fused(iflow_format_t format, const void *packed, int6
                                  int64_t batch, iflow_x_op_t x_op, const uint16_t *aux, float eps, const uint16_t *residual,
                                  uint16_t *Y, void *stream);
 
-/* A chain of batch-1 products in ONE launch (the 3.5-, 4- and 8-bit formats, Table 3's Q3H, Q4_B32/B64, Q8_B32/B64; the
- * bit-plane formats are IFLOW_ERR_FORMAT): the decode step applies its projections one
+/* A chain of batch-1 products in ONE launch (every format of Table 3 and the 2-bit format): the decode step applies its projections one
  * after the other to a single token (Section 3; Section 5 calls one such pass over all layers one Infer step), and
  * at 7B sizes each product is so short that the idle time between dependent launches costs as much as a third of
  * the weight stream.  The chain is a list of `nphases` (1..IFLOW_CHAIN_MAX_PHASES) phases.  Phase p multiplies counts[p]

@@ -362,7 +362,7 @@ iflow_status_t chain_validate(iflow_format_t format, int nphases, const int *cou
 {
     iflow::FormatInfo fi;
     if (!iflow::format_info((int)format, &fi)) return IFLOW_ERR_FORMAT;
-    if (!iflow::chain_supports_format((int)format)) return IFLOW_ERR_FORMAT;    // 3.5-, 4- and 8-bit formats (not the bit-plane ones)
+    if (!iflow::chain_supports_format((int)format)) return IFLOW_ERR_FORMAT;
     if (nphases < 1 || nphases > IFLOW_CHAIN_MAX_PHASES) return IFLOW_ERR_SHAPE;
     if (!counts || !cols || !x || !packed || !rows || !y) return IFLOW_ERR_NULL;
     int total = 0;

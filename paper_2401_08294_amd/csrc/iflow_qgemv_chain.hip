@@ -35,6 +35,7 @@
 namespace iflow {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <typename T> __device__ __forceinline__ IFLOW_GLOBAL T *global_ptr(const void *p) { return (IFLOW_GLOBAL T *)(uint64_t)p; }
 
 #ifndef IFLOW_CHAIN_WAVES
@@ -88,7 +89,8 @@ struct ChainMatrix {
     const uint16_t *residual;   // added to the output: an input of the launch ([rows] fp16) ...
     int residual_tag_word;      // ... or the tagged output of an earlier matrix (0: none)
     uint32_t hdr_off4;          // formats that keep the block headers behind the codes: where they start, in 4-byte units from `packed`
-    int pad_[2];
+    uint32_t hi_off4;           // bit-plane formats: where the high plane starts, in 4-byte units from `packed`
+    int pad_;
 };
 // what only the fused variant of the kernel reads about a phase
 struct ChainPhaseOps {
@@ -540,11 +542,14 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     constexpr int KIND = T::kind;
     using G = Geo<KIND>;
     constexpr bool Q3H = KIND == KIND_Q3H;
-    static_assert(Q3H || KIND == KIND_Q4 || KIND == KIND_Q8, "formats of the chained launch");
+    constexpr bool PLANES = kind_has_planes(KIND);             // 6-, 5-, 3-, 2-bit: a low and (but for 2-bit) a high plane, then the headers
+    constexpr int WA = Planes<KIND>::WA, WB = Planes<KIND>::WB;
+    constexpr int LANE_BYTES = PLANES ? 4 * WA : 16;           // code bytes per lane, row and strip (bit planes: of the low plane)
+    constexpr int LANE_BYTES_HI = 4 * WB;                      // ... of the high plane
     constexpr int XQ = G::XD / 4;                              // 16-byte quarters of a lane's staged activations
     constexpr int CHAIN_SLOT_BYTES = chain_slot_bytes<KIND>();
     constexpr int STRIP_COLS = chain_strip_cols<KIND>();
-    constexpr int ROW_BITS = Q3H ? 4 : (KIND == KIND_Q4 ? 4 : 8);  // code bits per weight in a row's code stream (Q3H: the whole block)
+    constexpr int ROW_BITS = Q3H ? 4 : (PLANES ? WA : (KIND == KIND_Q4 ? 4 : 8));  // code bits per weight in a row's (first) code stream (Q3H: the whole block)
     constexpr int HDR_PER_STRIP = STRIP_COLS / T::block;       // block headers per strip (formats with headers behind the codes)
     const ChainHeader *const hd = reinterpret_cast<const ChainHeader *>(plan);
     const ChainArgs a = {reinterpret_cast<const ChainPhase *>(plan + sizeof(ChainHeader)),
@@ -610,17 +615,24 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
     int q_rowjump = 0;                                         // from the last strip of a row to the wavefront's next row, bytes
     std::conditional_t<FUSED, int64_t, int> q_row1 = 0;        // from the first to the second row of the pair, bytes (0: no second row)
     uint32_t q_voff_last = 0;                                  // per-lane offset inside the last (ragged) strip of a row
-    const uint32_t voff_full = (uint32_t)lane * 16;
+    const uint32_t voff_full = (uint32_t)lane * (Q3H ? 16 : LANE_BYTES);
     // formats whose block headers sit behind the codes: the same walk over the headers (4 bytes per block)
     const uint8_t *q_hptr = reinterpret_cast<const uint8_t *>(ws);
     int q_hrowjump = 0;
     std::conditional_t<FUSED, int64_t, int> q_hrow1 = 0;
     uint32_t q_hoff_last = 0;
     const uint32_t hoff_full = (uint32_t)(lane * G::WPL / T::block) * 4;
+    // bit-plane formats: and over the high plane
+    const uint8_t *q_pptr = reinterpret_cast<const uint8_t *>(ws);
+    int q_prowjump = 0;
+    std::conditional_t<FUSED, int64_t, int> q_prow1 = 0;
+    uint32_t q_poff_last = 0;
+    const uint32_t poff_full = (uint32_t)lane * LANE_BYTES_HI;
     auto request_empty = [&](int count) __attribute__((always_inline)) {                      // `count` empty steps: one "row" of one empty strip each
         q_wptr = reinterpret_cast<const uint8_t *>(ws);
         q_last = 0; q_nlast16 = 0; q_rowjump = 0; q_row1 = 0; q_voff_last = 0;
         q_hptr = q_wptr; q_hrowjump = 0; q_hrow1 = 0; q_hoff_last = 0;
+        q_pptr = q_wptr; q_prowjump = 0; q_prow1 = 0; q_poff_last = 0;
         q.seg_left = count;
     };
     auto request_segment = [&]() __attribute__((always_inline)) {                             // q.seg_left == 0: find what the requests do next
@@ -666,29 +678,42 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                     }
                     q_voff_last = voff_full & mask_lt(lane, nlast);            // lanes past a ragged end redo block 0
                 } else {
-                    // a row: cols * ROW_BITS / 8 bytes of codes, 1024 per strip; its headers: 4 bytes per block, behind all codes
+                    // a row: cols * ROW_BITS / 8 bytes of codes, 64 * LANE_BYTES per strip; its headers: 4 bytes per block, behind
+                    // all codes; bit planes: cols * WB / 8 bytes of the high plane between the two
                     const int cols = ph.nbk * T::block;
-                    const int row_bytes = cols * ROW_BITS / 8, hrow_bytes = ph.nbk * 4;
+                    const int row_bytes = cols * ROW_BITS / 8, hrow_bytes = ph.nbk * 4, prow_bytes = cols * WB / 8;
+                    const uint8_t *hi_plane = a.mat[m].packed + (int64_t)a.mat[m].hi_off4 * 4;
                     const int nlast = (cols - (ph.nstrips - 1) * STRIP_COLS) / G::WPL;     // lanes of the last strip
                     const uint8_t *headers = a.mat[m].packed + (int64_t)a.mat[m].hdr_off4 * 4;
                     q_wptr = a.mat[m].packed + (int64_t)r * row_bytes;
                     q_hptr = headers + (int64_t)r * hrow_bytes;
-                    q_rowjump = CHAIN_STRIDE * row_bytes - (ph.nstrips - 1) * 1024;
+                    q_rowjump = CHAIN_STRIDE * row_bytes - (ph.nstrips - 1) * 64 * LANE_BYTES;
                     q_hrowjump = CHAIN_STRIDE * hrow_bytes - (ph.nstrips - 1) * HDR_PER_STRIP * 4;
                     q_row1 = single ? 0 : row_bytes;
                     q_hrow1 = single ? 0 : hrow_bytes;
+                    if constexpr (WB > 0) {
+                        q_pptr = hi_plane + (int64_t)r * prow_bytes;
+                        q_prowjump = CHAIN_STRIDE * prow_bytes - (ph.nstrips - 1) * 64 * LANE_BYTES_HI;
+                        q_prow1 = single ? 0 : prow_bytes;
+                    }
                     if constexpr (FUSED) {
                         if (a.mat[m].gated) {                  // both matrices have the same shape: one distance for codes and headers
                             q_wptr = a.mat[m].packed + (int64_t)(r >> 1) * row_bytes;
                             q_hptr = headers + (int64_t)(r >> 1) * hrow_bytes;
-                            q_rowjump = (CHAIN_STRIDE / 2) * row_bytes - (ph.nstrips - 1) * 1024;
+                            q_rowjump = (CHAIN_STRIDE / 2) * row_bytes - (ph.nstrips - 1) * 64 * LANE_BYTES;
                             q_hrowjump = (CHAIN_STRIDE / 2) * hrow_bytes - (ph.nstrips - 1) * HDR_PER_STRIP * 4;
                             q_row1 = a.mat[m].packed2 - a.mat[m].packed;
                             q_hrow1 = q_row1;
+                            if constexpr (WB > 0) {
+                                q_pptr = hi_plane + (int64_t)(r >> 1) * prow_bytes;
+                                q_prowjump = (CHAIN_STRIDE / 2) * prow_bytes - (ph.nstrips - 1) * 64 * LANE_BYTES_HI;
+                                q_prow1 = q_row1;
+                            }
                         }
                     }
                     q_voff_last = voff_full & mask_lt(lane, nlast);            // lanes past a ragged end redo lane 0 (their
                     q_hoff_last = hoff_full & mask_lt(lane, nlast);            // staged activations are zero)
+                    q_poff_last = poff_full & mask_lt(lane, nlast);
                 }
                 found = true;
             }
@@ -716,15 +741,28 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
             }
         } else {
             const uint32_t hoff = last_strip ? q_hoff_last : hoff_full;
+            [[maybe_unused]] const uint32_t poff = last_strip ? q_poff_last : poff_full;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(q_wptr + (int64_t)u * q_row1 + voff));
-                w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
+                if constexpr (LANE_BYTES == 16) {
+                    const u32x4 c0 = __builtin_nontemporal_load(global_ptr<const u32x4>(q_wptr + (int64_t)u * q_row1 + voff));
+                    w[u].d[0] = c0.x; w[u].d[1] = c0.y; w[u].d[2] = c0.z; w[u].d[3] = c0.w;
+                } else {                                       // (two-bit low plane: 8 bytes per lane)
+                    const u32x2 c0 = __builtin_nontemporal_load(global_ptr<const u32x2>(q_wptr + (int64_t)u * q_row1 + voff));
+                    w[u].d[0] = c0.x; w[u].d[1] = c0.y;
+                }
+                if constexpr (WB == 2) {
+                    const u32x2 c1 = __builtin_nontemporal_load(global_ptr<const u32x2>(q_pptr + (int64_t)u * q_prow1 + poff));
+                    w[u].d[WA] = c1.x; w[u].d[WA + 1] = c1.y;
+                } else if constexpr (WB == 1) {
+                    w[u].d[WA] = __builtin_nontemporal_load(global_ptr<const uint32_t>(q_pptr + (int64_t)u * q_prow1 + poff));
+                }
                 w[u].hdr = *global_ptr<const uint32_t>(q_hptr + (int64_t)u * q_hrow1 + hoff);
             }
             q_hptr += last_strip ? q_hrowjump : HDR_PER_STRIP * 4;
+            if constexpr (WB > 0) q_pptr += last_strip ? q_prowjump : 64 * LANE_BYTES_HI;
         }
-        q_wptr += last_strip ? q_rowjump : (Q3H ? 2048 : 1024);
+        q_wptr += last_strip ? q_rowjump : (Q3H ? 2048 : 64 * LANE_BYTES);
         q_lt = last_strip ? 0 : q_lt + 1;
         if (last_strip) {                                      // on to the wavefront's next row
             q.seg_left -= 1;
@@ -1265,6 +1303,11 @@ static bool chain_format(int format, int *strip_cols, int *slot_bytes, int *bloc
     case IFLOW_Q4_B32: *strip_cols = chain_strip_cols<KIND_Q4>(); *slot_bytes = chain_slot_bytes<KIND_Q4>(); *block = 32; *row_bits = 4; return true;
     case IFLOW_Q8_B64: *strip_cols = chain_strip_cols<KIND_Q8>(); *slot_bytes = chain_slot_bytes<KIND_Q8>(); *block = 64; *row_bits = 8; return true;
     case IFLOW_Q8_B32: *strip_cols = chain_strip_cols<KIND_Q8>(); *slot_bytes = chain_slot_bytes<KIND_Q8>(); *block = 32; *row_bits = 8; return true;
+    // bit planes: row_bits = the low plane's bits per weight (the first code stream of a row)
+    case IFLOW_Q6_B64: *strip_cols = chain_strip_cols<KIND_Q6>(); *slot_bytes = chain_slot_bytes<KIND_Q6>(); *block = 64; *row_bits = 4; return true;
+    case IFLOW_Q5_B64: *strip_cols = chain_strip_cols<KIND_Q5>(); *slot_bytes = chain_slot_bytes<KIND_Q5>(); *block = 64; *row_bits = 4; return true;
+    case IFLOW_Q3_B32: *strip_cols = chain_strip_cols<KIND_Q3>(); *slot_bytes = chain_slot_bytes<KIND_Q3>(); *block = 32; *row_bits = 2; return true;
+    case IFLOW_Q2_B32: *strip_cols = chain_strip_cols<KIND_Q2>(); *slot_bytes = chain_slot_bytes<KIND_Q2>(); *block = 32; *row_bits = 2; return true;
     default: return false;
     }
 }
@@ -1287,7 +1330,8 @@ int64_t chain_max_cols(int format)
 #define IFLOW_CHAIN_FOR_FORMAT(DO, FF) DO(FF, false, false) DO(FF, true, false) DO(FF, true, true)
 #define IFLOW_CHAIN_FOR_ALL(DO) \
     IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q3H_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q4_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q4_B32) \
-    IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q8_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q8_B32)
+    IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q8_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q8_B32) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q6_B64) \
+    IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q5_B64) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q3_B32) IFLOW_CHAIN_FOR_FORMAT(DO, IFLOW_Q2_B32)
 
 // Launch geometry: as many workgroups as the device has compute units (one each: 768 threads
 // and most of its LDS), so the whole grid is resident at once and producers and consumers of a hand-over run
@@ -1385,8 +1429,12 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
             mats[m].tag_word = (int)word;
             // (formats with the headers behind the codes: rows x cols x row_bits / 8 bytes of codes come first)
             const int64_t code_bytes = c.rows[m] * c.cols[p] * row_bits / 8;
+            const int code_bits = c.format == IFLOW_Q6_B64 ? 6 : c.format == IFLOW_Q5_B64 ? 5 : c.format == IFLOW_Q3_B32 ? 3 : row_bits;
             if (c.format != IFLOW_Q3H_B64 && code_bytes / 4 > 0xFFFFFFFFLL) return false;
-            mats[m].hdr_off4 = c.format != IFLOW_Q3H_B64 ? (uint32_t)(code_bytes / 4) : 0u;
+            const int64_t all_code_bytes = c.rows[m] * c.cols[p] * code_bits / 8;      // (bit planes: both planes)
+            if (c.format != IFLOW_Q3H_B64 && all_code_bytes / 4 > 0xFFFFFFFFLL) return false;
+            mats[m].hdr_off4 = c.format != IFLOW_Q3H_B64 ? (uint32_t)(all_code_bytes / 4) : 0u;
+            mats[m].hi_off4 = (uint32_t)(code_bytes / 4);
             word += (size_t)((c.rows[m] + 4095) / 4096) * 4096;
             if (gated) {                                       // the pair (gate, up) is one matrix of 2 x rows in the row space;
                 if (j == 0) {                                  // the up matrix keeps an (unused) descriptor of its own

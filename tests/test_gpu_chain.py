@@ -154,7 +154,7 @@ def test_chain_phases_of_every_step_count(gpu, orc):
     assert ticks > 0 and 300.0 < 100.0 * cycles / ticks < 3500.0, (w, cycles, ticks)
 
 
-@pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64", "Q4_B32", "Q8_B32"])
+@pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64", "Q4_B32", "Q8_B32", "Q6_B64", "Q5_B64", "Q3_B32", "Q2_B32"])
 def test_chain_other_formats_ragged_phases_and_relaunch(gpu, orc, fmt_name):
     """The 4- and 8-bit formats of Table 3 through the same chained launch (strips of 2048 and 1024 columns, block headers
     behind the codes): ragged strips, odd matrices, hand-overs across several phases, three launches."""
@@ -175,7 +175,7 @@ def test_chain_other_formats_ragged_phases_and_relaunch(gpu, orc, fmt_name):
         check_phases(torch, iflow, orc, phases, host, f"{fmt_name} launch {it}", fmt_name=fmt_name)
 
 
-@pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64"])
+@pytest.mark.parametrize("fmt_name", ["Q4_B64", "Q8_B64", "Q6_B64", "Q3_B32"])
 def test_chain_other_formats_two_7b_layers(gpu, orc, fmt_name):
     """Config 3's formats at the 7B layer shapes: two decoder layers (eight dependent phases) in one launch; all rows against
     the single-product kernel, sampled rows of every output against the oracle."""

@@ -123,7 +123,9 @@ def test_fused_layers_in_one_launch(gpu, orc, hidden, ffn, nlayers):
 
 
 @pytest.mark.parametrize("fmt_name,hidden,ffn,nlayers", [("Q4_B64", 1088, 4160, 2), ("Q8_B64", 1088, 4160, 2), ("Q4_B32", 256, 704, 3),
-                                                         ("Q8_B32", 2112, 1088, 1), ("Q4_B64", 4096, 11008, 1)])
+                                                         ("Q8_B32", 2112, 1088, 1), ("Q4_B64", 4096, 11008, 1),
+                                                         ("Q6_B64", 1088, 4160, 2), ("Q5_B64", 256, 704, 3), ("Q3_B32", 2112, 1088, 1),
+                                                         ("Q2_B32", 1088, 4160, 2)])
 def test_fused_layers_in_one_launch_other_formats(gpu, orc, fmt_name, hidden, ffn, nlayers):
     """The same decoder layers through the chained launch of the 4- and 8-bit formats (every module in use)."""
     torch, iflow = gpu

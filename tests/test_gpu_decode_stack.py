@@ -118,6 +118,8 @@ class Stack:
     ("Q3H_B64", 8, 2, 1408, 1),       # four: two passes over the range
     ("Q4_B64", 4, 2, 1408, 0),
     ("Q8_B32", 4, 2, 1408, 1),
+    ("Q6_B64", 4, 2, 1408, 1),        # a bit-plane format
+    ("Q3_B32", 4, 4, 704, 0),
 ])
 def test_decode_steps_of_a_small_stack_stage_by_stage(gpu, orc, name, n_heads, n_kv, ffn, pairing):
     torch, iflow = gpu
@@ -208,6 +210,6 @@ def test_decode_stack_launch_and_plan_refuse_what_they_cannot_run(gpu, orc):
             iflow.decode_stack_sizes(iflow.decode_stack(**args))
         assert info.value.status == iflow.ERR_SHAPE, change
     with pytest.raises(iflow.IflowError) as info:
-        iflow.decode_stack_sizes(iflow.decode_stack(iflow.FORMATS["Q5_B64"], 512, 704, 4, 2, 16, EPS, BASE, 1, n_layers=1))
+        iflow.decode_stack_sizes(iflow.decode_stack(99, 512, 704, 4, 2, 16, EPS, BASE, 1, n_layers=1))
     assert info.value.status == iflow.ERR_FORMAT
     st.step_and_check(3)                                         # the refused calls left the chain usable

@@ -90,8 +90,9 @@ def test_chain_validation_happens_before_any_launch(iflow):
                                         None, C.byref(chain))
 
     x0, pk, y0, y1 = base, base * 2, base * 3, base * 4
-    for bit_planes in (5, 6, 7, 8):                                              # 3.5-, 4- and 8-bit formats only
-        assert call(bit_planes, [1], [64], [x0], [pk], [8], [y0]) == iflow.ERR_FORMAT
+    assert call(9, [1], [64], [x0], [pk], [8], [y0]) == iflow.ERR_FORMAT          # no such format
+    assert call(7, [1], [65536 + 32], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE  # a bit-plane format: rows of at most 65536 columns
+    assert call(5, [1], [96], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE          # cols % block (64)
     assert call(1, [1], [61440 + 64], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE  # 8-bit: a row's staged activations must fit LDS
     assert call(3, [1], [65536 + 64], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE
     assert call(3, [1], [96], [x0], [pk], [8], [y0]) == iflow.ERR_SHAPE          # cols % block (64)
@@ -352,7 +353,7 @@ def test_decode_stack_validation_happens_before_any_launch(iflow):
     def plan(plan_ptr=base * 40, ws=base * 50, **change):
         return L.iflow_decode_stack_plan(C.byref(desc(**change)), plan_ptr, 1 << 30, ws, 1 << 30, None, C.byref(iflow.Chain()))
 
-    assert sizes(fmt=iflow.FORMATS["Q5_B64"]) == iflow.ERR_FORMAT and sizes(fmt=99) == iflow.ERR_FORMAT
+    assert sizes(fmt=99) == iflow.ERR_FORMAT
     assert sizes(head_dim=64) == iflow.ERR_SHAPE                                 # head dimension 128 only
     assert sizes(n_heads=6, n_kv_heads=2, hidden=768) == iflow.ERR_SHAPE         # 1 or an even number of query heads per kv head
     assert sizes(n_heads=4, n_kv_heads=3) == iflow.ERR_SHAPE
