@@ -188,12 +188,20 @@ struct ChainWalk {
 #define IFLOW_CHAIN_ABL 0
 #endif
 constexpr int CHAIN_SETS = IFLOW_CHAIN_SETS;
-#ifndef IFLOW_CHAIN_SETS_OTHER
-#define IFLOW_CHAIN_SETS_OTHER 4
-#endif
 // Register sets (steps of weights in flight) per wavefront: a step of the 3.5-bit format is 4 KB (two rows of a 2 KB
-// strip), a step of the 4- and 8-bit formats 2 KB, so those keep twice as many steps in flight for the same bytes.
-constexpr int chain_sets(int format) { return format == IFLOW_Q3H_B64 ? CHAIN_SETS : IFLOW_CHAIN_SETS_OTHER; }
+// strip), a step of the 4- and 8-bit formats 2 KB, of the bit-plane formats 0.75 to 1.75 KB.  The counts are the fastest
+// measured on 7B-shaped layers (eight layers in one launch, us per layer with 2 / 3 / 4 sets: Q4_B64 34.3 / 35.5 / 30.7,
+// Q8_B64 46.9 / 44.2 / 44.3, Q6_B64 44.2 / 45.2 / 47.4, Q5_B64 43.5 / 35.4 / 46.5, Q3_B32 42.7 / 43.8 / 35.6, Q2_B32 23.5 / 34.9 /
+// 36.0; the padding of a phase's steps to whole rounds is part of what they measure).  IFLOW_CHAIN_SETS_OTHER overrides
+// them all (measurement builds).
+constexpr int chain_sets(int format)
+{
+#ifdef IFLOW_CHAIN_SETS_OTHER
+    return format == IFLOW_Q3H_B64 ? CHAIN_SETS : IFLOW_CHAIN_SETS_OTHER;
+#else
+    return format == IFLOW_Q3H_B64 ? CHAIN_SETS : (format == IFLOW_Q6_B64 || format == IFLOW_Q2_B32) ? 2 : format == IFLOW_Q5_B64 ? 3 : 4;
+#endif
+}
 
 // The sums over all 64 lanes of two per-lane values, in the summation tree of wave_sum_to_lane63 (lanes ^1, ^2, the halves
 // and the mirror of a 16-lane row, rows 0+1 and 2+3, then the two halves), so the results are bit-identical to two
