@@ -55,6 +55,12 @@ constexpr int CHAIN_MAX_COLS = 65536;
 constexpr int CHAIN_MAX_GROUP = IFLOW_CHAIN_MAX_GROUP;         // matrices per phase
 constexpr int CHAIN_MAX_GRID = 960;
 constexpr int CHAIN_POLL_BUDGET = 1 << 17;                     // re-reads before a wait is given up (tens of milliseconds)
+// Between two reads of a hand-over word that has not arrived, x 64 cycles.  Measured on 7B-shaped layers, us per layer of
+// the plain stack with 0 / 2 / 8 / 24 / 64: 22.8 / 23.0 / 23.4 / 26.1 / 30.7 - the sooner the last producer's store is seen
+// the better (0 and 2 are within the noise of each other once the modules are in; 2 is kept); two rounds of reads in
+// flight at once (the words looked at twice per memory round trip) are slower again, 24.0: their traffic competes with
+// the weights.
+constexpr int CHAIN_POLL_SLEEP = 2;
 // workspace header, in 32-bit words: [1] error, [8, 12) the launch's clock stamps (below), [64, 64 + grid) the launch count,
 // one copy per workgroup;
 // tagged outputs start at byte IFLOW_CHAIN_WS_HEADER
@@ -263,7 +269,7 @@ __device__ __forceinline__ void chain_read_pairs(const uint16_t *plain, const ui
             __hip_atomic_store(const_cast<uint32_t *>(ws) + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
         }
-        __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_s_sleep(CHAIN_POLL_SLEEP);
     }
 }
 
@@ -511,7 +517,7 @@ __device__ __forceinline__ void chain_attn_merge(const ChainAttn &at, uint32_t *
                 __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
-            __builtin_amdgcn_s_sleep(2);
+            __builtin_amdgcn_s_sleep(CHAIN_POLL_SLEEP);
         }
         float *dst = lds + (i * per_wg + ol) * 3;
         dst[0] = __builtin_bit_cast(float, (uint32_t)wo);
@@ -1030,7 +1036,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                                     again = false;
                                     if (lane == 0) __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 } else {
-                                    __builtin_amdgcn_s_sleep(2);
+                                    __builtin_amdgcn_s_sleep(CHAIN_POLL_SLEEP);
                                 }
                             }
                         } while (again);
@@ -1084,7 +1090,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                                 again = false;
                                 if (lane == 0) __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             } else {
-                                __builtin_amdgcn_s_sleep(2);
+                                __builtin_amdgcn_s_sleep(CHAIN_POLL_SLEEP);
                             }
                         }
                     } while (again);
@@ -1131,7 +1137,7 @@ __global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *
                             __hip_atomic_store(ws + CHAIN_WS_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
-                        __builtin_amdgcn_s_sleep(2);
+                        __builtin_amdgcn_s_sleep(CHAIN_POLL_SLEEP);
                         wd = __hip_atomic_load(res_tagged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 } else if (res_plain) {
