@@ -211,7 +211,7 @@ struct GemvOps {
 // and row n of an "up" matrix (grp.packed[0] and [1], both rows0 x cols), and the one output is
 // fp16(silu(gate sum x scale) (up sum x scale)) - the gated feed-forward's hidden vector without storing its two factors.
 template <int NB, int U, bool MULTI, int XOP = -1, bool GATED = false>
-__global__ __launch_bounds__(NB <= 2 ? 1024 : 512) void q3h_gemv_kernel(const uint8_t *__restrict__ packed0, uint16_t *__restrict__ y0,
+__global__ __launch_bounds__(NB <= 1 ? 1024 : 512) void q3h_gemv_kernel(const uint8_t *__restrict__ packed0, uint16_t *__restrict__ y0,
                                                         const uint16_t *__restrict__ X, int rows0, int cols, int nbk, int nstrips,
                                                         int tgw, int x_op, const uint16_t *__restrict__ aux,
                                                         const GemvGroup grp, const GemvOps ops)
