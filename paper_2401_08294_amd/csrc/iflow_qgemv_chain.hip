@@ -41,9 +41,16 @@ template <typename T> __device__ __forceinline__ IFLOW_GLOBAL T *global_ptr(cons
 #ifndef IFLOW_CHAIN_WAVES
 #define IFLOW_CHAIN_WAVES 12
 #endif
-constexpr int CHAIN_WAVES = IFLOW_CHAIN_WAVES;                                // wavefronts per workgroup (measured: 8 is 3 % slower, 16 equal;
-                                                               // 12 divides the row pairs of 7B-sized phases evenly)
-constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;                  // a wavefront takes two rows per step: rows between its steps
+#ifndef IFLOW_CHAIN_WAVES_ATTN
+#define IFLOW_CHAIN_WAVES_ATTN 8
+#endif
+// Wavefronts per workgroup.  Launches of products only: 12 (measured on 7B-shaped layers with 8 / 10 / 12 / 16: 23.7 / 23.0 /
+// 22.9 / 27.6 us per layer; 12 divides the row pairs of 7B-sized phases evenly, 16 leaves a wavefront 128 registers and
+// spills).  Launches with the attention inside: 8 - two wavefronts per SIMD have 256 registers each, which the attention
+// phases need (with 12 the kernel keeps 90 registers in scratch memory): a 7B decode step at 1024 cached positions 37.3 ->
+// 33.9 us per layer.
+constexpr int chain_waves(bool attn) { return attn ? IFLOW_CHAIN_WAVES_ATTN : IFLOW_CHAIN_WAVES; }
+constexpr int CHAIN_WAVES_ATTN = IFLOW_CHAIN_WAVES_ATTN;       // (the attention's own code is built for that variant only)
 // A strip is what the 64 lanes of a wavefront cover of a row in one step: 64 x (weights per lane) columns - 4096 for the
 // 3.5-bit format (a block per lane), 2048 for the 4-bit and 1024 for the 8-bit formats (16 bytes of codes per lane).
 // Staged activations of one strip: the lanes' registers in decode order, 16 bytes per lane and quarter, then the two sums
@@ -295,15 +302,15 @@ __device__ __forceinline__ uint32_t chain_rope_pair(uint32_t own, uint32_t other
 }
 
 // Phase "part" for R of the query heads of a key/value head's group, heads r0 .. r0 + R - 1 of the group (a group larger than
-// two heads takes several passes over its range).  lds: (4 * CHAIN_WAVES) * 130 floats for the running states, and behind
+// two heads takes several passes over its range).  lds: (4 * CHAIN_WAVES_ATTN) * 130 floats for the running states, and behind
 // them CHAIN_ATTN_STAGE_BYTES for the step's rotated queries, rotated key and value.
-constexpr int CHAIN_ATTN_STATE_BYTES = 4 * CHAIN_WAVES * 130 * 4, CHAIN_ATTN_STAGE_BYTES = 64 * 16;
+constexpr int CHAIN_ATTN_STATE_BYTES = 4 * CHAIN_WAVES_ATTN * 130 * 4, CHAIN_ATTN_STAGE_BYTES = 64 * 16;
 template <int R>
 __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *ws, float *lds, const double2 *table, uint32_t tag, int position,
                                                 int wg, int wave, int lane, int r0, bool &failed, uint32_t *marks = nullptr)
 {
     const int group = at.n_heads / at.n_kv_heads;
-    constexpr int NST = 4 * CHAIN_WAVES;                       // (the LDS area holds up to this many states of 128 sums; R per wavefront are used)
+    constexpr int NST = 4 * CHAIN_WAVES_ATTN;                       // (the LDS area holds up to this many states of 128 sums; R per wavefront are used)
     const int nsplit = at.nsplit;
     if (wg >= at.n_kv_heads * nsplit) return;                  // (uniform over the workgroup)
     const int j = wg / nsplit, sp = wg - j * nsplit;
@@ -317,11 +324,11 @@ __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *w
 
     // The wavefront's first block of cached keys and values is requested before anything of this step is waited for: rows
     // below the step's position do not depend on the step.  (Blocks of sixteen positions, wavefront w takes blocks w,
-    // w + CHAIN_WAVES, ...; four positions per load instruction, one per lane group; positions past the range read its last
+    // w + CHAIN_WAVES_ATTN, ...; four positions per load instruction, one per lane group; positions past the range read its last
     // position (in bounds) and are masked; the step's own position comes from registers: its cache row is being written.)
     const uint8_t *kh = reinterpret_cast<const uint8_t *>(at.k_cache) + (int64_t)j * at.max_seq * 256;     // (uniform; rows of 256 bytes)
     const uint8_t *vh = reinterpret_cast<const uint8_t *>(at.v_cache) + (int64_t)j * at.max_seq * 256;
-    constexpr int STEP = 16 * CHAIN_WAVES;
+    constexpr int STEP = 16 * CHAIN_WAVES_ATTN;
     attn_u32x4 kt[4], vt[4];
     auto load_block = [&](int p0) {
 #pragma unroll
@@ -455,21 +462,21 @@ __device__ __forceinline__ void chain_attn_part(const ChainAttn &at, uint32_t *w
 #pragma unroll
         for (int r = 0; r < R; ++r) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s_acc[(r * CHAIN_WAVES + wave) * 128 + c0 + e] = acc[r][e];
-            if (dseg == 0) { s_m[r * CHAIN_WAVES + wave] = m[r]; s_l[r * CHAIN_WAVES + wave] = l[r]; }
+            for (int e = 0; e < 8; ++e) s_acc[(r * CHAIN_WAVES_ATTN + wave) * 128 + c0 + e] = acc[r][e];
+            if (dseg == 0) { s_m[r * CHAIN_WAVES_ATTN + wave] = m[r]; s_l[r * CHAIN_WAVES_ATTN + wave] = l[r]; }
         }
     }
     __syncthreads();
     if (tid < 128 * R) {
         const int r = tid >> 7, c = tid & 127;
-        const float *sm = s_m + r * CHAIN_WAVES, *sl = s_l + r * CHAIN_WAVES, *sa = s_acc + r * CHAIN_WAVES * 128 + c;
+        const float *sm = s_m + r * CHAIN_WAVES_ATTN, *sl = s_l + r * CHAIN_WAVES_ATTN, *sa = s_acc + r * CHAIN_WAVES_ATTN * 128 + c;
         float M = sm[0];
 #pragma unroll
-        for (int i = 1; i < CHAIN_WAVES; ++i) M = fmaxf(M, sm[i]);
+        for (int i = 1; i < CHAIN_WAVES_ATTN; ++i) M = fmaxf(M, sm[i]);
         float L = 0.f, O = 0.f;
         if (M != -INFINITY) {                                  // (an empty range leaves maximum -inf, sums zero)
 #pragma unroll
-            for (int i = 0; i < CHAIN_WAVES; ++i) {
+            for (int i = 0; i < CHAIN_WAVES_ATTN; ++i) {
                 const float f = __builtin_amdgcn_exp2f(sm[i] - M);
                 L = __builtin_fmaf(sl[i], f, L);
                 O = __builtin_fmaf(sa[i * 128], f, O);
@@ -502,7 +509,7 @@ __device__ __forceinline__ void chain_attn_merge(const ChainAttn &at, uint32_t *
     if (n_here <= 0) return;                                   // (uniform over the workgroup)
     const uint64_t *parts = reinterpret_cast<const uint64_t *>(ws + at.part_word);
     const int nsplit = at.nsplit;
-    for (int idx = tid; idx < nsplit * n_here; idx += 64 * CHAIN_WAVES) {
+    for (int idx = tid; idx < nsplit * n_here; idx += 64 * CHAIN_WAVES_ATTN) {
         const int i = idx / n_here, ol = idx - i * n_here, o = o_base + ol;
         const uint64_t *src = parts + ((int64_t)(o >> 7) * nsplit + i) * 130;
         uint64_t wo, wm, wl;
@@ -549,9 +556,11 @@ __device__ __forceinline__ void chain_attn_merge(const ChainAttn &at, uint32_t *
 // ATTN: the fused variant that also knows the two attention phases (a launch without them runs the code without them: the
 // attention's registers would otherwise cost every fused launch spills around those phases).
 template <int S, bool FUSED, int F, bool ATTN>
-__global__ __launch_bounds__(64 * CHAIN_WAVES) void chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws, int position)
+__global__ __launch_bounds__(64 * chain_waves(ATTN)) void chain_kernel(const uint8_t *__restrict__ plan, uint32_t *__restrict__ ws, int position)
 {
     constexpr bool EARLY = IFLOW_CHAIN_EARLY != 0;
+    constexpr int CHAIN_WAVES = chain_waves(ATTN);             // wavefronts of this workgroup
+    constexpr int CHAIN_STRIDE = 2 * CHAIN_WAVES;              // a wavefront takes two rows per step: rows between its steps
     using T = Fmt<F>;
     constexpr int KIND = T::kind;
     using G = Geo<KIND>;
@@ -1412,7 +1421,7 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
                 if (as.n_kv_heads * at.nsplit > grid) return false;
                 // the second half's LDS: a state per (range, output of the workgroup); one thread per output
                 const int per_wg = ((as.n_heads * 128 + grid - 1) / grid + 1) & ~1;
-                if (per_wg > 64 * CHAIN_WAVES || at.nsplit * per_wg * 3 > 4 * CHAIN_WAVES * 130) return false;
+                if (per_wg > 64 * CHAIN_WAVES_ATTN || at.nsplit * per_wg * 3 > 4 * CHAIN_WAVES_ATTN * 130) return false;
                 const int group = as.n_heads / as.n_kv_heads;
                 if (as.n_heads % as.n_kv_heads != 0 || (group != 1 && (group & 1))) return false;
                 at.max_seq = as.max_seq; at.pairing = as.pairing;
@@ -1469,7 +1478,7 @@ bool chain_build_plan(const ChainSpec &c, int grid, std::vector<uint8_t> &out)
         }
         const int64_t rpw = ((v + grid - 1) / grid + 1) & ~(int64_t)1;
         if (v > 0x3FFFFFFF || word > 0x3FFFFFFF) return false;
-        if (rpw > 64 * CHAIN_STRIDE) return false;             // a wavefront parks one pair of rows per lane
+        if (rpw > 64 * 2 * chain_waves(c.nattn > 0)) return false;      // a wavefront parks one pair of rows per lane
         ph.total = (int)v; ph.rows_per_wg = (int)rpw;
     }
     // the attentions' partial states, behind all tagged vectors
@@ -1510,7 +1519,7 @@ hipError_t launch_chain(const void *plan, void *workspace, int grid, int lds_byt
     bool launched = false;
 #define IFLOW_CHAIN_GO(FF, FUSED, ATTN) \
     if (!launched && format == FF && fused == FUSED && attn == ATTN) { \
-        hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF, ATTN>), dim3((unsigned)grid), dim3(64 * CHAIN_WAVES), lds, s, \
+        hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF, ATTN>), dim3((unsigned)grid), dim3(64 * chain_waves(ATTN)), lds, s, \
                            static_cast<const uint8_t *>(plan), static_cast<uint32_t *>(workspace), position); \
         launched = true; \
     }
