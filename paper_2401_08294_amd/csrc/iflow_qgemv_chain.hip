@@ -207,8 +207,11 @@ constexpr int CHAIN_SETS = IFLOW_CHAIN_SETS;
 // Q8_B64 46.9 / 44.2 / 44.3, Q6_B64 44.2 / 45.2 / 47.4, Q5_B64 43.5 / 35.4 / 46.5, Q3_B32 42.7 / 43.8 / 35.6, Q2_B32 23.5 / 34.9 /
 // 36.0; the padding of a phase's steps to whole rounds is part of what they measure).  IFLOW_CHAIN_SETS_OTHER overrides
 // them all (measurement builds).
-constexpr int chain_sets(int format)
+constexpr int chain_sets(int format, bool attn = false)
 {
+#ifdef IFLOW_CHAIN_SETS_ATTN
+    if (attn && format == IFLOW_Q3H_B64) return IFLOW_CHAIN_SETS_ATTN;
+#endif
 #ifdef IFLOW_CHAIN_SETS_OTHER
     return format == IFLOW_Q3H_B64 ? CHAIN_SETS : IFLOW_CHAIN_SETS_OTHER;
 #else
@@ -1366,7 +1369,7 @@ hipError_t chain_grid_for_device(int *grid)
     hipError_t e0 = once_per_device(pd, &cus, [] {
         hipError_t e = hipSuccess;
 #define IFLOW_CHAIN_ATTR(FF, FUSED, ATTN) \
-        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<chain_sets(FF), FUSED, FF, ATTN>), \
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<chain_sets(FF, ATTN), FUSED, FF, ATTN>), \
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, CHAIN_LDS_BYTES);
         IFLOW_CHAIN_FOR_ALL(IFLOW_CHAIN_ATTR)
 #undef IFLOW_CHAIN_ATTR
@@ -1519,7 +1522,7 @@ hipError_t launch_chain(const void *plan, void *workspace, int grid, int lds_byt
     bool launched = false;
 #define IFLOW_CHAIN_GO(FF, FUSED, ATTN) \
     if (!launched && format == FF && fused == FUSED && attn == ATTN) { \
-        hipLaunchKernelGGL((chain_kernel<chain_sets(FF), FUSED, FF, ATTN>), dim3((unsigned)grid), dim3(64 * chain_waves(ATTN)), lds, s, \
+        hipLaunchKernelGGL((chain_kernel<chain_sets(FF, ATTN), FUSED, FF, ATTN>), dim3((unsigned)grid), dim3(64 * chain_waves(ATTN)), lds, s, \
                            static_cast<const uint8_t *>(plan), static_cast<uint32_t *>(workspace), position); \
         launched = true; \
     }
