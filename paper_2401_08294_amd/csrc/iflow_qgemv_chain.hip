@@ -1,12 +1,12 @@
-// A chain of Q3H matrix-vector products in ONE launch: phase after phase, each phase a group of matrices that
+// A chain of matrix-vector products in ONE launch (every format; written for the 3.5-bit one): phase after phase, each phase a group of matrices that
 // share an activation vector, and a phase may take as its activations the output of a matrix of an earlier
 // phase (q/k/v -> o -> gate/up -> down of a decoder layer).  At batch 1 a 7B-sized product lasts a few
 // microseconds, of which a launch boundary costs 1.6 us of idle memory system plus the ramp of a fresh grid;
 // here the grid stays resident, and the weights of the next phase are already on their way while the outputs
 // of the current one are handed over.
 //
-// Resident grid: one workgroup of 12 wavefronts per compute unit.  Each phase's rows are cut into equal contiguous
-// ranges, one per workgroup; wavefront w of a workgroup takes the row pairs w, w + 12, ... of the range and walks
+// Resident grid: one workgroup of 12 wavefronts per compute unit (8 in the variant with the attention inside).  Each phase's
+// rows are cut into equal contiguous ranges, one per workgroup; wavefront w of a workgroup takes the row pairs w, w + 12, ... of the range and walks
 // each pair strip by strip (a strip = 64 blocks = 4096 columns, one block per lane, as in the single-product
 // kernel; the two rows of a pair share the activation registers).  A wavefront keeps S steps (row pair, strip) of
 // weights in flight in S register sets and requests step k + S as soon as step k is decoded, across phase
