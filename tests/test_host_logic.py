@@ -37,6 +37,17 @@ def test_library_exports_every_declared_symbol(iflow):
     assert iflow.layout_version() == 1
 
 
+def test_binding_constants_are_the_headers(iflow):
+    """The numbers the binding repeats from include/iflow.h (limits of the chained launch, where a launch leaves its clock stamps)."""
+    import re
+    defs = dict(re.findall(r"^#define (IFLOW_[A-Z_]+) (\d+)\s*$", open(HEADER).read(), flags=re.M))
+    assert int(defs["IFLOW_CHAIN_MAX_PHASES"]) == iflow.CHAIN_MAX_PHASES
+    assert int(defs["IFLOW_CHAIN_MAX_GROUP"]) == iflow.CHAIN_MAX_GROUP
+    assert int(defs["IFLOW_CHAIN_MAX_MATRICES"]) == iflow.CHAIN_MAX_MATRICES
+    assert int(defs["IFLOW_CHAIN_WS_CLOCKS"]) == iflow.CHAIN_WS_CLOCKS
+    assert 4 * (iflow.CHAIN_WS_CLOCKS + 4) <= int(defs["IFLOW_CHAIN_WS_HEADER"])      # the stamps lie inside the workspace header
+
+
 def test_format_queries_and_bit_budget(iflow):
     # Table 3: block sizes, levels (2^k, or 11 for Eq.3) and actual bits per weight
     expect = {"Q8_B32": (32, 256, 9), "Q8_B64": (64, 256, 8.5), "Q4_B32": (32, 16, 5), "Q4_B64": (64, 16, 4.5),
