@@ -235,7 +235,7 @@ def main():
     # projections that read the same activation vector and may share a launch: (q, k, v) and (gate, up)
     groups = [[0, 1, 2], [3], [4, 5], [6]] if args.launches in (1, 4) else [[i] for i in range(len(shapes))]
     if args.launches == 1:       # chained launches: o reads q's output, gate/up read o's, down reads gate's, the next layer's q/k/v read down's
-        assert args.format in ("Q3H_B64", "Q4_B64", "Q4_B32", "Q8_B64", "Q8_B32"), "the chained launch exists for the 3.5-, 4- and 8-bit formats"
+        assert args.format in iflow.FORMATS, "unknown format"
         args.layers_per_launch = max(1, min(args.layers_per_launch, args.ring))
         lpl = args.layers_per_launch
         # all outputs of the chain as views of one allocation
@@ -368,16 +368,19 @@ def main():
         # and the median is reported; the first,
         # untimed repeat also compiles every chain the region needs (iflow_qgemv_chain_plan stays outside the timing).
         repeats = 11 if args.steps < 8 * args.ring else 3
-        # Untimed steps in front of every timed region: the --warmup steps, and never fewer than two trips round the ring
+        # Untimed steps in front of every timed region: the --warmup steps, and never fewer than sixteen trips round the ring (12 ms)
         # (with a handful of steps the part has not reached its steady state: a 20-step region measured 26.3 us per step
         # after 5 warm-up steps and 24.9 after 64, 640 or 3200).  The line reports both numbers.
-        settle = max(0, 2 * args.ring - args.warmup) if args.launches == 1 else 0
-        region = None                                    # a short timed region as one graph of its own: one host call instead of
-        if args.launches == 1:                           # one per launch between the two events
+        settle = max(0, 16 * args.ring - args.warmup) if args.launches == 1 else 0
+        region = None                                    # a timed region of several launches as one graph of its own: one host call
+        if args.launches == 1:                           # instead of one per launch between the two events
             end = run(args.warmup, run(settle))
+            launch_count[0] = 0
             run(args.steps, end)
             stream.synchronize()
-            if repeats > 1 and graph is not None:
+            # (a region of one or two launches is issued directly: its launches then sit right behind the first event in the
+            # stream, where a graph's submission leaves a gap of its own - 462-467 against 470-474 us for a 20-layer launch)
+            if repeats > 1 and graph is not None and launch_count[0] > 2:
                 region = torch.cuda.CUDAGraph()
                 launch_count[0] = 0
                 with torch.cuda.graph(region, stream=stream):
